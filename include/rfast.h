@@ -1,0 +1,190 @@
+/*
+ * rfast.h — C ABI of the MI355X (gfx950) library that advances a batch of
+ * simulated R-FAST workers by one asynchronous activation round.
+ *
+ * The method is "R-FAST: Robust Fully-Asynchronous Stochastic Gradient
+ * Tracking over General Topology" (arXiv 2307.11617).  One round lets every
+ * node flagged active perform the node update of Algorithm 1 (steps S1-S5;
+ * global view: Algorithm 2) once, all of them reading the state as of the
+ * start of the round:
+ *   S1   v_i   = x_i - gamma z_i
+ *   S2a  x_i'  = w_ii v_i + sum_{j in N_in(W), j != i} w_ij v_j^(tau_v,ij)
+ *   S2b  z_i^½ = z_i + sum_{j in N_in(A), j != i} (rho_ij^(tau_rho,ij) - rho~_ij)
+ *                + grad f_i(x_i'; zeta') - grad f_i(x_i; zeta)      (stored sample)
+ *   S2c  z_i'  = a_ii z_i^½ ;  rho_li += a_li z_i^½  for every out-neighbour l
+ *   S3   publish (t_i+1, v_i) and (t_i+1, rho_li)
+ *   S4   rho~_ij = the rho_ij just consumed
+ *   S5   t_i += 1
+ * W is the row-stochastic pull matrix, A the column-stochastic push matrix
+ * (Assumption 1).  Here W is called R and A is called C.
+ *
+ * Conventions
+ *  - Every graph is CSR with ROW = RECEIVER: row i lists node i's in-neighbours
+ *    j (ascending, unique), the self-loop (j == i) included and mandatory.
+ *    Rows of R sum to 1; for every j the entries (.,j) of C sum to 1.
+ *  - "Off-diagonal entry e" = the e-th entry of the CSR with j != i, counted in
+ *    CSR order.  All per-edge arrays (delays, drops, stamps, rho rings) use
+ *    this numbering; e of graph R and e of graph C are separate numberings.
+ *  - Version t of node j is what j published at its t-th activation; version 0
+ *    is the zero vector (initialisation of Algorithm 1).  Version t lives in
+ *    ring slot t mod (D+2): D+1 readable versions plus the slot being written.
+ *  - "device" pointers are HIP device memory of the current device; "host"
+ *    pointers are ordinary host memory.  The library never frees or keeps a
+ *    host pointer past the call.  Device memory passed in stays owned by the
+ *    caller and must outlive the context.
+ *  - All calls return RFAST_OK (0) or a negative rfast_status; none throws or
+ *    aborts.  rfast_last_error() gives a text for the last failure.
+ *  - A context is bound to one HIP stream; calls on one context must be
+ *    serialised by the caller.  Work is enqueued asynchronously unless stated.
+ */
+#ifndef RFAST_H
+#define RFAST_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rfast_ctx rfast_ctx;
+
+typedef enum rfast_status {
+  RFAST_OK = 0,
+  RFAST_EINVAL = -1, /* null pointer, bad size, bad enum, misaligned buffer        */
+  RFAST_ESTOCH = -2, /* weights negative, diagonal missing, R rows / C columns != 1 */
+  RFAST_EGRAPH = -3, /* malformed CSR, or G(R), G(C^T) share no spanning-tree root  */
+  RFAST_ERANGE = -4, /* delay outside [0, D-burst+1], D or sample index out of range */
+  RFAST_ENOMEM = -5, /* workspace too small                                        */
+  RFAST_EHIP = -6    /* a HIP runtime call failed                                  */
+} rfast_status;
+
+/* Local objectives f_i (problem (1): F = sum_i f_i; each node samples an
+ * unbiased stochastic gradient of its own f_i, Assumption 5). */
+typedef enum rfast_objective {
+  RFAST_OBJ_DIAG_QUADRATIC = 0, /* f_i = 1/2 sum_k h_ik (x_k - c_ik)^2, gradient + noise_std*N(0,I) */
+  RFAST_OBJ_LEAST_SQUARES = 1,  /* f_i = 1/(2m) ||A_i x - b_i||^2                                   */
+  RFAST_OBJ_LOGISTIC = 2,       /* f_i = mean_s [log(1+exp(a_s.x)) - y_s a_s.x] + lambda/2 ||x||^2  */
+  RFAST_OBJ_SOFTMAX_BF16 = 3    /* softmax regression, W = x as d x K row-major, bf16 MFMA GEMMs    */
+} rfast_objective;
+
+typedef struct rfast_problem {
+  int32_t kind;        /* rfast_objective */
+  int32_t samples;     /* rows held per node (LS: m; logistic/softmax: pool size); 0 for diag quadratic */
+  int32_t batch;       /* rows per sampled gradient; 0 = all `samples` rows (full local gradient)       */
+  int32_t d, K;        /* softmax only: features, classes; p must equal d*K                             */
+  float lambda;        /* logistic only: l2 coefficient                                                 */
+  float noise_std;     /* diag quadratic only: std of the additive gradient noise                       */
+  uint64_t noise_seed; /* diag quadratic only: key of the counter-based generator (see below)           */
+  const void* data0;   /* device. diag: h  fp32 [n][p]. LS/logistic: rows fp32 [n][samples][p].
+                          softmax: pool bf16 [n][samples][d]                                            */
+  const void* data1;   /* device. diag: c  fp32 [n][p]. LS: b fp32 [n][samples]. logistic: y fp32 (0/1)
+                          [n][samples]. softmax: labels int32 [n][samples]                              */
+} rfast_problem;
+/* Gradient noise of the diagonal quadratic: coordinates are taken in groups of
+ * four; group q of (node i, sample version t) is Philox4x32-10 (Salmon et al.,
+ * SC'11) of counter (q mod 2^32, q div 2^32, i, t) under key (seed mod 2^32,
+ * seed div 2^32), giving words o0..o3.  u = ((o >> 8) + 1) / 2^24,
+ * angle = 2 pi o' / 2^32; (o0, o1) yields coordinates 4q, 4q+1 as r cos, r sin
+ * with r = sqrt(-2 ln u); (o2, o3) yields 4q+2, 4q+3.  The sample version of
+ * the initial gradient is 0, that of the t-th activation is t. */
+
+typedef enum rfast_field {
+  RFAST_X = 0,         /* fp32 [n][p]                                             */
+  RFAST_Z = 1,         /* fp32 [n][p]                                             */
+  RFAST_G = 2,         /* fp32 [n][p]  stored gradient sample of each node         */
+  RFAST_V_RING = 3,    /* fp32 [n][D+2][p]  slot s of node j = version t, t mod (D+2) == s */
+  RFAST_RHO_RING = 4,  /* fp32 [nnzC_off][D+2][p]  sender-side running sums        */
+  RFAST_RHO_TILDE = 5, /* fp32 [nnzC_off][p]  receiver-side buffers                */
+  RFAST_T_NODE = 6,    /* int32 [n]  local iteration counters t_i                  */
+  RFAST_TAU_R = 7,     /* int32 [nnzR_off]  largest stamp picked up per R edge     */
+  RFAST_TAU_C = 8,     /* int32 [nnzC_off]                                         */
+  RFAST_SLOT_R = 9,    /* int32 [nnzR_off]  ring slot resolved in the last round (receiver active), else -1 */
+  RFAST_SLOT_C = 10,   /* int32 [nnzC_off]                                         */
+  RFAST_ROUND = 11     /* int32 [1]  rounds executed                               */
+} rfast_field;
+
+typedef struct rfast_diag {
+  double consensus_sq;    /* || x - 1 xbar^T ||_F^2, xbar = (1/n) sum_i x_i (merit function of Theorem 2) */
+  double z_sq;            /* || z ||_F^2                                                                   */
+  double conservation_sq; /* || sum_i z_i + sum_e (rho_e latest - rho~_e) - sum_i g_i ||^2 (Lemma 3: 0)    */
+  double gsum_sq;         /* || sum_i g_i ||^2 (scale for the line above)                                  */
+  double xbar_gap_sq;     /* || xbar - x* ||^2, or -1 if no x* was given (optimality gap of Theorem 1)     */
+  double loss_at_xbar;    /* sum_i f_i(xbar) for the diagonal quadratic, else NaN                          */
+} rfast_diag;
+
+/* Bytes of device workspace rfast_create needs for these sizes (pure function;
+ * returns 0 if an argument is out of range).  nnzR / nnzC count the diagonal. */
+size_t rfast_workspace_bytes(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D,
+                             const rfast_problem* prob);
+
+/* Builds a context.  R_*, C_*: host CSR (row = receiver) with fp32 weights.
+ * D: largest staleness in sender versions any read may have (Assumption 3 ii),
+ *    1 <= D+2 <= 64.  burst >= 1: a version whose burst-1 predecessors on the
+ *    same edge were all lost is delivered even if flagged lost, so per-round
+ *    delays may range over [0, D-burst+1].
+ * prob: objective and device pointers to its data (copied by value).
+ * d_workspace: device, >= rfast_workspace_bytes(...), 256-byte aligned.
+ * hip_stream: a hipStream_t (NULL = the null stream).
+ * Checks Assumption 1 (RFAST_ESTOCH), CSR shape and Assumption 2 (RFAST_EGRAPH).
+ * On failure *out is NULL and rfast_last_error(NULL) describes the cause. */
+int rfast_create(rfast_ctx** out, int32_t n, int64_t p,
+                 const int32_t* R_rowptr, const int32_t* R_col, const float* R_w,
+                 const int32_t* C_rowptr, const int32_t* C_col, const float* C_w,
+                 int32_t D, int32_t burst, const rfast_problem* prob,
+                 void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Initialisation of Algorithm 1: x = x0 (device fp32 [n][p], NULL = zeros),
+ * g = z = grad f_i(x0; zeta^0), every ring, buffer and stamp zero, round 0.
+ * d_batch_idx0: device int32 [n][batch] rows of the initial sample (objectives
+ * with batch > 0), else NULL. */
+int rfast_init(rfast_ctx* ctx, const float* d_x0, const int32_t* d_batch_idx0);
+
+/* One activation round (asynchronous on the context's stream).  All pointers
+ * are DEVICE memory and must stay valid until the round has executed:
+ *  d_active  uint8 [n]          node i performs S1-S5 iff non-zero
+ *  d_delay_R int32 [nnzR_off]   receiver sees the sender as of the start of round r-delay
+ *  d_delay_C int32 [nnzC_off]
+ *  d_drop_R  uint8 [nnzR_off]   the packet the edge's sender publishes THIS round is lost
+ *  d_drop_C  uint8 [nnzC_off]
+ *  gamma     step size of S1
+ *  d_batch_idx int32 [n][batch] sample rows per node (used for active nodes), NULL if batch == 0
+ * Stamps resolve as: newest non-lost version the sender had published before
+ * round r-delay, never older than the stamp already held.  A delay or row index
+ * out of range is clamped on the device and recorded; rfast_check() reports it. */
+int rfast_round(rfast_ctx* ctx, const uint8_t* d_active, const int32_t* d_delay_R,
+                const int32_t* d_delay_C, const uint8_t* d_drop_R, const uint8_t* d_drop_C,
+                float gamma, const int32_t* d_batch_idx);
+
+/* `rounds` consecutive rounds from schedule arrays stacked along a leading
+ * round axis ([rounds][n], [rounds][nnzR_off], ..., [rounds][n][batch]). */
+int rfast_run(rfast_ctx* ctx, int32_t rounds, const uint8_t* d_active, const int32_t* d_delay_R,
+              const int32_t* d_delay_C, const uint8_t* d_drop_R, const uint8_t* d_drop_C,
+              float gamma, const int32_t* d_batch_idx);
+
+/* Waits for the stream, then returns RFAST_OK or the first error a round
+ * recorded on the device (RFAST_ERANGE) with its round and edge in the text. */
+int rfast_check(rfast_ctx* ctx);
+
+/* Waits for the stream and copies one field to HOST memory.  `bytes` must be
+ * exactly the field's size (RFAST_EINVAL otherwise). */
+int rfast_read_state(rfast_ctx* ctx, int32_t field, void* host_dst, size_t bytes);
+
+/* Reductions over the current state (synchronous).  d_xstar: device fp32 [p] or NULL. */
+int rfast_diagnostics(rfast_ctx* ctx, const float* d_xstar, rfast_diag* host_out);
+
+/* Kernel timing: when enabled, HIP events bracket the state-update kernels and
+ * the gradient kernels of each round (at most 4096 rounds are kept since the
+ * last enable).  rfast_kernel_time waits for the stream and returns the summed
+ * milliseconds and the number of timed launches of `which`
+ * (0 = fused/mix+track state kernels, 1 = gradient kernels, 2 = resolver). */
+int rfast_profile_enable(rfast_ctx* ctx, int32_t on);
+int rfast_kernel_time(rfast_ctx* ctx, int32_t which, double* ms_sum, int64_t* launches);
+
+const char* rfast_last_error(const rfast_ctx* ctx);
+void rfast_destroy(rfast_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RFAST_H */

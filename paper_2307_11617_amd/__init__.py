@@ -1,0 +1,8 @@
+"""R-FAST activation rounds on MI355X: thin ctypes binding over librfast.so.
+
+Nothing here computes: every step of the round runs in the HIP kernels.  The
+library must have been built (python -m paper_2307_11617_amd.build); loading
+fails loudly otherwise."""
+from .binding import (RFAST_FIELDS, RFast, RFastError, RfastProblem, lib, rfast_check, rfast_create,  # noqa: F401
+                      rfast_destroy, rfast_diagnostics, rfast_init, rfast_kernel_time, rfast_last_error,
+                      rfast_profile_enable, rfast_read_state, rfast_round, rfast_run, rfast_workspace_bytes)

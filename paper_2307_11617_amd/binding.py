@@ -1,0 +1,246 @@
+"""ctypes marshalling for the C ABI declared in include/rfast.h (same names)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "librfast.so")
+_lib = None
+
+
+class RFastError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"rfast error {code}: {msg}")
+        self.code = code
+
+
+class RfastProblem(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("samples", C.c_int32), ("batch", C.c_int32), ("d", C.c_int32),
+                ("K", C.c_int32), ("lam", C.c_float), ("noise_std", C.c_float), ("noise_seed", C.c_uint64),
+                ("data0", C.c_void_p), ("data1", C.c_void_p)]
+
+
+class RfastDiag(C.Structure):
+    _fields_ = [(k, C.c_double) for k in ("consensus_sq", "z_sq", "conservation_sq", "gsum_sq", "xbar_gap_sq",
+                                           "loss_at_xbar")]
+
+
+OBJECTIVES = {"diag_quadratic": 0, "least_squares": 1, "logistic": 2, "softmax_bf16": 3}
+RFAST_FIELDS = {"X": 0, "Z": 1, "G": 2, "V_RING": 3, "RHO_RING": 4, "RHO_TILDE": 5, "T_NODE": 6, "TAU_R": 7,
+                "TAU_C": 8, "SLOT_R": 9, "SLOT_C": 10, "ROUND": 11}
+EXPORTS = ["rfast_workspace_bytes", "rfast_create", "rfast_init", "rfast_round", "rfast_run", "rfast_check",
+           "rfast_read_state", "rfast_diagnostics", "rfast_profile_enable", "rfast_kernel_time", "rfast_last_error",
+           "rfast_destroy"]
+
+
+def lib():
+    """The loaded library; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RFastError(-6, f"{_LIB_PATH} is missing: run `python -m paper_2307_11617_amd.build`")
+    L = C.CDLL(_LIB_PATH)
+    vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    L.rfast_workspace_bytes.restype = sz
+    L.rfast_workspace_bytes.argtypes = [i32, i64, i32, i32, i32, C.POINTER(RfastProblem)]
+    L.rfast_create.restype = C.c_int
+    L.rfast_create.argtypes = [C.POINTER(vp), i32, i64, vp, vp, vp, vp, vp, vp, i32, i32, C.POINTER(RfastProblem),
+                               vp, sz, vp]
+    L.rfast_init.restype = C.c_int
+    L.rfast_init.argtypes = [vp, vp, vp]
+    L.rfast_round.restype = C.c_int
+    L.rfast_round.argtypes = [vp, vp, vp, vp, vp, vp, C.c_float, vp]
+    L.rfast_run.restype = C.c_int
+    L.rfast_run.argtypes = [vp, i32, vp, vp, vp, vp, vp, C.c_float, vp]
+    L.rfast_check.restype = C.c_int
+    L.rfast_check.argtypes = [vp]
+    L.rfast_read_state.restype = C.c_int
+    L.rfast_read_state.argtypes = [vp, i32, vp, sz]
+    L.rfast_diagnostics.restype = C.c_int
+    L.rfast_diagnostics.argtypes = [vp, vp, C.POINTER(RfastDiag)]
+    L.rfast_profile_enable.restype = C.c_int
+    L.rfast_profile_enable.argtypes = [vp, i32]
+    L.rfast_kernel_time.restype = C.c_int
+    L.rfast_kernel_time.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    L.rfast_last_error.restype = C.c_char_p
+    L.rfast_last_error.argtypes = [vp]
+    L.rfast_destroy.restype = None
+    L.rfast_destroy.argtypes = [vp]
+    _lib = L
+    return L
+
+
+def _np_ptr(a):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _dev_ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def rfast_last_error(ctx=None):
+    return lib().rfast_last_error(ctx).decode()
+
+
+def _chk(code, ctx=None):
+    if code != 0:
+        raise RFastError(code, rfast_last_error(ctx))
+
+
+def rfast_workspace_bytes(n, p, nnzR, nnzC, D, prob):
+    return int(lib().rfast_workspace_bytes(n, p, nnzR, nnzC, D, C.byref(prob)))
+
+
+def rfast_create(n, p, R, Cg, D, burst, prob, workspace, stream_ptr):
+    """R, Cg: (rowptr int32, col int32, w float32) host numpy arrays; workspace: uint8 device tensor."""
+    arrs = [np.ascontiguousarray(R[0], np.int32), np.ascontiguousarray(R[1], np.int32), np.ascontiguousarray(R[2], np.float32),
+            np.ascontiguousarray(Cg[0], np.int32), np.ascontiguousarray(Cg[1], np.int32), np.ascontiguousarray(Cg[2], np.float32)]
+    ctx = C.c_void_p()
+    code = lib().rfast_create(C.byref(ctx), n, p, *[_np_ptr(a) for a in arrs], D, burst, C.byref(prob),
+                              _dev_ptr(workspace), workspace.numel() * workspace.element_size(), C.c_void_p(stream_ptr))
+    _chk(code, None)
+    return ctx
+
+
+def rfast_init(ctx, x0=None, batch_idx0=None):
+    _chk(lib().rfast_init(ctx, _dev_ptr(x0), _dev_ptr(batch_idx0)), ctx)
+
+
+def rfast_round(ctx, active, delay_R, delay_C, drop_R, drop_C, gamma, batch_idx=None):
+    _chk(lib().rfast_round(ctx, _dev_ptr(active), _dev_ptr(delay_R), _dev_ptr(delay_C), _dev_ptr(drop_R),
+                           _dev_ptr(drop_C), gamma, _dev_ptr(batch_idx)), ctx)
+
+
+def rfast_run(ctx, rounds, active, delay_R, delay_C, drop_R, drop_C, gamma, batch_idx=None):
+    _chk(lib().rfast_run(ctx, rounds, _dev_ptr(active), _dev_ptr(delay_R), _dev_ptr(delay_C), _dev_ptr(drop_R),
+                         _dev_ptr(drop_C), gamma, _dev_ptr(batch_idx)), ctx)
+
+
+def rfast_check(ctx):
+    _chk(lib().rfast_check(ctx), ctx)
+
+
+def rfast_read_state(ctx, field, out):
+    """out: host numpy array of exactly the field's size."""
+    _chk(lib().rfast_read_state(ctx, RFAST_FIELDS[field] if isinstance(field, str) else field, _np_ptr(out), out.nbytes), ctx)
+    return out
+
+
+def rfast_diagnostics(ctx, xstar=None):
+    d = RfastDiag()
+    _chk(lib().rfast_diagnostics(ctx, _dev_ptr(xstar), C.byref(d)), ctx)
+    return {k: getattr(d, k) for k, _ in RfastDiag._fields_}
+
+
+def rfast_profile_enable(ctx, on=True):
+    _chk(lib().rfast_profile_enable(ctx, 1 if on else 0), ctx)
+
+
+def rfast_kernel_time(ctx, which):
+    ms, cnt = C.c_double(), C.c_int64()
+    _chk(lib().rfast_kernel_time(ctx, which, C.byref(ms), C.byref(cnt)), ctx)
+    return ms.value, cnt.value
+
+
+def rfast_destroy(ctx):
+    lib().rfast_destroy(ctx)
+
+
+class RFast:
+    """Owns the device tensors a context borrows (workspace, objective data) and
+    forwards to the C ABI.  torch is used for device memory and the stream only."""
+
+    def __init__(self, n, p, R, Cg, D, burst, objective, data0, data1, samples=0, batch=0, d=0, K=0, lam=0.0,
+                 noise_std=0.0, noise_seed=0, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.device = torch.device(device)
+        self.n, self.p, self.D, self.M = n, p, D, D + 2
+        self.nnzR_off, self.nnzC_off = len(R[1]) - n, len(Cg[1]) - n
+        self.data0 = data0.to(self.device).contiguous()
+        self.data1 = data1.to(self.device).contiguous()
+        kind = OBJECTIVES[objective]
+        need0 = {0: n * p, 1: n * samples * p, 2: n * samples * p, 3: n * samples * d}[kind]
+        need1 = n * p if kind == 0 else n * samples
+        dt0 = torch.bfloat16 if kind == 3 else torch.float32
+        dt1 = torch.int32 if kind == 3 else torch.float32
+        if self.data0.numel() != need0 or self.data1.numel() != need1 or self.data0.dtype != dt0 or self.data1.dtype != dt1:
+            raise RFastError(-1, "objective data has the wrong size or dtype")
+        self.prob = RfastProblem(OBJECTIVES[objective], samples, batch, d, K, lam, noise_std, noise_seed,
+                                 self.data0.data_ptr(), self.data1.data_ptr())
+        nbytes = rfast_workspace_bytes(n, p, len(R[1]), len(Cg[1]), D, self.prob)
+        if nbytes == 0:
+            raise RFastError(-1, "sizes out of range")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.stream = torch.cuda.current_stream(self.device)
+        self.ctx = rfast_create(n, p, R, Cg, D, burst, self.prob, self.workspace, self.stream.cuda_stream)
+
+    def dev(self, a, dtype=None):
+        t = self.torch.as_tensor(np.ascontiguousarray(a))
+        if dtype is not None:
+            t = t.to(dtype)
+        return t.to(self.device)
+
+    def init(self, x0=None, batch_idx0=None):
+        self._keep = (None if x0 is None else self.dev(x0, self.torch.float32),
+                      None if batch_idx0 is None else self.dev(batch_idx0, self.torch.int32))
+        if self._keep[0] is not None and self._keep[0].numel() != self.n * self.p:
+            raise RFastError(-1, "x0 must hold n*p values")
+        if self._keep[1] is not None and self._keep[1].numel() != self.n * self.prob.batch:
+            raise RFastError(-1, "batch_idx0 must hold n*batch rows")
+        rfast_init(self.ctx, *self._keep)
+
+    def _check_schedule(self, rounds, active, delay_R, delay_C, drop_R, drop_C, batch_idx):
+        """The library cannot see the extent of device arrays: check them here, before any launch."""
+        t = self.torch
+        want = [("active", active, t.uint8, self.n), ("delay_R", delay_R, t.int32, self.nnzR_off),
+                ("delay_C", delay_C, t.int32, self.nnzC_off), ("drop_R", drop_R, t.uint8, self.nnzR_off),
+                ("drop_C", drop_C, t.uint8, self.nnzC_off)]
+        if self.prob.kind != 0 and self.prob.batch > 0:
+            want.append(("batch_idx", batch_idx, t.int32, self.n * self.prob.batch))
+        for name, a, dt, per_round in want:
+            if per_round == 0 and a is None:
+                continue
+            if a is None or a.dtype != dt or a.device != self.device or not a.is_contiguous() \
+                    or a.numel() != rounds * per_round:
+                raise RFastError(-1, f"{name}: need a contiguous {dt} tensor of {rounds * per_round} elements on {self.device}")
+
+    def round(self, active, delay_R, delay_C, drop_R, drop_C, gamma, batch_idx=None):
+        self._check_schedule(1, active, delay_R, delay_C, drop_R, drop_C, batch_idx)
+        rfast_round(self.ctx, active, delay_R, delay_C, drop_R, drop_C, gamma, batch_idx)
+
+    def run(self, rounds, active, delay_R, delay_C, drop_R, drop_C, gamma, batch_idx=None):
+        self._check_schedule(rounds, active, delay_R, delay_C, drop_R, drop_C, batch_idx)
+        rfast_run(self.ctx, rounds, active, delay_R, delay_C, drop_R, drop_C, gamma, batch_idx)
+
+    def check(self):
+        rfast_check(self.ctx)
+
+    def read(self, field):
+        n, p, M = self.n, self.p, self.M
+        shapes = {"X": ((n, p), np.float32), "Z": ((n, p), np.float32), "G": ((n, p), np.float32),
+                  "V_RING": ((n, M, p), np.float32), "RHO_RING": ((self.nnzC_off, M, p), np.float32),
+                  "RHO_TILDE": ((self.nnzC_off, p), np.float32), "T_NODE": ((n,), np.int32),
+                  "TAU_R": ((self.nnzR_off,), np.int32), "TAU_C": ((self.nnzC_off,), np.int32),
+                  "SLOT_R": ((self.nnzR_off,), np.int32), "SLOT_C": ((self.nnzC_off,), np.int32),
+                  "ROUND": ((1,), np.int32)}
+        shape, dt = shapes[field]
+        return rfast_read_state(self.ctx, field, np.empty(shape, dtype=dt))
+
+    def diagnostics(self, xstar=None):
+        return rfast_diagnostics(self.ctx, xstar)
+
+    def close(self):
+        if self.ctx is not None:
+            rfast_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

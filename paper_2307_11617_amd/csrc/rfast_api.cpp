@@ -1,0 +1,526 @@
+// C-ABI entry points of librfast: argument checks, workspace layout, launch order.
+#include <math.h>
+#include <string.h>
+
+#include <algorithm>
+#include <string>
+#include <vector>
+
+#include "rfast_internal.h"
+
+size_t rfast_gemv_scratch_floats(int32_t n, const rfast_problem* prob);
+size_t rfast_softmax_scratch_bytes(int32_t n, const rfast_problem* prob);
+
+namespace {
+
+std::string g_create_error;
+
+constexpr size_t kAlign = 256;
+inline size_t up(size_t b) { return (b + kAlign - 1) / kAlign * kAlign; }
+
+// Sizes of every carve-out, in the order they are laid out.
+struct Layout {
+  size_t total = 0;
+  size_t take(size_t bytes) {
+    const size_t off = total;
+    total += up(bytes);
+    return off;
+  }
+};
+
+struct Offsets {
+  size_t x, z, g, v_ring, rho_ring, rho_tilde;
+  size_t r_ptr, r_src, r_w, r_self, c_ptr, c_src, c_self, co_ptr, co_eid, co_w, ro_ptr, ro_eid;
+  size_t t, t_hist, tau_r, tau_c, deliv_r, deliv_c, round_no, err;
+  size_t n_active, active_list, plan_t, slot_r, slot_c, skip_c;
+  size_t resid, gscratch, diag;
+  size_t total;
+};
+
+bool sizes_ok(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, const rfast_problem* prob) {
+  if (n < 1 || p < 1 || nnzR < n || nnzC < n || D < 0 || D + 2 > 64 || prob == nullptr) return false;
+  if (prob->kind < 0 || prob->kind > RFAST_OBJ_SOFTMAX_BF16) return false;
+  if (prob->kind != RFAST_OBJ_DIAG_QUADRATIC && (prob->samples < 1 || prob->batch < 0 || prob->batch > prob->samples))
+    return false;
+  if ((prob->kind == RFAST_OBJ_LEAST_SQUARES || prob->kind == RFAST_OBJ_LOGISTIC) &&
+      (prob->batch > 0 ? prob->batch : prob->samples) > 4096)
+    return false;  // the sampled residuals of one node are staged in LDS
+  if (prob->kind == RFAST_OBJ_SOFTMAX_BF16 && (prob->d < 1 || prob->K < 1 || (int64_t)prob->d * prob->K != p)) return false;
+  return true;
+}
+
+Offsets layout(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, const rfast_problem* prob) {
+  const size_t eR = (size_t)(nnzR - n), eC = (size_t)(nnzC - n), M = (size_t)D + 2, H = (size_t)D + 1;
+  const size_t vec = (size_t)p * sizeof(float);
+  Layout L;
+  Offsets o;
+  o.x = L.take(n * vec);
+  o.z = L.take(n * vec);
+  o.g = L.take(2 * n * vec);
+  o.v_ring = L.take(n * M * vec);
+  o.rho_ring = L.take(eC * M * vec);
+  o.rho_tilde = L.take(eC * vec);
+  o.r_ptr = L.take((n + 1) * 4);
+  o.r_src = L.take(eR * 4);
+  o.r_w = L.take(eR * 4);
+  o.r_self = L.take(n * 4);
+  o.c_ptr = L.take((n + 1) * 4);
+  o.c_src = L.take(eC * 4);
+  o.c_self = L.take(n * 4);
+  o.co_ptr = L.take((n + 1) * 4);
+  o.co_eid = L.take(eC * 4);
+  o.co_w = L.take(eC * 4);
+  o.ro_ptr = L.take((n + 1) * 4);
+  o.ro_eid = L.take(eR * 4);
+  o.t = L.take(n * 4);
+  o.t_hist = L.take(n * H * 4);
+  o.tau_r = L.take(eR * 4);
+  o.tau_c = L.take(eC * 4);
+  o.deliv_r = L.take(eR * 8);
+  o.deliv_c = L.take(eC * 8);
+  o.round_no = L.take(4);
+  o.err = L.take(16);
+  o.n_active = L.take(4);
+  o.active_list = L.take(n * 4);
+  o.plan_t = L.take(n * 4);
+  o.slot_r = L.take(eR * 4);
+  o.slot_c = L.take(eC * 4);
+  o.skip_c = L.take(eC);
+  o.resid = L.take(rfast_gemv_scratch_floats(n, prob) * 4);
+  o.gscratch = L.take(rfast_softmax_scratch_bytes(n, prob));
+  o.diag = L.take(64 * sizeof(double));
+  o.total = L.total;
+  return o;
+}
+
+struct HostGraph {
+  std::vector<int32_t> ptr, src, out_ptr, out_eid;
+  std::vector<float> w, self, out_w;
+};
+
+// Splits a CSR (row = receiver, diagonal included) into off-diagonal in-edge and
+// out-edge lists and checks Assumption 1: positive diagonal, non-negative
+// weights, rows (row_stochastic) or columns summing to one.
+int split_graph(const char* name, int32_t n, const int32_t* rowptr, const int32_t* col, const float* w,
+                bool row_stochastic, HostGraph* g, std::string* err) {
+  if (rowptr[0] != 0) { *err = std::string(name) + ": rowptr[0] != 0"; return RFAST_EGRAPH; }
+  g->ptr.assign(n + 1, 0);
+  g->self.assign(n, 0.f);
+  std::vector<double> colsum(n, 0.0);
+  for (int i = 0; i < n; ++i) {
+    if (rowptr[i + 1] < rowptr[i]) { *err = std::string(name) + ": rowptr not monotone"; return RFAST_EGRAPH; }
+    double rowsum = 0.0;
+    int prev = -1;
+    bool diag = false;
+    for (int k = rowptr[i]; k < rowptr[i + 1]; ++k) {
+      const int j = col[k];
+      if (j < 0 || j >= n || j <= prev) {
+        *err = std::string(name) + ": column indices must be in range, ascending and unique (row " + std::to_string(i) + ")";
+        return RFAST_EGRAPH;
+      }
+      prev = j;
+      if (!(w[k] > 0.f) || !std::isfinite(w[k])) {
+        *err = std::string(name) + ": stored weights must be positive (row " + std::to_string(i) + ")";
+        return RFAST_ESTOCH;
+      }
+      rowsum += w[k];
+      colsum[j] += w[k];
+      if (j == i) {
+        diag = true;
+        g->self[i] = w[k];
+      } else {
+        g->src.push_back(j);
+        g->w.push_back(w[k]);
+      }
+    }
+    if (!diag) { *err = std::string(name) + ": missing self-loop at node " + std::to_string(i); return RFAST_ESTOCH; }
+    if (row_stochastic && fabs(rowsum - 1.0) > 1e-6) {
+      *err = std::string(name) + ": row " + std::to_string(i) + " does not sum to 1";
+      return RFAST_ESTOCH;
+    }
+    g->ptr[i + 1] = (int32_t)g->src.size();
+  }
+  if (!row_stochastic)
+    for (int j = 0; j < n; ++j)
+      if (fabs(colsum[j] - 1.0) > 1e-6) {
+        *err = std::string(name) + ": column " + std::to_string(j) + " does not sum to 1";
+        return RFAST_ESTOCH;
+      }
+  // out-edge lists (sender-major)
+  const size_t E = g->src.size();
+  g->out_ptr.assign(n + 1, 0);
+  for (size_t e = 0; e < E; ++e) g->out_ptr[g->src[e] + 1]++;
+  for (int j = 0; j < n; ++j) g->out_ptr[j + 1] += g->out_ptr[j];
+  g->out_eid.assign(E, 0);
+  g->out_w.assign(E, 0.f);
+  std::vector<int32_t> fill(g->out_ptr.begin(), g->out_ptr.end() - 1);
+  for (size_t e = 0; e < E; ++e) {
+    const int pos = fill[g->src[e]]++;
+    g->out_eid[pos] = (int32_t)e;
+    g->out_w[pos] = g->w[e];
+  }
+  return RFAST_OK;
+}
+
+// Nodes from which every node can be reached along `forward` edges sender->receiver
+// (forward = true) or receiver->sender (forward = false).
+std::vector<char> roots_of(int32_t n, const HostGraph& g, bool forward) {
+  std::vector<std::vector<int>> adj(n);
+  for (int i = 0; i < n; ++i)
+    for (int e = g.ptr[i]; e < g.ptr[i + 1]; ++e) {
+      if (forward) adj[g.src[e]].push_back(i);
+      else adj[i].push_back(g.src[e]);
+    }
+  std::vector<char> is_root(n, 0);
+  std::vector<int> stack;
+  std::vector<char> seen;
+  for (int r = 0; r < n; ++r) {
+    seen.assign(n, 0);
+    stack.assign(1, r);
+    seen[r] = 1;
+    int cnt = 1;
+    while (!stack.empty()) {
+      const int u = stack.back();
+      stack.pop_back();
+      for (int v : adj[u])
+        if (!seen[v]) { seen[v] = 1; ++cnt; stack.push_back(v); }
+    }
+    is_root[r] = cnt == n;
+  }
+  return is_root;
+}
+
+template <class T>
+hipError_t upload(rfast_ctx* c, char* base, size_t off, const std::vector<T>& v) {
+  if (v.empty()) return hipSuccess;
+  return hipMemcpyAsync(base + off, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice, c->stream);
+}
+
+int fail(rfast_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg; else g_create_error = msg;
+  return code;
+}
+int hipfail(rfast_ctx* c, hipError_t e, const char* what) {
+  return fail(c, RFAST_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+size_t field_bytes(const rfast_ctx* c, int32_t field) {
+  const RfastDev& d = c->d;
+  const size_t vec = (size_t)d.p * 4;
+  switch (field) {
+    case RFAST_X: case RFAST_Z: case RFAST_G: return d.n * vec;
+    case RFAST_V_RING: return (size_t)d.n * d.M * vec;
+    case RFAST_RHO_RING: return (size_t)d.eC * d.M * vec;
+    case RFAST_RHO_TILDE: return (size_t)d.eC * vec;
+    case RFAST_T_NODE: return (size_t)d.n * 4;
+    case RFAST_TAU_R: case RFAST_SLOT_R: return (size_t)d.eR * 4;
+    case RFAST_TAU_C: case RFAST_SLOT_C: return (size_t)d.eC * 4;
+    case RFAST_ROUND: return 4;
+    default: return (size_t)-1;
+  }
+}
+
+void time_begin(rfast_ctx* c, int which) {
+  if (!c->profiling || c->ev_used[which] >= c->ev[which][0].size()) return;
+  (void)hipEventRecord(c->ev[which][0][c->ev_used[which]], c->stream);
+}
+void time_end(rfast_ctx* c, int which) {
+  if (!c->profiling || c->ev_used[which] >= c->ev[which][0].size()) return;
+  (void)hipEventRecord(c->ev[which][1][c->ev_used[which]], c->stream);
+  c->ev_used[which]++;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t rfast_workspace_bytes(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, const rfast_problem* prob) {
+  if (!sizes_ok(n, p, nnzR, nnzC, D, prob)) return 0;
+  return layout(n, p, nnzR, nnzC, D, prob).total;
+}
+
+int rfast_create(rfast_ctx** out, int32_t n, int64_t p, const int32_t* R_rowptr, const int32_t* R_col, const float* R_w,
+                 const int32_t* C_rowptr, const int32_t* C_col, const float* C_w, int32_t D, int32_t burst,
+                 const rfast_problem* prob, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  if (out == nullptr) return fail(nullptr, RFAST_EINVAL, "out is NULL");
+  *out = nullptr;
+  if (!R_rowptr || !R_col || !R_w || !C_rowptr || !C_col || !C_w || !prob || !d_workspace)
+    return fail(nullptr, RFAST_EINVAL, "NULL argument");
+  if (n < 1 || p < 1) return fail(nullptr, RFAST_EINVAL, "n and p must be positive");
+  if (D < 0 || D + 2 > 64) return fail(nullptr, RFAST_ERANGE, "D + 2 must be in [2, 64]");
+  if (burst < 1 || burst - 1 > D) return fail(nullptr, RFAST_ERANGE, "burst must be in [1, D+1]");
+  const int32_t nnzR = R_rowptr[n], nnzC = C_rowptr[n];
+  if (!sizes_ok(n, p, nnzR, nnzC, D, prob)) return fail(nullptr, RFAST_EINVAL, "sizes or problem description out of range");
+  if (!prob->data0 || !prob->data1) return fail(nullptr, RFAST_EINVAL, "problem data pointers are NULL");
+  if (((uintptr_t)d_workspace % kAlign) != 0) return fail(nullptr, RFAST_EINVAL, "workspace must be 256-byte aligned");
+  if ((p % 4) == 0 && ((((uintptr_t)prob->data0) | ((uintptr_t)prob->data1)) % 16) != 0)
+    return fail(nullptr, RFAST_EINVAL, "problem data must be 16-byte aligned");
+
+  HostGraph gr, gc;
+  std::string msg;
+  int rc = split_graph("R", n, R_rowptr, R_col, R_w, true, &gr, &msg);
+  if (rc != RFAST_OK) return fail(nullptr, rc, msg);
+  rc = split_graph("C", n, C_rowptr, C_col, C_w, false, &gc, &msg);
+  if (rc != RFAST_OK) return fail(nullptr, rc, msg);
+  {
+    // Assumption 2: G(R) and G(C^T) each contain a spanning tree and share a root.
+    // In G(R) information flows sender -> receiver; in G(C^T) the edges of C are reversed.
+    const std::vector<char> rr = roots_of(n, gr, true), rc2 = roots_of(n, gc, false);
+    bool common = false;
+    for (int i = 0; i < n; ++i) common = common || (rr[i] && rc2[i]);
+    if (!common) return fail(nullptr, RFAST_EGRAPH, "G(R) and G(C^T) share no spanning-tree root (Assumption 2)");
+  }
+  const Offsets o = layout(n, p, nnzR, nnzC, D, prob);
+  if (workspace_bytes < o.total)
+    return fail(nullptr, RFAST_ENOMEM, "workspace too small: need " + std::to_string(o.total) + " bytes");
+
+  rfast_ctx* c = new (std::nothrow) rfast_ctx();
+  if (!c) return fail(nullptr, RFAST_ENOMEM, "host allocation failed");
+  c->stream = (hipStream_t)hip_stream;
+  c->nnzR = nnzR;
+  c->nnzC = nnzC;
+  char* b = (char*)d_workspace;
+  RfastDev& d = c->d;
+  d.n = n; d.p = p; d.M = D + 2; d.H = D + 1; d.eR = nnzR - n; d.eC = nnzC - n;
+  d.burst = burst; d.d_max = D - (burst - 1);
+  d.x = (float*)(b + o.x); d.z = (float*)(b + o.z); d.g = (float*)(b + o.g);
+  d.v_ring = (float*)(b + o.v_ring); d.rho_ring = (float*)(b + o.rho_ring); d.rho_tilde = (float*)(b + o.rho_tilde);
+  d.r_ptr = (int32_t*)(b + o.r_ptr); d.r_src = (int32_t*)(b + o.r_src); d.r_w = (float*)(b + o.r_w);
+  d.r_self = (float*)(b + o.r_self);
+  d.c_ptr = (int32_t*)(b + o.c_ptr); d.c_src = (int32_t*)(b + o.c_src); d.c_self = (float*)(b + o.c_self);
+  d.co_ptr = (int32_t*)(b + o.co_ptr); d.co_eid = (int32_t*)(b + o.co_eid); d.co_w = (float*)(b + o.co_w);
+  d.ro_ptr = (int32_t*)(b + o.ro_ptr); d.ro_eid = (int32_t*)(b + o.ro_eid);
+  d.t = (int32_t*)(b + o.t); d.t_hist = (int32_t*)(b + o.t_hist);
+  d.tau_r = (int32_t*)(b + o.tau_r); d.tau_c = (int32_t*)(b + o.tau_c);
+  d.deliv_r = (unsigned long long*)(b + o.deliv_r); d.deliv_c = (unsigned long long*)(b + o.deliv_c);
+  d.round_no = (int32_t*)(b + o.round_no); d.err = (int32_t*)(b + o.err);
+  d.n_active = (int32_t*)(b + o.n_active); d.active_list = (int32_t*)(b + o.active_list);
+  d.plan_t = (int32_t*)(b + o.plan_t); d.slot_r = (int32_t*)(b + o.slot_r); d.slot_c = (int32_t*)(b + o.slot_c);
+  d.skip_c = (uint8_t*)(b + o.skip_c);
+  d.resid = (float*)(b + o.resid); d.gscratch = (void*)(b + o.gscratch);
+  c->d_diag = (double*)(b + o.diag);
+  d.prob = *prob;
+
+  hipError_t e = hipSuccess;
+  auto chk = [&](hipError_t r) { if (e == hipSuccess) e = r; };
+  chk(upload(c, b, o.r_ptr, gr.ptr)); chk(upload(c, b, o.r_src, gr.src)); chk(upload(c, b, o.r_w, gr.w));
+  chk(upload(c, b, o.r_self, gr.self));
+  chk(upload(c, b, o.c_ptr, gc.ptr)); chk(upload(c, b, o.c_src, gc.src)); chk(upload(c, b, o.c_self, gc.self));
+  chk(upload(c, b, o.co_ptr, gc.out_ptr)); chk(upload(c, b, o.co_eid, gc.out_eid)); chk(upload(c, b, o.co_w, gc.out_w));
+  chk(upload(c, b, o.ro_ptr, gr.out_ptr)); chk(upload(c, b, o.ro_eid, gr.out_eid));
+  chk(hipStreamSynchronize(c->stream));  // the host vectors die with this scope
+  if (e != hipSuccess) {
+    const int r = hipfail(nullptr, e, "uploading graph");
+    delete c;
+    return r;
+  }
+  *out = c;
+  return RFAST_OK;
+}
+
+int rfast_init(rfast_ctx* c, const float* d_x0, const int32_t* d_batch_idx0) {
+  if (!c) return RFAST_EINVAL;
+  RfastDev& d = c->d;
+  if (d.prob.kind != RFAST_OBJ_DIAG_QUADRATIC && d.prob.batch > 0 && !d_batch_idx0)
+    return fail(c, RFAST_EINVAL, "initial sample rows are required when batch > 0");
+  const size_t vec = (size_t)d.p * 4;
+  hipError_t e = hipSuccess;
+  auto chk = [&](hipError_t r) { if (e == hipSuccess) e = r; };
+  if (d_x0) chk(hipMemcpyAsync(d.x, d_x0, d.n * vec, hipMemcpyDeviceToDevice, c->stream));
+  else chk(hipMemsetAsync(d.x, 0, d.n * vec, c->stream));
+  chk(hipMemsetAsync(d.g, 0, 2 * d.n * vec, c->stream));
+  chk(hipMemsetAsync(d.v_ring, 0, (size_t)d.n * d.M * vec, c->stream));
+  if (d.eC) {
+    chk(hipMemsetAsync(d.rho_ring, 0, (size_t)d.eC * d.M * vec, c->stream));
+    chk(hipMemsetAsync(d.rho_tilde, 0, (size_t)d.eC * vec, c->stream));
+    chk(hipMemsetAsync(d.tau_c, 0, (size_t)d.eC * 4, c->stream));
+    chk(hipMemsetAsync(d.slot_c, 0xff, (size_t)d.eC * 4, c->stream));
+    chk(hipMemsetAsync(d.skip_c, 1, (size_t)d.eC, c->stream));
+    // only version 0 (slot 0) counts as delivered
+    chk(hipMemsetAsync(d.deliv_c, 0, (size_t)d.eC * 8, c->stream));
+  }
+  if (d.eR) {
+    chk(hipMemsetAsync(d.tau_r, 0, (size_t)d.eR * 4, c->stream));
+    chk(hipMemsetAsync(d.slot_r, 0xff, (size_t)d.eR * 4, c->stream));
+    chk(hipMemsetAsync(d.deliv_r, 0, (size_t)d.eR * 8, c->stream));
+  }
+  chk(hipMemsetAsync(d.t, 0, (size_t)d.n * 4, c->stream));
+  chk(hipMemsetAsync(d.t_hist, 0, (size_t)d.n * d.H * 4, c->stream));
+  chk(hipMemsetAsync(d.plan_t, 0, (size_t)d.n * 4, c->stream));
+  chk(hipMemsetAsync(d.round_no, 0, 4, c->stream));
+  chk(hipMemsetAsync(d.err, 0, 16, c->stream));
+  chk(hipMemsetAsync(d.n_active, 0, 4, c->stream));
+  if (e != hipSuccess) return hipfail(c, e, "rfast_init clears");
+  e = rfast_launch_init_grad(c, d_batch_idx0);
+  if (e != hipSuccess) return hipfail(c, e, "initial gradient");
+  return RFAST_OK;
+}
+
+int rfast_round(rfast_ctx* c, const uint8_t* d_active, const int32_t* d_delay_R, const int32_t* d_delay_C,
+                const uint8_t* d_drop_R, const uint8_t* d_drop_C, float gamma, const int32_t* d_batch_idx) {
+  if (!c) return RFAST_EINVAL;
+  const RfastDev& d = c->d;
+  if (!d_active || (d.eR && (!d_delay_R || !d_drop_R)) || (d.eC && (!d_delay_C || !d_drop_C)))
+    return fail(c, RFAST_EINVAL, "NULL schedule pointer");
+  const bool separable = d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC;
+  if (!separable && d.prob.batch > 0 && !d_batch_idx) return fail(c, RFAST_EINVAL, "sample rows are required when batch > 0");
+  if (!std::isfinite(gamma)) return fail(c, RFAST_EINVAL, "gamma is not finite");
+  hipError_t e;
+  time_begin(c, 2);
+  e = rfast_launch_resolve(c, d_active, d_delay_R, d_delay_C, d_drop_R, d_drop_C);
+  time_end(c, 2);
+  if (e != hipSuccess) return hipfail(c, e, "resolver launch");
+  if (separable) {
+    time_begin(c, 0);
+    e = rfast_launch_state(c, RFAST_MODE_FUSED, gamma);
+    time_end(c, 0);
+    if (e != hipSuccess) return hipfail(c, e, "fused round launch");
+    return RFAST_OK;
+  }
+  time_begin(c, 0);
+  e = rfast_launch_state(c, RFAST_MODE_MIX, gamma);
+  time_end(c, 0);
+  if (e != hipSuccess) return hipfail(c, e, "mix launch");
+  time_begin(c, 1);
+  e = rfast_launch_gradient(c, d_batch_idx);
+  time_end(c, 1);
+  if (e != hipSuccess) return hipfail(c, e, "gradient launch");
+  time_begin(c, 0);
+  e = rfast_launch_state(c, RFAST_MODE_TRACK, gamma);
+  time_end(c, 0);
+  if (e != hipSuccess) return hipfail(c, e, "track launch");
+  return RFAST_OK;
+}
+
+int rfast_run(rfast_ctx* c, int32_t rounds, const uint8_t* d_active, const int32_t* d_delay_R, const int32_t* d_delay_C,
+              const uint8_t* d_drop_R, const uint8_t* d_drop_C, float gamma, const int32_t* d_batch_idx) {
+  if (!c) return RFAST_EINVAL;
+  if (rounds < 0) return fail(c, RFAST_EINVAL, "rounds < 0");
+  const RfastDev& d = c->d;
+  const size_t B = d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC ? 0 : (size_t)d.prob.batch;
+  for (int32_t r = 0; r < rounds; ++r) {
+    const int rc = rfast_round(c, d_active + (size_t)r * d.n, d_delay_R ? d_delay_R + (size_t)r * d.eR : nullptr,
+                               d_delay_C ? d_delay_C + (size_t)r * d.eC : nullptr,
+                               d_drop_R ? d_drop_R + (size_t)r * d.eR : nullptr,
+                               d_drop_C ? d_drop_C + (size_t)r * d.eC : nullptr, gamma,
+                               d_batch_idx ? d_batch_idx + (size_t)r * d.n * B : nullptr);
+    if (rc != RFAST_OK) return rc;
+  }
+  return RFAST_OK;
+}
+
+int rfast_check(rfast_ctx* c) {
+  if (!c) return RFAST_EINVAL;
+  hipError_t e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return hipfail(c, e, "stream synchronize");
+  int32_t err[4];
+  e = hipMemcpy(err, c->d.err, 16, hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return hipfail(c, e, "reading device status");
+  if (err[0] == 0) return RFAST_OK;
+  static const char* kinds[] = {"delay on R edge", "delay on C edge", "sample row of node"};
+  const char* what = err[2] >= 0 && err[2] <= 2 ? kinds[err[2]] : "value";
+  return fail(c, err[0], std::string(what) + " " + std::to_string(err[3]) + " out of range in round " + std::to_string(err[1]) +
+                             " (clamped on the device)");
+}
+
+int rfast_read_state(rfast_ctx* c, int32_t field, void* host_dst, size_t bytes) {
+  if (!c || !host_dst) return RFAST_EINVAL;
+  const size_t want = field_bytes(c, field);
+  if (want == (size_t)-1) return fail(c, RFAST_EINVAL, "unknown field");
+  if (bytes != want) return fail(c, RFAST_EINVAL, "field holds " + std::to_string(want) + " bytes");
+  const RfastDev& d = c->d;
+  hipError_t e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return hipfail(c, e, "stream synchronize");
+  if (bytes == 0) return RFAST_OK;
+  const void* src = nullptr;
+  switch (field) {
+    case RFAST_X: src = d.x; break;
+    case RFAST_Z: src = d.z; break;
+    case RFAST_V_RING: src = d.v_ring; break;
+    case RFAST_RHO_RING: src = d.rho_ring; break;
+    case RFAST_RHO_TILDE: src = d.rho_tilde; break;
+    case RFAST_T_NODE: src = d.t; break;
+    case RFAST_TAU_R: src = d.tau_r; break;
+    case RFAST_TAU_C: src = d.tau_c; break;
+    case RFAST_SLOT_R: src = d.slot_r; break;
+    case RFAST_SLOT_C: src = d.slot_c; break;
+    case RFAST_ROUND: src = d.round_no; break;
+    default: break;
+  }
+  if (field == RFAST_G) {
+    // the stored sample of node i is the one of version t_i: g[t_i & 1][i]
+    std::vector<int32_t> t(d.n);
+    e = hipMemcpy(t.data(), d.t, (size_t)d.n * 4, hipMemcpyDeviceToHost);
+    const size_t vec = (size_t)d.p * 4;
+    for (int i = 0; i < d.n && e == hipSuccess; ++i)
+      e = hipMemcpy((char*)host_dst + i * vec, (const char*)d.g + ((size_t)(t[i] & 1) * d.n + i) * vec, vec, hipMemcpyDeviceToHost);
+  } else {
+    e = hipMemcpy(host_dst, src, bytes, hipMemcpyDeviceToHost);
+  }
+  if (e != hipSuccess) return hipfail(c, e, "copying state to host");
+  return RFAST_OK;
+}
+
+int rfast_diagnostics(rfast_ctx* c, const float* d_xstar, rfast_diag* host_out) {
+  if (!c || !host_out) return RFAST_EINVAL;
+  hipError_t e = rfast_launch_diag(c, d_xstar, c->d_diag);
+  if (e != hipSuccess) return hipfail(c, e, "diagnostics launch");
+  e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return hipfail(c, e, "stream synchronize");
+  double h[8];
+  e = hipMemcpy(h, c->d_diag, sizeof(h), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return hipfail(c, e, "copying diagnostics");
+  host_out->consensus_sq = h[0];
+  host_out->z_sq = h[1];
+  host_out->conservation_sq = h[2];
+  host_out->gsum_sq = h[3];
+  host_out->xbar_gap_sq = d_xstar ? h[4] : -1.0;
+  host_out->loss_at_xbar = c->d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC ? h[5] : NAN;
+  return RFAST_OK;
+}
+
+int rfast_profile_enable(rfast_ctx* c, int32_t on) {
+  if (!c) return RFAST_EINVAL;
+  constexpr size_t kMax = 4096;
+  if (on && c->ev[0][0].empty()) {
+    for (int w = 0; w < 3; ++w)
+      for (int s = 0; s < 2; ++s) {
+        const size_t cnt = (w == 0 ? 2 : 1) * kMax;
+        c->ev[w][s].resize(cnt);
+        for (size_t k = 0; k < cnt; ++k)
+          if (hipEventCreate(&c->ev[w][s][k]) != hipSuccess) return fail(c, RFAST_EHIP, "hipEventCreate failed");
+      }
+  }
+  for (int w = 0; w < 3; ++w) c->ev_used[w] = 0;
+  c->profiling = on != 0;
+  return RFAST_OK;
+}
+
+int rfast_kernel_time(rfast_ctx* c, int32_t which, double* ms_sum, int64_t* launches) {
+  if (!c || which < 0 || which > 2 || !ms_sum || !launches) return RFAST_EINVAL;
+  hipError_t e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return hipfail(c, e, "stream synchronize");
+  double tot = 0.0;
+  for (size_t k = 0; k < c->ev_used[which]; ++k) {
+    float ms = 0.f;
+    e = hipEventElapsedTime(&ms, c->ev[which][0][k], c->ev[which][1][k]);
+    if (e != hipSuccess) return hipfail(c, e, "hipEventElapsedTime");
+    tot += ms;
+  }
+  *ms_sum = tot;
+  *launches = (int64_t)c->ev_used[which];
+  return RFAST_OK;
+}
+
+const char* rfast_last_error(const rfast_ctx* c) { return c ? c->err.c_str() : g_create_error.c_str(); }
+
+void rfast_destroy(rfast_ctx* c) {
+  if (!c) return;
+  (void)hipStreamSynchronize(c->stream);
+  for (int w = 0; w < 3; ++w)
+    for (int s = 0; s < 2; ++s)
+      for (hipEvent_t ev : c->ev[w][s]) (void)hipEventDestroy(ev);
+  delete c;
+}
+
+}  // extern "C"

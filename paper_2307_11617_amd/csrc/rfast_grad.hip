@@ -1,0 +1,171 @@
+// Local stochastic gradients grad f_i(x_i; zeta) for the objectives that are
+// not separable per coordinate (step S2b of Algorithm 1 needs the sample at the
+// freshly mixed x_i), plus the initial gradients z^0 = g^0 of every objective.
+//
+// Least squares / logistic regression: a GEMV pair on the sampled rows,
+//   r_s = phi(a_s . x) - y_s,   g = (1/B) sum_s r_s a_s (+ lambda x),
+// phi = identity (least squares, y = b) or the logistic function.  The rows
+// kernel gives one wavefront per sampled row (float4 loads, 64-lane reduction);
+// the columns kernel gives one float4 of g per lane and streams the same rows
+// again, coalesced along k.
+#include "rfast_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+__device__ inline int sample_row(const RfastDev& s, const int32_t* batch_idx, int i, int b, int B) {
+  if (batch_idx == nullptr) return b;
+  int row = batch_idx[(size_t)i * B + b];
+  if (row < 0 || row >= s.prob.samples) {
+    if (atomicCAS(&s.err[0], 0, RFAST_ERANGE) == 0) {
+      s.err[1] = *s.round_no;
+      s.err[2] = 2;
+      s.err[3] = i;
+    }
+    row = row < 0 ? 0 : s.prob.samples - 1;
+  }
+  return row;
+}
+
+// node handled by blockIdx.y: all nodes at initialisation, the round's active list otherwise
+__device__ inline int pick_node(const RfastDev& s, bool init) {
+  if (init) return blockIdx.y;
+  return (int)blockIdx.y < *s.n_active ? s.active_list[blockIdx.y] : -1;
+}
+
+__global__ void __launch_bounds__(kThreads) rfast_rows_kernel(RfastDev s, const int32_t* batch_idx, int B, bool init) {
+  const int i = pick_node(s, init);
+  if (i < 0) return;
+  const int b = blockIdx.x * kWaves + (threadIdx.x >> 6);
+  if (b >= B) return;
+  const int lane = threadIdx.x & 63;
+  const int64_t p = s.p;
+  const int row = sample_row(s, batch_idx, i, b, B);
+  const float* a = (const float*)s.prob.data0 + ((size_t)i * s.prob.samples + row) * p;
+  const float* x = s.x + (size_t)i * p;
+  float acc = 0.f;
+  if ((p & 3) == 0) {
+    for (int64_t k = (int64_t)lane * 4; k < p; k += 256) {
+      const float4 av = *reinterpret_cast<const float4*>(a + k);
+      const float4 xv = *reinterpret_cast<const float4*>(x + k);
+      acc = fmaf(av.x, xv.x, acc);
+      acc = fmaf(av.y, xv.y, acc);
+      acc = fmaf(av.z, xv.z, acc);
+      acc = fmaf(av.w, xv.w, acc);
+    }
+  } else {
+    for (int64_t k = lane; k < p; k += 64) acc = fmaf(a[k], x[k], acc);
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) {
+    const float y = ((const float*)s.prob.data1)[(size_t)i * s.prob.samples + row];
+    const float r = s.prob.kind == RFAST_OBJ_LOGISTIC ? 1.0f / (1.0f + expf(-acc)) - y : acc - y;
+    s.resid[(size_t)i * B + b] = r;
+  }
+}
+
+template <int VEC>
+__global__ void __launch_bounds__(kThreads) rfast_cols_kernel(RfastDev s, const int32_t* batch_idx, int B, bool init) {
+  extern __shared__ float sh[];  // [B] residuals, then [B] row numbers
+  const int i = pick_node(s, init);
+  if (i < 0) return;
+  float* r_sh = sh;
+  int* row_sh = reinterpret_cast<int*>(sh + B);
+  for (int b = threadIdx.x; b < B; b += kThreads) {
+    r_sh[b] = s.resid[(size_t)i * B + b];
+    row_sh[b] = sample_row(s, batch_idx, i, b, B);
+  }
+  __syncthreads();
+  const int64_t p = s.p;
+  const int64_t k = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * VEC;
+  if (k >= p) return;
+  const float* base = (const float*)s.prob.data0 + (size_t)i * s.prob.samples * p + k;
+  const int t_old = init ? -1 : s.plan_t[i];
+  float* dst = s.g + (size_t)((t_old + 1) & 1) * s.n * p + (size_t)i * p + k;
+  const float inv = 1.0f / (float)B;
+  const float lam = s.prob.kind == RFAST_OBJ_LOGISTIC ? s.prob.lambda : 0.f;
+  if (VEC == 4) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int b = 0; b < B; ++b) {
+      const float4 av = *reinterpret_cast<const float4*>(base + (size_t)row_sh[b] * p);
+      const float r = r_sh[b];
+      acc.x = fmaf(r, av.x, acc.x);
+      acc.y = fmaf(r, av.y, acc.y);
+      acc.z = fmaf(r, av.z, acc.z);
+      acc.w = fmaf(r, av.w, acc.w);
+    }
+    const float4 xv = *reinterpret_cast<const float4*>(s.x + (size_t)i * p + k);
+    *reinterpret_cast<float4*>(dst) = make_float4(fmaf(lam, xv.x, acc.x * inv), fmaf(lam, xv.y, acc.y * inv),
+                                                  fmaf(lam, xv.z, acc.z * inv), fmaf(lam, xv.w, acc.w * inv));
+  } else {
+    float acc = 0.f;
+    for (int b = 0; b < B; ++b) acc = fmaf(r_sh[b], base[(size_t)row_sh[b] * p], acc);
+    *dst = fmaf(lam, s.x[(size_t)i * p + k], acc * inv);
+  }
+}
+
+// initial gradient of the diagonal quadratic (sample version 0) and z^0 = g^0
+__global__ void __launch_bounds__(kThreads) rfast_copy_z_kernel(RfastDev s) {
+  const size_t tot = (size_t)s.n * s.p;
+  for (size_t q = (size_t)blockIdx.x * kThreads + threadIdx.x; q < tot; q += (size_t)gridDim.x * kThreads) s.z[q] = s.g[q];
+}
+
+hipError_t gemv_pair(rfast_ctx* c, const int32_t* batch_idx, bool init) {
+  const RfastDev& d = c->d;
+  const int B = d.prob.batch > 0 ? d.prob.batch : d.prob.samples;
+  const int32_t* bi = d.prob.batch > 0 ? batch_idx : nullptr;
+  hipLaunchKernelGGL(rfast_rows_kernel, dim3((B + kWaves - 1) / kWaves, d.n), dim3(kThreads), 0, c->stream, d, bi, B, init);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const bool vec4 = (d.p % 4) == 0;
+  const int64_t per_block = (int64_t)kThreads * (vec4 ? 4 : 1);
+  const unsigned gx = (unsigned)((d.p + per_block - 1) / per_block);
+  const size_t shm = (size_t)B * 8;
+  if (vec4)
+    hipLaunchKernelGGL(rfast_cols_kernel<4>, dim3(gx, d.n), dim3(kThreads), shm, c->stream, d, bi, B, init);
+  else
+    hipLaunchKernelGGL(rfast_cols_kernel<1>, dim3(gx, d.n), dim3(kThreads), shm, c->stream, d, bi, B, init);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t rfast_softmax_gradient(rfast_ctx* c, const int32_t* batch_idx, bool init);  // rfast_softmax.hip
+hipError_t rfast_diag_init_gradient(rfast_ctx* c);                                       // rfast_round.hip
+
+size_t rfast_gemv_scratch_floats(int32_t n, const rfast_problem* prob) {
+  if (prob->kind != RFAST_OBJ_LEAST_SQUARES && prob->kind != RFAST_OBJ_LOGISTIC) return 0;
+  const int B = prob->batch > 0 ? prob->batch : prob->samples;
+  return (size_t)n * (size_t)B;
+}
+
+hipError_t rfast_launch_gradient(rfast_ctx* c, const int32_t* batch_idx) {
+  switch (c->d.prob.kind) {
+    case RFAST_OBJ_LEAST_SQUARES:
+    case RFAST_OBJ_LOGISTIC: return gemv_pair(c, batch_idx, false);
+    case RFAST_OBJ_SOFTMAX_BF16: return rfast_softmax_gradient(c, batch_idx, false);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t rfast_launch_init_grad(rfast_ctx* c, const int32_t* batch_idx0) {
+  hipError_t e;
+  switch (c->d.prob.kind) {
+    case RFAST_OBJ_DIAG_QUADRATIC: e = rfast_diag_init_gradient(c); break;
+    case RFAST_OBJ_LEAST_SQUARES:
+    case RFAST_OBJ_LOGISTIC: e = gemv_pair(c, batch_idx0, true); break;
+    case RFAST_OBJ_SOFTMAX_BF16: e = rfast_softmax_gradient(c, batch_idx0, true); break;
+    default: return hipErrorInvalidValue;
+  }
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(rfast_copy_z_kernel, dim3(1024), dim3(kThreads), 0, c->stream, c->d);
+  return hipGetLastError();
+}

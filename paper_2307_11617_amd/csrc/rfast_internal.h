@@ -1,0 +1,86 @@
+// Internal layout shared by the translation units of librfast (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "rfast.h"
+
+// ---------------------------------------------------------------------------
+// Device-side view of one context.  Passed to kernels by value.
+//
+// State is node-major structure-of-arrays: every logical vector is contiguous
+// in the coordinate k, so one wavefront reads 64 consecutive float4 (1 KiB).
+//   x, z        [n][p]
+//   g           [2][n][p]   the sample of version t lives in g[t & 1]
+//   v_ring      [n][M][p]   M = D + 2 slots, version t in slot t mod M
+//   rho_ring    [eC][M][p]  one ring per off-diagonal entry of C (sender side)
+//   rho_tilde   [eC][p]     receiver side
+// ---------------------------------------------------------------------------
+struct RfastDev {
+  int32_t n, M, H, eR, eC, d_max, burst;
+  int64_t p;
+  float* x;
+  float* z;
+  float* g;
+  float* v_ring;
+  float* rho_ring;
+  float* rho_tilde;
+  // graph, off-diagonal entries only (row = receiver)
+  const int32_t* r_ptr;   // [n+1] into R off-diagonal entries
+  const int32_t* r_src;   // [eR] sender j
+  const float* r_w;       // [eR] w_ij
+  const float* r_self;    // [n]  w_ii
+  const int32_t* c_ptr;   // [n+1] into C off-diagonal entries (in-edges of i are consecutive ids)
+  const int32_t* c_src;   // [eC] sender j
+  const float* c_self;    // [n]  a_ii
+  const int32_t* co_ptr;  // [n+1] out-edges of sender j over C
+  const int32_t* co_eid;  // [eC] edge id (into rho_ring)
+  const float* co_w;      // [eC] a_lj
+  const int32_t* ro_ptr;  // [n+1] out-edges of sender j over R
+  const int32_t* ro_eid;  // [eR]
+  // integer state
+  int32_t* t;             // [n]
+  int32_t* t_hist;        // [n][H]   t_hist[j][s mod H] = t_j at the start of round s
+  int32_t* tau_r;         // [eR]
+  int32_t* tau_c;         // [eC]
+  unsigned long long* deliv_r;  // [eR] bit s set: the version in slot s was delivered on this edge
+  unsigned long long* deliv_c;  // [eC]
+  int32_t* round_no;      // [1]
+  int32_t* err;           // [4] code, round, kind, edge (first error wins)
+  // per-round plan written by the resolver, read by the state kernels
+  int32_t* n_active;      // [1]
+  int32_t* active_list;   // [n]
+  int32_t* plan_t;        // [n]   t_i at the start of the round
+  int32_t* slot_r;        // [eR]  resolved slot, -1 if receiver inactive
+  int32_t* slot_c;        // [eC]
+  uint8_t* skip_c;        // [eC]  stamp unchanged since last consume: contributes exactly zero
+  // gradient scratch
+  float* resid;           // [n][rows] residuals of the GEMV pair / unused
+  void* gscratch;         // softmax: bf16 W copy and E matrix
+  rfast_problem prob;
+};
+
+struct rfast_ctx {
+  RfastDev d;
+  hipStream_t stream;
+  int32_t nnzR, nnzC;
+  std::string err;
+  bool profiling = false;
+  std::vector<hipEvent_t> ev[3][2];
+  size_t ev_used[3] = {0, 0, 0};
+  double* d_diag = nullptr;  // carved from the workspace
+};
+
+enum { RFAST_MODE_FUSED = 0, RFAST_MODE_MIX = 1, RFAST_MODE_TRACK = 2 };
+
+// launchers (each enqueues on ctx->stream and returns a hipError_t)
+hipError_t rfast_launch_resolve(rfast_ctx* c, const uint8_t* active, const int32_t* delay_R,
+                                const int32_t* delay_C, const uint8_t* drop_R, const uint8_t* drop_C);
+hipError_t rfast_launch_state(rfast_ctx* c, int mode, float gamma);
+hipError_t rfast_launch_init_grad(rfast_ctx* c, const int32_t* batch_idx0);
+hipError_t rfast_launch_gradient(rfast_ctx* c, const int32_t* batch_idx);
+hipError_t rfast_launch_diag(rfast_ctx* c, const float* d_xstar, double* d_out);
+size_t rfast_grad_scratch_bytes(int32_t n, int64_t p, const rfast_problem* prob);

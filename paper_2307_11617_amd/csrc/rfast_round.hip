@@ -1,0 +1,277 @@
+// State-update kernels of one activation round (Algorithm 1, steps S1-S5).
+//
+// One work item = (active node, tile of coordinates).  Everything is
+// elementwise in the coordinate k, has no reuse and moves 4 bytes per ~1 flop,
+// so the kernels are pure HBM streams: every access is a float4 per lane
+// (1 KiB per wavefront instruction), loads of one phase are issued back to back
+// before their first use, and inactive nodes cost nothing.
+//
+//   FUSED  separable objective (diagonal quadratic): S1, S2a, gradient, S2b,
+//          S2c, S3, S4 in one pass.
+//   MIX    S1, S2a and the v half of S3; the gradient kernels run next.
+//   TRACK  S2b, S2c, the rho half of S3, S4.
+#include "rfast_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kBatch = 8;  // loads kept in flight per edge phase
+
+// ------------------------------------------------------------ vector helpers
+template <int VEC> struct V;
+template <> struct V<4> {
+  using T = float4;
+  static __device__ inline T ld(const float* p) { return *reinterpret_cast<const float4*>(p); }
+  static __device__ inline void st(float* p, T v) { *reinterpret_cast<float4*>(p) = v; }
+};
+template <> struct V<1> {
+  using T = float;
+  static __device__ inline T ld(const float* p) { return *p; }
+  static __device__ inline void st(float* p, T v) { *p = v; }
+};
+__device__ inline float4 fma_s(float a, float4 b, float4 c) {
+  return make_float4(fmaf(a, b.x, c.x), fmaf(a, b.y, c.y), fmaf(a, b.z, c.z), fmaf(a, b.w, c.w));
+}
+__device__ inline float fma_s(float a, float b, float c) { return fmaf(a, b, c); }
+__device__ inline float4 mul_s(float a, float4 b) { return make_float4(a * b.x, a * b.y, a * b.z, a * b.w); }
+__device__ inline float mul_s(float a, float b) { return a * b; }
+__device__ inline float4 add(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
+__device__ inline float add(float a, float b) { return a + b; }
+__device__ inline float4 sub(float4 a, float4 b) { return make_float4(a.x - b.x, a.y - b.y, a.z - b.z, a.w - b.w); }
+__device__ inline float sub(float a, float b) { return a - b; }
+__device__ inline float4 mul(float4 a, float4 b) { return make_float4(a.x * b.x, a.y * b.y, a.z * b.z, a.w * b.w); }
+__device__ inline float mul(float a, float b) { return a * b; }
+
+// ------------------------------------------------- counter-based Gaussian noise
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11).
+__device__ inline void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1,
+                                     uint32_t out[4]) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// sin and cos of 2*pi*w/2^32.  The octant comes from the top three bits, so the
+// reduction is exact; the remainder a in [-pi/8, pi/8] goes through Taylor
+// polynomials whose truncation error is below 1e-8.
+__device__ inline void sincos_turns(uint32_t w, float* s, float* c) {
+  const uint32_t q = ((w >> 28) + 1u) >> 1;                // nearest multiple of pi/4 (0..8)
+  const int32_t rem = (int32_t)(w - (q << 29));            // signed offset from q*pi/4 (mod 2^32), |rem| <= 2^28
+  const float a = (float)rem * (6.283185307179586f / 4294967296.0f);
+  const float a2 = a * a;
+  float sp = fmaf(a2, fmaf(a2, fmaf(a2, fmaf(a2, 2.7557319e-6f, -1.9841270e-4f), 8.3333333e-3f), -1.6666667e-1f), 1.0f) * a;
+  float cp = fmaf(a2, fmaf(a2, fmaf(a2, fmaf(a2, 2.4801587e-5f, -1.3888889e-3f), 4.1666667e-2f), -0.5f), 1.0f);
+  // rotate by q * pi/4
+  const float h = 0.70710678118654752f;
+  float sq, cq;
+  switch (q & 7u) {
+    case 0: sq = 0.f; cq = 1.f; break;
+    case 1: sq = h; cq = h; break;
+    case 2: sq = 1.f; cq = 0.f; break;
+    case 3: sq = h; cq = -h; break;
+    case 4: sq = 0.f; cq = -1.f; break;
+    case 5: sq = -h; cq = -h; break;
+    case 6: sq = -1.f; cq = 0.f; break;
+    default: sq = -h; cq = h; break;
+  }
+  *s = fmaf(sq, cp, cq * sp);
+  *c = fmaf(cq, cp, -sq * sp);
+}
+
+__device__ inline void box_muller(uint32_t ou, uint32_t oa, float* n0, float* n1) {
+  const float u = (float)((ou >> 8) + 1u) * (1.0f / 16777216.0f);
+  const float r = sqrtf(-2.0f * logf(u));
+  float s, c;
+  sincos_turns(oa, &s, &c);
+  *n0 = r * c;
+  *n1 = r * s;
+}
+
+// four normals of coordinate group q
+__device__ inline float4 noise4(uint64_t seed, uint32_t node, uint32_t version, uint64_t q) {
+  uint32_t o[4];
+  philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), node, version, (uint32_t)seed, (uint32_t)(seed >> 32), o);
+  float4 z;
+  box_muller(o[0], o[1], &z.x, &z.y);
+  box_muller(o[2], o[3], &z.z, &z.w);
+  return z;
+}
+template <int VEC> __device__ inline typename V<VEC>::T noise_at(uint64_t seed, uint32_t node, uint32_t ver, int64_t k);
+template <> __device__ inline float4 noise_at<4>(uint64_t seed, uint32_t node, uint32_t ver, int64_t k) {
+  return noise4(seed, node, ver, (uint64_t)k >> 2);
+}
+template <> __device__ inline float noise_at<1>(uint64_t seed, uint32_t node, uint32_t ver, int64_t k) {
+  const float4 z = noise4(seed, node, ver, (uint64_t)k >> 2);
+  const int l = (int)(k & 3);
+  return l == 0 ? z.x : l == 1 ? z.y : l == 2 ? z.z : z.w;
+}
+
+// ------------------------------------------------------------------- kernel
+template <int MODE, int VEC>
+__global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float gamma, int tiles_per_node) {
+  using T = typename V<VEC>::T;
+  const int n_act = *s.n_active;
+  const int a = blockIdx.x / tiles_per_node;
+  if (a >= n_act) return;
+  const int tile = blockIdx.x - a * tiles_per_node;
+  const int64_t k = ((int64_t)tile * kThreads + threadIdx.x) * VEC;
+  if (k >= s.p) return;
+
+  const int i = s.active_list[a];
+  const int64_t p = s.p;
+  const int M = s.M;
+  const int t_old = s.plan_t[i];
+  const int slot_new = (t_old + 1) % M;
+  const int slot_cur = t_old % M;
+  const size_t node_off = (size_t)i * p + k;
+  float* g_old_p = s.g + (size_t)(t_old & 1) * s.n * p + node_off;
+  float* g_new_p = s.g + (size_t)((t_old + 1) & 1) * s.n * p + node_off;
+
+  T x_new, z_i, g_new, g_old;
+
+  if (MODE != RFAST_MODE_TRACK) {
+    // S1: local descent
+    const T x_i = V<VEC>::ld(s.x + node_off);
+    z_i = V<VEC>::ld(s.z + node_off);
+    const T v = fma_s(-gamma, z_i, x_i);
+    // S2a: pull the stamped neighbour copies and mix with row-stochastic weights
+    x_new = mul_s(s.r_self[i], v);
+    const int e0 = s.r_ptr[i], e1 = s.r_ptr[i + 1];
+    for (int eb = e0; eb < e1; eb += kBatch) {
+      T buf[kBatch];
+      float w[kBatch];
+#pragma unroll
+      for (int q = 0; q < kBatch; ++q) {
+        const int e = eb + q;
+        if (e < e1) {
+          const int j = s.r_src[e];
+          buf[q] = V<VEC>::ld(s.v_ring + ((size_t)j * M + s.slot_r[e]) * p + k);
+          w[q] = s.r_w[e];
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < kBatch; ++q)
+        if (eb + q < e1) x_new = fma_s(w[q], buf[q], x_new);
+    }
+    // S3 (v half): publish version t+1
+    V<VEC>::st(s.v_ring + ((size_t)i * M + slot_new) * p + k, v);
+    V<VEC>::st(s.x + node_off, x_new);
+    if (MODE == RFAST_MODE_MIX) return;
+  }
+
+  if (MODE == RFAST_MODE_FUSED) {
+    // sampled gradient of the diagonal quadratic at the new point
+    const T h = V<VEC>::ld((const float*)s.prob.data0 + node_off);
+    const T c = V<VEC>::ld((const float*)s.prob.data1 + node_off);
+    g_new = mul(h, sub(x_new, c));
+    if (s.prob.noise_std != 0.0f)
+      g_new = fma_s(s.prob.noise_std, noise_at<VEC>(s.prob.noise_seed, (uint32_t)i, (uint32_t)(t_old + 1), k), g_new);
+    V<VEC>::st(g_new_p, g_new);
+  } else {
+    z_i = V<VEC>::ld(s.z + node_off);
+    g_new = V<VEC>::ld(g_new_p);
+  }
+  g_old = V<VEC>::ld(g_old_p);
+
+  // S2b: tracker sum over the in-edges of C; S4: buffer what was consumed.
+  // An edge whose stamp did not move holds rho == rho~ exactly and is skipped.
+  T z_half = z_i;
+  {
+    const int e0 = s.c_ptr[i], e1 = s.c_ptr[i + 1];
+    for (int eb = e0; eb < e1; eb += kBatch) {
+      T rho[kBatch], rt[kBatch];
+      bool live[kBatch];
+#pragma unroll
+      for (int q = 0; q < kBatch; ++q) {
+        const int e = eb + q;
+        live[q] = e < e1 && !s.skip_c[e];
+        if (live[q]) {
+          rho[q] = V<VEC>::ld(s.rho_ring + ((size_t)e * M + s.slot_c[e]) * p + k);
+          rt[q] = V<VEC>::ld(s.rho_tilde + (size_t)e * p + k);
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < kBatch; ++q)
+        if (live[q]) {
+          z_half = add(z_half, sub(rho[q], rt[q]));
+          V<VEC>::st(s.rho_tilde + (size_t)(eb + q) * p + k, rho[q]);
+        }
+    }
+  }
+  z_half = sub(add(z_half, g_new), g_old);
+
+  // S2c: keep a_ii, push a_li as running sums; S3 (rho half): new version t+1
+  V<VEC>::st(s.z + node_off, mul_s(s.c_self[i], z_half));
+  {
+    const int o0 = s.co_ptr[i], o1 = s.co_ptr[i + 1];
+    for (int ob = o0; ob < o1; ob += kBatch) {
+      T cur[kBatch];
+#pragma unroll
+      for (int q = 0; q < kBatch; ++q)
+        if (ob + q < o1) cur[q] = V<VEC>::ld(s.rho_ring + ((size_t)s.co_eid[ob + q] * M + slot_cur) * p + k);
+#pragma unroll
+      for (int q = 0; q < kBatch; ++q)
+        if (ob + q < o1)
+          V<VEC>::st(s.rho_ring + ((size_t)s.co_eid[ob + q] * M + slot_new) * p + k, fma_s(s.co_w[ob + q], z_half, cur[q]));
+    }
+  }
+}
+
+// g^0 = h*(x^0 - c) + noise of sample version 0 (initialisation of Algorithm 1)
+template <int VEC>
+__global__ void __launch_bounds__(kThreads) rfast_diag_init_kernel(RfastDev s) {
+  const int i = blockIdx.y;
+  const int64_t k = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * VEC;
+  if (k >= s.p) return;
+  const size_t off = (size_t)i * s.p + k;
+  using T = typename V<VEC>::T;
+  const T h = V<VEC>::ld((const float*)s.prob.data0 + off);
+  const T c = V<VEC>::ld((const float*)s.prob.data1 + off);
+  T g = mul(h, sub(V<VEC>::ld(s.x + off), c));
+  if (s.prob.noise_std != 0.0f) g = fma_s(s.prob.noise_std, noise_at<VEC>(s.prob.noise_seed, (uint32_t)i, 0u, k), g);
+  V<VEC>::st(s.g + off, g);
+}
+
+template <int MODE>
+hipError_t launch(rfast_ctx* c, float gamma) {
+  const RfastDev& d = c->d;
+  const bool vec4 = (d.p % 4) == 0;
+  const int64_t per_block = (int64_t)kThreads * (vec4 ? 4 : 1);
+  const int64_t tiles = (d.p + per_block - 1) / per_block;
+  const int64_t blocks = tiles * d.n;
+  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (vec4)
+    hipLaunchKernelGGL((rfast_state_kernel<MODE, 4>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, d, gamma, (int)tiles);
+  else
+    hipLaunchKernelGGL((rfast_state_kernel<MODE, 1>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, d, gamma, (int)tiles);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t rfast_diag_init_gradient(rfast_ctx* c) {
+  const RfastDev& d = c->d;
+  const bool vec4 = (d.p % 4) == 0;
+  const int64_t per_block = (int64_t)kThreads * (vec4 ? 4 : 1);
+  const unsigned gx = (unsigned)((d.p + per_block - 1) / per_block);
+  if (vec4)
+    hipLaunchKernelGGL(rfast_diag_init_kernel<4>, dim3(gx, d.n), dim3(kThreads), 0, c->stream, d);
+  else
+    hipLaunchKernelGGL(rfast_diag_init_kernel<1>, dim3(gx, d.n), dim3(kThreads), 0, c->stream, d);
+  return hipGetLastError();
+}
+
+hipError_t rfast_launch_state(rfast_ctx* c, int mode, float gamma) {
+  switch (mode) {
+    case RFAST_MODE_FUSED: return launch<RFAST_MODE_FUSED>(c, gamma);
+    case RFAST_MODE_MIX: return launch<RFAST_MODE_MIX>(c, gamma);
+    default: return launch<RFAST_MODE_TRACK>(c, gamma);
+  }
+}

@@ -1,0 +1,116 @@
+"""Glue for the parity tests: builds the fp64 oracle and the GPU context from the
+same Workload and compares them.  The two sides only meet here."""
+import numpy as np
+
+
+def csr(g):
+    return (g.rowptr, g.col, g.w32())
+
+
+def make_oracle(w, coords=None, x0=None):
+    from oracle import objectives as ob
+    from oracle.rfast_oracle import RFastOracle
+    d = w.data
+    p = w.p
+    if w.objective == "diag_quadratic":
+        if coords is None:
+            obj = ob.DiagQuadratic(d["h"], d["c"], w.noise_std, w.noise_seed)
+        else:
+            obj = ob.DiagQuadratic(d["h"][:, coords], d["c"][:, coords], w.noise_std, w.noise_seed, coords, w.p)
+            p = len(coords)
+    elif w.objective == "least_squares":
+        obj = ob.LeastSquares(d["A"], d["b"])
+    elif w.objective == "logistic":
+        obj = ob.Logistic(d["X"], d["y"])
+    else:
+        from rfast_workloads.problems import bf16_bits_to_f32
+        obj = ob.SoftmaxBf16(bf16_bits_to_f32(d["Xb"]), d["labels"], w.extra["d"], w.extra["K"])
+    b0 = w.sched.initial_batch()
+    return RFastOracle(w.n, p, w.R, w.C, w.D, w.burst, obj, x0=x0, batch0=b0)
+
+
+def make_gpu(w, device="cuda:0"):
+    import torch
+    from paper_2307_11617_amd import RFast
+    d = w.data
+    kw = {}
+    if w.objective == "diag_quadratic":
+        d0, d1 = torch.from_numpy(d["h"]), torch.from_numpy(d["c"])
+        kw = dict(noise_std=w.noise_std, noise_seed=w.noise_seed)
+    elif w.objective == "least_squares":
+        d0, d1 = torch.from_numpy(d["A"]), torch.from_numpy(d["b"])
+        kw = dict(samples=d["A"].shape[1], batch=w.sched.batch)
+    elif w.objective == "logistic":
+        d0, d1 = torch.from_numpy(d["X"]), torch.from_numpy(d["y"])
+        kw = dict(samples=d["X"].shape[1], batch=w.sched.batch)
+    else:
+        d0 = torch.from_numpy(d["Xb"].view(np.int16)).view(torch.bfloat16)
+        d1 = torch.from_numpy(d["labels"])
+        kw = dict(samples=d["Xb"].shape[1], batch=w.sched.batch, d=w.extra["d"], K=w.extra["K"])
+    return RFast(w.n, w.p, csr(w.R), csr(w.C), w.D, w.burst, w.objective, d0, d1, device=device, **kw)
+
+
+def upload_chunk(gpu, w, r0, r1):
+    import torch
+    st = w.sched.stacked(r0, r1)
+    dev = {k: (None if v is None else torch.from_numpy(v).to(gpu.device)) for k, v in st.items()}
+    return st, dev
+
+
+def rel_l2(a, b, floor=0.0):
+    den = max(float(np.linalg.norm(b)), floor)
+    return float(np.linalg.norm(a.astype(np.float64) - b) / den) if den > 0 else float(np.linalg.norm(a))
+
+
+def run_parity(w, rounds, every=100, coords=None, x0=None, tol=None, check_rings=True, verbose=False):
+    """Runs `rounds` rounds on both sides; at every checkpoint compares integer
+    state exactly and x, z (and g, rho~) in relative L2.  Returns the worst errors."""
+    tol = w.tol if tol is None else tol
+    orc = make_oracle(w, coords, None if x0 is None else (x0 if coords is None else x0[:, coords]))
+    gpu = make_gpu(w)
+    gpu.init(x0, w.sched.initial_batch())
+    sel = slice(None) if coords is None else coords
+    M = w.D + 2
+    worst = {"x": 0.0, "z": 0.0, "g": 0.0}
+    g0 = gpu.read("G")[:, sel]
+    assert rel_l2(g0, orc.g) < 1e-5, ("initial gradient", rel_l2(g0, orc.g))
+    for r0 in range(0, rounds, every):
+        r1 = min(r0 + every, rounds)
+        st, dev = upload_chunk(gpu, w, r0, r1)
+        gpu.run(r1 - r0, dev["active"], dev["delay_R"], dev["delay_C"], dev["drop_R"], dev["drop_C"], w.gamma,
+                dev["batch_idx"])
+        for k in range(r1 - r0):
+            orc.round(st["active"][k], st["delay_R"][k], st["delay_C"][k], st["drop_R"][k], st["drop_C"][k], w.gamma,
+                      None if st["batch_idx"] is None else st["batch_idx"][k])
+        gpu.check()
+        # ---- integer state: bit-exact
+        sl = orc.slots()
+        assert np.array_equal(gpu.read("T_NODE"), sl["t"]), f"t differs at round {r1}"
+        assert np.array_equal(gpu.read("TAU_R"), sl["tau_v"]), f"tau_v differs at round {r1}"
+        assert np.array_equal(gpu.read("TAU_C"), sl["tau_rho"]), f"tau_rho differs at round {r1}"
+        assert int(gpu.read("ROUND")[0]) == r1
+        last = st["active"][r1 - r0 - 1]
+        for name, edges, slots in (("SLOT_R", orc.edges_R, sl["slot_v"]), ("SLOT_C", orc.edges_C, sl["slot_rho"])):
+            got = gpu.read(name)
+            exp = np.array([slots[e] if last[i] else -1 for e, (i, j) in enumerate(edges)], dtype=np.int32)
+            assert np.array_equal(got, exp), f"{name} differs at round {r1}"
+        # ---- floating state
+        x, z, g = gpu.read("X")[:, sel], gpu.read("Z")[:, sel], gpu.read("G")[:, sel]
+        gnorm = float(np.linalg.norm(orc.g))
+        ex, ez, eg = rel_l2(x, orc.x), rel_l2(z, orc.z, 1e-3 * gnorm), rel_l2(g, orc.g)
+        worst = {"x": max(worst["x"], ex), "z": max(worst["z"], ez), "g": max(worst["g"], eg)}
+        if verbose:
+            print(f"round {r1}: rel-L2 x {ex:.2e} z {ez:.2e} g {eg:.2e}", flush=True)
+        assert ex <= tol and ez <= tol, f"round {r1}: x {ex:.3e} z {ez:.3e} (tol {tol})"
+        if check_rings and coords is None and w.n * w.p * M <= 4_000_000:
+            vr, rr, rt = gpu.read("V_RING"), gpu.read("RHO_RING"), gpu.read("RHO_TILDE")
+            for j in range(w.n):
+                tj = int(orc.t[j])
+                for ver in range(max(0, tj - w.D), tj + 1):
+                    assert rel_l2(vr[j, ver % M], orc.v[j][ver], 1e-6) <= 10 * tol
+            for e, (i, j) in enumerate(orc.edges_C):
+                tj = int(orc.t[j])
+                scale = 1e-3 * gnorm + 1e-6
+                assert rel_l2(rr[e, tj % M], orc.rho[e][tj], scale) <= 10 * tol
+                assert rel_l2(rt[e], orc.rho_tilde[e], scale) <= 10 * tol
+    return worst, orc, gpu

@@ -1,0 +1,151 @@
+#!/usr/bin/env python3
+"""Benchmark of the R-FAST activation round on one MI355X.
+
+A step is one round of the whole hot path (resolver + state update + local
+gradients) over one batch of synthetic input that is already resident in HBM.
+The default workload is config 2 (n=16 bidirectional ring, diagonal quadratic,
+p = 11.2 M, every node active), the configuration the HBM-roofline target is
+quoted on.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for pth in (ROOT, os.path.join(ROOT, "tests")):
+    if pth not in sys.path:
+        sys.path.insert(0, pth)
+
+import numpy as np  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes_per_round(w, active_counts):
+    """7 + dR + 3 dI + 2 dO fp32 words per coordinate per node-update (reads x, z,
+    g_prev, dR v's, dI rho's, dI rho~'s, dO current rho's; writes x, z, g, v, dO new
+    rho's, dI rho~'s), plus 2 words of objective data (h, c) for the diagonal quadratic."""
+    Rd, Cd = w.R.dense(), w.C.dense()
+    n = w.n
+    dR = (Rd != 0).sum(axis=1) - 1
+    dI = (Cd != 0).sum(axis=1) - 1
+    dO = (Cd != 0).sum(axis=0) - 1
+    words = 7 + dR + 3 * dI + 2 * dO + (2 if w.objective == "diag_quadratic" else 0)
+    return float((words * active_counts).sum() * 4.0 * w.p)
+
+
+def cpu_baseline(w, seconds_target=15.0):
+    """The fp64 oracle as it stands, on a coordinate subset of the same workload
+    (the objective is separable, so a subset costs exactly its share)."""
+    import harness
+    if w.objective == "diag_quadratic":
+        p_sub = min(w.p, 400_000)
+        coords = np.arange(p_sub, dtype=np.int64) * (w.p // p_sub)
+    else:
+        coords, p_sub = None, w.p
+    orc = harness.make_oracle(w, coords)
+    rounds, updates = 0, 0
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds_target and rounds < w.rounds:
+        q = w.sched.round(rounds)
+        orc.round(q.active, q.delay_R, q.delay_C, q.drop_R, q.drop_C, w.gamma, q.batch_idx)
+        updates += int(q.active.sum())
+        rounds += 1
+    dt = time.perf_counter() - t0
+    frac = p_sub / w.p
+    return {"value": updates * frac / dt, "unit": "node-updates/s", "cores": 1, "kind": "oracle",
+            "param_elements_per_s": updates * p_sub / dt,
+            "sample": f"{rounds} rounds of the same schedule on {p_sub} of {w.p} coordinates "
+                      f"(every {w.p // p_sub}-th), scaled by {frac:.4g}; NumPy fp64, single thread"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--p", type=int, default=0, help="override p (not the headline workload)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="run only a plain 1 GiB device copy (10 launches): calibrates HBM byte counters")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives exist in it); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if args.copy_probe:
+        a = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda:0")
+        b = torch.empty_like(a)
+        for _ in range(10):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_read": a.numel() * 4, "copy_probe_bytes_written": a.numel() * 4, "launches": 10}))
+        return
+    import harness
+    from rfast_workloads import configs
+    import paper_2307_11617_amd as rf
+
+    kw = {"p": args.p} if args.p else {}
+    t_gen = time.perf_counter()
+    w = configs.CONFIGS[args.config](**kw)
+    gen_s = time.perf_counter() - t_gen
+    K, W = args.steps, args.warmup
+    gpu = harness.make_gpu(w)
+    gpu.init(None, w.sched.initial_batch())
+    st, dev = harness.upload_chunk(gpu, w, 0, W + 2 * K)
+    sl = lambda name, a, b: None if dev[name] is None else dev[name][a:b].contiguous()
+    run = lambda a, b: gpu.run(b - a, sl("active", a, b), sl("delay_R", a, b), sl("delay_C", a, b), sl("drop_R", a, b),
+                               sl("drop_C", a, b), w.gamma, sl("batch_idx", a, b))
+    run(0, W)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(W, W + K)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    gpu.check()
+
+    # second pass with HIP events around every kernel launch (on the library's stream)
+    rf.rfast_profile_enable(gpu.ctx, True)
+    run(W + K, W + 2 * K)
+    ms_state, n_state = rf.rfast_kernel_time(gpu.ctx, 0)
+    ms_grad, n_grad = rf.rfast_kernel_time(gpu.ctx, 1)
+    ms_res, n_res = rf.rfast_kernel_time(gpu.ctx, 2)
+    rf.rfast_profile_enable(gpu.ctx, False)
+
+    act_timed = st["active"][W:W + K].astype(np.int64)
+    act_prof = st["active"][W + K:W + 2 * K].astype(np.int64)
+    updates = int(act_timed.sum())
+    bytes_prof = sum(algorithmic_bytes_per_round(w, a) for a in act_prof)
+    launches = max(n_state, 1)
+    avg_ms = ms_state / launches
+    achieved = bytes_prof / (ms_state * 1e-3) / 1e9 if ms_state > 0 else 0.0
+    out = {
+        "metric": "node-updates/sec",
+        "value": updates / dt,
+        "unit": "node-updates/s",
+        "param_elements_per_s": updates * w.p / dt,
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": dt / K * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "n": w.n, "p": w.p, "D": w.D, "ring_slots": w.D + 2, "objective": w.objective,
+                   "mean_active_per_round": updates / K, "gamma": w.gamma},
+        "roofline": {"bound": "hbm", "kernel": "rfast_state_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "avg_kernel_ms": avg_ms, "launches": n_state,
+                     "algorithmic_bytes_per_launch": bytes_prof / launches, "traffic": None},
+        "kernel_ms": {"state": ms_state, "gradient": ms_grad, "resolver": ms_res,
+                      "launches": {"state": n_state, "gradient": n_grad, "resolver": n_res}},
+        "host_data_generation_s": gen_s,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+        out["gpu_over_cpu"] = out["value"] / out["cpu_baseline"]["value"]
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

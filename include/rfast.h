@@ -65,7 +65,8 @@ typedef enum rfast_objective {
   RFAST_OBJ_DIAG_QUADRATIC = 0, /* f_i = 1/2 sum_k h_ik (x_k - c_ik)^2, gradient + noise_std*N(0,I) */
   RFAST_OBJ_LEAST_SQUARES = 1,  /* f_i = 1/(2m) ||A_i x - b_i||^2                                   */
   RFAST_OBJ_LOGISTIC = 2,       /* f_i = mean_s [log(1+exp(a_s.x)) - y_s a_s.x] + lambda/2 ||x||^2  */
-  RFAST_OBJ_SOFTMAX_BF16 = 3    /* softmax regression, W = x as d x K row-major, bf16 MFMA GEMMs    */
+  RFAST_OBJ_SOFTMAX_BF16 = 3    /* softmax regression, W = x as d x K row-major, bf16 MFMA GEMMs;
+                                   needs d % 64 == 0, K in {32,64,96,128}, rows per gradient % 64 == 0 */
 } rfast_objective;
 
 typedef struct rfast_problem {

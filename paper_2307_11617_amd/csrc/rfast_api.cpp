@@ -10,6 +10,7 @@
 
 size_t rfast_gemv_scratch_floats(int32_t n, const rfast_problem* prob);
 size_t rfast_softmax_scratch_bytes(int32_t n, const rfast_problem* prob);
+bool rfast_softmax_shape_ok(const rfast_problem* prob);
 
 namespace {
 
@@ -45,7 +46,9 @@ bool sizes_ok(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, const
   if ((prob->kind == RFAST_OBJ_LEAST_SQUARES || prob->kind == RFAST_OBJ_LOGISTIC) &&
       (prob->batch > 0 ? prob->batch : prob->samples) > 4096)
     return false;  // the sampled residuals of one node are staged in LDS
-  if (prob->kind == RFAST_OBJ_SOFTMAX_BF16 && (prob->d < 1 || prob->K < 1 || (int64_t)prob->d * prob->K != p)) return false;
+  if (prob->kind == RFAST_OBJ_SOFTMAX_BF16 &&
+      (prob->d < 1 || prob->K < 1 || (int64_t)prob->d * prob->K != p || !rfast_softmax_shape_ok(prob)))
+    return false;  // MFMA tiling: d % 64 == 0, K in {32, 64, 96, 128}, rows per gradient % 64 == 0
   return true;
 }
 

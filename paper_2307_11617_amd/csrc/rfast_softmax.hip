@@ -1,4 +1,282 @@
-// Softmax-regression gradient (bf16 MFMA) — placeholder until the kernels land.
+// Softmax-regression minibatch gradient on the matrix cores (step S2b of
+// Algorithm 1 needs grad f_i at the freshly mixed x_i; this is the only dense
+// contraction on the path, so it is the only place MFMA is used).
+//
+// x_i is W (d x K, row-major).  With Xb the B sampled rows of the node's bf16
+// pool:   logits = Xb * bf16(W)            (B x K, contraction over d)
+//         E      = bf16((softmax(logits) - onehot) / B)
+//         G      = Xb^T * E                (d x K, contraction over B)
+// bf16 x bf16 products accumulate in fp32 (v_mfma_f32_32x32x16_bf16).  Both
+// MFMA operands want 8 consecutive elements of the contraction index per lane,
+// so three small kernels keep every operand contiguous along it:
+//   prep      Wt[k][f] = bf16(W[f][k])             (transpose through LDS)
+//   forward   tile of 64 sampled rows x all K classes: X rows and Wt rows are
+//             both contiguous in f; row softmax in the same block; E is written
+//             class-major, Et[k][b]
+//   backward  tile of 64 features x all K classes: Et rows are contiguous in b;
+//             the X tile is transposed while it is staged into LDS
+// Operand layout of the 32x32x16 instruction (lane l of 64):
+//   A: row l%32, contraction indices 8*(l/32) .. +7      (8 bf16)
+//   B: column l%32, contraction indices 8*(l/32) .. +7   (8 bf16)
+//   C/D: column l%32, rows 8*(v/4) + 4*(l/32) + v%4 for v = 0..15
 #include "rfast_internal.h"
-hipError_t rfast_softmax_gradient(rfast_ctx*, const int32_t*, bool) { return hipErrorNotSupported; }
-size_t rfast_softmax_scratch_bytes(int32_t, const rfast_problem*) { return 0; }
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned short u16;
+
+constexpr int kTile = 64;       // rows (forward) / features (backward) per block, and staging depth
+constexpr int kPad = 8;         // LDS row padding in bf16 elements (16 bytes)
+constexpr int kLd = kTile + kPad;
+
+__device__ inline u16 f32_to_bf16(float f) {  // round to nearest even
+  const uint32_t u = __float_as_uint(f);
+  return (u16)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+
+__device__ inline int pick_node(const RfastDev& s, bool init) {
+  if (init) return blockIdx.y;
+  return (int)blockIdx.y < *s.n_active ? s.active_list[blockIdx.y] : -1;
+}
+
+__device__ inline int sample_row(const RfastDev& s, const int32_t* batch_idx, int i, int b, int B) {
+  if (batch_idx == nullptr) return b;
+  int row = batch_idx[(size_t)i * B + b];
+  if (row < 0 || row >= s.prob.samples) {
+    if (atomicCAS(&s.err[0], 0, RFAST_ERANGE) == 0) {
+      s.err[1] = *s.round_no;
+      s.err[2] = 2;
+      s.err[3] = i;
+    }
+    row = row < 0 ? 0 : s.prob.samples - 1;
+  }
+  return row;
+}
+
+struct Scratch {
+  u16* wt;  // [n][K][d]
+  u16* et;  // [n][K][B]
+};
+__device__ __host__ inline Scratch scratch_of(const RfastDev& s, int B) {
+  Scratch r;
+  r.wt = (u16*)s.gscratch;
+  r.et = r.wt + (size_t)s.n * s.prob.K * s.prob.d;
+  return r;
+}
+
+// ---------------------------------------------------------------- prep: Wt = bf16(W)^T
+__global__ void __launch_bounds__(256) rfast_softmax_prep(RfastDev s, int B, bool init) {
+  extern __shared__ u16 lds[];  // [K][kLd]
+  const int i = pick_node(s, init);
+  if (i < 0) return;
+  const int d = s.prob.d, K = s.prob.K;
+  const int f0 = blockIdx.x * kTile;
+  const float* W = s.x + (size_t)i * s.p;
+  for (int q = threadIdx.x; q < kTile * K / 4; q += blockDim.x) {
+    const int f = q / (K / 4), k4 = (q % (K / 4)) * 4;
+    const float4 w = *reinterpret_cast<const float4*>(W + (size_t)(f0 + f) * K + k4);
+    lds[(k4 + 0) * kLd + f] = f32_to_bf16(w.x);
+    lds[(k4 + 1) * kLd + f] = f32_to_bf16(w.y);
+    lds[(k4 + 2) * kLd + f] = f32_to_bf16(w.z);
+    lds[(k4 + 3) * kLd + f] = f32_to_bf16(w.w);
+  }
+  __syncthreads();
+  u16* wt = scratch_of(s, B).wt + (size_t)i * K * d;
+  for (int q = threadIdx.x; q < K * kTile / 8; q += blockDim.x) {
+    const int k = q / (kTile / 8), c = (q % (kTile / 8)) * 8;
+    *reinterpret_cast<uint4*>(wt + (size_t)k * d + f0 + c) = *reinterpret_cast<const uint4*>(&lds[k * kLd + c]);
+  }
+}
+
+// ------------------------------------------------------------------------- forward
+// grid (B/64, nodes); blockDim = 64 * (K/32): wave w owns classes 32w .. 32w+31.
+__global__ void __launch_bounds__(256) rfast_softmax_forward(RfastDev s, const int32_t* batch_idx, int B, bool init) {
+  extern __shared__ u16 lds[];
+  const int i = pick_node(s, init);
+  if (i < 0) return;
+  const int d = s.prob.d, K = s.prob.K;
+  u16* Xs = lds;                  // [64][kLd]
+  u16* Ws = lds + kTile * kLd;    // [K][kLd]
+  __shared__ int rows[kTile];
+  __shared__ int labs[kTile];
+  const int b0 = blockIdx.x * kTile;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const u16* pool = (const u16*)s.prob.data0 + (size_t)i * s.prob.samples * d;
+  const int32_t* labels = (const int32_t*)s.prob.data1 + (size_t)i * s.prob.samples;
+  const Scratch sc = scratch_of(s, B);
+  const u16* wt = sc.wt + (size_t)i * K * d;
+  for (int r = threadIdx.x; r < kTile; r += blockDim.x) {
+    rows[r] = sample_row(s, batch_idx, i, b0 + r, B);
+    labs[r] = labels[rows[r]];
+  }
+  __syncthreads();
+
+  f32x16 acc[2];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) { acc[0][v] = 0.f; acc[1][v] = 0.f; }
+
+  for (int f0 = 0; f0 < d; f0 += kTile) {
+    for (int q = threadIdx.x; q < kTile * kTile / 8; q += blockDim.x) {
+      const int r = q / (kTile / 8), c = (q % (kTile / 8)) * 8;
+      *reinterpret_cast<uint4*>(&Xs[r * kLd + c]) = *reinterpret_cast<const uint4*>(pool + (size_t)rows[r] * d + f0 + c);
+    }
+    for (int q = threadIdx.x; q < K * kTile / 8; q += blockDim.x) {
+      const int k = q / (kTile / 8), c = (q % (kTile / 8)) * 8;
+      *reinterpret_cast<uint4*>(&Ws[k * kLd + c]) = *reinterpret_cast<const uint4*>(wt + (size_t)k * d + f0 + c);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < kTile; kk += 16) {
+      const int off = kk + 8 * (lane >> 5);
+      const bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(&Ws[(wave * 32 + (lane & 31)) * kLd + off]);
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt) {
+        const bf16x8 afrag = *reinterpret_cast<const bf16x8*>(&Xs[(rt * 32 + (lane & 31)) * kLd + off]);
+        acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag, acc[rt], 0, 0, 0);
+      }
+    }
+    __syncthreads();
+  }
+
+  // logits -> LDS [64][K+1] fp32 (reuses the staging space)
+  float* L = reinterpret_cast<float*>(lds);
+  const int ldl = K + 1;
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = rt * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+      L[row * ldl + wave * 32 + (lane & 31)] = acc[rt][v];
+    }
+  __syncthreads();
+  // row softmax: each wave takes rows wave, wave + nwaves, ...; lanes stride over classes
+  const int nwaves = blockDim.x >> 6;
+  const float invB = 1.0f / (float)B;
+  for (int r = wave; r < kTile; r += nwaves) {
+    float m = -INFINITY;
+    for (int k = lane; k < K; k += 64) m = fmaxf(m, L[r * ldl + k]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+    float sum = 0.f;
+    for (int k = lane; k < K; k += 64) {
+      const float e = expf(L[r * ldl + k] - m);
+      L[r * ldl + k] = e;
+      sum += e;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+    const float inv = 1.0f / sum;
+    for (int k = lane; k < K; k += 64) {
+      const float pr = L[r * ldl + k] * inv - (k == labs[r] ? 1.0f : 0.0f);
+      L[r * ldl + k] = pr * invB;
+    }
+  }
+  __syncthreads();
+  // Et[k][b0 .. b0+64): 8 consecutive rows per 16-byte store
+  u16* et = sc.et + (size_t)i * K * B;
+  for (int q = threadIdx.x; q < K * kTile / 8; q += blockDim.x) {
+    const int k = q / (kTile / 8), c = (q % (kTile / 8)) * 8;
+    u16 h[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) h[j] = f32_to_bf16(L[(c + j) * ldl + k]);
+    uint4 pk;
+    pk.x = h[0] | ((uint32_t)h[1] << 16);
+    pk.y = h[2] | ((uint32_t)h[3] << 16);
+    pk.z = h[4] | ((uint32_t)h[5] << 16);
+    pk.w = h[6] | ((uint32_t)h[7] << 16);
+    *reinterpret_cast<uint4*>(et + (size_t)k * B + b0 + c) = pk;
+  }
+}
+
+// ------------------------------------------------------------------------ backward
+// grid (d/64, nodes); wave w owns classes 32w .. 32w+31, both 32-feature tiles.
+__global__ void __launch_bounds__(256) rfast_softmax_backward(RfastDev s, const int32_t* batch_idx, int B, bool init) {
+  extern __shared__ u16 lds[];
+  const int i = pick_node(s, init);
+  if (i < 0) return;
+  const int d = s.prob.d, K = s.prob.K;
+  u16* Xt = lds;                  // [64 features][kLd]  (transposed while staging)
+  u16* Es = lds + kTile * kLd;    // [K][kLd]
+  __shared__ int rows[kTile];
+  const int f0 = blockIdx.x * kTile;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const u16* pool = (const u16*)s.prob.data0 + (size_t)i * s.prob.samples * d;
+  const u16* et = scratch_of(s, B).et + (size_t)i * K * B;
+
+  f32x16 acc[2];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) { acc[0][v] = 0.f; acc[1][v] = 0.f; }
+
+  for (int b0 = 0; b0 < B; b0 += kTile) {
+    for (int r = threadIdx.x; r < kTile; r += blockDim.x) rows[r] = sample_row(s, batch_idx, i, b0 + r, B);
+    __syncthreads();
+    for (int q = threadIdx.x; q < kTile * kTile / 8; q += blockDim.x) {
+      const int r = q / (kTile / 8), c = (q % (kTile / 8)) * 8;
+      const uint4 x8 = *reinterpret_cast<const uint4*>(pool + (size_t)rows[r] * d + f0 + c);
+      const uint32_t w[4] = {x8.x, x8.y, x8.z, x8.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        Xt[(c + 2 * j) * kLd + r] = (u16)(w[j] & 0xFFFFu);
+        Xt[(c + 2 * j + 1) * kLd + r] = (u16)(w[j] >> 16);
+      }
+    }
+    for (int q = threadIdx.x; q < K * kTile / 8; q += blockDim.x) {
+      const int k = q / (kTile / 8), c = (q % (kTile / 8)) * 8;
+      *reinterpret_cast<uint4*>(&Es[k * kLd + c]) = *reinterpret_cast<const uint4*>(et + (size_t)k * B + b0 + c);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < kTile; kk += 16) {
+      const int off = kk + 8 * (lane >> 5);
+      const bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(&Es[(wave * 32 + (lane & 31)) * kLd + off]);
+#pragma unroll
+      for (int ft = 0; ft < 2; ++ft) {
+        const bf16x8 afrag = *reinterpret_cast<const bf16x8*>(&Xt[(ft * 32 + (lane & 31)) * kLd + off]);
+        acc[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag, acc[ft], 0, 0, 0);
+      }
+    }
+    __syncthreads();
+  }
+  const int t_old = init ? -1 : s.plan_t[i];
+  float* G = s.g + (size_t)((t_old + 1) & 1) * s.n * s.p + (size_t)i * s.p;
+#pragma unroll
+  for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int f = f0 + ft * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+      G[(size_t)f * K + wave * 32 + (lane & 31)] = acc[ft][v];
+    }
+}
+
+}  // namespace
+
+// Shapes the kernels assume; checked once at context creation.
+bool rfast_softmax_shape_ok(const rfast_problem* prob) {
+  const int B = prob->batch > 0 ? prob->batch : prob->samples;
+  return prob->d % kTile == 0 && prob->K % 32 == 0 && prob->K >= 32 && prob->K <= 128 && B % kTile == 0;
+}
+
+size_t rfast_softmax_scratch_bytes(int32_t n, const rfast_problem* prob) {
+  if (prob->kind != RFAST_OBJ_SOFTMAX_BF16) return 0;
+  const int B = prob->batch > 0 ? prob->batch : prob->samples;
+  return ((size_t)n * prob->K * prob->d + (size_t)n * prob->K * B) * sizeof(u16);
+}
+
+hipError_t rfast_softmax_gradient(rfast_ctx* c, const int32_t* batch_idx, bool init) {
+  const RfastDev& d = c->d;
+  if (!rfast_softmax_shape_ok(&d.prob)) return hipErrorInvalidValue;
+  const int B = d.prob.batch > 0 ? d.prob.batch : d.prob.samples;
+  const int32_t* bi = d.prob.batch > 0 ? batch_idx : nullptr;
+  const int K = d.prob.K;
+  const unsigned threads = 64u * (unsigned)(K / 32);
+  const size_t lds_prep = (size_t)K * kLd * sizeof(u16);
+  const size_t lds_stage = (size_t)(kTile + K) * kLd * sizeof(u16);
+  const size_t lds_logits = (size_t)kTile * (K + 1) * sizeof(float);
+  const size_t lds_fwd = lds_stage > lds_logits ? lds_stage : lds_logits;
+  hipLaunchKernelGGL(rfast_softmax_prep, dim3(d.prob.d / kTile, d.n), dim3(256), lds_prep, c->stream, d, B, init);
+  hipLaunchKernelGGL(rfast_softmax_forward, dim3(B / kTile, d.n), dim3(threads), lds_fwd, c->stream, d, bi, B, init);
+  hipLaunchKernelGGL(rfast_softmax_backward, dim3(d.prob.d / kTile, d.n), dim3(threads), lds_stage, c->stream, d, bi, B, init);
+  return hipGetLastError();
+}

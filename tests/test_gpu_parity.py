@@ -43,6 +43,13 @@ def test_config1_small():
     _report(w.name, worst)
 
 
+def test_config4_small():
+    """bf16 MFMA softmax gradient: several row blocks and feature blocks, two class tiles."""
+    w = configs.config4(d=192, K=64, samples=320, batch=128, rounds=300)
+    worst, orc, gpu = harness.run_parity(w, 300, every=100)
+    _report(w.name, worst)
+
+
 def test_x0_nonzero_and_noise_free():
     rng = np.random.default_rng(0)
     w = configs.config2(p=2048, rounds=200)

@@ -32,8 +32,22 @@ def algorithmic_bytes_per_round(w, active_counts):
     dR = (Rd != 0).sum(axis=1) - 1
     dI = (Cd != 0).sum(axis=1) - 1
     dO = (Cd != 0).sum(axis=0) - 1
-    words = 7 + dR + 3 * dI + 2 * dO + (2 if w.objective == "diag_quadratic" else 0)
+    # fused kernel: + h and c; split mix/track pair: + the re-read of g_new and of z
+    words = 7 + dR + 3 * dI + 2 * dO + (2 if w.objective == "diag_quadratic" else 1)
     return float((words * active_counts).sum() * 4.0 * w.p)
+
+
+def measured_traffic(workload_name):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if any."""
+    path = os.path.join(ROOT, "profiles", f"{workload_name}_state_kernel_hbm_traffic.md")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(w, seconds_target=15.0):
@@ -133,14 +147,22 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "n": w.n, "p": w.p, "D": w.D, "ring_slots": w.D + 2, "objective": w.objective,
                    "mean_active_per_round": updates / K, "gamma": w.gamma},
-        "roofline": {"bound": "hbm", "kernel": "rfast_state_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "rfast_state_kernel" + ("<FUSED>" if w.objective == "diag_quadratic" else "<MIX>+<TRACK>"), "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "avg_kernel_ms": avg_ms, "launches": n_state,
-                     "algorithmic_bytes_per_launch": bytes_prof / launches, "traffic": None},
+                     "algorithmic_bytes_per_launch": bytes_prof / launches,
+                     "traffic": measured_traffic(w.name) if not args.p else None},
         "kernel_ms": {"state": ms_state, "gradient": ms_grad, "resolver": ms_res,
                       "launches": {"state": n_state, "gradient": n_grad, "resolver": n_res}},
         "host_data_generation_s": gen_s,
     }
+    if w.objective == "softmax_bf16":
+        # the two GEMMs of the softmax gradient: 2*B*d*K flops each per node-update
+        flops = 4.0 * w.sched.batch * w.extra["d"] * w.extra["K"] * float(act_prof.sum())
+        tf = flops / (ms_grad * 1e-3) / 1e12 if ms_grad > 0 else 0.0
+        out["roofline_mfma"] = {"bound": "mfma", "kernel": "rfast_softmax_prep+forward+backward", "achieved": tf,
+                                "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0,
+                                "intensity_limited_peak": 680.0, "avg_ms_per_round": ms_grad / max(n_grad, 1)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
         out["gpu_over_cpu"] = out["value"] / out["cpu_baseline"]["value"]

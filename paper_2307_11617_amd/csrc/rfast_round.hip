@@ -18,14 +18,32 @@ constexpr int kThreads = 256;
 constexpr int kBatch = 8;  // loads kept in flight per edge phase
 
 // ------------------------------------------------------------ vector helpers
+// VEC = 4: float4 per lane.  VEC = -4: the same with non-temporal (streaming)
+// loads and stores, used when the state is far larger than the caches, so
+// that lines with no reuse do not displace anything.  VEC = 1: scalar, p % 4 != 0.
+typedef float nt_f4 __attribute__((ext_vector_type(4)));
 template <int VEC> struct V;
 template <> struct V<4> {
   using T = float4;
+  static constexpr int W = 4;
   static __device__ inline T ld(const float* p) { return *reinterpret_cast<const float4*>(p); }
   static __device__ inline void st(float* p, T v) { *reinterpret_cast<float4*>(p) = v; }
 };
+template <> struct V<-4> {
+  using T = float4;
+  static constexpr int W = 4;
+  static __device__ inline T ld(const float* p) {
+    const nt_f4 t = __builtin_nontemporal_load(reinterpret_cast<const nt_f4*>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
+  }
+  static __device__ inline void st(float* p, T v) {
+    const nt_f4 t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<nt_f4*>(p));
+  }
+};
 template <> struct V<1> {
   using T = float;
+  static constexpr int W = 1;
   static __device__ inline T ld(const float* p) { return *p; }
   static __device__ inline void st(float* p, T v) { *p = v; }
 };
@@ -107,6 +125,9 @@ template <int VEC> __device__ inline typename V<VEC>::T noise_at(uint64_t seed, 
 template <> __device__ inline float4 noise_at<4>(uint64_t seed, uint32_t node, uint32_t ver, int64_t k) {
   return noise4(seed, node, ver, (uint64_t)k >> 2);
 }
+template <> __device__ inline float4 noise_at<-4>(uint64_t seed, uint32_t node, uint32_t ver, int64_t k) {
+  return noise4(seed, node, ver, (uint64_t)k >> 2);
+}
 template <> __device__ inline float noise_at<1>(uint64_t seed, uint32_t node, uint32_t ver, int64_t k) {
   const float4 z = noise4(seed, node, ver, (uint64_t)k >> 2);
   const int l = (int)(k & 3);
@@ -121,7 +142,7 @@ __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float
   const int a = blockIdx.x / tiles_per_node;
   if (a >= n_act) return;
   const int tile = blockIdx.x - a * tiles_per_node;
-  const int64_t k = ((int64_t)tile * kThreads + threadIdx.x) * VEC;
+  const int64_t k = ((int64_t)tile * kThreads + threadIdx.x) * V<VEC>::W;
   if (k >= s.p) return;
 
   const int i = s.active_list[a];
@@ -247,7 +268,11 @@ hipError_t launch(rfast_ctx* c, float gamma) {
   const int64_t tiles = (d.p + per_block - 1) / per_block;
   const int64_t blocks = tiles * d.n;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  if (vec4)
+  // stream past the caches once the per-round working set dwarfs them (256 MB of last-level cache)
+  const bool streaming = (double)d.n * (double)d.p * 4.0 >= 512.0e6;
+  if (vec4 && streaming)
+    hipLaunchKernelGGL((rfast_state_kernel<MODE, -4>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, d, gamma, (int)tiles);
+  else if (vec4)
     hipLaunchKernelGGL((rfast_state_kernel<MODE, 4>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, d, gamma, (int)tiles);
   else
     hipLaunchKernelGGL((rfast_state_kernel<MODE, 1>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, d, gamma, (int)tiles);

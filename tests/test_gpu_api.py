@@ -1,0 +1,139 @@
+"""GPU tests of the ABI's behaviour around the round itself: diagnostics against
+the oracle's, device-side range checks (inputs are clamped, never faulting),
+single rounds vs stacked runs, re-initialisation, the profiling hooks."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2307_11617_amd as rf
+from rfast_workloads import configs
+
+import harness
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev_round(gpu, q):
+    t = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(gpu.device)
+    return t(q.active), t(q.delay_R), t(q.delay_C), t(q.drop_R), t(q.drop_C), t(q.batch_idx)
+
+
+def test_diagnostics_match_oracle():
+    w = configs.config3(p=4100, rounds=150)
+    worst, orc, gpu = harness.run_parity(w, 150, every=50)
+    h, c = w.data["h"].astype(np.float64), w.data["c"].astype(np.float64)
+    x_star = (h * c).sum(axis=0) / h.sum(axis=0)
+    ref = orc.diagnostics(x_star)
+    got = gpu.diagnostics(torch.from_numpy(x_star.astype(np.float32)).to(gpu.device))
+    for key in ("consensus_sq", "z_sq", "gsum_sq", "xbar_gap_sq", "loss_at_xbar"):
+        assert abs(got[key] - ref[key]) <= 2e-4 * abs(ref[key]), (key, got[key], ref[key])
+    # Lemma 3 in fp32: the residual is rounding noise relative to the tracked mass
+    assert got["conservation_sq"] <= 1e-9 * (got["gsum_sq"] + got["z_sq"])
+    assert gpu.diagnostics(None)["xbar_gap_sq"] == -1.0
+
+
+def test_single_rounds_equal_stacked_run():
+    w = configs.config0(rounds=40)
+    a, b = harness.make_gpu(w), harness.make_gpu(w)
+    a.init()
+    b.init()
+    st, dev = harness.upload_chunk(a, w, 0, 40)
+    a.run(40, dev["active"], dev["delay_R"], dev["delay_C"], dev["drop_R"], dev["drop_C"], w.gamma)
+    for r in range(40):
+        act, dR, dC, xR, xC, _ = _dev_round(b, w.sched.round(r))
+        b.round(act, dR, dC, xR, xC, w.gamma)
+    for f in ("X", "Z", "G", "V_RING", "RHO_RING", "RHO_TILDE", "T_NODE", "TAU_R", "TAU_C"):
+        assert np.array_equal(a.read(f), b.read(f)), f
+    # re-initialising restores the start state exactly
+    g1 = a.read("G")
+    a.init()
+    b.init()
+    assert int(a.read("ROUND")[0]) == 0 and not a.read("T_NODE").any() and not a.read("V_RING").any()
+    assert np.array_equal(a.read("Z"), a.read("G")) and not np.array_equal(a.read("G"), g1)
+
+
+def test_out_of_range_delay_is_clamped_and_reported():
+    w = configs.config0(rounds=5)
+    gpu = harness.make_gpu(w)
+    gpu.init()
+    q = w.sched.round(0)
+    q.active[:] = 1
+    q.delay_C[3] = w.D + 5
+    act, dR, dC, xR, xC, _ = _dev_round(gpu, q)
+    gpu.round(act, dR, dC, xR, xC, w.gamma)
+    with pytest.raises(rf.RFastError) as ei:
+        gpu.check()
+    assert ei.value.code == -4 and "C edge 3" in str(ei.value) and "round 0" in str(ei.value)
+    assert np.isfinite(gpu.read("X")).all()
+    gpu.init()          # clears the sticky status
+    gpu.check()
+
+
+def test_out_of_range_sample_row_is_clamped_and_reported():
+    w = configs.config1(p=256, samples=64, batch=16, rounds=3)
+    gpu = harness.make_gpu(w)
+    gpu.init(None, w.sched.initial_batch())
+    q = w.sched.round(0)
+    q.active[:] = 1
+    q.batch_idx[5, 2] = 64
+    act, dR, dC, xR, xC, bi = _dev_round(gpu, q)
+    gpu.round(act, dR, dC, xR, xC, w.gamma, bi)
+    with pytest.raises(rf.RFastError) as ei:
+        gpu.check()
+    assert ei.value.code == -4 and "node 5" in str(ei.value)
+    assert np.isfinite(gpu.read("X")).all()
+
+
+def test_binding_rejects_wrong_schedule_shapes():
+    w = configs.config0(rounds=2)
+    gpu = harness.make_gpu(w)
+    gpu.init()
+    act, dR, dC, xR, xC, _ = _dev_round(gpu, w.sched.round(0))
+    with pytest.raises(rf.RFastError):
+        gpu.round(act[:-1].contiguous(), dR, dC, xR, xC, w.gamma)
+    with pytest.raises(rf.RFastError):
+        gpu.round(act, dR.to(torch.int64), dC, xR, xC, w.gamma)
+    with pytest.raises(rf.RFastError):
+        gpu.round(act, dR, dC, xR, xC.cpu(), w.gamma)
+
+
+def test_empty_round_and_no_edges():
+    """A round with no active node changes nothing; a single isolated node works (no edges at all)."""
+    w = configs.config2(p=1024, rounds=3)
+    gpu = harness.make_gpu(w)
+    gpu.init()
+    x0, z0 = gpu.read("X"), gpu.read("Z")
+    q = w.sched.round(0)
+    q.active[:] = 0
+    act, dR, dC, xR, xC, _ = _dev_round(gpu, q)
+    gpu.round(act, dR, dC, xR, xC, w.gamma)
+    gpu.check()
+    assert np.array_equal(gpu.read("X"), x0) and np.array_equal(gpu.read("Z"), z0)
+    assert not gpu.read("T_NODE").any() and int(gpu.read("ROUND")[0]) == 1
+    # n = 1: x' = v, z' = z_half = z + g' - g
+    one = (np.array([0, 1], np.int32), np.array([0], np.int32), np.array([1.0], np.float32))
+    h = torch.full((1, 8), 2.0)
+    c = torch.full((1, 8), 3.0)
+    solo = rf.RFast(1, 8, one, one, 0, 1, "diag_quadratic", h, c)
+    solo.init()
+    e = torch.empty(0, dtype=torch.int32, device=solo.device)
+    e8 = torch.empty(0, dtype=torch.uint8, device=solo.device)
+    for _ in range(200):
+        solo.round(torch.ones(1, dtype=torch.uint8, device=solo.device), e, e, e8, e8, 0.1)
+    solo.check()
+    np.testing.assert_allclose(solo.read("X"), 3.0, atol=1e-5)
+    assert int(solo.read("T_NODE")[0]) == 200
+
+
+def test_profiling_hooks_count_launches():
+    w = configs.config1(p=256, samples=64, batch=16, rounds=10)
+    gpu = harness.make_gpu(w)
+    gpu.init(None, w.sched.initial_batch())
+    rf.rfast_profile_enable(gpu.ctx, True)
+    st, dev = harness.upload_chunk(gpu, w, 0, 10)
+    gpu.run(10, dev["active"], dev["delay_R"], dev["delay_C"], dev["drop_R"], dev["drop_C"], w.gamma, dev["batch_idx"])
+    ms_s, n_s = rf.rfast_kernel_time(gpu.ctx, 0)
+    ms_g, n_g = rf.rfast_kernel_time(gpu.ctx, 1)
+    ms_r, n_r = rf.rfast_kernel_time(gpu.ctx, 2)
+    assert (n_s, n_g, n_r) == (20, 10, 10) and ms_s > 0 and ms_g > 0 and ms_r > 0
+    rf.rfast_profile_enable(gpu.ctx, False)

@@ -31,7 +31,7 @@ struct Layout {
 
 struct Offsets {
   size_t x, z, g, v_ring, rho_ring, rho_tilde;
-  size_t r_ptr, r_src, r_w, r_self, c_ptr, c_src, c_self, co_ptr, co_eid, co_w, ro_ptr, ro_eid;
+  size_t r_ptr, r_src, r_dst, r_w, r_self, c_ptr, c_src, c_dst, c_self, co_ptr, co_eid, co_w, ro_ptr, ro_eid;
   size_t t, t_hist, tau_r, tau_c, deliv_r, deliv_c, round_no, err;
   size_t n_active, active_list, plan_t, slot_r, slot_c, skip_c;
   size_t resid, gscratch, diag;
@@ -65,10 +65,12 @@ Offsets layout(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, cons
   o.rho_tilde = L.take(eC * vec);
   o.r_ptr = L.take((n + 1) * 4);
   o.r_src = L.take(eR * 4);
+  o.r_dst = L.take(eR * 4);
   o.r_w = L.take(eR * 4);
   o.r_self = L.take(n * 4);
   o.c_ptr = L.take((n + 1) * 4);
   o.c_src = L.take(eC * 4);
+  o.c_dst = L.take(eC * 4);
   o.c_self = L.take(n * 4);
   o.co_ptr = L.take((n + 1) * 4);
   o.co_eid = L.take(eC * 4);
@@ -97,7 +99,7 @@ Offsets layout(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, cons
 }
 
 struct HostGraph {
-  std::vector<int32_t> ptr, src, out_ptr, out_eid;
+  std::vector<int32_t> ptr, src, dst, out_ptr, out_eid;
   std::vector<float> w, self, out_w;
 };
 
@@ -133,6 +135,7 @@ int split_graph(const char* name, int32_t n, const int32_t* rowptr, const int32_
         g->self[i] = w[k];
       } else {
         g->src.push_back(j);
+        g->dst.push_back(i);
         g->w.push_back(w[k]);
       }
     }
@@ -288,9 +291,9 @@ int rfast_create(rfast_ctx** out, int32_t n, int64_t p, const int32_t* R_rowptr,
   d.burst = burst; d.d_max = D - (burst - 1);
   d.x = (float*)(b + o.x); d.z = (float*)(b + o.z); d.g = (float*)(b + o.g);
   d.v_ring = (float*)(b + o.v_ring); d.rho_ring = (float*)(b + o.rho_ring); d.rho_tilde = (float*)(b + o.rho_tilde);
-  d.r_ptr = (int32_t*)(b + o.r_ptr); d.r_src = (int32_t*)(b + o.r_src); d.r_w = (float*)(b + o.r_w);
+  d.r_ptr = (int32_t*)(b + o.r_ptr); d.r_src = (int32_t*)(b + o.r_src); d.r_dst = (int32_t*)(b + o.r_dst); d.r_w = (float*)(b + o.r_w);
   d.r_self = (float*)(b + o.r_self);
-  d.c_ptr = (int32_t*)(b + o.c_ptr); d.c_src = (int32_t*)(b + o.c_src); d.c_self = (float*)(b + o.c_self);
+  d.c_ptr = (int32_t*)(b + o.c_ptr); d.c_src = (int32_t*)(b + o.c_src); d.c_dst = (int32_t*)(b + o.c_dst); d.c_self = (float*)(b + o.c_self);
   d.co_ptr = (int32_t*)(b + o.co_ptr); d.co_eid = (int32_t*)(b + o.co_eid); d.co_w = (float*)(b + o.co_w);
   d.ro_ptr = (int32_t*)(b + o.ro_ptr); d.ro_eid = (int32_t*)(b + o.ro_eid);
   d.t = (int32_t*)(b + o.t); d.t_hist = (int32_t*)(b + o.t_hist);
@@ -306,9 +309,9 @@ int rfast_create(rfast_ctx** out, int32_t n, int64_t p, const int32_t* R_rowptr,
 
   hipError_t e = hipSuccess;
   auto chk = [&](hipError_t r) { if (e == hipSuccess) e = r; };
-  chk(upload(c, b, o.r_ptr, gr.ptr)); chk(upload(c, b, o.r_src, gr.src)); chk(upload(c, b, o.r_w, gr.w));
+  chk(upload(c, b, o.r_ptr, gr.ptr)); chk(upload(c, b, o.r_src, gr.src)); chk(upload(c, b, o.r_dst, gr.dst)); chk(upload(c, b, o.r_w, gr.w));
   chk(upload(c, b, o.r_self, gr.self));
-  chk(upload(c, b, o.c_ptr, gc.ptr)); chk(upload(c, b, o.c_src, gc.src)); chk(upload(c, b, o.c_self, gc.self));
+  chk(upload(c, b, o.c_ptr, gc.ptr)); chk(upload(c, b, o.c_src, gc.src)); chk(upload(c, b, o.c_dst, gc.dst)); chk(upload(c, b, o.c_self, gc.self));
   chk(upload(c, b, o.co_ptr, gc.out_ptr)); chk(upload(c, b, o.co_eid, gc.out_eid)); chk(upload(c, b, o.co_w, gc.out_w));
   chk(upload(c, b, o.ro_ptr, gr.out_ptr)); chk(upload(c, b, o.ro_eid, gr.out_eid));
   chk(hipStreamSynchronize(c->stream));  // the host vectors die with this scope

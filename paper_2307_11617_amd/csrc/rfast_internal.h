@@ -31,10 +31,12 @@ struct RfastDev {
   // graph, off-diagonal entries only (row = receiver)
   const int32_t* r_ptr;   // [n+1] into R off-diagonal entries
   const int32_t* r_src;   // [eR] sender j
+  const int32_t* r_dst;   // [eR] receiver i
   const float* r_w;       // [eR] w_ij
   const float* r_self;    // [n]  w_ii
   const int32_t* c_ptr;   // [n+1] into C off-diagonal entries (in-edges of i are consecutive ids)
   const int32_t* c_src;   // [eC] sender j
+  const int32_t* c_dst;   // [eC] receiver i
   const float* c_self;    // [n]  a_ii
   const int32_t* co_ptr;  // [n+1] out-edges of sender j over C
   const int32_t* co_eid;  // [eC] edge id (into rho_ring)

@@ -9,7 +9,7 @@
 // the next version is delivered regardless, which keeps every read within D
 // versions of the sender's counter (Assumption 3 ii).
 //
-// One workgroup; every step is integer and deterministic.
+// One workgroup, one lane per edge; every step is integer and deterministic.
 #include "rfast_internal.h"
 
 namespace {
@@ -26,76 +26,88 @@ __device__ inline void record_error(int32_t* err, int code, int round, int kind,
   }
 }
 
-// kind 0: graph R (v packets), kind 1: graph C (rho packets)
-__device__ void resolve_edges(const RfastDev& s, int kind, int r, const uint8_t* active,
-                              const int32_t* delay, const uint8_t* drop) {
-  const int32_t* ptr = kind ? s.c_ptr : s.r_ptr;
-  const int32_t* src = kind ? s.c_src : s.r_src;
+// One lane per off-diagonal entry.  kind 0: graph R (v packets), kind 1: graph C (rho packets).
+__device__ void resolve_edge(const RfastDev& s, int kind, int e, int r, const uint8_t* active,
+                             const int32_t* delay, const uint8_t* drop) {
+  const int i = (kind ? s.c_dst : s.r_dst)[e];
+  const int j = (kind ? s.c_src : s.r_src)[e];
   int32_t* tau = kind ? s.tau_c : s.tau_r;
   int32_t* slot = kind ? s.slot_c : s.slot_r;
   unsigned long long* deliv = kind ? s.deliv_c : s.deliv_r;
-  for (int i = threadIdx.x; i < s.n; i += blockDim.x) {
-    const bool recv_active = active[i] != 0;
-    for (int e = ptr[i]; e < ptr[i + 1]; ++e) {
-      const int j = src[e];
-      unsigned long long bits = deliv[e];
-      if (recv_active) {
-        int d = delay[e];
-        if (d < 0 || d > s.d_max) {
-          record_error(s.err, RFAST_ERANGE, r, kind, e);
-          d = d < 0 ? 0 : s.d_max;
-        }
-        const int at = r - d;
-        int u = at <= 0 ? 0 : s.t_hist[(size_t)j * s.H + (at % s.H)];
-        while (!delivered(bits, u, s.M)) --u;  // at most burst-1 steps
-        const int old = tau[e];
-        const int now = u > old ? u : old;
-        tau[e] = now;
-        slot[e] = now % s.M;
-        if (kind) s.skip_c[e] = (now == old);
-      } else {
-        slot[e] = -1;
-        if (kind) s.skip_c[e] = 1;
-      }
-      if (active[j] != 0) {  // the sender publishes version t_j + 1 this round
-        const int vn = s.plan_t[j] + 1;
-        bool ok = drop[e] == 0;
-        if (!ok) {
-          bool all_lost = true;
-          for (int k = 1; k < s.burst; ++k) all_lost = all_lost && !delivered(bits, vn - k, s.M);
-          ok = all_lost;
-        }
-        const unsigned long long bit = 1ull << (vn % s.M);
-        deliv[e] = ok ? (bits | bit) : (bits & ~bit);
-      }
+  const unsigned long long bits = deliv[e];
+  if (active[i] != 0) {
+    int d = delay[e];
+    if (d < 0 || d > s.d_max) {
+      record_error(s.err, RFAST_ERANGE, r, kind, e);
+      d = d < 0 ? 0 : s.d_max;
     }
+    const int at = r - d;
+    int u = at <= 0 ? 0 : s.t_hist[(size_t)j * s.H + (at % s.H)];
+    while (!delivered(bits, u, s.M)) --u;  // at most burst-1 steps; version 0 always counts as delivered
+    const int old = tau[e];
+    const int now = u > old ? u : old;
+    tau[e] = now;
+    slot[e] = now % s.M;
+    if (kind) s.skip_c[e] = (now == old);
+  } else {
+    slot[e] = -1;
+    if (kind) s.skip_c[e] = 1;
+  }
+  if (active[j] != 0) {  // the sender publishes version t_j + 1 this round
+    const int vn = s.plan_t[j] + 1;
+    bool ok = drop[e] == 0;
+    if (!ok) {
+      bool all_lost = true;
+      for (int k = 1; k < s.burst; ++k) all_lost = all_lost && !delivered(bits, vn - k, s.M);
+      ok = all_lost;
+    }
+    const unsigned long long bit = 1ull << (vn % s.M);
+    deliv[e] = ok ? (bits | bit) : (bits & ~bit);
   }
 }
 
-__global__ void __launch_bounds__(256) rfast_resolve_kernel(RfastDev s, const uint8_t* active,
-                                                            const int32_t* delay_R, const int32_t* delay_C,
-                                                            const uint8_t* drop_R, const uint8_t* drop_C) {
-  __shared__ int cnt;
+constexpr int kResolveThreads = 1024;
+
+__global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev s, const uint8_t* active,
+                                                                         const int32_t* delay_R, const int32_t* delay_C,
+                                                                         const uint8_t* drop_R, const uint8_t* drop_C) {
+  __shared__ int wave_cnt[kResolveThreads / 64];
+  __shared__ int base;
   const int r = *s.round_no;
-  if (threadIdx.x == 0) cnt = 0;
-  __syncthreads();
-  for (int i = threadIdx.x; i < s.n; i += blockDim.x) {
-    const int ti = s.t[i];
-    s.plan_t[i] = ti;
-    s.t_hist[(size_t)i * s.H + (r % s.H)] = ti;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (threadIdx.x == 0) base = 0;
+  // snapshot of the counters, and the ordered list of active nodes (ballot + prefix per chunk)
+  for (int i0 = 0; i0 < s.n; i0 += kResolveThreads) {
+    const int i = i0 + threadIdx.x;
+    bool act = false;
+    if (i < s.n) {
+      const int ti = s.t[i];
+      s.plan_t[i] = ti;
+      s.t_hist[(size_t)i * s.H + (r % s.H)] = ti;
+      act = active[i] != 0;
+    }
+    const unsigned long long m = __ballot(act);
+    if (lane == 0) wave_cnt[wave] = __popcll(m);
+    __syncthreads();
+    int off = base;
+    for (int w = 0; w < wave; ++w) off += wave_cnt[w];
+    if (act) s.active_list[off + __popcll(m & ((1ull << lane) - 1ull))] = i;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int tot = 0;
+      for (int w = 0; w < kResolveThreads / 64; ++w) tot += wave_cnt[w];
+      base += tot;
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *s.n_active = base;
+  // plan_t and t_hist are complete (the barriers above); stamps per edge
+  for (int e = threadIdx.x; e < s.eR + s.eC; e += kResolveThreads) {
+    if (e < s.eR) resolve_edge(s, 0, e, r, active, delay_R, drop_R);
+    else resolve_edge(s, 1, e - s.eR, r, active, delay_C, drop_C);
   }
   __syncthreads();
-  // ordered list of active nodes (thread 0; n is at most a few thousand)
-  if (threadIdx.x == 0) {
-    int c = 0;
-    for (int i = 0; i < s.n; ++i)
-      if (active[i] != 0) s.active_list[c++] = i;
-    *s.n_active = c;
-  }
-  resolve_edges(s, 0, r, active, delay_R, drop_R);
-  resolve_edges(s, 1, r, active, delay_C, drop_C);
-  __syncthreads();
-  for (int i = threadIdx.x; i < s.n; i += blockDim.x)
+  for (int i = threadIdx.x; i < s.n; i += kResolveThreads)
     if (active[i] != 0) s.t[i] = s.plan_t[i] + 1;
   if (threadIdx.x == 0) *s.round_no = r + 1;
 }
@@ -104,7 +116,7 @@ __global__ void __launch_bounds__(256) rfast_resolve_kernel(RfastDev s, const ui
 
 hipError_t rfast_launch_resolve(rfast_ctx* c, const uint8_t* active, const int32_t* delay_R,
                                 const int32_t* delay_C, const uint8_t* drop_R, const uint8_t* drop_C) {
-  hipLaunchKernelGGL(rfast_resolve_kernel, dim3(1), dim3(256), 0, c->stream, c->d, active, delay_R, delay_C,
+  hipLaunchKernelGGL(rfast_resolve_kernel, dim3(1), dim3(kResolveThreads), 0, c->stream, c->d, active, delay_R, delay_C,
                      drop_R, drop_C);
   return hipGetLastError();
 }

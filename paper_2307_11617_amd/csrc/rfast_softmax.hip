@@ -26,6 +26,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned short u16;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // plain vector type: stays in registers
 
 constexpr int kTile = 64;       // rows (forward) / features (backward) per block, and staging depth
 constexpr int kPad = 8;         // LDS row padding in bf16 elements (16 bytes)
@@ -91,23 +92,84 @@ __global__ void __launch_bounds__(256) rfast_softmax_prep(RfastDev s, int B, boo
 }
 
 // ------------------------------------------------------------------------- forward
-// grid (B/64, nodes); blockDim = 64 * (K/32): wave w owns classes 32w .. 32w+31.
-__global__ void __launch_bounds__(256) rfast_softmax_forward(RfastDev s, const int32_t* batch_idx, int B, bool init) {
+// grid (B/64, nodes); NW = K/32 wavefronts: wave w owns classes 32w .. 32w+31.
+// The contraction over d runs in stages of 64 features through two LDS buffers;
+// the global loads of the next two stages are already in flight (in registers)
+// while the current one is multiplied, because with one or two workgroups per
+// CU a single outstanding stage cannot cover the memory latency.
+template <int NW>
+struct FwdShape {
+  static constexpr int kThreads = 64 * NW;
+  static constexpr int kXc = (kTile * kTile / 8 + kThreads - 1) / kThreads;  // 16-byte chunks of the X tile per lane
+  static constexpr int kWc = 4;                                              // ... of the Wt tile per lane
+};
+
+template <int NW>
+__device__ __forceinline__ void fwd_load(u32x4 (&x)[FwdShape<NW>::kXc], u32x4 (&w)[4], const u16* pool, const int* rows,
+                                         const u16* wt, int d, int f0, int tid) {
+  constexpr int T = FwdShape<NW>::kThreads;
+#pragma unroll
+  for (int c = 0; c < FwdShape<NW>::kXc; ++c) {
+    const int q = tid + c * T;
+    if ((kTile * kTile / 8) % T == 0 || q < kTile * kTile / 8)
+      x[c] = *reinterpret_cast<const u32x4*>(pool + (size_t)rows[q / (kTile / 8)] * d + f0 + (q % (kTile / 8)) * 8);
+  }
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const int q = tid + c * T;
+    w[c] = *reinterpret_cast<const u32x4*>(wt + (size_t)(q / (kTile / 8)) * d + f0 + (q % (kTile / 8)) * 8);
+  }
+}
+
+template <int NW>
+__device__ __forceinline__ void fwd_store(const u32x4 (&x)[FwdShape<NW>::kXc], const u32x4 (&w)[4], u16* Xs, u16* Ws,
+                                          int tid) {
+  constexpr int T = FwdShape<NW>::kThreads;
+#pragma unroll
+  for (int c = 0; c < FwdShape<NW>::kXc; ++c) {
+    const int q = tid + c * T;
+    if ((kTile * kTile / 8) % T == 0 || q < kTile * kTile / 8)
+      *reinterpret_cast<u32x4*>(&Xs[(q / (kTile / 8)) * kLd + (q % (kTile / 8)) * 8]) = x[c];
+  }
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const int q = tid + c * T;
+    *reinterpret_cast<u32x4*>(&Ws[(q / (kTile / 8)) * kLd + (q % (kTile / 8)) * 8]) = w[c];
+  }
+}
+
+template <int NW>
+__device__ __forceinline__ void fwd_multiply(f32x16 (&acc)[2], const u16* Xs, int wave, int lane) {
+  const u16* Ws = Xs + kTile * kLd;
+#pragma unroll
+  for (int kk = 0; kk < kTile; kk += 16) {
+    const int off = kk + 8 * (lane >> 5);
+    const bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(&Ws[(wave * 32 + (lane & 31)) * kLd + off]);
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) {
+      const bf16x8 afrag = *reinterpret_cast<const bf16x8*>(&Xs[(rt * 32 + (lane & 31)) * kLd + off]);
+      acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag, acc[rt], 0, 0, 0);
+    }
+  }
+}
+
+template <int NW>
+__global__ void __launch_bounds__(64 * NW) rfast_softmax_forward(RfastDev s, const int32_t* batch_idx, int B, bool init) {
   extern __shared__ u16 lds[];
   const int i = pick_node(s, init);
   if (i < 0) return;
-  const int d = s.prob.d, K = s.prob.K;
-  u16* Xs = lds;                  // [64][kLd]
-  u16* Ws = lds + kTile * kLd;    // [K][kLd]
+  constexpr int K = 32 * NW;
+  constexpr int kBuf = (kTile + K) * kLd;  // one staging buffer: X tile then Wt tile
+  const int d = s.prob.d;
   __shared__ int rows[kTile];
   __shared__ int labs[kTile];
   const int b0 = blockIdx.x * kTile;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const u16* pool = (const u16*)s.prob.data0 + (size_t)i * s.prob.samples * d;
   const int32_t* labels = (const int32_t*)s.prob.data1 + (size_t)i * s.prob.samples;
   const Scratch sc = scratch_of(s, B);
   const u16* wt = sc.wt + (size_t)i * K * d;
-  for (int r = threadIdx.x; r < kTile; r += blockDim.x) {
+  for (int r = tid; r < kTile; r += 64 * NW) {
     rows[r] = sample_row(s, batch_idx, i, b0 + r, B);
     labs[r] = labels[rows[r]];
   }
@@ -117,32 +179,35 @@ __global__ void __launch_bounds__(256) rfast_softmax_forward(RfastDev s, const i
 #pragma unroll
   for (int v = 0; v < 16; ++v) { acc[0][v] = 0.f; acc[1][v] = 0.f; }
 
-  for (int f0 = 0; f0 < d; f0 += kTile) {
-    for (int q = threadIdx.x; q < kTile * kTile / 8; q += blockDim.x) {
-      const int r = q / (kTile / 8), c = (q % (kTile / 8)) * 8;
-      *reinterpret_cast<uint4*>(&Xs[r * kLd + c]) = *reinterpret_cast<const uint4*>(pool + (size_t)rows[r] * d + f0 + c);
-    }
-    for (int q = threadIdx.x; q < K * kTile / 8; q += blockDim.x) {
-      const int k = q / (kTile / 8), c = (q % (kTile / 8)) * 8;
-      *reinterpret_cast<uint4*>(&Ws[k * kLd + c]) = *reinterpret_cast<const uint4*>(wt + (size_t)k * d + f0 + c);
-    }
-    __syncthreads();
-#pragma unroll
-    for (int kk = 0; kk < kTile; kk += 16) {
-      const int off = kk + 8 * (lane >> 5);
-      const bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(&Ws[(wave * 32 + (lane & 31)) * kLd + off]);
-#pragma unroll
-      for (int rt = 0; rt < 2; ++rt) {
-        const bf16x8 afrag = *reinterpret_cast<const bf16x8*>(&Xs[(rt * 32 + (lane & 31)) * kLd + off]);
-        acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag, acc[rt], 0, 0, 0);
+  const int S = d / kTile;
+  // (ax, aw) carry the odd stages, (bx, bw) the even ones; neither pair is ever
+  // copied, so a wait for one never implies a wait for the other (loads retire in order).
+  u32x4 ax[FwdShape<NW>::kXc], aw[4], bx[FwdShape<NW>::kXc], bw[4];
+  u16* buf0 = lds;
+  u16* buf1 = lds + kBuf;
+  fwd_load<NW>(bx, bw, pool, rows, wt, d, 0, tid);
+  fwd_store<NW>(bx, bw, buf0, buf0 + kTile * kLd, tid);
+  if (S > 1) fwd_load<NW>(ax, aw, pool, rows, wt, d, kTile, tid);
+  if (S > 2) fwd_load<NW>(bx, bw, pool, rows, wt, d, 2 * kTile, tid);
+  for (int st = 0; st < S; st += 2) {
+    __syncthreads();  // buf0 holds stage st; everyone is done reading buf1
+    fwd_multiply<NW>(acc, buf0, wave, lane);
+    if (st + 1 < S) {
+      fwd_store<NW>(ax, aw, buf1, buf1 + kTile * kLd, tid);  // stage st+1
+      if (st + 3 < S) fwd_load<NW>(ax, aw, pool, rows, wt, d, (st + 3) * kTile, tid);
+      __syncthreads();  // buf1 holds stage st+1; everyone is done reading buf0
+      fwd_multiply<NW>(acc, buf1, wave, lane);
+      if (st + 2 < S) {
+        fwd_store<NW>(bx, bw, buf0, buf0 + kTile * kLd, tid);  // stage st+2
+        if (st + 4 < S) fwd_load<NW>(bx, bw, pool, rows, wt, d, (st + 4) * kTile, tid);
       }
     }
-    __syncthreads();
   }
+  __syncthreads();
 
   // logits -> LDS [64][K+1] fp32 (reuses the staging space)
   float* L = reinterpret_cast<float*>(lds);
-  const int ldl = K + 1;
+  constexpr int ldl = K + 1;
 #pragma unroll
   for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
@@ -151,10 +216,9 @@ __global__ void __launch_bounds__(256) rfast_softmax_forward(RfastDev s, const i
       L[row * ldl + wave * 32 + (lane & 31)] = acc[rt][v];
     }
   __syncthreads();
-  // row softmax: each wave takes rows wave, wave + nwaves, ...; lanes stride over classes
-  const int nwaves = blockDim.x >> 6;
+  // row softmax: each wave takes rows wave, wave + NW, ...; lanes stride over classes
   const float invB = 1.0f / (float)B;
-  for (int r = wave; r < kTile; r += nwaves) {
+  for (int r = wave; r < kTile; r += NW) {
     float m = -INFINITY;
     for (int k = lane; k < K; k += 64) m = fmaxf(m, L[r * ldl + k]);
 #pragma unroll
@@ -176,7 +240,7 @@ __global__ void __launch_bounds__(256) rfast_softmax_forward(RfastDev s, const i
   __syncthreads();
   // Et[k][b0 .. b0+64): 8 consecutive rows per 16-byte store
   u16* et = sc.et + (size_t)i * K * B;
-  for (int q = threadIdx.x; q < K * kTile / 8; q += blockDim.x) {
+  for (int q = tid; q < K * kTile / 8; q += 64 * NW) {
     const int k = q / (kTile / 8), c = (q % (kTile / 8)) * 8;
     u16 h[8];
 #pragma unroll
@@ -274,9 +338,15 @@ hipError_t rfast_softmax_gradient(rfast_ctx* c, const int32_t* batch_idx, bool i
   const size_t lds_prep = (size_t)K * kLd * sizeof(u16);
   const size_t lds_stage = (size_t)(kTile + K) * kLd * sizeof(u16);
   const size_t lds_logits = (size_t)kTile * (K + 1) * sizeof(float);
-  const size_t lds_fwd = lds_stage > lds_logits ? lds_stage : lds_logits;
+  const size_t lds_fwd = 2 * lds_stage > lds_logits ? 2 * lds_stage : lds_logits;
   hipLaunchKernelGGL(rfast_softmax_prep, dim3(d.prob.d / kTile, d.n), dim3(256), lds_prep, c->stream, d, B, init);
-  hipLaunchKernelGGL(rfast_softmax_forward, dim3(B / kTile, d.n), dim3(threads), lds_fwd, c->stream, d, bi, B, init);
+  const dim3 fgrid(B / kTile, d.n);
+  switch (K / 32) {
+    case 1: hipLaunchKernelGGL(rfast_softmax_forward<1>, fgrid, dim3(64), lds_fwd, c->stream, d, bi, B, init); break;
+    case 2: hipLaunchKernelGGL(rfast_softmax_forward<2>, fgrid, dim3(128), lds_fwd, c->stream, d, bi, B, init); break;
+    case 3: hipLaunchKernelGGL(rfast_softmax_forward<3>, fgrid, dim3(192), lds_fwd, c->stream, d, bi, B, init); break;
+    default: hipLaunchKernelGGL(rfast_softmax_forward<4>, fgrid, dim3(256), lds_fwd, c->stream, d, bi, B, init); break;
+  }
   hipLaunchKernelGGL(rfast_softmax_backward, dim3(d.prob.d / kTile, d.n), dim3(threads), lds_stage, c->stream, d, bi, B, init);
   return hipGetLastError();
 }

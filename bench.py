@@ -23,17 +23,19 @@ import numpy as np  # noqa: E402
 HBM_PEAK_GBS = 8000.0
 
 
-def algorithmic_bytes_per_round(w, active_counts):
-    """7 + dR + 3 dI + 2 dO fp32 words per coordinate per node-update (reads x, z,
-    g_prev, dR v's, dI rho's, dI rho~'s, dO current rho's; writes x, z, g, v, dO new
-    rho's, dI rho~'s), plus 2 words of objective data (h, c) for the diagonal quadratic."""
+def algorithmic_bytes_per_round(w, active_counts, layout=False):
+    """Literal traffic of Algorithm 1 per node-update: 7 + dR + 3 dI + 2 dO fp32 words
+    per coordinate (reads x, z, g_prev, dR v's, dI rho's, dI rho~'s, dO current rho's;
+    writes x, z, g, v, dO new rho's, dI rho~'s), plus the objective data (h, c) of the
+    diagonal quadratic, or the re-read of g_new by the split mix/track pair.
+    layout=True: the words this library's layout has to move (one running sum per
+    sender instead of one per out-edge: 2 words instead of 2 dO), skips not credited."""
     Rd, Cd = w.R.dense(), w.C.dense()
-    n = w.n
     dR = (Rd != 0).sum(axis=1) - 1
     dI = (Cd != 0).sum(axis=1) - 1
     dO = (Cd != 0).sum(axis=0) - 1
-    # fused kernel: + h and c; split mix/track pair: + the re-read of g_new and of z
-    words = 7 + dR + 3 * dI + 2 * dO + (2 if w.objective == "diag_quadratic" else 1)
+    push = 2 * np.minimum(dO, 1) if layout else 2 * dO
+    words = 7 + dR + 3 * dI + push + (2 if w.objective == "diag_quadratic" else 1)
     return float((words * active_counts).sum() * 4.0 * w.p)
 
 
@@ -134,6 +136,7 @@ def main():
     act_prof = st["active"][W + K:W + 2 * K].astype(np.int64)
     updates = int(act_timed.sum())
     bytes_prof = sum(algorithmic_bytes_per_round(w, a) for a in act_prof)
+    bytes_layout = sum(algorithmic_bytes_per_round(w, a, layout=True) for a in act_prof)
     launches = max(n_state, 1)
     avg_ms = ms_state / launches
     achieved = bytes_prof / (ms_state * 1e-3) / 1e9 if ms_state > 0 else 0.0
@@ -151,6 +154,9 @@ def main():
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "avg_kernel_ms": avg_ms, "launches": n_state,
                      "algorithmic_bytes_per_launch": bytes_prof / launches,
+                     "layout_bytes_per_launch": bytes_layout / launches,
+                     "achieved_layout": achieved * bytes_layout / bytes_prof if bytes_prof else 0.0,
+                     "frac_layout": achieved * bytes_layout / bytes_prof / HBM_PEAK_GBS if bytes_prof else 0.0,
                      "traffic": measured_traffic(w.name) if not args.p else None},
         "kernel_ms": {"state": ms_state, "gradient": ms_grad, "resolver": ms_res,
                       "launches": {"state": n_state, "gradient": n_grad, "resolver": n_res}},

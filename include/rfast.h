@@ -95,14 +95,15 @@ typedef enum rfast_field {
   RFAST_Z = 1,         /* fp32 [n][p]                                             */
   RFAST_G = 2,         /* fp32 [n][p]  stored gradient sample of each node         */
   RFAST_V_RING = 3,    /* fp32 [n][D+2][p]  slot s of node j = version t, t mod (D+2) == s */
-  RFAST_RHO_RING = 4,  /* fp32 [nnzC_off][D+2][p]  sender-side running sums        */
+  RFAST_RHO_RING = 4,  /* fp32 [nnzC_off][D+2][p]  sender-side running sums rho_ij = a_ij * sigma_j (expanded on read) */
   RFAST_RHO_TILDE = 5, /* fp32 [nnzC_off][p]  receiver-side buffers                */
   RFAST_T_NODE = 6,    /* int32 [n]  local iteration counters t_i                  */
   RFAST_TAU_R = 7,     /* int32 [nnzR_off]  largest stamp picked up per R edge     */
   RFAST_TAU_C = 8,     /* int32 [nnzC_off]                                         */
   RFAST_SLOT_R = 9,    /* int32 [nnzR_off]  ring slot resolved in the last round (receiver active), else -1 */
   RFAST_SLOT_C = 10,   /* int32 [nnzC_off]                                         */
-  RFAST_ROUND = 11     /* int32 [1]  rounds executed                               */
+  RFAST_ROUND = 11,    /* int32 [1]  rounds executed                               */
+  RFAST_SIGMA_RING = 12 /* fp32 [n][D+2][p]  per-sender running sum of z_half, as stored */
 } rfast_field;
 
 typedef struct rfast_diag {

@@ -30,7 +30,7 @@ class RfastDiag(C.Structure):
 
 OBJECTIVES = {"diag_quadratic": 0, "least_squares": 1, "logistic": 2, "softmax_bf16": 3}
 RFAST_FIELDS = {"X": 0, "Z": 1, "G": 2, "V_RING": 3, "RHO_RING": 4, "RHO_TILDE": 5, "T_NODE": 6, "TAU_R": 7,
-                "TAU_C": 8, "SLOT_R": 9, "SLOT_C": 10, "ROUND": 11}
+                "TAU_C": 8, "SLOT_R": 9, "SLOT_C": 10, "ROUND": 11, "SIGMA_RING": 12}
 EXPORTS = ["rfast_workspace_bytes", "rfast_create", "rfast_init", "rfast_round", "rfast_run", "rfast_check",
            "rfast_read_state", "rfast_diagnostics", "rfast_profile_enable", "rfast_kernel_time", "rfast_last_error",
            "rfast_destroy"]
@@ -227,7 +227,7 @@ class RFast:
                   "RHO_TILDE": ((self.nnzC_off, p), np.float32), "T_NODE": ((n,), np.int32),
                   "TAU_R": ((self.nnzR_off,), np.int32), "TAU_C": ((self.nnzC_off,), np.int32),
                   "SLOT_R": ((self.nnzR_off,), np.int32), "SLOT_C": ((self.nnzC_off,), np.int32),
-                  "ROUND": ((1,), np.int32)}
+                  "ROUND": ((1,), np.int32), "SIGMA_RING": ((n, M, p), np.float32)}
         shape, dt = shapes[field]
         return rfast_read_state(self.ctx, field, np.empty(shape, dtype=dt))
 

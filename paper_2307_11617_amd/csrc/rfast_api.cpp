@@ -30,8 +30,8 @@ struct Layout {
 };
 
 struct Offsets {
-  size_t x, z, g, v_ring, rho_ring, rho_tilde;
-  size_t r_ptr, r_src, r_dst, r_w, r_self, c_ptr, c_src, c_dst, c_self, co_ptr, co_eid, co_w, ro_ptr, ro_eid;
+  size_t x, z, g, v_ring, sigma_ring, rho_tilde;
+  size_t r_ptr, r_src, r_dst, r_w, r_self, c_ptr, c_src, c_dst, c_w, c_self, co_ptr, co_eid, co_w, ro_ptr, ro_eid;
   size_t t, t_hist, tau_r, tau_c, deliv_r, deliv_c, round_no, err;
   size_t n_active, active_list, plan_t, slot_r, slot_c, skip_c;
   size_t resid, gscratch, diag;
@@ -61,7 +61,7 @@ Offsets layout(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, cons
   o.z = L.take(n * vec);
   o.g = L.take(2 * n * vec);
   o.v_ring = L.take(n * M * vec);
-  o.rho_ring = L.take(eC * M * vec);
+  o.sigma_ring = L.take(n * M * vec);
   o.rho_tilde = L.take(eC * vec);
   o.r_ptr = L.take((n + 1) * 4);
   o.r_src = L.take(eR * 4);
@@ -71,6 +71,7 @@ Offsets layout(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, cons
   o.c_ptr = L.take((n + 1) * 4);
   o.c_src = L.take(eC * 4);
   o.c_dst = L.take(eC * 4);
+  o.c_w = L.take(eC * 4);
   o.c_self = L.take(n * 4);
   o.co_ptr = L.take((n + 1) * 4);
   o.co_eid = L.take(eC * 4);
@@ -217,6 +218,7 @@ size_t field_bytes(const rfast_ctx* c, int32_t field) {
     case RFAST_X: case RFAST_Z: case RFAST_G: return d.n * vec;
     case RFAST_V_RING: return (size_t)d.n * d.M * vec;
     case RFAST_RHO_RING: return (size_t)d.eC * d.M * vec;
+    case RFAST_SIGMA_RING: return (size_t)d.n * d.M * vec;
     case RFAST_RHO_TILDE: return (size_t)d.eC * vec;
     case RFAST_T_NODE: return (size_t)d.n * 4;
     case RFAST_TAU_R: case RFAST_SLOT_R: return (size_t)d.eR * 4;
@@ -290,10 +292,10 @@ int rfast_create(rfast_ctx** out, int32_t n, int64_t p, const int32_t* R_rowptr,
   d.n = n; d.p = p; d.M = D + 2; d.H = D + 1; d.eR = nnzR - n; d.eC = nnzC - n;
   d.burst = burst; d.d_max = D - (burst - 1);
   d.x = (float*)(b + o.x); d.z = (float*)(b + o.z); d.g = (float*)(b + o.g);
-  d.v_ring = (float*)(b + o.v_ring); d.rho_ring = (float*)(b + o.rho_ring); d.rho_tilde = (float*)(b + o.rho_tilde);
+  d.v_ring = (float*)(b + o.v_ring); d.sigma_ring = (float*)(b + o.sigma_ring); d.rho_tilde = (float*)(b + o.rho_tilde);
   d.r_ptr = (int32_t*)(b + o.r_ptr); d.r_src = (int32_t*)(b + o.r_src); d.r_dst = (int32_t*)(b + o.r_dst); d.r_w = (float*)(b + o.r_w);
   d.r_self = (float*)(b + o.r_self);
-  d.c_ptr = (int32_t*)(b + o.c_ptr); d.c_src = (int32_t*)(b + o.c_src); d.c_dst = (int32_t*)(b + o.c_dst); d.c_self = (float*)(b + o.c_self);
+  d.c_ptr = (int32_t*)(b + o.c_ptr); d.c_src = (int32_t*)(b + o.c_src); d.c_dst = (int32_t*)(b + o.c_dst); d.c_w = (float*)(b + o.c_w); d.c_self = (float*)(b + o.c_self);
   d.co_ptr = (int32_t*)(b + o.co_ptr); d.co_eid = (int32_t*)(b + o.co_eid); d.co_w = (float*)(b + o.co_w);
   d.ro_ptr = (int32_t*)(b + o.ro_ptr); d.ro_eid = (int32_t*)(b + o.ro_eid);
   d.t = (int32_t*)(b + o.t); d.t_hist = (int32_t*)(b + o.t_hist);
@@ -311,7 +313,7 @@ int rfast_create(rfast_ctx** out, int32_t n, int64_t p, const int32_t* R_rowptr,
   auto chk = [&](hipError_t r) { if (e == hipSuccess) e = r; };
   chk(upload(c, b, o.r_ptr, gr.ptr)); chk(upload(c, b, o.r_src, gr.src)); chk(upload(c, b, o.r_dst, gr.dst)); chk(upload(c, b, o.r_w, gr.w));
   chk(upload(c, b, o.r_self, gr.self));
-  chk(upload(c, b, o.c_ptr, gc.ptr)); chk(upload(c, b, o.c_src, gc.src)); chk(upload(c, b, o.c_dst, gc.dst)); chk(upload(c, b, o.c_self, gc.self));
+  chk(upload(c, b, o.c_ptr, gc.ptr)); chk(upload(c, b, o.c_src, gc.src)); chk(upload(c, b, o.c_dst, gc.dst)); chk(upload(c, b, o.c_w, gc.w)); chk(upload(c, b, o.c_self, gc.self));
   chk(upload(c, b, o.co_ptr, gc.out_ptr)); chk(upload(c, b, o.co_eid, gc.out_eid)); chk(upload(c, b, o.co_w, gc.out_w));
   chk(upload(c, b, o.ro_ptr, gr.out_ptr)); chk(upload(c, b, o.ro_eid, gr.out_eid));
   chk(hipStreamSynchronize(c->stream));  // the host vectors die with this scope
@@ -336,8 +338,8 @@ int rfast_init(rfast_ctx* c, const float* d_x0, const int32_t* d_batch_idx0) {
   else chk(hipMemsetAsync(d.x, 0, d.n * vec, c->stream));
   chk(hipMemsetAsync(d.g, 0, 2 * d.n * vec, c->stream));
   chk(hipMemsetAsync(d.v_ring, 0, (size_t)d.n * d.M * vec, c->stream));
+  chk(hipMemsetAsync(d.sigma_ring, 0, (size_t)d.n * d.M * vec, c->stream));
   if (d.eC) {
-    chk(hipMemsetAsync(d.rho_ring, 0, (size_t)d.eC * d.M * vec, c->stream));
     chk(hipMemsetAsync(d.rho_tilde, 0, (size_t)d.eC * vec, c->stream));
     chk(hipMemsetAsync(d.tau_c, 0, (size_t)d.eC * 4, c->stream));
     chk(hipMemsetAsync(d.slot_c, 0xff, (size_t)d.eC * 4, c->stream));
@@ -443,7 +445,7 @@ int rfast_read_state(rfast_ctx* c, int32_t field, void* host_dst, size_t bytes) 
     case RFAST_X: src = d.x; break;
     case RFAST_Z: src = d.z; break;
     case RFAST_V_RING: src = d.v_ring; break;
-    case RFAST_RHO_RING: src = d.rho_ring; break;
+    case RFAST_SIGMA_RING: src = d.sigma_ring; break;
     case RFAST_RHO_TILDE: src = d.rho_tilde; break;
     case RFAST_T_NODE: src = d.t; break;
     case RFAST_TAU_R: src = d.tau_r; break;
@@ -453,7 +455,20 @@ int rfast_read_state(rfast_ctx* c, int32_t field, void* host_dst, size_t bytes) 
     case RFAST_ROUND: src = d.round_no; break;
     default: break;
   }
-  if (field == RFAST_G) {
+  if (field == RFAST_RHO_RING) {
+    // rho_ij = a_ij * sigma_j: expand the per-sender rings into per-edge rings
+    // (fp32 product, the value the kernels consume)
+    std::vector<int32_t> src_h(d.eC);
+    std::vector<float> w_h(d.eC);
+    e = hipMemcpy(src_h.data(), d.c_src, (size_t)d.eC * 4, hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(w_h.data(), d.c_w, (size_t)d.eC * 4, hipMemcpyDeviceToHost);
+    const size_t ring = (size_t)d.M * d.p;
+    for (int q = 0; q < d.eC && e == hipSuccess; ++q) {
+      float* dst = (float*)host_dst + (size_t)q * ring;
+      e = hipMemcpy(dst, d.sigma_ring + (size_t)src_h[q] * ring, ring * 4, hipMemcpyDeviceToHost);
+      for (size_t k = 0; k < ring; ++k) dst[k] = w_h[q] * dst[k];
+    }
+  } else if (field == RFAST_G) {
     // the stored sample of node i is the one of version t_i: g[t_i & 1][i]
     std::vector<int32_t> t(d.n);
     e = hipMemcpy(t.data(), d.t, (size_t)d.n * 4, hipMemcpyDeviceToHost);

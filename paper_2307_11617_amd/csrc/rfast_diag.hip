@@ -49,7 +49,7 @@ __global__ void __launch_bounds__(kThreads) rfast_diag_kernel(RfastDev s, const 
     double flight = 0.0;
     for (int e = 0; e < s.eC; ++e) {
       const int j = s.c_src[e];
-      flight += (double)s.rho_ring[((size_t)e * s.M + (s.t[j] % s.M)) * p + k] - (double)s.rho_tilde[(size_t)e * p + k];
+      flight += (double)(s.c_w[e] * s.sigma_ring[((size_t)j * s.M + (s.t[j] % s.M)) * p + k]) - (double)s.rho_tilde[(size_t)e * p + k];
     }
     const double res = zs + flight - gs;
     acc[2] += res * res;

@@ -16,7 +16,10 @@
 //   x, z        [n][p]
 //   g           [2][n][p]   the sample of version t lives in g[t & 1]
 //   v_ring      [n][M][p]   M = D + 2 slots, version t in slot t mod M
-//   rho_ring    [eC][M][p]  one ring per off-diagonal entry of C (sender side)
+//   sigma_ring  [n][M][p]   sender-side running sum sigma_j = sum of every z_half node j
+//                           produced; the running sum rho_ij of Algorithm 1 (S2c) is
+//                           a_ij * sigma_j for every out-neighbour i, so one ring per
+//                           sender replaces one ring per edge
 //   rho_tilde   [eC][p]     receiver side
 // ---------------------------------------------------------------------------
 struct RfastDev {
@@ -26,7 +29,7 @@ struct RfastDev {
   float* z;
   float* g;
   float* v_ring;
-  float* rho_ring;
+  float* sigma_ring;
   float* rho_tilde;
   // graph, off-diagonal entries only (row = receiver)
   const int32_t* r_ptr;   // [n+1] into R off-diagonal entries
@@ -37,9 +40,10 @@ struct RfastDev {
   const int32_t* c_ptr;   // [n+1] into C off-diagonal entries (in-edges of i are consecutive ids)
   const int32_t* c_src;   // [eC] sender j
   const int32_t* c_dst;   // [eC] receiver i
+  const float* c_w;       // [eC] a_ij
   const float* c_self;    // [n]  a_ii
   const int32_t* co_ptr;  // [n+1] out-edges of sender j over C
-  const int32_t* co_eid;  // [eC] edge id (into rho_ring)
+  const int32_t* co_eid;  // [eC] edge id
   const float* co_w;      // [eC] a_lj
   const int32_t* ro_ptr;  // [n+1] out-edges of sender j over R
   const int32_t* ro_eid;  // [eR]

@@ -10,6 +10,11 @@
 //          S2c, S3, S4 in one pass.
 //   MIX    S1, S2a and the v half of S3; the gradient kernels run next.
 //   TRACK  S2b, S2c, the rho half of S3, S4.
+//
+// The per-edge running sums rho_li of S2c are kept as ONE running sum per sender,
+// sigma_i = sum of z_half, with rho_li = a_li * sigma_i formed by the receiver:
+// algebraically identical to the per-edge recursion, bit-identical when a_li is
+// a power of two, and it replaces dO reads + dO writes per coordinate by 1 + 1.
 #include "rfast_internal.h"
 
 namespace {
@@ -201,51 +206,48 @@ __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float
   }
   g_old = V<VEC>::ld(g_old_p);
 
+  // The running sums of S2c share one factor per sender: rho_li = a_li * sigma_i with
+  // sigma_i = sum of every z_half node i produced.  One ring of sigma per sender
+  // replaces a ring per edge (1 read + 1 write instead of dO reads + dO writes).
+  const bool pushes = s.co_ptr[i + 1] > s.co_ptr[i];
+  T sig_cur;
+  if (pushes) sig_cur = V<VEC>::ld(s.sigma_ring + ((size_t)i * M + slot_cur) * p + k);
+
   // S2b: tracker sum over the in-edges of C; S4: buffer what was consumed.
   // An edge whose stamp did not move holds rho == rho~ exactly and is skipped.
   T z_half = z_i;
   {
     const int e0 = s.c_ptr[i], e1 = s.c_ptr[i + 1];
     for (int eb = e0; eb < e1; eb += kBatch) {
-      T rho[kBatch], rt[kBatch];
+      T sig[kBatch], rt[kBatch];
+      float a[kBatch];
       bool live[kBatch];
 #pragma unroll
       for (int q = 0; q < kBatch; ++q) {
         const int e = eb + q;
         live[q] = e < e1 && !s.skip_c[e];
         if (live[q]) {
-          rho[q] = V<VEC>::ld(s.rho_ring + ((size_t)e * M + s.slot_c[e]) * p + k);
+          sig[q] = V<VEC>::ld(s.sigma_ring + ((size_t)s.c_src[e] * M + s.slot_c[e]) * p + k);
           rt[q] = V<VEC>::ld(s.rho_tilde + (size_t)e * p + k);
+          a[q] = s.c_w[e];
         }
       }
 #pragma unroll
       for (int q = 0; q < kBatch; ++q)
         if (live[q]) {
-          z_half = add(z_half, sub(rho[q], rt[q]));
-          V<VEC>::st(s.rho_tilde + (size_t)(eb + q) * p + k, rho[q]);
+          const T rho = mul_s(a[q], sig[q]);
+          z_half = add(z_half, sub(rho, rt[q]));
+          V<VEC>::st(s.rho_tilde + (size_t)(eb + q) * p + k, rho);
         }
     }
   }
   z_half = sub(add(z_half, g_new), g_old);
 
-  // S2c: keep a_ii, push a_li as running sums; S3 (rho half): new version t+1
+  // S2c: keep a_ii; push: sigma_i grows by z_half.  S3 (rho half): new version t+1
   V<VEC>::st(s.z + node_off, mul_s(s.c_self[i], z_half));
-  {
-    const int o0 = s.co_ptr[i], o1 = s.co_ptr[i + 1];
-    for (int ob = o0; ob < o1; ob += kBatch) {
-      T cur[kBatch];
-#pragma unroll
-      for (int q = 0; q < kBatch; ++q)
-        if (ob + q < o1) cur[q] = V<VEC>::ld(s.rho_ring + ((size_t)s.co_eid[ob + q] * M + slot_cur) * p + k);
-#pragma unroll
-      for (int q = 0; q < kBatch; ++q)
-        if (ob + q < o1)
-          V<VEC>::st(s.rho_ring + ((size_t)s.co_eid[ob + q] * M + slot_new) * p + k, fma_s(s.co_w[ob + q], z_half, cur[q]));
-    }
-  }
+  if (pushes) V<VEC>::st(s.sigma_ring + ((size_t)i * M + slot_new) * p + k, add(sig_cur, z_half));
 }
 
-// g^0 = h*(x^0 - c) + noise of sample version 0 (initialisation of Algorithm 1)
 template <int VEC>
 __global__ void __launch_bounds__(kThreads) rfast_diag_init_kernel(RfastDev s) {
   const int i = blockIdx.y;
@@ -269,7 +271,7 @@ hipError_t launch(rfast_ctx* c, float gamma) {
   const int64_t blocks = tiles * d.n;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   // stream past the caches once the per-round working set dwarfs them (256 MB of last-level cache)
-  const bool streaming = (double)d.n * (double)d.p * 4.0 >= 512.0e6;
+  const bool streaming = (double)d.n * (double)d.p * 4.0 >= 32.0e6;
   if (vec4 && streaming)
     hipLaunchKernelGGL((rfast_state_kernel<MODE, -4>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, d, gamma, (int)tiles);
   else if (vec4)

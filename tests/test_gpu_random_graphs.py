@@ -1,0 +1,54 @@
+"""GPU parity on random instances: random digraphs with non-dyadic weights and
+uneven degrees (in-degrees above the kernel's load batch of 8), random
+schedules, extreme ring depths and burst settings."""
+import numpy as np
+import pytest
+
+from rfast_workloads import configs, graphs, problems
+from rfast_workloads.schedule import ScheduleSpec
+
+import harness
+
+pytestmark = pytest.mark.gpu
+
+
+def _workload(n, p, wr, wc, d_max, burst, p_active, p_drop, seed, gamma=0.03, noise=0.05):
+    R, C = graphs.from_dense(wr), graphs.from_dense(wc)
+    sched = ScheduleSpec(n, R.nnz_off, C.nnz_off, np.full(n, p_active), d_max, p_drop, seed=seed)
+    return configs.Workload(f"random_n{n}_p{p}_s{seed}", n, p, R, C, d_max + burst - 1, burst, gamma, 0,
+                            "diag_quadratic", problems.diag_quadratic(n, p, seed), sched, noise, 777 + seed, 1e-4)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_random_digraph(seed):
+    rng = np.random.default_rng(seed)
+    n = [5, 13, 24][seed]
+    wr, wc = graphs.random_digraph(n, rng, extra=[0.3, 0.5, 0.6][seed])
+    w = _workload(n, [1028, 260, 516][seed], wr, wc, d_max=[2, 5, 3][seed], burst=[1, 3, 5][seed],
+                  p_active=[0.9, 0.5, 0.3][seed], p_drop=[0.5, 0.3, 0.4][seed], seed=seed)
+    assert (wr != 0).sum(axis=1).max() - 1 > 8 or seed == 0
+    worst, orc, gpu = harness.run_parity(w, 240, every=60)
+    print(f"\n[{w.name}] worst {worst}")
+
+
+def test_deepest_ring_and_dense_graph():
+    """D + 2 = 64 slots (the bitmask limit), complete graph: 15 in- and out-edges per node."""
+    n = 16
+    rng = np.random.default_rng(9)
+    wr, wc = graphs.random_digraph(n, rng, extra=1.1)
+    w = _workload(n, 132, wr, wc, d_max=40, burst=23, p_active=0.7, p_drop=0.8, seed=9)
+    assert w.D == 62
+    worst, orc, gpu = harness.run_parity(w, 400, every=100)
+    print(f"\n[{w.name}] worst {worst}")
+
+
+def test_no_delay_no_loss_is_synchronous_special_case():
+    """Remark 1: every node active, zero delay, nothing lost; D = 0 gives a two-slot ring."""
+    n = 6
+    wr, wc = graphs.exponential(n)
+    w = _workload(n, 2048, wr, wc, d_max=0, burst=1, p_active=1.0, p_drop=0.0, seed=4, gamma=0.08, noise=0.0)
+    assert w.D == 0
+    worst, orc, gpu = harness.run_parity(w, 150, every=50)
+    d = gpu.diagnostics()
+    assert d["consensus_sq"] < 1e-3 * w.p     # the nodes agree
+    print(f"\n[{w.name}] worst {worst}")

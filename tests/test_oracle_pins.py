@@ -324,6 +324,25 @@ def test_fixed_point_diag_quadratic_closed_form(topology):
     assert np.abs(orc.z).max() < 1e-8
 
 
+def test_sample_stamp_convention():
+    """The sample of the initial gradient has stamp 0, the one drawn at a node's
+    t-th activation has stamp t (the node's local iteration counter): with h = 0
+    the stored gradient is the noise alone."""
+    from oracle.objectives import gaussian_noise
+    n, p = 4, 8
+    wr, wc = graphs.directed_ring(n)
+    R, C = graphs.from_dense(wr), graphs.from_dense(wc)
+    obj = DiagQuadratic(np.zeros((n, p)), np.zeros((n, p)), 0.5, 31)
+    orc = RFastOracle(n, p, R, C, D=4, burst=2, objective=obj)
+    sched = ScheduleSpec(n, R.nnz_off, C.nnz_off, np.full(n, 0.5), 3, 0.2, seed=2)
+    for i in range(n):
+        np.testing.assert_array_equal(orc.g[i], 0.5 * gaussian_noise(31, i, 0, p))
+    _run(orc, sched, 25, 0.1)
+    assert len(set(orc.t.tolist())) > 1
+    for i in range(n):
+        np.testing.assert_array_equal(orc.g[i], 0.5 * gaussian_noise(31, i, int(orc.t[i]), p))
+
+
 def test_noise_floor_scales_with_sigma():
     """Theorem 1: with gradient noise the iterates settle in a neighbourhood of
     x* whose squared radius is proportional to sigma^2."""

@@ -9,8 +9,9 @@
 // bf16 x bf16 products accumulate in fp32 (v_mfma_f32_32x32x16_bf16).  Both
 // MFMA operands want 8 consecutive elements of the contraction index per lane,
 // so three small kernels keep every operand contiguous along it:
-//   prep      Wt[k][f] = bf16(W[f][k])             (transpose through LDS)
-//   forward   tile of 64 sampled rows x all K classes: X rows and Wt rows are
+//   prep      Wt[f/8][k][f%8] = bf16(W[f][k])      (transpose through LDS; blocks of 8
+//             features so that a stage of 64 features is one contiguous 16 KiB run)
+//   forward   tile of 64 sampled rows x all K classes: X rows and Wt blocks are
 //             both contiguous in f; row softmax in the same block; E is written
 //             class-major, Et[k][b]
 //   backward  tile of 64 features x all K classes: Et rows are contiguous in b;
@@ -37,9 +38,20 @@ __device__ inline u16 f32_to_bf16(float f) {  // round to nearest even
   return (u16)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
 }
 
-__device__ inline int pick_node(const RfastDev& s, bool init) {
-  if (init) return blockIdx.y;
-  return (int)blockIdx.y < *s.n_active ? s.active_list[blockIdx.y] : -1;
+// node handled by work slot `slot`: all nodes at initialisation, the round's active list otherwise
+__device__ inline int pick_node(const RfastDev& s, bool init, int slot) {
+  if (init) return slot < s.n ? slot : -1;
+  return slot < *s.n_active ? s.active_list[slot] : -1;
+}
+
+// Workgroups are dealt to the 8 XCDs round-robin by linear id.  The `per_node`
+// workgroups of one node share that node's W (forward) or E (backward), so they
+// are decoded onto one XCD and hit in its L2: id -> (node slot, part).
+__device__ inline void xcd_decode(int per_node, int* slot, int* part) {
+  const int L = blockIdx.x;
+  const int xcd = L & 7, q = L >> 3;
+  *slot = (q / per_node) * 8 + xcd;
+  *part = q % per_node;
 }
 
 __device__ inline int sample_row(const RfastDev& s, const int32_t* batch_idx, int i, int b, int B) {
@@ -67,32 +79,43 @@ __device__ __host__ inline Scratch scratch_of(const RfastDev& s, int B) {
   return r;
 }
 
-// ---------------------------------------------------------------- prep: Wt = bf16(W)^T
+// ---------------------------------------------------------------- prep: Wt = bf16(W), blocked transpose
+// grid (d/64, nodes).  LDS tile T[f][k] (row stride K+4: the transposed reads of
+// phase 2 then fall on distinct banks); phase 2 gathers 8 features of one class
+// and writes them as one 16-byte unit, lanes along k, fully coalesced.
 __global__ void __launch_bounds__(256) rfast_softmax_prep(RfastDev s, int B, bool init) {
-  extern __shared__ u16 lds[];  // [K][kLd]
-  const int i = pick_node(s, init);
+  extern __shared__ u16 lds[];  // [64][K+4]
+  const int i = pick_node(s, init, blockIdx.y);
   if (i < 0) return;
-  const int d = s.prob.d, K = s.prob.K;
+  const int d = s.prob.d, K = s.prob.K, TS = K + 4;
   const int f0 = blockIdx.x * kTile;
   const float* W = s.x + (size_t)i * s.p;
   for (int q = threadIdx.x; q < kTile * K / 4; q += blockDim.x) {
     const int f = q / (K / 4), k4 = (q % (K / 4)) * 4;
     const float4 w = *reinterpret_cast<const float4*>(W + (size_t)(f0 + f) * K + k4);
-    lds[(k4 + 0) * kLd + f] = f32_to_bf16(w.x);
-    lds[(k4 + 1) * kLd + f] = f32_to_bf16(w.y);
-    lds[(k4 + 2) * kLd + f] = f32_to_bf16(w.z);
-    lds[(k4 + 3) * kLd + f] = f32_to_bf16(w.w);
+    uint2 pk;
+    pk.x = f32_to_bf16(w.x) | ((uint32_t)f32_to_bf16(w.y) << 16);
+    pk.y = f32_to_bf16(w.z) | ((uint32_t)f32_to_bf16(w.w) << 16);
+    *reinterpret_cast<uint2*>(&lds[f * TS + k4]) = pk;
   }
   __syncthreads();
-  u16* wt = scratch_of(s, B).wt + (size_t)i * K * d;
-  for (int q = threadIdx.x; q < K * kTile / 8; q += blockDim.x) {
-    const int k = q / (kTile / 8), c = (q % (kTile / 8)) * 8;
-    *reinterpret_cast<uint4*>(wt + (size_t)k * d + f0 + c) = *reinterpret_cast<const uint4*>(&lds[k * kLd + c]);
+  u16* wt = scratch_of(s, B).wt + (size_t)i * K * d + (size_t)(f0 / 8) * K * 8;
+  for (int q = threadIdx.x; q < K * 8; q += blockDim.x) {
+    const int k = q % K, c = q / K;
+    u16 h[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) h[j] = lds[(c * 8 + j) * TS + k];
+    uint4 pk;
+    pk.x = h[0] | ((uint32_t)h[1] << 16);
+    pk.y = h[2] | ((uint32_t)h[3] << 16);
+    pk.z = h[4] | ((uint32_t)h[5] << 16);
+    pk.w = h[6] | ((uint32_t)h[7] << 16);
+    *reinterpret_cast<uint4*>(wt + ((size_t)c * K + k) * 8) = pk;
   }
 }
 
 // ------------------------------------------------------------------------- forward
-// grid (B/64, nodes); NW = K/32 wavefronts: wave w owns classes 32w .. 32w+31.
+// one workgroup per (node, 64-row block), XCD-aware ids; NW = K/32 wavefronts: wave w owns classes 32w .. 32w+31.
 // The contraction over d runs in stages of 64 features through two LDS buffers;
 // the global loads of the next two stages are already in flight (in registers)
 // while the current one is multiplied, because with one or two workgroups per
@@ -102,6 +125,8 @@ struct FwdShape {
   static constexpr int kThreads = 64 * NW;
   static constexpr int kXc = (kTile * kTile / 8 + kThreads - 1) / kThreads;  // 16-byte chunks of the X tile per lane
   static constexpr int kWc = 4;                                              // ... of the Wt tile per lane
+  static constexpr int kGs = 32 * NW * 8 + 8;  // LDS stride of one 8-feature block of Wt (K*8 + 16 bytes of pad)
+  static constexpr int kBuf = kTile * kLd + 8 * kGs;  // one staging buffer: X tile, then 8 blocks of Wt
 };
 
 template <int NW>
@@ -117,7 +142,7 @@ __device__ __forceinline__ void fwd_load(u32x4 (&x)[FwdShape<NW>::kXc], u32x4 (&
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
     const int q = tid + c * T;
-    w[c] = *reinterpret_cast<const u32x4*>(wt + (size_t)(q / (kTile / 8)) * d + f0 + (q % (kTile / 8)) * 8);
+    w[c] = *reinterpret_cast<const u32x4*>(wt + (size_t)(f0 / 8) * (32 * NW * 8) + (size_t)q * 8);  // contiguous run
   }
 }
 
@@ -134,7 +159,7 @@ __device__ __forceinline__ void fwd_store(const u32x4 (&x)[FwdShape<NW>::kXc], c
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
     const int q = tid + c * T;
-    *reinterpret_cast<u32x4*>(&Ws[(q / (kTile / 8)) * kLd + (q % (kTile / 8)) * 8]) = w[c];
+    *reinterpret_cast<u32x4*>(&Ws[(q / (32 * NW)) * FwdShape<NW>::kGs + (q % (32 * NW)) * 8]) = w[c];
   }
 }
 
@@ -144,7 +169,8 @@ __device__ __forceinline__ void fwd_multiply(f32x16 (&acc)[2], const u16* Xs, in
 #pragma unroll
   for (int kk = 0; kk < kTile; kk += 16) {
     const int off = kk + 8 * (lane >> 5);
-    const bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(&Ws[(wave * 32 + (lane & 31)) * kLd + off]);
+    const bf16x8 bfrag =
+        *reinterpret_cast<const bf16x8*>(&Ws[(kk / 8 + (lane >> 5)) * FwdShape<NW>::kGs + (wave * 32 + (lane & 31)) * 8]);
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt) {
       const bf16x8 afrag = *reinterpret_cast<const bf16x8*>(&Xs[(rt * 32 + (lane & 31)) * kLd + off]);
@@ -156,14 +182,16 @@ __device__ __forceinline__ void fwd_multiply(f32x16 (&acc)[2], const u16* Xs, in
 template <int NW>
 __global__ void __launch_bounds__(64 * NW) rfast_softmax_forward(RfastDev s, const int32_t* batch_idx, int B, bool init) {
   extern __shared__ u16 lds[];
-  const int i = pick_node(s, init);
+  int slot, rb;
+  xcd_decode(B / kTile, &slot, &rb);
+  const int i = pick_node(s, init, slot);
   if (i < 0) return;
   constexpr int K = 32 * NW;
-  constexpr int kBuf = (kTile + K) * kLd;  // one staging buffer: X tile then Wt tile
+  constexpr int kBuf = FwdShape<NW>::kBuf;
   const int d = s.prob.d;
   __shared__ int rows[kTile];
   __shared__ int labs[kTile];
-  const int b0 = blockIdx.x * kTile;
+  const int b0 = rb * kTile;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const u16* pool = (const u16*)s.prob.data0 + (size_t)i * s.prob.samples * d;
   const int32_t* labels = (const int32_t*)s.prob.data1 + (size_t)i * s.prob.samples;
@@ -255,17 +283,64 @@ __global__ void __launch_bounds__(64 * NW) rfast_softmax_forward(RfastDev s, con
 }
 
 // ------------------------------------------------------------------------ backward
-// grid (d/64, nodes); wave w owns classes 32w .. 32w+31, both 32-feature tiles.
-__global__ void __launch_bounds__(256) rfast_softmax_backward(RfastDev s, const int32_t* batch_idx, int B, bool init) {
+// one workgroup per (node, 64-feature block), XCD-aware ids; wave w owns classes
+// 32w .. 32w+31 and both 32-feature tiles.  The contraction over the B sampled
+// rows runs in stages of 64 rows through two LDS buffers; the next stage's global
+// loads are issued before the current stage is multiplied.  The X tile is
+// transposed on its way into LDS (Xt[f][b]) so that both operands are contiguous in b.
+template <int NW>
+__device__ __forceinline__ void bwd_load(u32x4 (&x)[FwdShape<NW>::kXc], u32x4 (&e)[4], const u16* pool, const int* rows,
+                                         const u16* et, int d, int B, int f0, int b0, int tid) {
+  constexpr int T = FwdShape<NW>::kThreads;
+#pragma unroll
+  for (int c = 0; c < FwdShape<NW>::kXc; ++c) {
+    const int q = tid + c * T;
+    if ((kTile * kTile / 8) % T == 0 || q < kTile * kTile / 8)
+      x[c] = *reinterpret_cast<const u32x4*>(pool + (size_t)rows[q / (kTile / 8)] * d + f0 + (q % (kTile / 8)) * 8);
+  }
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const int q = tid + c * T;
+    e[c] = *reinterpret_cast<const u32x4*>(et + (size_t)(q / (kTile / 8)) * B + b0 + (q % (kTile / 8)) * 8);
+  }
+}
+
+template <int NW>
+__device__ __forceinline__ void bwd_store(const u32x4 (&x)[FwdShape<NW>::kXc], const u32x4 (&e)[4], u16* Xt, u16* Es,
+                                          int tid) {
+  constexpr int T = FwdShape<NW>::kThreads;
+#pragma unroll
+  for (int c = 0; c < FwdShape<NW>::kXc; ++c) {
+    const int q = tid + c * T;
+    if ((kTile * kTile / 8) % T == 0 || q < kTile * kTile / 8) {
+      const int r = q / (kTile / 8), f = (q % (kTile / 8)) * 8;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        Xt[(f + 2 * j) * kLd + r] = (u16)(x[c][j] & 0xFFFFu);
+        Xt[(f + 2 * j + 1) * kLd + r] = (u16)(x[c][j] >> 16);
+      }
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const int q = tid + c * T;
+    *reinterpret_cast<u32x4*>(&Es[(q / (kTile / 8)) * kLd + (q % (kTile / 8)) * 8]) = e[c];
+  }
+}
+
+template <int NW>
+__global__ void __launch_bounds__(64 * NW) rfast_softmax_backward(RfastDev s, const int32_t* batch_idx, int B, bool init) {
   extern __shared__ u16 lds[];
-  const int i = pick_node(s, init);
+  int slot, fb;
+  const int d = s.prob.d;
+  xcd_decode(d / kTile, &slot, &fb);
+  const int i = pick_node(s, init, slot);
   if (i < 0) return;
-  const int d = s.prob.d, K = s.prob.K;
-  u16* Xt = lds;                  // [64 features][kLd]  (transposed while staging)
-  u16* Es = lds + kTile * kLd;    // [K][kLd]
-  __shared__ int rows[kTile];
-  const int f0 = blockIdx.x * kTile;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  constexpr int K = 32 * NW;
+  constexpr int kBuf = (kTile + K) * kLd;  // Xt tile [64 features][kLd], then Es [K][kLd]
+  __shared__ int rows[2][kTile];
+  const int f0 = fb * kTile;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const u16* pool = (const u16*)s.prob.data0 + (size_t)i * s.prob.samples * d;
   const u16* et = scratch_of(s, B).et + (size_t)i * K * B;
 
@@ -273,24 +348,19 @@ __global__ void __launch_bounds__(256) rfast_softmax_backward(RfastDev s, const 
 #pragma unroll
   for (int v = 0; v < 16; ++v) { acc[0][v] = 0.f; acc[1][v] = 0.f; }
 
-  for (int b0 = 0; b0 < B; b0 += kTile) {
-    for (int r = threadIdx.x; r < kTile; r += blockDim.x) rows[r] = sample_row(s, batch_idx, i, b0 + r, B);
+  const int S = B / kTile;
+  for (int r = tid; r < kTile; r += 64 * NW) rows[0][r] = sample_row(s, batch_idx, i, r, B);
+  __syncthreads();
+  u32x4 x[FwdShape<NW>::kXc], e[4];
+  bwd_load<NW>(x, e, pool, rows[0], et, d, B, f0, 0, tid);
+  for (int st = 0; st < S; ++st) {
+    u16* Xt = lds + (st & 1) * kBuf;
+    u16* Es = Xt + kTile * kLd;
+    bwd_store<NW>(x, e, Xt, Es, tid);  // stage st (its buffer was last read two stages ago)
+    if (st + 1 < S)
+      for (int r = tid; r < kTile; r += 64 * NW) rows[(st + 1) & 1][r] = sample_row(s, batch_idx, i, (st + 1) * kTile + r, B);
     __syncthreads();
-    for (int q = threadIdx.x; q < kTile * kTile / 8; q += blockDim.x) {
-      const int r = q / (kTile / 8), c = (q % (kTile / 8)) * 8;
-      const uint4 x8 = *reinterpret_cast<const uint4*>(pool + (size_t)rows[r] * d + f0 + c);
-      const uint32_t w[4] = {x8.x, x8.y, x8.z, x8.w};
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        Xt[(c + 2 * j) * kLd + r] = (u16)(w[j] & 0xFFFFu);
-        Xt[(c + 2 * j + 1) * kLd + r] = (u16)(w[j] >> 16);
-      }
-    }
-    for (int q = threadIdx.x; q < K * kTile / 8; q += blockDim.x) {
-      const int k = q / (kTile / 8), c = (q % (kTile / 8)) * 8;
-      *reinterpret_cast<uint4*>(&Es[k * kLd + c]) = *reinterpret_cast<const uint4*>(et + (size_t)k * B + b0 + c);
-    }
-    __syncthreads();
+    if (st + 1 < S) bwd_load<NW>(x, e, pool, rows[(st + 1) & 1], et, d, B, f0, (st + 1) * kTile, tid);
 #pragma unroll
     for (int kk = 0; kk < kTile; kk += 16) {
       const int off = kk + 8 * (lane >> 5);
@@ -301,7 +371,6 @@ __global__ void __launch_bounds__(256) rfast_softmax_backward(RfastDev s, const 
         acc[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag, acc[ft], 0, 0, 0);
       }
     }
-    __syncthreads();
   }
   const int t_old = init ? -1 : s.plan_t[i];
   float* G = s.g + (size_t)((t_old + 1) & 1) * s.n * s.p + (size_t)i * s.p;
@@ -333,20 +402,33 @@ hipError_t rfast_softmax_gradient(rfast_ctx* c, const int32_t* batch_idx, bool i
   if (!rfast_softmax_shape_ok(&d.prob)) return hipErrorInvalidValue;
   const int B = d.prob.batch > 0 ? d.prob.batch : d.prob.samples;
   const int32_t* bi = d.prob.batch > 0 ? batch_idx : nullptr;
-  const int K = d.prob.K;
-  const unsigned threads = 64u * (unsigned)(K / 32);
-  const size_t lds_prep = (size_t)K * kLd * sizeof(u16);
-  const size_t lds_stage = (size_t)(kTile + K) * kLd * sizeof(u16);
+  const int K = d.prob.K, NW = K / 32;
+  const unsigned threads = 64u * (unsigned)NW;
+  const size_t lds_prep = (size_t)kTile * (K + 4) * sizeof(u16);
+  const size_t lds_fwd_stage = 2 * (size_t)(kTile * kLd + 8 * (K * 8 + 8)) * sizeof(u16);
   const size_t lds_logits = (size_t)kTile * (K + 1) * sizeof(float);
-  const size_t lds_fwd = 2 * lds_stage > lds_logits ? 2 * lds_stage : lds_logits;
+  const size_t lds_fwd = lds_fwd_stage > lds_logits ? lds_fwd_stage : lds_logits;
+  const size_t lds_bwd = 2 * (size_t)(kTile + K) * kLd * sizeof(u16);
+  const unsigned n8 = (unsigned)((d.n + 7) / 8 * 8);  // node slots, padded so that ids decode per XCD
   hipLaunchKernelGGL(rfast_softmax_prep, dim3(d.prob.d / kTile, d.n), dim3(256), lds_prep, c->stream, d, B, init);
-  const dim3 fgrid(B / kTile, d.n);
-  switch (K / 32) {
-    case 1: hipLaunchKernelGGL(rfast_softmax_forward<1>, fgrid, dim3(64), lds_fwd, c->stream, d, bi, B, init); break;
-    case 2: hipLaunchKernelGGL(rfast_softmax_forward<2>, fgrid, dim3(128), lds_fwd, c->stream, d, bi, B, init); break;
-    case 3: hipLaunchKernelGGL(rfast_softmax_forward<3>, fgrid, dim3(192), lds_fwd, c->stream, d, bi, B, init); break;
-    default: hipLaunchKernelGGL(rfast_softmax_forward<4>, fgrid, dim3(256), lds_fwd, c->stream, d, bi, B, init); break;
+  const dim3 fgrid(n8 * (unsigned)(B / kTile)), bgrid(n8 * (unsigned)(d.prob.d / kTile));
+  switch (NW) {
+    case 1:
+      hipLaunchKernelGGL(rfast_softmax_forward<1>, fgrid, dim3(threads), lds_fwd, c->stream, d, bi, B, init);
+      hipLaunchKernelGGL(rfast_softmax_backward<1>, bgrid, dim3(threads), lds_bwd, c->stream, d, bi, B, init);
+      break;
+    case 2:
+      hipLaunchKernelGGL(rfast_softmax_forward<2>, fgrid, dim3(threads), lds_fwd, c->stream, d, bi, B, init);
+      hipLaunchKernelGGL(rfast_softmax_backward<2>, bgrid, dim3(threads), lds_bwd, c->stream, d, bi, B, init);
+      break;
+    case 3:
+      hipLaunchKernelGGL(rfast_softmax_forward<3>, fgrid, dim3(threads), lds_fwd, c->stream, d, bi, B, init);
+      hipLaunchKernelGGL(rfast_softmax_backward<3>, bgrid, dim3(threads), lds_bwd, c->stream, d, bi, B, init);
+      break;
+    default:
+      hipLaunchKernelGGL(rfast_softmax_forward<4>, fgrid, dim3(threads), lds_fwd, c->stream, d, bi, B, init);
+      hipLaunchKernelGGL(rfast_softmax_backward<4>, bgrid, dim3(threads), lds_bwd, c->stream, d, bi, B, init);
+      break;
   }
-  hipLaunchKernelGGL(rfast_softmax_backward, dim3(d.prob.d / kTile, d.n), dim3(threads), lds_stage, c->stream, d, bi, B, init);
   return hipGetLastError();
 }

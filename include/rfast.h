@@ -103,7 +103,10 @@ typedef enum rfast_field {
   RFAST_SLOT_R = 9,    /* int32 [nnzR_off]  ring slot resolved in the last round (receiver active), else -1 */
   RFAST_SLOT_C = 10,   /* int32 [nnzC_off]                                         */
   RFAST_ROUND = 11,    /* int32 [1]  rounds executed                               */
-  RFAST_SIGMA_RING = 12 /* fp32 [n][D+2][p]  per-sender running sum of z_half, as stored */
+  RFAST_SIGMA_RING = 12, /* fp32 [n][D+2][p]  per-sender running sum of z_half, as stored */
+  RFAST_DELIV_R = 13,    /* uint64 [nnzR_off]  bit s set: the version in ring slot s was delivered on this edge */
+  RFAST_DELIV_C = 14,    /* uint64 [nnzC_off]                                                                */
+  RFAST_T_HIST = 15      /* int32 [n][D+1]  t_j at the start of round s, stored at s mod (D+1)              */
 } rfast_field;
 
 typedef struct rfast_diag {
@@ -164,6 +167,18 @@ int rfast_run(rfast_ctx* ctx, int32_t rounds, const uint8_t* d_active, const int
               const int32_t* d_delay_C, const uint8_t* d_drop_R, const uint8_t* d_drop_C,
               float gamma, const int32_t* d_batch_idx);
 
+/* Between rounds (asynchronous): subtracts from every sender's running sums, and
+ * from the buffers rho~ they feed, the sender's latest running sum.  Algorithm 1
+ * only uses the differences rho_ij - rho~_ij (S2b), which this leaves unchanged in
+ * exact arithmetic; in fp32 it stops the growth of the cancellation error of that
+ * difference with the number of rounds.  Call it every few hundred rounds of a
+ * long run; state read back afterwards shows the shifted rho and rho~. */
+int rfast_rebase(rfast_ctx* ctx);
+/* rounds > 0: rfast_round / rfast_run enqueue rfast_rebase after every `rounds`
+ * rounds; 0 (the default) never does.  One rebase costs about one round of a
+ * sparse graph (2(D+2) + 2 dO + 1 words per coordinate per sender). */
+int rfast_set_rebase_interval(rfast_ctx* ctx, int32_t rounds);
+
 /* Waits for the stream, then returns RFAST_OK or the first error a round
  * recorded on the device (RFAST_ERANGE) with its round and edge in the text. */
 int rfast_check(rfast_ctx* ctx);
@@ -171,6 +186,14 @@ int rfast_check(rfast_ctx* ctx);
 /* Waits for the stream and copies one field to HOST memory.  `bytes` must be
  * exactly the field's size (RFAST_EINVAL otherwise). */
 int rfast_read_state(rfast_ctx* ctx, int32_t field, void* host_dst, size_t bytes);
+
+/* Waits for the stream and overwrites one field from HOST memory: the inverse
+ * of rfast_read_state, for checkpoint / resume.  Restoring X, Z, G, V_RING,
+ * SIGMA_RING, RHO_TILDE, T_NODE, TAU_R, TAU_C, DELIV_R, DELIV_C, T_HIST and
+ * ROUND into a context created with the same arguments reproduces the run bit
+ * for bit.  RHO_RING (derived), SLOT_R and SLOT_C (per-round plan) cannot be
+ * written (RFAST_EINVAL). */
+int rfast_write_state(rfast_ctx* ctx, int32_t field, const void* host_src, size_t bytes);
 
 /* Reductions over the current state (synchronous).  d_xstar: device fp32 [p] or NULL. */
 int rfast_diagnostics(rfast_ctx* ctx, const float* d_xstar, rfast_diag* host_out);

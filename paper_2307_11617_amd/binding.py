@@ -30,9 +30,10 @@ class RfastDiag(C.Structure):
 
 OBJECTIVES = {"diag_quadratic": 0, "least_squares": 1, "logistic": 2, "softmax_bf16": 3}
 RFAST_FIELDS = {"X": 0, "Z": 1, "G": 2, "V_RING": 3, "RHO_RING": 4, "RHO_TILDE": 5, "T_NODE": 6, "TAU_R": 7,
-                "TAU_C": 8, "SLOT_R": 9, "SLOT_C": 10, "ROUND": 11, "SIGMA_RING": 12}
-EXPORTS = ["rfast_workspace_bytes", "rfast_create", "rfast_init", "rfast_round", "rfast_run", "rfast_check",
-           "rfast_read_state", "rfast_diagnostics", "rfast_profile_enable", "rfast_kernel_time", "rfast_last_error",
+                "TAU_C": 8, "SLOT_R": 9, "SLOT_C": 10, "ROUND": 11, "SIGMA_RING": 12, "DELIV_R": 13, "DELIV_C": 14,
+                "T_HIST": 15}
+EXPORTS = ["rfast_workspace_bytes", "rfast_create", "rfast_init", "rfast_round", "rfast_run", "rfast_rebase", "rfast_set_rebase_interval", "rfast_check",
+           "rfast_read_state", "rfast_write_state", "rfast_diagnostics", "rfast_profile_enable", "rfast_kernel_time", "rfast_last_error",
            "rfast_destroy"]
 
 
@@ -56,10 +57,16 @@ def lib():
     L.rfast_round.argtypes = [vp, vp, vp, vp, vp, vp, C.c_float, vp]
     L.rfast_run.restype = C.c_int
     L.rfast_run.argtypes = [vp, i32, vp, vp, vp, vp, vp, C.c_float, vp]
+    L.rfast_rebase.restype = C.c_int
+    L.rfast_rebase.argtypes = [vp]
+    L.rfast_set_rebase_interval.restype = C.c_int
+    L.rfast_set_rebase_interval.argtypes = [vp, i32]
     L.rfast_check.restype = C.c_int
     L.rfast_check.argtypes = [vp]
     L.rfast_read_state.restype = C.c_int
     L.rfast_read_state.argtypes = [vp, i32, vp, sz]
+    L.rfast_write_state.restype = C.c_int
+    L.rfast_write_state.argtypes = [vp, i32, vp, sz]
     L.rfast_diagnostics.restype = C.c_int
     L.rfast_diagnostics.argtypes = [vp, vp, C.POINTER(RfastDiag)]
     L.rfast_profile_enable.restype = C.c_int
@@ -120,6 +127,14 @@ def rfast_run(ctx, rounds, active, delay_R, delay_C, drop_R, drop_C, gamma, batc
                          _dev_ptr(drop_C), gamma, _dev_ptr(batch_idx)), ctx)
 
 
+def rfast_rebase(ctx):
+    _chk(lib().rfast_rebase(ctx), ctx)
+
+
+def rfast_set_rebase_interval(ctx, rounds):
+    _chk(lib().rfast_set_rebase_interval(ctx, rounds), ctx)
+
+
 def rfast_check(ctx):
     _chk(lib().rfast_check(ctx), ctx)
 
@@ -128,6 +143,12 @@ def rfast_read_state(ctx, field, out):
     """out: host numpy array of exactly the field's size."""
     _chk(lib().rfast_read_state(ctx, RFAST_FIELDS[field] if isinstance(field, str) else field, _np_ptr(out), out.nbytes), ctx)
     return out
+
+
+def rfast_write_state(ctx, field, src):
+    """src: host numpy array of exactly the field's size and dtype."""
+    src = np.ascontiguousarray(src)
+    _chk(lib().rfast_write_state(ctx, RFAST_FIELDS[field] if isinstance(field, str) else field, _np_ptr(src), src.nbytes), ctx)
 
 
 def rfast_diagnostics(ctx, xstar=None):
@@ -217,19 +238,44 @@ class RFast:
         self._check_schedule(rounds, active, delay_R, delay_C, drop_R, drop_C, batch_idx)
         rfast_run(self.ctx, rounds, active, delay_R, delay_C, drop_R, drop_C, gamma, batch_idx)
 
+    def rebase(self):
+        rfast_rebase(self.ctx)
+
     def check(self):
         rfast_check(self.ctx)
 
-    def read(self, field):
+    def _shape(self, field):
         n, p, M = self.n, self.p, self.M
         shapes = {"X": ((n, p), np.float32), "Z": ((n, p), np.float32), "G": ((n, p), np.float32),
                   "V_RING": ((n, M, p), np.float32), "RHO_RING": ((self.nnzC_off, M, p), np.float32),
                   "RHO_TILDE": ((self.nnzC_off, p), np.float32), "T_NODE": ((n,), np.int32),
                   "TAU_R": ((self.nnzR_off,), np.int32), "TAU_C": ((self.nnzC_off,), np.int32),
                   "SLOT_R": ((self.nnzR_off,), np.int32), "SLOT_C": ((self.nnzC_off,), np.int32),
-                  "ROUND": ((1,), np.int32), "SIGMA_RING": ((n, M, p), np.float32)}
-        shape, dt = shapes[field]
+                  "ROUND": ((1,), np.int32), "SIGMA_RING": ((n, M, p), np.float32),
+                  "DELIV_R": ((self.nnzR_off,), np.uint64), "DELIV_C": ((self.nnzC_off,), np.uint64),
+                  "T_HIST": ((n, self.D + 1), np.int32)}
+        return shapes[field]
+
+    def read(self, field):
+        shape, dt = self._shape(field)
         return rfast_read_state(self.ctx, field, np.empty(shape, dtype=dt))
+
+    CHECKPOINT_FIELDS = ("X", "Z", "G", "V_RING", "SIGMA_RING", "RHO_TILDE", "T_NODE", "TAU_R", "TAU_C", "DELIV_R",
+                         "DELIV_C", "T_HIST", "ROUND")
+
+    def write(self, field, value):
+        shape, dt = self._shape(field)
+        value = np.ascontiguousarray(value, dtype=dt)
+        if value.shape != shape:
+            raise RFastError(-1, f"{field}: expected shape {shape}")
+        rfast_write_state(self.ctx, field, value)
+
+    def checkpoint(self):
+        return {f: self.read(f) for f in self.CHECKPOINT_FIELDS}
+
+    def restore(self, ck):
+        for f in self.CHECKPOINT_FIELDS:
+            self.write(f, ck[f])
 
     def diagnostics(self, xstar=None):
         return rfast_diagnostics(self.ctx, xstar)

@@ -224,6 +224,9 @@ size_t field_bytes(const rfast_ctx* c, int32_t field) {
     case RFAST_TAU_R: case RFAST_SLOT_R: return (size_t)d.eR * 4;
     case RFAST_TAU_C: case RFAST_SLOT_C: return (size_t)d.eC * 4;
     case RFAST_ROUND: return 4;
+    case RFAST_DELIV_R: return (size_t)d.eR * 8;
+    case RFAST_DELIV_C: return (size_t)d.eC * 8;
+    case RFAST_T_HIST: return (size_t)d.n * d.H * 4;
     default: return (size_t)-1;
   }
 }
@@ -236,6 +239,16 @@ void time_end(rfast_ctx* c, int which) {
   if (!c->profiling || c->ev_used[which] >= c->ev[which][0].size()) return;
   (void)hipEventRecord(c->ev[which][1][c->ev_used[which]], c->stream);
   c->ev_used[which]++;
+}
+
+// automatic rebase of the running sums every `rebase_interval` rounds (0 = never)
+int after_round(rfast_ctx* c) {
+  if (c->rebase_interval > 0 && ++c->rounds_since_rebase >= c->rebase_interval) {
+    c->rounds_since_rebase = 0;
+    const hipError_t e = rfast_launch_rebase(c);
+    if (e != hipSuccess) return hipfail(c, e, "rebase launch");
+  }
+  return RFAST_OK;
 }
 
 }  // namespace
@@ -383,7 +396,7 @@ int rfast_round(rfast_ctx* c, const uint8_t* d_active, const int32_t* d_delay_R,
     e = rfast_launch_state(c, RFAST_MODE_FUSED, gamma);
     time_end(c, 0);
     if (e != hipSuccess) return hipfail(c, e, "fused round launch");
-    return RFAST_OK;
+    return after_round(c);
   }
   time_begin(c, 0);
   e = rfast_launch_state(c, RFAST_MODE_MIX, gamma);
@@ -397,7 +410,7 @@ int rfast_round(rfast_ctx* c, const uint8_t* d_active, const int32_t* d_delay_R,
   e = rfast_launch_state(c, RFAST_MODE_TRACK, gamma);
   time_end(c, 0);
   if (e != hipSuccess) return hipfail(c, e, "track launch");
-  return RFAST_OK;
+  return after_round(c);
 }
 
 int rfast_run(rfast_ctx* c, int32_t rounds, const uint8_t* d_active, const int32_t* d_delay_R, const int32_t* d_delay_C,
@@ -414,6 +427,20 @@ int rfast_run(rfast_ctx* c, int32_t rounds, const uint8_t* d_active, const int32
                                d_batch_idx ? d_batch_idx + (size_t)r * d.n * B : nullptr);
     if (rc != RFAST_OK) return rc;
   }
+  return RFAST_OK;
+}
+
+int rfast_set_rebase_interval(rfast_ctx* c, int32_t rounds) {
+  if (!c || rounds < 0) return RFAST_EINVAL;
+  c->rebase_interval = rounds;
+  c->rounds_since_rebase = 0;
+  return RFAST_OK;
+}
+
+int rfast_rebase(rfast_ctx* c) {
+  if (!c) return RFAST_EINVAL;
+  const hipError_t e = rfast_launch_rebase(c);
+  if (e != hipSuccess) return hipfail(c, e, "rebase launch");
   return RFAST_OK;
 }
 
@@ -453,6 +480,9 @@ int rfast_read_state(rfast_ctx* c, int32_t field, void* host_dst, size_t bytes) 
     case RFAST_SLOT_R: src = d.slot_r; break;
     case RFAST_SLOT_C: src = d.slot_c; break;
     case RFAST_ROUND: src = d.round_no; break;
+    case RFAST_DELIV_R: src = d.deliv_r; break;
+    case RFAST_DELIV_C: src = d.deliv_c; break;
+    case RFAST_T_HIST: src = d.t_hist; break;
     default: break;
   }
   if (field == RFAST_RHO_RING) {
@@ -479,6 +509,44 @@ int rfast_read_state(rfast_ctx* c, int32_t field, void* host_dst, size_t bytes) 
     e = hipMemcpy(host_dst, src, bytes, hipMemcpyDeviceToHost);
   }
   if (e != hipSuccess) return hipfail(c, e, "copying state to host");
+  return RFAST_OK;
+}
+
+int rfast_write_state(rfast_ctx* c, int32_t field, const void* host_src, size_t bytes) {
+  if (!c || !host_src) return RFAST_EINVAL;
+  if (field == RFAST_RHO_RING || field == RFAST_SLOT_R || field == RFAST_SLOT_C)
+    return fail(c, RFAST_EINVAL, "this field is derived and cannot be written");
+  const size_t want = field_bytes(c, field);
+  if (want == (size_t)-1) return fail(c, RFAST_EINVAL, "unknown field");
+  if (bytes != want) return fail(c, RFAST_EINVAL, "field holds " + std::to_string(want) + " bytes");
+  const RfastDev& d = c->d;
+  hipError_t e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return hipfail(c, e, "stream synchronize");
+  if (bytes == 0) return RFAST_OK;
+  void* dst = nullptr;
+  switch (field) {
+    case RFAST_X: dst = d.x; break;
+    case RFAST_Z: dst = d.z; break;
+    case RFAST_V_RING: dst = d.v_ring; break;
+    case RFAST_SIGMA_RING: dst = d.sigma_ring; break;
+    case RFAST_RHO_TILDE: dst = d.rho_tilde; break;
+    case RFAST_T_NODE: dst = d.t; break;
+    case RFAST_TAU_R: dst = d.tau_r; break;
+    case RFAST_TAU_C: dst = d.tau_c; break;
+    case RFAST_ROUND: dst = d.round_no; break;
+    case RFAST_DELIV_R: dst = d.deliv_r; break;
+    case RFAST_DELIV_C: dst = d.deliv_c; break;
+    case RFAST_T_HIST: dst = d.t_hist; break;
+    default: break;
+  }
+  if (field == RFAST_G) {
+    // both parities receive the sample, so the order of restoring G and T_NODE does not matter
+    e = hipMemcpy(d.g, host_src, bytes, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy((char*)d.g + bytes, host_src, bytes, hipMemcpyHostToDevice);
+  } else {
+    e = hipMemcpy(dst, host_src, bytes, hipMemcpyHostToDevice);
+  }
+  if (e != hipSuccess) return hipfail(c, e, "copying state to the device");
   return RFAST_OK;
 }
 

@@ -78,6 +78,8 @@ struct rfast_ctx {
   std::vector<hipEvent_t> ev[3][2];
   size_t ev_used[3] = {0, 0, 0};
   double* d_diag = nullptr;  // carved from the workspace
+  int32_t rebase_interval = 0;
+  int32_t rounds_since_rebase = 0;
 };
 
 enum { RFAST_MODE_FUSED = 0, RFAST_MODE_MIX = 1, RFAST_MODE_TRACK = 2 };
@@ -86,6 +88,7 @@ enum { RFAST_MODE_FUSED = 0, RFAST_MODE_MIX = 1, RFAST_MODE_TRACK = 2 };
 hipError_t rfast_launch_resolve(rfast_ctx* c, const uint8_t* active, const int32_t* delay_R,
                                 const int32_t* delay_C, const uint8_t* drop_R, const uint8_t* drop_C);
 hipError_t rfast_launch_state(rfast_ctx* c, int mode, float gamma);
+hipError_t rfast_launch_rebase(rfast_ctx* c);
 hipError_t rfast_launch_init_grad(rfast_ctx* c, const int32_t* batch_idx0);
 hipError_t rfast_launch_gradient(rfast_ctx* c, const int32_t* batch_idx);
 hipError_t rfast_launch_diag(rfast_ctx* c, const float* d_xstar, double* d_out);

@@ -262,6 +262,27 @@ __global__ void __launch_bounds__(kThreads) rfast_diag_init_kernel(RfastDev s) {
   V<VEC>::st(s.g + off, g);
 }
 
+// Rebase of the running sums.  sigma_j only ever enters as a_ij*sigma_j - rho~_ij, so
+// subtracting c_j = sigma_j(latest) from every ring slot of sender j and a_ij*c_j from
+// every buffer rho~_ij fed by j changes nothing in exact arithmetic; in fp32 it
+// removes the ever-growing common offset that the difference otherwise has to cancel.
+template <int VEC>
+__global__ void __launch_bounds__(kThreads) rfast_rebase_kernel(RfastDev s) {
+  using T = typename V<VEC>::T;
+  const int j = blockIdx.y;
+  const int64_t k = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * V<VEC>::W;
+  if (k >= s.p) return;
+  const int o0 = s.co_ptr[j], o1 = s.co_ptr[j + 1];
+  if (o0 == o1) return;  // nobody reads this sender's sums
+  float* ring = s.sigma_ring + (size_t)j * s.M * s.p + k;
+  const T c = V<VEC>::ld(ring + (size_t)(s.t[j] % s.M) * s.p);
+  for (int m = 0; m < s.M; ++m) V<VEC>::st(ring + (size_t)m * s.p, sub(V<VEC>::ld(ring + (size_t)m * s.p), c));
+  for (int o = o0; o < o1; ++o) {
+    float* rt = s.rho_tilde + (size_t)s.co_eid[o] * s.p + k;
+    V<VEC>::st(rt, sub(V<VEC>::ld(rt), mul_s(s.co_w[o], c)));
+  }
+}
+
 template <int MODE>
 hipError_t launch(rfast_ctx* c, float gamma) {
   const RfastDev& d = c->d;
@@ -292,6 +313,18 @@ hipError_t rfast_diag_init_gradient(rfast_ctx* c) {
     hipLaunchKernelGGL(rfast_diag_init_kernel<4>, dim3(gx, d.n), dim3(kThreads), 0, c->stream, d);
   else
     hipLaunchKernelGGL(rfast_diag_init_kernel<1>, dim3(gx, d.n), dim3(kThreads), 0, c->stream, d);
+  return hipGetLastError();
+}
+
+hipError_t rfast_launch_rebase(rfast_ctx* c) {
+  const RfastDev& d = c->d;
+  const bool vec4 = (d.p % 4) == 0;
+  const int64_t per_block = (int64_t)kThreads * (vec4 ? 4 : 1);
+  const unsigned gx = (unsigned)((d.p + per_block - 1) / per_block);
+  if (vec4)
+    hipLaunchKernelGGL(rfast_rebase_kernel<4>, dim3(gx, d.n), dim3(kThreads), 0, c->stream, d);
+  else
+    hipLaunchKernelGGL(rfast_rebase_kernel<1>, dim3(gx, d.n), dim3(kThreads), 0, c->stream, d);
   return hipGetLastError();
 }
 

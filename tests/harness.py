@@ -62,7 +62,7 @@ def rel_l2(a, b, floor=0.0):
     return float(np.linalg.norm(a.astype(np.float64) - b) / den) if den > 0 else float(np.linalg.norm(a))
 
 
-def run_parity(w, rounds, every=100, coords=None, x0=None, tol=None, check_rings=True, verbose=False):
+def run_parity(w, rounds, every=100, coords=None, x0=None, tol=None, check_rings=True, verbose=False, rebase=False):
     """Runs `rounds` rounds on both sides; at every checkpoint compares integer
     state exactly and x, z (and g, rho~) in relative L2.  Returns the worst errors."""
     tol = w.tol if tol is None else tol
@@ -102,7 +102,9 @@ def run_parity(w, rounds, every=100, coords=None, x0=None, tol=None, check_rings
         if verbose:
             print(f"round {r1}: rel-L2 x {ex:.2e} z {ez:.2e} g {eg:.2e}", flush=True)
         assert ex <= tol and ez <= tol, f"round {r1}: x {ex:.3e} z {ez:.3e} (tol {tol})"
-        if check_rings and coords is None and w.n * w.p * M <= 4_000_000:
+        if rebase:
+            gpu.rebase()   # shifts rho and rho~ by a common offset: only their difference is comparable afterwards
+        if check_rings and not rebase and coords is None and w.n * w.p * M <= 4_000_000:
             vr, rr, rt = gpu.read("V_RING"), gpu.read("RHO_RING"), gpu.read("RHO_TILDE")
             for j in range(w.n):
                 tj = int(orc.t[j])

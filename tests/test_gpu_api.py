@@ -125,6 +125,67 @@ def test_empty_round_and_no_edges():
     assert int(solo.read("T_NODE")[0]) == 200
 
 
+def test_checkpoint_resume_is_bit_exact():
+    """Read every field after 60 rounds, restore into a fresh context, continue both: identical bits."""
+    w = configs.config3(p=1028, rounds=120)
+    a = harness.make_gpu(w)
+    a.init()
+    st, dev = harness.upload_chunk(a, w, 0, 120)
+    part = lambda g, lo, hi: g.run(hi - lo, dev["active"][lo:hi].contiguous(), dev["delay_R"][lo:hi].contiguous(),
+                                   dev["delay_C"][lo:hi].contiguous(), dev["drop_R"][lo:hi].contiguous(),
+                                   dev["drop_C"][lo:hi].contiguous(), w.gamma)
+    part(a, 0, 60)
+    ck = a.checkpoint()
+    b = harness.make_gpu(w)
+    b.init()
+    b.restore(ck)
+    part(a, 60, 120)
+    part(b, 60, 120)
+    a.check()
+    b.check()
+    for f in a.CHECKPOINT_FIELDS + ("RHO_RING",):
+        assert np.array_equal(a.read(f), b.read(f)), f
+    assert int(b.read("ROUND")[0]) == 120
+    with pytest.raises(rf.RFastError):
+        b.write("RHO_RING", a.read("RHO_RING"))
+
+
+def test_rebase_keeps_long_runs_accurate():
+    """The running sums grow without bound and only rho - rho~ matters; rebasing every 100
+    rounds must leave the trajectory on the oracle's and reduce the fp32 error of z."""
+    w = configs.config2(p=1024, rounds=3000)
+    plain, _, _ = harness.run_parity(w, 3000, every=100, tol=1e-3)
+    based, orc, gpu = harness.run_parity(w, 3000, every=100, tol=1e-4, rebase=True)
+    print(f"\nworst rel-L2 over 3000 rounds: plain {plain}, rebased {based}")
+    assert based["z"] < 0.5 * plain["z"]
+    d = gpu.diagnostics()
+    # fp32 rounding is never given back to the tracker, so the residual random-walks with the
+    # number of rounds; after 3000 rounds it must still be far below the tracked mass
+    assert d["conservation_sq"] <= 1e-6 * max(d["gsum_sq"], d["z_sq"], 1.0)
+    sig = gpu.read("SIGMA_RING")
+    t = gpu.read("T_NODE")
+    for j in range(w.n):
+        assert not sig[j, t[j] % (w.D + 2)].any()      # the latest running sum is the new origin
+
+
+def test_automatic_rebase_interval_equals_manual_calls():
+    w = configs.config2(p=516, rounds=300)
+    a, b = harness.make_gpu(w), harness.make_gpu(w)
+    a.init()
+    b.init()
+    rf.rfast_set_rebase_interval(b.ctx, 100)
+    st, dev = harness.upload_chunk(a, w, 0, 300)
+    args = lambda lo, hi: (hi - lo, dev["active"][lo:hi].contiguous(), dev["delay_R"][lo:hi].contiguous(),
+                           dev["delay_C"][lo:hi].contiguous(), dev["drop_R"][lo:hi].contiguous(),
+                           dev["drop_C"][lo:hi].contiguous(), w.gamma)
+    for lo in (0, 100, 200):
+        a.run(*args(lo, lo + 100))
+        a.rebase()
+    b.run(*args(0, 300))
+    for f in ("X", "Z", "G", "SIGMA_RING", "RHO_TILDE", "T_NODE"):
+        assert np.array_equal(a.read(f), b.read(f)), f
+
+
 def test_profiling_hooks_count_launches():
     w = configs.config1(p=256, samples=64, batch=16, rounds=10)
     gpu = harness.make_gpu(w)

@@ -85,6 +85,8 @@ def main():
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--p", type=int, default=0, help="override p (not the headline workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sync", action="store_true",
+                    help="time the synchronous push-pull step (eq. (2)) on the same workload instead of the round")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only a plain 1 GiB device copy (10 launches): calibrates HBM byte counters")
     args = ap.parse_args()
@@ -116,6 +118,9 @@ def main():
     sl = lambda name, a, b: None if dev[name] is None else dev[name][a:b].contiguous()
     run = lambda a, b: gpu.run(b - a, sl("active", a, b), sl("delay_R", a, b), sl("delay_C", a, b), sl("drop_R", a, b),
                                sl("drop_C", a, b), w.gamma, sl("batch_idx", a, b))
+    if args.sync:
+        bi = lambda a, b: sl("batch_idx", a, b)
+        run = lambda a, b: gpu.sync_run(b - a, w.gamma, bi(a, b))
     run(0, W)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -134,9 +139,17 @@ def main():
 
     act_timed = st["active"][W:W + K].astype(np.int64)
     act_prof = st["active"][W + K:W + 2 * K].astype(np.int64)
+    if args.sync:
+        act_timed, act_prof = np.ones_like(act_timed), np.ones_like(act_prof)
     updates = int(act_timed.sum())
     bytes_prof = sum(algorithmic_bytes_per_round(w, a) for a in act_prof)
     bytes_layout = sum(algorithmic_bytes_per_round(w, a, layout=True) for a in act_prof)
+    if args.sync:
+        # descent: x, z -> v (3 words); step: 1+dR v's, 1+dI z's, g_old (+ h, c | g_new) in; x, g_new|-, z out
+        dR = (w.R.dense() != 0).sum(axis=1) - 1
+        dI = (w.C.dense() != 0).sum(axis=1) - 1
+        words = 3 + (1 + dR) + (1 + dI) + 1 + (2 + 3 if w.objective == "diag_quadratic" else 1 + 2)
+        bytes_prof = bytes_layout = float(words.sum() * 4.0 * w.p * K)
     launches = max(n_state, 1)
     avg_ms = ms_state / launches
     achieved = bytes_prof / (ms_state * 1e-3) / 1e9 if ms_state > 0 else 0.0
@@ -148,16 +161,16 @@ def main():
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": dt / K * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w.name, "n": w.n, "p": w.p, "D": w.D, "ring_slots": w.D + 2, "objective": w.objective,
+        "config": {"workload": w.name + ("/synchronous-push-pull" if args.sync else ""), "n": w.n, "p": w.p, "D": w.D, "ring_slots": w.D + 2, "objective": w.objective,
                    "mean_active_per_round": updates / K, "gamma": w.gamma},
-        "roofline": {"bound": "hbm", "kernel": "rfast_state_kernel" + ("<FUSED>" if w.objective == "diag_quadratic" else "<MIX>+<TRACK>"), "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": ("rfast_sync_descent+step" if args.sync else "rfast_state_kernel" + ("<FUSED>" if w.objective == "diag_quadratic" else "<MIX>+<TRACK>")), "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "avg_kernel_ms": avg_ms, "launches": n_state,
                      "algorithmic_bytes_per_launch": bytes_prof / launches,
                      "layout_bytes_per_launch": bytes_layout / launches,
                      "achieved_layout": achieved * bytes_layout / bytes_prof if bytes_prof else 0.0,
                      "frac_layout": achieved * bytes_layout / bytes_prof / HBM_PEAK_GBS if bytes_prof else 0.0,
-                     "traffic": measured_traffic(w.name) if not args.p else None},
+                     "traffic": measured_traffic(w.name) if not (args.p or args.sync) else None},
         "kernel_ms": {"state": ms_state, "gradient": ms_grad, "resolver": ms_res,
                       "launches": {"state": n_state, "gradient": n_grad, "resolver": n_res}},
         "host_data_generation_s": gen_s,

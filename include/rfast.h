@@ -167,6 +167,18 @@ int rfast_run(rfast_ctx* ctx, int32_t rounds, const uint8_t* d_active, const int
               const int32_t* d_delay_C, const uint8_t* d_drop_R, const uint8_t* d_drop_C,
               float gamma, const int32_t* d_batch_idx);
 
+/* One step of the synchronous push-pull recursion the method is developed from
+ * (eq. (2) of the paper), on the same x, z and stored gradient samples:
+ *   x_i' = sum_j w_ij (x_j - gamma z_j),  z_i' = sum_j a_ij z_j + grad f_i(x_i'; zeta') - grad f_i(x_i; zeta)
+ * with every node stepping at once (both sums include j = i; no delays, no losses).
+ * Every t_i advances by one and the sample stamp is t_i + 1, as in rfast_round.
+ * The step uses slots 0 and 1 of the v rings as buffers: do not interleave it with
+ * rfast_round on the same context without an rfast_init in between.
+ * d_batch_idx: device int32 [n][batch] (objectives with batch > 0), else NULL.
+ * rfast_sync_run: `rounds` steps from sample rows stacked [rounds][n][batch]. */
+int rfast_sync_round(rfast_ctx* ctx, float gamma, const int32_t* d_batch_idx);
+int rfast_sync_run(rfast_ctx* ctx, int32_t rounds, float gamma, const int32_t* d_batch_idx);
+
 /* Between rounds (asynchronous): subtracts from every sender's running sums, and
  * from the buffers rho~ they feed, the sender's latest running sum.  Algorithm 1
  * only uses the differences rho_ij - rho~_ij (S2b), which this leaves unchanged in

@@ -78,6 +78,7 @@ class DiagQuadratic:
         self.noise_std, self.noise_seed = float(noise_std), int(noise_seed)
         self.coords = None if coords is None else np.asarray(coords, dtype=np.int64)
         self.p_full = self.h.shape[1] if p_full is None else int(p_full)
+        self.p = self.h.shape[1]
 
     def grad(self, i, x, version, batch=None):
         g = self.h[i] * (x - self.c[i])
@@ -111,6 +112,7 @@ class LeastSquares:
     def __init__(self, A, b):
         self.A = np.asarray(A, dtype=np.float64)
         self.b = np.asarray(b, dtype=np.float64)
+        self.p = self.A.shape[2]
 
     def grad(self, i, x, version, batch=None):
         A, b = (self.A[i], self.b[i]) if batch is None else (self.A[i][batch], self.b[i][batch])
@@ -128,6 +130,7 @@ class Logistic:
         self.X = np.asarray(X, dtype=np.float64)
         self.y = np.asarray(y, dtype=np.float64)
         self.lam = float(lam)
+        self.p = self.X.shape[2]
 
     def grad(self, i, x, version, batch=None):
         X, y = (self.X[i], self.y[i]) if batch is None else (self.X[i][batch], self.y[i][batch])
@@ -160,6 +163,7 @@ class SoftmaxBf16:
         self.X = np.asarray(X_pool, dtype=np.float64)       # [n, samples, d], bf16-representable
         self.lab = np.asarray(labels, dtype=np.int64)
         self.d, self.K = int(d), int(K)
+        self.p = self.d * self.K
 
     def grad(self, i, x, version, batch=None):
         rows = np.arange(self.X.shape[1]) if batch is None else np.asarray(batch)

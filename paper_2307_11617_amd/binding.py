@@ -32,7 +32,7 @@ OBJECTIVES = {"diag_quadratic": 0, "least_squares": 1, "logistic": 2, "softmax_b
 RFAST_FIELDS = {"X": 0, "Z": 1, "G": 2, "V_RING": 3, "RHO_RING": 4, "RHO_TILDE": 5, "T_NODE": 6, "TAU_R": 7,
                 "TAU_C": 8, "SLOT_R": 9, "SLOT_C": 10, "ROUND": 11, "SIGMA_RING": 12, "DELIV_R": 13, "DELIV_C": 14,
                 "T_HIST": 15}
-EXPORTS = ["rfast_workspace_bytes", "rfast_create", "rfast_init", "rfast_round", "rfast_run", "rfast_rebase", "rfast_set_rebase_interval", "rfast_check",
+EXPORTS = ["rfast_workspace_bytes", "rfast_create", "rfast_init", "rfast_round", "rfast_run", "rfast_sync_round", "rfast_sync_run", "rfast_rebase", "rfast_set_rebase_interval", "rfast_check",
            "rfast_read_state", "rfast_write_state", "rfast_diagnostics", "rfast_profile_enable", "rfast_kernel_time", "rfast_last_error",
            "rfast_destroy"]
 
@@ -57,6 +57,10 @@ def lib():
     L.rfast_round.argtypes = [vp, vp, vp, vp, vp, vp, C.c_float, vp]
     L.rfast_run.restype = C.c_int
     L.rfast_run.argtypes = [vp, i32, vp, vp, vp, vp, vp, C.c_float, vp]
+    L.rfast_sync_round.restype = C.c_int
+    L.rfast_sync_round.argtypes = [vp, C.c_float, vp]
+    L.rfast_sync_run.restype = C.c_int
+    L.rfast_sync_run.argtypes = [vp, i32, C.c_float, vp]
     L.rfast_rebase.restype = C.c_int
     L.rfast_rebase.argtypes = [vp]
     L.rfast_set_rebase_interval.restype = C.c_int
@@ -125,6 +129,14 @@ def rfast_round(ctx, active, delay_R, delay_C, drop_R, drop_C, gamma, batch_idx=
 def rfast_run(ctx, rounds, active, delay_R, delay_C, drop_R, drop_C, gamma, batch_idx=None):
     _chk(lib().rfast_run(ctx, rounds, _dev_ptr(active), _dev_ptr(delay_R), _dev_ptr(delay_C), _dev_ptr(drop_R),
                          _dev_ptr(drop_C), gamma, _dev_ptr(batch_idx)), ctx)
+
+
+def rfast_sync_round(ctx, gamma, batch_idx=None):
+    _chk(lib().rfast_sync_round(ctx, gamma, _dev_ptr(batch_idx)), ctx)
+
+
+def rfast_sync_run(ctx, rounds, gamma, batch_idx=None):
+    _chk(lib().rfast_sync_run(ctx, rounds, gamma, _dev_ptr(batch_idx)), ctx)
 
 
 def rfast_rebase(ctx):
@@ -237,6 +249,14 @@ class RFast:
     def run(self, rounds, active, delay_R, delay_C, drop_R, drop_C, gamma, batch_idx=None):
         self._check_schedule(rounds, active, delay_R, delay_C, drop_R, drop_C, batch_idx)
         rfast_run(self.ctx, rounds, active, delay_R, delay_C, drop_R, drop_C, gamma, batch_idx)
+
+    def sync_run(self, rounds, gamma, batch_idx=None):
+        if self.prob.kind != 0 and self.prob.batch > 0:
+            t = self.torch
+            if batch_idx is None or batch_idx.dtype != t.int32 or batch_idx.device != self.device \
+                    or not batch_idx.is_contiguous() or batch_idx.numel() != rounds * self.n * self.prob.batch:
+                raise RFastError(-1, "batch_idx: need a contiguous int32 device tensor of rounds*n*batch rows")
+        rfast_sync_run(self.ctx, rounds, gamma, batch_idx)
 
     def rebase(self):
         rfast_rebase(self.ctx)

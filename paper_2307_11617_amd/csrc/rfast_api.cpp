@@ -241,6 +241,15 @@ void time_end(rfast_ctx* c, int which) {
   c->ev_used[which]++;
 }
 
+// the synchronous mode double-buffers z; bring it back into its own array before anything else looks at it
+int fold_sync(rfast_ctx* c) {
+  if (c->sync_parity == 0) return RFAST_OK;
+  const hipError_t e = rfast_launch_sync(c, 3, 0.f, 1);
+  if (e != hipSuccess) return hipfail(c, e, "fold launch");
+  c->sync_parity = 0;
+  return RFAST_OK;
+}
+
 // automatic rebase of the running sums every `rebase_interval` rounds (0 = never)
 int after_round(rfast_ctx* c) {
   if (c->rebase_interval > 0 && ++c->rounds_since_rebase >= c->rebase_interval) {
@@ -345,6 +354,8 @@ int rfast_init(rfast_ctx* c, const float* d_x0, const int32_t* d_batch_idx0) {
   if (d.prob.kind != RFAST_OBJ_DIAG_QUADRATIC && d.prob.batch > 0 && !d_batch_idx0)
     return fail(c, RFAST_EINVAL, "initial sample rows are required when batch > 0");
   const size_t vec = (size_t)d.p * 4;
+  c->sync_parity = 0;
+  c->rounds_since_rebase = 0;
   hipError_t e = hipSuccess;
   auto chk = [&](hipError_t r) { if (e == hipSuccess) e = r; };
   if (d_x0) chk(hipMemcpyAsync(d.x, d_x0, d.n * vec, hipMemcpyDeviceToDevice, c->stream));
@@ -386,6 +397,7 @@ int rfast_round(rfast_ctx* c, const uint8_t* d_active, const int32_t* d_delay_R,
   const bool separable = d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC;
   if (!separable && d.prob.batch > 0 && !d_batch_idx) return fail(c, RFAST_EINVAL, "sample rows are required when batch > 0");
   if (!std::isfinite(gamma)) return fail(c, RFAST_EINVAL, "gamma is not finite");
+  if (fold_sync(c) != RFAST_OK) return RFAST_EHIP;
   hipError_t e;
   time_begin(c, 2);
   e = rfast_launch_resolve(c, d_active, d_delay_R, d_delay_C, d_drop_R, d_drop_C);
@@ -430,6 +442,43 @@ int rfast_run(rfast_ctx* c, int32_t rounds, const uint8_t* d_active, const int32
   return RFAST_OK;
 }
 
+int rfast_sync_round(rfast_ctx* c, float gamma, const int32_t* d_batch_idx) {
+  if (!c) return RFAST_EINVAL;
+  const RfastDev& d = c->d;
+  const bool separable = d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC;
+  if (!separable && d.prob.batch > 0 && !d_batch_idx) return fail(c, RFAST_EINVAL, "sample rows are required when batch > 0");
+  if (!std::isfinite(gamma)) return fail(c, RFAST_EINVAL, "gamma is not finite");
+  hipError_t e;
+  time_begin(c, 0);
+  e = rfast_launch_sync(c, separable ? 2 : 0, gamma, c->sync_parity);
+  time_end(c, 0);
+  if (e != hipSuccess) return hipfail(c, e, "synchronous step launch");
+  if (!separable) {
+    time_begin(c, 1);
+    e = rfast_launch_gradient(c, d_batch_idx);
+    time_end(c, 1);
+    if (e != hipSuccess) return hipfail(c, e, "gradient launch");
+    time_begin(c, 0);
+    e = rfast_launch_sync(c, 1, gamma, c->sync_parity);
+    time_end(c, 0);
+    if (e != hipSuccess) return hipfail(c, e, "synchronous tracker launch");
+  }
+  c->sync_parity ^= 1;
+  return RFAST_OK;
+}
+
+int rfast_sync_run(rfast_ctx* c, int32_t rounds, float gamma, const int32_t* d_batch_idx) {
+  if (!c) return RFAST_EINVAL;
+  if (rounds < 0) return fail(c, RFAST_EINVAL, "rounds < 0");
+  const RfastDev& d = c->d;
+  const size_t B = d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC ? 0 : (size_t)d.prob.batch;
+  for (int32_t r = 0; r < rounds; ++r) {
+    const int rc = rfast_sync_round(c, gamma, d_batch_idx ? d_batch_idx + (size_t)r * d.n * B : nullptr);
+    if (rc != RFAST_OK) return rc;
+  }
+  return RFAST_OK;
+}
+
 int rfast_set_rebase_interval(rfast_ctx* c, int32_t rounds) {
   if (!c || rounds < 0) return RFAST_EINVAL;
   c->rebase_interval = rounds;
@@ -464,6 +513,7 @@ int rfast_read_state(rfast_ctx* c, int32_t field, void* host_dst, size_t bytes) 
   if (want == (size_t)-1) return fail(c, RFAST_EINVAL, "unknown field");
   if (bytes != want) return fail(c, RFAST_EINVAL, "field holds " + std::to_string(want) + " bytes");
   const RfastDev& d = c->d;
+  if (fold_sync(c) != RFAST_OK) return RFAST_EHIP;
   hipError_t e = hipStreamSynchronize(c->stream);
   if (e != hipSuccess) return hipfail(c, e, "stream synchronize");
   if (bytes == 0) return RFAST_OK;
@@ -520,6 +570,7 @@ int rfast_write_state(rfast_ctx* c, int32_t field, const void* host_src, size_t 
   if (want == (size_t)-1) return fail(c, RFAST_EINVAL, "unknown field");
   if (bytes != want) return fail(c, RFAST_EINVAL, "field holds " + std::to_string(want) + " bytes");
   const RfastDev& d = c->d;
+  if (fold_sync(c) != RFAST_OK) return RFAST_EHIP;
   hipError_t e = hipStreamSynchronize(c->stream);
   if (e != hipSuccess) return hipfail(c, e, "stream synchronize");
   if (bytes == 0) return RFAST_OK;
@@ -552,6 +603,7 @@ int rfast_write_state(rfast_ctx* c, int32_t field, const void* host_src, size_t 
 
 int rfast_diagnostics(rfast_ctx* c, const float* d_xstar, rfast_diag* host_out) {
   if (!c || !host_out) return RFAST_EINVAL;
+  if (fold_sync(c) != RFAST_OK) return RFAST_EHIP;
   hipError_t e = rfast_launch_diag(c, d_xstar, c->d_diag);
   if (e != hipSuccess) return hipfail(c, e, "diagnostics launch");
   e = hipStreamSynchronize(c->stream);

@@ -79,6 +79,7 @@ struct rfast_ctx {
   size_t ev_used[3] = {0, 0, 0};
   double* d_diag = nullptr;  // carved from the workspace
   int32_t rebase_interval = 0;
+  int32_t sync_parity = 0;  // 1: the current z of the synchronous mode lives in slot 1 of the v ring
   int32_t rounds_since_rebase = 0;
 };
 
@@ -89,6 +90,7 @@ hipError_t rfast_launch_resolve(rfast_ctx* c, const uint8_t* active, const int32
                                 const int32_t* delay_C, const uint8_t* drop_R, const uint8_t* drop_C);
 hipError_t rfast_launch_state(rfast_ctx* c, int mode, float gamma);
 hipError_t rfast_launch_rebase(rfast_ctx* c);
+hipError_t rfast_launch_sync(rfast_ctx* c, int phase, float gamma, int parity);
 hipError_t rfast_launch_init_grad(rfast_ctx* c, const int32_t* batch_idx0);
 hipError_t rfast_launch_gradient(rfast_ctx* c, const int32_t* batch_idx);
 hipError_t rfast_launch_diag(rfast_ctx* c, const float* d_xstar, double* d_out);

@@ -283,6 +283,84 @@ __global__ void __launch_bounds__(kThreads) rfast_rebase_kernel(RfastDev s) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// Synchronous push-pull step, eq. (2) of the paper (the recursion R-FAST is built on):
+//   x_i' = sum_j w_ij (x_j - gamma z_j),   z_i' = sum_j a_ij z_j + grad f_i(x_i') - grad f_i(x_i)
+// Every node steps at once, so the v_j = x_j - gamma z_j of all nodes are formed
+// first (slot 0 of the v ring serves as the buffer) and z is double-buffered
+// (parity 0: the z array, parity 1: slot 1 of the v ring).
+// ---------------------------------------------------------------------------
+__device__ inline float* sync_z(const RfastDev& s, int parity, int i) {
+  return parity == 0 ? s.z + (size_t)i * s.p : s.v_ring + ((size_t)i * s.M + 1) * s.p;
+}
+
+__global__ void __launch_bounds__(256) rfast_sync_plan_kernel(RfastDev s) {
+  for (int i = threadIdx.x; i < s.n; i += blockDim.x) {
+    const int ti = s.t[i];
+    s.plan_t[i] = ti;
+    s.active_list[i] = i;
+    s.t[i] = ti + 1;
+  }
+  if (threadIdx.x == 0) {
+    *s.n_active = s.n;
+    *s.round_no = *s.round_no + 1;
+  }
+}
+
+template <int VEC>
+__global__ void __launch_bounds__(kThreads) rfast_sync_descent_kernel(RfastDev s, float gamma, int parity) {
+  const int i = blockIdx.y;
+  const int64_t k = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * V<VEC>::W;
+  if (k >= s.p) return;
+  const auto x = V<VEC>::ld(s.x + (size_t)i * s.p + k);
+  const auto z = V<VEC>::ld(sync_z(s, parity, i) + k);
+  V<VEC>::st(s.v_ring + (size_t)i * s.M * s.p + k, fma_s(-gamma, z, x));
+}
+
+// PHASE 0: mix only (x').  PHASE 1: tracker only (reads g' written by the gradient
+// kernels).  PHASE 2: mix + diagonal-quadratic gradient + tracker in one pass.
+template <int VEC, int PHASE>
+__global__ void __launch_bounds__(kThreads) rfast_sync_step_kernel(RfastDev s, int parity) {
+  using T = typename V<VEC>::T;
+  const int i = blockIdx.y;
+  const int64_t k = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * V<VEC>::W;
+  if (k >= s.p) return;
+  const int64_t p = s.p;
+  const int t_old = s.plan_t[i];
+  const size_t off = (size_t)i * p + k;
+  float* g_old_p = s.g + (size_t)(t_old & 1) * s.n * p + off;
+  float* g_new_p = s.g + (size_t)((t_old + 1) & 1) * s.n * p + off;
+  T x_new, g_new;
+  if (PHASE != 1) {
+    x_new = mul_s(s.r_self[i], V<VEC>::ld(s.v_ring + (size_t)i * s.M * p + k));
+    for (int e = s.r_ptr[i]; e < s.r_ptr[i + 1]; ++e)
+      x_new = fma_s(s.r_w[e], V<VEC>::ld(s.v_ring + (size_t)s.r_src[e] * s.M * p + k), x_new);
+    V<VEC>::st(s.x + off, x_new);
+    if (PHASE == 0) return;
+    const T h = V<VEC>::ld((const float*)s.prob.data0 + off);
+    const T c = V<VEC>::ld((const float*)s.prob.data1 + off);
+    g_new = mul(h, sub(x_new, c));
+    if (s.prob.noise_std != 0.0f)
+      g_new = fma_s(s.prob.noise_std, noise_at<VEC>(s.prob.noise_seed, (uint32_t)i, (uint32_t)(t_old + 1), k), g_new);
+    V<VEC>::st(g_new_p, g_new);
+  } else {
+    g_new = V<VEC>::ld(g_new_p);
+  }
+  T z_new = mul_s(s.c_self[i], V<VEC>::ld(sync_z(s, parity, i) + k));
+  for (int e = s.c_ptr[i]; e < s.c_ptr[i + 1]; ++e)
+    z_new = fma_s(s.c_w[e], V<VEC>::ld(sync_z(s, parity, s.c_src[e]) + k), z_new);
+  z_new = sub(add(z_new, g_new), V<VEC>::ld(g_old_p));
+  V<VEC>::st(sync_z(s, parity ^ 1, i) + k, z_new);
+}
+
+template <int VEC>
+__global__ void __launch_bounds__(kThreads) rfast_sync_fold_kernel(RfastDev s) {
+  const int i = blockIdx.y;
+  const int64_t k = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * V<VEC>::W;
+  if (k >= s.p) return;
+  V<VEC>::st(s.z + (size_t)i * s.p + k, V<VEC>::ld(sync_z(s, 1, i) + k));
+}
+
 template <int MODE>
 hipError_t launch(rfast_ctx* c, float gamma) {
   const RfastDev& d = c->d;
@@ -313,6 +391,38 @@ hipError_t rfast_diag_init_gradient(rfast_ctx* c) {
     hipLaunchKernelGGL(rfast_diag_init_kernel<4>, dim3(gx, d.n), dim3(kThreads), 0, c->stream, d);
   else
     hipLaunchKernelGGL(rfast_diag_init_kernel<1>, dim3(gx, d.n), dim3(kThreads), 0, c->stream, d);
+  return hipGetLastError();
+}
+
+// phase: 0 plan + descent + mix, 1 tracker, 2 plan + descent + fused step, 3 fold z back into its array
+hipError_t rfast_launch_sync(rfast_ctx* c, int phase, float gamma, int parity) {
+  const RfastDev& d = c->d;
+  const bool vec4 = (d.p % 4) == 0;
+  const int64_t per_block = (int64_t)kThreads * (vec4 ? 4 : 1);
+  const dim3 grid((unsigned)((d.p + per_block - 1) / per_block), d.n), blk(kThreads);
+  const bool streaming = vec4 && (double)d.n * (double)d.p * 4.0 >= 32.0e6;
+  if (phase == 0 || phase == 2) {
+    hipLaunchKernelGGL(rfast_sync_plan_kernel, dim3(1), dim3(256), 0, c->stream, d);
+    if (streaming) hipLaunchKernelGGL(rfast_sync_descent_kernel<-4>, grid, blk, 0, c->stream, d, gamma, parity);
+    else if (vec4) hipLaunchKernelGGL(rfast_sync_descent_kernel<4>, grid, blk, 0, c->stream, d, gamma, parity);
+    else hipLaunchKernelGGL(rfast_sync_descent_kernel<1>, grid, blk, 0, c->stream, d, gamma, parity);
+  }
+  if (streaming) {
+    if (phase == 0) hipLaunchKernelGGL((rfast_sync_step_kernel<-4, 0>), grid, blk, 0, c->stream, d, parity);
+    if (phase == 1) hipLaunchKernelGGL((rfast_sync_step_kernel<-4, 1>), grid, blk, 0, c->stream, d, parity);
+    if (phase == 2) hipLaunchKernelGGL((rfast_sync_step_kernel<-4, 2>), grid, blk, 0, c->stream, d, parity);
+    if (phase == 3) hipLaunchKernelGGL(rfast_sync_fold_kernel<-4>, grid, blk, 0, c->stream, d);
+  } else if (vec4) {
+    if (phase == 0) hipLaunchKernelGGL((rfast_sync_step_kernel<4, 0>), grid, blk, 0, c->stream, d, parity);
+    if (phase == 1) hipLaunchKernelGGL((rfast_sync_step_kernel<4, 1>), grid, blk, 0, c->stream, d, parity);
+    if (phase == 2) hipLaunchKernelGGL((rfast_sync_step_kernel<4, 2>), grid, blk, 0, c->stream, d, parity);
+    if (phase == 3) hipLaunchKernelGGL(rfast_sync_fold_kernel<4>, grid, blk, 0, c->stream, d);
+  } else {
+    if (phase == 0) hipLaunchKernelGGL((rfast_sync_step_kernel<1, 0>), grid, blk, 0, c->stream, d, parity);
+    if (phase == 1) hipLaunchKernelGGL((rfast_sync_step_kernel<1, 1>), grid, blk, 0, c->stream, d, parity);
+    if (phase == 2) hipLaunchKernelGGL((rfast_sync_step_kernel<1, 2>), grid, blk, 0, c->stream, d, parity);
+    if (phase == 3) hipLaunchKernelGGL(rfast_sync_fold_kernel<1>, grid, blk, 0, c->stream, d);
+  }
   return hipGetLastError();
 }
 

@@ -150,6 +150,7 @@ __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float
   const int64_t k = ((int64_t)tile * kThreads + threadIdx.x) * V<VEC>::W;
   if (k >= s.p) return;
 
+  constexpr bool kMix = MODE != RFAST_MODE_TRACK, kTrack = MODE != RFAST_MODE_MIX;
   const int i = s.active_list[a];
   const int64_t p = s.p;
   const int M = s.M;
@@ -159,32 +160,68 @@ __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float
   const size_t node_off = (size_t)i * p + k;
   float* g_old_p = s.g + (size_t)(t_old & 1) * s.n * p + node_off;
   float* g_new_p = s.g + (size_t)((t_old + 1) & 1) * s.n * p + node_off;
+  const int re0 = s.r_ptr[i], re1 = s.r_ptr[i + 1];
+  const int ce0 = s.c_ptr[i], ce1 = s.c_ptr[i + 1];
+  // The running sums of S2c share one factor per sender: rho_li = a_li * sigma_i with
+  // sigma_i = sum of every z_half node i produced (1 read + 1 write instead of dO + dO).
+  const bool pushes = s.co_ptr[i + 1] > s.co_ptr[i];
 
-  T x_new, z_i, g_new, g_old;
+  // ---- every load of the first batch of each phase is issued before its first use:
+  //      with few wavefronts per CU this is what keeps enough bytes in flight
+  T x_i, z_i, g_old, g_new, h, c, sig_cur;
+  T vb[kBatch], sg[kBatch], rt[kBatch];
+  float vw[kBatch], ca[kBatch];
+  bool live[kBatch];
+  z_i = V<VEC>::ld(s.z + node_off);
+  if (kMix) {
+    x_i = V<VEC>::ld(s.x + node_off);
+#pragma unroll
+    for (int q = 0; q < kBatch; ++q)
+      if (re0 + q < re1) {
+        vb[q] = V<VEC>::ld(s.v_ring + ((size_t)s.r_src[re0 + q] * M + s.slot_r[re0 + q]) * p + k);
+        vw[q] = s.r_w[re0 + q];
+      }
+  }
+  if (kTrack) {
+    g_old = V<VEC>::ld(g_old_p);
+    if (MODE == RFAST_MODE_FUSED) {
+      h = V<VEC>::ld((const float*)s.prob.data0 + node_off);
+      c = V<VEC>::ld((const float*)s.prob.data1 + node_off);
+    } else {
+      g_new = V<VEC>::ld(g_new_p);
+    }
+    if (pushes) sig_cur = V<VEC>::ld(s.sigma_ring + ((size_t)i * M + slot_cur) * p + k);
+#pragma unroll
+    for (int q = 0; q < kBatch; ++q) {
+      const int e = ce0 + q;
+      live[q] = e < ce1 && !s.skip_c[e];
+      if (live[q]) {
+        sg[q] = V<VEC>::ld(s.sigma_ring + ((size_t)s.c_src[e] * M + s.slot_c[e]) * p + k);
+        rt[q] = V<VEC>::ld(s.rho_tilde + (size_t)e * p + k);
+        ca[q] = s.c_w[e];
+      }
+    }
+  }
 
-  if (MODE != RFAST_MODE_TRACK) {
+  T x_new;
+  if (kMix) {
     // S1: local descent
-    const T x_i = V<VEC>::ld(s.x + node_off);
-    z_i = V<VEC>::ld(s.z + node_off);
     const T v = fma_s(-gamma, z_i, x_i);
     // S2a: pull the stamped neighbour copies and mix with row-stochastic weights
     x_new = mul_s(s.r_self[i], v);
-    const int e0 = s.r_ptr[i], e1 = s.r_ptr[i + 1];
-    for (int eb = e0; eb < e1; eb += kBatch) {
-      T buf[kBatch];
-      float w[kBatch];
 #pragma unroll
-      for (int q = 0; q < kBatch; ++q) {
-        const int e = eb + q;
-        if (e < e1) {
-          const int j = s.r_src[e];
-          buf[q] = V<VEC>::ld(s.v_ring + ((size_t)j * M + s.slot_r[e]) * p + k);
-          w[q] = s.r_w[e];
-        }
-      }
+    for (int q = 0; q < kBatch; ++q)
+      if (re0 + q < re1) x_new = fma_s(vw[q], vb[q], x_new);
+    for (int eb = re0 + kBatch; eb < re1; eb += kBatch) {  // in-degree above one batch
 #pragma unroll
       for (int q = 0; q < kBatch; ++q)
-        if (eb + q < e1) x_new = fma_s(w[q], buf[q], x_new);
+        if (eb + q < re1) {
+          vb[q] = V<VEC>::ld(s.v_ring + ((size_t)s.r_src[eb + q] * M + s.slot_r[eb + q]) * p + k);
+          vw[q] = s.r_w[eb + q];
+        }
+#pragma unroll
+      for (int q = 0; q < kBatch; ++q)
+        if (eb + q < re1) x_new = fma_s(vw[q], vb[q], x_new);
     }
     // S3 (v half): publish version t+1
     V<VEC>::st(s.v_ring + ((size_t)i * M + slot_new) * p + k, v);
@@ -194,52 +231,40 @@ __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float
 
   if (MODE == RFAST_MODE_FUSED) {
     // sampled gradient of the diagonal quadratic at the new point
-    const T h = V<VEC>::ld((const float*)s.prob.data0 + node_off);
-    const T c = V<VEC>::ld((const float*)s.prob.data1 + node_off);
     g_new = mul(h, sub(x_new, c));
     if (s.prob.noise_std != 0.0f)
       g_new = fma_s(s.prob.noise_std, noise_at<VEC>(s.prob.noise_seed, (uint32_t)i, (uint32_t)(t_old + 1), k), g_new);
     V<VEC>::st(g_new_p, g_new);
-  } else {
-    z_i = V<VEC>::ld(s.z + node_off);
-    g_new = V<VEC>::ld(g_new_p);
   }
-  g_old = V<VEC>::ld(g_old_p);
-
-  // The running sums of S2c share one factor per sender: rho_li = a_li * sigma_i with
-  // sigma_i = sum of every z_half node i produced.  One ring of sigma per sender
-  // replaces a ring per edge (1 read + 1 write instead of dO reads + dO writes).
-  const bool pushes = s.co_ptr[i + 1] > s.co_ptr[i];
-  T sig_cur;
-  if (pushes) sig_cur = V<VEC>::ld(s.sigma_ring + ((size_t)i * M + slot_cur) * p + k);
 
   // S2b: tracker sum over the in-edges of C; S4: buffer what was consumed.
   // An edge whose stamp did not move holds rho == rho~ exactly and is skipped.
   T z_half = z_i;
-  {
-    const int e0 = s.c_ptr[i], e1 = s.c_ptr[i + 1];
-    for (int eb = e0; eb < e1; eb += kBatch) {
-      T sig[kBatch], rt[kBatch];
-      float a[kBatch];
-      bool live[kBatch];
 #pragma unroll
-      for (int q = 0; q < kBatch; ++q) {
-        const int e = eb + q;
-        live[q] = e < e1 && !s.skip_c[e];
-        if (live[q]) {
-          sig[q] = V<VEC>::ld(s.sigma_ring + ((size_t)s.c_src[e] * M + s.slot_c[e]) * p + k);
-          rt[q] = V<VEC>::ld(s.rho_tilde + (size_t)e * p + k);
-          a[q] = s.c_w[e];
-        }
-      }
-#pragma unroll
-      for (int q = 0; q < kBatch; ++q)
-        if (live[q]) {
-          const T rho = mul_s(a[q], sig[q]);
-          z_half = add(z_half, sub(rho, rt[q]));
-          V<VEC>::st(s.rho_tilde + (size_t)(eb + q) * p + k, rho);
-        }
+  for (int q = 0; q < kBatch; ++q)
+    if (live[q]) {
+      const T rho = mul_s(ca[q], sg[q]);
+      z_half = add(z_half, sub(rho, rt[q]));
+      V<VEC>::st(s.rho_tilde + (size_t)(ce0 + q) * p + k, rho);
     }
+  for (int eb = ce0 + kBatch; eb < ce1; eb += kBatch) {  // in-degree above one batch
+#pragma unroll
+    for (int q = 0; q < kBatch; ++q) {
+      const int e = eb + q;
+      live[q] = e < ce1 && !s.skip_c[e];
+      if (live[q]) {
+        sg[q] = V<VEC>::ld(s.sigma_ring + ((size_t)s.c_src[e] * M + s.slot_c[e]) * p + k);
+        rt[q] = V<VEC>::ld(s.rho_tilde + (size_t)e * p + k);
+        ca[q] = s.c_w[e];
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < kBatch; ++q)
+      if (live[q]) {
+        const T rho = mul_s(ca[q], sg[q]);
+        z_half = add(z_half, sub(rho, rt[q]));
+        V<VEC>::st(s.rho_tilde + (size_t)(eb + q) * p + k, rho);
+      }
   }
   z_half = sub(add(z_half, g_new), g_old);
 
@@ -248,6 +273,7 @@ __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float
   if (pushes) V<VEC>::st(s.sigma_ring + ((size_t)i * M + slot_new) * p + k, add(sig_cur, z_half));
 }
 
+// g^0 = h*(x^0 - c) + noise of sample version 0 (initialisation of Algorithm 1)
 template <int VEC>
 __global__ void __launch_bounds__(kThreads) rfast_diag_init_kernel(RfastDev s) {
   const int i = blockIdx.y;
@@ -369,7 +395,9 @@ hipError_t launch(rfast_ctx* c, float gamma) {
   const int64_t tiles = (d.p + per_block - 1) / per_block;
   const int64_t blocks = tiles * d.n;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  // stream past the caches once the per-round working set dwarfs them (256 MB of last-level cache)
+  // Stream past the caches once the state dwarfs them (256 MB of last-level cache).  (Capping the
+  // CU at two workgroups by reserving LDS gained 5-8 % in a fixed-degree replica of this kernel but
+  // nothing here, where the 141 registers of the up-front loads already hold it to 12 wavefronts.)
   const bool streaming = (double)d.n * (double)d.p * 4.0 >= 32.0e6;
   if (vec4 && streaming)
     hipLaunchKernelGGL((rfast_state_kernel<MODE, -4>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, d, gamma, (int)tiles);

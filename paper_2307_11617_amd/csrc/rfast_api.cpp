@@ -39,7 +39,7 @@ struct Offsets {
 };
 
 bool sizes_ok(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, const rfast_problem* prob) {
-  if (n < 1 || p < 1 || nnzR < n || nnzC < n || D < 0 || D + 2 > 64 || prob == nullptr) return false;
+  if (n < 1 || n > 65535 || p < 1 || nnzR < n || nnzC < n || D < 0 || D + 2 > 64 || prob == nullptr) return false;  // n rides in gridDim.y
   if (prob->kind < 0 || prob->kind > RFAST_OBJ_SOFTMAX_BF16) return false;
   if (prob->kind != RFAST_OBJ_DIAG_QUADRATIC && (prob->samples < 1 || prob->batch < 0 || prob->batch > prob->samples))
     return false;
@@ -276,7 +276,7 @@ int rfast_create(rfast_ctx** out, int32_t n, int64_t p, const int32_t* R_rowptr,
   *out = nullptr;
   if (!R_rowptr || !R_col || !R_w || !C_rowptr || !C_col || !C_w || !prob || !d_workspace)
     return fail(nullptr, RFAST_EINVAL, "NULL argument");
-  if (n < 1 || p < 1) return fail(nullptr, RFAST_EINVAL, "n and p must be positive");
+  if (n < 1 || n > 65535 || p < 1) return fail(nullptr, RFAST_EINVAL, "need 1 <= n <= 65535 and p >= 1");
   if (D < 0 || D + 2 > 64) return fail(nullptr, RFAST_ERANGE, "D + 2 must be in [2, 64]");
   if (burst < 1 || burst - 1 > D) return fail(nullptr, RFAST_ERANGE, "burst must be in [1, D+1]");
   const int32_t nnzR = R_rowptr[n], nnzC = C_rowptr[n];

@@ -106,7 +106,14 @@ typedef enum rfast_field {
   RFAST_SIGMA_RING = 12, /* fp32 [n][D+2][p]  per-sender running sum of z_half, as stored */
   RFAST_DELIV_R = 13,    /* uint64 [nnzR_off]  bit s set: the version in ring slot s was delivered on this edge */
   RFAST_DELIV_C = 14,    /* uint64 [nnzC_off]                                                                */
-  RFAST_T_HIST = 15      /* int32 [n][D+1]  t_j at the start of round s, stored at s mod (D+1)              */
+  RFAST_T_HIST = 15,     /* int32 [n][D+1]  t_j at the start of round s, stored at s mod (D+1)              */
+  /* schedule of the last round generated on the device (rfast_run_generated), read-only: */
+  RFAST_SCHED_ACTIVE = 16,  /* uint8 [n] */
+  RFAST_SCHED_DELAY_R = 17, /* int32 [nnzR_off] */
+  RFAST_SCHED_DELAY_C = 18, /* int32 [nnzC_off] */
+  RFAST_SCHED_DROP_R = 19,  /* uint8 [nnzR_off] */
+  RFAST_SCHED_DROP_C = 20,  /* uint8 [nnzC_off] */
+  RFAST_SCHED_BATCH = 21    /* int32 [n][batch] */
 } rfast_field;
 
 typedef struct rfast_diag {
@@ -166,6 +173,23 @@ int rfast_round(rfast_ctx* ctx, const uint8_t* d_active, const int32_t* d_delay_
 int rfast_run(rfast_ctx* ctx, int32_t rounds, const uint8_t* d_active, const int32_t* d_delay_R,
               const int32_t* d_delay_C, const uint8_t* d_drop_R, const uint8_t* d_drop_C,
               float gamma, const int32_t* d_batch_idx);
+
+/* `rounds` rounds whose schedule is generated on the device as a pure function
+ * of (seed, round number), so that nothing is uploaded per round (Assumption 3:
+ * who is active, how stale each edge is, which packets are lost, which rows are
+ * sampled).  With word(stream, r, e) = Philox4x32-10(counter (e div 4, stream,
+ * r, 0), key seed)[e mod 4]:
+ *   active[i]  = word(0, r, i) < floor(p_active[i] * 2^32)
+ *   delay_R[e] = word(1, r, e) mod (max_delay + 1);   delay_C[e]: stream 2
+ *   drop_R[e]  = word(3, r, e) < floor(p_drop * 2^32);  drop_C[e]: stream 4
+ *   rows of node i = perm(0..batch-1), perm a keyed bijection of [0, samples):
+ *   4-round balanced Feistel network on 2h bits (h = ceil(bits/2), bits = bit
+ *   length of samples-1, at least 1), cycle-walked into range, round keys
+ *   Philox(counter (i, 5, r, 0)); round function on half R with key K:
+ *   t = R*0x9E3779B1 + K; t ^= t >> 15; t *= 0x85EBCA77; F = t >> (32-h) (mod 2^32).
+ * d_p_active: DEVICE fp32 [n].  max_delay in [0, D-burst+1] (RFAST_ERANGE). */
+int rfast_run_generated(rfast_ctx* ctx, int32_t rounds, uint64_t seed, const float* d_p_active,
+                        int32_t max_delay, float p_drop, float gamma);
 
 /* One step of the synchronous push-pull recursion the method is developed from
  * (eq. (2) of the paper), on the same x, z and stored gradient samples:

@@ -31,8 +31,9 @@ class RfastDiag(C.Structure):
 OBJECTIVES = {"diag_quadratic": 0, "least_squares": 1, "logistic": 2, "softmax_bf16": 3}
 RFAST_FIELDS = {"X": 0, "Z": 1, "G": 2, "V_RING": 3, "RHO_RING": 4, "RHO_TILDE": 5, "T_NODE": 6, "TAU_R": 7,
                 "TAU_C": 8, "SLOT_R": 9, "SLOT_C": 10, "ROUND": 11, "SIGMA_RING": 12, "DELIV_R": 13, "DELIV_C": 14,
-                "T_HIST": 15}
-EXPORTS = ["rfast_workspace_bytes", "rfast_create", "rfast_init", "rfast_round", "rfast_run", "rfast_sync_round", "rfast_sync_run", "rfast_rebase", "rfast_set_rebase_interval", "rfast_check",
+                "T_HIST": 15, "SCHED_ACTIVE": 16, "SCHED_DELAY_R": 17, "SCHED_DELAY_C": 18, "SCHED_DROP_R": 19,
+                "SCHED_DROP_C": 20, "SCHED_BATCH": 21}
+EXPORTS = ["rfast_workspace_bytes", "rfast_create", "rfast_init", "rfast_round", "rfast_run", "rfast_run_generated", "rfast_sync_round", "rfast_sync_run", "rfast_rebase", "rfast_set_rebase_interval", "rfast_check",
            "rfast_read_state", "rfast_write_state", "rfast_diagnostics", "rfast_profile_enable", "rfast_kernel_time", "rfast_last_error",
            "rfast_destroy"]
 
@@ -57,6 +58,8 @@ def lib():
     L.rfast_round.argtypes = [vp, vp, vp, vp, vp, vp, C.c_float, vp]
     L.rfast_run.restype = C.c_int
     L.rfast_run.argtypes = [vp, i32, vp, vp, vp, vp, vp, C.c_float, vp]
+    L.rfast_run_generated.restype = C.c_int
+    L.rfast_run_generated.argtypes = [vp, i32, C.c_uint64, vp, i32, C.c_float, C.c_float]
     L.rfast_sync_round.restype = C.c_int
     L.rfast_sync_round.argtypes = [vp, C.c_float, vp]
     L.rfast_sync_run.restype = C.c_int
@@ -129,6 +132,10 @@ def rfast_round(ctx, active, delay_R, delay_C, drop_R, drop_C, gamma, batch_idx=
 def rfast_run(ctx, rounds, active, delay_R, delay_C, drop_R, drop_C, gamma, batch_idx=None):
     _chk(lib().rfast_run(ctx, rounds, _dev_ptr(active), _dev_ptr(delay_R), _dev_ptr(delay_C), _dev_ptr(drop_R),
                          _dev_ptr(drop_C), gamma, _dev_ptr(batch_idx)), ctx)
+
+
+def rfast_run_generated(ctx, rounds, seed, p_active, max_delay, p_drop, gamma):
+    _chk(lib().rfast_run_generated(ctx, rounds, seed, _dev_ptr(p_active), max_delay, p_drop, gamma), ctx)
 
 
 def rfast_sync_round(ctx, gamma, batch_idx=None):
@@ -250,6 +257,13 @@ class RFast:
         self._check_schedule(rounds, active, delay_R, delay_C, drop_R, drop_C, batch_idx)
         rfast_run(self.ctx, rounds, active, delay_R, delay_C, drop_R, drop_C, gamma, batch_idx)
 
+    def run_generated(self, rounds, seed, p_active, max_delay, p_drop, gamma):
+        t = self.torch
+        if p_active.dtype != t.float32 or p_active.device != self.device or p_active.numel() != self.n \
+                or not p_active.is_contiguous():
+            raise RFastError(-1, "p_active: need a contiguous float32 device tensor of n probabilities")
+        rfast_run_generated(self.ctx, rounds, seed, p_active, max_delay, p_drop, gamma)
+
     def sync_run(self, rounds, gamma, batch_idx=None):
         if self.prob.kind != 0 and self.prob.batch > 0:
             t = self.torch
@@ -273,7 +287,10 @@ class RFast:
                   "SLOT_R": ((self.nnzR_off,), np.int32), "SLOT_C": ((self.nnzC_off,), np.int32),
                   "ROUND": ((1,), np.int32), "SIGMA_RING": ((n, M, p), np.float32),
                   "DELIV_R": ((self.nnzR_off,), np.uint64), "DELIV_C": ((self.nnzC_off,), np.uint64),
-                  "T_HIST": ((n, self.D + 1), np.int32)}
+                  "T_HIST": ((n, self.D + 1), np.int32), "SCHED_ACTIVE": ((n,), np.uint8),
+                  "SCHED_DELAY_R": ((self.nnzR_off,), np.int32), "SCHED_DELAY_C": ((self.nnzC_off,), np.int32),
+                  "SCHED_DROP_R": ((self.nnzR_off,), np.uint8), "SCHED_DROP_C": ((self.nnzC_off,), np.uint8),
+                  "SCHED_BATCH": ((n, self.prob.batch if self.prob.kind != 0 else 0), np.int32)}
         return shapes[field]
 
     def read(self, field):

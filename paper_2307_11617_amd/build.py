@@ -8,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "librfast.so")
 SOURCES = ["rfast_api.cpp", "rfast_resolve.hip", "rfast_round.hip", "rfast_grad.hip", "rfast_softmax.hip",
-           "rfast_diag.hip"]
+           "rfast_diag.hip", "rfast_schedule.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-shared", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

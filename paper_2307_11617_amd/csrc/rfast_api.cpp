@@ -34,6 +34,7 @@ struct Offsets {
   size_t r_ptr, r_src, r_dst, r_w, r_self, c_ptr, c_src, c_dst, c_w, c_self, co_ptr, co_eid, co_w, ro_ptr, ro_eid;
   size_t t, t_hist, tau_r, tau_c, deliv_r, deliv_c, round_no, err;
   size_t n_active, active_list, plan_t, slot_r, slot_c, skip_c;
+  size_t gen_active, gen_delay_r, gen_delay_c, gen_drop_r, gen_drop_c, gen_batch;
   size_t resid, gscratch, diag;
   size_t total;
 };
@@ -92,6 +93,12 @@ Offsets layout(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, cons
   o.slot_r = L.take(eR * 4);
   o.slot_c = L.take(eC * 4);
   o.skip_c = L.take(eC);
+  o.gen_active = L.take(n);
+  o.gen_delay_r = L.take(eR * 4);
+  o.gen_delay_c = L.take(eC * 4);
+  o.gen_drop_r = L.take(eR);
+  o.gen_drop_c = L.take(eC);
+  o.gen_batch = L.take((size_t)n * (size_t)(prob->kind == RFAST_OBJ_DIAG_QUADRATIC ? 0 : prob->batch) * 4);
   o.resid = L.take(rfast_gemv_scratch_floats(n, prob) * 4);
   o.gscratch = L.take(rfast_softmax_scratch_bytes(n, prob));
   o.diag = L.take(64 * sizeof(double));
@@ -227,6 +234,12 @@ size_t field_bytes(const rfast_ctx* c, int32_t field) {
     case RFAST_DELIV_R: return (size_t)d.eR * 8;
     case RFAST_DELIV_C: return (size_t)d.eC * 8;
     case RFAST_T_HIST: return (size_t)d.n * d.H * 4;
+    case RFAST_SCHED_ACTIVE: return (size_t)d.n;
+    case RFAST_SCHED_DELAY_R: return (size_t)d.eR * 4;
+    case RFAST_SCHED_DELAY_C: return (size_t)d.eC * 4;
+    case RFAST_SCHED_DROP_R: return (size_t)d.eR;
+    case RFAST_SCHED_DROP_C: return (size_t)d.eC;
+    case RFAST_SCHED_BATCH: return (size_t)d.n * (d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC ? 0 : d.prob.batch) * 4;
     default: return (size_t)-1;
   }
 }
@@ -327,6 +340,9 @@ int rfast_create(rfast_ctx** out, int32_t n, int64_t p, const int32_t* R_rowptr,
   d.n_active = (int32_t*)(b + o.n_active); d.active_list = (int32_t*)(b + o.active_list);
   d.plan_t = (int32_t*)(b + o.plan_t); d.slot_r = (int32_t*)(b + o.slot_r); d.slot_c = (int32_t*)(b + o.slot_c);
   d.skip_c = (uint8_t*)(b + o.skip_c);
+  d.gen_active = (uint8_t*)(b + o.gen_active); d.gen_delay_r = (int32_t*)(b + o.gen_delay_r);
+  d.gen_delay_c = (int32_t*)(b + o.gen_delay_c); d.gen_drop_r = (uint8_t*)(b + o.gen_drop_r);
+  d.gen_drop_c = (uint8_t*)(b + o.gen_drop_c); d.gen_batch = (int32_t*)(b + o.gen_batch);
   d.resid = (float*)(b + o.resid); d.gscratch = (void*)(b + o.gscratch);
   c->d_diag = (double*)(b + o.diag);
   d.prob = *prob;
@@ -442,6 +458,22 @@ int rfast_run(rfast_ctx* c, int32_t rounds, const uint8_t* d_active, const int32
   return RFAST_OK;
 }
 
+int rfast_run_generated(rfast_ctx* c, int32_t rounds, uint64_t seed, const float* d_p_active, int32_t max_delay,
+                        float p_drop, float gamma) {
+  if (!c || !d_p_active) return RFAST_EINVAL;
+  if (rounds < 0) return fail(c, RFAST_EINVAL, "rounds < 0");
+  const RfastDev& d = c->d;
+  if (max_delay < 0 || max_delay > d.d_max) return fail(c, RFAST_ERANGE, "max_delay must lie in [0, D - burst + 1]");
+  if (!(p_drop >= 0.f && p_drop <= 1.f)) return fail(c, RFAST_ERANGE, "p_drop must lie in [0, 1]");
+  for (int32_t r = 0; r < rounds; ++r) {
+    const hipError_t e = rfast_launch_generate(c, seed, d_p_active, max_delay, p_drop);
+    if (e != hipSuccess) return hipfail(c, e, "schedule generator launch");
+    const int rc = rfast_round(c, d.gen_active, d.gen_delay_r, d.gen_delay_c, d.gen_drop_r, d.gen_drop_c, gamma, d.gen_batch);
+    if (rc != RFAST_OK) return rc;
+  }
+  return RFAST_OK;
+}
+
 int rfast_sync_round(rfast_ctx* c, float gamma, const int32_t* d_batch_idx) {
   if (!c) return RFAST_EINVAL;
   const RfastDev& d = c->d;
@@ -533,6 +565,12 @@ int rfast_read_state(rfast_ctx* c, int32_t field, void* host_dst, size_t bytes) 
     case RFAST_DELIV_R: src = d.deliv_r; break;
     case RFAST_DELIV_C: src = d.deliv_c; break;
     case RFAST_T_HIST: src = d.t_hist; break;
+    case RFAST_SCHED_ACTIVE: src = d.gen_active; break;
+    case RFAST_SCHED_DELAY_R: src = d.gen_delay_r; break;
+    case RFAST_SCHED_DELAY_C: src = d.gen_delay_c; break;
+    case RFAST_SCHED_DROP_R: src = d.gen_drop_r; break;
+    case RFAST_SCHED_DROP_C: src = d.gen_drop_c; break;
+    case RFAST_SCHED_BATCH: src = d.gen_batch; break;
     default: break;
   }
   if (field == RFAST_RHO_RING) {
@@ -564,7 +602,7 @@ int rfast_read_state(rfast_ctx* c, int32_t field, void* host_dst, size_t bytes) 
 
 int rfast_write_state(rfast_ctx* c, int32_t field, const void* host_src, size_t bytes) {
   if (!c || !host_src) return RFAST_EINVAL;
-  if (field == RFAST_RHO_RING || field == RFAST_SLOT_R || field == RFAST_SLOT_C)
+  if (field == RFAST_RHO_RING || field == RFAST_SLOT_R || field == RFAST_SLOT_C || field >= RFAST_SCHED_ACTIVE)
     return fail(c, RFAST_EINVAL, "this field is derived and cannot be written");
   const size_t want = field_bytes(c, field);
   if (want == (size_t)-1) return fail(c, RFAST_EINVAL, "unknown field");

@@ -63,6 +63,13 @@ struct RfastDev {
   int32_t* slot_r;        // [eR]  resolved slot, -1 if receiver inactive
   int32_t* slot_c;        // [eC]
   uint8_t* skip_c;        // [eC]  stamp unchanged since last consume: contributes exactly zero
+  // schedule of the current round when it is generated on the device
+  uint8_t* gen_active;    // [n]
+  int32_t* gen_delay_r;   // [eR]
+  int32_t* gen_delay_c;   // [eC]
+  uint8_t* gen_drop_r;    // [eR]
+  uint8_t* gen_drop_c;    // [eC]
+  int32_t* gen_batch;     // [n][batch]
   // gradient scratch
   float* resid;           // [n][rows] residuals of the GEMV pair / unused
   void* gscratch;         // softmax: bf16 W copy and E matrix
@@ -90,6 +97,7 @@ hipError_t rfast_launch_resolve(rfast_ctx* c, const uint8_t* active, const int32
                                 const int32_t* delay_C, const uint8_t* drop_R, const uint8_t* drop_C);
 hipError_t rfast_launch_state(rfast_ctx* c, int mode, float gamma);
 hipError_t rfast_launch_rebase(rfast_ctx* c);
+hipError_t rfast_launch_generate(rfast_ctx* c, uint64_t seed, const float* d_p_active, int d_max, float p_drop);
 hipError_t rfast_launch_sync(rfast_ctx* c, int phase, float gamma, int parity);
 hipError_t rfast_launch_init_grad(rfast_ctx* c, const int32_t* batch_idx0);
 hipError_t rfast_launch_gradient(rfast_ctx* c, const int32_t* batch_idx);

@@ -16,6 +16,7 @@
 // algebraically identical to the per-edge recursion, bit-identical when a_li is
 // a power of two, and it replaces dO reads + dO writes per coordinate by 1 + 1.
 #include "rfast_internal.h"
+#include "rfast_philox.h"
 
 namespace {
 
@@ -66,21 +67,6 @@ __device__ inline float4 mul(float4 a, float4 b) { return make_float4(a.x * b.x,
 __device__ inline float mul(float a, float b) { return a * b; }
 
 // ------------------------------------------------- counter-based Gaussian noise
-// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11).
-__device__ inline void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1,
-                                     uint32_t out[4]) {
-#pragma unroll
-  for (int r = 0; r < 10; ++r) {
-    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
-    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
-    const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
-    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
-    k0 += 0x9E3779B9u;
-    k1 += 0xBB67AE85u;
-  }
-  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
-}
-
 // sin and cos of 2*pi*w/2^32.  The octant comes from the top three bits, so the
 // reduction is exact; the remainder a in [-pi/8, pi/8] goes through Taylor
 // polynomials whose truncation error is below 1e-8.
@@ -120,7 +106,7 @@ __device__ inline void box_muller(uint32_t ou, uint32_t oa, float* n0, float* n1
 // four normals of coordinate group q
 __device__ inline float4 noise4(uint64_t seed, uint32_t node, uint32_t version, uint64_t q) {
   uint32_t o[4];
-  philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), node, version, (uint32_t)seed, (uint32_t)(seed >> 32), o);
+  rfast_philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), node, version, (uint32_t)seed, (uint32_t)(seed >> 32), o);
   float4 z;
   box_muller(o[0], o[1], &z.x, &z.y);
   box_muller(o[2], o[3], &z.z, &z.w);

@@ -87,6 +87,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sync", action="store_true",
                     help="time the synchronous push-pull step (eq. (2)) on the same workload instead of the round")
+    ap.add_argument("--generated", action="store_true",
+                    help="generate the schedule on the device (rfast_run_generated) instead of uploading it")
+    ap.add_argument("--graphs", action="store_true", help="with --generated: replay HIP graphs of 16 rounds")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only a plain 1 GiB device copy (10 launches): calibrates HBM byte counters")
     args = ap.parse_args()
@@ -118,16 +121,23 @@ def main():
     sl = lambda name, a, b: None if dev[name] is None else dev[name][a:b].contiguous()
     run = lambda a, b: gpu.run(b - a, sl("active", a, b), sl("delay_R", a, b), sl("delay_C", a, b), sl("drop_R", a, b),
                                sl("drop_C", a, b), w.gamma, sl("batch_idx", a, b))
+    if args.generated:
+        p_act = torch.from_numpy(w.sched.p_active.astype(np.float32)).to(gpu.device)
+        if args.graphs:
+            rf.rfast_use_graphs(gpu.ctx, True)
+        run = lambda a, b: gpu.run_generated(b - a, 20231117, p_act, w.sched.d_max, w.sched.p_drop, w.gamma)
     if args.sync:
         bi = lambda a, b: sl("batch_idx", a, b)
         run = lambda a, b: gpu.sync_run(b - a, w.gamma, bi(a, b))
     run(0, W)
     torch.cuda.synchronize()
+    t_before = int(gpu.read("T_NODE").sum()) if args.generated else 0
     t0 = time.perf_counter()
     run(W, W + K)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     gpu.check()
+    t_after = int(gpu.read("T_NODE").sum()) if args.generated else 0
 
     # second pass with HIP events around every kernel launch (on the library's stream)
     rf.rfast_profile_enable(gpu.ctx, True)
@@ -141,7 +151,10 @@ def main():
     act_prof = st["active"][W + K:W + 2 * K].astype(np.int64)
     if args.sync:
         act_timed, act_prof = np.ones_like(act_timed), np.ones_like(act_prof)
-    updates = int(act_timed.sum())
+    if args.generated:   # the masks live on the device; count the activations from the counters
+        updates = t_after - t_before
+    else:
+        updates = int(act_timed.sum())
     bytes_prof = sum(algorithmic_bytes_per_round(w, a) for a in act_prof)
     bytes_layout = sum(algorithmic_bytes_per_round(w, a, layout=True) for a in act_prof)
     if args.sync:
@@ -161,7 +174,8 @@ def main():
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": dt / K * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w.name + ("/synchronous-push-pull" if args.sync else ""), "n": w.n, "p": w.p, "D": w.D, "ring_slots": w.D + 2, "objective": w.objective,
+        "config": {"workload": w.name + ("/synchronous-push-pull" if args.sync else "") +
+                               ("/generated-schedule" if args.generated else "") + ("/hip-graphs" if args.graphs else ""), "n": w.n, "p": w.p, "D": w.D, "ring_slots": w.D + 2, "objective": w.objective,
                    "mean_active_per_round": updates / K, "gamma": w.gamma},
         "roofline": {"bound": "hbm", "kernel": ("rfast_sync_descent+step" if args.sync else "rfast_state_kernel" + ("<FUSED>" if w.objective == "diag_quadratic" else "<MIX>+<TRACK>")), "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,

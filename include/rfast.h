@@ -191,6 +191,12 @@ int rfast_run(rfast_ctx* ctx, int32_t rounds, const uint8_t* d_active, const int
 int rfast_run_generated(rfast_ctx* ctx, int32_t rounds, uint64_t seed, const float* d_p_active,
                         int32_t max_delay, float p_drop, float gamma);
 
+/* on != 0: rfast_run_generated replays a HIP graph of 16 generated rounds (one
+ * launch per 16 rounds instead of 4-7 per round) whenever at least 16 rounds are
+ * asked for, profiling is off and no rebase interval is set; the remaining rounds
+ * run as ordinary launches.  Results are identical either way.  Off by default. */
+int rfast_use_graphs(rfast_ctx* ctx, int32_t on);
+
 /* One step of the synchronous push-pull recursion the method is developed from
  * (eq. (2) of the paper), on the same x, z and stored gradient samples:
  *   x_i' = sum_j w_ij (x_j - gamma z_j),  z_i' = sum_j a_ij z_j + grad f_i(x_i'; zeta') - grad f_i(x_i; zeta)

@@ -263,6 +263,13 @@ int fold_sync(rfast_ctx* c) {
   return RFAST_OK;
 }
 
+constexpr int32_t kGraphRounds = 16;
+
+void drop_graph(rfast_ctx* c) {
+  if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
+  c->graph_exec = nullptr;
+}
+
 // automatic rebase of the running sums every `rebase_interval` rounds (0 = never)
 int after_round(rfast_ctx* c) {
   if (c->rebase_interval > 0 && ++c->rounds_since_rebase >= c->rebase_interval) {
@@ -270,6 +277,54 @@ int after_round(rfast_ctx* c) {
     const hipError_t e = rfast_launch_rebase(c);
     if (e != hipSuccess) return hipfail(c, e, "rebase launch");
   }
+  return RFAST_OK;
+}
+
+}  // namespace
+
+extern "C" int rfast_round(rfast_ctx* c, const uint8_t* d_active, const int32_t* d_delay_R, const int32_t* d_delay_C,
+                           const uint8_t* d_drop_R, const uint8_t* d_drop_C, float gamma, const int32_t* d_batch_idx);
+
+namespace {
+
+// Captures kGraphRounds generated rounds on a private stream (capture is not allowed on
+// the legacy default stream, which is what callers usually hand over) and instantiates them.
+int build_graph(rfast_ctx* c, uint64_t seed, const float* d_p_active, int32_t max_delay, float p_drop, float gamma) {
+  drop_graph(c);
+  if (!c->capture_stream) {
+    const hipError_t e = hipStreamCreateWithFlags(&c->capture_stream, hipStreamNonBlocking);
+    if (e != hipSuccess) return hipfail(c, e, "hipStreamCreateWithFlags");
+  }
+  const RfastDev& d = c->d;
+  hipStream_t user = c->stream;
+  hipError_t e = hipStreamBeginCapture(c->capture_stream, hipStreamCaptureModeThreadLocal);
+  if (e != hipSuccess) return hipfail(c, e, "hipStreamBeginCapture");
+  c->stream = c->capture_stream;
+  int rc = RFAST_OK;
+  for (int32_t r = 0; r < kGraphRounds && rc == RFAST_OK; ++r) {
+    const hipError_t g = rfast_launch_generate(c, seed, d_p_active, max_delay, p_drop);
+    if (g != hipSuccess) rc = hipfail(c, g, "schedule generator launch");
+    else rc = rfast_round(c, d.gen_active, d.gen_delay_r, d.gen_delay_c, d.gen_drop_r, d.gen_drop_c, gamma, d.gen_batch);
+  }
+  c->stream = user;
+  hipGraph_t graph = nullptr;
+  e = hipStreamEndCapture(c->capture_stream, &graph);
+  if (rc != RFAST_OK) {
+    if (graph) (void)hipGraphDestroy(graph);
+    return rc;
+  }
+  if (e != hipSuccess) return hipfail(c, e, "hipStreamEndCapture");
+  e = hipGraphInstantiate(&c->graph_exec, graph, nullptr, nullptr, 0);
+  (void)hipGraphDestroy(graph);
+  if (e != hipSuccess) {
+    c->graph_exec = nullptr;
+    return hipfail(c, e, "hipGraphInstantiate");
+  }
+  c->graph_seed = seed;
+  c->graph_p_active = d_p_active;
+  c->graph_max_delay = max_delay;
+  c->graph_p_drop = p_drop;
+  c->graph_gamma = gamma;
   return RFAST_OK;
 }
 
@@ -458,6 +513,13 @@ int rfast_run(rfast_ctx* c, int32_t rounds, const uint8_t* d_active, const int32
   return RFAST_OK;
 }
 
+int rfast_use_graphs(rfast_ctx* c, int32_t on) {
+  if (!c) return RFAST_EINVAL;
+  c->use_graphs = on != 0;
+  if (!on) drop_graph(c);
+  return RFAST_OK;
+}
+
 int rfast_run_generated(rfast_ctx* c, int32_t rounds, uint64_t seed, const float* d_p_active, int32_t max_delay,
                         float p_drop, float gamma) {
   if (!c || !d_p_active) return RFAST_EINVAL;
@@ -465,6 +527,24 @@ int rfast_run_generated(rfast_ctx* c, int32_t rounds, uint64_t seed, const float
   const RfastDev& d = c->d;
   if (max_delay < 0 || max_delay > d.d_max) return fail(c, RFAST_ERANGE, "max_delay must lie in [0, D - burst + 1]");
   if (!(p_drop >= 0.f && p_drop <= 1.f)) return fail(c, RFAST_ERANGE, "p_drop must lie in [0, 1]");
+  if (!std::isfinite(gamma)) return fail(c, RFAST_EINVAL, "gamma is not finite");
+  // A generated round takes no host argument that varies from round to round (the
+  // generator reads the round number on the device), so kGraphRounds of them are
+  // captured once into a HIP graph and replayed: one launch per kGraphRounds rounds.
+  if (c->use_graphs && !c->profiling && c->rebase_interval == 0 && rounds >= kGraphRounds) {
+    if (fold_sync(c) != RFAST_OK) return RFAST_EHIP;
+    const bool same = c->graph_exec && c->graph_seed == seed && c->graph_p_active == d_p_active &&
+                      c->graph_max_delay == max_delay && c->graph_p_drop == p_drop && c->graph_gamma == gamma;
+    if (!same) {
+      const int rc = build_graph(c, seed, d_p_active, max_delay, p_drop, gamma);
+      if (rc != RFAST_OK) return rc;
+    }
+    while (rounds >= kGraphRounds) {
+      const hipError_t e = hipGraphLaunch(c->graph_exec, c->stream);
+      if (e != hipSuccess) return hipfail(c, e, "hipGraphLaunch");
+      rounds -= kGraphRounds;
+    }
+  }
   for (int32_t r = 0; r < rounds; ++r) {
     const hipError_t e = rfast_launch_generate(c, seed, d_p_active, max_delay, p_drop);
     if (e != hipSuccess) return hipfail(c, e, "schedule generator launch");
@@ -696,6 +776,8 @@ const char* rfast_last_error(const rfast_ctx* c) { return c ? c->err.c_str() : g
 void rfast_destroy(rfast_ctx* c) {
   if (!c) return;
   (void)hipStreamSynchronize(c->stream);
+  drop_graph(c);
+  if (c->capture_stream) (void)hipStreamDestroy(c->capture_stream);
   for (int w = 0; w < 3; ++w)
     for (int s = 0; s < 2; ++s)
       for (hipEvent_t ev : c->ev[w][s]) (void)hipEventDestroy(ev);

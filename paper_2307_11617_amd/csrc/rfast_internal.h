@@ -86,6 +86,14 @@ struct rfast_ctx {
   size_t ev_used[3] = {0, 0, 0};
   double* d_diag = nullptr;  // carved from the workspace
   int32_t rebase_interval = 0;
+  // replayable HIP graph of kGraphRounds generated rounds (rfast_run_generated), and what it was built for
+  bool use_graphs = false;
+  hipGraphExec_t graph_exec = nullptr;
+  hipStream_t capture_stream = nullptr;
+  uint64_t graph_seed = 0;
+  const float* graph_p_active = nullptr;
+  int32_t graph_max_delay = 0;
+  float graph_p_drop = 0.f, graph_gamma = 0.f;
   int32_t sync_parity = 0;  // 1: the current z of the synchronous mode lives in slot 1 of the v ring
   int32_t rounds_since_rebase = 0;
 };

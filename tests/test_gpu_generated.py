@@ -61,3 +61,39 @@ def test_generated_run_matches_oracle(which):
         ex, ez = harness.rel_l2(gpu.read("X"), orc.x), harness.rel_l2(gpu.read("Z"), orc.z, 1e-3 * gn)
         assert ex <= 1e-4 and ez <= 1e-4, (chunk, ex, ez)
     assert 0 < orc.t.min() < orc.t.max()
+
+
+@pytest.mark.parametrize("which", ["diag", "logistic"])
+def test_graph_replay_equals_eager_launches(which):
+    """A HIP graph of 16 generated rounds, replayed several times with eager work and
+    host synchronisations in between, must leave exactly the state eager launches leave."""
+    import paper_2307_11617_amd as rf
+    if which == "diag":
+        w = configs.config2(p=2048, rounds=0)
+        d_max, p_drop = 4, 0.02
+    else:
+        w = configs.config1(p=132, samples=64, batch=16, rounds=0)
+        d_max, p_drop = 8, 0.05
+    p_act = torch.full((w.n,), 0.6, dtype=torch.float32)
+    eager, graph = harness.make_gpu(w), harness.make_gpu(w)
+    dev_p = p_act.to(eager.device)
+    for g in (eager, graph):
+        g.init(None, w.sched.initial_batch())
+    rf.rfast_use_graphs(graph.ctx, True)
+    fields = ("X", "Z", "G", "V_RING", "SIGMA_RING", "RHO_TILDE", "T_NODE", "TAU_R", "TAU_C", "DELIV_R", "DELIV_C", "ROUND")
+    for rounds in (16, 37, 5, 48, 16):          # replays, remainders, a short eager-only call
+        eager.run_generated(rounds, 7, dev_p, d_max, p_drop, w.gamma)
+        graph.run_generated(rounds, 7, dev_p, d_max, p_drop, w.gamma)
+        graph.check()
+        for f in fields:
+            assert np.array_equal(eager.read(f), graph.read(f)), (rounds, f)
+        graph.diagnostics()                      # unrelated eager work between replays
+    # changing an argument rebuilds the graph
+    eager.run_generated(32, 8, dev_p, d_max, p_drop, w.gamma * 0.5)
+    graph.run_generated(32, 8, dev_p, d_max, p_drop, w.gamma * 0.5)
+    for f in fields:
+        assert np.array_equal(eager.read(f), graph.read(f)), f
+    rf.rfast_use_graphs(graph.ctx, False)
+    eager.run_generated(20, 8, dev_p, d_max, p_drop, w.gamma)
+    graph.run_generated(20, 8, dev_p, d_max, p_drop, w.gamma)
+    assert np.array_equal(eager.read("X"), graph.read("X"))

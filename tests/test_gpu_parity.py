@@ -50,6 +50,13 @@ def test_config4_small():
     _report(w.name, worst)
 
 
+def test_config4_small_all_classes():
+    """K = 128 (four class tiles, the full-size wave layout) at a small d."""
+    w = configs.config4(d=256, K=128, samples=256, batch=64, rounds=200)
+    worst, orc, gpu = harness.run_parity(w, 200, every=100)
+    _report(w.name + " d=256", worst)
+
+
 def test_x0_nonzero_and_noise_free():
     rng = np.random.default_rng(0)
     w = configs.config2(p=2048, rounds=200)

@@ -52,3 +52,27 @@ def test_no_delay_no_loss_is_synchronous_special_case():
     d = gpu.diagnostics()
     assert d["consensus_sq"] < 1e-3 * w.p     # the nodes agree
     print(f"\n[{w.name}] worst {worst}")
+
+
+def test_many_nodes_tiny_vectors():
+    """n above the resolver's workgroup size (active-list compaction and edge loops in
+    several chunks), p = 3 (scalar path, one partial tile)."""
+    n = 1500
+    rng = np.random.default_rng(3)
+    adj = np.eye(n, dtype=bool)
+    for j in range(n):
+        adj[(j + 1) % n, j] = True
+        for t in rng.integers(0, n, 2):
+            adj[t, j] = True
+    wr = adj / adj.sum(axis=1, keepdims=True)
+    wc = adj / adj.sum(axis=0, keepdims=True)
+    w = _workload(n, 3, wr, wc, d_max=3, burst=2, p_active=0.4, p_drop=0.2, seed=5, gamma=0.05, noise=0.1)
+    assert w.R.nnz_off > 2048
+    worst, orc, gpu = harness.run_parity(w, 60, every=20)
+    print(f"\n[{w.name}] worst {worst}")
+
+
+def test_single_coordinate_and_full_batch_logistic():
+    w = configs.config1(p=1, samples=64, batch=64, rounds=0)
+    worst, orc, gpu = harness.run_parity(w, 120, every=40)
+    print(f"\n[{w.name} p=1 full batch] worst {worst}")

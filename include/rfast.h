@@ -130,6 +130,14 @@ typedef struct rfast_diag {
 size_t rfast_workspace_bytes(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D,
                              const rfast_problem* prob);
 
+/* Assumption 2 as a host-only check: host_is_root[i] (nullable) = 1 iff node i is the
+ * root of a spanning tree of G(R) (reaches every node along sender -> receiver edges)
+ * AND of G(C^T) (is reached by every node along C's sender -> receiver edges).  Returns
+ * the number of common roots (0 = the pair of graphs violates the assumption) or a
+ * negative rfast_status.  CSR as for rfast_create (row = receiver); weights are not needed. */
+int rfast_common_roots(int32_t n, const int32_t* R_rowptr, const int32_t* R_col, const int32_t* C_rowptr,
+                       const int32_t* C_col, uint8_t* host_is_root);
+
 /* Builds a context.  R_*, C_*: host CSR (row = receiver) with fp32 weights.
  * D: largest staleness in sender versions any read may have (Assumption 3 ii),
  *    1 <= D+2 <= 64.  burst >= 1: a version whose burst-1 predecessors on the

@@ -33,7 +33,7 @@ RFAST_FIELDS = {"X": 0, "Z": 1, "G": 2, "V_RING": 3, "RHO_RING": 4, "RHO_TILDE":
                 "TAU_C": 8, "SLOT_R": 9, "SLOT_C": 10, "ROUND": 11, "SIGMA_RING": 12, "DELIV_R": 13, "DELIV_C": 14,
                 "T_HIST": 15, "SCHED_ACTIVE": 16, "SCHED_DELAY_R": 17, "SCHED_DELAY_C": 18, "SCHED_DROP_R": 19,
                 "SCHED_DROP_C": 20, "SCHED_BATCH": 21}
-EXPORTS = ["rfast_workspace_bytes", "rfast_create", "rfast_init", "rfast_round", "rfast_run", "rfast_run_generated", "rfast_use_graphs", "rfast_sync_round", "rfast_sync_run", "rfast_rebase", "rfast_set_rebase_interval", "rfast_check",
+EXPORTS = ["rfast_common_roots", "rfast_workspace_bytes", "rfast_create", "rfast_init", "rfast_round", "rfast_run", "rfast_run_generated", "rfast_use_graphs", "rfast_sync_round", "rfast_sync_run", "rfast_rebase", "rfast_set_rebase_interval", "rfast_check",
            "rfast_read_state", "rfast_write_state", "rfast_diagnostics", "rfast_profile_enable", "rfast_kernel_time", "rfast_last_error",
            "rfast_destroy"]
 
@@ -49,6 +49,8 @@ def lib():
     vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
     L.rfast_workspace_bytes.restype = sz
     L.rfast_workspace_bytes.argtypes = [i32, i64, i32, i32, i32, C.POINTER(RfastProblem)]
+    L.rfast_common_roots.restype = C.c_int
+    L.rfast_common_roots.argtypes = [i32, vp, vp, vp, vp, vp]
     L.rfast_create.restype = C.c_int
     L.rfast_create.argtypes = [C.POINTER(vp), i32, i64, vp, vp, vp, vp, vp, vp, i32, i32, C.POINTER(RfastProblem),
                                vp, sz, vp]
@@ -109,6 +111,16 @@ def _chk(code, ctx=None):
 
 def rfast_workspace_bytes(n, p, nnzR, nnzC, D, prob):
     return int(lib().rfast_workspace_bytes(n, p, nnzR, nnzC, D, C.byref(prob)))
+
+
+def rfast_common_roots(n, R_rowptr, R_col, C_rowptr, C_col):
+    """Nodes that are roots of spanning trees of both G(R) and G(C^T) (Assumption 2), as a uint8 mask."""
+    arrs = [np.ascontiguousarray(a, np.int32) for a in (R_rowptr, R_col, C_rowptr, C_col)]
+    out = np.zeros(n, dtype=np.uint8)
+    code = lib().rfast_common_roots(n, *[_np_ptr(a) for a in arrs], _np_ptr(out))
+    if code < 0:
+        raise RFastError(code, rfast_last_error(None))
+    return out
 
 
 def rfast_create(n, p, R, Cg, D, burst, prob, workspace, stream_ptr):

@@ -332,6 +332,35 @@ int build_graph(rfast_ctx* c, uint64_t seed, const float* d_p_active, int32_t ma
 
 extern "C" {
 
+int rfast_common_roots(int32_t n, const int32_t* R_rowptr, const int32_t* R_col, const int32_t* C_rowptr,
+                       const int32_t* C_col, uint8_t* host_is_root) {
+  if (n < 1 || !R_rowptr || !R_col || !C_rowptr || !C_col) return fail(nullptr, RFAST_EINVAL, "NULL argument or n < 1");
+  HostGraph g[2];
+  const int32_t* ptrs[2] = {R_rowptr, C_rowptr};
+  const int32_t* cols[2] = {R_col, C_col};
+  for (int q = 0; q < 2; ++q) {
+    if (ptrs[q][0] != 0) return fail(nullptr, RFAST_EGRAPH, "rowptr[0] != 0");
+    g[q].ptr.assign(n + 1, 0);
+    for (int i = 0; i < n; ++i) {
+      if (ptrs[q][i + 1] < ptrs[q][i]) return fail(nullptr, RFAST_EGRAPH, "rowptr not monotone");
+      for (int k = ptrs[q][i]; k < ptrs[q][i + 1]; ++k) {
+        const int j = cols[q][k];
+        if (j < 0 || j >= n) return fail(nullptr, RFAST_EGRAPH, "column index out of range");
+        if (j != i) g[q].src.push_back(j);
+      }
+      g[q].ptr[i + 1] = (int32_t)g[q].src.size();
+    }
+  }
+  const std::vector<char> rr = roots_of(n, g[0], true), rc = roots_of(n, g[1], false);
+  int count = 0;
+  for (int i = 0; i < n; ++i) {
+    const bool both = rr[i] && rc[i];
+    if (host_is_root) host_is_root[i] = both ? 1 : 0;
+    count += both;
+  }
+  return count;
+}
+
 size_t rfast_workspace_bytes(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, const rfast_problem* prob) {
   if (!sizes_ok(n, p, nnzR, nnzC, D, prob)) return 0;
   return layout(n, p, nnzR, nnzC, D, prob).total;

@@ -133,3 +133,28 @@ def test_null_context_calls_fail_cleanly():
     assert L.rfast_round(None, None, None, None, None, None, 0.1, None) == -1
     assert L.rfast_check(None) == -1
     L.rfast_destroy(None)
+
+
+def test_common_roots_of_named_topologies():
+    def roots(build, n):
+        r, c = build(n)
+        R, Cg = graphs.from_dense(r), graphs.from_dense(c)
+        return rf.rfast_common_roots(n, R.rowptr, R.col, Cg.rowptr, Cg.col).nonzero()[0].tolist()
+    assert roots(graphs.tree_pull_star_push, 9) == [0]
+    assert roots(graphs.line_tree, 6) == [0]
+    assert roots(graphs.directed_ring, 5) == [0, 1, 2, 3, 4]
+    assert roots(graphs.exponential, 8) == list(range(8))
+    # two roots: nodes 0 and 1 exchange both ways, node 2 only listens / only sends
+    r = np.array([[.5, .5, 0], [.5, .5, 0], [0, .5, .5]])
+    c = np.array([[.5, .25, .25], [.5, .5, .25], [0, .25, .5]])
+    R, Cg = graphs.from_dense(r), graphs.from_dense(c)
+    assert rf.rfast_common_roots(3, R.rowptr, R.col, Cg.rowptr, Cg.col).tolist() == [1, 1, 0]
+    # R rooted at 0 but C pushing away from 0: no common root
+    n = 4
+    rr, _ = graphs.line_tree(n)
+    cw = np.zeros((n, n))
+    cw[n - 1, n - 1] = 1.0
+    for j in range(n - 1):
+        cw[j, j] = cw[j + 1, j] = 0.5
+    R, Cg = graphs.from_dense(rr), graphs.from_dense(cw)
+    assert rf.rfast_common_roots(n, R.rowptr, R.col, Cg.rowptr, Cg.col).sum() == 0

@@ -122,7 +122,7 @@ typedef struct rfast_diag {
   double conservation_sq; /* || sum_i z_i + sum_e (rho_e latest - rho~_e) - sum_i g_i ||^2 (Lemma 3: 0)    */
   double gsum_sq;         /* || sum_i g_i ||^2 (scale for the line above)                                  */
   double xbar_gap_sq;     /* || xbar - x* ||^2, or -1 if no x* was given (optimality gap of Theorem 1)     */
-  double loss_at_xbar;    /* sum_i f_i(xbar) for the diagonal quadratic, else NaN                          */
+  double loss_at_xbar;    /* sum_i f_i(xbar): the training loss at the network average (full local data)   */
 } rfast_diag;
 
 /* Bytes of device workspace rfast_create needs for these sizes (pure function;

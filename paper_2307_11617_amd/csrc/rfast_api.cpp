@@ -35,7 +35,7 @@ struct Offsets {
   size_t t, t_hist, tau_r, tau_c, deliv_r, deliv_c, round_no, err;
   size_t n_active, active_list, plan_t, slot_r, slot_c, skip_c;
   size_t gen_active, gen_delay_r, gen_delay_c, gen_drop_r, gen_drop_c, gen_batch;
-  size_t resid, gscratch, diag;
+  size_t xbar, resid, gscratch, diag;
   size_t total;
 };
 
@@ -99,6 +99,7 @@ Offsets layout(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, cons
   o.gen_drop_r = L.take(eR);
   o.gen_drop_c = L.take(eC);
   o.gen_batch = L.take((size_t)n * (size_t)(prob->kind == RFAST_OBJ_DIAG_QUADRATIC ? 0 : prob->batch) * 4);
+  o.xbar = L.take(vec);
   o.resid = L.take(rfast_gemv_scratch_floats(n, prob) * 4);
   o.gscratch = L.take(rfast_softmax_scratch_bytes(n, prob));
   o.diag = L.take(64 * sizeof(double));
@@ -427,6 +428,7 @@ int rfast_create(rfast_ctx** out, int32_t n, int64_t p, const int32_t* R_rowptr,
   d.gen_active = (uint8_t*)(b + o.gen_active); d.gen_delay_r = (int32_t*)(b + o.gen_delay_r);
   d.gen_delay_c = (int32_t*)(b + o.gen_delay_c); d.gen_drop_r = (uint8_t*)(b + o.gen_drop_r);
   d.gen_drop_c = (uint8_t*)(b + o.gen_drop_c); d.gen_batch = (int32_t*)(b + o.gen_batch);
+  d.xbar = (float*)(b + o.xbar);
   d.resid = (float*)(b + o.resid); d.gscratch = (void*)(b + o.gscratch);
   c->d_diag = (double*)(b + o.diag);
   d.prob = *prob;
@@ -763,7 +765,8 @@ int rfast_diagnostics(rfast_ctx* c, const float* d_xstar, rfast_diag* host_out) 
   host_out->conservation_sq = h[2];
   host_out->gsum_sq = h[3];
   host_out->xbar_gap_sq = d_xstar ? h[4] : -1.0;
-  host_out->loss_at_xbar = c->d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC ? h[5] : NAN;
+  // sum_i f_i(xbar); the l2 term of the logistic objective is n * lambda/2 * ||xbar||^2
+  host_out->loss_at_xbar = h[5] + (c->d.prob.kind == RFAST_OBJ_LOGISTIC ? 0.5 * c->d.prob.lambda * c->d.n * h[6] : 0.0);
   return RFAST_OK;
 }
 

@@ -24,7 +24,7 @@ __global__ void rfast_diag_zero(double* out) {
 
 __global__ void __launch_bounds__(kThreads) rfast_diag_kernel(RfastDev s, const float* xstar, double* out) {
   const int64_t p = s.p;
-  double acc[6] = {0, 0, 0, 0, 0, 0};
+  double acc[7] = {0, 0, 0, 0, 0, 0, 0};
   for (int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x; k < p; k += (int64_t)gridDim.x * kThreads) {
     double xs = 0.0, zs = 0.0, gs = 0.0;
     for (int i = 0; i < s.n; ++i) {
@@ -36,6 +36,8 @@ __global__ void __launch_bounds__(kThreads) rfast_diag_kernel(RfastDev s, const 
       gs += s.g[(size_t)(s.t[i] & 1) * s.n * p + off];
     }
     const double xbar = xs / s.n;
+    s.xbar[k] = (float)xbar;
+    acc[6] += xbar * xbar;
     double loss = 0.0;
     for (int i = 0; i < s.n; ++i) {
       const size_t off = (size_t)i * p + k;
@@ -58,9 +60,30 @@ __global__ void __launch_bounds__(kThreads) rfast_diag_kernel(RfastDev s, const 
     acc[5] += loss;
   }
 #pragma unroll
-  for (int q = 0; q < 6; ++q) {
+  for (int q = 0; q < 7; ++q) {
     const double w = wave_sum(acc[q]);
     if ((threadIdx.x & 63) == 0) atomicAdd(&out[q], w);
+  }
+}
+
+// sum_i f_i(xbar) for least squares and logistic regression over each node's FULL
+// local data: one wavefront per row, a . xbar reduced across the 64 lanes.
+__global__ void __launch_bounds__(kThreads) rfast_loss_rows_kernel(RfastDev s, double* out) {
+  const int i = blockIdx.y;
+  const int row = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+  if (row >= s.prob.samples) return;
+  const int lane = threadIdx.x & 63;
+  const int64_t p = s.p;
+  const float* a = (const float*)s.prob.data0 + ((size_t)i * s.prob.samples + row) * p;
+  double acc = 0.0;
+  for (int64_t k = lane; k < p; k += 64) acc += (double)a[k] * (double)s.xbar[k];
+  acc = wave_sum(acc);
+  if (lane == 0) {
+    const double y = ((const float*)s.prob.data1)[(size_t)i * s.prob.samples + row];
+    double l;
+    if (s.prob.kind == RFAST_OBJ_LOGISTIC) l = (acc > 0 ? acc + log1p(exp(-acc)) : log1p(exp(acc))) - y * acc;
+    else l = 0.5 * (acc - y) * (acc - y);
+    atomicAdd(&out[5], l / s.prob.samples);
   }
 }
 
@@ -71,5 +94,13 @@ hipError_t rfast_launch_diag(rfast_ctx* c, const float* d_xstar, double* d_out) 
   int64_t blocks = (c->d.p + kThreads - 1) / kThreads;
   if (blocks > 4096) blocks = 4096;
   hipLaunchKernelGGL(rfast_diag_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, c->d, d_xstar, d_out);
+  const int kind = c->d.prob.kind;
+  if (kind == RFAST_OBJ_LEAST_SQUARES || kind == RFAST_OBJ_LOGISTIC)
+    hipLaunchKernelGGL(rfast_loss_rows_kernel, dim3((c->d.prob.samples + 3) / 4, c->d.n), dim3(kThreads), 0, c->stream, c->d,
+                       d_out);
+  if (kind == RFAST_OBJ_SOFTMAX_BF16) {
+    const hipError_t e = rfast_softmax_loss(c, d_out + 5);
+    if (e != hipSuccess) return e;
+  }
   return hipGetLastError();
 }

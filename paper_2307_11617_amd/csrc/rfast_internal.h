@@ -70,6 +70,7 @@ struct RfastDev {
   uint8_t* gen_drop_r;    // [eR]
   uint8_t* gen_drop_c;    // [eC]
   int32_t* gen_batch;     // [n][batch]
+  float* xbar;            // [p] node average, written by the diagnostics kernel
   // gradient scratch
   float* resid;           // [n][rows] residuals of the GEMV pair / unused
   void* gscratch;         // softmax: bf16 W copy and E matrix
@@ -110,4 +111,5 @@ hipError_t rfast_launch_sync(rfast_ctx* c, int phase, float gamma, int parity);
 hipError_t rfast_launch_init_grad(rfast_ctx* c, const int32_t* batch_idx0);
 hipError_t rfast_launch_gradient(rfast_ctx* c, const int32_t* batch_idx);
 hipError_t rfast_launch_diag(rfast_ctx* c, const float* d_xstar, double* d_out);
+hipError_t rfast_softmax_loss(rfast_ctx* c, double* d_out);  // adds sum_i f_i(xbar) to *d_out
 size_t rfast_grad_scratch_bytes(int32_t n, int64_t p, const rfast_problem* prob);

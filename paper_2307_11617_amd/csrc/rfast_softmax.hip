@@ -83,13 +83,14 @@ __device__ __host__ inline Scratch scratch_of(const RfastDev& s, int B) {
 // grid (d/64, nodes).  LDS tile T[f][k] (row stride K+4: the transposed reads of
 // phase 2 then fall on distinct banks); phase 2 gathers 8 features of one class
 // and writes them as one 16-byte unit, lanes along k, fully coalesced.
-__global__ void __launch_bounds__(256) rfast_softmax_prep(RfastDev s, int B, bool init) {
+// wsrc != NULL: convert that matrix (the node average, for the loss) into node slot 0.
+__global__ void __launch_bounds__(256) rfast_softmax_prep(RfastDev s, int B, bool init, const float* wsrc) {
   extern __shared__ u16 lds[];  // [64][K+4]
   const int i = pick_node(s, init, blockIdx.y);
   if (i < 0) return;
   const int d = s.prob.d, K = s.prob.K, TS = K + 4;
   const int f0 = blockIdx.x * kTile;
-  const float* W = s.x + (size_t)i * s.p;
+  const float* W = wsrc ? wsrc : s.x + (size_t)i * s.p;
   for (int q = threadIdx.x; q < kTile * K / 4; q += blockDim.x) {
     const int f = q / (K / 4), k4 = (q % (K / 4)) * 4;
     const float4 w = *reinterpret_cast<const float4*>(W + (size_t)(f0 + f) * K + k4);
@@ -179,8 +180,11 @@ __device__ __forceinline__ void fwd_multiply(f32x16 (&acc)[2], const u16* Xs, in
   }
 }
 
-template <int NW>
-__global__ void __launch_bounds__(64 * NW) rfast_softmax_forward(RfastDev s, const int32_t* batch_idx, int B, bool init) {
+// LOSS: instead of E, accumulate the mean cross-entropy of rows b0.. of EVERY node's
+// pool under the W held in node slot 0 (the node average) into *loss_out (B = samples).
+template <int NW, bool LOSS>
+__global__ void __launch_bounds__(64 * NW) rfast_softmax_forward(RfastDev s, const int32_t* batch_idx, int B, bool init,
+                                                                 double* loss_out) {
   extern __shared__ u16 lds[];
   int slot, rb;
   xcd_decode(B / kTile, &slot, &rb);
@@ -196,7 +200,7 @@ __global__ void __launch_bounds__(64 * NW) rfast_softmax_forward(RfastDev s, con
   const u16* pool = (const u16*)s.prob.data0 + (size_t)i * s.prob.samples * d;
   const int32_t* labels = (const int32_t*)s.prob.data1 + (size_t)i * s.prob.samples;
   const Scratch sc = scratch_of(s, B);
-  const u16* wt = sc.wt + (size_t)i * K * d;
+  const u16* wt = sc.wt + (LOSS ? (size_t)0 : (size_t)i * K * d);
   for (int r = tid; r < kTile; r += 64 * NW) {
     rows[r] = sample_row(s, batch_idx, i, b0 + r, B);
     labs[r] = labels[rows[r]];
@@ -246,11 +250,13 @@ __global__ void __launch_bounds__(64 * NW) rfast_softmax_forward(RfastDev s, con
   __syncthreads();
   // row softmax: each wave takes rows wave, wave + NW, ...; lanes stride over classes
   const float invB = 1.0f / (float)B;
+  double wave_loss = 0.0;
   for (int r = wave; r < kTile; r += NW) {
     float m = -INFINITY;
     for (int k = lane; k < K; k += 64) m = fmaxf(m, L[r * ldl + k]);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+    const float logit_label = L[r * ldl + labs[r]];
     float sum = 0.f;
     for (int k = lane; k < K; k += 64) {
       const float e = expf(L[r * ldl + k] - m);
@@ -259,11 +265,19 @@ __global__ void __launch_bounds__(64 * NW) rfast_softmax_forward(RfastDev s, con
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+    if (LOSS) {
+      wave_loss += (double)logf(sum) + (double)m - (double)logit_label;  // -log softmax[label]
+      continue;
+    }
     const float inv = 1.0f / sum;
     for (int k = lane; k < K; k += 64) {
       const float pr = L[r * ldl + k] * inv - (k == labs[r] ? 1.0f : 0.0f);
       L[r * ldl + k] = pr * invB;
     }
+  }
+  if (LOSS) {
+    if (lane == 0) atomicAdd(loss_out, wave_loss / (double)B);
+    return;
   }
   __syncthreads();
   // Et[k][b0 .. b0+64): 8 consecutive rows per 16-byte store
@@ -410,25 +424,52 @@ hipError_t rfast_softmax_gradient(rfast_ctx* c, const int32_t* batch_idx, bool i
   const size_t lds_fwd = lds_fwd_stage > lds_logits ? lds_fwd_stage : lds_logits;
   const size_t lds_bwd = 2 * (size_t)(kTile + K) * kLd * sizeof(u16);
   const unsigned n8 = (unsigned)((d.n + 7) / 8 * 8);  // node slots, padded so that ids decode per XCD
-  hipLaunchKernelGGL(rfast_softmax_prep, dim3(d.prob.d / kTile, d.n), dim3(256), lds_prep, c->stream, d, B, init);
+  hipLaunchKernelGGL(rfast_softmax_prep, dim3(d.prob.d / kTile, d.n), dim3(256), lds_prep, c->stream, d, B, init, (const float*)nullptr);
   const dim3 fgrid(n8 * (unsigned)(B / kTile)), bgrid(n8 * (unsigned)(d.prob.d / kTile));
   switch (NW) {
     case 1:
-      hipLaunchKernelGGL(rfast_softmax_forward<1>, fgrid, dim3(threads), lds_fwd, c->stream, d, bi, B, init);
+      hipLaunchKernelGGL((rfast_softmax_forward<1, false>), fgrid, dim3(threads), lds_fwd, c->stream, d, bi, B, init, (double*)nullptr);
       hipLaunchKernelGGL(rfast_softmax_backward<1>, bgrid, dim3(threads), lds_bwd, c->stream, d, bi, B, init);
       break;
     case 2:
-      hipLaunchKernelGGL(rfast_softmax_forward<2>, fgrid, dim3(threads), lds_fwd, c->stream, d, bi, B, init);
+      hipLaunchKernelGGL((rfast_softmax_forward<2, false>), fgrid, dim3(threads), lds_fwd, c->stream, d, bi, B, init, (double*)nullptr);
       hipLaunchKernelGGL(rfast_softmax_backward<2>, bgrid, dim3(threads), lds_bwd, c->stream, d, bi, B, init);
       break;
     case 3:
-      hipLaunchKernelGGL(rfast_softmax_forward<3>, fgrid, dim3(threads), lds_fwd, c->stream, d, bi, B, init);
+      hipLaunchKernelGGL((rfast_softmax_forward<3, false>), fgrid, dim3(threads), lds_fwd, c->stream, d, bi, B, init, (double*)nullptr);
       hipLaunchKernelGGL(rfast_softmax_backward<3>, bgrid, dim3(threads), lds_bwd, c->stream, d, bi, B, init);
       break;
     default:
-      hipLaunchKernelGGL(rfast_softmax_forward<4>, fgrid, dim3(threads), lds_fwd, c->stream, d, bi, B, init);
+      hipLaunchKernelGGL((rfast_softmax_forward<4, false>), fgrid, dim3(threads), lds_fwd, c->stream, d, bi, B, init, (double*)nullptr);
       hipLaunchKernelGGL(rfast_softmax_backward<4>, bgrid, dim3(threads), lds_bwd, c->stream, d, bi, B, init);
       break;
+  }
+  return hipGetLastError();
+}
+
+// sum_i f_i(xbar): mean cross-entropy of every node's whole pool under W = bf16(xbar).
+// Needs the pool size to be a multiple of the 64-row tile; otherwise the loss is left at NaN.
+hipError_t rfast_softmax_loss(rfast_ctx* c, double* d_out) {
+  const RfastDev& d = c->d;
+  const int K = d.prob.K, NW = K / 32, S = d.prob.samples;
+  if (!rfast_softmax_shape_ok(&d.prob) || S % kTile != 0) {
+    static const double kNan = __builtin_nan("");
+    return hipMemcpyAsync(d_out, &kNan, sizeof(double), hipMemcpyHostToDevice, c->stream);
+  }
+  const unsigned threads = 64u * (unsigned)NW;
+  const size_t lds_prep = (size_t)kTile * (K + 4) * sizeof(u16);
+  const size_t lds_stage = 2 * (size_t)(kTile * kLd + 8 * (K * 8 + 8)) * sizeof(u16);
+  const size_t lds_logits = (size_t)kTile * (K + 1) * sizeof(float);
+  const size_t lds_fwd = lds_stage > lds_logits ? lds_stage : lds_logits;
+  hipLaunchKernelGGL(rfast_softmax_prep, dim3(d.prob.d / kTile, 1), dim3(256), lds_prep, c->stream, d, S, true,
+                     (const float*)d.xbar);
+  const unsigned n8 = (unsigned)((d.n + 7) / 8 * 8);
+  const dim3 grid(n8 * (unsigned)(S / kTile));
+  switch (NW) {
+    case 1: hipLaunchKernelGGL((rfast_softmax_forward<1, true>), grid, dim3(threads), lds_fwd, c->stream, d, (const int32_t*)nullptr, S, true, d_out); break;
+    case 2: hipLaunchKernelGGL((rfast_softmax_forward<2, true>), grid, dim3(threads), lds_fwd, c->stream, d, (const int32_t*)nullptr, S, true, d_out); break;
+    case 3: hipLaunchKernelGGL((rfast_softmax_forward<3, true>), grid, dim3(threads), lds_fwd, c->stream, d, (const int32_t*)nullptr, S, true, d_out); break;
+    default: hipLaunchKernelGGL((rfast_softmax_forward<4, true>), grid, dim3(threads), lds_fwd, c->stream, d, (const int32_t*)nullptr, S, true, d_out); break;
   }
   return hipGetLastError();
 }

@@ -32,6 +32,23 @@ def test_diagnostics_match_oracle():
     assert gpu.diagnostics(None)["xbar_gap_sq"] == -1.0
 
 
+@pytest.mark.parametrize("which", ["least_squares", "logistic", "softmax"])
+def test_training_loss_at_the_average_matches_oracle(which):
+    """sum_i f_i(xbar) over every node's full local data, for the objectives with per-sample losses."""
+    if which == "least_squares":
+        w, rounds, tol = configs.config0(rounds=200), 200, 1e-5
+    elif which == "logistic":
+        w, rounds, tol = configs.config1(p=260, samples=96, batch=16, rounds=150), 150, 1e-5
+    else:
+        w, rounds, tol = configs.config4(d=128, K=64, samples=192, batch=64, rounds=100), 100, 2e-3
+    worst, orc, gpu = harness.run_parity(w, rounds, every=50)
+    ref = orc.diagnostics()
+    got = gpu.diagnostics()
+    assert abs(got["loss_at_xbar"] - ref["loss_at_xbar"]) <= tol * abs(ref["loss_at_xbar"]), (got, ref)
+    for key in ("consensus_sq", "z_sq", "gsum_sq"):
+        assert abs(got[key] - ref[key]) <= 1e-3 * abs(ref[key]) + 1e-12, (key, got[key], ref[key])
+
+
 def test_single_rounds_equal_stacked_run():
     w = configs.config0(rounds=40)
     a, b = harness.make_gpu(w), harness.make_gpu(w)

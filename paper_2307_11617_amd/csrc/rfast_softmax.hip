@@ -302,6 +302,9 @@ __global__ void __launch_bounds__(64 * NW) rfast_softmax_forward(RfastDev s, con
 // rows runs in stages of 64 rows through two LDS buffers; the next stage's global
 // loads are issued before the current stage is multiplied.  The X tile is
 // transposed on its way into LDS (Xt[f][b]) so that both operands are contiguous in b.
+// X tile of the backward pass: 64 sampled rows x 64 features = 512 chunks of 16 bytes.
+// Chunk q belongs to row q % 64 (so the lanes of a wavefront hold 64 different rows of
+// the same 8 features) and feature group q / 64.
 template <int NW>
 __device__ __forceinline__ void bwd_load(u32x4 (&x)[FwdShape<NW>::kXc], u32x4 (&e)[4], const u16* pool, const int* rows,
                                          const u16* et, int d, int B, int f0, int b0, int tid) {
@@ -310,7 +313,7 @@ __device__ __forceinline__ void bwd_load(u32x4 (&x)[FwdShape<NW>::kXc], u32x4 (&
   for (int c = 0; c < FwdShape<NW>::kXc; ++c) {
     const int q = tid + c * T;
     if ((kTile * kTile / 8) % T == 0 || q < kTile * kTile / 8)
-      x[c] = *reinterpret_cast<const u32x4*>(pool + (size_t)rows[q / (kTile / 8)] * d + f0 + (q % (kTile / 8)) * 8);
+      x[c] = *reinterpret_cast<const u32x4*>(pool + (size_t)rows[q & 63] * d + f0 + (q >> 6) * 8);
   }
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
@@ -319,20 +322,32 @@ __device__ __forceinline__ void bwd_load(u32x4 (&x)[FwdShape<NW>::kXc], u32x4 (&
   }
 }
 
+// Transposed store Xt[f][b].  Neighbouring lanes hold neighbouring rows b, so an even lane
+// and its odd partner swap halves: the even lane then owns features 0-3 of both rows, the
+// odd lane features 4-7, and each writes four 32-bit words (two rows of one feature) that
+// fall on consecutive LDS banks across the wavefront.
 template <int NW>
 __device__ __forceinline__ void bwd_store(const u32x4 (&x)[FwdShape<NW>::kXc], const u32x4 (&e)[4], u16* Xt, u16* Es,
                                           int tid) {
   constexpr int T = FwdShape<NW>::kThreads;
+  const bool odd = tid & 1;
 #pragma unroll
   for (int c = 0; c < FwdShape<NW>::kXc; ++c) {
     const int q = tid + c * T;
+    // every lane of the wavefront takes part in the exchange (q < 512 is wave-uniform: 512 % 64 == 0)
     if ((kTile * kTile / 8) % T == 0 || q < kTile * kTile / 8) {
-      const int r = q / (kTile / 8), f = (q % (kTile / 8)) * 8;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        Xt[(f + 2 * j) * kLd + r] = (u16)(x[c][j] & 0xFFFFu);
-        Xt[(f + 2 * j + 1) * kLd + r] = (u16)(x[c][j] >> 16);
-      }
+      const int r = q & 63, f = (q >> 6) * 8;
+      const uint32_t mine0 = odd ? x[c][2] : x[c][0], mine1 = odd ? x[c][3] : x[c][1];
+      const uint32_t send0 = odd ? x[c][0] : x[c][2], send1 = odd ? x[c][1] : x[c][3];
+      const uint32_t got0 = __shfl_xor(send0, 1, 64), got1 = __shfl_xor(send1, 1, 64);
+      // rows (r & ~1, r | 1): the even row goes to the low half of the word
+      const uint32_t lo0 = odd ? got0 : mine0, hi0 = odd ? mine0 : got0;
+      const uint32_t lo1 = odd ? got1 : mine1, hi1 = odd ? mine1 : got1;
+      const int fb = f + (odd ? 4 : 0), rb = r & ~1;
+      *reinterpret_cast<uint32_t*>(&Xt[(fb + 0) * kLd + rb]) = (lo0 & 0xFFFFu) | (hi0 << 16);
+      *reinterpret_cast<uint32_t*>(&Xt[(fb + 1) * kLd + rb]) = (lo0 >> 16) | (hi0 & 0xFFFF0000u);
+      *reinterpret_cast<uint32_t*>(&Xt[(fb + 2) * kLd + rb]) = (lo1 & 0xFFFFu) | (hi1 << 16);
+      *reinterpret_cast<uint32_t*>(&Xt[(fb + 3) * kLd + rb]) = (lo1 >> 16) | (hi1 & 0xFFFF0000u);
     }
   }
 #pragma unroll

@@ -248,36 +248,47 @@ __global__ void __launch_bounds__(64 * NW) rfast_softmax_forward(RfastDev s, con
       L[row * ldl + wave * 32 + (lane & 31)] = acc[rt][v];
     }
   __syncthreads();
-  // row softmax: each wave takes rows wave, wave + NW, ...; lanes stride over classes
+  // Row softmax, all 64 rows at once: lane = row, wave w = classes 32w .. 32w+31 (the
+  // odd row stride K+1 keeps the 64 lanes on distinct LDS banks).  The per-row maximum
+  // and sum cross the NW waves through a few words of LDS instead of 12 dependent
+  // wavefront shuffles per row, which cost more than the whole contraction.
+  __shared__ float red[2][4][kTile];
   const float invB = 1.0f / (float)B;
-  double wave_loss = 0.0;
-  for (int r = wave; r < kTile; r += NW) {
-    float m = -INFINITY;
-    for (int k = lane; k < K; k += 64) m = fmaxf(m, L[r * ldl + k]);
+  float* Lr = L + lane * ldl + wave * 32;
+  const float logit_label = L[lane * ldl + labs[lane]];
+  float m = -INFINITY;
+#pragma unroll 8
+  for (int j = 0; j < 32; ++j) m = fmaxf(m, Lr[j]);
+  red[0][wave][lane] = m;
+  __syncthreads();  // every logit_label is read before any logit is overwritten below
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
-    const float logit_label = L[r * ldl + labs[r]];
-    float sum = 0.f;
-    for (int k = lane; k < K; k += 64) {
-      const float e = expf(L[r * ldl + k] - m);
-      L[r * ldl + k] = e;
-      sum += e;
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
-    if (LOSS) {
-      wave_loss += (double)logf(sum) + (double)m - (double)logit_label;  // -log softmax[label]
-      continue;
-    }
-    const float inv = 1.0f / sum;
-    for (int k = lane; k < K; k += 64) {
-      const float pr = L[r * ldl + k] * inv - (k == labs[r] ? 1.0f : 0.0f);
-      L[r * ldl + k] = pr * invB;
-    }
+  for (int w2 = 0; w2 < NW; ++w2) m = fmaxf(m, red[0][w2][lane]);
+  float sum = 0.f;
+#pragma unroll 8
+  for (int j = 0; j < 32; ++j) {
+    const float e = __expf(Lr[j] - m);
+    Lr[j] = e;
+    sum += e;
   }
+  red[1][wave][lane] = sum;
+  __syncthreads();
+  sum = 0.f;
+#pragma unroll
+  for (int w2 = 0; w2 < NW; ++w2) sum += red[1][w2][lane];
   if (LOSS) {
-    if (lane == 0) atomicAdd(loss_out, wave_loss / (double)B);
+    if (wave == 0) {
+      double row_loss = (double)logf(sum) + (double)m - (double)logit_label;  // -log softmax[label]
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) row_loss += __shfl_xor(row_loss, o, 64);
+      if (lane == 0) atomicAdd(loss_out, row_loss / (double)B);
+    }
     return;
+  }
+  {
+    const float inv = 1.0f / sum;
+    const int lab = labs[lane] - wave * 32;
+#pragma unroll 8
+    for (int j = 0; j < 32; ++j) Lr[j] = (Lr[j] * inv - (j == lab ? 1.0f : 0.0f)) * invB;
   }
   __syncthreads();
   // Et[k][b0 .. b0+64): 8 consecutive rows per 16-byte store

@@ -30,14 +30,34 @@ Readings taken where the paper is silent (each also listed in the design notes):
    is never visible on that edge; after burst-1 consecutive losses on an edge
    the next version is delivered regardless (Assumption 3 excludes links that
    fail forever), so staleness in versions is at most D = d_max + burst - 1.
+
+Optimizer variant (labelled: the paper's large-scale experiment lists momentum,
+weight decay and a step-decayed learning rate among its hyper-parameters but
+does not say where they enter Algorithm 1).  Reading taken here:
+ * weight decay lambda is part of the sampled gradient, g = grad f_i(x; zeta) +
+   lambda * x, at initialisation and in S2b, so it is tracked like any gradient
+   (the objective becomes f_i + lambda/2 ||x||^2);
+ * momentum beta is a heavy-ball buffer on the tracked direction in S1:
+   m_i <- beta m_i + z_i (m_i^0 = 0), v = x_i - gamma m_i; only the node that
+   is activated touches its buffer.  beta = 0 is the paper's S1;
+ * the step size of round r is gamma * factor^(r div step_rounds), computed by
+   the caller (step_gamma below).
+With one node and no edges the recursion is textbook SGD with momentum and
+weight decay, which is what the tests pin it to.
 """
 from __future__ import annotations
 
 import numpy as np
 
 
+def step_gamma(gamma0, factor, step_rounds, r):
+    """Step-decayed learning rate of round r (large-scale experiment, hyper-parameter ii)."""
+    return gamma0 * factor ** (r // step_rounds) if step_rounds > 0 else gamma0
+
+
 class RFastOracle:
-    def __init__(self, n, p, R, C, D, burst, objective, x0=None, batch0=None, prune=True):
+    def __init__(self, n, p, R, C, D, burst, objective, x0=None, batch0=None, prune=True,
+                 momentum=0.0, weight_decay=0.0):
         """R, C: objects with rowptr, col, w (CSR, row = receiver, diagonal included).
         objective: object with grad(i, x, version, batch_rows) -> float64 [p]."""
         self.n, self.p, self.D, self.burst = int(n), int(p), int(D), int(burst)
@@ -45,6 +65,7 @@ class RFastOracle:
         self.d_max = self.D - (self.burst - 1)
         self.obj = objective
         self.prune = prune
+        self.momentum, self.weight_decay = float(momentum), float(weight_decay)
         self.r_self, self.r_in = self._split(R)      # r_in[i] = [(edge id, j, w_ij)]
         self.c_self, self.c_in = self._split(C)
         self.edges_R = [(i, j) for i in range(n) for (_, j, _) in self.r_in[i]]
@@ -61,8 +82,9 @@ class RFastOracle:
         self.x = np.zeros((n, p)) if x0 is None else np.array(x0, dtype=np.float64).reshape(n, p)
         self.t = np.zeros(n, dtype=np.int64)
         self.g = np.stack([
-            self.obj.grad(i, self.x[i], 0, None if batch0 is None else batch0[i]) for i in range(n)])
+            self._sample(i, self.x[i], 0, None if batch0 is None else batch0[i]) for i in range(n)])
         self.z = self.g.copy()
+        self.m = np.zeros((n, p))
         self.v = [{0: np.zeros(p)} for _ in range(n)]
         self.rho = [{0: np.zeros(p)} for _ in self.edges_C]
         self.rho_tilde = [np.zeros(p) for _ in self.edges_C]
@@ -73,6 +95,10 @@ class RFastOracle:
         self.t_start = [self.t.copy()]   # t_start[s] = counters at the start of round s
         self.round_no = 0
         self.last_z_half = np.zeros((n, p))
+
+    def _sample(self, i, x, version, batch):
+        g = self.obj.grad(i, x, version, batch)
+        return g + self.weight_decay * x if self.weight_decay != 0.0 else g
 
     @staticmethod
     def _split(G):
@@ -96,14 +122,18 @@ class RFastOracle:
         stamp_v[e] of v on each R in-edge e and version stamp_rho[e] of rho on
         each C in-edge e.  lost_R / lost_C: out-edge ids whose new packet is lost."""
         t = int(self.t[i])
-        # S1: local descent
-        v_new = self.x[i] - gamma * self.z[i]
+        # S1: local descent (variant: along the heavy-ball buffer of the tracked direction)
+        if self.momentum != 0.0:
+            self.m[i] = self.momentum * self.m[i] + self.z[i]
+            v_new = self.x[i] - gamma * self.m[i]
+        else:
+            v_new = self.x[i] - gamma * self.z[i]
         # S2a: pull / mix over R
         x_new = self.r_self[i] * v_new
         for (e, j, w) in self.r_in[i]:
             x_new = x_new + w * self.v[j][int(stamp_v[e])]
         # S2b: tracker sum over C with the new and the stored old gradient sample
-        g_new = self.obj.grad(i, x_new, t + 1, batch)
+        g_new = self._sample(i, x_new, t + 1, batch)
         z_half = self.z[i].copy()
         consumed = {}
         for (e, j, w) in self.c_in[i]:

@@ -30,7 +30,7 @@ MUTANTS = {
     "loss_ignored": ("return all(not hist.get(t - k, True) for k in range(1, self.burst))", "return True"),
     "stamps_not_monotone": ("sr[e] = max(int(self.tau_rho[e]), cand)", "sr[e] = cand"),
     "forced_delivery_missing": ("return all(not hist.get(t - k, True) for k in range(1, self.burst))", "return False"),
-    "gradient_sample_stamp": ("g_new = self.obj.grad(i, x_new, t + 1, batch)", "g_new = self.obj.grad(i, x_new, t, batch)"),
+    "gradient_sample_stamp": ("g_new = self._sample(i, x_new, t + 1, batch)", "g_new = self._sample(i, x_new, t, batch)"),
 }
 
 PINS = [
@@ -72,3 +72,38 @@ def test_unmutated_source_passes_the_same_pins(monkeypatch):
     monkeypatch.setattr(pins, "RFastOracle", mod.RFastOracle)
     for pin in PINS[:5]:
         pin()
+
+
+# ------------------------------------------------ the labelled optimizer variant
+import test_oracle_optimizer as opt_pins
+
+OPT_MUTANTS = {
+    "buffer_takes_gradient": ("self.m[i] = self.momentum * self.m[i] + self.z[i]", "self.m[i] = self.momentum * self.m[i] + self.g[i]"),
+    "buffer_not_damped": ("self.m[i] = self.momentum * self.m[i] + self.z[i]", "self.m[i] = self.m[i] + self.z[i]"),
+    "descent_ignores_buffer": ("v_new = self.x[i] - gamma * self.m[i]", "v_new = self.x[i] - gamma * self.z[i]"),
+    "decay_missing_at_init": ("self._sample(i, self.x[i], 0, None if batch0 is None else batch0[i])",
+                              "self.obj.grad(i, self.x[i], 0, None if batch0 is None else batch0[i])"),
+    "decay_at_old_point": ("g_new = self._sample(i, x_new, t + 1, batch)",
+                           "g_new = self.obj.grad(i, x_new, t + 1, batch) + self.weight_decay * self.x[i]"),
+    "decay_sign": ("return g + self.weight_decay * x if", "return g - self.weight_decay * x if"),
+}
+
+OPT_PINS = [
+    lambda: opt_pins.test_one_node_is_textbook_sgd(0.9, 1e-2),
+    opt_pins.test_momentum_first_steps_by_hand,
+    opt_pins.test_tracking_identity_and_untouched_buffers,
+]
+
+
+@pytest.mark.parametrize("name", sorted(OPT_MUTANTS))
+def test_optimizer_pins_catch_planted_mistake(name, monkeypatch):
+    old, new = OPT_MUTANTS[name]
+    monkeypatch.setattr(opt_pins, "RFastOracle", _mutant_class(old, new))
+    caught = False
+    for pin in OPT_PINS:
+        try:
+            pin()
+        except AssertionError:
+            caught = True
+            break
+    assert caught, f"no pin noticed the planted mistake '{name}'"

@@ -90,6 +90,9 @@ def main():
     ap.add_argument("--generated", action="store_true",
                     help="generate the schedule on the device (rfast_run_generated) instead of uploading it")
     ap.add_argument("--graphs", action="store_true", help="with --generated: replay HIP graphs of 16 rounds")
+    ap.add_argument("--momentum", type=float, default=0.0,
+                    help="optimizer variant (not the headline workload): heavy-ball buffer, +2 words per coordinate")
+    ap.add_argument("--weight-decay", type=float, default=0.0, help="optimizer variant: weight decay inside the gradient")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only a plain 1 GiB device copy (10 launches): calibrates HBM byte counters")
     args = ap.parse_args()
@@ -116,6 +119,9 @@ def main():
     gen_s = time.perf_counter() - t_gen
     K, W = args.steps, args.warmup
     gpu = harness.make_gpu(w)
+    variant = args.momentum != 0.0 or args.weight_decay != 0.0
+    if variant:
+        gpu.set_optimizer(args.momentum, args.weight_decay)
     gpu.init(None, w.sched.initial_batch())
     st, dev = harness.upload_chunk(gpu, w, 0, W + 2 * K)
     sl = lambda name, a, b: None if dev[name] is None else dev[name][a:b].contiguous()
@@ -163,6 +169,9 @@ def main():
         dI = (w.C.dense() != 0).sum(axis=1) - 1
         words = 3 + (1 + dR) + (1 + dI) + 1 + (2 + 3 if w.objective == "diag_quadratic" else 1 + 2)
         bytes_prof = bytes_layout = float(words.sum() * 4.0 * w.p * K)
+    if args.momentum != 0.0:   # read and write of the buffer m_i
+        extra = 8.0 * w.p * (w.n * K if args.sync else float(act_prof.sum()))
+        bytes_prof, bytes_layout = bytes_prof + extra, bytes_layout + extra
     launches = max(n_state, 1)
     avg_ms = ms_state / launches
     achieved = bytes_prof / (ms_state * 1e-3) / 1e9 if ms_state > 0 else 0.0
@@ -175,7 +184,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name + ("/synchronous-push-pull" if args.sync else "") +
-                               ("/generated-schedule" if args.generated else "") + ("/hip-graphs" if args.graphs else ""), "n": w.n, "p": w.p, "D": w.D, "ring_slots": w.D + 2, "objective": w.objective,
+                               ("/generated-schedule" if args.generated else "") + ("/hip-graphs" if args.graphs else "") +
+                               (f"/momentum={args.momentum},weight_decay={args.weight_decay}" if variant else ""), "n": w.n, "p": w.p, "D": w.D, "ring_slots": w.D + 2, "objective": w.objective,
                    "mean_active_per_round": updates / K, "gamma": w.gamma},
         "roofline": {"bound": "hbm", "kernel": ("rfast_sync_descent+step" if args.sync else "rfast_state_kernel" + ("<FUSED>" if w.objective == "diag_quadratic" else "<MIX>+<TRACK>")), "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
@@ -184,7 +194,7 @@ def main():
                      "layout_bytes_per_launch": bytes_layout / launches,
                      "achieved_layout": achieved * bytes_layout / bytes_prof if bytes_prof else 0.0,
                      "frac_layout": achieved * bytes_layout / bytes_prof / HBM_PEAK_GBS if bytes_prof else 0.0,
-                     "traffic": measured_traffic(w.name) if not (args.p or args.sync) else None},
+                     "traffic": measured_traffic(w.name) if not (args.p or args.sync or variant) else None},
         "kernel_ms": {"state": ms_state, "gradient": ms_grad, "resolver": ms_res,
                       "launches": {"state": n_state, "gradient": n_grad, "resolver": n_res}},
         "host_data_generation_s": gen_s,

@@ -113,7 +113,8 @@ typedef enum rfast_field {
   RFAST_SCHED_DELAY_C = 18, /* int32 [nnzC_off] */
   RFAST_SCHED_DROP_R = 19,  /* uint8 [nnzR_off] */
   RFAST_SCHED_DROP_C = 20,  /* uint8 [nnzC_off] */
-  RFAST_SCHED_BATCH = 21    /* int32 [n][batch] */
+  RFAST_SCHED_BATCH = 21,   /* int32 [n][batch] */
+  RFAST_MOMENTUM = 22       /* fp32 [n][p]  heavy-ball buffers m_i (only after rfast_set_optimizer gave one) */
 } rfast_field;
 
 typedef struct rfast_diag {
@@ -122,7 +123,8 @@ typedef struct rfast_diag {
   double conservation_sq; /* || sum_i z_i + sum_e (rho_e latest - rho~_e) - sum_i g_i ||^2 (Lemma 3: 0)    */
   double gsum_sq;         /* || sum_i g_i ||^2 (scale for the line above)                                  */
   double xbar_gap_sq;     /* || xbar - x* ||^2, or -1 if no x* was given (optimality gap of Theorem 1)     */
-  double loss_at_xbar;    /* sum_i f_i(xbar): the training loss at the network average (full local data)   */
+  double loss_at_xbar;    /* sum_i f_i(xbar): the training loss at the network average (full local data),
+                             plus n * weight_decay/2 ||xbar||^2 under rfast_set_optimizer                   */
 } rfast_diag;
 
 /* Bytes of device workspace rfast_create needs for these sizes (pure function;
@@ -229,6 +231,30 @@ int rfast_rebase(rfast_ctx* ctx);
  * sparse graph (2(D+2) + 2 dO + 1 words per coordinate per sender). */
 int rfast_set_rebase_interval(rfast_ctx* ctx, int32_t rounds);
 
+/* Optimizer variant.  The large-scale experiment of the paper (Section
+ * "Large-scale image classification", hyper-parameters ii-iv) trains with
+ * momentum 0.9, weight decay 1e-4 and a learning rate divided by 10 every 30
+ * epochs, without saying where these enter Algorithm 1.  The reading built here:
+ *   weight decay   g = grad f_i(x; zeta) + weight_decay * x wherever a gradient is
+ *                  sampled (initialisation and S2b), so it is tracked like the rest
+ *                  of the gradient; the objective becomes f_i + weight_decay/2 ||x||^2;
+ *   momentum       S1 becomes m_i <- momentum * m_i + z_i, v = x_i - gamma * m_i
+ *                  (m_i = 0 at rfast_init; only an activated node touches its
+ *                  buffer); momentum = 0 is S1 as printed.  Costs 2 more words per
+ *                  coordinate and update.  The same holds for rfast_sync_round.
+ * With one node this is SGD with momentum and weight decay as in the textbooks.
+ * d_momentum: device fp32 [n][p], 16-byte aligned, owned by the caller, must
+ * outlive the context; required iff momentum != 0.  momentum in [0, 1),
+ * weight_decay >= 0 (RFAST_ERANGE otherwise).  Because the stored gradients and
+ * the buffers change meaning, rfast_init must follow before the next round
+ * (rounds return RFAST_EINVAL until it has). */
+int rfast_set_optimizer(rfast_ctx* ctx, float momentum, float weight_decay, float* d_momentum);
+/* Step-decayed learning rate (same experiment, hyper-parameter ii): round number r
+ * (RFAST_ROUND, counted from rfast_init) runs with gamma * factor^(r div step_rounds),
+ * where gamma is what the round call passes.  step_rounds = 0 (default) switches it off.
+ * factor must be finite and > 0. */
+int rfast_set_gamma_schedule(rfast_ctx* ctx, int32_t step_rounds, float factor);
+
 /* Waits for the stream, then returns RFAST_OK or the first error a round
  * recorded on the device (RFAST_ERANGE) with its round and edge in the text. */
 int rfast_check(rfast_ctx* ctx);
@@ -239,8 +265,8 @@ int rfast_read_state(rfast_ctx* ctx, int32_t field, void* host_dst, size_t bytes
 
 /* Waits for the stream and overwrites one field from HOST memory: the inverse
  * of rfast_read_state, for checkpoint / resume.  Restoring X, Z, G, V_RING,
- * SIGMA_RING, RHO_TILDE, T_NODE, TAU_R, TAU_C, DELIV_R, DELIV_C, T_HIST and
- * ROUND into a context created with the same arguments reproduces the run bit
+ * SIGMA_RING, RHO_TILDE, T_NODE, TAU_R, TAU_C, DELIV_R, DELIV_C, T_HIST,
+ * ROUND (and MOMENTUM when used) into a context created with the same arguments reproduces the run bit
  * for bit.  RHO_RING (derived), SLOT_R and SLOT_C (per-round plan) cannot be
  * written (RFAST_EINVAL). */
 int rfast_write_state(rfast_ctx* ctx, int32_t field, const void* host_src, size_t bytes);

@@ -233,7 +233,9 @@ class RFastOracle:
             out["xbar_gap_sq"] = float(((xbar - x_star) ** 2).sum())
             out["x_gap_sq"] = float(((self.x - x_star) ** 2).sum())
         if hasattr(self.obj, "loss"):
-            out["loss_at_xbar"] = float(sum(self.obj.loss(i, xbar) for i in range(self.n)))
+            # objective of the run: with weight decay each f_i carries lambda/2 ||x||^2
+            out["loss_at_xbar"] = float(sum(self.obj.loss(i, xbar) for i in range(self.n))
+                                        + 0.5 * self.weight_decay * self.n * (xbar ** 2).sum())
         return out
 
     def slots(self):

@@ -32,8 +32,8 @@ OBJECTIVES = {"diag_quadratic": 0, "least_squares": 1, "logistic": 2, "softmax_b
 RFAST_FIELDS = {"X": 0, "Z": 1, "G": 2, "V_RING": 3, "RHO_RING": 4, "RHO_TILDE": 5, "T_NODE": 6, "TAU_R": 7,
                 "TAU_C": 8, "SLOT_R": 9, "SLOT_C": 10, "ROUND": 11, "SIGMA_RING": 12, "DELIV_R": 13, "DELIV_C": 14,
                 "T_HIST": 15, "SCHED_ACTIVE": 16, "SCHED_DELAY_R": 17, "SCHED_DELAY_C": 18, "SCHED_DROP_R": 19,
-                "SCHED_DROP_C": 20, "SCHED_BATCH": 21}
-EXPORTS = ["rfast_common_roots", "rfast_workspace_bytes", "rfast_create", "rfast_init", "rfast_round", "rfast_run", "rfast_run_generated", "rfast_use_graphs", "rfast_sync_round", "rfast_sync_run", "rfast_rebase", "rfast_set_rebase_interval", "rfast_check",
+                "SCHED_DROP_C": 20, "SCHED_BATCH": 21, "MOMENTUM": 22}
+EXPORTS = ["rfast_common_roots", "rfast_workspace_bytes", "rfast_create", "rfast_init", "rfast_round", "rfast_run", "rfast_run_generated", "rfast_use_graphs", "rfast_sync_round", "rfast_sync_run", "rfast_rebase", "rfast_set_rebase_interval", "rfast_set_optimizer", "rfast_set_gamma_schedule", "rfast_check",
            "rfast_read_state", "rfast_write_state", "rfast_diagnostics", "rfast_profile_enable", "rfast_kernel_time", "rfast_last_error",
            "rfast_destroy"]
 
@@ -72,6 +72,10 @@ def lib():
     L.rfast_rebase.argtypes = [vp]
     L.rfast_set_rebase_interval.restype = C.c_int
     L.rfast_set_rebase_interval.argtypes = [vp, i32]
+    L.rfast_set_optimizer.restype = C.c_int
+    L.rfast_set_optimizer.argtypes = [vp, C.c_float, C.c_float, vp]
+    L.rfast_set_gamma_schedule.restype = C.c_int
+    L.rfast_set_gamma_schedule.argtypes = [vp, i32, C.c_float]
     L.rfast_check.restype = C.c_int
     L.rfast_check.argtypes = [vp]
     L.rfast_read_state.restype = C.c_int
@@ -170,6 +174,14 @@ def rfast_rebase(ctx):
 
 def rfast_set_rebase_interval(ctx, rounds):
     _chk(lib().rfast_set_rebase_interval(ctx, rounds), ctx)
+
+
+def rfast_set_optimizer(ctx, momentum, weight_decay, momentum_buffer=None):
+    _chk(lib().rfast_set_optimizer(ctx, momentum, weight_decay, _dev_ptr(momentum_buffer)), ctx)
+
+
+def rfast_set_gamma_schedule(ctx, step_rounds, factor):
+    _chk(lib().rfast_set_gamma_schedule(ctx, step_rounds, factor), ctx)
 
 
 def rfast_check(ctx):
@@ -293,6 +305,16 @@ class RFast:
     def rebase(self):
         rfast_rebase(self.ctx)
 
+    def set_optimizer(self, momentum=0.0, weight_decay=0.0):
+        """Optimizer variant; init() must follow.  The buffer of the heavy-ball terms is allocated here."""
+        self.momentum_buffer = None
+        if momentum != 0.0:
+            self.momentum_buffer = self.torch.zeros(self.n * self.p, dtype=self.torch.float32, device=self.device)
+        rfast_set_optimizer(self.ctx, momentum, weight_decay, self.momentum_buffer)
+
+    def set_gamma_schedule(self, step_rounds, factor):
+        rfast_set_gamma_schedule(self.ctx, step_rounds, factor)
+
     def check(self):
         rfast_check(self.ctx)
 
@@ -308,7 +330,8 @@ class RFast:
                   "T_HIST": ((n, self.D + 1), np.int32), "SCHED_ACTIVE": ((n,), np.uint8),
                   "SCHED_DELAY_R": ((self.nnzR_off,), np.int32), "SCHED_DELAY_C": ((self.nnzC_off,), np.int32),
                   "SCHED_DROP_R": ((self.nnzR_off,), np.uint8), "SCHED_DROP_C": ((self.nnzC_off,), np.uint8),
-                  "SCHED_BATCH": ((n, self.prob.batch if self.prob.kind != 0 else 0), np.int32)}
+                  "SCHED_BATCH": ((n, self.prob.batch if self.prob.kind != 0 else 0), np.int32),
+                  "MOMENTUM": ((n, p), np.float32)}
         return shapes[field]
 
     def read(self, field):
@@ -325,11 +348,15 @@ class RFast:
             raise RFastError(-1, f"{field}: expected shape {shape}")
         rfast_write_state(self.ctx, field, value)
 
+    def _checkpoint_fields(self):
+        extra = ("MOMENTUM",) if getattr(self, "momentum_buffer", None) is not None else ()
+        return self.CHECKPOINT_FIELDS + extra
+
     def checkpoint(self):
-        return {f: self.read(f) for f in self.CHECKPOINT_FIELDS}
+        return {f: self.read(f) for f in self._checkpoint_fields()}
 
     def restore(self, ck):
-        for f in self.CHECKPOINT_FIELDS:
+        for f in self._checkpoint_fields():
             self.write(f, ck[f])
 
     def diagnostics(self, xstar=None):

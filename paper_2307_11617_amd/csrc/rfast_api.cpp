@@ -241,6 +241,7 @@ size_t field_bytes(const rfast_ctx* c, int32_t field) {
     case RFAST_SCHED_DROP_R: return (size_t)d.eR;
     case RFAST_SCHED_DROP_C: return (size_t)d.eC;
     case RFAST_SCHED_BATCH: return (size_t)d.n * (d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC ? 0 : d.prob.batch) * 4;
+    case RFAST_MOMENTUM: return d.mom ? d.n * vec : (size_t)-1;
     default: return (size_t)-1;
   }
 }
@@ -266,6 +267,12 @@ int fold_sync(rfast_ctx* c) {
 
 constexpr int32_t kGraphRounds = 16;
 
+// step size of the round about to run: gamma * factor^(round div step_rounds)
+float gamma_now(const rfast_ctx* c, float gamma) {
+  if (c->gamma_step <= 0) return gamma;
+  return gamma * powf(c->gamma_factor, (float)(c->host_round / c->gamma_step));
+}
+
 void drop_graph(rfast_ctx* c) {
   if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
   c->graph_exec = nullptr;
@@ -273,6 +280,7 @@ void drop_graph(rfast_ctx* c) {
 
 // automatic rebase of the running sums every `rebase_interval` rounds (0 = never)
 int after_round(rfast_ctx* c) {
+  c->host_round++;
   if (c->rebase_interval > 0 && ++c->rounds_since_rebase >= c->rebase_interval) {
     c->rounds_since_rebase = 0;
     const hipError_t e = rfast_launch_rebase(c);
@@ -301,6 +309,7 @@ int build_graph(rfast_ctx* c, uint64_t seed, const float* d_p_active, int32_t ma
   hipError_t e = hipStreamBeginCapture(c->capture_stream, hipStreamCaptureModeThreadLocal);
   if (e != hipSuccess) return hipfail(c, e, "hipStreamBeginCapture");
   c->stream = c->capture_stream;
+  const int64_t round_before = c->host_round;  // capture enqueues nothing: the counter moves when the graph is launched
   int rc = RFAST_OK;
   for (int32_t r = 0; r < kGraphRounds && rc == RFAST_OK; ++r) {
     const hipError_t g = rfast_launch_generate(c, seed, d_p_active, max_delay, p_drop);
@@ -308,6 +317,7 @@ int build_graph(rfast_ctx* c, uint64_t seed, const float* d_p_active, int32_t ma
     else rc = rfast_round(c, d.gen_active, d.gen_delay_r, d.gen_delay_c, d.gen_drop_r, d.gen_drop_c, gamma, d.gen_batch);
   }
   c->stream = user;
+  c->host_round = round_before;
   hipGraph_t graph = nullptr;
   e = hipStreamEndCapture(c->capture_stream, &graph);
   if (rc != RFAST_OK) {
@@ -325,7 +335,7 @@ int build_graph(rfast_ctx* c, uint64_t seed, const float* d_p_active, int32_t ma
   c->graph_p_active = d_p_active;
   c->graph_max_delay = max_delay;
   c->graph_p_drop = p_drop;
-  c->graph_gamma = gamma;
+  c->graph_gamma = gamma_now(c, gamma);
   return RFAST_OK;
 }
 
@@ -429,6 +439,7 @@ int rfast_create(rfast_ctx** out, int32_t n, int64_t p, const int32_t* R_rowptr,
   d.gen_delay_c = (int32_t*)(b + o.gen_delay_c); d.gen_drop_r = (uint8_t*)(b + o.gen_drop_r);
   d.gen_drop_c = (uint8_t*)(b + o.gen_drop_c); d.gen_batch = (int32_t*)(b + o.gen_batch);
   d.xbar = (float*)(b + o.xbar);
+  d.mom = nullptr; d.beta = 0.f; d.wd = 0.f;
   d.resid = (float*)(b + o.resid); d.gscratch = (void*)(b + o.gscratch);
   c->d_diag = (double*)(b + o.diag);
   d.prob = *prob;
@@ -458,8 +469,11 @@ int rfast_init(rfast_ctx* c, const float* d_x0, const int32_t* d_batch_idx0) {
   const size_t vec = (size_t)d.p * 4;
   c->sync_parity = 0;
   c->rounds_since_rebase = 0;
+  c->host_round = 0;
+  c->needs_init = false;
   hipError_t e = hipSuccess;
   auto chk = [&](hipError_t r) { if (e == hipSuccess) e = r; };
+  if (d.mom) chk(hipMemsetAsync(d.mom, 0, d.n * vec, c->stream));
   if (d_x0) chk(hipMemcpyAsync(d.x, d_x0, d.n * vec, hipMemcpyDeviceToDevice, c->stream));
   else chk(hipMemsetAsync(d.x, 0, d.n * vec, c->stream));
   chk(hipMemsetAsync(d.g, 0, 2 * d.n * vec, c->stream));
@@ -499,7 +513,9 @@ int rfast_round(rfast_ctx* c, const uint8_t* d_active, const int32_t* d_delay_R,
   const bool separable = d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC;
   if (!separable && d.prob.batch > 0 && !d_batch_idx) return fail(c, RFAST_EINVAL, "sample rows are required when batch > 0");
   if (!std::isfinite(gamma)) return fail(c, RFAST_EINVAL, "gamma is not finite");
+  if (c->needs_init) return fail(c, RFAST_EINVAL, "rfast_init must follow rfast_set_optimizer");
   if (fold_sync(c) != RFAST_OK) return RFAST_EHIP;
+  gamma = gamma_now(c, gamma);
   hipError_t e;
   time_begin(c, 2);
   e = rfast_launch_resolve(c, d_active, d_delay_R, d_delay_C, d_drop_R, d_drop_C);
@@ -562,25 +578,30 @@ int rfast_run_generated(rfast_ctx* c, int32_t rounds, uint64_t seed, const float
   // A generated round takes no host argument that varies from round to round (the
   // generator reads the round number on the device), so kGraphRounds of them are
   // captured once into a HIP graph and replayed: one launch per kGraphRounds rounds.
-  if (c->use_graphs && !c->profiling && c->rebase_interval == 0 && rounds >= kGraphRounds) {
-    if (fold_sync(c) != RFAST_OK) return RFAST_EHIP;
-    const bool same = c->graph_exec && c->graph_seed == seed && c->graph_p_active == d_p_active &&
-                      c->graph_max_delay == max_delay && c->graph_p_drop == p_drop && c->graph_gamma == gamma;
-    if (!same) {
-      const int rc = build_graph(c, seed, d_p_active, max_delay, p_drop, gamma);
-      if (rc != RFAST_OK) return rc;
-    }
-    while (rounds >= kGraphRounds) {
+  if (c->needs_init) return fail(c, RFAST_EINVAL, "rfast_init must follow rfast_set_optimizer");
+  const bool graphs = c->use_graphs && !c->profiling && c->rebase_interval == 0;
+  while (rounds > 0) {
+    // a graph bakes the step size in, so a replay must not straddle a decay step of the schedule
+    const bool one_step_size = c->gamma_step <= 0 || c->host_round % c->gamma_step + kGraphRounds <= c->gamma_step;
+    if (graphs && rounds >= kGraphRounds && one_step_size) {
+      if (fold_sync(c) != RFAST_OK) return RFAST_EHIP;
+      const bool same = c->graph_exec && c->graph_seed == seed && c->graph_p_active == d_p_active &&
+                        c->graph_max_delay == max_delay && c->graph_p_drop == p_drop && c->graph_gamma == gamma_now(c, gamma);
+      if (!same) {
+        const int rc = build_graph(c, seed, d_p_active, max_delay, p_drop, gamma);
+        if (rc != RFAST_OK) return rc;
+      }
       const hipError_t e = hipGraphLaunch(c->graph_exec, c->stream);
       if (e != hipSuccess) return hipfail(c, e, "hipGraphLaunch");
+      c->host_round += kGraphRounds;
       rounds -= kGraphRounds;
+      continue;
     }
-  }
-  for (int32_t r = 0; r < rounds; ++r) {
     const hipError_t e = rfast_launch_generate(c, seed, d_p_active, max_delay, p_drop);
     if (e != hipSuccess) return hipfail(c, e, "schedule generator launch");
     const int rc = rfast_round(c, d.gen_active, d.gen_delay_r, d.gen_delay_c, d.gen_drop_r, d.gen_drop_c, gamma, d.gen_batch);
     if (rc != RFAST_OK) return rc;
+    --rounds;
   }
   return RFAST_OK;
 }
@@ -591,6 +612,8 @@ int rfast_sync_round(rfast_ctx* c, float gamma, const int32_t* d_batch_idx) {
   const bool separable = d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC;
   if (!separable && d.prob.batch > 0 && !d_batch_idx) return fail(c, RFAST_EINVAL, "sample rows are required when batch > 0");
   if (!std::isfinite(gamma)) return fail(c, RFAST_EINVAL, "gamma is not finite");
+  if (c->needs_init) return fail(c, RFAST_EINVAL, "rfast_init must follow rfast_set_optimizer");
+  gamma = gamma_now(c, gamma);
   hipError_t e;
   time_begin(c, 0);
   e = rfast_launch_sync(c, separable ? 2 : 0, gamma, c->sync_parity);
@@ -607,6 +630,7 @@ int rfast_sync_round(rfast_ctx* c, float gamma, const int32_t* d_batch_idx) {
     if (e != hipSuccess) return hipfail(c, e, "synchronous tracker launch");
   }
   c->sync_parity ^= 1;
+  c->host_round++;
   return RFAST_OK;
 }
 
@@ -619,6 +643,29 @@ int rfast_sync_run(rfast_ctx* c, int32_t rounds, float gamma, const int32_t* d_b
     const int rc = rfast_sync_round(c, gamma, d_batch_idx ? d_batch_idx + (size_t)r * d.n * B : nullptr);
     if (rc != RFAST_OK) return rc;
   }
+  return RFAST_OK;
+}
+
+int rfast_set_optimizer(rfast_ctx* c, float momentum, float weight_decay, float* d_momentum) {
+  if (!c) return RFAST_EINVAL;
+  if (!(momentum >= 0.f && momentum < 1.f)) return fail(c, RFAST_ERANGE, "momentum must lie in [0, 1)");
+  if (!(weight_decay >= 0.f) || !std::isfinite(weight_decay)) return fail(c, RFAST_ERANGE, "weight_decay must be finite and >= 0");
+  if (momentum != 0.f && !d_momentum) return fail(c, RFAST_EINVAL, "momentum != 0 needs a buffer of n*p floats");
+  if (d_momentum && ((uintptr_t)d_momentum % 16) != 0) return fail(c, RFAST_EINVAL, "momentum buffer must be 16-byte aligned");
+  drop_graph(c);  // a captured graph holds the old kernel arguments
+  c->d.beta = momentum;
+  c->d.wd = weight_decay;
+  c->d.mom = momentum != 0.f ? d_momentum : nullptr;
+  c->needs_init = true;
+  return RFAST_OK;
+}
+
+int rfast_set_gamma_schedule(rfast_ctx* c, int32_t step_rounds, float factor) {
+  if (!c) return RFAST_EINVAL;
+  if (step_rounds < 0) return fail(c, RFAST_EINVAL, "step_rounds < 0");
+  if (!(factor > 0.f) || !std::isfinite(factor)) return fail(c, RFAST_ERANGE, "factor must be finite and > 0");
+  c->gamma_step = step_rounds;
+  c->gamma_factor = factor;
   return RFAST_OK;
 }
 
@@ -682,6 +729,7 @@ int rfast_read_state(rfast_ctx* c, int32_t field, void* host_dst, size_t bytes) 
     case RFAST_SCHED_DROP_R: src = d.gen_drop_r; break;
     case RFAST_SCHED_DROP_C: src = d.gen_drop_c; break;
     case RFAST_SCHED_BATCH: src = d.gen_batch; break;
+    case RFAST_MOMENTUM: src = d.mom; break;
     default: break;
   }
   if (field == RFAST_RHO_RING) {
@@ -713,7 +761,8 @@ int rfast_read_state(rfast_ctx* c, int32_t field, void* host_dst, size_t bytes) 
 
 int rfast_write_state(rfast_ctx* c, int32_t field, const void* host_src, size_t bytes) {
   if (!c || !host_src) return RFAST_EINVAL;
-  if (field == RFAST_RHO_RING || field == RFAST_SLOT_R || field == RFAST_SLOT_C || field >= RFAST_SCHED_ACTIVE)
+  if (field == RFAST_RHO_RING || field == RFAST_SLOT_R || field == RFAST_SLOT_C ||
+      (field >= RFAST_SCHED_ACTIVE && field <= RFAST_SCHED_BATCH))
     return fail(c, RFAST_EINVAL, "this field is derived and cannot be written");
   const size_t want = field_bytes(c, field);
   if (want == (size_t)-1) return fail(c, RFAST_EINVAL, "unknown field");
@@ -737,8 +786,10 @@ int rfast_write_state(rfast_ctx* c, int32_t field, const void* host_src, size_t 
     case RFAST_DELIV_R: dst = d.deliv_r; break;
     case RFAST_DELIV_C: dst = d.deliv_c; break;
     case RFAST_T_HIST: dst = d.t_hist; break;
+    case RFAST_MOMENTUM: dst = d.mom; break;
     default: break;
   }
+  if (field == RFAST_ROUND) c->host_round = *(const int32_t*)host_src;
   if (field == RFAST_G) {
     // both parities receive the sample, so the order of restoring G and T_NODE does not matter
     e = hipMemcpy(d.g, host_src, bytes, hipMemcpyHostToDevice);
@@ -765,8 +816,10 @@ int rfast_diagnostics(rfast_ctx* c, const float* d_xstar, rfast_diag* host_out) 
   host_out->conservation_sq = h[2];
   host_out->gsum_sq = h[3];
   host_out->xbar_gap_sq = d_xstar ? h[4] : -1.0;
-  // sum_i f_i(xbar); the l2 term of the logistic objective is n * lambda/2 * ||xbar||^2
-  host_out->loss_at_xbar = h[5] + (c->d.prob.kind == RFAST_OBJ_LOGISTIC ? 0.5 * c->d.prob.lambda * c->d.n * h[6] : 0.0);
+  // sum_i f_i(xbar); the l2 term of the logistic objective and the weight decay of the optimizer
+  // variant each add n * coefficient/2 * ||xbar||^2
+  const double l2 = (c->d.prob.kind == RFAST_OBJ_LOGISTIC ? (double)c->d.prob.lambda : 0.0) + (double)c->d.wd;
+  host_out->loss_at_xbar = h[5] + 0.5 * l2 * c->d.n * h[6];
   return RFAST_OK;
 }
 

@@ -91,7 +91,8 @@ __global__ void __launch_bounds__(kThreads) rfast_cols_kernel(RfastDev s, const 
   const int t_old = init ? -1 : s.plan_t[i];
   float* dst = s.g + (size_t)((t_old + 1) & 1) * s.n * p + (size_t)i * p + k;
   const float inv = 1.0f / (float)B;
-  const float lam = s.prob.kind == RFAST_OBJ_LOGISTIC ? s.prob.lambda : 0.f;
+  // l2 term of the logistic objective plus the weight decay of the optimizer variant
+  const float lam = (s.prob.kind == RFAST_OBJ_LOGISTIC ? s.prob.lambda : 0.f) + s.wd;
   if (VEC == 4) {
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int b = 0; b < B; ++b) {

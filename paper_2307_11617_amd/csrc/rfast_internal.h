@@ -71,6 +71,9 @@ struct RfastDev {
   uint8_t* gen_drop_c;    // [eC]
   int32_t* gen_batch;     // [n][batch]
   float* xbar;            // [p] node average, written by the diagnostics kernel
+  // optimizer variant: heavy-ball buffers m_i [n][p] (caller's memory, NULL when beta == 0)
+  float* mom;
+  float beta, wd;
   // gradient scratch
   float* resid;           // [n][rows] residuals of the GEMV pair / unused
   void* gscratch;         // softmax: bf16 W copy and E matrix
@@ -97,6 +100,10 @@ struct rfast_ctx {
   float graph_p_drop = 0.f, graph_gamma = 0.f;
   int32_t sync_parity = 0;  // 1: the current z of the synchronous mode lives in slot 1 of the v ring
   int32_t rounds_since_rebase = 0;
+  int64_t host_round = 0;       // mirror of the device round counter, for the step-size schedule
+  int32_t gamma_step = 0;       // rounds per decay step, 0 = constant step size
+  float gamma_factor = 1.f;
+  bool needs_init = false;      // rfast_set_optimizer was called and rfast_init has not followed yet
 };
 
 enum { RFAST_MODE_FUSED = 0, RFAST_MODE_MIX = 1, RFAST_MODE_TRACK = 2 };

@@ -126,7 +126,9 @@ template <> __device__ inline float noise_at<1>(uint64_t seed, uint32_t node, ui
 }
 
 // ------------------------------------------------------------------- kernel
-template <int MODE, int VEC>
+// MOM: the optimizer variant's heavy-ball buffer is in use (a template flag so that the
+// plain method carries neither the branch nor the registers).
+template <int MODE, int VEC, bool MOM>
 __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float gamma, int tiles_per_node) {
   using T = typename V<VEC>::T;
   const int n_act = *s.n_active;
@@ -154,13 +156,14 @@ __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float
 
   // ---- every load of the first batch of each phase is issued before its first use:
   //      with few wavefronts per CU this is what keeps enough bytes in flight
-  T x_i, z_i, g_old, g_new, h, c, sig_cur;
+  T x_i, z_i, g_old, g_new, h, c, sig_cur, m_i;
   T vb[kBatch], sg[kBatch], rt[kBatch];
   float vw[kBatch], ca[kBatch];
   bool live[kBatch];
   z_i = V<VEC>::ld(s.z + node_off);
   if (kMix) {
     x_i = V<VEC>::ld(s.x + node_off);
+    if (MOM) m_i = V<VEC>::ld(s.mom + node_off);
 #pragma unroll
     for (int q = 0; q < kBatch; ++q)
       if (re0 + q < re1) {
@@ -191,8 +194,13 @@ __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float
 
   T x_new;
   if (kMix) {
-    // S1: local descent
-    const T v = fma_s(-gamma, z_i, x_i);
+    // S1: local descent; with the optimizer variant along the heavy-ball buffer m <- beta m + z
+    T dir = z_i;
+    if (MOM) {
+      dir = fma_s(s.beta, m_i, z_i);
+      V<VEC>::st(s.mom + node_off, dir);
+    }
+    const T v = fma_s(-gamma, dir, x_i);
     // S2a: pull the stamped neighbour copies and mix with row-stochastic weights
     x_new = mul_s(s.r_self[i], v);
 #pragma unroll
@@ -220,6 +228,7 @@ __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float
     g_new = mul(h, sub(x_new, c));
     if (s.prob.noise_std != 0.0f)
       g_new = fma_s(s.prob.noise_std, noise_at<VEC>(s.prob.noise_seed, (uint32_t)i, (uint32_t)(t_old + 1), k), g_new);
+    if (s.wd != 0.0f) g_new = fma_s(s.wd, x_new, g_new);  // weight decay is part of the sampled gradient
     V<VEC>::st(g_new_p, g_new);
   }
 
@@ -269,8 +278,10 @@ __global__ void __launch_bounds__(kThreads) rfast_diag_init_kernel(RfastDev s) {
   using T = typename V<VEC>::T;
   const T h = V<VEC>::ld((const float*)s.prob.data0 + off);
   const T c = V<VEC>::ld((const float*)s.prob.data1 + off);
-  T g = mul(h, sub(V<VEC>::ld(s.x + off), c));
+  const T x0 = V<VEC>::ld(s.x + off);
+  T g = mul(h, sub(x0, c));
   if (s.prob.noise_std != 0.0f) g = fma_s(s.prob.noise_std, noise_at<VEC>(s.prob.noise_seed, (uint32_t)i, 0u, k), g);
+  if (s.wd != 0.0f) g = fma_s(s.wd, x0, g);
   V<VEC>::st(s.g + off, g);
 }
 
@@ -325,8 +336,12 @@ __global__ void __launch_bounds__(kThreads) rfast_sync_descent_kernel(RfastDev s
   const int64_t k = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * V<VEC>::W;
   if (k >= s.p) return;
   const auto x = V<VEC>::ld(s.x + (size_t)i * s.p + k);
-  const auto z = V<VEC>::ld(sync_z(s, parity, i) + k);
-  V<VEC>::st(s.v_ring + (size_t)i * s.M * s.p + k, fma_s(-gamma, z, x));
+  auto dir = V<VEC>::ld(sync_z(s, parity, i) + k);
+  if (s.mom) {
+    dir = fma_s(s.beta, V<VEC>::ld(s.mom + (size_t)i * s.p + k), dir);
+    V<VEC>::st(s.mom + (size_t)i * s.p + k, dir);
+  }
+  V<VEC>::st(s.v_ring + (size_t)i * s.M * s.p + k, fma_s(-gamma, dir, x));
 }
 
 // PHASE 0: mix only (x').  PHASE 1: tracker only (reads g' written by the gradient
@@ -354,6 +369,7 @@ __global__ void __launch_bounds__(kThreads) rfast_sync_step_kernel(RfastDev s, i
     g_new = mul(h, sub(x_new, c));
     if (s.prob.noise_std != 0.0f)
       g_new = fma_s(s.prob.noise_std, noise_at<VEC>(s.prob.noise_seed, (uint32_t)i, (uint32_t)(t_old + 1), k), g_new);
+    if (s.wd != 0.0f) g_new = fma_s(s.wd, x_new, g_new);
     V<VEC>::st(g_new_p, g_new);
   } else {
     g_new = V<VEC>::ld(g_new_p);
@@ -373,7 +389,7 @@ __global__ void __launch_bounds__(kThreads) rfast_sync_fold_kernel(RfastDev s) {
   V<VEC>::st(s.z + (size_t)i * s.p + k, V<VEC>::ld(sync_z(s, 1, i) + k));
 }
 
-template <int MODE>
+template <int MODE, bool MOM>
 hipError_t launch(rfast_ctx* c, float gamma) {
   const RfastDev& d = c->d;
   const bool vec4 = (d.p % 4) == 0;
@@ -386,11 +402,11 @@ hipError_t launch(rfast_ctx* c, float gamma) {
   // nothing here, where the 141 registers of the up-front loads already hold it to 12 wavefronts.)
   const bool streaming = (double)d.n * (double)d.p * 4.0 >= 32.0e6;
   if (vec4 && streaming)
-    hipLaunchKernelGGL((rfast_state_kernel<MODE, -4>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, d, gamma, (int)tiles);
+    hipLaunchKernelGGL((rfast_state_kernel<MODE, -4, MOM>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, d, gamma, (int)tiles);
   else if (vec4)
-    hipLaunchKernelGGL((rfast_state_kernel<MODE, 4>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, d, gamma, (int)tiles);
+    hipLaunchKernelGGL((rfast_state_kernel<MODE, 4, MOM>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, d, gamma, (int)tiles);
   else
-    hipLaunchKernelGGL((rfast_state_kernel<MODE, 1>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, d, gamma, (int)tiles);
+    hipLaunchKernelGGL((rfast_state_kernel<MODE, 1, MOM>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, d, gamma, (int)tiles);
   return hipGetLastError();
 }
 
@@ -453,9 +469,10 @@ hipError_t rfast_launch_rebase(rfast_ctx* c) {
 }
 
 hipError_t rfast_launch_state(rfast_ctx* c, int mode, float gamma) {
+  const bool mom = c->d.mom != nullptr;
   switch (mode) {
-    case RFAST_MODE_FUSED: return launch<RFAST_MODE_FUSED>(c, gamma);
-    case RFAST_MODE_MIX: return launch<RFAST_MODE_MIX>(c, gamma);
-    default: return launch<RFAST_MODE_TRACK>(c, gamma);
+    case RFAST_MODE_FUSED: return mom ? launch<RFAST_MODE_FUSED, true>(c, gamma) : launch<RFAST_MODE_FUSED, false>(c, gamma);
+    case RFAST_MODE_MIX: return mom ? launch<RFAST_MODE_MIX, true>(c, gamma) : launch<RFAST_MODE_MIX, false>(c, gamma);
+    default: return launch<RFAST_MODE_TRACK, false>(c, gamma);  // S1 is not part of this pass
   }
 }

@@ -414,12 +414,15 @@ __global__ void __launch_bounds__(64 * NW) rfast_softmax_backward(RfastDev s, co
   }
   const int t_old = init ? -1 : s.plan_t[i];
   float* G = s.g + (size_t)((t_old + 1) & 1) * s.n * s.p + (size_t)i * s.p;
+  const float* Wi = s.x + (size_t)i * s.p;  // weight decay of the optimizer variant acts on the fp32 weights
+  const float wd = s.wd;
 #pragma unroll
   for (int ft = 0; ft < 2; ++ft)
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int f = f0 + ft * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-      G[(size_t)f * K + wave * 32 + (lane & 31)] = acc[ft][v];
+      const size_t o = (size_t)f * K + wave * 32 + (lane & 31);
+      G[o] = wd != 0.0f ? fmaf(wd, Wi[o], acc[ft][v]) : acc[ft][v];
     }
 }
 

@@ -7,7 +7,7 @@ def csr(g):
     return (g.rowptr, g.col, g.w32())
 
 
-def make_oracle(w, coords=None, x0=None):
+def make_oracle(w, coords=None, x0=None, momentum=0.0, weight_decay=0.0):
     from oracle import objectives as ob
     from oracle.rfast_oracle import RFastOracle
     d = w.data
@@ -26,7 +26,8 @@ def make_oracle(w, coords=None, x0=None):
         from rfast_workloads.problems import bf16_bits_to_f32
         obj = ob.SoftmaxBf16(bf16_bits_to_f32(d["Xb"]), d["labels"], w.extra["d"], w.extra["K"])
     b0 = w.sched.initial_batch()
-    return RFastOracle(w.n, p, w.R, w.C, w.D, w.burst, obj, x0=x0, batch0=b0)
+    return RFastOracle(w.n, p, w.R, w.C, w.D, w.burst, obj, x0=x0, batch0=b0, momentum=momentum,
+                       weight_decay=weight_decay)
 
 
 def make_gpu(w, device="cuda:0"):
@@ -62,12 +63,21 @@ def rel_l2(a, b, floor=0.0):
     return float(np.linalg.norm(a.astype(np.float64) - b) / den) if den > 0 else float(np.linalg.norm(a))
 
 
-def run_parity(w, rounds, every=100, coords=None, x0=None, tol=None, check_rings=True, verbose=False, rebase=False):
+def run_parity(w, rounds, every=100, coords=None, x0=None, tol=None, check_rings=True, verbose=False, rebase=False,
+               momentum=0.0, weight_decay=0.0, gamma_schedule=None):
     """Runs `rounds` rounds on both sides; at every checkpoint compares integer
-    state exactly and x, z (and g, rho~) in relative L2.  Returns the worst errors."""
+    state exactly and x, z (and g, rho~) in relative L2.  Returns the worst errors.
+    momentum / weight_decay / gamma_schedule = (step_rounds, factor): the optimizer variant."""
+    from oracle.rfast_oracle import step_gamma
     tol = w.tol if tol is None else tol
-    orc = make_oracle(w, coords, None if x0 is None else (x0 if coords is None else x0[:, coords]))
+    orc = make_oracle(w, coords, None if x0 is None else (x0 if coords is None else x0[:, coords]), momentum,
+                      weight_decay)
     gpu = make_gpu(w)
+    if momentum != 0.0 or weight_decay != 0.0:
+        gpu.set_optimizer(momentum, weight_decay)
+    step_rounds, factor = gamma_schedule if gamma_schedule is not None else (0, 1.0)
+    if gamma_schedule is not None:
+        gpu.set_gamma_schedule(step_rounds, factor)
     gpu.init(x0, w.sched.initial_batch())
     sel = slice(None) if coords is None else coords
     M = w.D + 2
@@ -80,7 +90,8 @@ def run_parity(w, rounds, every=100, coords=None, x0=None, tol=None, check_rings
         gpu.run(r1 - r0, dev["active"], dev["delay_R"], dev["delay_C"], dev["drop_R"], dev["drop_C"], w.gamma,
                 dev["batch_idx"])
         for k in range(r1 - r0):
-            orc.round(st["active"][k], st["delay_R"][k], st["delay_C"][k], st["drop_R"][k], st["drop_C"][k], w.gamma,
+            orc.round(st["active"][k], st["delay_R"][k], st["delay_C"][k], st["drop_R"][k], st["drop_C"][k],
+                      step_gamma(w.gamma, factor, step_rounds, r0 + k),
                       None if st["batch_idx"] is None else st["batch_idx"][k])
         gpu.check()
         # ---- integer state: bit-exact
@@ -102,6 +113,9 @@ def run_parity(w, rounds, every=100, coords=None, x0=None, tol=None, check_rings
         if verbose:
             print(f"round {r1}: rel-L2 x {ex:.2e} z {ez:.2e} g {eg:.2e}", flush=True)
         assert ex <= tol and ez <= tol, f"round {r1}: x {ex:.3e} z {ez:.3e} (tol {tol})"
+        if momentum != 0.0:
+            em = rel_l2(gpu.read("MOMENTUM")[:, sel], orc.m, 1e-3 * gnorm)
+            assert em <= tol, f"round {r1}: momentum buffer {em:.3e} (tol {tol})"
         if rebase:
             gpu.rebase()   # shifts rho and rho~ by a common offset: only their difference is comparable afterwards
         if check_rings and not rebase and coords is None and w.n * w.p * M <= 4_000_000:

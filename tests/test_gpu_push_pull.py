@@ -22,11 +22,13 @@ def _objective(w):
     return ob.Logistic(d["X"], d["y"])
 
 
-def _run(w, steps, every, x0=None, tol_g=1e-4, z_floor=1e-3, tol_z=1e-4):
+def _run(w, steps, every, x0=None, tol_g=1e-4, z_floor=1e-3, tol_z=1e-4, momentum=0.0, weight_decay=0.0):
     b0 = w.sched.initial_batch()
     orc = PushPullOracle(w.R.dense(), w.C.dense(), _objective(w), x0=x0 if x0 is not None else np.zeros((w.n, w.p)),
-                         batch0=b0)
+                         batch0=b0, momentum=momentum, weight_decay=weight_decay)
     gpu = harness.make_gpu(w)
+    if momentum != 0.0 or weight_decay != 0.0:
+        gpu.set_optimizer(momentum, weight_decay)
     gpu.init(x0, b0)
     worst = {"x": 0.0, "z": 0.0}
     for r0 in range(0, steps, every):
@@ -44,6 +46,8 @@ def _run(w, steps, every, x0=None, tol_g=1e-4, z_floor=1e-3, tol_z=1e-4):
         eg = harness.rel_l2(gpu.read("G"), orc.g)
         worst = {"x": max(worst["x"], ex), "z": max(worst["z"], ez)}
         assert ex <= 1e-4 and ez <= tol_z and eg <= tol_g, (r0 + every, ex, ez, eg)
+        if momentum != 0.0:
+            assert harness.rel_l2(gpu.read("MOMENTUM"), orc.m, z_floor * gn) <= tol_z
     return worst, orc, gpu
 
 

@@ -93,7 +93,9 @@ typedef struct rfast_problem {
 typedef enum rfast_field {
   RFAST_X = 0,         /* fp32 [n][p]                                             */
   RFAST_Z = 1,         /* fp32 [n][p]                                             */
-  RFAST_G = 2,         /* fp32 [n][p]  stored gradient sample of each node         */
+  RFAST_G = 2,         /* fp32 [n][p]  stored gradient sample of each node.  For the diagonal quadratic the
+                          sample is a pure function of (x_i, t_i): it is recomputed where needed and on
+                          read; writing it is accepted and has no effect                              */
   RFAST_V_RING = 3,    /* fp32 [n][D+2][p]  slot s of node j = version t, t mod (D+2) == s */
   RFAST_RHO_RING = 4,  /* fp32 [nnzC_off][D+2][p]  sender-side running sums rho_ij = a_ij * sigma_j (expanded on read) */
   RFAST_RHO_TILDE = 5, /* fp32 [nnzC_off][p]  receiver-side buffers                */

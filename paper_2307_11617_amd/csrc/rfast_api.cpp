@@ -746,6 +746,12 @@ int rfast_read_state(rfast_ctx* c, int32_t field, void* host_dst, size_t bytes) 
       for (size_t k = 0; k < ring; ++k) dst[k] = w_h[q] * dst[k];
     }
   } else if (field == RFAST_G) {
+    // the separable objective keeps no sample in memory: write the current ones out first
+    if (d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC) {
+      e = rfast_diag_init_gradient(c);
+      if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+      if (e != hipSuccess) return hipfail(c, e, "forming the gradient samples");
+    }
     // the stored sample of node i is the one of version t_i: g[t_i & 1][i]
     std::vector<int32_t> t(d.n);
     e = hipMemcpy(t.data(), d.t, (size_t)d.n * 4, hipMemcpyDeviceToHost);

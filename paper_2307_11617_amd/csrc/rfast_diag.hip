@@ -6,7 +6,7 @@
 // One lane owns one coordinate and walks over nodes and edges (coalesced along
 // k); partial sums are kept in fp64, reduced across the 64 lanes with shuffles
 // and added to the result with one fp64 atomic per wavefront.
-#include "rfast_internal.h"
+#include "rfast_vec.h"
 
 namespace {
 
@@ -33,7 +33,10 @@ __global__ void __launch_bounds__(kThreads) rfast_diag_kernel(RfastDev s, const 
       xs += s.x[off];
       zs += zi;
       acc[1] += zi * zi;
-      gs += s.g[(size_t)(s.t[i] & 1) * s.n * p + off];
+      if (s.prob.kind == RFAST_OBJ_DIAG_QUADRATIC)  // the sample is a function of (x_i, t_i), not kept in memory
+        gs += diag_sample<1>(s, ((const float*)s.prob.data0)[off], ((const float*)s.prob.data1)[off], s.x[off], i, s.t[i], k);
+      else
+        gs += s.g[(size_t)(s.t[i] & 1) * s.n * p + off];
     }
     const double xbar = xs / s.n;
     s.xbar[k] = (float)xbar;

@@ -116,6 +116,7 @@ hipError_t rfast_launch_rebase(rfast_ctx* c);
 hipError_t rfast_launch_generate(rfast_ctx* c, uint64_t seed, const float* d_p_active, int d_max, float p_drop);
 hipError_t rfast_launch_sync(rfast_ctx* c, int phase, float gamma, int parity);
 hipError_t rfast_launch_init_grad(rfast_ctx* c, const int32_t* batch_idx0);
+hipError_t rfast_diag_init_gradient(rfast_ctx* c);  // separable objective: g[t_i & 1][i] = sample(x_i, t_i) for every node
 hipError_t rfast_launch_gradient(rfast_ctx* c, const int32_t* batch_idx);
 hipError_t rfast_launch_diag(rfast_ctx* c, const float* d_xstar, double* d_out);
 hipError_t rfast_softmax_loss(rfast_ctx* c, double* d_out);  // adds sum_i f_i(xbar) to *d_out

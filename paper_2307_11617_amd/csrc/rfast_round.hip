@@ -16,114 +16,12 @@
 // algebraically identical to the per-edge recursion, bit-identical when a_li is
 // a power of two, and it replaces dO reads + dO writes per coordinate by 1 + 1.
 #include "rfast_internal.h"
-#include "rfast_philox.h"
+#include "rfast_vec.h"
 
 namespace {
 
 constexpr int kThreads = 256;
 constexpr int kBatch = 8;  // loads kept in flight per edge phase
-
-// ------------------------------------------------------------ vector helpers
-// VEC = 4: float4 per lane.  VEC = -4: the same with non-temporal (streaming)
-// loads and stores, used when the state is far larger than the caches, so
-// that lines with no reuse do not displace anything.  VEC = 1: scalar, p % 4 != 0.
-typedef float nt_f4 __attribute__((ext_vector_type(4)));
-template <int VEC> struct V;
-template <> struct V<4> {
-  using T = float4;
-  static constexpr int W = 4;
-  static __device__ inline T ld(const float* p) { return *reinterpret_cast<const float4*>(p); }
-  static __device__ inline void st(float* p, T v) { *reinterpret_cast<float4*>(p) = v; }
-};
-template <> struct V<-4> {
-  using T = float4;
-  static constexpr int W = 4;
-  static __device__ inline T ld(const float* p) {
-    const nt_f4 t = __builtin_nontemporal_load(reinterpret_cast<const nt_f4*>(p));
-    return make_float4(t.x, t.y, t.z, t.w);
-  }
-  static __device__ inline void st(float* p, T v) {
-    const nt_f4 t = {v.x, v.y, v.z, v.w};
-    __builtin_nontemporal_store(t, reinterpret_cast<nt_f4*>(p));
-  }
-};
-template <> struct V<1> {
-  using T = float;
-  static constexpr int W = 1;
-  static __device__ inline T ld(const float* p) { return *p; }
-  static __device__ inline void st(float* p, T v) { *p = v; }
-};
-__device__ inline float4 fma_s(float a, float4 b, float4 c) {
-  return make_float4(fmaf(a, b.x, c.x), fmaf(a, b.y, c.y), fmaf(a, b.z, c.z), fmaf(a, b.w, c.w));
-}
-__device__ inline float fma_s(float a, float b, float c) { return fmaf(a, b, c); }
-__device__ inline float4 mul_s(float a, float4 b) { return make_float4(a * b.x, a * b.y, a * b.z, a * b.w); }
-__device__ inline float mul_s(float a, float b) { return a * b; }
-__device__ inline float4 add(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
-__device__ inline float add(float a, float b) { return a + b; }
-__device__ inline float4 sub(float4 a, float4 b) { return make_float4(a.x - b.x, a.y - b.y, a.z - b.z, a.w - b.w); }
-__device__ inline float sub(float a, float b) { return a - b; }
-__device__ inline float4 mul(float4 a, float4 b) { return make_float4(a.x * b.x, a.y * b.y, a.z * b.z, a.w * b.w); }
-__device__ inline float mul(float a, float b) { return a * b; }
-
-// ------------------------------------------------- counter-based Gaussian noise
-// sin and cos of 2*pi*w/2^32.  The octant comes from the top three bits, so the
-// reduction is exact; the remainder a in [-pi/8, pi/8] goes through Taylor
-// polynomials whose truncation error is below 1e-8.
-__device__ inline void sincos_turns(uint32_t w, float* s, float* c) {
-  const uint32_t q = ((w >> 28) + 1u) >> 1;                // nearest multiple of pi/4 (0..8)
-  const int32_t rem = (int32_t)(w - (q << 29));            // signed offset from q*pi/4 (mod 2^32), |rem| <= 2^28
-  const float a = (float)rem * (6.283185307179586f / 4294967296.0f);
-  const float a2 = a * a;
-  float sp = fmaf(a2, fmaf(a2, fmaf(a2, fmaf(a2, 2.7557319e-6f, -1.9841270e-4f), 8.3333333e-3f), -1.6666667e-1f), 1.0f) * a;
-  float cp = fmaf(a2, fmaf(a2, fmaf(a2, fmaf(a2, 2.4801587e-5f, -1.3888889e-3f), 4.1666667e-2f), -0.5f), 1.0f);
-  // rotate by q * pi/4
-  const float h = 0.70710678118654752f;
-  float sq, cq;
-  switch (q & 7u) {
-    case 0: sq = 0.f; cq = 1.f; break;
-    case 1: sq = h; cq = h; break;
-    case 2: sq = 1.f; cq = 0.f; break;
-    case 3: sq = h; cq = -h; break;
-    case 4: sq = 0.f; cq = -1.f; break;
-    case 5: sq = -h; cq = -h; break;
-    case 6: sq = -1.f; cq = 0.f; break;
-    default: sq = -h; cq = h; break;
-  }
-  *s = fmaf(sq, cp, cq * sp);
-  *c = fmaf(cq, cp, -sq * sp);
-}
-
-__device__ inline void box_muller(uint32_t ou, uint32_t oa, float* n0, float* n1) {
-  const float u = (float)((ou >> 8) + 1u) * (1.0f / 16777216.0f);
-  const float r = sqrtf(-2.0f * logf(u));
-  float s, c;
-  sincos_turns(oa, &s, &c);
-  *n0 = r * c;
-  *n1 = r * s;
-}
-
-// four normals of coordinate group q
-__device__ inline float4 noise4(uint64_t seed, uint32_t node, uint32_t version, uint64_t q) {
-  uint32_t o[4];
-  rfast_philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), node, version, (uint32_t)seed, (uint32_t)(seed >> 32), o);
-  float4 z;
-  box_muller(o[0], o[1], &z.x, &z.y);
-  box_muller(o[2], o[3], &z.z, &z.w);
-  return z;
-}
-template <int VEC> __device__ inline typename V<VEC>::T noise_at(uint64_t seed, uint32_t node, uint32_t ver, int64_t k);
-template <> __device__ inline float4 noise_at<4>(uint64_t seed, uint32_t node, uint32_t ver, int64_t k) {
-  return noise4(seed, node, ver, (uint64_t)k >> 2);
-}
-template <> __device__ inline float4 noise_at<-4>(uint64_t seed, uint32_t node, uint32_t ver, int64_t k) {
-  return noise4(seed, node, ver, (uint64_t)k >> 2);
-}
-template <> __device__ inline float noise_at<1>(uint64_t seed, uint32_t node, uint32_t ver, int64_t k) {
-  const float4 z = noise4(seed, node, ver, (uint64_t)k >> 2);
-  const int l = (int)(k & 3);
-  return l == 0 ? z.x : l == 1 ? z.y : l == 2 ? z.z : z.w;
-}
 
 // ------------------------------------------------------------------- kernel
 // MOM: the optimizer variant's heavy-ball buffer is in use (a template flag so that the
@@ -172,11 +70,11 @@ __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float
       }
   }
   if (kTrack) {
-    g_old = V<VEC>::ld(g_old_p);
     if (MODE == RFAST_MODE_FUSED) {
       h = V<VEC>::ld((const float*)s.prob.data0 + node_off);
       c = V<VEC>::ld((const float*)s.prob.data1 + node_off);
     } else {
+      g_old = V<VEC>::ld(g_old_p);
       g_new = V<VEC>::ld(g_new_p);
     }
     if (pushes) sig_cur = V<VEC>::ld(s.sigma_ring + ((size_t)i * M + slot_cur) * p + k);
@@ -224,12 +122,10 @@ __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float
   }
 
   if (MODE == RFAST_MODE_FUSED) {
-    // sampled gradient of the diagonal quadratic at the new point
-    g_new = mul(h, sub(x_new, c));
-    if (s.prob.noise_std != 0.0f)
-      g_new = fma_s(s.prob.noise_std, noise_at<VEC>(s.prob.noise_seed, (uint32_t)i, (uint32_t)(t_old + 1), k), g_new);
-    if (s.wd != 0.0f) g_new = fma_s(s.wd, x_new, g_new);  // weight decay is part of the sampled gradient
-    V<VEC>::st(g_new_p, g_new);
+    // New sample at the new point; the old sample is the same function of the old x and the
+    // old counter, so it is recomputed rather than kept in memory (2 words per coordinate less).
+    g_new = diag_sample<VEC>(s, h, c, x_new, i, t_old + 1, k);
+    g_old = diag_sample<VEC>(s, h, c, x_i, i, t_old, k);
   }
 
   // S2b: tracker sum over the in-edges of C; S4: buffer what was consumed.
@@ -268,21 +164,20 @@ __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float
   if (pushes) V<VEC>::st(s.sigma_ring + ((size_t)i * M + slot_new) * p + k, add(sig_cur, z_half));
 }
 
-// g^0 = h*(x^0 - c) + noise of sample version 0 (initialisation of Algorithm 1)
+// Writes the current sample of every node, g_i = sample(x_i, t_i), into g[t_i & 1][i]: the
+// initial gradient g^0 (t = 0, initialisation of Algorithm 1) and the copy that reads of
+// the G field return.
 template <int VEC>
-__global__ void __launch_bounds__(kThreads) rfast_diag_init_kernel(RfastDev s) {
+__global__ void __launch_bounds__(kThreads) rfast_diag_sample_kernel(RfastDev s) {
   const int i = blockIdx.y;
   const int64_t k = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * VEC;
   if (k >= s.p) return;
   const size_t off = (size_t)i * s.p + k;
   using T = typename V<VEC>::T;
+  const int t = s.t[i];
   const T h = V<VEC>::ld((const float*)s.prob.data0 + off);
   const T c = V<VEC>::ld((const float*)s.prob.data1 + off);
-  const T x0 = V<VEC>::ld(s.x + off);
-  T g = mul(h, sub(x0, c));
-  if (s.prob.noise_std != 0.0f) g = fma_s(s.prob.noise_std, noise_at<VEC>(s.prob.noise_seed, (uint32_t)i, 0u, k), g);
-  if (s.wd != 0.0f) g = fma_s(s.wd, x0, g);
-  V<VEC>::st(s.g + off, g);
+  V<VEC>::st(s.g + (size_t)(t & 1) * s.n * s.p + off, diag_sample<VEC>(s, h, c, V<VEC>::ld(s.x + off), i, t, k));
 }
 
 // Rebase of the running sums.  sigma_j only ever enters as a_ij*sigma_j - rho~_ij, so
@@ -357,8 +252,9 @@ __global__ void __launch_bounds__(kThreads) rfast_sync_step_kernel(RfastDev s, i
   const size_t off = (size_t)i * p + k;
   float* g_old_p = s.g + (size_t)(t_old & 1) * s.n * p + off;
   float* g_new_p = s.g + (size_t)((t_old + 1) & 1) * s.n * p + off;
-  T x_new, g_new;
+  T x_new, g_new, g_old;
   if (PHASE != 1) {
+    const T x_old = V<VEC>::ld(s.x + off);
     x_new = mul_s(s.r_self[i], V<VEC>::ld(s.v_ring + (size_t)i * s.M * p + k));
     for (int e = s.r_ptr[i]; e < s.r_ptr[i + 1]; ++e)
       x_new = fma_s(s.r_w[e], V<VEC>::ld(s.v_ring + (size_t)s.r_src[e] * s.M * p + k), x_new);
@@ -366,18 +262,16 @@ __global__ void __launch_bounds__(kThreads) rfast_sync_step_kernel(RfastDev s, i
     if (PHASE == 0) return;
     const T h = V<VEC>::ld((const float*)s.prob.data0 + off);
     const T c = V<VEC>::ld((const float*)s.prob.data1 + off);
-    g_new = mul(h, sub(x_new, c));
-    if (s.prob.noise_std != 0.0f)
-      g_new = fma_s(s.prob.noise_std, noise_at<VEC>(s.prob.noise_seed, (uint32_t)i, (uint32_t)(t_old + 1), k), g_new);
-    if (s.wd != 0.0f) g_new = fma_s(s.wd, x_new, g_new);
-    V<VEC>::st(g_new_p, g_new);
+    g_new = diag_sample<VEC>(s, h, c, x_new, i, t_old + 1, k);
+    g_old = diag_sample<VEC>(s, h, c, x_old, i, t_old, k);
   } else {
     g_new = V<VEC>::ld(g_new_p);
+    g_old = V<VEC>::ld(g_old_p);
   }
   T z_new = mul_s(s.c_self[i], V<VEC>::ld(sync_z(s, parity, i) + k));
   for (int e = s.c_ptr[i]; e < s.c_ptr[i + 1]; ++e)
     z_new = fma_s(s.c_w[e], V<VEC>::ld(sync_z(s, parity, s.c_src[e]) + k), z_new);
-  z_new = sub(add(z_new, g_new), V<VEC>::ld(g_old_p));
+  z_new = sub(add(z_new, g_new), g_old);
   V<VEC>::st(sync_z(s, parity ^ 1, i) + k, z_new);
 }
 
@@ -418,9 +312,9 @@ hipError_t rfast_diag_init_gradient(rfast_ctx* c) {
   const int64_t per_block = (int64_t)kThreads * (vec4 ? 4 : 1);
   const unsigned gx = (unsigned)((d.p + per_block - 1) / per_block);
   if (vec4)
-    hipLaunchKernelGGL(rfast_diag_init_kernel<4>, dim3(gx, d.n), dim3(kThreads), 0, c->stream, d);
+    hipLaunchKernelGGL(rfast_diag_sample_kernel<4>, dim3(gx, d.n), dim3(kThreads), 0, c->stream, d);
   else
-    hipLaunchKernelGGL(rfast_diag_init_kernel<1>, dim3(gx, d.n), dim3(kThreads), 0, c->stream, d);
+    hipLaunchKernelGGL(rfast_diag_sample_kernel<1>, dim3(gx, d.n), dim3(kThreads), 0, c->stream, d);
   return hipGetLastError();
 }
 

@@ -1,0 +1,123 @@
+// Vector access helpers and the counter-based Gaussian noise of the separable
+// objective, shared by the state-update and the diagnostics kernels (gfx950 only).
+#pragma once
+#include "rfast_internal.h"
+#include "rfast_philox.h"
+
+// ------------------------------------------------------------ vector helpers
+// VEC = 4: float4 per lane.  VEC = -4: the same with non-temporal (streaming)
+// loads and stores, used when the state is far larger than the caches, so
+// that lines with no reuse do not displace anything.  VEC = 1: scalar, p % 4 != 0.
+typedef float nt_f4 __attribute__((ext_vector_type(4)));
+template <int VEC> struct V;
+template <> struct V<4> {
+  using T = float4;
+  static constexpr int W = 4;
+  static __device__ inline T ld(const float* p) { return *reinterpret_cast<const float4*>(p); }
+  static __device__ inline void st(float* p, T v) { *reinterpret_cast<float4*>(p) = v; }
+};
+template <> struct V<-4> {
+  using T = float4;
+  static constexpr int W = 4;
+  static __device__ inline T ld(const float* p) {
+    const nt_f4 t = __builtin_nontemporal_load(reinterpret_cast<const nt_f4*>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
+  }
+  static __device__ inline void st(float* p, T v) {
+    const nt_f4 t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<nt_f4*>(p));
+  }
+};
+template <> struct V<1> {
+  using T = float;
+  static constexpr int W = 1;
+  static __device__ inline T ld(const float* p) { return *p; }
+  static __device__ inline void st(float* p, T v) { *p = v; }
+};
+__device__ inline float4 fma_s(float a, float4 b, float4 c) {
+  return make_float4(fmaf(a, b.x, c.x), fmaf(a, b.y, c.y), fmaf(a, b.z, c.z), fmaf(a, b.w, c.w));
+}
+__device__ inline float fma_s(float a, float b, float c) { return fmaf(a, b, c); }
+__device__ inline float4 mul_s(float a, float4 b) { return make_float4(a * b.x, a * b.y, a * b.z, a * b.w); }
+__device__ inline float mul_s(float a, float b) { return a * b; }
+__device__ inline float4 add(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
+__device__ inline float add(float a, float b) { return a + b; }
+__device__ inline float4 sub(float4 a, float4 b) { return make_float4(a.x - b.x, a.y - b.y, a.z - b.z, a.w - b.w); }
+__device__ inline float sub(float a, float b) { return a - b; }
+__device__ inline float4 mul(float4 a, float4 b) { return make_float4(a.x * b.x, a.y * b.y, a.z * b.z, a.w * b.w); }
+__device__ inline float mul(float a, float b) { return a * b; }
+
+// ------------------------------------------------- counter-based Gaussian noise
+// sin and cos of 2*pi*w/2^32.  The octant comes from the top three bits, so the
+// reduction is exact; the remainder a in [-pi/8, pi/8] goes through Taylor
+// polynomials whose truncation error is below 1e-8.
+__device__ inline void sincos_turns(uint32_t w, float* s, float* c) {
+  const uint32_t q = ((w >> 28) + 1u) >> 1;                // nearest multiple of pi/4 (0..8)
+  const int32_t rem = (int32_t)(w - (q << 29));            // signed offset from q*pi/4 (mod 2^32), |rem| <= 2^28
+  const float a = (float)rem * (6.283185307179586f / 4294967296.0f);
+  const float a2 = a * a;
+  float sp = fmaf(a2, fmaf(a2, fmaf(a2, fmaf(a2, 2.7557319e-6f, -1.9841270e-4f), 8.3333333e-3f), -1.6666667e-1f), 1.0f) * a;
+  float cp = fmaf(a2, fmaf(a2, fmaf(a2, fmaf(a2, 2.4801587e-5f, -1.3888889e-3f), 4.1666667e-2f), -0.5f), 1.0f);
+  // rotate by q * pi/4
+  const float h = 0.70710678118654752f;
+  float sq, cq;
+  switch (q & 7u) {
+    case 0: sq = 0.f; cq = 1.f; break;
+    case 1: sq = h; cq = h; break;
+    case 2: sq = 1.f; cq = 0.f; break;
+    case 3: sq = h; cq = -h; break;
+    case 4: sq = 0.f; cq = -1.f; break;
+    case 5: sq = -h; cq = -h; break;
+    case 6: sq = -1.f; cq = 0.f; break;
+    default: sq = -h; cq = h; break;
+  }
+  *s = fmaf(sq, cp, cq * sp);
+  *c = fmaf(cq, cp, -sq * sp);
+}
+
+__device__ inline void box_muller(uint32_t ou, uint32_t oa, float* n0, float* n1) {
+  const float u = (float)((ou >> 8) + 1u) * (1.0f / 16777216.0f);
+  const float r = sqrtf(-2.0f * logf(u));
+  float s, c;
+  sincos_turns(oa, &s, &c);
+  *n0 = r * c;
+  *n1 = r * s;
+}
+
+// four normals of coordinate group q
+__device__ inline float4 noise4(uint64_t seed, uint32_t node, uint32_t version, uint64_t q) {
+  uint32_t o[4];
+  rfast_philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), node, version, (uint32_t)seed, (uint32_t)(seed >> 32), o);
+  float4 z;
+  box_muller(o[0], o[1], &z.x, &z.y);
+  box_muller(o[2], o[3], &z.z, &z.w);
+  return z;
+}
+template <int VEC> __device__ inline typename V<VEC>::T noise_at(uint64_t seed, uint32_t node, uint32_t ver, int64_t k);
+template <> __device__ inline float4 noise_at<4>(uint64_t seed, uint32_t node, uint32_t ver, int64_t k) {
+  return noise4(seed, node, ver, (uint64_t)k >> 2);
+}
+template <> __device__ inline float4 noise_at<-4>(uint64_t seed, uint32_t node, uint32_t ver, int64_t k) {
+  return noise4(seed, node, ver, (uint64_t)k >> 2);
+}
+template <> __device__ inline float noise_at<1>(uint64_t seed, uint32_t node, uint32_t ver, int64_t k) {
+  const float4 z = noise4(seed, node, ver, (uint64_t)k >> 2);
+  const int l = (int)(k & 3);
+  return l == 0 ? z.x : l == 1 ? z.y : l == 2 ? z.z : z.w;
+}
+
+
+// ------------------------------------------- sample of the diagonal quadratic
+// grad f_i(x; zeta^version) = h (x - c) + noise_std * N(0, I)[node, version] (+ weight decay * x).
+// A pure function of (x, node, version): the "stored" sample of step S2b is recomputed
+// from the node's own x and counter wherever it is needed, with these very
+// instructions, instead of being written to and read back from memory.
+template <int VEC>
+__device__ inline typename V<VEC>::T diag_sample(const RfastDev& s, typename V<VEC>::T h, typename V<VEC>::T c,
+                                                 typename V<VEC>::T x, int node, int version, int64_t k) {
+  typename V<VEC>::T g = mul(h, sub(x, c));
+  if (s.prob.noise_std != 0.0f)
+    g = fma_s(s.prob.noise_std, noise_at<VEC>(s.prob.noise_seed, (uint32_t)node, (uint32_t)version, k), g);
+  if (s.wd != 0.0f) g = fma_s(s.wd, x, g);  // weight decay is part of the sampled gradient
+  return g;
+}

@@ -44,14 +44,15 @@ def algorithmic_bytes_per_round(w, active_counts, layout=False):
 
 def measured_traffic(workload_name):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if any."""
-    path = os.path.join(ROOT, "profiles", f"{workload_name}_state_kernel_hbm_traffic.md")
-    try:
-        with open(path) as f:
-            for line in f:
-                if line.startswith("traffic_bytes_per_launch:"):
-                    return float(line.split(":")[1])
-    except OSError:
-        pass
+    for suffix in ("hbm_traffic", "stats"):
+        path = os.path.join(ROOT, "profiles", f"{workload_name}_state_kernel_{suffix}.md")
+        try:
+            with open(path) as f:
+                for line in f:
+                    if line.startswith("traffic_bytes_per_launch:"):
+                        return float(line.split(":")[1])
+        except OSError:
+            pass
     return None
 
 

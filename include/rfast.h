@@ -203,6 +203,20 @@ int rfast_run(rfast_ctx* ctx, int32_t rounds, const uint8_t* d_active, const int
 int rfast_run_generated(rfast_ctx* ctx, int32_t rounds, uint64_t seed, const float* d_p_active,
                         int32_t max_delay, float p_drop, float gamma);
 
+/* Event-driven form, the global view of Algorithm 2 taken literally: `iterations`
+ * global iterations k (k = RFAST_ROUND, counted from rfast_init), each activating
+ * exactly one agent i^k, with delays counted in global iterations.  i^k is drawn on
+ * the device: u = word(6, k, 0) (the generator of rfast_run_generated), and agent i
+ * is taken when cdf[i-1] <= u < cdf[i], where cdf[i] = min(floor(2^32 * (w_0 + .. +
+ * w_i) / (w_0 + .. + w_{n-1})), 2^32 - 1) in double precision and cdf[-1] = 0; u =
+ * 2^32 - 1 goes to the last agent if its weight is positive (to nobody otherwise: an
+ * empty iteration).  Delays, losses and sample rows are those of rfast_run_generated.
+ * Slow agents (stragglers) are agents with a small weight.
+ * host_weights: HOST fp32 [n], finite, >= 0, not all zero (RFAST_ERANGE), or NULL for
+ * uniform selection; consumed before return. */
+int rfast_run_events(rfast_ctx* ctx, int32_t iterations, uint64_t seed, const float* host_weights,
+                     int32_t max_delay, float p_drop, float gamma);
+
 /* on != 0: rfast_run_generated replays a HIP graph of 16 generated rounds (one
  * launch per 16 rounds instead of 4-7 per round) whenever at least 16 rounds are
  * asked for, profiling is off and no rebase interval is set; the remaining rounds

@@ -15,6 +15,11 @@ sampled).  The schedule of round r is a pure function of (seed, r):
   h-bit half R with key K: t = (R * 0x9E3779B1 + K) mod 2^32; t ^= t >> 15;
   t = (t * 0x85EBCA77) mod 2^32; F = t >> (32 - h).
 
+Event-driven form (Algorithm 2 of the paper: exactly one agent i^k per global
+iteration k): u = word(6, k, 0); agent i is taken when cdf[i-1] <= u < cdf[i],
+cdf[i] = min(floor(2^32 (w_0 + .. + w_i) / sum w), 2^32 - 1) in double precision,
+cdf[-1] = 0; u = 2^32 - 1 goes to the last agent if its weight is positive.
+
 Only tests may import this file; it shares no code with the HIP library.
 """
 import numpy as np
@@ -79,4 +84,30 @@ def generate_round(seed, r, n, eR, eC, p_active, d_max, p_drop, batch=0, samples
     }
     if batch > 0:
         out["batch_idx"] = np.stack([sample_rows(seed, r, i, batch, samples) for i in range(n)])
+    return out
+
+
+def selection_thresholds(weights, n):
+    w = np.ones(n, dtype=np.float64) if weights is None else np.asarray(weights, dtype=np.float32).astype(np.float64)
+    total = 0.0
+    for v in w:          # the same left-to-right sums as a plain loop
+        total += float(v)
+    cdf, cum = np.empty(n, dtype=np.uint64), 0.0
+    for i, v in enumerate(w):
+        cum += float(v)
+        cdf[i] = min(int(np.floor(cum / total * 4294967296.0)), 0xFFFFFFFF)
+    return cdf
+
+
+def generate_event(seed, k, n, eR, eC, weights, d_max, p_drop, batch=0, samples=0):
+    """Schedule of global iteration k: one-hot `active`, the rest as in generate_round."""
+    out = generate_round(seed, k, n, eR, eC, 0.0, d_max, p_drop, batch, samples)
+    cdf = selection_thresholds(weights, n)
+    u = int(_words(seed, 6, k, 1)[0])
+    active = np.zeros(n, dtype=np.uint8)
+    for i in range(n):
+        lo, hi = (int(cdf[i - 1]) if i else 0), int(cdf[i])
+        if u >= lo and (u < hi or (i == n - 1 and hi > lo)):
+            active[i] = 1
+    out["active"] = active
     return out

@@ -33,7 +33,7 @@ RFAST_FIELDS = {"X": 0, "Z": 1, "G": 2, "V_RING": 3, "RHO_RING": 4, "RHO_TILDE":
                 "TAU_C": 8, "SLOT_R": 9, "SLOT_C": 10, "ROUND": 11, "SIGMA_RING": 12, "DELIV_R": 13, "DELIV_C": 14,
                 "T_HIST": 15, "SCHED_ACTIVE": 16, "SCHED_DELAY_R": 17, "SCHED_DELAY_C": 18, "SCHED_DROP_R": 19,
                 "SCHED_DROP_C": 20, "SCHED_BATCH": 21, "MOMENTUM": 22}
-EXPORTS = ["rfast_common_roots", "rfast_workspace_bytes", "rfast_create", "rfast_init", "rfast_round", "rfast_run", "rfast_run_generated", "rfast_use_graphs", "rfast_sync_round", "rfast_sync_run", "rfast_rebase", "rfast_set_rebase_interval", "rfast_set_optimizer", "rfast_set_gamma_schedule", "rfast_check",
+EXPORTS = ["rfast_common_roots", "rfast_workspace_bytes", "rfast_create", "rfast_init", "rfast_round", "rfast_run", "rfast_run_generated", "rfast_run_events", "rfast_use_graphs", "rfast_sync_round", "rfast_sync_run", "rfast_rebase", "rfast_set_rebase_interval", "rfast_set_optimizer", "rfast_set_gamma_schedule", "rfast_check",
            "rfast_read_state", "rfast_write_state", "rfast_diagnostics", "rfast_profile_enable", "rfast_kernel_time", "rfast_last_error",
            "rfast_destroy"]
 
@@ -62,6 +62,8 @@ def lib():
     L.rfast_run.argtypes = [vp, i32, vp, vp, vp, vp, vp, C.c_float, vp]
     L.rfast_run_generated.restype = C.c_int
     L.rfast_run_generated.argtypes = [vp, i32, C.c_uint64, vp, i32, C.c_float, C.c_float]
+    L.rfast_run_events.restype = C.c_int
+    L.rfast_run_events.argtypes = [vp, i32, C.c_uint64, vp, i32, C.c_float, C.c_float]
     L.rfast_use_graphs.restype = C.c_int
     L.rfast_use_graphs.argtypes = [vp, i32]
     L.rfast_sync_round.restype = C.c_int
@@ -154,6 +156,12 @@ def rfast_run(ctx, rounds, active, delay_R, delay_C, drop_R, drop_C, gamma, batc
 
 def rfast_run_generated(ctx, rounds, seed, p_active, max_delay, p_drop, gamma):
     _chk(lib().rfast_run_generated(ctx, rounds, seed, _dev_ptr(p_active), max_delay, p_drop, gamma), ctx)
+
+
+def rfast_run_events(ctx, iterations, seed, weights, max_delay, p_drop, gamma):
+    """weights: host numpy float32 [n] or None (uniform)."""
+    _chk(lib().rfast_run_events(ctx, iterations, seed, None if weights is None else _np_ptr(weights), max_delay, p_drop,
+                                gamma), ctx)
 
 
 def rfast_use_graphs(ctx, on=True):
@@ -293,6 +301,13 @@ class RFast:
                 or not p_active.is_contiguous():
             raise RFastError(-1, "p_active: need a contiguous float32 device tensor of n probabilities")
         rfast_run_generated(self.ctx, rounds, seed, p_active, max_delay, p_drop, gamma)
+
+    def run_events(self, iterations, seed, weights, max_delay, p_drop, gamma):
+        if weights is not None:
+            weights = np.ascontiguousarray(weights, dtype=np.float32)
+            if weights.shape != (self.n,):
+                raise RFastError(-1, "weights: need n selection weights")
+        rfast_run_events(self.ctx, iterations, seed, weights, max_delay, p_drop, gamma)
 
     def sync_run(self, rounds, gamma, batch_idx=None):
         if self.prob.kind != 0 and self.prob.batch > 0:

@@ -34,7 +34,7 @@ struct Offsets {
   size_t r_ptr, r_src, r_dst, r_w, r_self, c_ptr, c_src, c_dst, c_w, c_self, co_ptr, co_eid, co_w, ro_ptr, ro_eid;
   size_t t, t_hist, tau_r, tau_c, deliv_r, deliv_c, round_no, err;
   size_t n_active, active_list, plan_t, slot_r, slot_c, skip_c;
-  size_t gen_active, gen_delay_r, gen_delay_c, gen_drop_r, gen_drop_c, gen_batch;
+  size_t gen_active, gen_delay_r, gen_delay_c, gen_drop_r, gen_drop_c, gen_batch, gen_cdf;
   size_t xbar, resid, gscratch, diag;
   size_t total;
 };
@@ -99,6 +99,7 @@ Offsets layout(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, cons
   o.gen_drop_r = L.take(eR);
   o.gen_drop_c = L.take(eC);
   o.gen_batch = L.take((size_t)n * (size_t)(prob->kind == RFAST_OBJ_DIAG_QUADRATIC ? 0 : prob->batch) * 4);
+  o.gen_cdf = L.take(n * 4);
   o.xbar = L.take(vec);
   o.resid = L.take(rfast_gemv_scratch_floats(n, prob) * 4);
   o.gscratch = L.take(rfast_softmax_scratch_bytes(n, prob));
@@ -312,7 +313,7 @@ int build_graph(rfast_ctx* c, uint64_t seed, const float* d_p_active, int32_t ma
   const int64_t round_before = c->host_round;  // capture enqueues nothing: the counter moves when the graph is launched
   int rc = RFAST_OK;
   for (int32_t r = 0; r < kGraphRounds && rc == RFAST_OK; ++r) {
-    const hipError_t g = rfast_launch_generate(c, seed, d_p_active, max_delay, p_drop);
+    const hipError_t g = rfast_launch_generate(c, seed, d_p_active, max_delay, p_drop, false);
     if (g != hipSuccess) rc = hipfail(c, g, "schedule generator launch");
     else rc = rfast_round(c, d.gen_active, d.gen_delay_r, d.gen_delay_c, d.gen_drop_r, d.gen_drop_c, gamma, d.gen_batch);
   }
@@ -438,6 +439,7 @@ int rfast_create(rfast_ctx** out, int32_t n, int64_t p, const int32_t* R_rowptr,
   d.gen_active = (uint8_t*)(b + o.gen_active); d.gen_delay_r = (int32_t*)(b + o.gen_delay_r);
   d.gen_delay_c = (int32_t*)(b + o.gen_delay_c); d.gen_drop_r = (uint8_t*)(b + o.gen_drop_r);
   d.gen_drop_c = (uint8_t*)(b + o.gen_drop_c); d.gen_batch = (int32_t*)(b + o.gen_batch);
+  d.gen_cdf = (uint32_t*)(b + o.gen_cdf);
   d.xbar = (float*)(b + o.xbar);
   d.mom = nullptr; d.beta = 0.f; d.wd = 0.f;
   d.resid = (float*)(b + o.resid); d.gscratch = (void*)(b + o.gscratch);
@@ -597,11 +599,47 @@ int rfast_run_generated(rfast_ctx* c, int32_t rounds, uint64_t seed, const float
       rounds -= kGraphRounds;
       continue;
     }
-    const hipError_t e = rfast_launch_generate(c, seed, d_p_active, max_delay, p_drop);
+    const hipError_t e = rfast_launch_generate(c, seed, d_p_active, max_delay, p_drop, false);
     if (e != hipSuccess) return hipfail(c, e, "schedule generator launch");
     const int rc = rfast_round(c, d.gen_active, d.gen_delay_r, d.gen_delay_c, d.gen_drop_r, d.gen_drop_c, gamma, d.gen_batch);
     if (rc != RFAST_OK) return rc;
     --rounds;
+  }
+  return RFAST_OK;
+}
+
+int rfast_run_events(rfast_ctx* c, int32_t iterations, uint64_t seed, const float* host_weights, int32_t max_delay,
+                     float p_drop, float gamma) {
+  if (!c) return RFAST_EINVAL;
+  if (iterations < 0) return fail(c, RFAST_EINVAL, "iterations < 0");
+  const RfastDev& d = c->d;
+  if (max_delay < 0 || max_delay > d.d_max) return fail(c, RFAST_ERANGE, "max_delay must lie in [0, D - burst + 1]");
+  if (!(p_drop >= 0.f && p_drop <= 1.f)) return fail(c, RFAST_ERANGE, "p_drop must lie in [0, 1]");
+  if (!std::isfinite(gamma)) return fail(c, RFAST_EINVAL, "gamma is not finite");
+  if (c->needs_init) return fail(c, RFAST_EINVAL, "rfast_init must follow rfast_set_optimizer");
+  // selection thresholds: node i is drawn when cdf[i-1] <= u < cdf[i], u a 32-bit word
+  std::vector<uint32_t> cdf(d.n);
+  double total = 0.0;
+  for (int i = 0; i < d.n; ++i) {
+    const double w = host_weights ? (double)host_weights[i] : 1.0;
+    if (!(w >= 0.0) || !std::isfinite(w)) return fail(c, RFAST_ERANGE, "selection weights must be finite and >= 0");
+    total += w;
+  }
+  if (!(total > 0.0)) return fail(c, RFAST_ERANGE, "selection weights sum to zero");
+  double cum = 0.0;
+  for (int i = 0; i < d.n; ++i) {
+    cum += host_weights ? (double)host_weights[i] : 1.0;
+    const double thr = std::floor(cum / total * 4294967296.0);
+    cdf[i] = thr >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)thr;
+  }
+  hipError_t e = hipMemcpyAsync(d.gen_cdf, cdf.data(), (size_t)d.n * 4, hipMemcpyHostToDevice, c->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);  // the host vector dies with this scope
+  if (e != hipSuccess) return hipfail(c, e, "uploading selection thresholds");
+  for (int32_t k = 0; k < iterations; ++k) {
+    e = rfast_launch_generate(c, seed, nullptr, max_delay, p_drop, true);
+    if (e != hipSuccess) return hipfail(c, e, "schedule generator launch");
+    const int rc = rfast_round(c, d.gen_active, d.gen_delay_r, d.gen_delay_c, d.gen_drop_r, d.gen_drop_c, gamma, d.gen_batch);
+    if (rc != RFAST_OK) return rc;
   }
   return RFAST_OK;
 }

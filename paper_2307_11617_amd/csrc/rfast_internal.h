@@ -70,6 +70,7 @@ struct RfastDev {
   uint8_t* gen_drop_r;    // [eR]
   uint8_t* gen_drop_c;    // [eC]
   int32_t* gen_batch;     // [n][batch]
+  uint32_t* gen_cdf;      // [n] selection thresholds of the event-driven mode (one node per iteration)
   float* xbar;            // [p] node average, written by the diagnostics kernel
   // optimizer variant: heavy-ball buffers m_i [n][p] (caller's memory, NULL when beta == 0)
   float* mom;
@@ -113,7 +114,7 @@ hipError_t rfast_launch_resolve(rfast_ctx* c, const uint8_t* active, const int32
                                 const int32_t* delay_C, const uint8_t* drop_R, const uint8_t* drop_C);
 hipError_t rfast_launch_state(rfast_ctx* c, int mode, float gamma);
 hipError_t rfast_launch_rebase(rfast_ctx* c);
-hipError_t rfast_launch_generate(rfast_ctx* c, uint64_t seed, const float* d_p_active, int d_max, float p_drop);
+hipError_t rfast_launch_generate(rfast_ctx* c, uint64_t seed, const float* d_p_active, int d_max, float p_drop, bool events);
 hipError_t rfast_launch_sync(rfast_ctx* c, int phase, float gamma, int parity);
 hipError_t rfast_launch_init_grad(rfast_ctx* c, const int32_t* batch_idx0);
 hipError_t rfast_diag_init_gradient(rfast_ctx* c);  // separable objective: g[t_i & 1][i] = sample(x_i, t_i) for every node

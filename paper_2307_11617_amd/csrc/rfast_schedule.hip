@@ -5,6 +5,9 @@
 //
 //   word(stream, r, e) = Philox4x32-10(counter = (e div 4, stream, r, 0), key = seed)[e mod 4]
 //   active[i]  = word(0, r, i) < floor(p_active[i] * 2^32)
+//                event-driven mode (Algorithm 2: one agent i^k per global iteration k = r):
+//                u = word(6, r, 0); active[i] = cdf[i-1] <= u < cdf[i]  (cdf[-1] = 0, the last
+//                threshold closed at 2^32 - 1), cdf = 32-bit cumulative selection thresholds
 //   delay_R[e] = word(1, r, e) mod (d_max + 1)          delay_C[e]: stream 2
 //   drop_R[e]  = word(3, r, e) < floor(p_drop * 2^32)     drop_C[e]: stream 4
 //   rows of node i: perm(b), b = 0..B-1; perm = 4-round balanced Feistel network on
@@ -28,11 +31,17 @@ __device__ inline unsigned long long threshold(float prob) {
 }
 
 __global__ void __launch_bounds__(256) rfast_generate_kernel(RfastDev s, uint64_t seed, const float* p_active, int d_max,
-                                                             float p_drop, int B) {
+                                                             float p_drop, int B, bool events) {
   const uint32_t r = (uint32_t)*s.round_no;
   int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (q < s.n) {
-    s.gen_active[q] = (unsigned long long)word(seed, 0u, r, (uint32_t)q) < threshold(p_active[q]);
+    if (events) {
+      const uint32_t u = word(seed, 6u, r, 0u);
+      const uint32_t lo = q ? s.gen_cdf[q - 1] : 0u, hi = s.gen_cdf[q];
+      s.gen_active[q] = u >= lo && (u < hi || (q == s.n - 1 && hi > lo));
+    } else {
+      s.gen_active[q] = (unsigned long long)word(seed, 0u, r, (uint32_t)q) < threshold(p_active[q]);
+    }
     return;
   }
   q -= s.n;
@@ -74,11 +83,11 @@ __global__ void __launch_bounds__(256) rfast_generate_kernel(RfastDev s, uint64_
 
 }  // namespace
 
-hipError_t rfast_launch_generate(rfast_ctx* c, uint64_t seed, const float* d_p_active, int d_max, float p_drop) {
+hipError_t rfast_launch_generate(rfast_ctx* c, uint64_t seed, const float* d_p_active, int d_max, float p_drop, bool events) {
   const RfastDev& d = c->d;
   const int B = d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC ? 0 : d.prob.batch;
   const int64_t total = (int64_t)d.n + 2 * (int64_t)d.eR + 2 * (int64_t)d.eC + (int64_t)d.n * B;
   hipLaunchKernelGGL(rfast_generate_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, c->stream, d, seed,
-                     d_p_active, d_max, p_drop, B);
+                     d_p_active, d_max, p_drop, B, events);
   return hipGetLastError();
 }

@@ -97,3 +97,44 @@ def test_graph_replay_equals_eager_launches(which):
     eager.run_generated(20, 8, dev_p, d_max, p_drop, w.gamma)
     graph.run_generated(20, 8, dev_p, d_max, p_drop, w.gamma)
     assert np.array_equal(eager.read("X"), graph.read("X"))
+
+
+@pytest.mark.parametrize("which", ["diag", "logistic"])
+def test_event_driven_run_is_algorithm_2_taken_literally(which):
+    """One agent per global iteration, delays in global iterations: the device draws i^k,
+    the oracle activates that very agent with Algorithm 2's steps (its `activate`, through
+    a round whose mask is one-hot).  Stragglers are agents with small selection weights."""
+    if which == "diag":
+        w = configs.config3(p=1028, rounds=0)
+        d_max, p_drop, weights = 16, 0.2, np.where(np.arange(w.n) % 9 == 0, 0.05, 1.0).astype(np.float32)
+        w.gamma = 0.002
+    else:
+        w = configs.config1(p=132, samples=64, batch=16, rounds=0)
+        d_max, p_drop, weights = 8, 0.05, None
+    seed = 4242
+    orc = harness.make_oracle(w)
+    gpu = harness.make_gpu(w)
+    gpu.init(None, w.sched.initial_batch())
+    drawn = np.zeros(w.n, dtype=np.int64)
+    for chunk in range(4):
+        gpu.run_events(150, seed, weights, d_max, p_drop, w.gamma)
+        for k in range(chunk * 150, chunk * 150 + 150):
+            q = sg.generate_event(seed, k, w.n, w.R.nnz_off, w.C.nnz_off, weights, d_max, p_drop, w.sched.batch, w.sched.samples)
+            assert q["active"].sum() == 1
+            drawn += q["active"]
+            orc.round(q["active"], q["delay_R"], q["delay_C"], q["drop_R"], q["drop_C"], w.gamma, q["batch_idx"])
+        gpu.check()
+        assert np.array_equal(gpu.read("SCHED_ACTIVE"), q["active"])       # the last iteration's draw
+        sl = orc.slots()
+        assert np.array_equal(gpu.read("T_NODE"), sl["t"]) and int(gpu.read("T_NODE").sum()) == (chunk + 1) * 150
+        assert np.array_equal(gpu.read("TAU_R"), sl["tau_v"]) and np.array_equal(gpu.read("TAU_C"), sl["tau_rho"])
+        gn = float(np.linalg.norm(orc.g))
+        ex = harness.rel_l2(gpu.read("X"), orc.x)
+        ez = harness.rel_l2(gpu.read("Z"), orc.z, 1e-3 * gn)
+        assert ex <= w.tol and ez <= w.tol, (chunk, ex, ez)
+    if weights is not None:
+        assert drawn[np.arange(w.n) % 9 == 0].sum() < 0.05 * drawn.sum()    # the slow agents are rarely drawn
+    with pytest.raises(Exception):
+        gpu.run_events(1, seed, np.zeros(w.n, np.float32), d_max, p_drop, w.gamma)
+    with pytest.raises(Exception):
+        gpu.run_events(1, seed, weights, w.D, p_drop, w.gamma)

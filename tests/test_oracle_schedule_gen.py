@@ -48,3 +48,26 @@ def test_sampled_rows_are_a_permutation_prefix():
     # spread: mean of the first 256 of 2048 close to the middle
     assert abs(full[:256].mean() - 1023.5) < 120
     assert not np.array_equal(sg.sample_rows(9, 0, 0, 32, 2048), sg.sample_rows(9, 0, 1, 32, 2048))
+
+
+def test_event_selection_is_one_hot_with_the_stated_frequencies():
+    """Algorithm 2 activates exactly one agent per global iteration; the empirical
+    frequencies follow the weights; zero-weight agents are never drawn."""
+    n, K = 12, 6000
+    w = np.array([0, 1, 1, 4, 0.5, 0, 2, 1, 1, 1, 0.25, 0], dtype=np.float32)
+    counts = np.zeros(n)
+    for k in range(K):
+        q = sg.generate_event(5, k, n, 20, 20, w, 3, 0.1)
+        assert q["active"].sum() == 1
+        counts += q["active"]
+    assert counts[w == 0].sum() == 0
+    np.testing.assert_allclose(counts / K, w / w.sum(), atol=4 * np.sqrt(0.25 / K))
+    uni = np.zeros(5)
+    for k in range(3000):
+        uni += sg.generate_event(6, k, 5, 4, 4, None, 0, 0.0)["active"]
+    np.testing.assert_allclose(uni / 3000, 0.2, atol=0.03)
+    # thresholds: monotone, closed at the top; delays and drops are those of the round generator
+    cdf = sg.selection_thresholds(w, n)
+    assert np.all(np.diff(cdf.astype(np.int64)) >= 0) and int(cdf[-1]) == 0xFFFFFFFF
+    a, b = sg.generate_event(5, 9, n, 20, 20, w, 3, 0.1), sg.generate_round(5, 9, n, 20, 20, 0.5, 3, 0.1)
+    assert all(np.array_equal(a[k], b[k]) for k in ("delay_R", "delay_C", "drop_R", "drop_C"))

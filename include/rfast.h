@@ -98,7 +98,8 @@ typedef enum rfast_field {
                           read; writing it is accepted and has no effect                              */
   RFAST_V_RING = 3,    /* fp32 [n][D+2][p]  slot s of node j = version t, t mod (D+2) == s */
   RFAST_RHO_RING = 4,  /* fp32 [nnzC_off][D+2][p]  sender-side running sums rho_ij = a_ij * sigma_j (expanded on read) */
-  RFAST_RHO_TILDE = 5, /* fp32 [nnzC_off][p]  receiver-side buffers                */
+  RFAST_RHO_TILDE = 5, /* fp32 [nnzC_off][p]  receiver-side buffers (assembled on read: a buffer whose version
+                          is still in its sender's ring is taken from there, cf. RFAST_SIGMA_RING)   */
   RFAST_T_NODE = 6,    /* int32 [n]  local iteration counters t_i                  */
   RFAST_TAU_R = 7,     /* int32 [nnzR_off]  largest stamp picked up per R edge     */
   RFAST_TAU_C = 8,     /* int32 [nnzC_off]                                         */

@@ -33,7 +33,7 @@ struct Offsets {
   size_t x, z, g, v_ring, sigma_ring, rho_tilde;
   size_t r_ptr, r_src, r_dst, r_w, r_self, c_ptr, c_src, c_dst, c_w, c_self, co_ptr, co_eid, co_w, ro_ptr, ro_eid;
   size_t t, t_hist, tau_r, tau_c, deliv_r, deliv_c, round_no, err;
-  size_t n_active, active_list, plan_t, slot_r, slot_c, skip_c;
+  size_t n_active, active_list, plan_t, slot_r, slot_c, plan_c, node_spill;
   size_t gen_active, gen_delay_r, gen_delay_c, gen_drop_r, gen_drop_c, gen_batch, gen_cdf;
   size_t xbar, resid, gscratch, diag;
   size_t total;
@@ -92,7 +92,8 @@ Offsets layout(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, cons
   o.plan_t = L.take(n * 4);
   o.slot_r = L.take(eR * 4);
   o.slot_c = L.take(eC * 4);
-  o.skip_c = L.take(eC);
+  o.plan_c = L.take(eC * 4);
+  o.node_spill = L.take(n);
   o.gen_active = L.take(n);
   o.gen_delay_r = L.take(eR * 4);
   o.gen_delay_c = L.take(eC * 4);
@@ -435,7 +436,7 @@ int rfast_create(rfast_ctx** out, int32_t n, int64_t p, const int32_t* R_rowptr,
   d.round_no = (int32_t*)(b + o.round_no); d.err = (int32_t*)(b + o.err);
   d.n_active = (int32_t*)(b + o.n_active); d.active_list = (int32_t*)(b + o.active_list);
   d.plan_t = (int32_t*)(b + o.plan_t); d.slot_r = (int32_t*)(b + o.slot_r); d.slot_c = (int32_t*)(b + o.slot_c);
-  d.skip_c = (uint8_t*)(b + o.skip_c);
+  d.plan_c = (int32_t*)(b + o.plan_c); d.node_spill = (uint8_t*)(b + o.node_spill);
   d.gen_active = (uint8_t*)(b + o.gen_active); d.gen_delay_r = (int32_t*)(b + o.gen_delay_r);
   d.gen_delay_c = (int32_t*)(b + o.gen_delay_c); d.gen_drop_r = (uint8_t*)(b + o.gen_drop_r);
   d.gen_drop_c = (uint8_t*)(b + o.gen_drop_c); d.gen_batch = (int32_t*)(b + o.gen_batch);
@@ -485,7 +486,7 @@ int rfast_init(rfast_ctx* c, const float* d_x0, const int32_t* d_batch_idx0) {
     chk(hipMemsetAsync(d.rho_tilde, 0, (size_t)d.eC * vec, c->stream));
     chk(hipMemsetAsync(d.tau_c, 0, (size_t)d.eC * 4, c->stream));
     chk(hipMemsetAsync(d.slot_c, 0xff, (size_t)d.eC * 4, c->stream));
-    chk(hipMemsetAsync(d.skip_c, 1, (size_t)d.eC, c->stream));
+    chk(hipMemsetAsync(d.plan_c, 0, (size_t)d.eC * 4, c->stream));
     // only version 0 (slot 0) counts as delivered
     chk(hipMemsetAsync(d.deliv_c, 0, (size_t)d.eC * 8, c->stream));
   }
@@ -782,6 +783,23 @@ int rfast_read_state(rfast_ctx* c, int32_t field, void* host_dst, size_t bytes) 
       float* dst = (float*)host_dst + (size_t)q * ring;
       e = hipMemcpy(dst, d.sigma_ring + (size_t)src_h[q] * ring, ring * 4, hipMemcpyDeviceToHost);
       for (size_t k = 0; k < ring; ++k) dst[k] = w_h[q] * dst[k];
+    }
+  } else if (field == RFAST_RHO_TILDE) {
+    // rho~_ij = a_ij * sigma_j[tau_ij] lives in the sender's ring while tau_ij >= t_j - D and in the
+    // array otherwise: put the two together
+    std::vector<int32_t> src_h(d.eC), tau_h(d.eC), t_h(d.n);
+    std::vector<float> w_h(d.eC);
+    e = hipMemcpy(host_dst, d.rho_tilde, bytes, hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(src_h.data(), d.c_src, (size_t)d.eC * 4, hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(w_h.data(), d.c_w, (size_t)d.eC * 4, hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(tau_h.data(), d.tau_c, (size_t)d.eC * 4, hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(t_h.data(), d.t, (size_t)d.n * 4, hipMemcpyDeviceToHost);
+    for (int q = 0; q < d.eC && e == hipSuccess; ++q) {
+      const int j = src_h[q];
+      if (tau_h[q] < t_h[j] - (d.M - 2)) continue;
+      float* dst = (float*)host_dst + (size_t)q * d.p;
+      e = hipMemcpy(dst, d.sigma_ring + ((size_t)j * d.M + tau_h[q] % d.M) * d.p, (size_t)d.p * 4, hipMemcpyDeviceToHost);
+      for (int64_t k = 0; k < d.p; ++k) dst[k] = w_h[q] * dst[k];
     }
   } else if (field == RFAST_G) {
     // the separable objective keeps no sample in memory: write the current ones out first

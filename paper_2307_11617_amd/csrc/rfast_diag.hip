@@ -54,7 +54,11 @@ __global__ void __launch_bounds__(kThreads) rfast_diag_kernel(RfastDev s, const 
     double flight = 0.0;
     for (int e = 0; e < s.eC; ++e) {
       const int j = s.c_src[e];
-      flight += (double)(s.c_w[e] * s.sigma_ring[((size_t)j * s.M + (s.t[j] % s.M)) * p + k]) - (double)s.rho_tilde[(size_t)e * p + k];
+      // rho~ is read from the sender's ring while its version is still there (tau >= t_j - D)
+      const int tau = s.tau_c[e];
+      const float rt = tau >= s.t[j] - (s.M - 2) ? s.c_w[e] * s.sigma_ring[((size_t)j * s.M + (tau % s.M)) * p + k]
+                                                 : s.rho_tilde[(size_t)e * p + k];
+      flight += (double)(s.c_w[e] * s.sigma_ring[((size_t)j * s.M + (s.t[j] % s.M)) * p + k]) - (double)rt;
     }
     const double res = zs + flight - gs;
     acc[2] += res * res;

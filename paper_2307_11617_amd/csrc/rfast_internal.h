@@ -20,7 +20,13 @@
 //                           produced; the running sum rho_ij of Algorithm 1 (S2c) is
 //                           a_ij * sigma_j for every out-neighbour i, so one ring per
 //                           sender replaces one ring per edge
-//   rho_tilde   [eC][p]     receiver side
+//   rho_tilde   [eC][p]     receiver side.  The buffer of S4 holds a_ij * sigma_j[tau_ij], a value
+//                           that also sits in the sender's ring while tau_ij >= t_j - D.  It is
+//                           therefore read from the ring ("implicit") and only written out
+//                           ("explicit") in the round in which that version is about to leave
+//                           the ring: by the receiver if it consumes exactly that version then,
+//                           by the sender otherwise.  Invariant: tau_ij < t_j - D  =>  the array
+//                           holds a_ij * sigma_j[tau_ij].
 // ---------------------------------------------------------------------------
 struct RfastDev {
   int32_t n, M, H, eR, eC, d_max, burst;
@@ -62,7 +68,14 @@ struct RfastDev {
   int32_t* plan_t;        // [n]   t_i at the start of the round
   int32_t* slot_r;        // [eR]  resolved slot, -1 if receiver inactive
   int32_t* slot_c;        // [eC]
-  uint8_t* skip_c;        // [eC]  stamp unchanged since last consume: contributes exactly zero
+  // everything the state kernels need to know about a C edge in this round, in one word:
+  //   bits 0-7   ring slot of the version consumed (valid when live)
+  //   bits 8-15  ring slot of the version consumed last time, 0xFF = it is in the rho_tilde array
+  //   bit 16     live: the receiver is active and its stamp moved (otherwise the edge contributes exactly zero)
+  //   bit 17     the receiver writes what it consumes to the rho_tilde array
+  //   bit 18     the sender copies a_ij * sigma_j[t_j - D] to the rho_tilde array
+  int32_t* plan_c;        // [eC]
+  uint8_t* node_spill;    // [n]   some out-edge of this node has bit 18 set
   // schedule of the current round when it is generated on the device
   uint8_t* gen_active;    // [n]
   int32_t* gen_delay_r;   // [eR]

@@ -9,6 +9,11 @@
 // the next version is delivered regardless, which keeps every read within D
 // versions of the sender's counter (Assumption 3 ii).
 //
+// The same lane decides where the buffer rho~ of step S4 lives for its C edge.  rho~_ij
+// equals a_ij * sigma_j[tau_ij], which the sender's ring still holds while
+// tau_ij >= t_j - D; only a version about to leave the ring is copied to the rho~ array
+// (by the receiver if it consumes exactly that version in this round, else by the sender).
+//
 // One workgroup, one lane per edge; every step is integer and deterministic.
 #include "rfast_internal.h"
 
@@ -48,10 +53,23 @@ __device__ void resolve_edge(const RfastDev& s, int kind, int e, int r, const ui
     const int now = u > old ? u : old;
     tau[e] = now;
     slot[e] = now % s.M;
-    if (kind) s.skip_c[e] = (now == old);
+    if (kind) {
+      const int lo = s.plan_t[j] - (s.M - 2);  // oldest version that stays readable in j's ring during this round
+      const bool live = now != old;
+      // after this round the ring of an active sender no longer covers version lo
+      const bool leaves = active[j] != 0 && now == lo;
+      const bool spill = !live && leaves;
+      s.plan_c[e] = (now % s.M) | ((old >= lo ? old % s.M : 0xFF) << 8) | (live ? 1 << 16 : 0) |
+                    (live && leaves ? 1 << 17 : 0) | (spill ? 1 << 18 : 0);
+      if (spill) s.node_spill[j] = 1;
+    }
   } else {
     slot[e] = -1;
-    if (kind) s.skip_c[e] = 1;
+    if (kind) {
+      const bool spill = active[j] != 0 && tau[e] == s.plan_t[j] - (s.M - 2);
+      s.plan_c[e] = spill ? 1 << 18 : 0;
+      if (spill) s.node_spill[j] = 1;
+    }
   }
   if (active[j] != 0) {  // the sender publishes version t_j + 1 this round
     const int vn = s.plan_t[j] + 1;
@@ -83,6 +101,7 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev
     if (i < s.n) {
       const int ti = s.t[i];
       s.plan_t[i] = ti;
+      s.node_spill[i] = 0;
       s.t_hist[(size_t)i * s.H + (r % s.H)] = ti;
       act = active[i] != 0;
     }

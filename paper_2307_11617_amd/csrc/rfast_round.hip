@@ -21,12 +21,26 @@
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kBatch = 8;  // loads kept in flight per edge phase
 
 // ------------------------------------------------------------------- kernel
+// Loads of one live in-edge of C (plan word pl): the running sum being consumed and the one
+// consumed last time (rho~ of S4), which is read from the sender's ring while it is still there.
+template <int VEC>
+__device__ inline void load_edge(const RfastDev& s, int e, int pl, int M, int64_t p, int64_t k, typename V<VEC>::T* sg,
+                                 typename V<VEC>::T* rt) {
+  const float* ring = s.sigma_ring + (size_t)s.c_src[e] * M * p + k;
+  const int prev = (pl >> 8) & 0xFF;
+  const float* last = prev != 0xFF ? ring + (size_t)prev * p : s.rho_tilde + (size_t)e * p + k;
+  *sg = V<VEC>::ld(ring + (size_t)(pl & 0xFF) * p);
+  *rt = V<VEC>::ld(last);
+}
+
 // MOM: the optimizer variant's heavy-ball buffer is in use (a template flag so that the
 // plain method carries neither the branch nor the registers).
-template <int MODE, int VEC, bool MOM>
+// KB: in-edge loads kept in flight per phase.  8 costs 139 registers (3 wavefronts per SIMD), 4 costs
+// 91 (5 wavefronts): graphs with many in-edges per node want the deeper batch, graphs with few want
+// the wavefronts (measured: bidirectional ring 1.53 vs 1.59 ms with 8 vs 4, tree/star 0.293 vs 0.274).
+template <int MODE, int VEC, bool MOM, int KB>
 __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float gamma, int tiles_per_node) {
   using T = typename V<VEC>::T;
   const int n_act = *s.n_active;
@@ -55,15 +69,16 @@ __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float
   // ---- every load of the first batch of each phase is issued before its first use:
   //      with few wavefronts per CU this is what keeps enough bytes in flight
   T x_i, z_i, g_old, g_new, h, c, sig_cur, m_i;
-  T vb[kBatch], sg[kBatch], rt[kBatch];
-  float vw[kBatch], ca[kBatch];
-  bool live[kBatch];
+  T vb[KB], sg[KB], rt[KB];
+  float vw[KB], ca[KB];
+  int pl[KB];  // plan words of the C in-edges of the current batch (0: nothing to do)
+  const bool spills = pushes && s.node_spill[i] != 0;
   z_i = V<VEC>::ld(s.z + node_off);
   if (kMix) {
     x_i = V<VEC>::ld(s.x + node_off);
     if (MOM) m_i = V<VEC>::ld(s.mom + node_off);
 #pragma unroll
-    for (int q = 0; q < kBatch; ++q)
+    for (int q = 0; q < KB; ++q)
       if (re0 + q < re1) {
         vb[q] = V<VEC>::ld(s.v_ring + ((size_t)s.r_src[re0 + q] * M + s.slot_r[re0 + q]) * p + k);
         vw[q] = s.r_w[re0 + q];
@@ -79,12 +94,11 @@ __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float
     }
     if (pushes) sig_cur = V<VEC>::ld(s.sigma_ring + ((size_t)i * M + slot_cur) * p + k);
 #pragma unroll
-    for (int q = 0; q < kBatch; ++q) {
+    for (int q = 0; q < KB; ++q) {
       const int e = ce0 + q;
-      live[q] = e < ce1 && !s.skip_c[e];
-      if (live[q]) {
-        sg[q] = V<VEC>::ld(s.sigma_ring + ((size_t)s.c_src[e] * M + s.slot_c[e]) * p + k);
-        rt[q] = V<VEC>::ld(s.rho_tilde + (size_t)e * p + k);
+      pl[q] = e < ce1 ? s.plan_c[e] : 0;
+      if (pl[q] & (1 << 16)) {
+        load_edge<VEC>(s, e, pl[q], M, p, k, &sg[q], &rt[q]);
         ca[q] = s.c_w[e];
       }
     }
@@ -102,17 +116,17 @@ __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float
     // S2a: pull the stamped neighbour copies and mix with row-stochastic weights
     x_new = mul_s(s.r_self[i], v);
 #pragma unroll
-    for (int q = 0; q < kBatch; ++q)
+    for (int q = 0; q < KB; ++q)
       if (re0 + q < re1) x_new = fma_s(vw[q], vb[q], x_new);
-    for (int eb = re0 + kBatch; eb < re1; eb += kBatch) {  // in-degree above one batch
+    for (int eb = re0 + KB; eb < re1; eb += KB) {  // in-degree above one batch
 #pragma unroll
-      for (int q = 0; q < kBatch; ++q)
+      for (int q = 0; q < KB; ++q)
         if (eb + q < re1) {
           vb[q] = V<VEC>::ld(s.v_ring + ((size_t)s.r_src[eb + q] * M + s.slot_r[eb + q]) * p + k);
           vw[q] = s.r_w[eb + q];
         }
 #pragma unroll
-      for (int q = 0; q < kBatch; ++q)
+      for (int q = 0; q < KB; ++q)
         if (eb + q < re1) x_new = fma_s(vw[q], vb[q], x_new);
     }
     // S3 (v half): publish version t+1
@@ -132,36 +146,45 @@ __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float
   // An edge whose stamp did not move holds rho == rho~ exactly and is skipped.
   T z_half = z_i;
 #pragma unroll
-  for (int q = 0; q < kBatch; ++q)
-    if (live[q]) {
+  for (int q = 0; q < KB; ++q)
+    if (pl[q] & (1 << 16)) {
       const T rho = mul_s(ca[q], sg[q]);
-      z_half = add(z_half, sub(rho, rt[q]));
-      V<VEC>::st(s.rho_tilde + (size_t)(ce0 + q) * p + k, rho);
+      z_half = add(z_half, sub(rho, ((pl[q] >> 8) & 0xFF) != 0xFF ? mul_s(ca[q], rt[q]) : rt[q]));
+      if (pl[q] & (1 << 17)) V<VEC>::st(s.rho_tilde + (size_t)(ce0 + q) * p + k, rho);
     }
-  for (int eb = ce0 + kBatch; eb < ce1; eb += kBatch) {  // in-degree above one batch
+  for (int eb = ce0 + KB; eb < ce1; eb += KB) {  // in-degree above one batch
 #pragma unroll
-    for (int q = 0; q < kBatch; ++q) {
+    for (int q = 0; q < KB; ++q) {
       const int e = eb + q;
-      live[q] = e < ce1 && !s.skip_c[e];
-      if (live[q]) {
-        sg[q] = V<VEC>::ld(s.sigma_ring + ((size_t)s.c_src[e] * M + s.slot_c[e]) * p + k);
-        rt[q] = V<VEC>::ld(s.rho_tilde + (size_t)e * p + k);
+      pl[q] = e < ce1 ? s.plan_c[e] : 0;
+      if (pl[q] & (1 << 16)) {
+        load_edge<VEC>(s, e, pl[q], M, p, k, &sg[q], &rt[q]);
         ca[q] = s.c_w[e];
       }
     }
 #pragma unroll
-    for (int q = 0; q < kBatch; ++q)
-      if (live[q]) {
+    for (int q = 0; q < KB; ++q)
+      if (pl[q] & (1 << 16)) {
         const T rho = mul_s(ca[q], sg[q]);
-        z_half = add(z_half, sub(rho, rt[q]));
-        V<VEC>::st(s.rho_tilde + (size_t)(eb + q) * p + k, rho);
+        z_half = add(z_half, sub(rho, ((pl[q] >> 8) & 0xFF) != 0xFF ? mul_s(ca[q], rt[q]) : rt[q]));
+        if (pl[q] & (1 << 17)) V<VEC>::st(s.rho_tilde + (size_t)(eb + q) * p + k, rho);
       }
   }
   z_half = sub(add(z_half, g_new), g_old);
 
   // S2c: keep a_ii; push: sigma_i grows by z_half.  S3 (rho half): new version t+1
   V<VEC>::st(s.z + node_off, mul_s(s.c_self[i], z_half));
-  if (pushes) V<VEC>::st(s.sigma_ring + ((size_t)i * M + slot_new) * p + k, add(sig_cur, z_half));
+  if (pushes) {
+    V<VEC>::st(s.sigma_ring + ((size_t)i * M + slot_new) * p + k, add(sig_cur, z_half));
+    // S4 for receivers that do not do it themselves in this round: version t - D of this node's
+    // running sum leaves the ring with this activation; a receiver whose buffer rho~ is that
+    // version gets it copied to the rho~ array now (the slot read here is not the one written above).
+    if (spills) {
+      const T leaving = V<VEC>::ld(s.sigma_ring + ((size_t)i * M + (t_old - (M - 2)) % M) * p + k);
+      for (int o = s.co_ptr[i]; o < s.co_ptr[i + 1]; ++o)
+        if (s.plan_c[s.co_eid[o]] & (1 << 18)) V<VEC>::st(s.rho_tilde + (size_t)s.co_eid[o] * p + k, mul_s(s.co_w[o], leaving));
+    }
+  }
 }
 
 // Writes the current sample of every node, g_i = sample(x_i, t_i), into g[t_i & 1][i]: the
@@ -283,7 +306,7 @@ __global__ void __launch_bounds__(kThreads) rfast_sync_fold_kernel(RfastDev s) {
   V<VEC>::st(s.z + (size_t)i * s.p + k, V<VEC>::ld(sync_z(s, 1, i) + k));
 }
 
-template <int MODE, bool MOM>
+template <int MODE, bool MOM, int KB>
 hipError_t launch(rfast_ctx* c, float gamma) {
   const RfastDev& d = c->d;
   const bool vec4 = (d.p % 4) == 0;
@@ -291,16 +314,16 @@ hipError_t launch(rfast_ctx* c, float gamma) {
   const int64_t tiles = (d.p + per_block - 1) / per_block;
   const int64_t blocks = tiles * d.n;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  // Stream past the caches once the state dwarfs them (256 MB of last-level cache).  (Capping the
-  // CU at two workgroups by reserving LDS gained 5-8 % in a fixed-degree replica of this kernel but
-  // nothing here, where the 141 registers of the up-front loads already hold it to 12 wavefronts.)
+  // Stream past the caches once the state dwarfs them (256 MB of last-level cache).  Wavefronts per
+  // SIMD matter: the bidirectional ring (about 15 streams per node-update) is fastest at 3, slower at
+  // 2 (capped through reserved LDS: +11 %) and at 4 or 5 (+2 %, +4 %); the register count of KB sets it.
   const bool streaming = (double)d.n * (double)d.p * 4.0 >= 32.0e6;
   if (vec4 && streaming)
-    hipLaunchKernelGGL((rfast_state_kernel<MODE, -4, MOM>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, d, gamma, (int)tiles);
+    hipLaunchKernelGGL((rfast_state_kernel<MODE, -4, MOM, KB>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, d, gamma, (int)tiles);
   else if (vec4)
-    hipLaunchKernelGGL((rfast_state_kernel<MODE, 4, MOM>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, d, gamma, (int)tiles);
+    hipLaunchKernelGGL((rfast_state_kernel<MODE, 4, MOM, KB>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, d, gamma, (int)tiles);
   else
-    hipLaunchKernelGGL((rfast_state_kernel<MODE, 1, MOM>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, d, gamma, (int)tiles);
+    hipLaunchKernelGGL((rfast_state_kernel<MODE, 1, MOM, KB>), dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, d, gamma, (int)tiles);
   return hipGetLastError();
 }
 
@@ -364,9 +387,16 @@ hipError_t rfast_launch_rebase(rfast_ctx* c) {
 
 hipError_t rfast_launch_state(rfast_ctx* c, int mode, float gamma) {
   const bool mom = c->d.mom != nullptr;
+  // three or more in-edges per node on average (both graphs together): the deeper load batch
+  const bool deep = (int64_t)c->d.eR + c->d.eC >= 3 * (int64_t)c->d.n;
   switch (mode) {
-    case RFAST_MODE_FUSED: return mom ? launch<RFAST_MODE_FUSED, true>(c, gamma) : launch<RFAST_MODE_FUSED, false>(c, gamma);
-    case RFAST_MODE_MIX: return mom ? launch<RFAST_MODE_MIX, true>(c, gamma) : launch<RFAST_MODE_MIX, false>(c, gamma);
-    default: return launch<RFAST_MODE_TRACK, false>(c, gamma);  // S1 is not part of this pass
+    case RFAST_MODE_FUSED:
+      if (deep) return mom ? launch<RFAST_MODE_FUSED, true, 8>(c, gamma) : launch<RFAST_MODE_FUSED, false, 8>(c, gamma);
+      return mom ? launch<RFAST_MODE_FUSED, true, 4>(c, gamma) : launch<RFAST_MODE_FUSED, false, 4>(c, gamma);
+    case RFAST_MODE_MIX:
+      if (deep) return mom ? launch<RFAST_MODE_MIX, true, 8>(c, gamma) : launch<RFAST_MODE_MIX, false, 8>(c, gamma);
+      return mom ? launch<RFAST_MODE_MIX, true, 4>(c, gamma) : launch<RFAST_MODE_MIX, false, 4>(c, gamma);
+    default:  // S1 is not part of this pass
+      return deep ? launch<RFAST_MODE_TRACK, false, 8>(c, gamma) : launch<RFAST_MODE_TRACK, false, 4>(c, gamma);
   }
 }

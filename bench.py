@@ -29,16 +29,18 @@ def algorithmic_bytes_per_round(w, active_counts, layout=False):
     writes x, z, g, v, dO new rho's, dI rho~'s), plus the objective data (h, c) of the
     diagonal quadratic, or the re-read of g_new by the split mix/track pair.
     layout=True: the words this library's layout has to move (one running sum per
-    sender instead of one per out-edge: 2 words instead of 2 dO; no stored sample for
-    the separable objective), skips not credited."""
+    sender instead of one per out-edge: 2 words instead of 2 dO; no write of the S4
+    buffer; no stored sample for the separable objective), skips not credited."""
     Rd, Cd = w.R.dense(), w.C.dense()
     dR = (Rd != 0).sum(axis=1) - 1
     dI = (Cd != 0).sum(axis=1) - 1
     dO = (Cd != 0).sum(axis=0) - 1
     push = 2 * np.minimum(dO, 1) if layout else 2 * dO
     words = 7 + dR + 3 * dI + push + (2 if w.objective == "diag_quadratic" else 1)
-    if layout and w.objective == "diag_quadratic":
-        words = words - 2   # the old sample is recomputed from (x_i, t_i): g is neither read nor written
+    if layout:
+        words = words - dI      # the buffer of S4 is read from the sender's ring and (almost) never written
+        if w.objective == "diag_quadratic":
+            words = words - 2   # the old sample is recomputed from (x_i, t_i): g is neither read nor written
     return float((words * active_counts).sum() * 4.0 * w.p)
 
 

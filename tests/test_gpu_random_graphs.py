@@ -76,3 +76,26 @@ def test_single_coordinate_and_full_batch_logistic():
     w = configs.config1(p=1, samples=64, batch=64, rounds=0)
     worst, orc, gpu = harness.run_parity(w, 120, every=40)
     print(f"\n[{w.name} p=1 full batch] worst {worst}")
+
+
+def test_buffers_that_leave_the_senders_ring():
+    """The S4 buffer rho~ is kept implicitly (the sender's ring still holds that version) or in
+    its own array (the version has left the ring).  Shallow ring, always-active senders and
+    rarely active receivers: every way of handing a buffer over occurs, and every buffer read
+    back equals the oracle's (run_parity compares rho~ of every edge at every checkpoint)."""
+    n = 10
+    rng = np.random.default_rng(21)
+    wr, wc = graphs.random_digraph(n, rng, extra=0.6)
+    R, C = graphs.from_dense(wr), graphs.from_dense(wc)
+    p_act = np.where(np.arange(n) % 3 == 0, 0.15, 1.0)
+    sched = ScheduleSpec(n, R.nnz_off, C.nnz_off, p_act, 1, 0.3, seed=5)
+    w = configs.Workload("shallow_ring_lagging_receivers", n, 260, R, C, 1 + 2 - 1, 2, 0.01, 0, "diag_quadratic",
+                         problems.diag_quadratic(n, 260, 5), sched, 0.05, 31, 1e-4)
+    assert w.D == 2
+    worst, orc, gpu = harness.run_parity(w, 300, every=20)
+    # at the end: buffers inside the ring window, on its edge, and outside it all exist
+    lag = np.array([int(orc.t[j]) - int(orc.tau_rho[e]) for e, (i, j) in enumerate(orc.edges_C)])
+    assert (lag < w.D).any() and (lag == w.D).any() and (lag > w.D).any(), lag
+    d = gpu.diagnostics()
+    assert d["conservation_sq"] <= 1e-8 * max(d["gsum_sq"], 1.0)
+    print(f"\n[{w.name}] worst {worst}, lags {np.bincount(np.minimum(lag, 8))}")

@@ -35,6 +35,26 @@ __device__ inline void load_edge(const RfastDev& s, int e, int pl, int M, int64_
   *rt = V<VEC>::ld(last);
 }
 
+// Softmax objective: the GEMMs read the weights as bf16, 8 consecutive features of one class per
+// 16-byte unit (layout [d/8][K][8]).  The 1024 coordinates of one tile are 1024/K whole features
+// x K classes, i.e. exactly the elements [1024*tile, 1024*tile + 1024) of that layout in another
+// order: permute through LDS and write them out coalesced, instead of a pass that re-reads x.
+template <int VEC>
+__device__ inline void emit_bf16_blocked(const RfastDev& s, int i, int tile, typename V<VEC>::T x_new) {
+  __shared__ unsigned short perm[kThreads * 4];
+  const int K = s.prob.K;
+  const int l = threadIdx.x * 4, f = l / K, k0 = l % K;
+  unsigned short* dst = perm + (f >> 3) * (8 * K) + k0 * 8 + (f & 7);
+  const float4 w = *reinterpret_cast<const float4*>(&x_new);
+  dst[0] = rfast_f32_to_bf16(w.x);
+  dst[8] = rfast_f32_to_bf16(w.y);
+  dst[16] = rfast_f32_to_bf16(w.z);
+  dst[24] = rfast_f32_to_bf16(w.w);
+  __syncthreads();
+  unsigned short* wt = (unsigned short*)s.gscratch + (size_t)i * s.p + (size_t)tile * (kThreads * 4);
+  *reinterpret_cast<uint2*>(wt + l) = *reinterpret_cast<const uint2*>(perm + l);
+}
+
 // MOM: the optimizer variant's heavy-ball buffer is in use (a template flag so that the
 // plain method carries neither the branch nor the registers).
 // KB: in-edge loads kept in flight per phase.  8 costs 139 registers (3 wavefronts per SIMD), 4 costs
@@ -132,7 +152,12 @@ __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float
     // S3 (v half): publish version t+1
     V<VEC>::st(s.v_ring + ((size_t)i * M + slot_new) * p + k, v);
     V<VEC>::st(s.x + node_off, x_new);
-    if (MODE == RFAST_MODE_MIX) return;
+    if (MODE == RFAST_MODE_MIX) {
+      if constexpr (VEC != 1) {  // p is a multiple of 2048 for this objective: every tile is full
+        if (s.prob.kind == RFAST_OBJ_SOFTMAX_BF16 && (1024 % s.prob.K) == 0) emit_bf16_blocked<VEC>(s, i, tile, x_new);
+      }
+      return;
+    }
   }
 
   if (MODE == RFAST_MODE_FUSED) {

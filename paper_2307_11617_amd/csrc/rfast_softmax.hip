@@ -20,7 +20,7 @@
 //   A: row l%32, contraction indices 8*(l/32) .. +7      (8 bf16)
 //   B: column l%32, contraction indices 8*(l/32) .. +7   (8 bf16)
 //   C/D: column l%32, rows 8*(v/4) + 4*(l/32) + v%4 for v = 0..15
-#include "rfast_internal.h"
+#include "rfast_vec.h"
 
 namespace {
 
@@ -33,10 +33,7 @@ constexpr int kTile = 64;       // rows (forward) / features (backward) per bloc
 constexpr int kPad = 8;         // LDS row padding in bf16 elements (16 bytes)
 constexpr int kLd = kTile + kPad;
 
-__device__ inline u16 f32_to_bf16(float f) {  // round to nearest even
-  const uint32_t u = __float_as_uint(f);
-  return (u16)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
-}
+__device__ inline u16 f32_to_bf16(float f) { return rfast_f32_to_bf16(f); }
 
 // node handled by work slot `slot`: all nodes at initialisation, the round's active list otherwise
 __device__ inline int pick_node(const RfastDev& s, bool init, int slot) {
@@ -428,6 +425,12 @@ __global__ void __launch_bounds__(64 * NW) rfast_softmax_backward(RfastDev s, co
 
 }  // namespace
 
+// The state kernel that mixes x (S2a) can emit the blocked bf16 copy of the new weights itself when
+// its 1024-coordinate tile covers whole 8-feature blocks: K divides 1024.
+bool rfast_softmax_prep_is_fused(const rfast_problem* prob) {
+  return prob->kind == RFAST_OBJ_SOFTMAX_BF16 && (prob->K == 32 || prob->K == 64 || prob->K == 128);
+}
+
 // Shapes the kernels assume; checked once at context creation.
 bool rfast_softmax_shape_ok(const rfast_problem* prob) {
   const int B = prob->batch > 0 ? prob->batch : prob->samples;
@@ -453,7 +456,9 @@ hipError_t rfast_softmax_gradient(rfast_ctx* c, const int32_t* batch_idx, bool i
   const size_t lds_fwd = lds_fwd_stage > lds_logits ? lds_fwd_stage : lds_logits;
   const size_t lds_bwd = 2 * (size_t)(kTile + K) * kLd * sizeof(u16);
   const unsigned n8 = (unsigned)((d.n + 7) / 8 * 8);  // node slots, padded so that ids decode per XCD
-  hipLaunchKernelGGL(rfast_softmax_prep, dim3(d.prob.d / kTile, d.n), dim3(256), lds_prep, c->stream, d, B, init, (const float*)nullptr);
+  // during rounds the mixing pass has already written the bf16 copy of the weights it produced
+  if (init || !rfast_softmax_prep_is_fused(&d.prob))
+    hipLaunchKernelGGL(rfast_softmax_prep, dim3(d.prob.d / kTile, d.n), dim3(256), lds_prep, c->stream, d, B, init, (const float*)nullptr);
   const dim3 fgrid(n8 * (unsigned)(B / kTile)), bgrid(n8 * (unsigned)(d.prob.d / kTile));
   switch (NW) {
     case 1:

@@ -107,6 +107,12 @@ template <> __device__ inline float noise_at<1>(uint64_t seed, uint32_t node, ui
 }
 
 
+// fp32 -> bf16 bits, round to nearest even (the rounding both softmax GEMM operands get)
+__device__ inline unsigned short rfast_f32_to_bf16(float f) {
+  const uint32_t u = __float_as_uint(f);
+  return (unsigned short)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+
 // ------------------------------------------- sample of the diagonal quadratic
 // grad f_i(x; zeta^version) = h (x - c) + noise_std * N(0, I)[node, version] (+ weight decay * x).
 // A pure function of (x, node, version): the "stored" sample of step S2b is recomputed

@@ -57,6 +57,15 @@ def test_config4_small_all_classes():
     _report(w.name + " d=256", worst)
 
 
+@pytest.mark.parametrize("K", [32, 96])
+def test_config4_small_other_class_counts(K):
+    """K = 32: one class tile, 32 features per state tile (the mixing pass writes the bf16 copy of
+    the weights itself); K = 96 does not divide the state tile, so the separate conversion pass runs."""
+    w = configs.config4(d=128, K=K, samples=192, batch=64, rounds=150)
+    worst, orc, gpu = harness.run_parity(w, 150, every=50)
+    _report(w.name + f" K={K}", worst)
+
+
 def test_x0_nonzero_and_noise_free():
     rng = np.random.default_rng(0)
     w = configs.config2(p=2048, rounds=200)

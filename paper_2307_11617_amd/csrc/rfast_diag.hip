@@ -3,9 +3,9 @@
 //   quantities of Theorem 1 and the merit function of Theorem 2), ||z||^2, and
 //   the residual of the tracking-conservation identity of Lemma 3,
 //   sum_i z_i + sum_e (rho_e latest - rho~_e) - sum_i g_i  (zero in exact arithmetic).
-// One lane owns one coordinate and walks over nodes and edges (coalesced along
-// k); partial sums are kept in fp64, reduced across the 64 lanes with shuffles
-// and added to the result with one fp64 atomic per wavefront.
+// One lane owns four consecutive coordinates (one when p is not a multiple of four)
+// and walks over nodes and edges (coalesced along k); partial sums are kept in fp64, reduced across the 64 lanes with shuffles
+// then across the workgroup through LDS, and added to the result with one fp64 atomic per workgroup.
 #include "rfast_vec.h"
 
 namespace {
@@ -22,54 +22,108 @@ __global__ void rfast_diag_zero(double* out) {
   if (threadIdx.x < 8) out[threadIdx.x] = 0.0;
 }
 
+template <int VEC>
+__device__ inline float comp(const typename V<VEC>::T& v, int u) { return reinterpret_cast<const float*>(&v)[u]; }
+
+// VEC = 4: four coordinates per lane (float4 loads, one Philox call per node for the four);
+// VEC = 1: p not a multiple of four.
+template <int VEC>
 __global__ void __launch_bounds__(kThreads) rfast_diag_kernel(RfastDev s, const float* xstar, double* out) {
+  using T = typename V<VEC>::T;
+  constexpr int W = V<VEC>::W;
   const int64_t p = s.p;
+  const bool separable = s.prob.kind == RFAST_OBJ_DIAG_QUADRATIC;
+  const float* hp = (const float*)s.prob.data0;
+  const float* cp = (const float*)s.prob.data1;
   double acc[7] = {0, 0, 0, 0, 0, 0, 0};
-  for (int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x; k < p; k += (int64_t)gridDim.x * kThreads) {
-    double xs = 0.0, zs = 0.0, gs = 0.0;
+  for (int64_t k = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * W; k < p; k += (int64_t)gridDim.x * kThreads * W) {
+    double xs[W], zs[W], gs[W], flight[W];
+#pragma unroll
+    for (int u = 0; u < W; ++u) xs[u] = zs[u] = gs[u] = flight[u] = 0.0;
+#pragma unroll 2
     for (int i = 0; i < s.n; ++i) {
       const size_t off = (size_t)i * p + k;
-      const double zi = s.z[off];
-      xs += s.x[off];
-      zs += zi;
-      acc[1] += zi * zi;
-      if (s.prob.kind == RFAST_OBJ_DIAG_QUADRATIC)  // the sample is a function of (x_i, t_i), not kept in memory
-        gs += diag_sample<1>(s, ((const float*)s.prob.data0)[off], ((const float*)s.prob.data1)[off], s.x[off], i, s.t[i], k);
-      else
-        gs += s.g[(size_t)(s.t[i] & 1) * s.n * p + off];
-    }
-    const double xbar = xs / s.n;
-    s.xbar[k] = (float)xbar;
-    acc[6] += xbar * xbar;
-    double loss = 0.0;
-    for (int i = 0; i < s.n; ++i) {
-      const size_t off = (size_t)i * p + k;
-      const double dx = (double)s.x[off] - xbar;
-      acc[0] += dx * dx;
-      if (s.prob.kind == RFAST_OBJ_DIAG_QUADRATIC) {
-        const double h = ((const float*)s.prob.data0)[off], c = ((const float*)s.prob.data1)[off];
-        loss += 0.5 * h * (xbar - c) * (xbar - c);
+      const int ti = s.t[i];
+      const T x = V<VEC>::ld(s.x + off), z = V<VEC>::ld(s.z + off);
+      // the separable objective keeps no sample in memory: it is a function of (x_i, t_i)
+      const T g = separable ? diag_sample<VEC>(s, V<VEC>::ld(hp + off), V<VEC>::ld(cp + off), x, i, ti, k)
+                            : V<VEC>::ld(s.g + (size_t)(ti & 1) * s.n * p + off);
+#pragma unroll
+      for (int u = 0; u < W; ++u) {
+        const double zi = comp<VEC>(z, u);
+        xs[u] += comp<VEC>(x, u);
+        zs[u] += zi;
+        acc[1] += zi * zi;
+        gs[u] += comp<VEC>(g, u);
       }
     }
-    double flight = 0.0;
+    double xbar[W];
+    T xbar_f;
+#pragma unroll
+    for (int u = 0; u < W; ++u) {
+      xbar[u] = xs[u] / s.n;
+      reinterpret_cast<float*>(&xbar_f)[u] = (float)xbar[u];
+      acc[6] += xbar[u] * xbar[u];
+    }
+    V<VEC>::st(s.xbar + k, xbar_f);
+#pragma unroll 2
+    for (int i = 0; i < s.n; ++i) {
+      const size_t off = (size_t)i * p + k;
+      const T x = V<VEC>::ld(s.x + off);
+      T h, c;
+      if (separable) {
+        h = V<VEC>::ld(hp + off);
+        c = V<VEC>::ld(cp + off);
+      }
+#pragma unroll
+      for (int u = 0; u < W; ++u) {
+        const double dx = (double)comp<VEC>(x, u) - xbar[u];
+        acc[0] += dx * dx;
+        if (separable) {
+          const double d = xbar[u] - (double)comp<VEC>(c, u);
+          acc[5] += 0.5 * (double)comp<VEC>(h, u) * d * d;
+        }
+      }
+    }
+#pragma unroll 2
     for (int e = 0; e < s.eC; ++e) {
       const int j = s.c_src[e];
+      const int tj = s.t[j], tau = s.tau_c[e];
+      const float a = s.c_w[e];
+      const float* ring = s.sigma_ring + (size_t)j * s.M * p + k;
+      const T latest = V<VEC>::ld(ring + (size_t)(tj % s.M) * p);
       // rho~ is read from the sender's ring while its version is still there (tau >= t_j - D)
-      const int tau = s.tau_c[e];
-      const float rt = tau >= s.t[j] - (s.M - 2) ? s.c_w[e] * s.sigma_ring[((size_t)j * s.M + (tau % s.M)) * p + k]
-                                                 : s.rho_tilde[(size_t)e * p + k];
-      flight += (double)(s.c_w[e] * s.sigma_ring[((size_t)j * s.M + (s.t[j] % s.M)) * p + k]) - (double)rt;
+      const bool in_ring = tau >= tj - (s.M - 2);
+      const T last = V<VEC>::ld(in_ring ? ring + (size_t)(tau % s.M) * p : s.rho_tilde + (size_t)e * p + k);
+#pragma unroll
+      for (int u = 0; u < W; ++u) {
+        const float rt = in_ring ? a * comp<VEC>(last, u) : comp<VEC>(last, u);
+        flight[u] += (double)(a * comp<VEC>(latest, u)) - (double)rt;
+      }
     }
-    const double res = zs + flight - gs;
-    acc[2] += res * res;
-    acc[3] += gs * gs;
-    if (xstar) acc[4] += (xbar - xstar[k]) * (xbar - xstar[k]);
-    acc[5] += loss;
+    T xs_f;
+    if (xstar) xs_f = V<VEC>::ld(xstar + k);
+#pragma unroll
+    for (int u = 0; u < W; ++u) {
+      const double res = zs[u] + flight[u] - gs[u];
+      acc[2] += res * res;
+      acc[3] += gs[u] * gs[u];
+      if (xstar) acc[4] += (xbar[u] - comp<VEC>(xs_f, u)) * (xbar[u] - comp<VEC>(xs_f, u));
+    }
   }
+  // one fp64 atomic per quantity and workgroup: the seven results are single addresses, and
+  // tens of thousands of atomics on them would serialise
+  __shared__ double part[kThreads / 64][7];
 #pragma unroll
   for (int q = 0; q < 7; ++q) {
     const double w = wave_sum(acc[q]);
-    if ((threadIdx.x & 63) == 0) atomicAdd(&out[q], w);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6][q] = w;
+  }
+  __syncthreads();
+  if (threadIdx.x < 7) {
+    double w = 0.0;
+    for (int v = 0; v < kThreads / 64; ++v) w += part[v][threadIdx.x];
+    atomicAdd(&out[threadIdx.x], w);
   }
 }
 
@@ -98,9 +152,17 @@ __global__ void __launch_bounds__(kThreads) rfast_loss_rows_kernel(RfastDev s, d
 
 hipError_t rfast_launch_diag(rfast_ctx* c, const float* d_xstar, double* d_out) {
   hipLaunchKernelGGL(rfast_diag_zero, dim3(1), dim3(64), 0, c->stream, d_out);
-  int64_t blocks = (c->d.p + kThreads - 1) / kThreads;
-  if (blocks > 4096) blocks = 4096;
-  hipLaunchKernelGGL(rfast_diag_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, c->d, d_xstar, d_out);
+  const bool vec4 = (c->d.p % 4) == 0 && ((uintptr_t)d_xstar % 16) == 0;
+  const int64_t per_block = (int64_t)kThreads * (vec4 ? 4 : 1);
+  int64_t blocks = (c->d.p + per_block - 1) / per_block;
+  if (blocks > 2048) blocks = 2048;  // grid-stride beyond that: 8 workgroups per CU
+  const bool streaming = (double)c->d.n * (double)c->d.p * 4.0 >= 32.0e6;  // far beyond the caches: non-temporal loads
+  if (vec4 && streaming)
+    hipLaunchKernelGGL(rfast_diag_kernel<-4>, dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, c->d, d_xstar, d_out);
+  else if (vec4)
+    hipLaunchKernelGGL(rfast_diag_kernel<4>, dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, c->d, d_xstar, d_out);
+  else
+    hipLaunchKernelGGL(rfast_diag_kernel<1>, dim3((unsigned)blocks), dim3(kThreads), 0, c->stream, c->d, d_xstar, d_out);
   const int kind = c->d.prob.kind;
   if (kind == RFAST_OBJ_LEAST_SQUARES || kind == RFAST_OBJ_LOGISTIC)
     hipLaunchKernelGGL(rfast_loss_rows_kernel, dim3((c->d.prob.samples + 3) / 4, c->d.n), dim3(kThreads), 0, c->stream, c->d,

@@ -6,8 +6,8 @@
 //   r_s = phi(a_s . x) - y_s,   g = (1/B) sum_s r_s a_s (+ lambda x),
 // phi = identity (least squares, y = b) or the logistic function.  The rows
 // kernel gives one wavefront per sampled row (float4 loads, 64-lane reduction);
-// the columns kernel gives one float4 of g per lane and streams the same rows
-// again, coalesced along k.
+// the columns kernel gives one float4 of g per lane of a wavefront and streams the
+// same rows again, coalesced along k, its four wavefronts sharing the rows.
 #include "rfast_internal.h"
 
 namespace {
@@ -53,7 +53,25 @@ __global__ void __launch_bounds__(kThreads) rfast_rows_kernel(RfastDev s, const 
   const float* x = s.x + (size_t)i * p;
   float acc = 0.f;
   if ((p & 3) == 0) {
-    for (int64_t k = (int64_t)lane * 4; k < p; k += 256) {
+    // four 1 KiB pieces of the row per step, all eight loads issued before the first use:
+    // one wavefront per row has nothing else to hide the memory latency with
+    int64_t k = (int64_t)lane * 4;
+    for (; k + 768 < p; k += 1024) {
+      float4 av[4], xv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        av[u] = *reinterpret_cast<const float4*>(a + k + 256 * u);
+        xv[u] = *reinterpret_cast<const float4*>(x + k + 256 * u);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        acc = fmaf(av[u].x, xv[u].x, acc);
+        acc = fmaf(av[u].y, xv[u].y, acc);
+        acc = fmaf(av[u].z, xv[u].z, acc);
+        acc = fmaf(av[u].w, xv[u].w, acc);
+      }
+    }
+    for (; k < p; k += 256) {
       const float4 av = *reinterpret_cast<const float4*>(a + k);
       const float4 xv = *reinterpret_cast<const float4*>(x + k);
       acc = fmaf(av.x, xv.x, acc);
@@ -72,9 +90,15 @@ __global__ void __launch_bounds__(kThreads) rfast_rows_kernel(RfastDev s, const 
   }
 }
 
+// VEC = 4: a workgroup owns 256 coordinates (one float4 per lane); its four wavefronts each take
+// every fourth sampled row (a row is then one coalesced 1 KiB read per wavefront and the row
+// number is wavefront-uniform) and the four partial sums meet in LDS.  That gives p/256
+// workgroups per node instead of p/1024 and a quarter of the loop per lane: with a few dozen
+// rows per node there is not enough work to hide the latency otherwise.  VEC = 1: one coordinate
+// per lane, every lane walks over all rows.
 template <int VEC>
 __global__ void __launch_bounds__(kThreads) rfast_cols_kernel(RfastDev s, const int32_t* batch_idx, int B, bool init) {
-  extern __shared__ float sh[];  // [B] residuals, then [B] row numbers
+  extern __shared__ float sh[];  // [B] residuals, [B] row numbers, then (VEC = 4) [4][64] float4 partial sums
   const int i = pick_node(s, init);
   if (i < 0) return;
   float* r_sh = sh;
@@ -85,31 +109,47 @@ __global__ void __launch_bounds__(kThreads) rfast_cols_kernel(RfastDev s, const 
   }
   __syncthreads();
   const int64_t p = s.p;
-  const int64_t k = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * VEC;
-  if (k >= p) return;
-  const float* base = (const float*)s.prob.data0 + (size_t)i * s.prob.samples * p + k;
   const int t_old = init ? -1 : s.plan_t[i];
-  float* dst = s.g + (size_t)((t_old + 1) & 1) * s.n * p + (size_t)i * p + k;
+  float* g_new = s.g + (size_t)((t_old + 1) & 1) * s.n * p + (size_t)i * p;
   const float inv = 1.0f / (float)B;
   // l2 term of the logistic objective plus the weight decay of the optimizer variant
   const float lam = (s.prob.kind == RFAST_OBJ_LOGISTIC ? s.prob.lambda : 0.f) + s.wd;
   if (VEC == 4) {
+    const int lane = threadIdx.x & 63, rg = threadIdx.x >> 6;
+    const int64_t k = ((int64_t)blockIdx.x * 64 + lane) * 4;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int b = 0; b < B; ++b) {
-      const float4 av = *reinterpret_cast<const float4*>(base + (size_t)row_sh[b] * p);
-      const float r = r_sh[b];
-      acc.x = fmaf(r, av.x, acc.x);
-      acc.y = fmaf(r, av.y, acc.y);
-      acc.z = fmaf(r, av.z, acc.z);
-      acc.w = fmaf(r, av.w, acc.w);
+    if (k < p) {
+      const float* base = (const float*)s.prob.data0 + (size_t)i * s.prob.samples * p + k;
+#pragma unroll 4
+      for (int b = rg; b < B; b += kWaves) {
+        const float4 av = *reinterpret_cast<const float4*>(base + (size_t)row_sh[b] * p);
+        const float r = r_sh[b];
+        acc.x = fmaf(r, av.x, acc.x);
+        acc.y = fmaf(r, av.y, acc.y);
+        acc.z = fmaf(r, av.z, acc.z);
+        acc.w = fmaf(r, av.w, acc.w);
+      }
     }
-    const float4 xv = *reinterpret_cast<const float4*>(s.x + (size_t)i * p + k);
-    *reinterpret_cast<float4*>(dst) = make_float4(fmaf(lam, xv.x, acc.x * inv), fmaf(lam, xv.y, acc.y * inv),
-                                                  fmaf(lam, xv.z, acc.z * inv), fmaf(lam, xv.w, acc.w * inv));
+    float4* part = reinterpret_cast<float4*>(sh + ((2 * B + 3) & ~3));
+    part[rg * 64 + lane] = acc;
+    __syncthreads();
+    if (rg == 0 && k < p) {
+#pragma unroll
+      for (int q = 1; q < kWaves; ++q) {
+        const float4 o = part[q * 64 + lane];
+        acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w;
+      }
+      const float4 xv = *reinterpret_cast<const float4*>(s.x + (size_t)i * p + k);
+      *reinterpret_cast<float4*>(g_new + k) = make_float4(fmaf(lam, xv.x, acc.x * inv), fmaf(lam, xv.y, acc.y * inv),
+                                                          fmaf(lam, xv.z, acc.z * inv), fmaf(lam, xv.w, acc.w * inv));
+    }
   } else {
+    const int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (k >= p) return;
+    const float* base = (const float*)s.prob.data0 + (size_t)i * s.prob.samples * p + k;
     float acc = 0.f;
     for (int b = 0; b < B; ++b) acc = fmaf(r_sh[b], base[(size_t)row_sh[b] * p], acc);
-    *dst = fmaf(lam, s.x[(size_t)i * p + k], acc * inv);
+    g_new[k] = fmaf(lam, s.x[(size_t)i * p + k], acc * inv);
   }
 }
 
@@ -127,9 +167,9 @@ hipError_t gemv_pair(rfast_ctx* c, const int32_t* batch_idx, bool init) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const bool vec4 = (d.p % 4) == 0;
-  const int64_t per_block = (int64_t)kThreads * (vec4 ? 4 : 1);
+  const int64_t per_block = vec4 ? 256 : kThreads;  // coordinates per workgroup
   const unsigned gx = (unsigned)((d.p + per_block - 1) / per_block);
-  const size_t shm = (size_t)B * 8;
+  const size_t shm = (size_t)((2 * B + 3) & ~3) * 4 + (vec4 ? (size_t)kWaves * 64 * 16 : 0);
   if (vec4)
     hipLaunchKernelGGL(rfast_cols_kernel<4>, dim3(gx, d.n), dim3(kThreads), shm, c->stream, d, bi, B, init);
   else

@@ -112,3 +112,41 @@ def test_softmax_gradient_against_autograd(monkeypatch):
     W = torch.from_numpy(x.reshape(d, K))
     ref_loss = torch.nn.functional.cross_entropy(torch.from_numpy(X[0]) @ W, torch.from_numpy(lab[0])).item()
     assert abs(sm.loss(0, x) - ref_loss) < 1e-12
+
+
+def test_logistic_limit_is_the_newton_optimum():
+    """No closed form, but the regularised logistic objective is strongly convex: its minimiser is
+    found independently by Newton's method on F = sum_i f_i (written out here with the logistic
+    Hessian), and the oracle, run with full local gradients over an exponential graph with
+    delays and losses, must converge to it although every shard is label-skewed."""
+    from oracle.rfast_oracle import RFastOracle
+    from rfast_workloads import graphs
+    from rfast_workloads.schedule import ScheduleSpec
+    n, p, m, lam = 8, 5, 30, 0.3
+    rng = np.random.default_rng(12)
+    X = rng.standard_normal((n, m, p))
+    teacher = rng.standard_normal(p)
+    y = (np.einsum("imp,p->im", X, teacher) + 0.5 * rng.standard_normal((n, m)) + 0.8 * (np.arange(n)[:, None] % 2) > 0)
+    y = y.astype(np.float64)
+    x = np.zeros(p)
+    for _ in range(40):                                   # Newton on F
+        g, H = np.zeros(p), np.zeros((p, p))
+        for i in range(n):
+            s = 1.0 / (1.0 + np.exp(-(X[i] @ x)))
+            g += X[i].T @ (s - y[i]) / m + lam * x
+            H += (X[i].T * (s * (1 - s))) @ X[i] / m + lam * np.eye(p)
+        x = x - np.linalg.solve(H, g)
+    assert np.abs(g).max() < 1e-13
+    x_star = x
+    wr, wc = graphs.exponential(n)
+    R, C = graphs.from_dense(wr, fp32_weights=False), graphs.from_dense(wc, fp32_weights=False)
+    obj = ob.Logistic(X, y, lam)
+    local_gap = max(np.abs(obj.grad(i, x_star, 0)).max() for i in range(n))
+    assert local_gap > 0.05                               # x* is no node's own optimum
+    orc = RFastOracle(n, p, R, C, D=7, burst=4, objective=obj)
+    sched = ScheduleSpec(n, R.nnz_off, C.nnz_off, np.full(n, 0.6), 4, 0.15, seed=2)
+    for r in range(6000):
+        q = sched.round(r)
+        orc.round(q.active, q.delay_R, q.delay_C, q.drop_R, q.drop_C, 0.5)
+    assert np.abs(orc.x - x_star).max() < 1e-8, np.abs(orc.x - x_star).max()
+    assert np.abs(orc.z).max() < 1e-8

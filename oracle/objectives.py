@@ -9,6 +9,13 @@ implemented here on its own from its published definition.
 Each objective offers  grad(i, x, version, batch_rows) -> float64 [p]  (the
 sample is identified by the node's local iteration stamp `version`, 0 for the
 initial gradient) and  loss(i, x) -> float  (the full local loss).
+
+Pins (tests/test_oracle_objectives.py, tests/test_oracle_pins.py): every gradient against
+finite differences of its loss; the softmax gradient against autograd and its bf16
+rounding against the library conversion; the generator against published known-answer
+vectors; the limits of least-squares, diagonal-quadratic and logistic runs against the
+closed-form / Newton optimum.  Parity unpinned: the limit of runs with SoftmaxBf16 (the
+bf16 rounding of W makes its gradient piecewise constant: no exact limit point exists).
 """
 from __future__ import annotations
 

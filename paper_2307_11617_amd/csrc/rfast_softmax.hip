@@ -179,7 +179,12 @@ __device__ __forceinline__ void fwd_multiply(f32x16 (&acc)[2], const u16* Xs, in
 
 // LOSS: instead of E, accumulate the mean cross-entropy of rows b0.. of EVERY node's
 // pool under the W held in node slot 0 (the node average) into *loss_out (B = samples).
-template <int NW, bool LOSS>
+// SC > 0: the number of 64-feature stages is this compile-time constant and the stage loop is
+// unrolled completely.  The compiler's wait-count bookkeeping only tells "the oldest stage has
+// arrived, two younger ones may still be in flight" apart in straight-line code: with a loop (or
+// conditional prefetches) it waits for every outstanding load at each stage, which exposes the
+// memory latency once per stage pair (0.84 us per stage measured) whatever the prefetch depth.
+template <int NW, bool LOSS, int SC = 0>
 __global__ void __launch_bounds__(64 * NW) rfast_softmax_forward(RfastDev s, const int32_t* batch_idx, int B, bool init,
                                                                  double* loss_out) {
   extern __shared__ u16 lds[];
@@ -208,7 +213,28 @@ __global__ void __launch_bounds__(64 * NW) rfast_softmax_forward(RfastDev s, con
 #pragma unroll
   for (int v = 0; v < 16; ++v) { acc[0][v] = 0.f; acc[1][v] = 0.f; }
 
-  const int S = d / kTile;
+  const int S = SC > 0 ? SC : d / kTile;
+  if constexpr (SC > 0) {
+    // three register sets in rotation: while stage st is multiplied out of LDS, the loads of
+    // stages st+1 .. st+3 are in flight and only the oldest of them is waited for
+    u32x4 rx[3][FwdShape<NW>::kXc], rw[3][4];
+    u16* bufs[2] = {lds, lds + kBuf};
+    fwd_load<NW>(rx[0], rw[0], pool, rows, wt, d, 0, tid);
+    fwd_store<NW>(rx[0], rw[0], bufs[0], bufs[0] + kTile * kLd, tid);
+    if (1 < SC) fwd_load<NW>(rx[1], rw[1], pool, rows, wt, d, 1 * kTile, tid);
+    if (2 < SC) fwd_load<NW>(rx[2], rw[2], pool, rows, wt, d, 2 * kTile, tid);
+    if (3 < SC) fwd_load<NW>(rx[0], rw[0], pool, rows, wt, d, 3 * kTile, tid);
+#pragma unroll
+    for (int st = 0; st < SC; ++st) {
+      __syncthreads();  // bufs[st & 1] holds stage st; everyone is done reading the other buffer
+      fwd_multiply<NW>(acc, bufs[st & 1], wave, lane);
+      if (st + 1 < SC) {
+        fwd_store<NW>(rx[(st + 1) % 3], rw[(st + 1) % 3], bufs[(st + 1) & 1], bufs[(st + 1) & 1] + kTile * kLd, tid);
+        if (st + 4 < SC) fwd_load<NW>(rx[(st + 1) % 3], rw[(st + 1) % 3], pool, rows, wt, d, (st + 4) * kTile, tid);
+      }
+    }
+    __syncthreads();
+  } else {
   // (ax, aw) carry the odd stages, (bx, bw) the even ones; neither pair is ever
   // copied, so a wait for one never implies a wait for the other (loads retire in order).
   u32x4 ax[FwdShape<NW>::kXc], aw[4], bx[FwdShape<NW>::kXc], bw[4];
@@ -233,6 +259,7 @@ __global__ void __launch_bounds__(64 * NW) rfast_softmax_forward(RfastDev s, con
     }
   }
   __syncthreads();
+  }
 
   // logits -> LDS [64][K+1] fp32 (reuses the staging space)
   float* L = reinterpret_cast<float*>(lds);
@@ -474,7 +501,10 @@ hipError_t rfast_softmax_gradient(rfast_ctx* c, const int32_t* batch_idx, bool i
       hipLaunchKernelGGL(rfast_softmax_backward<3>, bgrid, dim3(threads), lds_bwd, c->stream, d, bi, B, init);
       break;
     default:
-      hipLaunchKernelGGL((rfast_softmax_forward<4, false>), fgrid, dim3(threads), lds_fwd, c->stream, d, bi, B, init, (double*)nullptr);
+      if (d.prob.d == 16 * kTile)
+        hipLaunchKernelGGL((rfast_softmax_forward<4, false, 16>), fgrid, dim3(threads), lds_fwd, c->stream, d, bi, B, init, (double*)nullptr);
+      else
+        hipLaunchKernelGGL((rfast_softmax_forward<4, false>), fgrid, dim3(threads), lds_fwd, c->stream, d, bi, B, init, (double*)nullptr);
       hipLaunchKernelGGL(rfast_softmax_backward<4>, bgrid, dim3(threads), lds_bwd, c->stream, d, bi, B, init);
       break;
   }

@@ -33,7 +33,7 @@ struct Offsets {
   size_t x, z, g, v_ring, sigma_ring, rho_tilde;
   size_t r_ptr, r_src, r_dst, r_w, r_self, c_ptr, c_src, c_dst, c_w, c_self, co_ptr, co_eid, co_w, ro_ptr, ro_eid;
   size_t t, t_hist, tau_r, tau_c, deliv_r, deliv_c, round_no, err;
-  size_t n_active, active_list, plan_t, slot_r, slot_c, plan_c, node_spill;
+  size_t n_active, active_plan, plan_t, slot_r, slot_c, plan_c, node_spill;
   size_t gen_active, gen_delay_r, gen_delay_c, gen_drop_r, gen_drop_c, gen_batch, gen_cdf;
   size_t xbar, resid, gscratch, diag;
   size_t total;
@@ -88,7 +88,7 @@ Offsets layout(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, cons
   o.round_no = L.take(4);
   o.err = L.take(16);
   o.n_active = L.take(4);
-  o.active_list = L.take(n * 4);
+  o.active_plan = L.take(((size_t)n + 8) * 8);
   o.plan_t = L.take(n * 4);
   o.slot_r = L.take(eR * 4);
   o.slot_c = L.take(eC * 4);
@@ -434,7 +434,7 @@ int rfast_create(rfast_ctx** out, int32_t n, int64_t p, const int32_t* R_rowptr,
   d.tau_r = (int32_t*)(b + o.tau_r); d.tau_c = (int32_t*)(b + o.tau_c);
   d.deliv_r = (unsigned long long*)(b + o.deliv_r); d.deliv_c = (unsigned long long*)(b + o.deliv_c);
   d.round_no = (int32_t*)(b + o.round_no); d.err = (int32_t*)(b + o.err);
-  d.n_active = (int32_t*)(b + o.n_active); d.active_list = (int32_t*)(b + o.active_list);
+  d.n_active = (int32_t*)(b + o.n_active); d.active_plan = (int2*)(b + o.active_plan);
   d.plan_t = (int32_t*)(b + o.plan_t); d.slot_r = (int32_t*)(b + o.slot_r); d.slot_c = (int32_t*)(b + o.slot_c);
   d.plan_c = (int32_t*)(b + o.plan_c); d.node_spill = (uint8_t*)(b + o.node_spill);
   d.gen_active = (uint8_t*)(b + o.gen_active); d.gen_delay_r = (int32_t*)(b + o.gen_delay_r);

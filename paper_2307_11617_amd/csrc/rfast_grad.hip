@@ -35,14 +35,21 @@ __device__ inline int sample_row(const RfastDev& s, const int32_t* batch_idx, in
   return row;
 }
 
-// node handled by blockIdx.y: all nodes at initialisation, the round's active list otherwise
-__device__ inline int pick_node(const RfastDev& s, bool init) {
-  if (init) return blockIdx.y;
-  return (int)blockIdx.y < *s.n_active ? s.active_list[blockIdx.y] : -1;
+// node handled by blockIdx.y and the stamp of its stored sample (-1: the initial gradient is being
+// formed): all nodes at initialisation, the round's work slots otherwise
+__device__ inline int pick_node(const RfastDev& s, bool init, int* t_old) {
+  if (init) {
+    *t_old = -1;
+    return blockIdx.y;
+  }
+  const int2 slot = s.active_plan[blockIdx.y];
+  *t_old = slot.y;
+  return slot.x;
 }
 
 __global__ void __launch_bounds__(kThreads) rfast_rows_kernel(RfastDev s, const int32_t* batch_idx, int B, bool init) {
-  const int i = pick_node(s, init);
+  int t_unused;
+  const int i = pick_node(s, init, &t_unused);
   if (i < 0) return;
   const int b = blockIdx.x * kWaves + (threadIdx.x >> 6);
   if (b >= B) return;
@@ -99,7 +106,8 @@ __global__ void __launch_bounds__(kThreads) rfast_rows_kernel(RfastDev s, const 
 template <int VEC>
 __global__ void __launch_bounds__(kThreads) rfast_cols_kernel(RfastDev s, const int32_t* batch_idx, int B, bool init) {
   extern __shared__ float sh[];  // [B] residuals, [B] row numbers, then (VEC = 4) [4][64] float4 partial sums
-  const int i = pick_node(s, init);
+  int t_old;
+  const int i = pick_node(s, init, &t_old);
   if (i < 0) return;
   float* r_sh = sh;
   int* row_sh = reinterpret_cast<int*>(sh + B);
@@ -109,7 +117,6 @@ __global__ void __launch_bounds__(kThreads) rfast_cols_kernel(RfastDev s, const 
   }
   __syncthreads();
   const int64_t p = s.p;
-  const int t_old = init ? -1 : s.plan_t[i];
   float* g_new = s.g + (size_t)((t_old + 1) & 1) * s.n * p + (size_t)i * p;
   const float inv = 1.0f / (float)B;
   // l2 term of the logistic objective plus the weight decay of the optimizer variant

@@ -64,7 +64,10 @@ struct RfastDev {
   int32_t* err;           // [4] code, round, kind, edge (first error wins)
   // per-round plan written by the resolver, read by the state kernels
   int32_t* n_active;      // [1]
-  int32_t* active_list;   // [n]
+  // [n + 8] work slots of the round: {node, t_node at the start of the round}, the active nodes in
+  // increasing order first, then {-1, 0}.  One 8-byte load tells a workgroup whether it has work, for
+  // which node and at which counter (instead of a chain of three dependent loads).
+  int2* active_plan;
   int32_t* plan_t;        // [n]   t_i at the start of the round
   int32_t* slot_r;        // [eR]  resolved slot, -1 if receiver inactive
   int32_t* slot_c;        // [eC]

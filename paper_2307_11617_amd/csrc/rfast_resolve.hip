@@ -98,8 +98,9 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev
   for (int i0 = 0; i0 < s.n; i0 += kResolveThreads) {
     const int i = i0 + threadIdx.x;
     bool act = false;
+    int ti = 0;
     if (i < s.n) {
-      const int ti = s.t[i];
+      ti = s.t[i];
       s.plan_t[i] = ti;
       s.node_spill[i] = 0;
       s.t_hist[(size_t)i * s.H + (r % s.H)] = ti;
@@ -110,7 +111,7 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev
     __syncthreads();
     int off = base;
     for (int w = 0; w < wave; ++w) off += wave_cnt[w];
-    if (act) s.active_list[off + __popcll(m & ((1ull << lane) - 1ull))] = i;
+    if (act) s.active_plan[off + __popcll(m & ((1ull << lane) - 1ull))] = make_int2(i, ti);
     __syncthreads();
     if (threadIdx.x == 0) {
       int tot = 0;
@@ -120,6 +121,7 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev
     __syncthreads();
   }
   if (threadIdx.x == 0) *s.n_active = base;
+  for (int q = base + threadIdx.x; q < s.n + 8; q += kResolveThreads) s.active_plan[q] = make_int2(-1, 0);
   // plan_t and t_hist are complete (the barriers above); stamps per edge
   for (int e = threadIdx.x; e < s.eR + s.eC; e += kResolveThreads) {
     if (e < s.eR) resolve_edge(s, 0, e, r, active, delay_R, drop_R);

@@ -63,18 +63,18 @@ __device__ inline void emit_bf16_blocked(const RfastDev& s, int i, int tile, typ
 template <int MODE, int VEC, bool MOM, int KB>
 __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float gamma, int tiles_per_node) {
   using T = typename V<VEC>::T;
-  const int n_act = *s.n_active;
   const int a = blockIdx.x / tiles_per_node;
-  if (a >= n_act) return;
+  const int2 slot = s.active_plan[a];  // {node, its counter at the start of the round}, node < 0: no work
+  if (slot.x < 0) return;
   const int tile = blockIdx.x - a * tiles_per_node;
   const int64_t k = ((int64_t)tile * kThreads + threadIdx.x) * V<VEC>::W;
   if (k >= s.p) return;
 
   constexpr bool kMix = MODE != RFAST_MODE_TRACK, kTrack = MODE != RFAST_MODE_MIX;
-  const int i = s.active_list[a];
+  const int i = slot.x;
   const int64_t p = s.p;
   const int M = s.M;
-  const int t_old = s.plan_t[i];
+  const int t_old = slot.y;
   const int slot_new = (t_old + 1) % M;
   const int slot_cur = t_old % M;
   const size_t node_off = (size_t)i * p + k;
@@ -264,11 +264,12 @@ __global__ void __launch_bounds__(256) rfast_sync_plan_kernel(RfastDev s) {
   for (int i = threadIdx.x; i < s.n; i += blockDim.x) {
     const int ti = s.t[i];
     s.plan_t[i] = ti;
-    s.active_list[i] = i;
+    s.active_plan[i] = make_int2(i, ti);
     s.t[i] = ti + 1;
   }
   if (threadIdx.x == 0) {
     *s.n_active = s.n;
+    for (int q = 0; q < 8; ++q) s.active_plan[s.n + q] = make_int2(-1, 0);
     *s.round_no = *s.round_no + 1;
   }
 }

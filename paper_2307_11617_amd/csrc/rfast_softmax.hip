@@ -35,10 +35,15 @@ constexpr int kLd = kTile + kPad;
 
 __device__ inline u16 f32_to_bf16(float f) { return rfast_f32_to_bf16(f); }
 
-// node handled by work slot `slot`: all nodes at initialisation, the round's active list otherwise
-__device__ inline int pick_node(const RfastDev& s, bool init, int slot) {
+// node handled by work slot `slot` and the stamp of its stored sample (-1 while the initial gradient
+// is formed): all nodes at initialisation, the round's work slots otherwise (slot < n + 8: the
+// XCD-aware ids pad the slot count to a multiple of 8, and the slot array carries 8 spare entries)
+__device__ inline int pick_node(const RfastDev& s, bool init, int slot, int* t_old) {
+  *t_old = -1;
   if (init) return slot < s.n ? slot : -1;
-  return slot < *s.n_active ? s.active_list[slot] : -1;
+  const int2 ap = s.active_plan[slot];
+  *t_old = ap.y;
+  return ap.x;
 }
 
 // Workgroups are dealt to the 8 XCDs round-robin by linear id.  The `per_node`
@@ -83,7 +88,8 @@ __device__ __host__ inline Scratch scratch_of(const RfastDev& s, int B) {
 // wsrc != NULL: convert that matrix (the node average, for the loss) into node slot 0.
 __global__ void __launch_bounds__(256) rfast_softmax_prep(RfastDev s, int B, bool init, const float* wsrc) {
   extern __shared__ u16 lds[];  // [64][K+4]
-  const int i = pick_node(s, init, blockIdx.y);
+  int t_unused;
+  const int i = pick_node(s, init, blockIdx.y, &t_unused);
   if (i < 0) return;
   const int d = s.prob.d, K = s.prob.K, TS = K + 4;
   const int f0 = blockIdx.x * kTile;
@@ -190,7 +196,8 @@ __global__ void __launch_bounds__(64 * NW) rfast_softmax_forward(RfastDev s, con
   extern __shared__ u16 lds[];
   int slot, rb;
   xcd_decode(B / kTile, &slot, &rb);
-  const int i = pick_node(s, init, slot);
+  int t_unused;
+  const int i = pick_node(s, init, slot, &t_unused);
   if (i < 0) return;
   constexpr int K = 32 * NW;
   constexpr int kBuf = FwdShape<NW>::kBuf;
@@ -203,9 +210,13 @@ __global__ void __launch_bounds__(64 * NW) rfast_softmax_forward(RfastDev s, con
   const int32_t* labels = (const int32_t*)s.prob.data1 + (size_t)i * s.prob.samples;
   const Scratch sc = scratch_of(s, B);
   const u16* wt = sc.wt + (LOSS ? (size_t)0 : (size_t)i * K * d);
-  for (int r = tid; r < kTile; r += 64 * NW) {
-    rows[r] = sample_row(s, batch_idx, i, b0 + r, B);
-    labs[r] = labels[rows[r]];
+  // The label of a row is not needed before the softmax: its load (which depends on the row number,
+  // itself a load) is issued here and only parked in LDS after the contraction.
+  int my_label = 0;
+  if (tid < kTile) {
+    const int row = sample_row(s, batch_idx, i, b0 + tid, B);
+    rows[tid] = row;
+    my_label = labels[row];
   }
   __syncthreads();
 
@@ -261,6 +272,7 @@ __global__ void __launch_bounds__(64 * NW) rfast_softmax_forward(RfastDev s, con
   __syncthreads();
   }
 
+  if (tid < kTile) labs[tid] = my_label;
   // logits -> LDS [64][K+1] fp32 (reuses the staging space)
   float* L = reinterpret_cast<float*>(lds);
   constexpr int ldl = K + 1;
@@ -398,7 +410,8 @@ __global__ void __launch_bounds__(64 * NW) rfast_softmax_backward(RfastDev s, co
   int slot, fb;
   const int d = s.prob.d;
   xcd_decode(d / kTile, &slot, &fb);
-  const int i = pick_node(s, init, slot);
+  int t_old;
+  const int i = pick_node(s, init, slot, &t_old);
   if (i < 0) return;
   constexpr int K = 32 * NW;
   constexpr int kBuf = (kTile + K) * kLd;  // Xt tile [64 features][kLd], then Es [K][kLd]
@@ -436,7 +449,6 @@ __global__ void __launch_bounds__(64 * NW) rfast_softmax_backward(RfastDev s, co
       }
     }
   }
-  const int t_old = init ? -1 : s.plan_t[i];
   float* G = s.g + (size_t)((t_old + 1) & 1) * s.n * s.p + (size_t)i * s.p;
   const float* Wi = s.x + (size_t)i * s.p;  // weight decay of the optimizer variant acts on the fp32 weights
   const float wd = s.wd;

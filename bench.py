@@ -197,10 +197,12 @@ def main():
     bytes_prof = sum(algorithmic_bytes_per_round(w, a) for a in act_prof)
     bytes_layout = sum(algorithmic_bytes_per_round(w, a, layout=True) for a in act_prof)
     if args.sync:
-        # descent: x, z -> v (3 words); step: 1+dR v's, 1+dI z's, g_old (+ h, c | g_new) in; x, g_new|-, z out
+        # descent: x, z -> v (3 words); step: 1+dR v's, 1+dI z's in, x and z out, plus
+        #   separable objective: the old x (its sample is recomputed, not stored), h, c in (3 words)
+        #   otherwise: the old and the new sample in (2 words)
         dR = (w.R.dense() != 0).sum(axis=1) - 1
         dI = (w.C.dense() != 0).sum(axis=1) - 1
-        words = 3 + (1 + dR) + (1 + dI) + 1 + (2 + 3 if w.objective == "diag_quadratic" else 1 + 2)
+        words = 3 + (1 + dR) + (1 + dI) + 2 + (3 if w.objective == "diag_quadratic" else 2)
         bytes_prof = bytes_layout = float(words.sum() * 4.0 * w.p * K)
     if args.momentum != 0.0:   # read and write of the buffer m_i
         extra = 8.0 * w.p * (w.n * K if args.sync else float(act_prof.sum()))

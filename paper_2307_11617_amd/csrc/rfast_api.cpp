@@ -280,11 +280,11 @@ void drop_graph(rfast_ctx* c) {
   c->graph_exec = nullptr;
 }
 
-// automatic rebase of the running sums every `rebase_interval` rounds (0 = never)
+// automatic rebase of the running sums whenever the round counter reaches a multiple of
+// `rebase_interval` (0 = never): a function of the round number, so a restored run repeats it
 int after_round(rfast_ctx* c) {
   c->host_round++;
-  if (c->rebase_interval > 0 && ++c->rounds_since_rebase >= c->rebase_interval) {
-    c->rounds_since_rebase = 0;
+  if (c->rebase_interval > 0 && c->host_round % c->rebase_interval == 0) {
     const hipError_t e = rfast_launch_rebase(c);
     if (e != hipSuccess) return hipfail(c, e, "rebase launch");
   }
@@ -471,7 +471,6 @@ int rfast_init(rfast_ctx* c, const float* d_x0, const int32_t* d_batch_idx0) {
     return fail(c, RFAST_EINVAL, "initial sample rows are required when batch > 0");
   const size_t vec = (size_t)d.p * 4;
   c->sync_parity = 0;
-  c->rounds_since_rebase = 0;
   c->host_round = 0;
   c->needs_init = false;
   hipError_t e = hipSuccess;
@@ -582,11 +581,14 @@ int rfast_run_generated(rfast_ctx* c, int32_t rounds, uint64_t seed, const float
   // generator reads the round number on the device), so kGraphRounds of them are
   // captured once into a HIP graph and replayed: one launch per kGraphRounds rounds.
   if (c->needs_init) return fail(c, RFAST_EINVAL, "rfast_init must follow rfast_set_optimizer");
-  const bool graphs = c->use_graphs && !c->profiling && c->rebase_interval == 0;
+  const bool graphs = c->use_graphs && !c->profiling;
   while (rounds > 0) {
-    // a graph bakes the step size in, so a replay must not straddle a decay step of the schedule
+    // a graph bakes the step size in, so a replay must not straddle a decay step of the schedule,
+    // and it must hold no rebase, so it must end before the next multiple of the rebase interval
     const bool one_step_size = c->gamma_step <= 0 || c->host_round % c->gamma_step + kGraphRounds <= c->gamma_step;
-    if (graphs && rounds >= kGraphRounds && one_step_size) {
+    const bool no_rebase_inside =
+        c->rebase_interval <= 0 || c->host_round % c->rebase_interval + kGraphRounds < c->rebase_interval;
+    if (graphs && rounds >= kGraphRounds && one_step_size && no_rebase_inside) {
       if (fold_sync(c) != RFAST_OK) return RFAST_EHIP;
       const bool same = c->graph_exec && c->graph_seed == seed && c->graph_p_active == d_p_active &&
                         c->graph_max_delay == max_delay && c->graph_p_drop == p_drop && c->graph_gamma == gamma_now(c, gamma);
@@ -711,7 +713,6 @@ int rfast_set_gamma_schedule(rfast_ctx* c, int32_t step_rounds, float factor) {
 int rfast_set_rebase_interval(rfast_ctx* c, int32_t rounds) {
   if (!c || rounds < 0) return RFAST_EINVAL;
   c->rebase_interval = rounds;
-  c->rounds_since_rebase = 0;
   return RFAST_OK;
 }
 

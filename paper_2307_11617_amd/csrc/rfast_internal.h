@@ -106,7 +106,7 @@ struct rfast_ctx {
   std::vector<hipEvent_t> ev[3][2];
   size_t ev_used[3] = {0, 0, 0};
   double* d_diag = nullptr;  // carved from the workspace
-  int32_t rebase_interval = 0;
+  int32_t rebase_interval = 512;  // rounds between automatic rebases of the running sums (0 = never)
   // replayable HIP graph of kGraphRounds generated rounds (rfast_run_generated), and what it was built for
   bool use_graphs = false;
   hipGraphExec_t graph_exec = nullptr;
@@ -116,7 +116,6 @@ struct rfast_ctx {
   int32_t graph_max_delay = 0;
   float graph_p_drop = 0.f, graph_gamma = 0.f;
   int32_t sync_parity = 0;  // 1: the current z of the synchronous mode lives in slot 1 of the v ring
-  int32_t rounds_since_rebase = 0;
   int64_t host_round = 0;       // mirror of the device round counter, for the step-size schedule
   int32_t gamma_step = 0;       // rounds per decay step, 0 = constant step size
   float gamma_factor = 1.f;

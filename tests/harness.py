@@ -58,6 +58,11 @@ def upload_chunk(gpu, w, r0, r1):
     return st, dev
 
 
+def rf_set_interval(gpu, rounds):
+    from paper_2307_11617_amd import rfast_set_rebase_interval
+    rfast_set_rebase_interval(gpu.ctx, rounds)
+
+
 def rel_l2(a, b, floor=0.0):
     den = max(float(np.linalg.norm(b)), floor)
     return float(np.linalg.norm(a.astype(np.float64) - b) / den) if den > 0 else float(np.linalg.norm(a))
@@ -78,6 +83,9 @@ def run_parity(w, rounds, every=100, coords=None, x0=None, tol=None, check_rings
     step_rounds, factor = gamma_schedule if gamma_schedule is not None else (0, 1.0)
     if gamma_schedule is not None:
         gpu.set_gamma_schedule(step_rounds, factor)
+    compare_rings = check_rings and not rebase and coords is None and w.n * w.p * (w.D + 2) <= 4_000_000
+    if compare_rings:
+        rf_set_interval(gpu, 0)   # the ring / buffer comparison below needs unshifted running sums
     gpu.init(x0, w.sched.initial_batch())
     sel = slice(None) if coords is None else coords
     M = w.D + 2
@@ -118,7 +126,7 @@ def run_parity(w, rounds, every=100, coords=None, x0=None, tol=None, check_rings
             assert em <= tol, f"round {r1}: momentum buffer {em:.3e} (tol {tol})"
         if rebase:
             gpu.rebase()   # shifts rho and rho~ by a common offset: only their difference is comparable afterwards
-        if check_rings and not rebase and coords is None and w.n * w.p * M <= 4_000_000:
+        if compare_rings:
             vr, rr, rt = gpu.read("V_RING"), gpu.read("RHO_RING"), gpu.read("RHO_TILDE")
             for j in range(w.n):
                 tj = int(orc.t[j])

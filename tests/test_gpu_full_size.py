@@ -44,7 +44,8 @@ def test_config3_full_sampled():
 def test_config1_full():
     w = configs.config1()
     rounds = w.rounds if LONG else 1500
-    worst, orc, gpu = harness.run_parity(w, rounds, every=100, verbose=True)
+    # the library's defaults, automatic rebase every 512 rounds included (the rings are compared in the small case)
+    worst, orc, gpu = harness.run_parity(w, rounds, every=100, verbose=True, check_rings=False)
     _report(w.name + f" ({rounds} rounds)", worst)
 
 

@@ -52,5 +52,5 @@ def test_config1_full():
 def test_config4_full_size():
     w = configs.config4()
     rounds = w.rounds if LONG else 200
-    worst, orc, gpu = harness.run_parity(w, rounds, every=100, verbose=True)
+    worst, orc, gpu = harness.run_parity(w, rounds, every=100, verbose=True, check_rings=False)
     _report(w.name + f" ({rounds} rounds)", worst)

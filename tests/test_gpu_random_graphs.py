@@ -99,3 +99,50 @@ def test_buffers_that_leave_the_senders_ring():
     d = gpu.diagnostics()
     assert d["conservation_sq"] <= 1e-8 * max(d["gsum_sq"], 1.0)
     print(f"\n[{w.name}] worst {worst}, lags {np.bincount(np.minimum(lag, 8))}")
+
+
+@pytest.mark.parametrize("seed", list(range(100, 112)))
+def test_random_configuration_sweep(seed):
+    """Seeded random draws of everything at once: size, ring depth, burst bound, activity (uniform
+    or with near-idle nodes), loss rate, delays, vector length (float4 and scalar paths), step size.
+    Every checkpoint compares stamps, slots, x, z, g, the v and rho rings and the S4 buffers."""
+    rng = np.random.default_rng(seed)
+    n = int(rng.integers(2, 20))
+    p = int(rng.choice([1, 3, 4, 64, 130, 257, 516]))
+    d_max = int(rng.integers(0, 7))
+    burst = int(rng.integers(1, 6))
+    wr, wc = graphs.random_digraph(n, rng, extra=float(rng.uniform(0.0, 1.0)))
+    R, C = graphs.from_dense(wr), graphs.from_dense(wc)
+    p_act = rng.uniform(0.05, 1.0, n) if seed % 2 else np.full(n, float(rng.uniform(0.2, 1.0)))
+    sched = ScheduleSpec(n, R.nnz_off, C.nnz_off, p_act, d_max, float(rng.uniform(0.0, 0.9)), seed=seed)
+    w = configs.Workload(f"sweep_{seed}", n, p, R, C, d_max + burst - 1, burst, float(rng.uniform(0.005, 0.04)), 0,
+                         "diag_quadratic", problems.diag_quadratic(n, p, seed), sched, float(rng.choice([0.0, 0.1])),
+                         1000 + seed, 1e-4)
+    x0 = rng.standard_normal((n, p)).astype(np.float32) if seed % 3 == 0 else None
+    worst, orc, gpu = harness.run_parity(w, 160, every=20, x0=x0)
+    d = gpu.diagnostics()
+    assert d["conservation_sq"] <= 1e-7 * max(d["gsum_sq"], d["z_sq"], 1.0)
+
+
+@pytest.mark.parametrize("seed", list(range(200, 208)))
+def test_random_configuration_sweep_sampled_gradients(seed):
+    """The same kind of sweep on the split path (mix, gradient kernels, track): least squares with
+    full local gradients and logistic regression with minibatches, random sizes incl. odd p."""
+    rng = np.random.default_rng(seed)
+    n = int(rng.integers(2, 14))
+    p = int(rng.choice([5, 64, 132, 259, 1028]))
+    d_max = int(rng.integers(0, 6))
+    burst = int(rng.integers(1, 5))
+    wr, wc = graphs.random_digraph(n, rng, extra=float(rng.uniform(0.0, 0.8)))
+    p_act = rng.uniform(0.1, 1.0, n)
+    if seed % 2:
+        m = int(rng.integers(3, 40))
+        w = configs._mk(f"sweep_ls_{seed}", n, p, wr, wc, d_max, 0.4 / p, 0, "least_squares",
+                        problems.least_squares(n, p, m, seed), p_act, float(rng.uniform(0, 0.6)), seed, samples=m, burst=burst)
+    else:
+        samples = int(rng.integers(8, 80))
+        batch = int(rng.integers(1, samples + 1))
+        w = configs._mk(f"sweep_logistic_{seed}", n, p, wr, wc, d_max, 0.05, 0, "logistic",
+                        problems.logistic(n, p, samples, seed), p_act, float(rng.uniform(0, 0.6)), seed, batch=batch,
+                        samples=samples, burst=burst)
+    worst, orc, gpu = harness.run_parity(w, 120, every=30)

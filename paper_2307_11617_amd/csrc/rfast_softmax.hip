@@ -404,7 +404,10 @@ __device__ __forceinline__ void bwd_store(const u32x4 (&x)[FwdShape<NW>::kXc], c
   }
 }
 
-template <int NW>
+// SC > 0: B = 64 * SC rows at compile time: every row number is fetched once up front (not one
+// dependent load per stage on the critical path), the stage loop is unrolled completely and three
+// stages of loads stay in flight with exact wait counts (see the forward pass).
+template <int NW, int SC = 0>
 __global__ void __launch_bounds__(64 * NW) rfast_softmax_backward(RfastDev s, const int32_t* batch_idx, int B, bool init) {
   extern __shared__ u16 lds[];
   int slot, fb;
@@ -425,6 +428,34 @@ __global__ void __launch_bounds__(64 * NW) rfast_softmax_backward(RfastDev s, co
 #pragma unroll
   for (int v = 0; v < 16; ++v) { acc[0][v] = 0.f; acc[1][v] = 0.f; }
 
+  if constexpr (SC > 0) {
+    __shared__ int rows_all[(SC > 0 ? SC : 1) * kTile];
+    for (int r = tid; r < SC * kTile; r += 64 * NW) rows_all[r] = sample_row(s, batch_idx, i, r, B);
+    __syncthreads();
+    u32x4 rx[3][FwdShape<NW>::kXc], re[3][4];
+    bwd_load<NW>(rx[0], re[0], pool, rows_all, et, d, B, f0, 0, tid);
+    if (1 < SC) bwd_load<NW>(rx[1], re[1], pool, rows_all + kTile, et, d, B, f0, kTile, tid);
+    if (2 < SC) bwd_load<NW>(rx[2], re[2], pool, rows_all + 2 * kTile, et, d, B, f0, 2 * kTile, tid);
+#pragma unroll
+    for (int st = 0; st < SC; ++st) {
+      u16* Xt = lds + (st & 1) * kBuf;
+      u16* Es = Xt + kTile * kLd;
+      bwd_store<NW>(rx[st % 3], re[st % 3], Xt, Es, tid);  // stage st (its buffer was last read two stages ago)
+      if (st + 3 < SC)
+        bwd_load<NW>(rx[st % 3], re[st % 3], pool, rows_all + (st + 3) * kTile, et, d, B, f0, (st + 3) * kTile, tid);
+      __syncthreads();
+#pragma unroll
+      for (int kk = 0; kk < kTile; kk += 16) {
+        const int off = kk + 8 * (lane >> 5);
+        const bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(&Es[(wave * 32 + (lane & 31)) * kLd + off]);
+#pragma unroll
+        for (int ft = 0; ft < 2; ++ft) {
+          const bf16x8 afrag = *reinterpret_cast<const bf16x8*>(&Xt[(ft * 32 + (lane & 31)) * kLd + off]);
+          acc[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag, acc[ft], 0, 0, 0);
+        }
+      }
+    }
+  } else {
   const int S = B / kTile;
   for (int r = tid; r < kTile; r += 64 * NW) rows[0][r] = sample_row(s, batch_idx, i, r, B);
   __syncthreads();
@@ -448,6 +479,7 @@ __global__ void __launch_bounds__(64 * NW) rfast_softmax_backward(RfastDev s, co
         acc[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag, acc[ft], 0, 0, 0);
       }
     }
+  }
   }
   float* G = s.g + (size_t)((t_old + 1) & 1) * s.n * s.p + (size_t)i * s.p;
   const float* Wi = s.x + (size_t)i * s.p;  // weight decay of the optimizer variant acts on the fp32 weights
@@ -517,7 +549,10 @@ hipError_t rfast_softmax_gradient(rfast_ctx* c, const int32_t* batch_idx, bool i
         hipLaunchKernelGGL((rfast_softmax_forward<4, false, 16>), fgrid, dim3(threads), lds_fwd, c->stream, d, bi, B, init, (double*)nullptr);
       else
         hipLaunchKernelGGL((rfast_softmax_forward<4, false>), fgrid, dim3(threads), lds_fwd, c->stream, d, bi, B, init, (double*)nullptr);
-      hipLaunchKernelGGL(rfast_softmax_backward<4>, bgrid, dim3(threads), lds_bwd, c->stream, d, bi, B, init);
+      if (B == 4 * kTile)
+        hipLaunchKernelGGL((rfast_softmax_backward<4, 4>), bgrid, dim3(threads), lds_bwd, c->stream, d, bi, B, init);
+      else
+        hipLaunchKernelGGL(rfast_softmax_backward<4>, bgrid, dim3(threads), lds_bwd, c->stream, d, bi, B, init);
       break;
   }
   return hipGetLastError();

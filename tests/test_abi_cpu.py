@@ -132,6 +132,12 @@ def test_null_context_calls_fail_cleanly():
     assert L.rfast_init(None, None, None) == -1
     assert L.rfast_round(None, None, None, None, None, None, 0.1, None) == -1
     assert L.rfast_check(None) == -1
+    assert L.rfast_set_optimizer(None, 0.9, 0.0, None) == -1
+    assert L.rfast_set_gamma_schedule(None, 10, 0.5) == -1
+    assert L.rfast_run_generated(None, 1, 0, None, 0, 0.0, 0.1) == -1
+    assert L.rfast_run_events(None, 1, 0, None, 0, 0.0, 0.1) == -1
+    assert L.rfast_set_rebase_interval(None, 10) == -1
+    assert L.rfast_write_state(None, 0, None, 0) == -1
     L.rfast_destroy(None)
 
 

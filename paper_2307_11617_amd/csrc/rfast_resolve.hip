@@ -31,60 +31,82 @@ __device__ inline void record_error(int32_t* err, int code, int round, int kind,
   }
 }
 
-// One lane per off-diagonal entry.  kind 0: graph R (v packets), kind 1: graph C (rho packets).
-__device__ void resolve_edge(const RfastDev& s, int kind, int e, int r, const uint8_t* active,
-                             const int32_t* delay, const uint8_t* drop) {
-  const int i = (kind ? s.c_dst : s.r_dst)[e];
-  const int j = (kind ? s.c_src : s.r_src)[e];
+// What one lane knows about its edge before it decides anything.  The loads come in two levels of
+// dependency (by edge number; by the node numbers and the delay found there), and both are issued
+// ahead of the node pass of the kernel, so that the whole resolver costs about two memory round
+// trips instead of four or five.
+struct EdgeIn {
+  int i, j, d, old, tj, u;
+  unsigned long long bits;
+  bool act_i, act_j, dropped;
+};
+
+// kind 0: graph R (v packets), kind 1: graph C (rho packets); e counts within its graph
+__device__ inline void edge_level1(const RfastDev& s, int kind, int e, const int32_t* delay, const uint8_t* drop, EdgeIn* q) {
+  q->i = (kind ? s.c_dst : s.r_dst)[e];
+  q->j = (kind ? s.c_src : s.r_src)[e];
+  q->bits = (kind ? s.deliv_c : s.deliv_r)[e];
+  q->d = delay[e];
+  q->old = (kind ? s.tau_c : s.tau_r)[e];
+  q->dropped = drop[e] != 0;
+}
+
+__device__ inline void edge_level2(const RfastDev& s, int r, const uint8_t* active, EdgeIn* q) {
+  q->act_i = active[q->i] != 0;
+  q->act_j = active[q->j] != 0;
+  q->tj = s.t[q->j];  // the counters are advanced only after the last barrier of the kernel
+  const int d = q->d < 0 ? 0 : (q->d > s.d_max ? s.d_max : q->d);
+  const int at = r - d;
+  // the sender's counter at the start of round `at`; round r itself is the current counter (its
+  // history slot is being written by the node pass)
+  q->u = at <= 0 ? 0 : (at >= r ? q->tj : s.t_hist[(size_t)q->j * s.H + (at % s.H)]);
+}
+
+__device__ inline void edge_decide(const RfastDev& s, int kind, int e, int r, const EdgeIn& q) {
   int32_t* tau = kind ? s.tau_c : s.tau_r;
   int32_t* slot = kind ? s.slot_c : s.slot_r;
   unsigned long long* deliv = kind ? s.deliv_c : s.deliv_r;
-  const unsigned long long bits = deliv[e];
-  if (active[i] != 0) {
-    int d = delay[e];
-    if (d < 0 || d > s.d_max) {
-      record_error(s.err, RFAST_ERANGE, r, kind, e);
-      d = d < 0 ? 0 : s.d_max;
-    }
-    const int at = r - d;
-    int u = at <= 0 ? 0 : s.t_hist[(size_t)j * s.H + (at % s.H)];
-    while (!delivered(bits, u, s.M)) --u;  // at most burst-1 steps; version 0 always counts as delivered
-    const int old = tau[e];
+  const int lo = q.tj - (s.M - 2);  // oldest version that stays readable in j's ring during this round
+  if (q.act_i) {
+    if (q.d < 0 || q.d > s.d_max) record_error(s.err, RFAST_ERANGE, r, kind, e);  // clamped in edge_level2
+    int u = q.u;
+    while (!delivered(q.bits, u, s.M)) --u;  // at most burst-1 steps; version 0 always counts as delivered
+    const int old = q.old;
     const int now = u > old ? u : old;
     tau[e] = now;
     slot[e] = now % s.M;
     if (kind) {
-      const int lo = s.plan_t[j] - (s.M - 2);  // oldest version that stays readable in j's ring during this round
       const bool live = now != old;
       // after this round the ring of an active sender no longer covers version lo
-      const bool leaves = active[j] != 0 && now == lo;
+      const bool leaves = q.act_j && now == lo;
       const bool spill = !live && leaves;
       s.plan_c[e] = (now % s.M) | ((old >= lo ? old % s.M : 0xFF) << 8) | (live ? 1 << 16 : 0) |
                     (live && leaves ? 1 << 17 : 0) | (spill ? 1 << 18 : 0);
-      if (spill) s.node_spill[j] = 1;
+      if (spill) s.node_spill[q.j] = 1;
     }
   } else {
     slot[e] = -1;
     if (kind) {
-      const bool spill = active[j] != 0 && tau[e] == s.plan_t[j] - (s.M - 2);
+      const bool spill = q.act_j && q.old == lo;
       s.plan_c[e] = spill ? 1 << 18 : 0;
-      if (spill) s.node_spill[j] = 1;
+      if (spill) s.node_spill[q.j] = 1;
     }
   }
-  if (active[j] != 0) {  // the sender publishes version t_j + 1 this round
-    const int vn = s.plan_t[j] + 1;
-    bool ok = drop[e] == 0;
+  if (q.act_j) {  // the sender publishes version t_j + 1 this round
+    const int vn = q.tj + 1;
+    bool ok = !q.dropped;
     if (!ok) {
       bool all_lost = true;
-      for (int k = 1; k < s.burst; ++k) all_lost = all_lost && !delivered(bits, vn - k, s.M);
+      for (int k = 1; k < s.burst; ++k) all_lost = all_lost && !delivered(q.bits, vn - k, s.M);
       ok = all_lost;
     }
     const unsigned long long bit = 1ull << (vn % s.M);
-    deliv[e] = ok ? (bits | bit) : (bits & ~bit);
+    deliv[e] = ok ? (q.bits | bit) : (q.bits & ~bit);
   }
 }
 
 constexpr int kResolveThreads = 1024;
+constexpr int kAhead = 2;  // edges per lane whose loads are issued before the node pass
 
 __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev s, const uint8_t* active,
                                                                          const int32_t* delay_R, const int32_t* delay_C,
@@ -93,8 +115,19 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev
   __shared__ int base;
   const int r = *s.round_no;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int E = s.eR + s.eC;
+  EdgeIn ahead[kAhead];
+#pragma unroll
+  for (int a = 0; a < kAhead; ++a) {
+    const int e = threadIdx.x + a * kResolveThreads;
+    if (e < s.eR) edge_level1(s, 0, e, delay_R, drop_R, &ahead[a]);
+    else if (e < E) edge_level1(s, 1, e - s.eR, delay_C, drop_C, &ahead[a]);
+  }
+#pragma unroll
+  for (int a = 0; a < kAhead; ++a)
+    if (threadIdx.x + a * kResolveThreads < E) edge_level2(s, r, active, &ahead[a]);
   if (threadIdx.x == 0) base = 0;
-  // snapshot of the counters, and the ordered list of active nodes (ballot + prefix per chunk)
+  // node pass: snapshot of the counters, and the ordered list of active nodes (ballot + prefix per chunk)
   for (int i0 = 0; i0 < s.n; i0 += kResolveThreads) {
     const int i = i0 + threadIdx.x;
     bool act = false;
@@ -122,12 +155,20 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev
   }
   if (threadIdx.x == 0) *s.n_active = base;
   for (int q = base + threadIdx.x; q < s.n + 8; q += kResolveThreads) s.active_plan[q] = make_int2(-1, 0);
-  // plan_t and t_hist are complete (the barriers above); stamps per edge
-  for (int e = threadIdx.x; e < s.eR + s.eC; e += kResolveThreads) {
-    if (e < s.eR) resolve_edge(s, 0, e, r, active, delay_R, drop_R);
-    else resolve_edge(s, 1, e - s.eR, r, active, delay_C, drop_C);
+  // edge pass (node_spill was cleared above, before the barriers); nothing in it depends on the node pass
+#pragma unroll
+  for (int a = 0; a < kAhead; ++a) {
+    const int e = threadIdx.x + a * kResolveThreads;
+    if (e < E) edge_decide(s, e >= s.eR, e >= s.eR ? e - s.eR : e, r, ahead[a]);
   }
-  __syncthreads();
+  for (int e = threadIdx.x + kAhead * kResolveThreads; e < E; e += kResolveThreads) {  // more than 2048 edges
+    const int kind = e >= s.eR, el = kind ? e - s.eR : e;
+    EdgeIn q;
+    edge_level1(s, kind, el, kind ? delay_C : delay_R, kind ? drop_C : drop_R, &q);
+    edge_level2(s, r, active, &q);
+    edge_decide(s, kind, el, r, q);
+  }
+  __syncthreads();  // every read of the counters is done
   for (int i = threadIdx.x; i < s.n; i += kResolveThreads)
     if (active[i] != 0) s.t[i] = s.plan_t[i] + 1;
   if (threadIdx.x == 0) *s.round_no = r + 1;

@@ -126,6 +126,9 @@ def main():
     ap.add_argument("--momentum", type=float, default=0.0,
                     help="optimizer variant (not the headline workload): heavy-ball buffer, +2 words per coordinate")
     ap.add_argument("--weight-decay", type=float, default=0.0, help="optimizer variant: weight decay inside the gradient")
+    ap.add_argument("--no-blocks", action="store_true",
+                    help="one kernel pass per round even where several rounds per launch are possible")
+    ap.add_argument("--noise-std", type=float, default=None, help="override the gradient noise (not the headline workload)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only a plain 1 GiB device copy (10 launches): calibrates HBM byte counters")
     args = ap.parse_args()
@@ -151,7 +154,11 @@ def main():
     w = configs.CONFIGS[args.config](**kw)
     gen_s = time.perf_counter() - t_gen
     K, W = args.steps, args.warmup
+    if args.noise_std is not None:
+        w.noise_std = args.noise_std
     gpu = harness.make_gpu(w)
+    if args.no_blocks:
+        rf.rfast_use_blocks(gpu.ctx, False)
     variant = args.momentum != 0.0 or args.weight_decay != 0.0
     if variant:
         gpu.set_optimizer(args.momentum, args.weight_decay)

@@ -224,6 +224,16 @@ int rfast_run_events(rfast_ctx* ctx, int32_t iterations, uint64_t seed, const fl
  * run as ordinary launches.  Results are identical either way.  Off by default. */
 int rfast_use_graphs(rfast_ctx* ctx, int32_t on);
 
+/* on != 0 (the default): rfast_run and rfast_run_generated advance up to 16 rounds with one
+ * launch where that is possible and pays -- the separable objective (diagonal quadratic) without
+ * the momentum variant, p a multiple of 4, at most 64 nodes, 64 coordinates of every node's two
+ * rings fitting into the 160 KB of LDS of a CU (n * (D+2) * 512 B + nnzC_off * 256 B + plans), and
+ * n * p * 4 <= 8 MB (beyond that, streaming one round per pass is faster).  Every step of a round
+ * is elementwise in the coordinate, so a tile of coordinates can stay in LDS over several rounds;
+ * the results are the same bits as round-by-round execution.  on == 0: always one kernel pass
+ * per round. */
+int rfast_use_blocks(rfast_ctx* ctx, int32_t on);
+
 /* One step of the synchronous push-pull recursion the method is developed from
  * (eq. (2) of the paper), on the same x, z and stored gradient samples:
  *   x_i' = sum_j w_ij (x_j - gamma z_j),  z_i' = sum_j a_ij z_j + grad f_i(x_i'; zeta') - grad f_i(x_i; zeta)

@@ -33,7 +33,7 @@ struct Offsets {
   size_t x, z, g, v_ring, sigma_ring, rho_tilde;
   size_t r_ptr, r_src, r_dst, r_w, r_self, c_ptr, c_src, c_dst, c_w, c_self, co_ptr, co_eid, co_w, ro_ptr, ro_eid;
   size_t t, t_hist, tau_r, tau_c, deliv_r, deliv_c, round_no, err;
-  size_t n_active, active_plan, plan_t, slot_r, slot_c, plan_c, node_spill;
+  size_t n_active, active_plan, plan_t, slot_r, slot_c, plan_c, node_spill, blk_plan;
   size_t gen_active, gen_delay_r, gen_delay_c, gen_drop_r, gen_drop_c, gen_batch, gen_cdf;
   size_t xbar, resid, gscratch, diag;
   size_t total;
@@ -94,6 +94,7 @@ Offsets layout(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, cons
   o.slot_c = L.take(eC * 4);
   o.plan_c = L.take(eC * 4);
   o.node_spill = L.take(n);
+  o.blk_plan = L.take((size_t)kBlockRounds * ((size_t)n + eR + eC) * 4);
   o.gen_active = L.take(n);
   o.gen_delay_r = L.take(eR * 4);
   o.gen_delay_c = L.take(eC * 4);
@@ -437,6 +438,8 @@ int rfast_create(rfast_ctx** out, int32_t n, int64_t p, const int32_t* R_rowptr,
   d.n_active = (int32_t*)(b + o.n_active); d.active_plan = (int2*)(b + o.active_plan);
   d.plan_t = (int32_t*)(b + o.plan_t); d.slot_r = (int32_t*)(b + o.slot_r); d.slot_c = (int32_t*)(b + o.slot_c);
   d.plan_c = (int32_t*)(b + o.plan_c); d.node_spill = (uint8_t*)(b + o.node_spill);
+  d.blk_plan = nullptr;
+  c->blk_plan_base = (int32_t*)(b + o.blk_plan);
   d.gen_active = (uint8_t*)(b + o.gen_active); d.gen_delay_r = (int32_t*)(b + o.gen_delay_r);
   d.gen_delay_c = (int32_t*)(b + o.gen_delay_c); d.gen_drop_r = (uint8_t*)(b + o.gen_drop_r);
   d.gen_drop_c = (uint8_t*)(b + o.gen_drop_c); d.gen_batch = (int32_t*)(b + o.gen_batch);
@@ -545,12 +548,89 @@ int rfast_round(rfast_ctx* c, const uint8_t* d_active, const int32_t* d_delay_R,
   return after_round(c);
 }
 
+// How many of the next `rounds` rounds one launch of the LDS-resident kernel may take: it holds
+// no rebase, so it must end at the latest on the next multiple of the rebase interval.
+static int32_t block_length(const rfast_ctx* c, int32_t rounds) {
+  int32_t len = rounds < kBlockRounds ? rounds : kBlockRounds;
+  if (c->rebase_interval > 0) {
+    const int64_t to_boundary = c->rebase_interval - c->host_round % c->rebase_interval;
+    if (to_boundary < len) len = (int32_t)to_boundary;
+  }
+  return len;
+}
+
+// Resolves `len` rounds (schedule arrays of round q at offset q of each pointer, or generated on
+// the device when seed_gen is set) into plan records and advances them with one launch.
+static int run_block(rfast_ctx* c, int32_t len, const uint8_t* d_active, const int32_t* d_delay_R,
+                     const int32_t* d_delay_C, const uint8_t* d_drop_R, const uint8_t* d_drop_C, float gamma,
+                     bool generated, uint64_t seed, const float* d_p_active, int32_t max_delay, float p_drop) {
+  RfastDev& d = c->d;
+  if (fold_sync(c) != RFAST_OK) return RFAST_EHIP;
+  const size_t PL = (size_t)d.n + d.eR + d.eC;
+  RfastBlock blk;
+  blk.rounds = len;
+  hipError_t e = hipSuccess;
+  time_begin(c, 2);
+  for (int32_t q = 0; q < len && e == hipSuccess; ++q) {
+    blk.gamma[q] = gamma_now(c, gamma);
+    d.blk_plan = c->blk_plan_base + (size_t)q * PL;
+    if (generated) {
+      e = rfast_launch_generate(c, seed, d_p_active, max_delay, p_drop, false);
+      if (e == hipSuccess)
+        e = rfast_launch_resolve(c, d.gen_active, d.gen_delay_r, d.gen_delay_c, d.gen_drop_r, d.gen_drop_c);
+    } else {
+      e = rfast_launch_resolve(c, d_active + (size_t)q * d.n, d_delay_R ? d_delay_R + (size_t)q * d.eR : nullptr,
+                               d_delay_C ? d_delay_C + (size_t)q * d.eC : nullptr,
+                               d_drop_R ? d_drop_R + (size_t)q * d.eR : nullptr,
+                               d_drop_C ? d_drop_C + (size_t)q * d.eC : nullptr);
+    }
+    c->host_round++;
+  }
+  time_end(c, 2);
+  d.blk_plan = c->blk_plan_base;
+  if (e == hipSuccess) {
+    time_begin(c, 0);
+    e = rfast_launch_block(c, blk);
+    time_end(c, 0);
+  }
+  d.blk_plan = nullptr;
+  if (e != hipSuccess) return hipfail(c, e, "multi-round launch");
+  if (c->rebase_interval > 0 && c->host_round % c->rebase_interval == 0) {
+    e = rfast_launch_rebase(c);
+    if (e != hipSuccess) return hipfail(c, e, "rebase launch");
+  }
+  return RFAST_OK;
+}
+
+int rfast_use_blocks(rfast_ctx* c, int32_t on) {
+  if (!c) return RFAST_EINVAL;
+  c->use_blocks = on != 0;
+  return RFAST_OK;
+}
+
 int rfast_run(rfast_ctx* c, int32_t rounds, const uint8_t* d_active, const int32_t* d_delay_R, const int32_t* d_delay_C,
               const uint8_t* d_drop_R, const uint8_t* d_drop_C, float gamma, const int32_t* d_batch_idx) {
   if (!c) return RFAST_EINVAL;
   if (rounds < 0) return fail(c, RFAST_EINVAL, "rounds < 0");
   const RfastDev& d = c->d;
   const size_t B = d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC ? 0 : (size_t)d.prob.batch;
+  if (c->use_blocks && rounds > 1 && rfast_block_eligible(c)) {
+    // the separable objective on a small graph: tiles of coordinates stay in LDS over up to kBlockRounds rounds
+    if (!d_active || (d.eR && (!d_delay_R || !d_drop_R)) || (d.eC && (!d_delay_C || !d_drop_C)))
+      return fail(c, RFAST_EINVAL, "NULL schedule pointer");
+    if (!std::isfinite(gamma)) return fail(c, RFAST_EINVAL, "gamma is not finite");
+    if (c->needs_init) return fail(c, RFAST_EINVAL, "rfast_init must follow rfast_set_optimizer");
+    for (int32_t r = 0; r < rounds;) {
+      const int32_t len = block_length(c, rounds - r);
+      const int rc = run_block(c, len, d_active + (size_t)r * d.n, d_delay_R ? d_delay_R + (size_t)r * d.eR : nullptr,
+                               d_delay_C ? d_delay_C + (size_t)r * d.eC : nullptr,
+                               d_drop_R ? d_drop_R + (size_t)r * d.eR : nullptr,
+                               d_drop_C ? d_drop_C + (size_t)r * d.eC : nullptr, gamma, false, 0, nullptr, 0, 0.f);
+      if (rc != RFAST_OK) return rc;
+      r += len;
+    }
+    return RFAST_OK;
+  }
   for (int32_t r = 0; r < rounds; ++r) {
     const int rc = rfast_round(c, d_active + (size_t)r * d.n, d_delay_R ? d_delay_R + (size_t)r * d.eR : nullptr,
                                d_delay_C ? d_delay_C + (size_t)r * d.eC : nullptr,
@@ -582,6 +662,16 @@ int rfast_run_generated(rfast_ctx* c, int32_t rounds, uint64_t seed, const float
   // captured once into a HIP graph and replayed: one launch per kGraphRounds rounds.
   if (c->needs_init) return fail(c, RFAST_EINVAL, "rfast_init must follow rfast_set_optimizer");
   const bool graphs = c->use_graphs && !c->profiling;
+  if (!graphs && c->use_blocks && rounds > 1 && rfast_block_eligible(c)) {
+    while (rounds > 0) {
+      const int32_t len = block_length(c, rounds);
+      const int rc = run_block(c, len, nullptr, nullptr, nullptr, nullptr, nullptr, gamma, true, seed, d_p_active, max_delay,
+                               p_drop);
+      if (rc != RFAST_OK) return rc;
+      rounds -= len;
+    }
+    return RFAST_OK;
+  }
   while (rounds > 0) {
     // a graph bakes the step size in, so a replay must not straddle a decay step of the schedule,
     // and it must hold no rebase, so it must end before the next multiple of the rebase interval

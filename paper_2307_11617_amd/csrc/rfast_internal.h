@@ -79,6 +79,10 @@ struct RfastDev {
   //   bit 18     the sender copies a_ij * sigma_j[t_j - D] to the rho_tilde array
   int32_t* plan_c;        // [eC]
   uint8_t* node_spill;    // [n]   some out-edge of this node has bit 18 set
+  // The plan of one round once more, as one record for the kernel that keeps a tile of coordinates
+  // in LDS over several rounds (NULL: not wanted): [n] node words (bit 31 active, low 30 bits the
+  // counter at the start of the round), [eR] ring slot per R edge, [eC] plan word per C edge.
+  int32_t* blk_plan;
   // schedule of the current round when it is generated on the device
   uint8_t* gen_active;    // [n]
   int32_t* gen_delay_r;   // [eR]
@@ -120,15 +124,27 @@ struct rfast_ctx {
   int32_t gamma_step = 0;       // rounds per decay step, 0 = constant step size
   float gamma_factor = 1.f;
   bool needs_init = false;      // rfast_set_optimizer was called and rfast_init has not followed yet
+  bool use_blocks = true;       // rfast_run / rfast_run_generated may advance several rounds per launch
+  int32_t* blk_plan_base = nullptr;  // kBlockRounds plan records
 };
 
 enum { RFAST_MODE_FUSED = 0, RFAST_MODE_MIX = 1, RFAST_MODE_TRACK = 2 };
+
+// rounds that one launch of the LDS-resident kernel can advance
+constexpr int kBlockRounds = 16;
+struct RfastBlock {
+  float gamma[kBlockRounds];  // step size of each round
+  int32_t rounds;             // 1 .. kBlockRounds
+};
 
 // launchers (each enqueues on ctx->stream and returns a hipError_t)
 hipError_t rfast_launch_resolve(rfast_ctx* c, const uint8_t* active, const int32_t* delay_R,
                                 const int32_t* delay_C, const uint8_t* drop_R, const uint8_t* drop_C);
 hipError_t rfast_launch_state(rfast_ctx* c, int mode, float gamma);
 hipError_t rfast_launch_rebase(rfast_ctx* c);
+// several rounds of the separable objective on LDS-resident tiles; the rounds' plans are in blk_plan
+bool rfast_block_eligible(const rfast_ctx* c);
+hipError_t rfast_launch_block(rfast_ctx* c, const RfastBlock& blk);
 hipError_t rfast_launch_generate(rfast_ctx* c, uint64_t seed, const float* d_p_active, int d_max, float p_drop, bool events);
 hipError_t rfast_launch_sync(rfast_ctx* c, int phase, float gamma, int parity);
 hipError_t rfast_launch_init_grad(rfast_ctx* c, const int32_t* batch_idx0);

@@ -75,20 +75,25 @@ __device__ inline void edge_decide(const RfastDev& s, int kind, int e, int r, co
     const int now = u > old ? u : old;
     tau[e] = now;
     slot[e] = now % s.M;
+    if (s.blk_plan && !kind) s.blk_plan[s.n + e] = now % s.M;
     if (kind) {
       const bool live = now != old;
       // after this round the ring of an active sender no longer covers version lo
       const bool leaves = q.act_j && now == lo;
       const bool spill = !live && leaves;
-      s.plan_c[e] = (now % s.M) | ((old >= lo ? old % s.M : 0xFF) << 8) | (live ? 1 << 16 : 0) |
-                    (live && leaves ? 1 << 17 : 0) | (spill ? 1 << 18 : 0);
+      const int word = (now % s.M) | ((old >= lo ? old % s.M : 0xFF) << 8) | (live ? 1 << 16 : 0) |
+                       (live && leaves ? 1 << 17 : 0) | (spill ? 1 << 18 : 0);
+      s.plan_c[e] = word;
+      if (s.blk_plan) s.blk_plan[s.n + s.eR + e] = word;
       if (spill) s.node_spill[q.j] = 1;
     }
   } else {
     slot[e] = -1;
+    if (s.blk_plan && !kind) s.blk_plan[s.n + e] = 0;
     if (kind) {
       const bool spill = q.act_j && q.old == lo;
       s.plan_c[e] = spill ? 1 << 18 : 0;
+      if (s.blk_plan) s.blk_plan[s.n + s.eR + e] = spill ? 1 << 18 : 0;
       if (spill) s.node_spill[q.j] = 1;
     }
   }
@@ -138,6 +143,7 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev
       s.node_spill[i] = 0;
       s.t_hist[(size_t)i * s.H + (r % s.H)] = ti;
       act = active[i] != 0;
+      if (s.blk_plan) s.blk_plan[i] = (ti & 0x3FFFFFFF) | (act ? (int)0x80000000 : 0);
     }
     const unsigned long long m = __ballot(act);
     if (lane == 0) wave_cnt[wave] = __popcll(m);

@@ -128,6 +128,8 @@ def main():
     ap.add_argument("--weight-decay", type=float, default=0.0, help="optimizer variant: weight decay inside the gradient")
     ap.add_argument("--no-blocks", action="store_true",
                     help="one kernel pass per round even where several rounds per launch are possible")
+    ap.add_argument("--force-blocks", action="store_true",
+                    help="several rounds per launch wherever possible, also where streaming is faster (measurement)")
     ap.add_argument("--noise-std", type=float, default=None, help="override the gradient noise (not the headline workload)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only a plain 1 GiB device copy (10 launches): calibrates HBM byte counters")
@@ -159,6 +161,8 @@ def main():
     gpu = harness.make_gpu(w)
     if args.no_blocks:
         rf.rfast_use_blocks(gpu.ctx, False)
+    if args.force_blocks:
+        rf.rfast_use_blocks(gpu.ctx, 2)
     variant = args.momentum != 0.0 or args.weight_decay != 0.0
     if variant:
         gpu.set_optimizer(args.momentum, args.weight_decay)

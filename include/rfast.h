@@ -224,15 +224,21 @@ int rfast_run_events(rfast_ctx* ctx, int32_t iterations, uint64_t seed, const fl
  * run as ordinary launches.  Results are identical either way.  Off by default. */
 int rfast_use_graphs(rfast_ctx* ctx, int32_t on);
 
-/* on != 0 (the default): rfast_run and rfast_run_generated advance up to 16 rounds with one
+/* on != 0 (the default): rfast_run and rfast_run_generated advance up to 64 rounds with one
  * launch where that is possible and pays -- the separable objective (diagonal quadratic) without
- * the momentum variant, p a multiple of 4, at most 64 nodes, 64 coordinates of every node's two
- * rings fitting into the 160 KB of LDS of a CU (n * (D+2) * 512 B + nnzC_off * 256 B + plans), and
- * n * p * 4 <= 8 MB (beyond that, streaming one round per pass is faster).  Every step of a round
- * is elementwise in the coordinate, so a tile of coordinates can stay in LDS over several rounds;
- * the results are the same bits as round-by-round execution.  on == 0: always one kernel pass
- * per round. */
+ * the momentum variant, p a multiple of 4, no node with more than 4 in-edges of R, in-edges of C or
+ * out-edges of C, at least 64 coordinates of every node's two rings fitting into the 160 KB of LDS
+ * of a CU (n * (D+2) * 512 B + nnzC_off * 256 B + plans), and at least 2 rounds to run before the
+ * next multiple of the rebase interval (12 where n * p * 4 > 8 MB: a launch moves every ring slot
+ * in and out once, which a large state earns back only over that many rounds); rounds that do not
+ * qualify run one pass each.  Every step of a round is elementwise in the coordinate, so a tile of
+ * coordinates can stay in LDS over several rounds; the results are the same bits as round-by-round
+ * execution.  on == 0: always one kernel pass per round.  on == 2: as the default, but 2 rounds
+ * are enough at any size (for measurements). */
 int rfast_use_blocks(rfast_ctx* ctx, int32_t on);
+/* *lanes_per_node = 0 if a call of rfast_run for several rounds would now run one pass per round,
+ * else the number of lanes per node of the multi-round kernel (its tile is 4 * lanes coordinates). */
+int rfast_block_info(rfast_ctx* ctx, int32_t* lanes_per_node);
 
 /* One step of the synchronous push-pull recursion the method is developed from
  * (eq. (2) of the paper), on the same x, z and stored gradient samples:

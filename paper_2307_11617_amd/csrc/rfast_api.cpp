@@ -94,7 +94,7 @@ Offsets layout(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, cons
   o.slot_c = L.take(eC * 4);
   o.plan_c = L.take(eC * 4);
   o.node_spill = L.take(n);
-  o.blk_plan = L.take((size_t)kBlockRounds * ((size_t)n + eR + eC) * 4);
+  o.blk_plan = L.take((size_t)kBlockRounds * ((size_t)n + eR + eC + 1) * 4);
   o.gen_active = L.take(n);
   o.gen_delay_r = L.take(eR * 4);
   o.gen_delay_c = L.take(eC * 4);
@@ -457,6 +457,8 @@ int rfast_create(rfast_ctx** out, int32_t n, int64_t p, const int32_t* R_rowptr,
   chk(upload(c, b, o.c_ptr, gc.ptr)); chk(upload(c, b, o.c_src, gc.src)); chk(upload(c, b, o.c_dst, gc.dst)); chk(upload(c, b, o.c_w, gc.w)); chk(upload(c, b, o.c_self, gc.self));
   chk(upload(c, b, o.co_ptr, gc.out_ptr)); chk(upload(c, b, o.co_eid, gc.out_eid)); chk(upload(c, b, o.co_w, gc.out_w));
   chk(upload(c, b, o.ro_ptr, gr.out_ptr)); chk(upload(c, b, o.ro_eid, gr.out_eid));
+  for (int i = 0; i < n; ++i)
+    c->max_degree = std::max({c->max_degree, gr.ptr[i + 1] - gr.ptr[i], gc.ptr[i + 1] - gc.ptr[i], gc.out_ptr[i + 1] - gc.out_ptr[i]});
   chk(hipStreamSynchronize(c->stream));  // the host vectors die with this scope
   if (e != hipSuccess) {
     const int r = hipfail(nullptr, e, "uploading graph");
@@ -548,15 +550,19 @@ int rfast_round(rfast_ctx* c, const uint8_t* d_active, const int32_t* d_delay_R,
   return after_round(c);
 }
 
-// How many of the next `rounds` rounds one launch of the LDS-resident kernel may take: it holds
-// no rebase, so it must end at the latest on the next multiple of the rebase interval.
+// How many of the next `rounds` rounds one launch of the LDS-resident kernel should take (0: run
+// the next round as one pass).  A launch holds no rebase, so it must end at the latest on the next
+// multiple of the rebase interval; and it reads and writes every ring slot once, which a large
+// state earns back only over enough rounds.
 static int32_t block_length(const rfast_ctx* c, int32_t rounds) {
+  if (!c->use_blocks || !rfast_block_eligible(c)) return 0;
   int32_t len = rounds < kBlockRounds ? rounds : kBlockRounds;
   if (c->rebase_interval > 0) {
     const int64_t to_boundary = c->rebase_interval - c->host_round % c->rebase_interval;
     if (to_boundary < len) len = (int32_t)to_boundary;
   }
-  return len;
+  const bool large = (double)c->d.n * (double)c->d.p * 4.0 > 8.0e6;
+  return len >= (large && c->use_blocks != 2 ? kBlockMinRoundsLarge : 2) ? len : 0;
 }
 
 // Resolves `len` rounds (schedule arrays of round q at offset q of each pointer, or generated on
@@ -566,7 +572,7 @@ static int run_block(rfast_ctx* c, int32_t len, const uint8_t* d_active, const i
                      bool generated, uint64_t seed, const float* d_p_active, int32_t max_delay, float p_drop) {
   RfastDev& d = c->d;
   if (fold_sync(c) != RFAST_OK) return RFAST_EHIP;
-  const size_t PL = (size_t)d.n + d.eR + d.eC;
+  const size_t PL = (size_t)d.n + d.eR + d.eC + 1;  // a record ends with a word that is always zero
   RfastBlock blk;
   blk.rounds = len;
   hipError_t e = hipSuccess;
@@ -602,9 +608,15 @@ static int run_block(rfast_ctx* c, int32_t len, const uint8_t* d_active, const i
   return RFAST_OK;
 }
 
+int rfast_block_info(rfast_ctx* c, int32_t* lanes_per_node) {
+  if (!c || !lanes_per_node) return RFAST_EINVAL;
+  *lanes_per_node = block_length(c, kBlockRounds) > 0 ? rfast_block_lanes(c) : 0;
+  return RFAST_OK;
+}
+
 int rfast_use_blocks(rfast_ctx* c, int32_t on) {
   if (!c) return RFAST_EINVAL;
-  c->use_blocks = on != 0;
+  c->use_blocks = on == 2 ? 2 : (on != 0 ? 1 : 0);
   return RFAST_OK;
 }
 
@@ -614,24 +626,22 @@ int rfast_run(rfast_ctx* c, int32_t rounds, const uint8_t* d_active, const int32
   if (rounds < 0) return fail(c, RFAST_EINVAL, "rounds < 0");
   const RfastDev& d = c->d;
   const size_t B = d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC ? 0 : (size_t)d.prob.batch;
-  if (c->use_blocks && rounds > 1 && rfast_block_eligible(c)) {
+  for (int32_t r = 0; r < rounds; ++r) {
     // the separable objective on a small graph: tiles of coordinates stay in LDS over up to kBlockRounds rounds
-    if (!d_active || (d.eR && (!d_delay_R || !d_drop_R)) || (d.eC && (!d_delay_C || !d_drop_C)))
-      return fail(c, RFAST_EINVAL, "NULL schedule pointer");
-    if (!std::isfinite(gamma)) return fail(c, RFAST_EINVAL, "gamma is not finite");
-    if (c->needs_init) return fail(c, RFAST_EINVAL, "rfast_init must follow rfast_set_optimizer");
-    for (int32_t r = 0; r < rounds;) {
-      const int32_t len = block_length(c, rounds - r);
+    const int32_t len = block_length(c, rounds - r);
+    if (len > 0) {
+      if (!d_active || (d.eR && (!d_delay_R || !d_drop_R)) || (d.eC && (!d_delay_C || !d_drop_C)))
+        return fail(c, RFAST_EINVAL, "NULL schedule pointer");
+      if (!std::isfinite(gamma)) return fail(c, RFAST_EINVAL, "gamma is not finite");
+      if (c->needs_init) return fail(c, RFAST_EINVAL, "rfast_init must follow rfast_set_optimizer");
       const int rc = run_block(c, len, d_active + (size_t)r * d.n, d_delay_R ? d_delay_R + (size_t)r * d.eR : nullptr,
                                d_delay_C ? d_delay_C + (size_t)r * d.eC : nullptr,
                                d_drop_R ? d_drop_R + (size_t)r * d.eR : nullptr,
                                d_drop_C ? d_drop_C + (size_t)r * d.eC : nullptr, gamma, false, 0, nullptr, 0, 0.f);
       if (rc != RFAST_OK) return rc;
-      r += len;
+      r += len - 1;
+      continue;
     }
-    return RFAST_OK;
-  }
-  for (int32_t r = 0; r < rounds; ++r) {
     const int rc = rfast_round(c, d_active + (size_t)r * d.n, d_delay_R ? d_delay_R + (size_t)r * d.eR : nullptr,
                                d_delay_C ? d_delay_C + (size_t)r * d.eC : nullptr,
                                d_drop_R ? d_drop_R + (size_t)r * d.eR : nullptr,
@@ -662,17 +672,15 @@ int rfast_run_generated(rfast_ctx* c, int32_t rounds, uint64_t seed, const float
   // captured once into a HIP graph and replayed: one launch per kGraphRounds rounds.
   if (c->needs_init) return fail(c, RFAST_EINVAL, "rfast_init must follow rfast_set_optimizer");
   const bool graphs = c->use_graphs && !c->profiling;
-  if (!graphs && c->use_blocks && rounds > 1 && rfast_block_eligible(c)) {
-    while (rounds > 0) {
-      const int32_t len = block_length(c, rounds);
+  while (rounds > 0) {
+    const int32_t len = graphs ? 0 : block_length(c, rounds);
+    if (len > 0) {
       const int rc = run_block(c, len, nullptr, nullptr, nullptr, nullptr, nullptr, gamma, true, seed, d_p_active, max_delay,
                                p_drop);
       if (rc != RFAST_OK) return rc;
       rounds -= len;
+      continue;
     }
-    return RFAST_OK;
-  }
-  while (rounds > 0) {
     // a graph bakes the step size in, so a replay must not straddle a decay step of the schedule,
     // and it must hold no rebase, so it must end before the next multiple of the rebase interval
     const bool one_step_size = c->gamma_step <= 0 || c->host_round % c->gamma_step + kGraphRounds <= c->gamma_step;

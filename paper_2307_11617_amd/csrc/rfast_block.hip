@@ -3,20 +3,20 @@
 // Everything in a round of Algorithm 1 is elementwise in the coordinate k: coordinate k of every
 // node, ring slot and buffer depends, over any number of rounds, only on coordinate k of the
 // others.  For the separable objective (whose gradient is elementwise too) a workgroup can
-// therefore take 64 coordinates of EVERY node, load the rings of v and of the running sums for
-// them into LDS once, advance them through up to kBlockRounds rounds -- all neighbour reads of
+// therefore take a tile of coordinates of EVERY node, load the rings of v and of the running sums
+// for them into LDS once, advance them through up to kBlockRounds rounds -- all neighbour reads of
 // S2a / S2b and all publications of S3 are LDS traffic -- and write them back once.  HBM traffic
 // per round drops from 13 words per coordinate and node-update to (2 M + 4 + 2 M + 2) / rounds
 // words per coordinate and node (read everything, write everything, once per launch); the 160 KB
-// of LDS per CU are what makes the tile fit (config 2: 16 nodes x 2 rings x 9 slots x 256 B = 72 KB).
-// One launch also replaces up to kBlockRounds launches, which is where the path pays: see
-// rfast_block_eligible below for what was measured.
+// of LDS per CU are what makes a useful tile fit (config 2: 16 nodes x 2 rings x 9 slots + 32
+// buffers, 5 KB per lane column of 4 coordinates, 28 columns).  One launch also replaces up to
+// kBlockRounds launches.
 //
-// Layout of the work: 16 lanes per node, 4 consecutive coordinates per lane (one Philox call per
-// lane and sample, as in the streaming kernel), so a workgroup has 16 n lanes; x, z, the stored
-// sample and the objective data of a node stay in the registers of its 16 lanes for the whole
-// launch.  The arithmetic is, operation for operation, that of rfast_state_kernel<FUSED>: the two
-// paths give the same bits.
+// Layout of the work: kLanes lanes per node, 4 consecutive coordinates per lane (one Philox call per
+// lane and sample, as in the streaming kernel), so a workgroup has n kLanes lanes; x, z, the stored
+// sample, the objective data and the edges of a node stay in the registers of its lanes for the
+// whole launch.  The arithmetic is, operation for operation, that of rfast_state_kernel<FUSED>:
+// the two paths give the same bits.
 //
 // The integer plans of the rounds (who is active, which slot each edge reads, where each S4
 // buffer lives) are made by the resolver, one record per round, and copied to LDS first.
@@ -24,47 +24,46 @@
 
 namespace {
 
-constexpr int kLanes = 16;  // lanes per node; each owns 4 coordinates of the 64-coordinate tile
+constexpr int kDeg = 4;     // most in-edges of R, in-edges of C and out-edges of C a node may have on this path
+// Plan words a lane moves per refill: a record has at most (1 + 2 kDeg) n + 1 words and a workgroup at
+// least 16 n lanes, so kPlanChunk records are at most 16 (9 n + 1) <= 10 * 16 n words.
+constexpr int kPlanPerLane = 10;
 
-// VEC: 4 or -4 (non-temporal global accesses); TPB: upper bound of the workgroup size (16 lanes per
-// node; with 256 the compiler may use twice the registers of 1024)
-template <int VEC, int TPB>
+// kLanes: lanes per node, each owning 4 coordinates of a tile of 4 kLanes; TPB: upper bound of the
+// workgroup size (n kLanes lanes, rounded up to whole wavefronts), which sets how many registers
+// the compiler may use
+template <int kLanes, int TPB>
 __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock blk) {
+  constexpr int VEC = 4;
   extern __shared__ float4 lds4[];
   const int n = s.n, M = s.M;
   const int64_t p = s.p;
   const int PL = n + s.eR + s.eC;
-  float4* v_l = lds4;                                  // [n][M][16]
-  float4* sg_l = v_l + (size_t)n * M * kLanes;         // [n][M][16]
-  float4* rt_l = sg_l + (size_t)n * M * kLanes;        // [eC][16]
-  int* plan_l = reinterpret_cast<int*>(rt_l + (size_t)s.eC * kLanes);  // [kBlockRounds][PL]
-  // the graph, so that no round has to wait for global memory: sender and weight per in-edge of R and
-  // of C, edge id and weight per out-edge of C
-  int* r_src_l = plan_l + kBlockRounds * PL;                   // [eR]
-  float* r_w_l = reinterpret_cast<float*>(r_src_l + s.eR);     // [eR]
-  int* c_src_l = reinterpret_cast<int*>(r_w_l + s.eR);         // [eC]
-  float* c_w_l = reinterpret_cast<float*>(c_src_l + s.eC);     // [eC]
-  int* co_eid_l = reinterpret_cast<int*>(c_w_l + s.eC);        // [eC]
-  float* co_w_l = reinterpret_cast<float*>(co_eid_l + s.eC);   // [eC]
+  float4* v_l = lds4;                                  // [n][M][kLanes]
+  float4* sg_l = v_l + (size_t)n * M * kLanes;         // [n][M][kLanes]
+  float4* rt_l = sg_l + (size_t)n * M * kLanes;        // [eC][kLanes]
+  int* plan_l = reinterpret_cast<int*>(rt_l + (size_t)s.eC * kLanes);  // [kPlanChunk][PL + 1]
   const int i = threadIdx.x / kLanes, ln = threadIdx.x % kLanes;
   const int64_t k = (int64_t)blockIdx.x * (4 * kLanes) + ln * 4;
   const bool mine = i < n && k < p;
 
-  for (int q = threadIdx.x; q < blk.rounds * PL; q += blockDim.x) plan_l[q] = s.blk_plan[q];
-  for (int e = threadIdx.x; e < s.eR; e += blockDim.x) {
-    r_src_l[e] = s.r_src[e];
-    r_w_l[e] = s.r_w[e];
-  }
-  for (int e = threadIdx.x; e < s.eC; e += blockDim.x) {
-    c_src_l[e] = s.c_src[e];
-    c_w_l[e] = s.c_w[e];
-    co_eid_l[e] = s.co_eid[e];
-    co_w_l[e] = s.co_w[e];
+  // Plan records of kPlanChunk rounds at a time.  A record ends with a word that is always zero:
+  // what the lanes of a node with fewer than kDeg edges read for the missing ones (slot 0, not live,
+  // no spill), so that no read in the round loop is conditional.
+  const int W1 = PL + 1;
+  {
+    const int words = (blk.rounds < kPlanChunk ? blk.rounds : kPlanChunk) * W1;
+    for (int w = threadIdx.x; w < words; w += blockDim.x) plan_l[w] = s.blk_plan[w];
   }
 
   float4 x, z, g, h, c;
-  int re0 = 0, re1 = 0, ce0 = 0, ce1 = 0, o0 = 0, o1 = 0;
+  int re0 = 0, ce0 = 0, o0 = 0, dR = 0, dI = 0, dO = 0;
   float r_self = 0.f, c_self = 0.f;
+  // the node's edges, in registers for the whole launch (at most kDeg of each kind, checked by the
+  // host): LDS column of the sender's ring, weight, position of the edge's plan word in a record; a
+  // missing edge has weight zero, the node's own column and the zero word of the record
+  int r_col[kDeg], c_col[kDeg], r_pw[kDeg], c_pw[kDeg], o_pw[kDeg], c_rt[kDeg], o_rt[kDeg];
+  float r_w[kDeg], c_w[kDeg], o_w[kDeg];
   const int own = i * M * kLanes + ln;  // this lane's column in the rings of its node (LDS offsets fit in 32 bits)
   if (mine) {
     const size_t off = (size_t)i * p + k;
@@ -72,11 +71,26 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
     z = V<VEC>::ld(s.z + off);
     h = V<VEC>::ld((const float*)s.prob.data0 + off);
     c = V<VEC>::ld((const float*)s.prob.data1 + off);
-    re0 = s.r_ptr[i]; re1 = s.r_ptr[i + 1];
-    ce0 = s.c_ptr[i]; ce1 = s.c_ptr[i + 1];
-    o0 = s.co_ptr[i]; o1 = s.co_ptr[i + 1];
+    re0 = s.r_ptr[i]; dR = s.r_ptr[i + 1] - re0;
+    ce0 = s.c_ptr[i]; dI = s.c_ptr[i + 1] - ce0;
+    o0 = s.co_ptr[i]; dO = s.co_ptr[i + 1] - o0;
     r_self = s.r_self[i];
     c_self = s.c_self[i];
+#pragma unroll
+    for (int u = 0; u < kDeg; ++u) {
+      const bool hr = u < dR, hc = u < dI, ho = u < dO;
+      const int oe = ho ? s.co_eid[o0 + u] : 0;
+      r_col[u] = (hr ? s.r_src[re0 + u] : i) * M * kLanes + ln;
+      r_w[u] = hr ? s.r_w[re0 + u] : 0.f;
+      r_pw[u] = hr ? n + re0 + u : PL;
+      c_col[u] = (hc ? s.c_src[ce0 + u] : i) * M * kLanes + ln;
+      c_w[u] = hc ? s.c_w[ce0 + u] : 0.f;
+      c_pw[u] = hc ? n + s.eR + ce0 + u : PL;
+      c_rt[u] = (hc ? ce0 + u : 0) * kLanes + ln;
+      o_w[u] = ho ? s.co_w[o0 + u] : 0.f;
+      o_pw[u] = ho ? n + s.eR + oe : PL;
+      o_rt[u] = oe * kLanes + ln;
+    }
     // rings: eight slots of both rings (sixteen loads) in flight at a time, then into LDS
     const float* vg = s.v_ring + (size_t)i * M * p + k;
     const float* sgg = s.sigma_ring + (size_t)i * M * p + k;
@@ -95,7 +109,7 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
           sg_l[own + (m0 + u) * kLanes] = ts[u];
         }
     }
-    for (int e = ce0; e < ce1; ++e) rt_l[e * kLanes + ln] = V<VEC>::ld(s.rho_tilde + (size_t)e * p + k);
+    for (int u = 0; u < dI; ++u) rt_l[(ce0 + u) * kLanes + ln] = V<VEC>::ld(s.rho_tilde + (size_t)(ce0 + u) * p + k);
   }
   __syncthreads();
   // The stored sample of S2b is a function of (x_i, t_i); from here on it lives in registers, and so
@@ -108,68 +122,73 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
   }
 
   for (int q = 0; q < blk.rounds; ++q) {
-    const int* P = plan_l + q * PL;
+    const int* P = plan_l + (q % kPlanChunk) * W1;
+    // the records of the next kPlanChunk rounds are fetched during the last round of a chunk and
+    // put into LDS once every lane is done with the old ones (the condition is uniform)
+    const bool refill = (q + 1) % kPlanChunk == 0 && q + 1 < blk.rounds;
+    int next_plan[kPlanPerLane];
+    if (refill) {
+      const int words = (blk.rounds - (q + 1) < kPlanChunk ? blk.rounds - (q + 1) : kPlanChunk) * W1;
+#pragma unroll
+      for (int u = 0; u < kPlanPerLane; ++u) {
+        const int w = threadIdx.x + u * blockDim.x;
+        next_plan[u] = w < words ? s.blk_plan[(q + 1) * W1 + w] : 0;
+      }
+    }
     if (mine && P[i] < 0) {  // bit 31: node i is activated in this round
       const int t_old = P[i] & 0x3FFFFFFF;
       const int slot_new = slot_cur + 1 == M ? 0 : slot_cur + 1;
+      const int leaving = slot_new + 1 == M ? 0 : slot_new + 1;
+      // every plan word of the round in one batch of LDS reads ...
+      int r_slot[kDeg], c_pl[kDeg], o_pl[kDeg];
+#pragma unroll
+      for (int u = 0; u < kDeg; ++u) {
+        r_slot[u] = P[r_pw[u]];
+        c_pl[u] = P[c_pw[u]];
+        o_pl[u] = P[o_pw[u]];
+      }
+      // ... and every ring value of the round in a second one (what a missing or idle edge reads
+      // is a valid address and is not used)
+      float4 nb[kDeg], cur[kDeg], last[kDeg];
+#pragma unroll
+      for (int u = 0; u < kDeg; ++u) nb[u] = v_l[r_col[u] + r_slot[u] * kLanes];
+      if (TPB > 512) __builtin_amdgcn_sched_barrier(0);  // registers: do not start the next batch early
+#pragma unroll
+      for (int u = 0; u < kDeg; ++u) {
+        const int prev = (c_pl[u] >> 8) & 0xFF;
+        const float4* from_ring = sg_l + c_col[u] + prev * kLanes;
+        cur[u] = sg_l[c_col[u] + (c_pl[u] & 0xFF) * kLanes];
+        last[u] = *(prev != 0xFF ? from_ring : rt_l + c_rt[u]);
+      }
+      const float4 sig_cur = sg_l[own + slot_cur * kLanes];
+      const float4 sig_leaving = sg_l[own + leaving * kLanes];
       // S1: local descent
       const float4 v = fma_s(-blk.gamma[q], z, x);
-      // S2a: pull the stamped neighbour copies and mix with row-stochastic weights (LDS reads of up
-      // to four edges are issued together)
+      // S2a: pull the stamped neighbour copies and mix with row-stochastic weights
       float4 x_new = mul_s(r_self, v);
-      for (int e0 = re0; e0 < re1; e0 += 4) {
-        float4 nb[4];
-        float w[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-          if (e0 + u < re1) {
-            nb[u] = v_l[(r_src_l[e0 + u] * M + P[n + e0 + u]) * kLanes + ln];
-            w[u] = r_w_l[e0 + u];
-          }
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-          if (e0 + u < re1) x_new = fma_s(w[u], nb[u], x_new);
-      }
+      for (int u = 0; u < kDeg; ++u)
+        if (u < dR) x_new = fma_s(r_w[u], nb[u], x_new);
       const float4 g_new = diag_sample<VEC>(s, h, c, x_new, i, t_old + 1, k);
       // S2b: tracker sum over the in-edges of C; S4: buffer what was consumed
       float4 z_half = z;
-      for (int e0 = ce0; e0 < ce1; e0 += 4) {
-        float4 cur[4], last[4];
-        float ca[4];
-        int pl[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          pl[u] = e0 + u < ce1 ? P[n + s.eR + e0 + u] : 0;
-          if (pl[u] & (1 << 16)) {
-            const int ring = c_src_l[e0 + u] * M * kLanes + ln;
-            const int prev = (pl[u] >> 8) & 0xFF;
-            cur[u] = sg_l[ring + (pl[u] & 0xFF) * kLanes];
-            last[u] = prev != 0xFF ? sg_l[ring + prev * kLanes] : rt_l[(e0 + u) * kLanes + ln];
-            ca[u] = c_w_l[e0 + u];
-          }
+      for (int u = 0; u < kDeg; ++u)
+        if (c_pl[u] & (1 << 16)) {
+          const float4 rho = mul_s(c_w[u], cur[u]);
+          z_half = add(z_half, sub(rho, ((c_pl[u] >> 8) & 0xFF) != 0xFF ? mul_s(c_w[u], last[u]) : last[u]));
+          if (c_pl[u] & (1 << 17)) rt_l[c_rt[u]] = rho;
         }
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-          if (pl[u] & (1 << 16)) {
-            const float4 rho = mul_s(ca[u], cur[u]);
-            z_half = add(z_half, sub(rho, ((pl[u] >> 8) & 0xFF) != 0xFF ? mul_s(ca[u], last[u]) : last[u]));
-            if (pl[u] & (1 << 17)) rt_l[(e0 + u) * kLanes + ln] = rho;
-          }
-      }
       z_half = sub(add(z_half, g_new), g);
       // S3: publish version t+1 (slots nobody reads in this round); S2c: keep a_ii, push
       v_l[own + slot_new * kLanes] = v;
-      if (o1 > o0) {
-        sg_l[own + slot_new * kLanes] = add(sg_l[own + slot_cur * kLanes], z_half);
+      if (dO > 0) {
+        sg_l[own + slot_new * kLanes] = add(sig_cur, z_half);
         // S4 for receivers that do not do it themselves: version t - D leaves the ring; it sits two
         // slots ahead of the current one
-        for (int o = o0; o < o1; ++o) {
-          const int eid = co_eid_l[o];
-          if (P[n + s.eR + eid] & (1 << 18)) {
-            const int leaving = slot_cur + 2 >= M ? slot_cur + 2 - M : slot_cur + 2;
-            rt_l[eid * kLanes + ln] = mul_s(co_w_l[o], sg_l[own + leaving * kLanes]);
-          }
-        }
+#pragma unroll
+        for (int u = 0; u < kDeg; ++u)
+          if (o_pl[u] & (1 << 18)) rt_l[o_rt[u]] = mul_s(o_w[u], sig_leaving);
       }
       x = x_new;
       z = mul_s(c_self, z_half);
@@ -177,6 +196,14 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
       slot_cur = slot_new;
     }
     __syncthreads();  // S5: the round is over, its publications are visible
+    if (refill) {
+#pragma unroll
+      for (int u = 0; u < kPlanPerLane; ++u) {
+        const int w = threadIdx.x + u * blockDim.x;
+        if (w < kPlanChunk * W1) plan_l[w] = next_plan[u];
+      }
+      __syncthreads();
+    }
   }
 
   if (mine) {
@@ -200,53 +227,75 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
           V<VEC>::st(sgg + (size_t)(m0 + u) * p, ts[u]);
         }
     }
-    for (int e = ce0; e < ce1; ++e) V<VEC>::st(s.rho_tilde + (size_t)e * p + k, rt_l[e * kLanes + ln]);
+    for (int u = 0; u < dI; ++u) V<VEC>::st(s.rho_tilde + (size_t)(ce0 + u) * p + k, rt_l[(ce0 + u) * kLanes + ln]);
   }
 }
 
-size_t block_lds_bytes(const RfastDev& d) {
-  return ((size_t)2 * d.n * d.M + d.eC) * kLanes * sizeof(float4) + (size_t)kBlockRounds * (d.n + d.eR + d.eC) * sizeof(int) +
-         ((size_t)2 * d.eR + 4 * d.eC) * sizeof(int);
+size_t block_lds_bytes(const RfastDev& d, int lanes) {
+  return ((size_t)2 * d.n * d.M + d.eC) * lanes * sizeof(float4) + (size_t)kPlanChunk * (d.n + d.eR + d.eC + 1) * sizeof(int);
+}
+
+// Lanes per node.  One wavefront per SIMD leaves every LDS wait, barrier and scalar instruction of
+// the round loop exposed, so the tile is made as wide as LDS allows (two wavefronts per SIMD need
+// 512 lanes per workgroup), as long as that still leaves two tiles per CU of the chip to schedule.
+constexpr int kLaneChoices[] = {64, 48, 32, 28, 24, 16};
+constexpr size_t kLdsBudget = 156 * 1024;
+
+int block_lanes(const RfastDev& d) {
+  for (int lanes : kLaneChoices) {
+    const int threads = (d.n * lanes + 63) / 64 * 64;
+    const bool fits = threads <= 1024 && block_lds_bytes(d, lanes) <= kLdsBudget &&
+                      (int64_t)kPlanChunk * (d.n + d.eR + d.eC + 1) <= (int64_t)kPlanPerLane * threads;
+    if (fits && (lanes == 16 || (d.p + 4 * lanes - 1) / (4 * lanes) >= 512)) return lanes;
+  }
+  return 0;
 }
 
 }  // namespace
 
-// The tile of every node must fit into the LDS of one CU next to the plans, a workgroup holds 16
-// lanes per node, and the path exists for the separable objective without the momentum variant.
-// It is taken where rounds are bound by kernel launches, not by HBM: one workgroup of 16 n lanes per
-// CU issues about 780 instructions per round and tile, which is slower than streaming once the
-// state is large (measured on 16 nodes, ms per round, this path / one pass per round: p = 4096
-// 0.0072 / 0.0115, 16 384 0.0074 / 0.0121, 65 536 0.0155 / 0.0188, 262 144 0.048 / 0.045,
-// 1 048 576 0.186 / 0.156, 11.2 M 1.90 / 1.53), so it stops at 8 MB of x.
+// The tile of every node must fit into the LDS of one CU next to the plans, a workgroup holds at
+// least 16 lanes per node, no node has more than kDeg edges of a kind, and the path exists for the
+// separable objective without the momentum variant.
 bool rfast_block_eligible(const rfast_ctx* c) {
   const RfastDev& d = c->d;
-  return d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC && d.mom == nullptr && (d.p % 4) == 0 && d.n * kLanes <= 1024 &&
-         block_lds_bytes(d) <= 156 * 1024 && (double)d.n * (double)d.p * 4.0 <= 8.0e6;
+  return d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC && d.mom == nullptr && (d.p % 4) == 0 && c->max_degree <= kDeg &&
+         block_lanes(d) != 0;
 }
 
-template <int VEC, int TPB>
-static hipError_t launch_block(rfast_ctx* c, const RfastBlock& blk, unsigned threads, unsigned tiles, size_t lds) {
+int rfast_block_lanes(const rfast_ctx* c) { return block_lanes(c->d); }
+
+template <int kLanes, int TPB>
+static hipError_t launch_block(rfast_ctx* c, const RfastBlock& blk, unsigned threads) {
   static bool raised = false;
   if (!raised) {  // more than 64 KB of dynamic LDS has to be asked for once per kernel
-    const hipError_t e = hipFuncSetAttribute((const void*)rfast_block_kernel<VEC, TPB>,
+    const hipError_t e = hipFuncSetAttribute((const void*)rfast_block_kernel<kLanes, TPB>,
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     raised = true;
   }
-  hipLaunchKernelGGL((rfast_block_kernel<VEC, TPB>), dim3(tiles), dim3(threads), lds, c->stream, c->d, blk);
+  const int64_t tiles = (c->d.p + 4 * kLanes - 1) / (4 * kLanes);
+  if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((rfast_block_kernel<kLanes, TPB>), dim3((unsigned)tiles), dim3(threads), block_lds_bytes(c->d, kLanes),
+                     c->stream, c->d, blk);
   return hipGetLastError();
 }
 
+template <int kLanes>
+static hipError_t launch_block_lanes(rfast_ctx* c, const RfastBlock& blk) {
+  const unsigned threads = (unsigned)((c->d.n * kLanes + 63) / 64 * 64);
+  if (threads <= 256) return launch_block<kLanes, 256>(c, blk, threads);
+  if (threads <= 512) return launch_block<kLanes, 512>(c, blk, threads);
+  return launch_block<kLanes, 1024>(c, blk, threads);
+}
+
 hipError_t rfast_launch_block(rfast_ctx* c, const RfastBlock& blk) {
-  const RfastDev& d = c->d;
-  const size_t lds = block_lds_bytes(d);
-  const bool streaming = (double)d.n * (double)d.p * 4.0 >= 32.0e6;
-  const unsigned threads = (unsigned)((d.n * kLanes + 63) / 64 * 64);
-  const int64_t tiles = (d.p + 4 * kLanes - 1) / (4 * kLanes);
-  if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
-  if (threads <= 256)
-    return streaming ? launch_block<-4, 256>(c, blk, threads, (unsigned)tiles, lds)
-                     : launch_block<4, 256>(c, blk, threads, (unsigned)tiles, lds);
-  return streaming ? launch_block<-4, 1024>(c, blk, threads, (unsigned)tiles, lds)
-                   : launch_block<4, 1024>(c, blk, threads, (unsigned)tiles, lds);
+  switch (block_lanes(c->d)) {
+    case 64: return launch_block_lanes<64>(c, blk);
+    case 48: return launch_block_lanes<48>(c, blk);
+    case 32: return launch_block_lanes<32>(c, blk);
+    case 28: return launch_block_lanes<28>(c, blk);
+    case 24: return launch_block_lanes<24>(c, blk);
+    case 16: return launch_block_lanes<16>(c, blk);
+    default: return hipErrorInvalidValue;
+  }
 }

@@ -124,14 +124,20 @@ struct rfast_ctx {
   int32_t gamma_step = 0;       // rounds per decay step, 0 = constant step size
   float gamma_factor = 1.f;
   bool needs_init = false;      // rfast_set_optimizer was called and rfast_init has not followed yet
-  bool use_blocks = true;       // rfast_run / rfast_run_generated may advance several rounds per launch
+  int32_t use_blocks = 1;       // 1: where it pays, 2: wherever possible; rfast_run / rfast_run_generated may advance several rounds per launch
   int32_t* blk_plan_base = nullptr;  // kBlockRounds plan records
+  int32_t max_degree = 0;       // most in-edges of R, in-edges of C or out-edges of C at any node
 };
 
 enum { RFAST_MODE_FUSED = 0, RFAST_MODE_MIX = 1, RFAST_MODE_TRACK = 2 };
 
-// rounds that one launch of the LDS-resident kernel can advance
-constexpr int kBlockRounds = 16;
+// rounds that one launch of the LDS-resident kernel can advance, rounds whose plan records it holds
+// in LDS at a time, and the shortest launch that pays where the state is large (the launch moves
+// every ring slot in and out once: measured on 16 nodes x 11.2 M coordinates, 7.9 ms per launch
+// plus 0.78 ms per round against 1.53 ms per round of the streaming kernel)
+constexpr int kBlockRounds = 64;
+constexpr int kPlanChunk = 16;
+constexpr int kBlockMinRoundsLarge = 12;
 struct RfastBlock {
   float gamma[kBlockRounds];  // step size of each round
   int32_t rounds;             // 1 .. kBlockRounds
@@ -144,6 +150,7 @@ hipError_t rfast_launch_state(rfast_ctx* c, int mode, float gamma);
 hipError_t rfast_launch_rebase(rfast_ctx* c);
 // several rounds of the separable objective on LDS-resident tiles; the rounds' plans are in blk_plan
 bool rfast_block_eligible(const rfast_ctx* c);
+int rfast_block_lanes(const rfast_ctx* c);  // lanes per node of the multi-round kernel, 0 if no tile fits
 hipError_t rfast_launch_block(rfast_ctx* c, const RfastBlock& blk);
 hipError_t rfast_launch_generate(rfast_ctx* c, uint64_t seed, const float* d_p_active, int d_max, float p_drop, bool events);
 hipError_t rfast_launch_sync(rfast_ctx* c, int phase, float gamma, int parity);

@@ -132,6 +132,7 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev
   for (int a = 0; a < kAhead; ++a)
     if (threadIdx.x + a * kResolveThreads < E) edge_level2(s, r, active, &ahead[a]);
   if (threadIdx.x == 0) base = 0;
+  if (threadIdx.x == 0 && s.blk_plan) s.blk_plan[s.n + E] = 0;  // a record ends with a word that is always zero
   // node pass: snapshot of the counters, and the ordered list of active nodes (ballot + prefix per chunk)
   for (int i0 = 0; i0 < s.n; i0 += kResolveThreads) {
     const int i = i0 + threadIdx.x;

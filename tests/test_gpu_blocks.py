@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 import torch
 
-from paper_2307_11617_amd import rfast_use_blocks, rfast_set_rebase_interval
+from paper_2307_11617_amd import rfast_block_info, rfast_use_blocks, rfast_set_rebase_interval
 from rfast_workloads import configs, graphs, problems
 from rfast_workloads.schedule import ScheduleSpec
 
@@ -27,19 +27,24 @@ def _same(a, b, where):
         assert np.array_equal(a.read(f), b.read(f)), (where, f)
 
 
-@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+@pytest.mark.parametrize("seed", [0, 1, 2, 3, 4])
 def test_uploaded_schedules(seed):
+    """Seeds 1-3: random graphs with at most four edges of a kind per node; seed 4 has more, and must
+    run one pass per round."""
     rng = np.random.default_rng(seed)
-    n = [16, 5, 33, 9][seed]
-    p = [1028, 64, 260, 4100][seed]
-    d_max, burst = [4, 0, 2, 1][seed], [4, 1, 2, 3][seed]
-    wr, wc = graphs.random_digraph(n, rng, extra=0.4) if seed else graphs.bidirectional_ring(n)
+    n = [16, 5, 33, 9, 9][seed]
+    p = [1028, 64, 260, 4100, 512][seed]
+    d_max, burst = [4, 0, 2, 1, 1][seed], [4, 1, 2, 3, 2][seed]
+    wr, wc = graphs.random_digraph(n, rng, extra=[0, 0.4, 0.02, 0.2, 0.4][seed]) if seed else graphs.bidirectional_ring(n)
     R, C = graphs.from_dense(wr), graphs.from_dense(wc)
     p_act = np.where(np.arange(n) % 4 == 1, 0.1, 0.9)
     sched = ScheduleSpec(n, R.nnz_off, C.nnz_off, p_act, d_max, 0.3, seed=seed)
     w = configs.Workload(f"blocks_{seed}", n, p, R, C, d_max + burst - 1, burst, 0.02, 0, "diag_quadratic",
                          problems.diag_quadratic(n, p, seed), sched, 0.1, 50 + seed, 1e-4)
     a, b = _pair(w)
+    off = lambda m: (m != 0) & ~np.eye(n, dtype=bool)
+    degree = max(off(wr).sum(1).max(), off(wc).sum(1).max(), off(wc).sum(0).max())   # in R, in C, out C
+    assert (rfast_block_info(a.ctx) != 0) == (degree <= 4), degree
     x0 = rng.standard_normal((n, p)).astype(np.float32)
     for g in (a, b):
         rfast_set_rebase_interval(g.ctx, 23)       # launches end on multiples of 23
@@ -61,6 +66,48 @@ def test_uploaded_schedules(seed):
     assert harness.rel_l2(a.read("X"), orc.x) <= 1e-4
     assert harness.rel_l2(a.read("Z"), orc.z, 1e-3 * float(np.linalg.norm(orc.g))) <= 1e-4
     assert np.array_equal(a.read("T_NODE"), orc.t)
+
+
+# n, d_max, burst, p, lanes per node the library must choose (the widest tile that fits LDS and 1024
+# lanes while leaving 512 tiles); every p ends in a ragged tile
+TILES = [(16, 4, 4, 57_348, 28), (16, 5, 4, 49_156, 24), (5, 0, 1, 131_076, 64), (9, 3, 4, 98_308, 48),
+         (24, 1, 2, 65_540, 32), (16, 4, 4, 4_100, 16)]
+
+
+@pytest.mark.parametrize("n,d_max,burst,p,lanes", TILES)
+def test_tile_widths(n, d_max, burst, p, lanes):
+    wr, wc = graphs.bidirectional_ring(n)
+    R, C = graphs.from_dense(wr), graphs.from_dense(wc)
+    p_act = np.where(np.arange(n) % 3 == 1, 0.3, 0.9)
+    sched = ScheduleSpec(n, R.nnz_off, C.nnz_off, p_act, d_max, 0.3, seed=n)
+    w = configs.Workload(f"tiles_{lanes}", n, p, R, C, d_max + burst - 1, burst, 0.02, 0, "diag_quadratic",
+                         problems.diag_quadratic(n, p, n), sched, 0.1, 90 + n, 1e-4)
+    a, b = _pair(w)
+    assert rfast_block_info(a.ctx) == lanes and rfast_block_info(b.ctx) == 0
+    for g in (a, b):
+        g.init(None, None)
+    st, dev = harness.upload_chunk(a, w, 0, 40)
+    args = [dev[k] for k in ("active", "delay_R", "delay_C", "drop_R", "drop_C")]
+    for g in (a, b):
+        g.run(40, *args, w.gamma)
+        g.check()
+    _same(a, b, lanes)
+
+
+def test_large_state_short_and_long_calls():
+    """Above 8 MB of x a launch needs 12 rounds to pay: shorter calls run one pass per round, longer
+    ones take the multi-round kernel (three refills of its plan records at 70 rounds), same bits."""
+    w = configs.config2(p=131_076, rounds=0)
+    a, b = _pair(w)
+    for g in (a, b):
+        g.init(None, None)
+    st, dev = harness.upload_chunk(a, w, 0, 100)
+    cut = lambda lo, hi: [dev[k][lo:hi] for k in ("active", "delay_R", "delay_C", "drop_R", "drop_C")]
+    for lo, hi in ((0, 11), (11, 81), (81, 100)):
+        for g in (a, b):
+            g.run(hi - lo, *cut(lo, hi), w.gamma)
+            g.check()
+        _same(a, b, hi)
 
 
 def test_generated_schedules_and_events():

@@ -44,18 +44,26 @@ def algorithmic_bytes_per_round(w, active_counts, layout=False):
     return float((words * active_counts).sum() * 4.0 * w.p)
 
 
-def measured_traffic(workload_name):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if any."""
+def profile_figure(workload_name, kernel, key):
+    """A figure per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if any."""
     for suffix in ("hbm_traffic", "stats"):
-        path = os.path.join(ROOT, "profiles", f"{workload_name}_state_kernel_{suffix}.md")
+        path = os.path.join(ROOT, "profiles", f"{workload_name}_{kernel}_kernel_{suffix}.md")
         try:
             with open(path) as f:
                 for line in f:
-                    if line.startswith("traffic_bytes_per_launch:"):
+                    if line.startswith(key + ":"):
                         return float(line.split(":")[1])
         except OSError:
             pass
     return None
+
+
+def measured_traffic(workload_name, kernel="state"):
+    return profile_figure(workload_name, kernel, "traffic_bytes_per_launch")
+
+
+# one VALU instruction per SIMD every 4 cycles (a wavefront of 64 on 16 lanes): 256 CUs x 4 SIMDs x 2.4 GHz / 4
+VALU_ISSUE_PEAK = 256 * 4 * 2.4e9 / 4
 
 
 def _time_rounds(step, w, seconds_target):
@@ -220,6 +228,16 @@ def main():
         bytes_prof, bytes_layout = bytes_prof + extra, bytes_layout + extra
     launches = max(n_state, 1)
     avg_ms = ms_state / launches
+    # several rounds per launch with the state resident in LDS (the default where it applies)
+    blocked = not args.sync and w.objective == "diag_quadratic" and 0 < n_state < K
+    lanes = rf.rfast_block_info(gpu.ctx) if blocked else 0
+    if args.sync:
+        kernel = "rfast_sync_descent+step"
+    elif blocked:
+        kernel = f"rfast_block_kernel<{lanes} lanes per node>"
+    else:
+        kernel = "rfast_state_kernel" + ("<FUSED>" if w.objective == "diag_quadratic" else "<MIX>+<TRACK>")
+    headline = not (args.p or args.sync or variant or args.generated)
     achieved = bytes_prof / (ms_state * 1e-3) / 1e9 if ms_state > 0 else 0.0
     out = {
         "metric": "node-updates/sec",
@@ -233,18 +251,31 @@ def main():
                                ("/generated-schedule" if args.generated else "") + ("/hip-graphs" if args.graphs else "") +
                                (f"/momentum={args.momentum},weight_decay={args.weight_decay}" if variant else ""), "n": w.n, "p": w.p, "D": w.D, "ring_slots": w.D + 2, "objective": w.objective,
                    "mean_active_per_round": updates / K, "gamma": w.gamma},
-        "roofline": {"bound": "hbm", "kernel": ("rfast_sync_descent+step" if args.sync else "rfast_state_kernel" + ("<FUSED>" if w.objective == "diag_quadratic" else "<MIX>+<TRACK>")), "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "avg_kernel_ms": avg_ms, "launches": n_state,
                      "algorithmic_bytes_per_launch": bytes_prof / launches,
                      "layout_bytes_per_launch": bytes_layout / launches,
                      "achieved_layout": achieved * bytes_layout / bytes_prof if bytes_prof else 0.0,
                      "frac_layout": achieved * bytes_layout / bytes_prof / HBM_PEAK_GBS if bytes_prof else 0.0,
-                     "traffic": measured_traffic(w.name) if not (args.p or args.sync or variant) else None},
+                     "traffic": measured_traffic(w.name, "block" if blocked else "state") if headline else None},
         "kernel_ms": {"state": ms_state, "gradient": ms_grad, "resolver": ms_res,
                       "launches": {"state": n_state, "gradient": n_grad, "resolver": n_res}},
         "host_data_generation_s": gen_s,
     }
+    if blocked:
+        # The launch keeps the state in LDS over rounds_per_launch rounds, so the HBM traffic the
+        # algorithmic figure counts per round is not moved: frac above 1 says so, and what bounds the
+        # kernel is instruction issue.  VALU instructions per wavefront from the committed counter summary.
+        out["roofline"]["rounds_per_launch"] = K / launches
+        out["roofline"]["note"] = ("state resident in LDS over rounds_per_launch rounds: HBM moves every ring slot once "
+                                   "per launch (traffic), not the per-round words of the algorithmic figure")
+        per_round = profile_figure(w.name, "block", "valu_wave_instructions_per_round") if headline else None
+        if per_round:
+            rate = per_round * K / (ms_state * 1e-3)
+            out["roofline_alu"] = {"bound": "alu", "kernel": kernel, "achieved": rate / 1e9, "peak": VALU_ISSUE_PEAK / 1e9,
+                                   "unit": "G wavefront-instructions/s (VALU)", "frac": rate / VALU_ISSUE_PEAK,
+                                   "source": "SQ_INSTS_VALU per round from profiles/ x rounds / live kernel time"}
     if w.objective == "softmax_bf16":
         # the two GEMMs of the softmax gradient: 2*B*d*K flops each per node-update
         flops = 4.0 * w.sched.batch * w.extra["d"] * w.extra["K"] * float(act_prof.sum())

@@ -24,15 +24,15 @@
 
 namespace {
 
-constexpr int kDeg = 4;     // most in-edges of R, in-edges of C and out-edges of C a node may have on this path
-// Plan words a lane moves per refill: a record has at most (1 + 2 kDeg) n + 1 words and a workgroup at
+constexpr int kMaxDeg = 4;  // most in-edges of R, in-edges of C and out-edges of C a node may have on this path
+// Plan words a lane moves per refill: a record has at most (1 + 2 kMaxDeg) n + 1 words and a workgroup at
 // least 16 n lanes, so kPlanChunk records are at most 16 (9 n + 1) <= 10 * 16 n words.
 constexpr int kPlanPerLane = 10;
 
 // kLanes: lanes per node, each owning 4 coordinates of a tile of 4 kLanes; TPB: upper bound of the
 // workgroup size (n kLanes lanes, rounded up to whole wavefronts), which sets how many registers
-// the compiler may use
-template <int kLanes, int TPB>
+// the compiler may use; kDeg: edge slots per node and kind (2 for rings and paths, else kMaxDeg)
+template <int kLanes, int TPB, int kDeg>
 __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock blk) {
   constexpr int VEC = 4;
   extern __shared__ float4 lds4[];
@@ -41,11 +41,14 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
   const int PL = n + s.eR + s.eC;
   float4* v_l = lds4;                                  // [n][M][kLanes]
   float4* sg_l = v_l + (size_t)n * M * kLanes;         // [n][M][kLanes]
-  float4* rt_l = sg_l + (size_t)n * M * kLanes;        // [eC][kLanes]
-  int* plan_l = reinterpret_cast<int*>(rt_l + (size_t)s.eC * kLanes);  // [kPlanChunk][PL + 1]
+  int* plan_l = reinterpret_cast<int*>(sg_l + (size_t)n * M * kLanes);  // [kPlanChunk][PL + 1]
   const int i = threadIdx.x / kLanes, ln = threadIdx.x % kLanes;
   const int64_t k = (int64_t)blockIdx.x * (4 * kLanes) + ln * 4;
   const bool mine = i < n && k < p;
+  // The S4 buffers stay in global memory: they are touched only when a version leaves a ring before
+  // its receiver has consumed a newer one (a store by one lane; a load by another lane of this
+  // workgroup in a later round, with the barrier of every round in between).
+  float* const rt_g = s.rho_tilde + k;  // + e p: these coordinates of edge e
 
   // Plan records of kPlanChunk rounds at a time.  A record ends with a word that is always zero:
   // what the lanes of a node with fewer than kDeg edges read for the missing ones (slot 0, not live,
@@ -62,7 +65,7 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
   // the node's edges, in registers for the whole launch (at most kDeg of each kind, checked by the
   // host): LDS column of the sender's ring, weight, position of the edge's plan word in a record; a
   // missing edge has weight zero, the node's own column and the zero word of the record
-  int r_col[kDeg], c_col[kDeg], r_pw[kDeg], c_pw[kDeg], o_pw[kDeg], c_rt[kDeg], o_rt[kDeg];
+  int r_col[kDeg], c_col[kDeg], r_pw[kDeg], c_pw[kDeg], o_pw[kDeg], o_eid[kDeg];
   float r_w[kDeg], c_w[kDeg], o_w[kDeg];
   const int own = i * M * kLanes + ln;  // this lane's column in the rings of its node (LDS offsets fit in 32 bits)
   if (mine) {
@@ -86,10 +89,9 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
       c_col[u] = (hc ? s.c_src[ce0 + u] : i) * M * kLanes + ln;
       c_w[u] = hc ? s.c_w[ce0 + u] : 0.f;
       c_pw[u] = hc ? n + s.eR + ce0 + u : PL;
-      c_rt[u] = (hc ? ce0 + u : 0) * kLanes + ln;
       o_w[u] = ho ? s.co_w[o0 + u] : 0.f;
       o_pw[u] = ho ? n + s.eR + oe : PL;
-      o_rt[u] = oe * kLanes + ln;
+      o_eid[u] = oe;
     }
     // rings: eight slots of both rings (sixteen loads) in flight at a time, then into LDS
     const float* vg = s.v_ring + (size_t)i * M * p + k;
@@ -109,7 +111,6 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
           sg_l[own + (m0 + u) * kLanes] = ts[u];
         }
     }
-    for (int u = 0; u < dI; ++u) rt_l[(ce0 + u) * kLanes + ln] = V<VEC>::ld(s.rho_tilde + (size_t)(ce0 + u) * p + k);
   }
   __syncthreads();
   // The stored sample of S2b is a function of (x_i, t_i); from here on it lives in registers, and so
@@ -156,10 +157,12 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
 #pragma unroll
       for (int u = 0; u < kDeg; ++u) {
         const int prev = (c_pl[u] >> 8) & 0xFF;
-        const float4* from_ring = sg_l + c_col[u] + prev * kLanes;
         cur[u] = sg_l[c_col[u] + (c_pl[u] & 0xFF) * kLanes];
-        last[u] = *(prev != 0xFF ? from_ring : rt_l + c_rt[u]);
+        last[u] = sg_l[c_col[u] + (prev != 0xFF ? prev : 0) * kLanes];
       }
+#pragma unroll
+      for (int u = 0; u < kDeg; ++u)  // rare: the version consumed last time has left the sender's ring
+        if ((c_pl[u] & (1 << 16)) && ((c_pl[u] >> 8) & 0xFF) == 0xFF) last[u] = V<VEC>::ld(rt_g + (size_t)(ce0 + u) * p);
       const float4 sig_cur = sg_l[own + slot_cur * kLanes];
       const float4 sig_leaving = sg_l[own + leaving * kLanes];
       // S1: local descent
@@ -177,7 +180,7 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
         if (c_pl[u] & (1 << 16)) {
           const float4 rho = mul_s(c_w[u], cur[u]);
           z_half = add(z_half, sub(rho, ((c_pl[u] >> 8) & 0xFF) != 0xFF ? mul_s(c_w[u], last[u]) : last[u]));
-          if (c_pl[u] & (1 << 17)) rt_l[c_rt[u]] = rho;
+          if (c_pl[u] & (1 << 17)) V<VEC>::st(rt_g + (size_t)(ce0 + u) * p, rho);
         }
       z_half = sub(add(z_half, g_new), g);
       // S3: publish version t+1 (slots nobody reads in this round); S2c: keep a_ii, push
@@ -188,7 +191,7 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
         // slots ahead of the current one
 #pragma unroll
         for (int u = 0; u < kDeg; ++u)
-          if (o_pl[u] & (1 << 18)) rt_l[o_rt[u]] = mul_s(o_w[u], sig_leaving);
+          if (o_pl[u] & (1 << 18)) V<VEC>::st(rt_g + (size_t)o_eid[u] * p, mul_s(o_w[u], sig_leaving));
       }
       x = x_new;
       z = mul_s(c_self, z_half);
@@ -227,12 +230,11 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
           V<VEC>::st(sgg + (size_t)(m0 + u) * p, ts[u]);
         }
     }
-    for (int u = 0; u < dI; ++u) V<VEC>::st(s.rho_tilde + (size_t)(ce0 + u) * p + k, rt_l[(ce0 + u) * kLanes + ln]);
   }
 }
 
 size_t block_lds_bytes(const RfastDev& d, int lanes) {
-  return ((size_t)2 * d.n * d.M + d.eC) * lanes * sizeof(float4) + (size_t)kPlanChunk * (d.n + d.eR + d.eC + 1) * sizeof(int);
+  return (size_t)2 * d.n * d.M * lanes * sizeof(float4) + (size_t)kPlanChunk * (d.n + d.eR + d.eC + 1) * sizeof(int);
 }
 
 // Lanes per node.  One wavefront per SIMD leaves every LDS wait, barrier and scalar instruction of
@@ -254,28 +256,28 @@ int block_lanes(const RfastDev& d) {
 }  // namespace
 
 // The tile of every node must fit into the LDS of one CU next to the plans, a workgroup holds at
-// least 16 lanes per node, no node has more than kDeg edges of a kind, and the path exists for the
+// least 16 lanes per node, no node has more than kMaxDeg edges of a kind, and the path exists for the
 // separable objective without the momentum variant.
 bool rfast_block_eligible(const rfast_ctx* c) {
   const RfastDev& d = c->d;
-  return d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC && d.mom == nullptr && (d.p % 4) == 0 && c->max_degree <= kDeg &&
+  return d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC && d.mom == nullptr && (d.p % 4) == 0 && c->max_degree <= kMaxDeg &&
          block_lanes(d) != 0;
 }
 
 int rfast_block_lanes(const rfast_ctx* c) { return block_lanes(c->d); }
 
-template <int kLanes, int TPB>
+template <int kLanes, int TPB, int kDeg>
 static hipError_t launch_block(rfast_ctx* c, const RfastBlock& blk, unsigned threads) {
   static bool raised = false;
   if (!raised) {  // more than 64 KB of dynamic LDS has to be asked for once per kernel
-    const hipError_t e = hipFuncSetAttribute((const void*)rfast_block_kernel<kLanes, TPB>,
+    const hipError_t e = hipFuncSetAttribute((const void*)rfast_block_kernel<kLanes, TPB, kDeg>,
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     raised = true;
   }
   const int64_t tiles = (c->d.p + 4 * kLanes - 1) / (4 * kLanes);
   if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((rfast_block_kernel<kLanes, TPB>), dim3((unsigned)tiles), dim3(threads), block_lds_bytes(c->d, kLanes),
+  hipLaunchKernelGGL((rfast_block_kernel<kLanes, TPB, kDeg>), dim3((unsigned)tiles), dim3(threads), block_lds_bytes(c->d, kLanes),
                      c->stream, c->d, blk);
   return hipGetLastError();
 }
@@ -283,9 +285,14 @@ static hipError_t launch_block(rfast_ctx* c, const RfastBlock& blk, unsigned thr
 template <int kLanes>
 static hipError_t launch_block_lanes(rfast_ctx* c, const RfastBlock& blk) {
   const unsigned threads = (unsigned)((c->d.n * kLanes + 63) / 64 * 64);
-  if (threads <= 256) return launch_block<kLanes, 256>(c, blk, threads);
-  if (threads <= 512) return launch_block<kLanes, 512>(c, blk, threads);
-  return launch_block<kLanes, 1024>(c, blk, threads);
+  if (c->max_degree <= 2) {
+    if (threads <= 256) return launch_block<kLanes, 256, 2>(c, blk, threads);
+    if (threads <= 512) return launch_block<kLanes, 512, 2>(c, blk, threads);
+    return launch_block<kLanes, 1024, 2>(c, blk, threads);
+  }
+  if (threads <= 256) return launch_block<kLanes, 256, kMaxDeg>(c, blk, threads);
+  if (threads <= 512) return launch_block<kLanes, 512, kMaxDeg>(c, blk, threads);
+  return launch_block<kLanes, 1024, kMaxDeg>(c, blk, threads);
 }
 
 hipError_t rfast_launch_block(rfast_ctx* c, const RfastBlock& blk) {

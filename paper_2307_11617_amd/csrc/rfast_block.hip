@@ -178,9 +178,8 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
 #pragma unroll
       for (int u = 0; u < kDeg; ++u)
         if (c_pl[u] & (1 << 16)) {
-          const float4 rho = mul_s(c_w[u], cur[u]);
-          z_half = add(z_half, sub(rho, ((c_pl[u] >> 8) & 0xFF) != 0xFF ? mul_s(c_w[u], last[u]) : last[u]));
-          if (c_pl[u] & (1 << 17)) V<VEC>::st(rt_g + (size_t)(ce0 + u) * p, rho);
+          z_half = track_edge(z_half, c_w[u], cur[u], last[u], ((c_pl[u] >> 8) & 0xFF) != 0xFF);
+          if (c_pl[u] & (1 << 17)) V<VEC>::st(rt_g + (size_t)(ce0 + u) * p, mul_s(c_w[u], cur[u]));
         }
       z_half = sub(add(z_half, g_new), g);
       // S3: publish version t+1 (slots nobody reads in this round); S2c: keep a_ii, push

@@ -173,9 +173,8 @@ __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float
 #pragma unroll
   for (int q = 0; q < KB; ++q)
     if (pl[q] & (1 << 16)) {
-      const T rho = mul_s(ca[q], sg[q]);
-      z_half = add(z_half, sub(rho, ((pl[q] >> 8) & 0xFF) != 0xFF ? mul_s(ca[q], rt[q]) : rt[q]));
-      if (pl[q] & (1 << 17)) V<VEC>::st(s.rho_tilde + (size_t)(ce0 + q) * p + k, rho);
+      z_half = track_edge(z_half, ca[q], sg[q], rt[q], ((pl[q] >> 8) & 0xFF) != 0xFF);
+      if (pl[q] & (1 << 17)) V<VEC>::st(s.rho_tilde + (size_t)(ce0 + q) * p + k, mul_s(ca[q], sg[q]));
     }
   for (int eb = ce0 + KB; eb < ce1; eb += KB) {  // in-degree above one batch
 #pragma unroll
@@ -190,9 +189,8 @@ __global__ void __launch_bounds__(kThreads) rfast_state_kernel(RfastDev s, float
 #pragma unroll
     for (int q = 0; q < KB; ++q)
       if (pl[q] & (1 << 16)) {
-        const T rho = mul_s(ca[q], sg[q]);
-        z_half = add(z_half, sub(rho, ((pl[q] >> 8) & 0xFF) != 0xFF ? mul_s(ca[q], rt[q]) : rt[q]));
-        if (pl[q] & (1 << 17)) V<VEC>::st(s.rho_tilde + (size_t)(eb + q) * p + k, rho);
+        z_half = track_edge(z_half, ca[q], sg[q], rt[q], ((pl[q] >> 8) & 0xFF) != 0xFF);
+        if (pl[q] & (1 << 17)) V<VEC>::st(s.rho_tilde + (size_t)(eb + q) * p + k, mul_s(ca[q], sg[q]));
       }
   }
   z_half = sub(add(z_half, g_new), g_old);

@@ -68,10 +68,10 @@ def test_uploaded_schedules(seed):
     assert np.array_equal(a.read("T_NODE"), orc.t)
 
 
-# n, d_max, burst, p, lanes per node the library must choose (the widest tile that fits LDS and 1024
-# lanes while leaving 512 tiles); every p ends in a ragged tile
-TILES = [(16, 4, 4, 57_348, 28), (16, 5, 4, 49_156, 24), (5, 0, 1, 131_076, 64), (9, 3, 4, 98_308, 48),
-         (24, 1, 2, 65_540, 32), (16, 4, 4, 65_540, 32), (16, 4, 4, 4_100, 16)]
+# n, d_max, burst, p, lanes per node the library must choose (the widest tile of which two workgroups fit
+# the LDS of a CU, else the widest that fits alone, leaving 512 tiles); every p ends in a ragged tile
+TILES = [(16, 4, 4, 65_540, 16), (16, 5, 4, 49_156, 24), (5, 0, 1, 131_076, 64), (9, 3, 4, 98_308, 32),
+         (9, 3, 1, 98_308, 48), (14, 7, 4, 57_348, 28), (24, 1, 2, 65_540, 16), (16, 4, 4, 4_100, 16)]
 
 
 @pytest.mark.parametrize("n,d_max,burst,p,lanes", TILES)

@@ -152,6 +152,54 @@ def line_tree(n: int):
     return r, c
 
 
+def binary_tree(n: int):
+    """The tree pair of the experiments on general topologies: G(R) is the oriented
+    balanced binary tree rooted at 0 (node i > 0 hears its parent (i-1)//2), G(C) its
+    inverse (node i > 0 sends to its parent); weights from the degrees, so 1/2 and 1/2
+    off the root, 1 at the root of R, and a parent with k children receives 1/2 from each
+    while keeping 1 itself in its own column."""
+    adj_r = np.eye(n, dtype=bool)
+    adj_c = np.eye(n, dtype=bool)
+    for i in range(1, n):
+        adj_r[i, (i - 1) // 2] = True   # receiver i hears its parent
+        adj_c[(i - 1) // 2, i] = True   # receiver parent hears child i
+    return _row_uniform(adj_r), _col_uniform(adj_c)
+
+
+def mesh(n: int, cols: int = 0):
+    """Bidirectional 2-D grid (4-neighbourhood, no wrap-around), row-major on `cols`
+    columns (default: ceil(sqrt(n))); the last row may be short.  Strongly connected, so
+    every node is a common root.  The paper shows its mesh only as a figure: the grid is
+    this repository's reading of the word."""
+    if cols <= 0:
+        cols = int(np.ceil(np.sqrt(n)))
+    adj = np.eye(n, dtype=bool)
+    for a in range(n):
+        r, c = divmod(a, cols)
+        for b in ((r, c + 1), (r + 1, c)):
+            j = b[0] * cols + b[1]
+            if b[1] < cols and j < n:
+                adj[a, j] = adj[j, a] = True
+    return _row_uniform(adj), _col_uniform(adj)
+
+
+def multi_root_split(n: int, servers: int):
+    """Parameter-server-like split of the appendix on topology design: nodes 0..servers-1
+    exchange both ways on a ring among themselves in both graphs; a worker w >= servers
+    hears server w mod servers in G(R) and sends to it in G(C).  The common roots are
+    exactly the servers."""
+    assert 1 <= servers <= n
+    adj_r = np.eye(n, dtype=bool)
+    adj_c = np.eye(n, dtype=bool)
+    for a in range(servers):
+        for b in ((a + 1) % servers, (a - 1) % servers):
+            adj_r[a, b] = adj_c[a, b] = True
+    for w in range(servers, n):
+        adj_r[w, w % servers] = True
+        adj_c[w % servers, w] = True
+    return _row_uniform(adj_r), _col_uniform(adj_c)
+
+
 def random_digraph(n: int, rng: np.random.Generator, extra: float = 0.3):
     """A random strongly connected pair (ring backbone plus random chords with
     random positive weights); used by property tests."""

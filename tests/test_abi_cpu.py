@@ -150,6 +150,11 @@ def test_common_roots_of_named_topologies():
     assert roots(graphs.line_tree, 6) == [0]
     assert roots(graphs.directed_ring, 5) == [0, 1, 2, 3, 4]
     assert roots(graphs.exponential, 8) == list(range(8))
+    assert roots(graphs.binary_tree, 7) == [0]
+    assert roots(graphs.binary_tree, 10) == [0]
+    assert roots(graphs.mesh, 7) == list(range(7))          # 3 columns, short last row
+    assert roots(lambda n: graphs.multi_root_split(n, 3), 11) == [0, 1, 2]
+    assert roots(lambda n: graphs.multi_root_split(n, 1), 5) == [0]
     # two roots: nodes 0 and 1 exchange both ways, node 2 only listens / only sends
     r = np.array([[.5, .5, 0], [.5, .5, 0], [0, .5, .5]])
     c = np.array([[.5, .25, .25], [.5, .5, .25], [0, .25, .5]])

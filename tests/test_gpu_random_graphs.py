@@ -31,6 +31,19 @@ def test_random_digraph(seed):
     print(f"\n[{w.name}] worst {worst}")
 
 
+@pytest.mark.parametrize("name", ["binary_tree", "line", "mesh", "multi_root", "directed_ring", "exponential"])
+def test_named_topologies(name):
+    """The topologies of the experiments on general graphs (trees and lines as a pull tree and
+    its inverse, which are not strongly connected) and the parameter-server-like split."""
+    build, n = {"binary_tree": (graphs.binary_tree, 15), "line": (graphs.line_tree, 7), "mesh": (graphs.mesh, 11),
+                "multi_root": (lambda m: graphs.multi_root_split(m, 3), 11), "directed_ring": (graphs.directed_ring, 7),
+                "exponential": (graphs.exponential, 7)}[name]
+    wr, wc = build(n)
+    w = _workload(n, 1028, wr, wc, d_max=3, burst=2, p_active=0.6, p_drop=0.2, seed=n, gamma=0.01)
+    worst, orc, gpu = harness.run_parity(w, 300, every=75)
+    print(f"\n[{name} n={n}] worst {worst}")
+
+
 def test_deepest_ring_and_dense_graph():
     """D + 2 = 64 slots (the bitmask limit), complete graph: 15 in- and out-edges per node."""
     n = 16

@@ -304,19 +304,47 @@ def test_fixed_point_least_squares_closed_form():
     assert all(0.01 < rt < 0.3 for rt in ratios), errs
 
 
-@pytest.mark.parametrize("topology", ["tree_star", "biring", "exp"])
+def test_named_topologies_satisfy_assumption_1_and_2():
+    """Row- / column-stochastic with positive diagonal, weights from the degrees, and the common
+    roots the construction promises (reachability by brute force on the dense matrices)."""
+    def reach(adj, src):          # nodes that hear src, directly or not (adj[i, j]: i hears j)
+        seen, todo = {src}, [src]
+        while todo:
+            j = todo.pop()
+            for i in np.nonzero(adj[:, j])[0]:
+                if int(i) not in seen:
+                    seen.add(int(i)); todo.append(int(i))
+        return seen
+    cases = [(graphs.binary_tree(7), {0}), (graphs.binary_tree(12), {0}), (graphs.mesh(9), set(range(9))),
+             (graphs.mesh(7), set(range(7))), (graphs.multi_root_split(11, 3), {0, 1, 2}),
+             (graphs.line_tree(5), {0}), (graphs.directed_ring(4), set(range(4)))]
+    for (wr, wc), roots in cases:
+        n = wr.shape[0]
+        assert np.allclose(wr.sum(axis=1), 1) and np.allclose(wc.sum(axis=0), 1)
+        assert (np.diag(wr) > 0).all() and (np.diag(wc) > 0).all() and (wr >= 0).all() and (wc >= 0).all()
+        for m in (wr, wc):   # uniform over the non-zeros of a row of R / a column of C
+            nz = m != 0
+            assert np.allclose(m[nz], (nz / nz.sum(axis=1, keepdims=True))[nz] if m is wr
+                               else (nz / nz.sum(axis=0, keepdims=True))[nz])
+        # root of G(R): everybody hears it through R; root of G(C^T): it hears everybody through C
+        got = {j for j in range(n) if len(reach(wr != 0, j)) == n and len(reach((wc != 0).T, j)) == n}
+        assert got == roots, (got, roots)
+
+
+@pytest.mark.parametrize("topology", ["tree_star", "biring", "exp", "binary_tree", "mesh", "multi_root"])
 def test_fixed_point_diag_quadratic_closed_form(topology):
     """x*_k = sum_i h_ik c_ik / sum_i h_ik, reached over spanning-tree graphs
     that are not strongly connected (Assumption 2) as well."""
     n, p = 8, 6
     wr, wc = {"tree_star": graphs.tree_pull_star_push, "biring": graphs.bidirectional_ring,
-              "exp": graphs.exponential}[topology](n)
+              "exp": graphs.exponential, "binary_tree": graphs.binary_tree, "mesh": graphs.mesh,
+              "multi_root": lambda m: graphs.multi_root_split(m, 3)}[topology](n)
     # exact weights: with fp32-rounded thirds the columns of C sum to 1 + 3e-8 and
     # the tracker leaks that share of every z_half, which moves the limit by ~1e-6
     R, C = graphs.from_dense(wr, fp32_weights=False), graphs.from_dense(wc, fp32_weights=False)
     obj, h, c = _random_problem(n, p, 21)
     x_star = (h * c).sum(axis=0) / h.sum(axis=0)
-    gamma = {"tree_star": 0.01, "biring": 0.12, "exp": 0.15}[topology]
+    gamma = {"tree_star": 0.01, "biring": 0.12, "exp": 0.15, "binary_tree": 0.01, "mesh": 0.12, "multi_root": 0.03}[topology]
     orc = RFastOracle(n, p, R, C, D=7, burst=4, objective=obj)
     sched = ScheduleSpec(n, R.nnz_off, C.nnz_off, np.full(n, 0.6), 4, 0.15, seed=1)
     _run(orc, sched, 6000, gamma)

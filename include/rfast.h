@@ -225,8 +225,8 @@ int rfast_run_events(rfast_ctx* ctx, int32_t iterations, uint64_t seed, const fl
 int rfast_use_graphs(rfast_ctx* ctx, int32_t on);
 
 /* on != 0 (the default): rfast_run and rfast_run_generated advance up to 128 rounds with one
- * launch where that is possible and pays -- the separable objective (diagonal quadratic) without
- * the momentum variant, p a multiple of 4, no node with more than 4 in-edges of R, in-edges of C or
+ * launch where that is possible and pays -- the separable objective (diagonal quadratic, with or
+ * without the optimizer variant), p a multiple of 4, no node with more than 4 in-edges of R, in-edges of C or
  * out-edges of C, at least 64 coordinates of every node's two rings fitting into the 160 KB of LDS
  * of a CU (n * (D+2) * 512 B + nnzC_off * 256 B + plans), and at least 2 rounds to run before the
  * next multiple of the rebase interval (12 where n * p * 4 > 8 MB: a launch moves every ring slot

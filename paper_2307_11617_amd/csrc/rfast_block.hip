@@ -59,7 +59,8 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
     for (int w = threadIdx.x; w < words; w += blockDim.x) plan_l[w] = s.blk_plan[w];
   }
 
-  float4 x, z, g, h, c;
+  float4 x, z, g, h, c, m = make_float4(0.f, 0.f, 0.f, 0.f);
+  const bool momentum = s.mom != nullptr;  // the optimizer variant's heavy-ball buffer (uniform)
   int re0 = 0, ce0 = 0, o0 = 0, dR = 0, dI = 0, dO = 0;
   float r_self = 0.f, c_self = 0.f;
   // the node's edges, in registers for the whole launch (at most kDeg of each kind, checked by the
@@ -74,6 +75,7 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
     z = V<VEC>::ld(s.z + off);
     h = V<VEC>::ld((const float*)s.prob.data0 + off);
     c = V<VEC>::ld((const float*)s.prob.data1 + off);
+    if (momentum) m = V<VEC>::ld(s.mom + off);
     re0 = s.r_ptr[i]; dR = s.r_ptr[i + 1] - re0;
     ce0 = s.c_ptr[i]; dI = s.c_ptr[i + 1] - ce0;
     o0 = s.co_ptr[i]; dO = s.co_ptr[i + 1] - o0;
@@ -165,8 +167,9 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
         if ((c_pl[u] & (1 << 16)) && ((c_pl[u] >> 8) & 0xFF) == 0xFF) last[u] = V<VEC>::ld(rt_g + (size_t)(ce0 + u) * p);
       const float4 sig_cur = sg_l[own + slot_cur * kLanes];
       const float4 sig_leaving = sg_l[own + leaving * kLanes];
-      // S1: local descent
-      const float4 v = fma_s(-blk.gamma[q], z, x);
+      // S1: local descent; with the optimizer variant along the heavy-ball buffer m <- beta m + z
+      if (momentum) m = fma_s(s.beta, m, z);
+      const float4 v = fma_s(-blk.gamma[q], momentum ? m : z, x);
       // S2a: pull the stamped neighbour copies and mix with row-stochastic weights
       float4 x_new = mul_s(r_self, v);
 #pragma unroll
@@ -212,6 +215,7 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
     const size_t off = (size_t)i * p + k;
     V<VEC>::st(s.x + off, x);
     V<VEC>::st(s.z + off, z);
+    if (momentum) V<VEC>::st(s.mom + off, m);
     float* vg = s.v_ring + (size_t)i * M * p + k;
     float* sgg = s.sigma_ring + (size_t)i * M * p + k;
     for (int m0 = 0; m0 < M; m0 += 8) {
@@ -263,10 +267,10 @@ int block_lanes(const RfastDev& d) {
 
 // The tile of every node must fit into the LDS of one CU next to the plans, a workgroup holds at
 // least 16 lanes per node, no node has more than kMaxDeg edges of a kind, and the path exists for the
-// separable objective without the momentum variant.
+// separable objective (the heavy-ball buffer of the optimizer variant is one more register set).
 bool rfast_block_eligible(const rfast_ctx* c) {
   const RfastDev& d = c->d;
-  return d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC && d.mom == nullptr && (d.p % 4) == 0 && c->max_degree <= kMaxDeg &&
+  return d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC && (d.p % 4) == 0 && c->max_degree <= kMaxDeg &&
          block_lanes(d) != 0;
 }
 

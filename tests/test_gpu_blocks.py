@@ -125,21 +125,32 @@ def test_generated_schedules_and_events():
     _same(a, b, "generated after events")
 
 
-def test_not_taken_where_it_does_not_apply():
-    """Momentum variant, p not a multiple of four: the call must simply run one pass per round."""
+def test_odd_p_runs_one_pass_per_round_and_momentum_variant_same_bits():
+    """p not a multiple of four: the call must simply run one pass per round.  The optimizer variant
+    (heavy-ball buffer, weight decay, step-size schedule) goes through the multi-round kernel."""
     w = configs.config2(p=1027, rounds=0)
     a, b = _pair(w)
+    assert rfast_block_info(a.ctx) == 0
     for g in (a, b):
         g.init(None, None)
-    st, dev = harness.upload_chunk(a, w, 0, 20)
+    st, dev = harness.upload_chunk(a, w, 0, 40)
     args = [dev[k] for k in ("active", "delay_R", "delay_C", "drop_R", "drop_C")]
     for g in (a, b):
-        g.run(20, *args, w.gamma)
+        g.run(40, *args, w.gamma)
     _same(a, b, "odd p")
-    w = configs.config2(p=1024, rounds=0)
+    w = configs.config2(p=1028, rounds=0)
+    w.sched.p_active[:] = 0.7
     a, b = _pair(w)
     for g in (a, b):
         g.set_optimizer(0.9, 0.01)
+        g.set_gamma_schedule(15, 0.5)
         g.init(None, None)
-        g.run(20, *[v.clone() for v in args], w.gamma)
+    assert rfast_block_info(a.ctx) == 16
+    st, dev = harness.upload_chunk(a, w, 0, 40)
+    args = [dev[k] for k in ("active", "delay_R", "delay_C", "drop_R", "drop_C")]
+    for g in (a, b):
+        g.run(40, *args, w.gamma)
+        g.check()
     _same(a, b, "momentum")
+    assert np.array_equal(a.read("MOMENTUM"), b.read("MOMENTUM"))
+    assert np.abs(a.read("MOMENTUM")).max() > 0

@@ -229,7 +229,7 @@ int rfast_use_graphs(rfast_ctx* ctx, int32_t on);
  * without the optimizer variant), p a multiple of 4, no node with more than 4 in-edges of R, in-edges of C or
  * out-edges of C, at least 64 coordinates of every node's two rings fitting into the 160 KB of LDS
  * of a CU (n * (D+2) * 512 B + nnzC_off * 256 B + plans), and at least 2 rounds to run before the
- * next multiple of the rebase interval (12 where n * p * 4 > 8 MB: a launch moves every ring slot
+ * next multiple of the rebase interval (8 where n * p * 4 > 8 MB: a launch moves every ring slot
  * in and out once, which a large state earns back only over that many rounds); rounds that do not
  * qualify run one pass each.  Every step of a round is elementwise in the coordinate, so a tile of
  * coordinates can stay in LDS over several rounds; the results are the same bits as round-by-round

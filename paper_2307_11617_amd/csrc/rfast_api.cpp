@@ -577,18 +577,17 @@ static int run_block(rfast_ctx* c, int32_t len, const uint8_t* d_active, const i
   blk.rounds = len;
   hipError_t e = hipSuccess;
   time_begin(c, 2);
+  if (!generated) {  // uploaded schedules: every round of the launch resolved by one launch
+    d.blk_plan = c->blk_plan_base;
+    e = rfast_launch_resolve(c, d_active, d_delay_R, d_delay_C, d_drop_R, d_drop_C, len);
+  }
   for (int32_t q = 0; q < len && e == hipSuccess; ++q) {
     blk.gamma[q] = gamma_now(c, gamma);
-    d.blk_plan = c->blk_plan_base + (size_t)q * PL;
-    if (generated) {
+    if (generated) {  // the generator draws one round at a time
+      d.blk_plan = c->blk_plan_base + (size_t)q * PL;
       e = rfast_launch_generate(c, seed, d_p_active, max_delay, p_drop, false);
       if (e == hipSuccess)
         e = rfast_launch_resolve(c, d.gen_active, d.gen_delay_r, d.gen_delay_c, d.gen_drop_r, d.gen_drop_c);
-    } else {
-      e = rfast_launch_resolve(c, d_active + (size_t)q * d.n, d_delay_R ? d_delay_R + (size_t)q * d.eR : nullptr,
-                               d_delay_C ? d_delay_C + (size_t)q * d.eC : nullptr,
-                               d_drop_R ? d_drop_R + (size_t)q * d.eR : nullptr,
-                               d_drop_C ? d_drop_C + (size_t)q * d.eC : nullptr);
     }
     c->host_round++;
   }

@@ -133,11 +133,11 @@ enum { RFAST_MODE_FUSED = 0, RFAST_MODE_MIX = 1, RFAST_MODE_TRACK = 2 };
 
 // rounds that one launch of the LDS-resident kernel can advance, rounds whose plan records it holds
 // in LDS at a time, and the shortest launch that pays where the state is large (the launch moves
-// every ring slot in and out once: measured on 16 nodes x 11.2 M coordinates, 7.9 ms per launch
-// plus 0.78 ms per round against 1.53 ms per round of the streaming kernel)
+// every ring slot in and out once: measured on 16 nodes x 11.2 M coordinates, about 7 ms per launch
+// plus 0.33 ms per round against 1.53 ms per round of the streaming kernel: even from 6 rounds on)
 constexpr int kBlockRounds = 128;
 constexpr int kPlanChunk = 16;
-constexpr int kBlockMinRoundsLarge = 12;
+constexpr int kBlockMinRoundsLarge = 8;
 struct RfastBlock {
   float gamma[kBlockRounds];  // step size of each round
   int32_t rounds;             // 1 .. kBlockRounds
@@ -145,7 +145,7 @@ struct RfastBlock {
 
 // launchers (each enqueues on ctx->stream and returns a hipError_t)
 hipError_t rfast_launch_resolve(rfast_ctx* c, const uint8_t* active, const int32_t* delay_R,
-                                const int32_t* delay_C, const uint8_t* drop_R, const uint8_t* drop_C);
+                                const int32_t* delay_C, const uint8_t* drop_R, const uint8_t* drop_C, int rounds = 1);
 hipError_t rfast_launch_state(rfast_ctx* c, int mode, float gamma);
 hipError_t rfast_launch_rebase(rfast_ctx* c);
 // several rounds of the separable objective on LDS-resident tiles; the rounds' plans are in blk_plan

@@ -113,79 +113,96 @@ __device__ inline void edge_decide(const RfastDev& s, int kind, int e, int r, co
 constexpr int kResolveThreads = 1024;
 constexpr int kAhead = 2;  // edges per lane whose loads are issued before the node pass
 
-__global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev s, const uint8_t* active,
+// rounds > 1: consecutive rounds in one launch, the schedule arrays of round q at offset q of each
+// pointer and its plan record behind the previous one (the per-round plan arrays then hold the last
+// round only, so this form serves the multi-round kernel, which reads records).  The rounds are
+// sequential -- each reads the counters, stamps and delivery bits the one before wrote -- with the
+// workgroup's barrier between them.
+__global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev s, int rounds, const uint8_t* active,
                                                                          const int32_t* delay_R, const int32_t* delay_C,
                                                                          const uint8_t* drop_R, const uint8_t* drop_C) {
   __shared__ int wave_cnt[kResolveThreads / 64];
   __shared__ int base;
-  const int r = *s.round_no;
+  const int r0 = *s.round_no;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int E = s.eR + s.eC;
-  EdgeIn ahead[kAhead];
+  for (int rq = 0; rq < rounds; ++rq) {
+    const int r = r0 + rq;
+    EdgeIn ahead[kAhead];
 #pragma unroll
-  for (int a = 0; a < kAhead; ++a) {
-    const int e = threadIdx.x + a * kResolveThreads;
-    if (e < s.eR) edge_level1(s, 0, e, delay_R, drop_R, &ahead[a]);
-    else if (e < E) edge_level1(s, 1, e - s.eR, delay_C, drop_C, &ahead[a]);
-  }
-#pragma unroll
-  for (int a = 0; a < kAhead; ++a)
-    if (threadIdx.x + a * kResolveThreads < E) edge_level2(s, r, active, &ahead[a]);
-  if (threadIdx.x == 0) base = 0;
-  if (threadIdx.x == 0 && s.blk_plan) s.blk_plan[s.n + E] = 0;  // a record ends with a word that is always zero
-  // node pass: snapshot of the counters, and the ordered list of active nodes (ballot + prefix per chunk)
-  for (int i0 = 0; i0 < s.n; i0 += kResolveThreads) {
-    const int i = i0 + threadIdx.x;
-    bool act = false;
-    int ti = 0;
-    if (i < s.n) {
-      ti = s.t[i];
-      s.plan_t[i] = ti;
-      s.node_spill[i] = 0;
-      s.t_hist[(size_t)i * s.H + (r % s.H)] = ti;
-      act = active[i] != 0;
-      if (s.blk_plan) s.blk_plan[i] = (ti & 0x3FFFFFFF) | (act ? (int)0x80000000 : 0);
+    for (int a = 0; a < kAhead; ++a) {
+      const int e = threadIdx.x + a * kResolveThreads;
+      if (e < s.eR) edge_level1(s, 0, e, delay_R, drop_R, &ahead[a]);
+      else if (e < E) edge_level1(s, 1, e - s.eR, delay_C, drop_C, &ahead[a]);
     }
-    const unsigned long long m = __ballot(act);
-    if (lane == 0) wave_cnt[wave] = __popcll(m);
-    __syncthreads();
-    int off = base;
-    for (int w = 0; w < wave; ++w) off += wave_cnt[w];
-    if (act) s.active_plan[off + __popcll(m & ((1ull << lane) - 1ull))] = make_int2(i, ti);
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      int tot = 0;
-      for (int w = 0; w < kResolveThreads / 64; ++w) tot += wave_cnt[w];
-      base += tot;
-    }
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) *s.n_active = base;
-  for (int q = base + threadIdx.x; q < s.n + 8; q += kResolveThreads) s.active_plan[q] = make_int2(-1, 0);
-  // edge pass (node_spill was cleared above, before the barriers); nothing in it depends on the node pass
 #pragma unroll
-  for (int a = 0; a < kAhead; ++a) {
-    const int e = threadIdx.x + a * kResolveThreads;
-    if (e < E) edge_decide(s, e >= s.eR, e >= s.eR ? e - s.eR : e, r, ahead[a]);
+    for (int a = 0; a < kAhead; ++a)
+      if (threadIdx.x + a * kResolveThreads < E) edge_level2(s, r, active, &ahead[a]);
+    if (threadIdx.x == 0) base = 0;
+    if (threadIdx.x == 0 && s.blk_plan) s.blk_plan[s.n + E] = 0;  // a record ends with a word that is always zero
+    // node pass: snapshot of the counters, and the ordered list of active nodes (ballot + prefix per chunk)
+    for (int i0 = 0; i0 < s.n; i0 += kResolveThreads) {
+      const int i = i0 + threadIdx.x;
+      bool act = false;
+      int ti = 0;
+      if (i < s.n) {
+        ti = s.t[i];
+        s.plan_t[i] = ti;
+        s.node_spill[i] = 0;
+        s.t_hist[(size_t)i * s.H + (r % s.H)] = ti;
+        act = active[i] != 0;
+        if (s.blk_plan) s.blk_plan[i] = (ti & 0x3FFFFFFF) | (act ? (int)0x80000000 : 0);
+      }
+      const unsigned long long m = __ballot(act);
+      if (lane == 0) wave_cnt[wave] = __popcll(m);
+      __syncthreads();
+      int off = base;
+      for (int w = 0; w < wave; ++w) off += wave_cnt[w];
+      if (act) s.active_plan[off + __popcll(m & ((1ull << lane) - 1ull))] = make_int2(i, ti);
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        int tot = 0;
+        for (int w = 0; w < kResolveThreads / 64; ++w) tot += wave_cnt[w];
+        base += tot;
+      }
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) *s.n_active = base;
+    for (int q = base + threadIdx.x; q < s.n + 8; q += kResolveThreads) s.active_plan[q] = make_int2(-1, 0);
+    // edge pass (node_spill was cleared above, before the barriers); nothing in it depends on the node pass
+#pragma unroll
+    for (int a = 0; a < kAhead; ++a) {
+      const int e = threadIdx.x + a * kResolveThreads;
+      if (e < E) edge_decide(s, e >= s.eR, e >= s.eR ? e - s.eR : e, r, ahead[a]);
+    }
+    for (int e = threadIdx.x + kAhead * kResolveThreads; e < E; e += kResolveThreads) {  // more than 2048 edges
+      const int kind = e >= s.eR, el = kind ? e - s.eR : e;
+      EdgeIn q;
+      edge_level1(s, kind, el, kind ? delay_C : delay_R, kind ? drop_C : drop_R, &q);
+      edge_level2(s, r, active, &q);
+      edge_decide(s, kind, el, r, q);
+    }
+    __syncthreads();  // every read of the counters is done
+    for (int i = threadIdx.x; i < s.n; i += kResolveThreads)
+      if (active[i] != 0) s.t[i] = s.plan_t[i] + 1;
+    if (rq + 1 < rounds) {
+      __syncthreads();  // the next round reads what this one wrote
+      active += s.n;
+      delay_R += s.eR;
+      drop_R += s.eR;
+      delay_C += s.eC;
+      drop_C += s.eC;
+      if (s.blk_plan) s.blk_plan += s.n + E + 1;
+    }
   }
-  for (int e = threadIdx.x + kAhead * kResolveThreads; e < E; e += kResolveThreads) {  // more than 2048 edges
-    const int kind = e >= s.eR, el = kind ? e - s.eR : e;
-    EdgeIn q;
-    edge_level1(s, kind, el, kind ? delay_C : delay_R, kind ? drop_C : drop_R, &q);
-    edge_level2(s, r, active, &q);
-    edge_decide(s, kind, el, r, q);
-  }
-  __syncthreads();  // every read of the counters is done
-  for (int i = threadIdx.x; i < s.n; i += kResolveThreads)
-    if (active[i] != 0) s.t[i] = s.plan_t[i] + 1;
-  if (threadIdx.x == 0) *s.round_no = r + 1;
+  if (threadIdx.x == 0) *s.round_no = r0 + rounds;
 }
 
 }  // namespace
 
 hipError_t rfast_launch_resolve(rfast_ctx* c, const uint8_t* active, const int32_t* delay_R,
-                                const int32_t* delay_C, const uint8_t* drop_R, const uint8_t* drop_C) {
-  hipLaunchKernelGGL(rfast_resolve_kernel, dim3(1), dim3(kResolveThreads), 0, c->stream, c->d, active, delay_R, delay_C,
-                     drop_R, drop_C);
+                                const int32_t* delay_C, const uint8_t* drop_R, const uint8_t* drop_C, int rounds) {
+  hipLaunchKernelGGL(rfast_resolve_kernel, dim3(1), dim3(kResolveThreads), 0, c->stream, c->d, rounds, active, delay_R,
+                     delay_C, drop_R, drop_C);
   return hipGetLastError();
 }

@@ -95,7 +95,7 @@ def test_tile_widths(n, d_max, burst, p, lanes):
 
 
 def test_large_state_short_and_long_calls():
-    """Above 8 MB of x a launch needs 12 rounds to pay: shorter calls run one pass per round, longer
+    """Above 8 MB of x a launch needs 8 rounds to pay: shorter calls run one pass per round, longer
     ones take the multi-round kernel (four refills of its plan records at 70 rounds), same bits."""
     w = configs.config2(p=131_076, rounds=0)
     a, b = _pair(w)
@@ -103,7 +103,7 @@ def test_large_state_short_and_long_calls():
         g.init(None, None)
     st, dev = harness.upload_chunk(a, w, 0, 100)
     cut = lambda lo, hi: [dev[k][lo:hi] for k in ("active", "delay_R", "delay_C", "drop_R", "drop_C")]
-    for lo, hi in ((0, 11), (11, 81), (81, 100)):
+    for lo, hi in ((0, 7), (7, 77), (77, 100)):
         for g in (a, b):
             g.run(hi - lo, *cut(lo, hi), w.gamma)
             g.check()

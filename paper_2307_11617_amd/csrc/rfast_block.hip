@@ -131,25 +131,32 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
     const bool refill = (q + 1) % kPlanChunk == 0 && q + 1 < blk.rounds;
     int next_plan[kPlanPerLane];
     if (refill) {
+      // every load unconditional (a word past the end reads word 0 instead and is not stored), so
+      // that they are issued back to back and land while the round computes
       const int words = (blk.rounds - (q + 1) < kPlanChunk ? blk.rounds - (q + 1) : kPlanChunk) * W1;
+      const int* src = s.blk_plan + (q + 1) * W1;
 #pragma unroll
       for (int u = 0; u < kPlanPerLane; ++u) {
-        const int w = threadIdx.x + u * blockDim.x;
-        next_plan[u] = w < words ? s.blk_plan[(q + 1) * W1 + w] : 0;
+        const int w = threadIdx.x + u * (int)blockDim.x;
+        next_plan[u] = src[w < words ? w : 0];
       }
     }
-    if (mine && P[i] < 0) {  // bit 31: node i is activated in this round
-      const int t_old = P[i] & 0x3FFFFFFF;
-      const int slot_new = slot_cur + 1 == M ? 0 : slot_cur + 1;
-      const int leaving = slot_new + 1 == M ? 0 : slot_new + 1;
-      // every plan word of the round in one batch of LDS reads ...
-      int r_slot[kDeg], c_pl[kDeg], o_pl[kDeg];
+    // every plan word of the round in one batch of LDS reads, the node's own among them (an idle
+    // node reads its edges' words for nothing, which is cheaper than a second round trip for the rest) ...
+    int node_w = 0, r_slot[kDeg], c_pl[kDeg], o_pl[kDeg];
+    if (mine) {
+      node_w = P[i];
 #pragma unroll
       for (int u = 0; u < kDeg; ++u) {
         r_slot[u] = P[r_pw[u]];
         c_pl[u] = P[c_pw[u]];
         o_pl[u] = P[o_pw[u]];
       }
+    }
+    if (node_w < 0) {  // bit 31: node i is activated in this round
+      const int t_old = node_w & 0x3FFFFFFF;
+      const int slot_new = slot_cur + 1 == M ? 0 : slot_cur + 1;
+      const int leaving = slot_new + 1 == M ? 0 : slot_new + 1;
       // ... and every ring value of the round in a second one (what a missing or idle edge reads
       // is a valid address and is not used)
       float4 nb[kDeg], cur[kDeg], last[kDeg];
@@ -204,7 +211,7 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
     if (refill) {
 #pragma unroll
       for (int u = 0; u < kPlanPerLane; ++u) {
-        const int w = threadIdx.x + u * blockDim.x;
+        const int w = threadIdx.x + u * (int)blockDim.x;
         if (w < kPlanChunk * W1) plan_l[w] = next_plan[u];
       }
       __syncthreads();

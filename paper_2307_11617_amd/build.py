@@ -7,7 +7,7 @@ import subprocess
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "librfast.so")
-SOURCES = ["rfast_api.cpp", "rfast_resolve.hip", "rfast_round.hip", "rfast_block.hip", "rfast_grad.hip", "rfast_softmax.hip",
+SOURCES = ["rfast_api.cpp", "rfast_resolve.hip", "rfast_round.hip", "rfast_block.hip", "rfast_wave.hip", "rfast_grad.hip", "rfast_softmax.hip",
            "rfast_diag.hip", "rfast_schedule.hip"]
 # no floating-point contraction: the two kernels that implement the separable round must round alike
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-shared", "-std=c++17", "-ffp-contract=off",

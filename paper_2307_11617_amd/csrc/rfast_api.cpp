@@ -555,7 +555,7 @@ int rfast_round(rfast_ctx* c, const uint8_t* d_active, const int32_t* d_delay_R,
 // multiple of the rebase interval; and it reads and writes every ring slot once, which a large
 // state earns back only over enough rounds.
 static int32_t block_length(const rfast_ctx* c, int32_t rounds) {
-  if (!c->use_blocks || !rfast_block_eligible(c)) return 0;
+  if (!c->use_blocks || !(rfast_wave_eligible(c) || rfast_block_eligible(c))) return 0;
   int32_t len = rounds < kBlockRounds ? rounds : kBlockRounds;
   if (c->rebase_interval > 0) {
     const int64_t to_boundary = c->rebase_interval - c->host_round % c->rebase_interval;
@@ -595,7 +595,7 @@ static int run_block(rfast_ctx* c, int32_t len, const uint8_t* d_active, const i
   d.blk_plan = c->blk_plan_base;
   if (e == hipSuccess) {
     time_begin(c, 0);
-    e = rfast_launch_block(c, blk);
+    e = rfast_wave_eligible(c) ? rfast_launch_wave(c, blk) : rfast_launch_block(c, blk);
     time_end(c, 0);
   }
   d.blk_plan = nullptr;
@@ -609,7 +609,7 @@ static int run_block(rfast_ctx* c, int32_t len, const uint8_t* d_active, const i
 
 int rfast_block_info(rfast_ctx* c, int32_t* lanes_per_node) {
   if (!c || !lanes_per_node) return RFAST_EINVAL;
-  *lanes_per_node = block_length(c, kBlockRounds) > 0 ? rfast_block_lanes(c) : 0;
+  *lanes_per_node = block_length(c, kBlockRounds) > 0 ? (rfast_wave_eligible(c) ? rfast_wave_lanes(c) : rfast_block_lanes(c)) : 0;
   return RFAST_OK;
 }
 

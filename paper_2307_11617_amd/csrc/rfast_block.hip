@@ -1,16 +1,16 @@
-// Several activation rounds per launch with the state of a tile of coordinates resident in LDS.
+// Several activation rounds per launch with the state of a tile of coordinates resident in LDS,
+// one tile per WORKGROUP: the form for graphs of 33 to 64 nodes (smaller graphs take the kernel of
+// rfast_wave.hip, whose tile belongs to one wavefront and which needs no barrier).
 //
 // Everything in a round of Algorithm 1 is elementwise in the coordinate k: coordinate k of every
 // node, ring slot and buffer depends, over any number of rounds, only on coordinate k of the
 // others.  For the separable objective (whose gradient is elementwise too) a workgroup can
 // therefore take a tile of coordinates of EVERY node, load the rings of v and of the running sums
 // for them into LDS once, advance them through up to kBlockRounds rounds -- all neighbour reads of
-// S2a / S2b and all publications of S3 are LDS traffic -- and write them back once.  HBM traffic
-// per round drops from 13 words per coordinate and node-update to (2 M + 4 + 2 M + 2) / rounds
-// words per coordinate and node (read everything, write everything, once per launch); the 160 KB
-// of LDS per CU are what makes a useful tile fit (config 2: 16 nodes x 2 rings x 9 slots + 32
-// buffers, 5 KB per lane column of 4 coordinates, 28 columns).  One launch also replaces up to
-// kBlockRounds launches.
+// S2a / S2b and all publications of S3 are LDS traffic, with one barrier per round -- and write
+// them back once.  HBM traffic per round drops from 13 words per coordinate and node-update to
+// (2 M + 4 + 2 M + 2) / rounds words per coordinate and node (read everything, write everything,
+// once per launch).  One launch also replaces up to kBlockRounds launches.
 //
 // Layout of the work: kLanes lanes per node, 4 consecutive coordinates per lane (one Philox call per
 // lane and sample, as in the streaming kernel), so a workgroup has n kLanes lanes; x, z, the stored
@@ -19,7 +19,8 @@
 // the two paths give the same bits.
 //
 // The integer plans of the rounds (who is active, which slot each edge reads, where each S4
-// buffer lives) are made by the resolver, one record per round, and copied to LDS first.
+// buffer lives) are made by the resolver, one record per round, and copied to LDS sixteen rounds at
+// a time.
 #include "rfast_vec.h"
 
 namespace {
@@ -31,7 +32,7 @@ constexpr int kPlanPerLane = 10;
 
 // kLanes: lanes per node, each owning 4 coordinates of a tile of 4 kLanes; TPB: upper bound of the
 // workgroup size (n kLanes lanes, rounded up to whole wavefronts), which sets how many registers
-// the compiler may use; kDeg: edge slots per node and kind (2 for rings and paths, else kMaxDeg)
+// the compiler may use (at 1024 it is held to 128 and spills some to scratch); kDeg: edge slots per node and kind (2 for rings and paths, else kMaxDeg)
 template <int kLanes, int TPB, int kDeg>
 __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock blk) {
   constexpr int VEC = 4;
@@ -247,26 +248,19 @@ size_t block_lds_bytes(const RfastDev& d, int lanes) {
   return (size_t)2 * d.n * d.M * lanes * sizeof(float4) + (size_t)kPlanChunk * (d.n + d.eR + d.eC + 1) * sizeof(int);
 }
 
-// Lanes per node.  One wavefront per SIMD leaves every LDS wait, barrier and scalar instruction of
-// the round loop exposed, so a CU should hold at least two.  The widest tile of which two workgroups
-// fit into the LDS of a CU is taken first: two workgroups are out of step, so that one computes
-// while the other sits at its barrier or moves its tile in or out (measured on 16 nodes x 11.2 M:
-// 0.389 ms per round with two workgroups of 16 lanes per node against 0.412 with one of 32, 0.523
-// with four of 8).  Where two do not fit, the widest tile that fits alone.  A tile wider than 16
-// lanes per node must leave two tiles per CU of the chip to schedule.
-constexpr int kLaneChoices[] = {64, 48, 32, 28, 24, 16};
-constexpr size_t kLdsBudget = 156 * 1024;  // of one workgroup
-constexpr size_t kLdsTwo = 158 * 1024;     // of two workgroups on one CU (160 KB less allocation granules)
+// Lanes per node: the widest tile that fits LDS and 1024 lanes; a tile wider than 16 lanes per
+// node must leave two tiles per CU of the chip to schedule.  (Graphs of up to 32 nodes take the
+// kernel with one tile per wavefront instead, so a workgroup here has more than 512 lanes.)
+constexpr int kLaneChoices[] = {28, 24, 16};
+constexpr size_t kLdsBudget = 156 * 1024;
 
 int block_lanes(const RfastDev& d) {
-  for (int two = 1; two >= 0; --two)
-    for (int lanes : kLaneChoices) {
-      const int threads = (d.n * lanes + 63) / 64 * 64;
-      const size_t lds = block_lds_bytes(d, lanes);
-      const bool fits = threads <= 1024 && (two ? 2 * lds <= kLdsTwo && threads <= 512 : lds <= kLdsBudget) &&
-                        (int64_t)kPlanChunk * (d.n + d.eR + d.eC + 1) <= (int64_t)kPlanPerLane * threads;
-      if (fits && (lanes == 16 || (d.p + 4 * lanes - 1) / (4 * lanes) >= 512)) return lanes;
-    }
+  for (int lanes : kLaneChoices) {
+    const int threads = (d.n * lanes + 63) / 64 * 64;
+    const bool fits = threads <= 1024 && block_lds_bytes(d, lanes) <= kLdsBudget &&
+                      (int64_t)kPlanChunk * (d.n + d.eR + d.eC + 1) <= (int64_t)kPlanPerLane * threads;
+    if (fits && (lanes == 16 || (d.p + 4 * lanes - 1) / (4 * lanes) >= 512)) return lanes;
+  }
   return 0;
 }
 
@@ -302,21 +296,14 @@ static hipError_t launch_block(rfast_ctx* c, const RfastBlock& blk, unsigned thr
 template <int kLanes>
 static hipError_t launch_block_lanes(rfast_ctx* c, const RfastBlock& blk) {
   const unsigned threads = (unsigned)((c->d.n * kLanes + 63) / 64 * 64);
-  if (c->max_degree <= 2) {
-    if (threads <= 256) return launch_block<kLanes, 256, 2>(c, blk, threads);
-    if (threads <= 512) return launch_block<kLanes, 512, 2>(c, blk, threads);
-    return launch_block<kLanes, 1024, 2>(c, blk, threads);
-  }
-  if (threads <= 256) return launch_block<kLanes, 256, kMaxDeg>(c, blk, threads);
-  if (threads <= 512) return launch_block<kLanes, 512, kMaxDeg>(c, blk, threads);
-  return launch_block<kLanes, 1024, kMaxDeg>(c, blk, threads);
+  if (threads <= 512) return c->max_degree <= 2 ? launch_block<kLanes, 512, 2>(c, blk, threads)
+                                                : launch_block<kLanes, 512, kMaxDeg>(c, blk, threads);
+  return c->max_degree <= 2 ? launch_block<kLanes, 1024, 2>(c, blk, threads)
+                            : launch_block<kLanes, 1024, kMaxDeg>(c, blk, threads);
 }
 
 hipError_t rfast_launch_block(rfast_ctx* c, const RfastBlock& blk) {
   switch (block_lanes(c->d)) {
-    case 64: return launch_block_lanes<64>(c, blk);
-    case 48: return launch_block_lanes<48>(c, blk);
-    case 32: return launch_block_lanes<32>(c, blk);
     case 28: return launch_block_lanes<28>(c, blk);
     case 24: return launch_block_lanes<24>(c, blk);
     case 16: return launch_block_lanes<16>(c, blk);

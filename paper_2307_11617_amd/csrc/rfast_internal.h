@@ -149,7 +149,10 @@ hipError_t rfast_launch_resolve(rfast_ctx* c, const uint8_t* active, const int32
 hipError_t rfast_launch_state(rfast_ctx* c, int mode, float gamma);
 hipError_t rfast_launch_rebase(rfast_ctx* c);
 // several rounds of the separable objective on LDS-resident tiles; the rounds' plans are in blk_plan
-bool rfast_block_eligible(const rfast_ctx* c);
+bool rfast_wave_eligible(const rfast_ctx* c);   // the multi-round kernel with one tile per wavefront
+int rfast_wave_lanes(const rfast_ctx* c);       // its lanes per node
+hipError_t rfast_launch_wave(rfast_ctx* c, const RfastBlock& blk);
+bool rfast_block_eligible(const rfast_ctx* c);  // the multi-round kernel with one tile per workgroup
 int rfast_block_lanes(const rfast_ctx* c);  // lanes per node of the multi-round kernel, 0 if no tile fits
 hipError_t rfast_launch_block(rfast_ctx* c, const RfastBlock& blk);
 hipError_t rfast_launch_generate(rfast_ctx* c, uint64_t seed, const float* d_p_active, int d_max, float p_drop, bool events);

@@ -1,0 +1,267 @@
+// Several activation rounds per launch with the tile of one WAVEFRONT resident in LDS.
+//
+// Like rfast_block.hip (every step of Algorithm 1 is elementwise in the coordinate, so a tile of
+// coordinates of every node can stay on chip over many rounds), with one difference that removes
+// every barrier from the round loop: a tile belongs to a single wavefront.  The 64 lanes of a
+// wavefront are split among ALL nodes (16 nodes: 4 lanes per node, 4 coordinates per lane, a tile of
+// 16 coordinates), so every neighbour read of S2a / S2b and every publication of S3 stays within the
+// wavefront, whose LDS operations execute in program order: a round needs no synchronisation with
+// any other wavefront, the wavefronts of a CU drift out of step, and while one waits for its LDS
+// reads another computes.  The plan words of a round are read from global memory one round ahead
+// (the records of all rounds are a few KB that every wavefront of the chip reads, so they stay in the
+// caches), which leaves LDS to the rings and takes the plan reads out of the critical path.
+//
+// The arithmetic is, operation for operation, that of rfast_state_kernel<FUSED> and of
+// rfast_block_kernel: the three paths give the same bits.
+#include "rfast_vec.h"
+
+namespace {
+
+constexpr int kWaveMaxDeg = 4;  // most in-edges of R, in-edges of C and out-edges of C a node may have on this path
+constexpr int kWaveMaxNodes = 32;  // at least 2 lanes (8 coordinates, 32 B of a row) per node
+
+// Orders the LDS and global accesses of the lanes of one wavefront: everything before it is done
+// (in program order of the wavefront) before anything after it starts.
+__device__ inline void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// lw: lanes per node (64 / n, rounded down); kDeg: edge slots per node and kind.  A workgroup is one
+// wavefront with a tile of 4 lw coordinates (measured on 16 nodes x 11.2 M coordinates: 0.345 ms per
+// round, against 0.350 and 0.352 with two and four such wavefronts per workgroup).
+template <int kDeg>
+__global__ void __launch_bounds__(64) rfast_wave_kernel(RfastDev s, RfastBlock blk, int lw) {
+  constexpr int VEC = 4;
+  extern __shared__ float4 lds4[];
+  const int n = s.n, M = s.M;
+  const int64_t p = s.p;
+  const int W1 = n + s.eR + s.eC + 1;  // words of a plan record; the last one is always zero
+  const int lane = threadIdx.x;
+  const int i = lane / lw, ln = lane - i * lw;
+  const int64_t k = (int64_t)blockIdx.x * (4 * lw) + ln * 4;
+  const bool mine = i < n && k < p;
+  float4* v_l = lds4;                          // [n][M][lw]
+  float4* sg_l = v_l + (size_t)n * M * lw;     // [n][M][lw]
+  float* const rt_g = s.rho_tilde + k;                 // + e p: these coordinates of the S4 buffer of edge e
+
+  float4 x, z, g, h, c, m = make_float4(0.f, 0.f, 0.f, 0.f);
+  const bool momentum = s.mom != nullptr;  // the optimizer variant's heavy-ball buffer (uniform)
+  int ce0 = 0, dR = 0, dI = 0, dO = 0;
+  float r_self = 0.f, c_self = 0.f;
+  // the node's edges, in registers for the whole launch: LDS column of the sender's ring, weight,
+  // position of the edge's plan word in a record; a missing edge has weight zero, the node's own
+  // column and the zero word of the record
+  int r_col[kDeg], c_col[kDeg], r_pw[kDeg], c_pw[kDeg], o_pw[kDeg], o_eid[kDeg];
+  float r_w[kDeg], c_w[kDeg], o_w[kDeg];
+#pragma unroll
+  for (int u = 0; u < kDeg; ++u) {
+    r_col[u] = c_col[u] = o_eid[u] = 0;
+    r_pw[u] = c_pw[u] = o_pw[u] = W1 - 1;
+    r_w[u] = c_w[u] = o_w[u] = 0.f;
+  }
+  const int own = i * M * lw + ln;  // this lane's column in the rings of its node
+  int node_pw = W1 - 1;
+  if (mine) {
+    node_pw = i;
+    const int re0 = s.r_ptr[i], o0 = s.co_ptr[i];
+    dR = s.r_ptr[i + 1] - re0;
+    ce0 = s.c_ptr[i];
+    dI = s.c_ptr[i + 1] - ce0;
+    dO = s.co_ptr[i + 1] - o0;
+    r_self = s.r_self[i];
+    c_self = s.c_self[i];
+#pragma unroll
+    for (int u = 0; u < kDeg; ++u) {
+      const bool hr = u < dR, hc = u < dI, ho = u < dO;
+      const int oe = ho ? s.co_eid[o0 + u] : 0;
+      r_col[u] = (hr ? s.r_src[re0 + u] : i) * M * lw + ln;
+      r_w[u] = hr ? s.r_w[re0 + u] : 0.f;
+      r_pw[u] = hr ? n + re0 + u : W1 - 1;
+      c_col[u] = (hc ? s.c_src[ce0 + u] : i) * M * lw + ln;
+      c_w[u] = hc ? s.c_w[ce0 + u] : 0.f;
+      c_pw[u] = hc ? n + s.eR + ce0 + u : W1 - 1;
+      o_w[u] = ho ? s.co_w[o0 + u] : 0.f;
+      o_pw[u] = ho ? n + s.eR + oe : W1 - 1;
+      o_eid[u] = oe;
+    }
+  }
+  // plan words of round 0 (every lane: the lanes of a wavefront without a node read the zero word)
+  int node_w = s.blk_plan[node_pw], r_slot[kDeg], c_pl[kDeg], o_pl[kDeg];
+#pragma unroll
+  for (int u = 0; u < kDeg; ++u) {
+    r_slot[u] = s.blk_plan[r_pw[u]];
+    c_pl[u] = s.blk_plan[c_pw[u]];
+    o_pl[u] = s.blk_plan[o_pw[u]];
+  }
+  if (mine) {
+    const size_t off = (size_t)i * p + k;
+    x = V<VEC>::ld(s.x + off);
+    z = V<VEC>::ld(s.z + off);
+    h = V<VEC>::ld((const float*)s.prob.data0 + off);
+    c = V<VEC>::ld((const float*)s.prob.data1 + off);
+    if (momentum) m = V<VEC>::ld(s.mom + off);
+    // rings: eight slots of both rings (sixteen loads) in flight at a time, then into LDS
+    const float* vg = s.v_ring + (size_t)i * M * p + k;
+    const float* sgg = s.sigma_ring + (size_t)i * M * p + k;
+    for (int m0 = 0; m0 < M; m0 += 8) {
+      float4 tv[8], ts[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (m0 + u < M) {
+          tv[u] = V<VEC>::ld(vg + (size_t)(m0 + u) * p);
+          ts[u] = V<VEC>::ld(sgg + (size_t)(m0 + u) * p);
+        }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (m0 + u < M) {
+          v_l[own + (m0 + u) * lw] = tv[u];
+          sg_l[own + (m0 + u) * lw] = ts[u];
+        }
+    }
+  }
+  // The stored sample of S2b is a function of (x_i, t_i); from here on it lives in registers, and so
+  // does the ring slot of the node's current version (advanced without a division).
+  int slot_cur = 0;
+  if (mine) {
+    const int t0 = node_w & 0x3FFFFFFF;
+    g = diag_sample<VEC>(s, h, c, x, i, t0, k);
+    slot_cur = t0 % M;
+  }
+  wave_sync();
+
+  for (int q = 0; q < blk.rounds; ++q) {
+    // the plan words of the next round, from global memory, used one round from now
+    const int* Pn = s.blk_plan + (size_t)(q + 1 < blk.rounds ? q + 1 : q) * W1;
+    const int n_node = Pn[node_pw];
+    int n_r[kDeg], n_c[kDeg], n_o[kDeg];
+#pragma unroll
+    for (int u = 0; u < kDeg; ++u) {
+      n_r[u] = Pn[r_pw[u]];
+      n_c[u] = Pn[c_pw[u]];
+      n_o[u] = Pn[o_pw[u]];
+    }
+    if (node_w < 0) {  // bit 31: node i is activated in this round (never set in the zero word)
+      const int t_old = node_w & 0x3FFFFFFF;
+      const int slot_new = slot_cur + 1 == M ? 0 : slot_cur + 1;
+      const int leaving = slot_new + 1 == M ? 0 : slot_new + 1;
+      // every ring value of the round in one batch of LDS reads (what a missing or idle edge reads
+      // is a valid address and is not used)
+      float4 nb[kDeg], cur[kDeg], last[kDeg];
+#pragma unroll
+      for (int u = 0; u < kDeg; ++u) nb[u] = v_l[r_col[u] + r_slot[u] * lw];
+#pragma unroll
+      for (int u = 0; u < kDeg; ++u) {
+        const int prev = (c_pl[u] >> 8) & 0xFF;
+        cur[u] = sg_l[c_col[u] + (c_pl[u] & 0xFF) * lw];
+        last[u] = sg_l[c_col[u] + (prev != 0xFF ? prev : 0) * lw];
+      }
+#pragma unroll
+      for (int u = 0; u < kDeg; ++u)  // rare: the version consumed last time has left the sender's ring
+        if ((c_pl[u] & (1 << 16)) && ((c_pl[u] >> 8) & 0xFF) == 0xFF) last[u] = V<VEC>::ld(rt_g + (size_t)(ce0 + u) * p);
+      const float4 sig_cur = sg_l[own + slot_cur * lw];
+      const float4 sig_leaving = sg_l[own + leaving * lw];
+      // S1: local descent; with the optimizer variant along the heavy-ball buffer m <- beta m + z
+      if (momentum) m = fma_s(s.beta, m, z);
+      const float4 v = fma_s(-blk.gamma[q], momentum ? m : z, x);
+      // S2a: pull the stamped neighbour copies and mix with row-stochastic weights
+      float4 x_new = mul_s(r_self, v);
+#pragma unroll
+      for (int u = 0; u < kDeg; ++u)
+        if (u < dR) x_new = fma_s(r_w[u], nb[u], x_new);
+      const float4 g_new = diag_sample<VEC>(s, h, c, x_new, i, t_old + 1, k);
+      // S2b: tracker sum over the in-edges of C; S4: buffer what was consumed
+      float4 z_half = z;
+#pragma unroll
+      for (int u = 0; u < kDeg; ++u)
+        if (c_pl[u] & (1 << 16)) {
+          z_half = track_edge(z_half, c_w[u], cur[u], last[u], ((c_pl[u] >> 8) & 0xFF) != 0xFF);
+          if (c_pl[u] & (1 << 17)) V<VEC>::st(rt_g + (size_t)(ce0 + u) * p, mul_s(c_w[u], cur[u]));
+        }
+      z_half = sub(add(z_half, g_new), g);
+      // S3: publish version t+1 (slots nobody reads in this round); S2c: keep a_ii, push
+      v_l[own + slot_new * lw] = v;
+      if (dO > 0) {
+        sg_l[own + slot_new * lw] = add(sig_cur, z_half);
+        // S4 for receivers that do not do it themselves: version t - D leaves the ring; it sits two
+        // slots ahead of the current one
+#pragma unroll
+        for (int u = 0; u < kDeg; ++u)
+          if (o_pl[u] & (1 << 18)) V<VEC>::st(rt_g + (size_t)o_eid[u] * p, mul_s(o_w[u], sig_leaving));
+      }
+      x = x_new;
+      z = mul_s(c_self, z_half);
+      g = g_new;
+      slot_cur = slot_new;
+    }
+    wave_sync();  // S5: the round is over, its publications are visible to the lanes of this wavefront
+    node_w = n_node;
+#pragma unroll
+    for (int u = 0; u < kDeg; ++u) {
+      r_slot[u] = n_r[u];
+      c_pl[u] = n_c[u];
+      o_pl[u] = n_o[u];
+    }
+  }
+
+  if (mine) {
+    const size_t off = (size_t)i * p + k;
+    V<VEC>::st(s.x + off, x);
+    V<VEC>::st(s.z + off, z);
+    if (momentum) V<VEC>::st(s.mom + off, m);
+    float* vg = s.v_ring + (size_t)i * M * p + k;
+    float* sgg = s.sigma_ring + (size_t)i * M * p + k;
+    for (int m0 = 0; m0 < M; m0 += 8) {
+      float4 tv[8], ts[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (m0 + u < M) {
+          tv[u] = v_l[own + (m0 + u) * lw];
+          ts[u] = sg_l[own + (m0 + u) * lw];
+        }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (m0 + u < M) {
+          V<VEC>::st(vg + (size_t)(m0 + u) * p, tv[u]);
+          V<VEC>::st(sgg + (size_t)(m0 + u) * p, ts[u]);
+        }
+    }
+  }
+}
+
+size_t wave_lds_bytes(const RfastDev& d, int lw) { return (size_t)2 * d.n * d.M * lw * sizeof(float4); }
+
+}  // namespace
+
+// The separable objective, p a multiple of 4, at most 32 nodes with at most kWaveMaxDeg edges of a
+// kind each, and the rings of one wavefront's tile fitting into LDS.
+bool rfast_wave_eligible(const rfast_ctx* c) {
+  const RfastDev& d = c->d;
+  return d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC && (d.p % 4) == 0 && c->max_degree <= kWaveMaxDeg &&
+         d.n <= kWaveMaxNodes && wave_lds_bytes(d, 64 / d.n) <= 156 * 1024;
+}
+
+int rfast_wave_lanes(const rfast_ctx* c) { return 64 / c->d.n; }
+
+template <int kDeg>
+static hipError_t launch_wave(rfast_ctx* c, const RfastBlock& blk) {
+  static bool raised = false;
+  if (!raised) {  // more than 64 KB of dynamic LDS has to be asked for once per kernel
+    const hipError_t e = hipFuncSetAttribute((const void*)rfast_wave_kernel<kDeg>,
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    raised = true;
+  }
+  const RfastDev& d = c->d;
+  const int lw = 64 / d.n;
+  const int64_t tiles = (d.p + 4 * lw - 1) / (4 * lw);
+  if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((rfast_wave_kernel<kDeg>), dim3((unsigned)tiles), dim3(64), wave_lds_bytes(d, lw), c->stream, c->d, blk,
+                     lw);
+  return hipGetLastError();
+}
+
+hipError_t rfast_launch_wave(rfast_ctx* c, const RfastBlock& blk) {
+  return c->max_degree <= 2 ? launch_wave<2>(c, blk) : launch_wave<kWaveMaxDeg>(c, blk);
+}

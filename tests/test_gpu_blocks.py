@@ -68,10 +68,12 @@ def test_uploaded_schedules(seed):
     assert np.array_equal(a.read("T_NODE"), orc.t)
 
 
-# n, d_max, burst, p, lanes per node the library must choose (the widest tile of which two workgroups fit
-# the LDS of a CU, else the widest that fits alone, leaving 512 tiles); every p ends in a ragged tile
-TILES = [(16, 4, 4, 65_540, 16), (16, 5, 4, 49_156, 24), (5, 0, 1, 131_076, 64), (9, 3, 4, 98_308, 32),
-         (9, 3, 1, 98_308, 48), (14, 7, 4, 57_348, 28), (24, 1, 2, 65_540, 16), (16, 4, 4, 4_100, 16)]
+# n, d_max, burst, p, lanes per node the library must choose: up to 32 nodes one tile per wavefront
+# (64 // n lanes per node); beyond, one tile per workgroup (the widest that fits LDS and 1024 lanes and
+# leaves 512 tiles, from 64, 48, 32, 28, 24, 16); every p ends in a ragged tile
+TILES = [(16, 4, 4, 65_540, 4), (16, 5, 4, 49_156, 4), (5, 0, 1, 131_076, 12), (9, 3, 4, 98_308, 7),
+         (14, 7, 4, 57_348, 4), (24, 1, 2, 65_540, 2), (32, 2, 2, 8_196, 2), (16, 4, 4, 4_100, 4),
+         (36, 0, 1, 57_348, 28), (40, 0, 1, 49_156, 24), (48, 1, 1, 8_196, 16)]
 
 
 @pytest.mark.parametrize("n,d_max,burst,p,lanes", TILES)
@@ -145,7 +147,7 @@ def test_odd_p_runs_one_pass_per_round_and_momentum_variant_same_bits():
         g.set_optimizer(0.9, 0.01)
         g.set_gamma_schedule(15, 0.5)
         g.init(None, None)
-    assert rfast_block_info(a.ctx) == 16
+    assert rfast_block_info(a.ctx) == 4
     st, dev = harness.upload_chunk(a, w, 0, 40)
     args = [dev[k] for k in ("active", "delay_R", "delay_C", "drop_R", "drop_C")]
     for g in (a, b):

@@ -30,9 +30,12 @@ __device__ inline void wave_sync() {
 
 // lw: lanes per node (64 / n, rounded down); kDeg: edge slots per node and kind.  A workgroup is one
 // wavefront with a tile of 4 lw coordinates (measured on 16 nodes x 11.2 M coordinates: 0.345 ms per
-// round, against 0.350 and 0.352 with two and four such wavefronts per workgroup).
+// round, against 0.350 and 0.352 with two and four such wavefronts per workgroup).  Occupancy is
+// pinned to two wavefronts per SIMD, which is what the LDS of a CU holds at nine ring slots: once
+// the registers allowed three, the eight wavefronts of a CU were spread unevenly over its SIMDs and
+// the launch took 4 % longer.
 template <int kDeg>
-__global__ void __launch_bounds__(64) rfast_wave_kernel(RfastDev s, RfastBlock blk, int lw) {
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) rfast_wave_kernel(RfastDev s, RfastBlock blk, int lw) {
   constexpr int VEC = 4;
   extern __shared__ float4 lds4[];
   const int n = s.n, M = s.M;
@@ -44,7 +47,13 @@ __global__ void __launch_bounds__(64) rfast_wave_kernel(RfastDev s, RfastBlock b
   const bool mine = i < n && k < p;
   float4* v_l = lds4;                          // [n][M][lw]
   float4* sg_l = v_l + (size_t)n * M * lw;     // [n][M][lw]
-  float* const rt_g = s.rho_tilde + k;                 // + e p: these coordinates of the S4 buffer of edge e
+  float* const rt_g = s.rho_tilde + k;         // + e p: these coordinates of the S4 buffer of edge e
+  // LDS addresses are byte offsets: column of the lane in a node's ring + slot * bytes per slot, one
+  // 24-bit multiply-add each
+  const unsigned slot_bytes = (unsigned)lw * sizeof(float4);
+  auto at = [&](float4* ring, unsigned column, int slot) -> float4& {
+    return *reinterpret_cast<float4*>(reinterpret_cast<char*>(ring) + (__umul24((unsigned)slot, slot_bytes) + column));
+  };
 
   float4 x, z, g, h, c, m = make_float4(0.f, 0.f, 0.f, 0.f);
   const bool momentum = s.mom != nullptr;  // the optimizer variant's heavy-ball buffer (uniform)
@@ -53,15 +62,17 @@ __global__ void __launch_bounds__(64) rfast_wave_kernel(RfastDev s, RfastBlock b
   // the node's edges, in registers for the whole launch: LDS column of the sender's ring, weight,
   // position of the edge's plan word in a record; a missing edge has weight zero, the node's own
   // column and the zero word of the record
-  int r_col[kDeg], c_col[kDeg], r_pw[kDeg], c_pw[kDeg], o_pw[kDeg], o_eid[kDeg];
+  unsigned r_col[kDeg], c_col[kDeg];
+  int r_pw[kDeg], c_pw[kDeg], o_pw[kDeg], o_eid[kDeg];
   float r_w[kDeg], c_w[kDeg], o_w[kDeg];
 #pragma unroll
   for (int u = 0; u < kDeg; ++u) {
-    r_col[u] = c_col[u] = o_eid[u] = 0;
+    r_col[u] = c_col[u] = 0;
+    o_eid[u] = 0;
     r_pw[u] = c_pw[u] = o_pw[u] = W1 - 1;
     r_w[u] = c_w[u] = o_w[u] = 0.f;
   }
-  const int own = i * M * lw + ln;  // this lane's column in the rings of its node
+  const unsigned own = (unsigned)(i * M * lw + ln) * sizeof(float4);  // this lane's column in the rings of its node
   int node_pw = W1 - 1;
   if (mine) {
     node_pw = i;
@@ -76,10 +87,10 @@ __global__ void __launch_bounds__(64) rfast_wave_kernel(RfastDev s, RfastBlock b
     for (int u = 0; u < kDeg; ++u) {
       const bool hr = u < dR, hc = u < dI, ho = u < dO;
       const int oe = ho ? s.co_eid[o0 + u] : 0;
-      r_col[u] = (hr ? s.r_src[re0 + u] : i) * M * lw + ln;
+      r_col[u] = (unsigned)((hr ? s.r_src[re0 + u] : i) * M * lw + ln) * sizeof(float4);
       r_w[u] = hr ? s.r_w[re0 + u] : 0.f;
       r_pw[u] = hr ? n + re0 + u : W1 - 1;
-      c_col[u] = (hc ? s.c_src[ce0 + u] : i) * M * lw + ln;
+      c_col[u] = (unsigned)((hc ? s.c_src[ce0 + u] : i) * M * lw + ln) * sizeof(float4);
       c_w[u] = hc ? s.c_w[ce0 + u] : 0.f;
       c_pw[u] = hc ? n + s.eR + ce0 + u : W1 - 1;
       o_w[u] = ho ? s.co_w[o0 + u] : 0.f;
@@ -116,8 +127,8 @@ __global__ void __launch_bounds__(64) rfast_wave_kernel(RfastDev s, RfastBlock b
 #pragma unroll
       for (int u = 0; u < 8; ++u)
         if (m0 + u < M) {
-          v_l[own + (m0 + u) * lw] = tv[u];
-          sg_l[own + (m0 + u) * lw] = ts[u];
+          at(v_l, own, m0 + u) = tv[u];
+          at(sg_l, own, m0 + u) = ts[u];
         }
     }
   }
@@ -150,18 +161,18 @@ __global__ void __launch_bounds__(64) rfast_wave_kernel(RfastDev s, RfastBlock b
       // is a valid address and is not used)
       float4 nb[kDeg], cur[kDeg], last[kDeg];
 #pragma unroll
-      for (int u = 0; u < kDeg; ++u) nb[u] = v_l[r_col[u] + r_slot[u] * lw];
+      for (int u = 0; u < kDeg; ++u) nb[u] = at(v_l, r_col[u], r_slot[u]);
 #pragma unroll
       for (int u = 0; u < kDeg; ++u) {
         const int prev = (c_pl[u] >> 8) & 0xFF;
-        cur[u] = sg_l[c_col[u] + (c_pl[u] & 0xFF) * lw];
-        last[u] = sg_l[c_col[u] + (prev != 0xFF ? prev : 0) * lw];
+        cur[u] = at(sg_l, c_col[u], c_pl[u] & 0xFF);
+        last[u] = at(sg_l, c_col[u], prev != 0xFF ? prev : 0);
       }
 #pragma unroll
       for (int u = 0; u < kDeg; ++u)  // rare: the version consumed last time has left the sender's ring
         if ((c_pl[u] & (1 << 16)) && ((c_pl[u] >> 8) & 0xFF) == 0xFF) last[u] = V<VEC>::ld(rt_g + (size_t)(ce0 + u) * p);
-      const float4 sig_cur = sg_l[own + slot_cur * lw];
-      const float4 sig_leaving = sg_l[own + leaving * lw];
+      const float4 sig_cur = at(sg_l, own, slot_cur);
+      const float4 sig_leaving = at(sg_l, own, leaving);
       // S1: local descent; with the optimizer variant along the heavy-ball buffer m <- beta m + z
       if (momentum) m = fma_s(s.beta, m, z);
       const float4 v = fma_s(-blk.gamma[q], momentum ? m : z, x);
@@ -181,9 +192,9 @@ __global__ void __launch_bounds__(64) rfast_wave_kernel(RfastDev s, RfastBlock b
         }
       z_half = sub(add(z_half, g_new), g);
       // S3: publish version t+1 (slots nobody reads in this round); S2c: keep a_ii, push
-      v_l[own + slot_new * lw] = v;
+      at(v_l, own, slot_new) = v;
       if (dO > 0) {
-        sg_l[own + slot_new * lw] = add(sig_cur, z_half);
+        at(sg_l, own, slot_new) = add(sig_cur, z_half);
         // S4 for receivers that do not do it themselves: version t - D leaves the ring; it sits two
         // slots ahead of the current one
 #pragma unroll
@@ -217,8 +228,8 @@ __global__ void __launch_bounds__(64) rfast_wave_kernel(RfastDev s, RfastBlock b
 #pragma unroll
       for (int u = 0; u < 8; ++u)
         if (m0 + u < M) {
-          tv[u] = v_l[own + (m0 + u) * lw];
-          ts[u] = sg_l[own + (m0 + u) * lw];
+          tv[u] = at(v_l, own, m0 + u);
+          ts[u] = at(sg_l, own, m0 + u);
         }
 #pragma unroll
       for (int u = 0; u < 8; ++u)

@@ -231,11 +231,11 @@ def main():
     avg_ms = ms_state / launches
     # several rounds per launch with the state resident in LDS (the default where it applies)
     blocked = not args.sync and w.objective == "diag_quadratic" and 0 < n_state < K
-    lanes = rf.rfast_block_info(gpu.ctx) if blocked else 0
+    lanes, per_wave = rf.rfast_block_info(gpu.ctx, with_kind=True) if blocked else (0, False)
     if args.sync:
         kernel = "rfast_sync_descent+step"
     elif blocked:
-        kernel = f"rfast_block_kernel<{lanes} lanes per node>"
+        kernel = f"rfast_wave_kernel<{lanes} lanes per node>" if per_wave else f"rfast_block_kernel<{lanes} lanes per node>"
     else:
         kernel = "rfast_state_kernel" + ("<FUSED>" if w.objective == "diag_quadratic" else "<MIX>+<TRACK>")
     headline = not (args.p or args.sync or variant or args.generated)
@@ -259,7 +259,7 @@ def main():
                      "layout_bytes_per_launch": bytes_layout / launches,
                      "achieved_layout": achieved * bytes_layout / bytes_prof if bytes_prof else 0.0,
                      "frac_layout": achieved * bytes_layout / bytes_prof / HBM_PEAK_GBS if bytes_prof else 0.0,
-                     "traffic": measured_traffic(w.name, "block" if blocked else "state") if headline else None},
+                     "traffic": measured_traffic(w.name, ("wave" if per_wave else "block") if blocked else "state") if headline else None},
         "kernel_ms": {"state": ms_state, "gradient": ms_grad, "resolver": ms_res,
                       "launches": {"state": n_state, "gradient": n_grad, "resolver": n_res}},
         "host_data_generation_s": gen_s,
@@ -271,7 +271,7 @@ def main():
         out["roofline"]["rounds_per_launch"] = K / launches
         out["roofline"]["note"] = ("state resident in LDS over rounds_per_launch rounds: HBM moves every ring slot once "
                                    "per launch (traffic), not the per-round words of the algorithmic figure")
-        per_round = profile_figure(w.name, "block", "valu_wave_instructions_per_round") if headline else None
+        per_round = profile_figure(w.name, "wave" if per_wave else "block", "valu_wave_instructions_per_round") if headline else None
         if per_round:
             # the bound that holds: vector instructions issued (64 lanes per wavefront instruction)
             rate = per_round * 64.0 * K / (ms_state * 1e-3)

@@ -226,19 +226,22 @@ int rfast_use_graphs(rfast_ctx* ctx, int32_t on);
 
 /* on != 0 (the default): rfast_run and rfast_run_generated advance up to 128 rounds with one
  * launch where that is possible and pays -- the separable objective (diagonal quadratic, with or
- * without the optimizer variant), p a multiple of 4, no node with more than 4 in-edges of R, in-edges of C or
- * out-edges of C, at least 64 coordinates of every node's two rings fitting into the 160 KB of LDS
- * of a CU (n * (D+2) * 512 B + nnzC_off * 256 B + plans), and at least 2 rounds to run before the
- * next multiple of the rebase interval (8 where n * p * 4 > 8 MB: a launch moves every ring slot
- * in and out once, which a large state earns back only over that many rounds); rounds that do not
- * qualify run one pass each.  Every step of a round is elementwise in the coordinate, so a tile of
- * coordinates can stay in LDS over several rounds; the results are the same bits as round-by-round
- * execution.  on == 0: always one kernel pass per round.  on == 2: as the default, but 2 rounds
- * are enough at any size (for measurements). */
+ * without the optimizer variant), p a multiple of 4, at most 64 nodes, no node with more than 4
+ * in-edges of R, in-edges of C or out-edges of C, a tile of coordinates of every node's two rings
+ * fitting into the 160 KB of LDS of a CU (up to 32 nodes: 64 / n lanes of one wavefront per node, 4
+ * coordinates per lane, n * (D+2) * (64 / n) * 32 B; beyond: at least 16 lanes of one workgroup per
+ * node, n * (D+2) * 512 B + plans), and at least 2 rounds to run before the next multiple of the
+ * rebase interval (8 where n * p * 4 > 8 MB: a launch moves every ring slot in and out once, which a
+ * large state earns back only over that many rounds); rounds that do not qualify run one pass
+ * each.  Every step of a round is elementwise in the coordinate, so a tile of coordinates can stay
+ * in LDS over several rounds; the results are the same bits as round-by-round execution.
+ * on == 0: always one kernel pass per round.  on == 2: as the default, but 2 rounds are enough at
+ * any size (for measurements). */
 int rfast_use_blocks(rfast_ctx* ctx, int32_t on);
 /* *lanes_per_node = 0 if a call of rfast_run for several rounds would now run one pass per round,
- * else the number of lanes per node of the multi-round kernel (its tile is 4 * lanes coordinates). */
-int rfast_block_info(rfast_ctx* ctx, int32_t* lanes_per_node);
+ * else the number of lanes per node of the multi-round kernel (its tile is 4 * lanes coordinates);
+ * *tile_per_wavefront (may be NULL) = 1 if a tile belongs to one wavefront, 0 if to a workgroup. */
+int rfast_block_info(rfast_ctx* ctx, int32_t* lanes_per_node, int32_t* tile_per_wavefront);
 
 /* One step of the synchronous push-pull recursion the method is developed from
  * (eq. (2) of the paper), on the same x, z and stored gradient samples:

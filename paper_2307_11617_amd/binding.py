@@ -65,7 +65,7 @@ def lib():
     L.rfast_run_events.restype = C.c_int
     L.rfast_run_events.argtypes = [vp, i32, C.c_uint64, vp, i32, C.c_float, C.c_float]
     L.rfast_block_info.restype = C.c_int
-    L.rfast_block_info.argtypes = [vp, C.POINTER(C.c_int32)]
+    L.rfast_block_info.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     L.rfast_use_blocks.restype = C.c_int
     L.rfast_use_blocks.argtypes = [vp, i32]
     L.rfast_use_graphs.restype = C.c_int
@@ -168,10 +168,12 @@ def rfast_run_events(ctx, iterations, seed, weights, max_delay, p_drop, gamma):
                                 gamma), ctx)
 
 
-def rfast_block_info(ctx):
-    lanes = C.c_int32(0)
-    _chk(lib().rfast_block_info(ctx, C.byref(lanes)), ctx)
-    return lanes.value
+def rfast_block_info(ctx, with_kind=False):
+    """Lanes per node of the multi-round kernel (0: one pass per round); with_kind: also whether a
+    tile belongs to one wavefront (True) or to a workgroup."""
+    lanes, wave = C.c_int32(0), C.c_int32(0)
+    _chk(lib().rfast_block_info(ctx, C.byref(lanes), C.byref(wave)), ctx)
+    return (lanes.value, bool(wave.value)) if with_kind else lanes.value
 
 
 def rfast_use_blocks(ctx, on=True):

@@ -607,9 +607,11 @@ static int run_block(rfast_ctx* c, int32_t len, const uint8_t* d_active, const i
   return RFAST_OK;
 }
 
-int rfast_block_info(rfast_ctx* c, int32_t* lanes_per_node) {
+int rfast_block_info(rfast_ctx* c, int32_t* lanes_per_node, int32_t* tile_per_wavefront) {
   if (!c || !lanes_per_node) return RFAST_EINVAL;
-  *lanes_per_node = block_length(c, kBlockRounds) > 0 ? (rfast_wave_eligible(c) ? rfast_wave_lanes(c) : rfast_block_lanes(c)) : 0;
+  const bool taken = block_length(c, kBlockRounds) > 0, wave = rfast_wave_eligible(c);
+  *lanes_per_node = taken ? (wave ? rfast_wave_lanes(c) : rfast_block_lanes(c)) : 0;
+  if (tile_per_wavefront) *tile_per_wavefront = taken && wave ? 1 : 0;
   return RFAST_OK;
 }
 

@@ -19,6 +19,8 @@ namespace {
 
 constexpr int kWaveMaxDeg = 4;  // most in-edges of R, in-edges of C and out-edges of C a node may have on this path
 constexpr int kWaveMaxNodes = 32;  // at least 2 lanes (8 coordinates, 32 B of a row) per node
+constexpr unsigned kXcds = 8;      // accelerator dies; consecutive workgroups go round them
+constexpr unsigned kTileRun = 4;   // neighbouring tiles that one XCD takes in a row
 
 // Orders the LDS and global accesses of the lanes of one wavefront: everything before it is done
 // (in program order of the wavefront) before anything after it starts.
@@ -43,7 +45,12 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int W1 = n + s.eR + s.eC + 1;  // words of a plan record; the last one is always zero
   const int lane = threadIdx.x;
   const int i = lane / lw, ln = lane - i * lw;
-  const int64_t k = (int64_t)blockIdx.x * (4 * lw) + ln * 4;
+  // Workgroup b runs on XCD b mod 8, each with an L2 of its own.  A tile row of 4 lw coordinates can be
+  // half a cache line (16 nodes: 64 B), so neighbouring tiles go to the same XCD, one right after the
+  // other: the second finds the line in that L2 instead of fetching it from HBM again.
+  const unsigned xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+  const int64_t tile = ((int64_t)(slot / kTileRun) * kXcds + xcd) * kTileRun + slot % kTileRun;
+  const int64_t k = tile * (4 * lw) + ln * 4;
   const bool mine = i < n && k < p;
   float4* v_l = lds4;                          // [n][M][lw]
   float4* sg_l = v_l + (size_t)n * M * lw;     // [n][M][lw]
@@ -266,7 +273,8 @@ static hipError_t launch_wave(rfast_ctx* c, const RfastBlock& blk) {
   }
   const RfastDev& d = c->d;
   const int lw = 64 / d.n;
-  const int64_t tiles = (d.p + 4 * lw - 1) / (4 * lw);
+  const int64_t run = (int64_t)kXcds * kTileRun;
+  const int64_t tiles = ((d.p + 4 * lw - 1) / (4 * lw) + run - 1) / run * run;  // whole runs: a tile past the end has no lanes
   if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL((rfast_wave_kernel<kDeg>), dim3((unsigned)tiles), dim3(64), wave_lds_bytes(d, lw), c->stream, c->d, blk,
                      lw);

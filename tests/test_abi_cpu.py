@@ -138,7 +138,7 @@ def test_null_context_calls_fail_cleanly():
     assert L.rfast_run_events(None, 1, 0, None, 0, 0.0, 0.1) == -1
     assert L.rfast_set_rebase_interval(None, 10) == -1
     assert L.rfast_use_blocks(None, 1) == -1
-    assert L.rfast_block_info(None, None) == -1
+    assert L.rfast_block_info(None, None, None) == -1
     assert L.rfast_write_state(None, 0, None, 0) == -1
     L.rfast_destroy(None)
 

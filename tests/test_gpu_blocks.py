@@ -85,7 +85,7 @@ def test_tile_widths(n, d_max, burst, p, lanes):
     w = configs.Workload(f"tiles_{lanes}", n, p, R, C, d_max + burst - 1, burst, 0.02, 0, "diag_quadratic",
                          problems.diag_quadratic(n, p, n), sched, 0.1, 90 + n, 1e-4)
     a, b = _pair(w)
-    assert rfast_block_info(a.ctx) == lanes and rfast_block_info(b.ctx) == 0
+    assert rfast_block_info(a.ctx, with_kind=True) == (lanes, n <= 32) and rfast_block_info(b.ctx) == 0
     for g in (a, b):
         g.init(None, None)
     st, dev = harness.upload_chunk(a, w, 0, 40)

@@ -73,6 +73,7 @@ def test_uploaded_schedules(seed):
 # leaves 512 tiles, from 64, 48, 32, 28, 24, 16); every p ends in a ragged tile
 TILES = [(16, 4, 4, 65_540, 4), (16, 5, 4, 49_156, 4), (5, 0, 1, 131_076, 12), (9, 3, 4, 98_308, 7),
          (14, 7, 4, 57_348, 4), (24, 1, 2, 65_540, 2), (32, 2, 2, 8_196, 2), (16, 4, 4, 4_100, 4),
+         (1, 0, 1, 4_100, 64), (2, 1, 1, 4_100, 32), (3, 1, 2, 4_100, 21),
          (36, 0, 1, 57_348, 28), (40, 0, 1, 49_156, 24), (48, 1, 1, 8_196, 16)]
 
 

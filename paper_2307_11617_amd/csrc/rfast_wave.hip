@@ -30,13 +30,15 @@ __device__ inline void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// lw: lanes per node (64 / n, rounded down); kDeg: edge slots per node and kind.  A workgroup is one
+// lw: lanes per node (64 / n, rounded down); kDeg: edge slots per node and kind; MOM: the optimizer
+// variant's heavy-ball buffer is in use (a template flag, so that the plain method carries neither
+// the registers nor the copies at the join).  A workgroup is one
 // wavefront with a tile of 4 lw coordinates (measured on 16 nodes x 11.2 M coordinates: 0.345 ms per
 // round, against 0.350 and 0.352 with two and four such wavefronts per workgroup).  Occupancy is
 // pinned to two wavefronts per SIMD, which is what the LDS of a CU holds at nine ring slots: once
 // the registers allowed three, the eight wavefronts of a CU were spread unevenly over its SIMDs and
 // the launch took 4 % longer.
-template <int kDeg>
+template <int kDeg, bool MOM>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) rfast_wave_kernel(RfastDev s, RfastBlock blk, int lw) {
   constexpr int VEC = 4;
   extern __shared__ float4 lds4[];
@@ -63,7 +65,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   };
 
   float4 x, z, g, h, c, m = make_float4(0.f, 0.f, 0.f, 0.f);
-  const bool momentum = s.mom != nullptr;  // the optimizer variant's heavy-ball buffer (uniform)
+  constexpr bool momentum = MOM;  // the optimizer variant's heavy-ball buffer is in use
   int ce0 = 0, dR = 0, dI = 0, dO = 0;
   float r_self = 0.f, c_self = 0.f;
   // the node's edges, in registers for the whole launch: LDS column of the sender's ring, weight,
@@ -262,11 +264,11 @@ bool rfast_wave_eligible(const rfast_ctx* c) {
 
 int rfast_wave_lanes(const rfast_ctx* c) { return 64 / c->d.n; }
 
-template <int kDeg>
+template <int kDeg, bool MOM>
 static hipError_t launch_wave(rfast_ctx* c, const RfastBlock& blk) {
   static bool raised = false;
   if (!raised) {  // more than 64 KB of dynamic LDS has to be asked for once per kernel
-    const hipError_t e = hipFuncSetAttribute((const void*)rfast_wave_kernel<kDeg>,
+    const hipError_t e = hipFuncSetAttribute((const void*)rfast_wave_kernel<kDeg, MOM>,
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     raised = true;
@@ -276,11 +278,12 @@ static hipError_t launch_wave(rfast_ctx* c, const RfastBlock& blk) {
   const int64_t run = (int64_t)kXcds * kTileRun;
   const int64_t tiles = ((d.p + 4 * lw - 1) / (4 * lw) + run - 1) / run * run;  // whole runs: a tile past the end has no lanes
   if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((rfast_wave_kernel<kDeg>), dim3((unsigned)tiles), dim3(64), wave_lds_bytes(d, lw), c->stream, c->d, blk,
+  hipLaunchKernelGGL((rfast_wave_kernel<kDeg, MOM>), dim3((unsigned)tiles), dim3(64), wave_lds_bytes(d, lw), c->stream, c->d, blk,
                      lw);
   return hipGetLastError();
 }
 
 hipError_t rfast_launch_wave(rfast_ctx* c, const RfastBlock& blk) {
-  return c->max_degree <= 2 ? launch_wave<2>(c, blk) : launch_wave<kWaveMaxDeg>(c, blk);
+  if (c->d.mom) return c->max_degree <= 2 ? launch_wave<2, true>(c, blk) : launch_wave<kWaveMaxDeg, true>(c, blk);
+  return c->max_degree <= 2 ? launch_wave<2, false>(c, blk) : launch_wave<kWaveMaxDeg, false>(c, blk);
 }

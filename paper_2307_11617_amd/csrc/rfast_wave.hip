@@ -72,19 +72,21 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // position of the edge's plan word in a record; a missing edge has weight zero, the node's own
   // column and the zero word of the record
   unsigned r_col[kDeg], c_col[kDeg];
-  int r_pw[kDeg], c_pw[kDeg], o_pw[kDeg], o_eid[kDeg];
+  // positions of plan words as unsigned byte offsets: a 32-bit offset from a uniform base, no 64-bit address arithmetic
+  unsigned r_pw[kDeg], c_pw[kDeg], o_pw[kDeg];
+  int o_eid[kDeg];
   float r_w[kDeg], c_w[kDeg], o_w[kDeg];
 #pragma unroll
   for (int u = 0; u < kDeg; ++u) {
     r_col[u] = c_col[u] = 0;
     o_eid[u] = 0;
-    r_pw[u] = c_pw[u] = o_pw[u] = W1 - 1;
+    r_pw[u] = c_pw[u] = o_pw[u] = 4u * (W1 - 1);
     r_w[u] = c_w[u] = o_w[u] = 0.f;
   }
   const unsigned own = (unsigned)(i * M * lw + ln) * sizeof(float4);  // this lane's column in the rings of its node
-  int node_pw = W1 - 1;
+  unsigned node_pw = 4u * (W1 - 1);
   if (mine) {
-    node_pw = i;
+    node_pw = 4u * i;
     const int re0 = s.r_ptr[i], o0 = s.co_ptr[i];
     dR = s.r_ptr[i + 1] - re0;
     ce0 = s.c_ptr[i];
@@ -98,22 +100,30 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       const int oe = ho ? s.co_eid[o0 + u] : 0;
       r_col[u] = (unsigned)((hr ? s.r_src[re0 + u] : i) * M * lw + ln) * sizeof(float4);
       r_w[u] = hr ? s.r_w[re0 + u] : 0.f;
-      r_pw[u] = hr ? n + re0 + u : W1 - 1;
+      r_pw[u] = 4u * (hr ? n + re0 + u : W1 - 1);
       c_col[u] = (unsigned)((hc ? s.c_src[ce0 + u] : i) * M * lw + ln) * sizeof(float4);
       c_w[u] = hc ? s.c_w[ce0 + u] : 0.f;
-      c_pw[u] = hc ? n + s.eR + ce0 + u : W1 - 1;
+      c_pw[u] = 4u * (hc ? n + s.eR + ce0 + u : W1 - 1);
       o_w[u] = ho ? s.co_w[o0 + u] : 0.f;
-      o_pw[u] = ho ? n + s.eR + oe : W1 - 1;
+      o_pw[u] = 4u * (ho ? n + s.eR + oe : W1 - 1);
       o_eid[u] = oe;
     }
   }
   // plan words of round 0 (every lane: the lanes of a wavefront without a node read the zero word)
-  int node_w = s.blk_plan[node_pw], r_slot[kDeg], c_pl[kDeg], o_pl[kDeg];
+  // Plan words are read through a buffer descriptor over the records of this launch: the address is
+  // descriptor + uniform record offset + 32-bit lane offset, formed by the load itself (no 64-bit
+  // address arithmetic per word), and a read past the records returns zero instead of faulting.
+  const __amdgpu_buffer_rsrc_t plans = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<int*>(s.blk_plan), 0, blk.rounds * W1 * (int)sizeof(int), 0x00020000);
+  auto word = [&](int round, unsigned byte_offset) {
+    return __builtin_amdgcn_raw_buffer_load_b32(plans, byte_offset, round * W1 * (int)sizeof(int), 0);
+  };
+  int node_w = word(0, node_pw), r_slot[kDeg], c_pl[kDeg], o_pl[kDeg];
 #pragma unroll
   for (int u = 0; u < kDeg; ++u) {
-    r_slot[u] = s.blk_plan[r_pw[u]];
-    c_pl[u] = s.blk_plan[c_pw[u]];
-    o_pl[u] = s.blk_plan[o_pw[u]];
+    r_slot[u] = word(0, r_pw[u]);
+    c_pl[u] = word(0, c_pw[u]);
+    o_pl[u] = word(0, o_pw[u]);
   }
   if (mine) {
     const size_t off = (size_t)i * p + k;
@@ -153,14 +163,14 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
   for (int q = 0; q < blk.rounds; ++q) {
     // the plan words of the next round, from global memory, used one round from now
-    const int* Pn = s.blk_plan + (size_t)(q + 1 < blk.rounds ? q + 1 : q) * W1;
-    const int n_node = Pn[node_pw];
+    const int qn = q + 1 < blk.rounds ? q + 1 : q;
+    const int n_node = word(qn, node_pw);
     int n_r[kDeg], n_c[kDeg], n_o[kDeg];
 #pragma unroll
     for (int u = 0; u < kDeg; ++u) {
-      n_r[u] = Pn[r_pw[u]];
-      n_c[u] = Pn[c_pw[u]];
-      n_o[u] = Pn[o_pw[u]];
+      n_r[u] = word(qn, r_pw[u]);
+      n_c[u] = word(qn, c_pw[u]);
+      n_o[u] = word(qn, o_pw[u]);
     }
     if (node_w < 0) {  // bit 31: node i is activated in this round (never set in the zero word)
       const int t_old = node_w & 0x3FFFFFFF;

@@ -552,7 +552,8 @@ int rfast_round(rfast_ctx* c, const uint8_t* d_active, const int32_t* d_delay_R,
 
 // How many of the next `rounds` rounds one launch of the LDS-resident kernel should take (0: run
 // the next round as one pass).  A launch holds no rebase, so it must end at the latest on the next
-// multiple of the rebase interval; and it reads and writes every ring slot once, which a large
+// multiple of the rebase interval, and it runs with one step size, so it must end with the current
+// step of the step-size schedule; and it reads and writes every ring slot once, which a large
 // state earns back only over enough rounds.
 static int32_t block_length(const rfast_ctx* c, int32_t rounds) {
   if (!c->use_blocks || !(rfast_wave_eligible(c) || rfast_block_eligible(c))) return 0;
@@ -560,6 +561,10 @@ static int32_t block_length(const rfast_ctx* c, int32_t rounds) {
   if (c->rebase_interval > 0) {
     const int64_t to_boundary = c->rebase_interval - c->host_round % c->rebase_interval;
     if (to_boundary < len) len = (int32_t)to_boundary;
+  }
+  if (c->gamma_step > 0) {  // one step size per launch
+    const int64_t to_decay = c->gamma_step - c->host_round % c->gamma_step;
+    if (to_decay < len) len = (int32_t)to_decay;
   }
   const bool large = (double)c->d.n * (double)c->d.p * 4.0 > 8.0e6;
   return len >= (large && c->use_blocks != 2 ? kBlockMinRoundsLarge : 2) ? len : 0;
@@ -581,8 +586,8 @@ static int run_block(rfast_ctx* c, int32_t len, const uint8_t* d_active, const i
     d.blk_plan = c->blk_plan_base;
     e = rfast_launch_resolve(c, d_active, d_delay_R, d_delay_C, d_drop_R, d_drop_C, len);
   }
+  blk.gamma = gamma_now(c, gamma);
   for (int32_t q = 0; q < len && e == hipSuccess; ++q) {
-    blk.gamma[q] = gamma_now(c, gamma);
     if (generated) {  // the generator draws one round at a time
       d.blk_plan = c->blk_plan_base + (size_t)q * PL;
       e = rfast_launch_generate(c, seed, d_p_active, max_delay, p_drop, false);

@@ -139,7 +139,7 @@ constexpr int kBlockRounds = 128;
 constexpr int kPlanChunk = 16;
 constexpr int kBlockMinRoundsLarge = 8;
 struct RfastBlock {
-  float gamma[kBlockRounds];  // step size of each round
+  float gamma;                // step size of its rounds (a launch does not straddle a decay step)
   int32_t rounds;             // 1 .. kBlockRounds
 };
 

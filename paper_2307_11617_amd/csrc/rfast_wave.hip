@@ -194,7 +194,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       const float4 sig_leaving = at(sg_l, own, leaving);
       // S1: local descent; with the optimizer variant along the heavy-ball buffer m <- beta m + z
       if (momentum) m = fma_s(s.beta, m, z);
-      const float4 v = fma_s(-blk.gamma[q], momentum ? m : z, x);
+      const float4 v = fma_s(-blk.gamma, momentum ? m : z, x);
       // S2a: pull the stamped neighbour copies and mix with row-stochastic weights
       float4 x_new = mul_s(r_self, v);
 #pragma unroll

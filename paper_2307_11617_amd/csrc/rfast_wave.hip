@@ -162,23 +162,13 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   wave_sync();
 
   for (int q = 0; q < blk.rounds; ++q) {
-    // the plan words of the next round, from global memory, used one round from now
-    const int qn = q + 1 < blk.rounds ? q + 1 : q;
-    const int n_node = word(qn, node_pw);
-    int n_r[kDeg], n_c[kDeg], n_o[kDeg];
-#pragma unroll
-    for (int u = 0; u < kDeg; ++u) {
-      n_r[u] = word(qn, r_pw[u]);
-      n_c[u] = word(qn, c_pw[u]);
-      n_o[u] = word(qn, o_pw[u]);
-    }
-    if (node_w < 0) {  // bit 31: node i is activated in this round (never set in the zero word)
-      const int t_old = node_w & 0x3FFFFFFF;
-      const int slot_new = slot_cur + 1 == M ? 0 : slot_cur + 1;
-      const int leaving = slot_new + 1 == M ? 0 : slot_new + 1;
+    const bool active = node_w < 0;  // bit 31: node i is activated in this round (never set in the zero word)
+    const int slot_new = slot_cur + 1 == M ? 0 : slot_cur + 1;
+    const int leaving = slot_new + 1 == M ? 0 : slot_new + 1;
+    float4 nb[kDeg], cur[kDeg], last[kDeg], sig_cur, sig_leaving;
+    if (active) {
       // every ring value of the round in one batch of LDS reads (what a missing or idle edge reads
       // is a valid address and is not used)
-      float4 nb[kDeg], cur[kDeg], last[kDeg];
 #pragma unroll
       for (int u = 0; u < kDeg; ++u) nb[u] = at(v_l, r_col[u], r_slot[u]);
 #pragma unroll
@@ -190,8 +180,23 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
       for (int u = 0; u < kDeg; ++u)  // rare: the version consumed last time has left the sender's ring
         if ((c_pl[u] & (1 << 16)) && ((c_pl[u] >> 8) & 0xFF) == 0xFF) last[u] = V<VEC>::ld(rt_g + (size_t)(ce0 + u) * p);
-      const float4 sig_cur = at(sg_l, own, slot_cur);
-      const float4 sig_leaving = at(sg_l, own, leaving);
+      sig_cur = at(sg_l, own, slot_cur);
+      sig_leaving = at(sg_l, own, leaving);
+    }
+    // The plan words of the next round, from global memory, used one round from now.  Issued after the
+    // loads of the S4 buffers above: the vector memory counter is in order, so a wait for those does
+    // not wait for these.
+    const int qn = q + 1 < blk.rounds ? q + 1 : q;
+    const int n_node = word(qn, node_pw);
+    int n_r[kDeg], n_c[kDeg], n_o[kDeg];
+#pragma unroll
+    for (int u = 0; u < kDeg; ++u) {
+      n_r[u] = word(qn, r_pw[u]);
+      n_c[u] = word(qn, c_pw[u]);
+      n_o[u] = word(qn, o_pw[u]);
+    }
+    if (active) {
+      const int t_old = node_w & 0x3FFFFFFF;
       // S1: local descent; with the optimizer variant along the heavy-ball buffer m <- beta m + z
       if (momentum) m = fma_s(s.beta, m, z);
       const float4 v = fma_s(-blk.gamma, momentum ? m : z, x);

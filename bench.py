@@ -230,7 +230,8 @@ def main():
     launches = max(n_state, 1)
     avg_ms = ms_state / launches
     # several rounds per launch with the state resident in LDS (the default where it applies)
-    blocked = not args.sync and w.objective == "diag_quadratic" and 0 < n_state < K
+    # (graph replays, which the timed pass of --graphs uses, are one pass per round; the event-timed pass cannot replay)
+    blocked = not args.sync and not args.graphs and w.objective == "diag_quadratic" and 0 < n_state < K
     lanes, per_wave = rf.rfast_block_info(gpu.ctx, with_kind=True) if blocked else (0, False)
     if args.sync:
         kernel = "rfast_sync_descent+step"

@@ -234,7 +234,7 @@ def main():
     blocked = not args.sync and not args.graphs and w.objective == "diag_quadratic" and 0 < n_state < K
     lanes, per_wave = rf.rfast_block_info(gpu.ctx, with_kind=True) if blocked else (0, False)
     if args.sync:
-        kernel = "rfast_sync_descent+step"
+        kernel = "rfast_sync_wave_kernel (several steps per launch, state in registers and LDS)" if 0 < n_state < K else "rfast_sync_descent+step"
     elif blocked:
         kernel = f"rfast_wave_kernel<{lanes} lanes per node>" if per_wave else f"rfast_block_kernel<{lanes} lanes per node>"
     else:

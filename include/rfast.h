@@ -251,7 +251,10 @@ int rfast_block_info(rfast_ctx* ctx, int32_t* lanes_per_node, int32_t* tile_per_
  * The step uses slots 0 and 1 of the v rings as buffers: do not interleave it with
  * rfast_round on the same context without an rfast_init in between.
  * d_batch_idx: device int32 [n][batch] (objectives with batch > 0), else NULL.
- * rfast_sync_run: `rounds` steps from sample rows stacked [rounds][n][batch]. */
+ * rfast_sync_run: `rounds` steps from sample rows stacked [rounds][n][batch].  Where rfast_use_blocks
+ * allows it (separable objective, p a multiple of 4, at most 32 nodes with at most 4 edges of a kind)
+ * the steps between two decay steps of the step-size schedule are taken by one launch that keeps
+ * x, z and the samples in registers and exchanges x - gamma z and z through LDS: same bits. */
 int rfast_sync_round(rfast_ctx* ctx, float gamma, const int32_t* d_batch_idx);
 int rfast_sync_run(rfast_ctx* ctx, int32_t rounds, float gamma, const int32_t* d_batch_idx);
 

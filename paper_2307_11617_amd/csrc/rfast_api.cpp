@@ -784,9 +784,31 @@ int rfast_sync_run(rfast_ctx* c, int32_t rounds, float gamma, const int32_t* d_b
   if (rounds < 0) return fail(c, RFAST_EINVAL, "rounds < 0");
   const RfastDev& d = c->d;
   const size_t B = d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC ? 0 : (size_t)d.prob.batch;
-  for (int32_t r = 0; r < rounds; ++r) {
+  const bool multi = c->use_blocks && rfast_sync_wave_eligible(c);
+  const bool large = (double)d.n * (double)d.p * 4.0 > 8.0e6;
+  for (int32_t r = 0; r < rounds;) {
+    // several steps per launch for the separable objective on a small graph, with one step size
+    int32_t len = multi ? rounds - r : 0;
+    if (len > 0 && c->gamma_step > 0) {
+      const int64_t to_decay = c->gamma_step - c->host_round % c->gamma_step;
+      if (to_decay < len) len = (int32_t)to_decay;
+    }
+    if (len >= (large && c->use_blocks != 2 ? kBlockMinRoundsLarge : 2)) {
+      if (!std::isfinite(gamma)) return fail(c, RFAST_EINVAL, "gamma is not finite");
+      if (c->needs_init) return fail(c, RFAST_EINVAL, "rfast_init must follow rfast_set_optimizer");
+      if (fold_sync(c) != RFAST_OK) return RFAST_EHIP;
+      time_begin(c, 0);
+      hipError_t e = rfast_launch_sync_wave(c, gamma_now(c, gamma), len);
+      time_end(c, 0);
+      if (e == hipSuccess) e = rfast_launch_sync_plan(c, len);
+      if (e != hipSuccess) return hipfail(c, e, "multi-step synchronous launch");
+      c->host_round += len;
+      r += len;
+      continue;
+    }
     const int rc = rfast_sync_round(c, gamma, d_batch_idx ? d_batch_idx + (size_t)r * d.n * B : nullptr);
     if (rc != RFAST_OK) return rc;
+    ++r;
   }
   return RFAST_OK;
 }

@@ -157,6 +157,9 @@ int rfast_block_lanes(const rfast_ctx* c);  // lanes per node of the multi-round
 hipError_t rfast_launch_block(rfast_ctx* c, const RfastBlock& blk);
 hipError_t rfast_launch_generate(rfast_ctx* c, uint64_t seed, const float* d_p_active, int d_max, float p_drop, bool events);
 hipError_t rfast_launch_sync(rfast_ctx* c, int phase, float gamma, int parity);
+hipError_t rfast_launch_sync_plan(rfast_ctx* c, int rounds);
+bool rfast_sync_wave_eligible(const rfast_ctx* c);  // several synchronous steps per launch
+hipError_t rfast_launch_sync_wave(rfast_ctx* c, float gamma, int rounds);
 hipError_t rfast_launch_init_grad(rfast_ctx* c, const int32_t* batch_idx0);
 hipError_t rfast_diag_init_gradient(rfast_ctx* c);  // separable objective: g[t_i & 1][i] = sample(x_i, t_i) for every node
 hipError_t rfast_launch_gradient(rfast_ctx* c, const int32_t* batch_idx);

@@ -258,9 +258,10 @@ __device__ inline float* sync_z(const RfastDev& s, int parity, int i) {
   return parity == 0 ? s.z + (size_t)i * s.p : s.v_ring + ((size_t)i * s.M + 1) * s.p;
 }
 
-__global__ void __launch_bounds__(256) rfast_sync_plan_kernel(RfastDev s) {
+// rounds: steps taken at once (the plan arrays are left as the last of them leaves them)
+__global__ void __launch_bounds__(256) rfast_sync_plan_kernel(RfastDev s, int rounds) {
   for (int i = threadIdx.x; i < s.n; i += blockDim.x) {
-    const int ti = s.t[i];
+    const int ti = s.t[i] + rounds - 1;
     s.plan_t[i] = ti;
     s.active_plan[i] = make_int2(i, ti);
     s.t[i] = ti + 1;
@@ -268,7 +269,7 @@ __global__ void __launch_bounds__(256) rfast_sync_plan_kernel(RfastDev s) {
   if (threadIdx.x == 0) {
     *s.n_active = s.n;
     for (int q = 0; q < 8; ++q) s.active_plan[s.n + q] = make_int2(-1, 0);
-    *s.round_no = *s.round_no + 1;
+    *s.round_no = *s.round_no + rounds;
   }
 }
 
@@ -373,7 +374,7 @@ hipError_t rfast_launch_sync(rfast_ctx* c, int phase, float gamma, int parity) {
   const dim3 grid((unsigned)((d.p + per_block - 1) / per_block), d.n), blk(kThreads);
   const bool streaming = vec4 && (double)d.n * (double)d.p * 4.0 >= 32.0e6;
   if (phase == 0 || phase == 2) {
-    hipLaunchKernelGGL(rfast_sync_plan_kernel, dim3(1), dim3(256), 0, c->stream, d);
+    hipLaunchKernelGGL(rfast_sync_plan_kernel, dim3(1), dim3(256), 0, c->stream, d, 1);
     if (streaming) hipLaunchKernelGGL(rfast_sync_descent_kernel<-4>, grid, blk, 0, c->stream, d, gamma, parity);
     else if (vec4) hipLaunchKernelGGL(rfast_sync_descent_kernel<4>, grid, blk, 0, c->stream, d, gamma, parity);
     else hipLaunchKernelGGL(rfast_sync_descent_kernel<1>, grid, blk, 0, c->stream, d, gamma, parity);
@@ -394,6 +395,12 @@ hipError_t rfast_launch_sync(rfast_ctx* c, int phase, float gamma, int parity) {
     if (phase == 2) hipLaunchKernelGGL((rfast_sync_step_kernel<1, 2>), grid, blk, 0, c->stream, d, parity);
     if (phase == 3) hipLaunchKernelGGL(rfast_sync_fold_kernel<1>, grid, blk, 0, c->stream, d);
   }
+  return hipGetLastError();
+}
+
+// the integer side of `rounds` synchronous steps taken by one launch of the multi-step kernel
+hipError_t rfast_launch_sync_plan(rfast_ctx* c, int rounds) {
+  hipLaunchKernelGGL(rfast_sync_plan_kernel, dim3(1), dim3(256), 0, c->stream, c->d, rounds);
   return hipGetLastError();
 }
 

@@ -265,6 +265,84 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   }
 }
 
+// ---------------------------------------------------------------------------
+// The synchronous push-pull step of eq. (2), several steps per launch, on the same tiling: every
+// node steps at once and reads its neighbours' current x - gamma z and z, which the lanes of the
+// wavefront exchange through two LDS rows per node.  x, z, the stored sample and the objective data
+// stay in registers; the arithmetic is that of rfast_sync_descent_kernel + rfast_sync_step_kernel
+// (the stored sample of a step is the new sample of the step before: the same function of the same
+// arguments that the one-step kernels recompute).  On return z is in its own array and slot 0 of
+// the v ring holds the last x - gamma z, as after the one-step kernels.
+// ---------------------------------------------------------------------------
+template <int kDeg, bool MOM>
+__global__ void __launch_bounds__(64) rfast_sync_wave_kernel(RfastDev s, float gamma, int rounds, int lw) {
+  constexpr int VEC = 4;
+  extern __shared__ float4 lds4[];
+  const int n = s.n;
+  const int64_t p = s.p;
+  const int lane = threadIdx.x;
+  const int i = lane / lw, ln = lane - i * lw;
+  const unsigned xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+  const int64_t tile = ((int64_t)(slot / kTileRun) * kXcds + xcd) * kTileRun + slot % kTileRun;
+  const int64_t k = tile * (4 * lw) + ln * 4;
+  const bool mine = i < n && k < p;
+  float4* v_l = lds4;                   // [n][lw]
+  float4* z_l = v_l + (size_t)n * lw;   // [n][lw]
+  if (!mine) return;  // no barrier below: the lanes of a wavefront without coordinates may leave
+  const int own = i * lw + ln;
+  const size_t off = (size_t)i * p + k;
+  float4 x = V<VEC>::ld(s.x + off), z = V<VEC>::ld(s.z + off);
+  const float4 h = V<VEC>::ld((const float*)s.prob.data0 + off), c = V<VEC>::ld((const float*)s.prob.data1 + off);
+  float4 m = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (MOM) m = V<VEC>::ld(s.mom + off);
+  const int re0 = s.r_ptr[i], ce0 = s.c_ptr[i];
+  const int dR = s.r_ptr[i + 1] - re0, dI = s.c_ptr[i + 1] - ce0;
+  const float r_self = s.r_self[i], c_self = s.c_self[i];
+  int r_col[kDeg], c_col[kDeg];
+  float r_w[kDeg], c_w[kDeg];
+#pragma unroll
+  for (int u = 0; u < kDeg; ++u) {
+    r_col[u] = (u < dR ? s.r_src[re0 + u] : i) * lw + ln;
+    r_w[u] = u < dR ? s.r_w[re0 + u] : 0.f;
+    c_col[u] = (u < dI ? s.c_src[ce0 + u] : i) * lw + ln;
+    c_w[u] = u < dI ? s.c_w[ce0 + u] : 0.f;
+  }
+  int t = s.t[i];
+  float4 g = diag_sample<VEC>(s, h, c, x, i, t, k), v = x;
+  for (int q = 0; q < rounds; ++q) {
+    if (MOM) m = fma_s(s.beta, m, z);
+    v = fma_s(-gamma, MOM ? m : z, x);
+    v_l[own] = v;
+    z_l[own] = z;
+    wave_sync();  // every node's v and z of this step are out
+    float4 nb[kDeg], zb[kDeg];
+#pragma unroll
+    for (int u = 0; u < kDeg; ++u) {
+      nb[u] = v_l[r_col[u]];
+      zb[u] = z_l[c_col[u]];
+    }
+    float4 x_new = mul_s(r_self, v);
+#pragma unroll
+    for (int u = 0; u < kDeg; ++u)
+      if (u < dR) x_new = fma_s(r_w[u], nb[u], x_new);
+    const float4 g_new = diag_sample<VEC>(s, h, c, x_new, i, t + 1, k);
+    float4 z_new = mul_s(c_self, z);
+#pragma unroll
+    for (int u = 0; u < kDeg; ++u)
+      if (u < dI) z_new = fma_s(c_w[u], zb[u], z_new);
+    z_new = sub(add(z_new, g_new), g);
+    wave_sync();  // every read of this step is done before the next one overwrites the rows
+    x = x_new;
+    z = z_new;
+    g = g_new;
+    ++t;
+  }
+  V<VEC>::st(s.x + off, x);
+  V<VEC>::st(s.z + off, z);
+  if (MOM) V<VEC>::st(s.mom + off, m);
+  V<VEC>::st(s.v_ring + (size_t)i * s.M * p + k, v);
+}
+
 size_t wave_lds_bytes(const RfastDev& d, int lw) { return (size_t)2 * d.n * d.M * lw * sizeof(float4); }
 
 }  // namespace
@@ -301,4 +379,29 @@ static hipError_t launch_wave(rfast_ctx* c, const RfastBlock& blk) {
 hipError_t rfast_launch_wave(rfast_ctx* c, const RfastBlock& blk) {
   if (c->d.mom) return c->max_degree <= 2 ? launch_wave<2, true>(c, blk) : launch_wave<kWaveMaxDeg, true>(c, blk);
   return c->max_degree <= 2 ? launch_wave<2, false>(c, blk) : launch_wave<kWaveMaxDeg, false>(c, blk);
+}
+
+// The synchronous mode through the multi-step kernel: the separable objective, p a multiple of 4,
+// at most 32 nodes with at most kWaveMaxDeg in-edges of a kind each.
+bool rfast_sync_wave_eligible(const rfast_ctx* c) {
+  const RfastDev& d = c->d;
+  return d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC && (d.p % 4) == 0 && c->max_degree <= kWaveMaxDeg && d.n <= kWaveMaxNodes;
+}
+
+template <int kDeg, bool MOM>
+static hipError_t launch_sync_wave(rfast_ctx* c, float gamma, int rounds) {
+  const RfastDev& d = c->d;
+  const int lw = 64 / d.n;
+  const int64_t run = (int64_t)kXcds * kTileRun;
+  const int64_t tiles = ((d.p + 4 * lw - 1) / (4 * lw) + run - 1) / run * run;
+  if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((rfast_sync_wave_kernel<kDeg, MOM>), dim3((unsigned)tiles), dim3(64),
+                     (size_t)2 * d.n * lw * sizeof(float4), c->stream, c->d, gamma, rounds, lw);
+  return hipGetLastError();
+}
+
+hipError_t rfast_launch_sync_wave(rfast_ctx* c, float gamma, int rounds) {
+  if (c->d.mom)
+    return c->max_degree <= 2 ? launch_sync_wave<2, true>(c, gamma, rounds) : launch_sync_wave<kWaveMaxDeg, true>(c, gamma, rounds);
+  return c->max_degree <= 2 ? launch_sync_wave<2, false>(c, gamma, rounds) : launch_sync_wave<kWaveMaxDeg, false>(c, gamma, rounds);
 }

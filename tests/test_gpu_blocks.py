@@ -113,6 +113,32 @@ def test_large_state_short_and_long_calls():
         _same(a, b, hi)
 
 
+@pytest.mark.parametrize("n,variant", [(16, False), (16, True), (5, False), (24, True)])
+def test_synchronous_steps_per_launch(n, variant):
+    """rfast_sync_run through the multi-step kernel against one step per launch: same bits, with the
+    optimizer variant and a step-size schedule that cuts the launches, a single step in between."""
+    p = 4100
+    wr, wc = graphs.bidirectional_ring(n) if n != 5 else graphs.exponential(n)
+    R, C = graphs.from_dense(wr), graphs.from_dense(wc)
+    sched = ScheduleSpec(n, R.nnz_off, C.nnz_off, np.ones(n), 0, 0.0, seed=n)
+    w = configs.Workload(f"sync_{n}", n, p, R, C, 1, 1, 0.03, 0, "diag_quadratic",
+                         problems.diag_quadratic(n, p, n), sched, 0.1, 70 + n, 1e-4)
+    a, b = _pair(w)
+    x0 = np.random.default_rng(n).standard_normal((n, p)).astype(np.float32)
+    for g in (a, b):
+        if variant:
+            g.set_optimizer(0.8, 0.01)
+            g.set_gamma_schedule(17, 0.5)
+        g.init(x0, None)
+    for steps in (40, 1, 25):
+        for g in (a, b):
+            g.sync_run(steps, w.gamma, None)
+            g.check()
+        for f_ in ("X", "Z", "G", "T_NODE", "ROUND") + (("MOMENTUM",) if variant else ()):
+            assert np.array_equal(a.read(f_), b.read(f_)), (n, variant, steps, f_)
+    assert np.abs(a.read("X") - x0).max() > 1e-3
+
+
 def test_generated_schedules_and_events():
     w = configs.config2(p=2052, rounds=0)
     a, b = _pair(w)

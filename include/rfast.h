@@ -224,7 +224,7 @@ int rfast_run_events(rfast_ctx* ctx, int32_t iterations, uint64_t seed, const fl
  * run as ordinary launches.  Results are identical either way.  Off by default. */
 int rfast_use_graphs(rfast_ctx* ctx, int32_t on);
 
-/* on != 0 (the default): rfast_run and rfast_run_generated advance up to 128 rounds with one
+/* on != 0 (the default): rfast_run and rfast_run_generated advance up to 512 rounds with one
  * launch where that is possible and pays -- the separable objective (diagonal quadratic, with or
  * without the optimizer variant), p a multiple of 4, at most 64 nodes, no node with more than 4
  * in-edges of R, in-edges of C or out-edges of C, a tile of coordinates of every node's two rings

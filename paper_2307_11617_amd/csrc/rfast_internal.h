@@ -135,7 +135,7 @@ enum { RFAST_MODE_FUSED = 0, RFAST_MODE_MIX = 1, RFAST_MODE_TRACK = 2 };
 // in LDS at a time, and the shortest launch that pays where the state is large (the launch moves
 // every ring slot in and out once: measured on 16 nodes x 11.2 M coordinates, about 7 ms per launch
 // plus 0.33 ms per round against 1.53 ms per round of the streaming kernel: even from 6 rounds on)
-constexpr int kBlockRounds = 128;
+constexpr int kBlockRounds = 512;
 constexpr int kPlanChunk = 16;
 constexpr int kBlockMinRoundsLarge = 8;
 struct RfastBlock {

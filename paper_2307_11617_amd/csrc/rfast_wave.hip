@@ -32,12 +32,12 @@ __device__ inline void wave_sync() {
 
 // lw: lanes per node (64 / n, rounded down); kDeg: edge slots per node and kind; MOM: the optimizer
 // variant's heavy-ball buffer is in use (a template flag, so that the plain method carries neither
-// the registers nor the copies at the join).  A workgroup is one
-// wavefront with a tile of 4 lw coordinates (measured on 16 nodes x 11.2 M coordinates: 0.345 ms per
-// round, against 0.350 and 0.352 with two and four such wavefronts per workgroup).  Occupancy is
-// pinned to two wavefronts per SIMD, which is what the LDS of a CU holds at nine ring slots: once
-// the registers allowed three, the eight wavefronts of a CU were spread unevenly over its SIMDs and
-// the launch took 4 % longer.
+// the registers nor the copies at the join).
+// A workgroup is one wavefront with a tile of 4 lw coordinates (two and four such wavefronts per
+// workgroup were 1.5 % and 2 % slower on 16 nodes x 11.2 M coordinates).  Occupancy is pinned to two
+// wavefronts per SIMD, which is what the LDS of a CU holds at nine ring slots: once the registers
+// allowed three, the eight wavefronts of a CU were spread unevenly over its SIMDs and the launch
+// took 4 % longer.
 template <int kDeg, bool MOM>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) rfast_wave_kernel(RfastDev s, RfastBlock blk, int lw) {
   constexpr int VEC = 4;
@@ -109,10 +109,10 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       o_eid[u] = oe;
     }
   }
-  // plan words of round 0 (every lane: the lanes of a wavefront without a node read the zero word)
   // Plan words are read through a buffer descriptor over the records of this launch: the address is
   // descriptor + uniform record offset + 32-bit lane offset, formed by the load itself (no 64-bit
   // address arithmetic per word), and a read past the records returns zero instead of faulting.
+  // First those of round 0 (every lane: the lanes of a wavefront without a node read the zero word).
   const __amdgpu_buffer_rsrc_t plans = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<int*>(s.blk_plan), 0, blk.rounds * W1 * (int)sizeof(int), 0x00020000);
   auto word = [&](int round, unsigned byte_offset) {

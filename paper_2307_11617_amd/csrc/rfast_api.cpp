@@ -4,6 +4,7 @@
 
 #include <algorithm>
 #include <string>
+#include <type_traits>
 #include <vector>
 
 #include "rfast_internal.h"
@@ -33,7 +34,7 @@ struct Offsets {
   size_t x, z, g, v_ring, sigma_ring, rho_tilde;
   size_t r_ptr, r_src, r_dst, r_w, r_self, c_ptr, c_src, c_dst, c_w, c_self, co_ptr, co_eid, co_w, ro_ptr, ro_eid;
   size_t t, t_hist, tau_r, tau_c, deliv_r, deliv_c, round_no, err;
-  size_t n_active, active_plan, plan_t, slot_r, slot_c, plan_c, node_spill, blk_plan;
+  size_t n_active, active_plan, plan_t, slot_r, slot_c, plan_c, node_spill, plan_set_bytes, blk_plan;
   size_t gen_active, gen_delay_r, gen_delay_c, gen_drop_r, gen_drop_c, gen_batch, gen_cdf;
   size_t xbar, resid, gscratch, diag;
   size_t total;
@@ -87,13 +88,17 @@ Offsets layout(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, cons
   o.deliv_c = L.take(eC * 8);
   o.round_no = L.take(4);
   o.err = L.take(16);
-  o.n_active = L.take(4);
+  o.n_active = L.take(8);
   o.active_plan = L.take(((size_t)n + 8) * 8);
   o.plan_t = L.take(n * 4);
   o.slot_r = L.take(eR * 4);
   o.slot_c = L.take(eC * 4);
   o.plan_c = L.take(eC * 4);
   o.node_spill = L.take(n);
+  // the seven arrays above are the plan of one round; kResolveAhead - 1 more such sets follow, so that the
+  // resolver can run that many rounds ahead of the kernels that read the plans
+  o.plan_set_bytes = L.total - o.n_active;
+  (void)L.take((size_t)(kResolveAhead - 1) * o.plan_set_bytes);
   o.blk_plan = L.take((size_t)kBlockRounds * ((size_t)n + eR + eC + 1) * 4);
   o.gen_active = L.take(n);
   o.gen_delay_r = L.take(eR * 4);
@@ -440,6 +445,9 @@ int rfast_create(rfast_ctx** out, int32_t n, int64_t p, const int32_t* R_rowptr,
   d.plan_c = (int32_t*)(b + o.plan_c); d.node_spill = (uint8_t*)(b + o.node_spill);
   d.blk_plan = nullptr;
   c->blk_plan_base = (int32_t*)(b + o.blk_plan);
+  c->plan_set0 = b + o.n_active;
+  c->plan_set_bytes = o.plan_set_bytes;
+  c->plan_set = 0;
   d.gen_active = (uint8_t*)(b + o.gen_active); d.gen_delay_r = (int32_t*)(b + o.gen_delay_r);
   d.gen_delay_c = (int32_t*)(b + o.gen_delay_c); d.gen_drop_r = (uint8_t*)(b + o.gen_drop_r);
   d.gen_drop_c = (uint8_t*)(b + o.gen_drop_c); d.gen_batch = (int32_t*)(b + o.gen_batch);
@@ -504,16 +512,25 @@ int rfast_init(rfast_ctx* c, const float* d_x0, const int32_t* d_batch_idx0) {
   chk(hipMemsetAsync(d.plan_t, 0, (size_t)d.n * 4, c->stream));
   chk(hipMemsetAsync(d.round_no, 0, 4, c->stream));
   chk(hipMemsetAsync(d.err, 0, 16, c->stream));
-  chk(hipMemsetAsync(d.n_active, 0, 4, c->stream));
+  chk(hipMemsetAsync(d.n_active, 0, 8, c->stream));
   if (e != hipSuccess) return hipfail(c, e, "rfast_init clears");
   e = rfast_launch_init_grad(c, d_batch_idx0);
   if (e != hipSuccess) return hipfail(c, e, "initial gradient");
   return RFAST_OK;
 }
 
-int rfast_round(rfast_ctx* c, const uint8_t* d_active, const int32_t* d_delay_R, const int32_t* d_delay_C,
-                const uint8_t* d_drop_R, const uint8_t* d_drop_C, float gamma, const int32_t* d_batch_idx) {
-  if (!c) return RFAST_EINVAL;
+// Points the per-round plan arrays of c->d at set q (the resolver writes the rounds it takes in one
+// launch into consecutive sets; the kernels of a round read the set of that round).
+static void use_plan_set(rfast_ctx* c, int32_t q) {
+  RfastDev& d = c->d;
+  const ptrdiff_t shift = (ptrdiff_t)(q - c->plan_set) * (ptrdiff_t)c->plan_set_bytes;
+  auto move = [shift](auto*& ptr) { ptr = reinterpret_cast<std::remove_reference_t<decltype(ptr)>>(reinterpret_cast<char*>(ptr) + shift); };
+  move(d.n_active); move(d.active_plan); move(d.plan_t); move(d.slot_r); move(d.slot_c); move(d.plan_c); move(d.node_spill);
+  c->plan_set = q;
+}
+
+static int check_round_args(rfast_ctx* c, const uint8_t* d_active, const int32_t* d_delay_R, const int32_t* d_delay_C,
+                            const uint8_t* d_drop_R, const uint8_t* d_drop_C, float gamma, const int32_t* d_batch_idx) {
   const RfastDev& d = c->d;
   if (!d_active || (d.eR && (!d_delay_R || !d_drop_R)) || (d.eC && (!d_delay_C || !d_drop_C)))
     return fail(c, RFAST_EINVAL, "NULL schedule pointer");
@@ -521,13 +538,29 @@ int rfast_round(rfast_ctx* c, const uint8_t* d_active, const int32_t* d_delay_R,
   if (!separable && d.prob.batch > 0 && !d_batch_idx) return fail(c, RFAST_EINVAL, "sample rows are required when batch > 0");
   if (!std::isfinite(gamma)) return fail(c, RFAST_EINVAL, "gamma is not finite");
   if (c->needs_init) return fail(c, RFAST_EINVAL, "rfast_init must follow rfast_set_optimizer");
+  return RFAST_OK;
+}
+
+static int float_round(rfast_ctx* c, float gamma, const int32_t* d_batch_idx);
+
+int rfast_round(rfast_ctx* c, const uint8_t* d_active, const int32_t* d_delay_R, const int32_t* d_delay_C,
+                const uint8_t* d_drop_R, const uint8_t* d_drop_C, float gamma, const int32_t* d_batch_idx) {
+  if (!c) return RFAST_EINVAL;
+  const int rc = check_round_args(c, d_active, d_delay_R, d_delay_C, d_drop_R, d_drop_C, gamma, d_batch_idx);
+  if (rc != RFAST_OK) return rc;
   if (fold_sync(c) != RFAST_OK) return RFAST_EHIP;
-  gamma = gamma_now(c, gamma);
-  hipError_t e;
   time_begin(c, 2);
-  e = rfast_launch_resolve(c, d_active, d_delay_R, d_delay_C, d_drop_R, d_drop_C);
+  const hipError_t e = rfast_launch_resolve(c, d_active, d_delay_R, d_delay_C, d_drop_R, d_drop_C);
   time_end(c, 2);
   if (e != hipSuccess) return hipfail(c, e, "resolver launch");
+  return float_round(c, gamma, d_batch_idx);
+}
+
+// The floating-point part of a round whose plan the resolver has written into the current plan set.
+static int float_round(rfast_ctx* c, float gamma, const int32_t* d_batch_idx) {
+  const bool separable = c->d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC;
+  gamma = gamma_now(c, gamma);
+  hipError_t e;
   if (separable) {
     time_begin(c, 0);
     e = rfast_launch_state(c, RFAST_MODE_FUSED, gamma);
@@ -555,15 +588,16 @@ int rfast_round(rfast_ctx* c, const uint8_t* d_active, const int32_t* d_delay_R,
 // multiple of the rebase interval, and it runs with one step size, so it must end with the current
 // step of the step-size schedule; and it reads and writes every ring slot once, which a large
 // state earns back only over enough rounds.
-static int32_t block_length(const rfast_ctx* c, int32_t rounds) {
+static int32_t block_length(const rfast_ctx* c, int32_t rounds, int64_t at_round = -1) {
   if (!c->use_blocks || !(rfast_wave_eligible(c) || rfast_block_eligible(c))) return 0;
+  const int64_t now = at_round >= 0 ? at_round : c->host_round;  // the round the launch would start with
   int32_t len = rounds < kBlockRounds ? rounds : kBlockRounds;
   if (c->rebase_interval > 0) {
-    const int64_t to_boundary = c->rebase_interval - c->host_round % c->rebase_interval;
+    const int64_t to_boundary = c->rebase_interval - now % c->rebase_interval;
     if (to_boundary < len) len = (int32_t)to_boundary;
   }
   if (c->gamma_step > 0) {  // one step size per launch
-    const int64_t to_decay = c->gamma_step - c->host_round % c->gamma_step;
+    const int64_t to_decay = c->gamma_step - now % c->gamma_step;
     if (to_decay < len) len = (int32_t)to_decay;
   }
   const bool large = (double)c->d.n * (double)c->d.p * 4.0 > 8.0e6;
@@ -648,12 +682,33 @@ int rfast_run(rfast_ctx* c, int32_t rounds, const uint8_t* d_active, const int32
       r += len - 1;
       continue;
     }
-    const int rc = rfast_round(c, d_active + (size_t)r * d.n, d_delay_R ? d_delay_R + (size_t)r * d.eR : nullptr,
-                               d_delay_C ? d_delay_C + (size_t)r * d.eC : nullptr,
-                               d_drop_R ? d_drop_R + (size_t)r * d.eR : nullptr,
-                               d_drop_C ? d_drop_C + (size_t)r * d.eC : nullptr, gamma,
-                               d_batch_idx ? d_batch_idx + (size_t)r * d.n * B : nullptr);
+    // One pass per round: the resolver takes up to kResolveAhead rounds in one launch, into as many
+    // plan sets (integer state only, so it may run ahead of the kernels); a stretch ends where a
+    // multi-round launch may start and, because the rebase reads the counters, on the multiples of
+    // the rebase interval.
+    int32_t ahead = rounds - r < kResolveAhead ? rounds - r : kResolveAhead;
+    for (int32_t q = 1; q < ahead; ++q) {
+      const int64_t then = c->host_round + q;
+      const bool boundary = c->rebase_interval > 0 && then % c->rebase_interval == 0;
+      if (boundary || block_length(c, rounds - r - q, then) > 0) { ahead = q; break; }
+    }
+    int rc = check_round_args(c, d_active + (size_t)r * d.n, d_delay_R, d_delay_C, d_drop_R, d_drop_C, gamma, d_batch_idx);
     if (rc != RFAST_OK) return rc;
+    if (fold_sync(c) != RFAST_OK) return RFAST_EHIP;
+    use_plan_set(c, 0);
+    time_begin(c, 2);
+    const hipError_t e = rfast_launch_resolve(c, d_active + (size_t)r * d.n, d_delay_R ? d_delay_R + (size_t)r * d.eR : nullptr,
+                                              d_delay_C ? d_delay_C + (size_t)r * d.eC : nullptr,
+                                              d_drop_R ? d_drop_R + (size_t)r * d.eR : nullptr,
+                                              d_drop_C ? d_drop_C + (size_t)r * d.eC : nullptr, ahead, c->plan_set_bytes);
+    time_end(c, 2);
+    if (e != hipSuccess) return hipfail(c, e, "resolver launch");
+    for (int32_t q = 0; q < ahead; ++q) {
+      use_plan_set(c, q);
+      rc = float_round(c, gamma, d_batch_idx ? d_batch_idx + (size_t)(r + q) * d.n * B : nullptr);
+      if (rc != RFAST_OK) return rc;
+    }
+    r += ahead - 1;
   }
   return RFAST_OK;
 }

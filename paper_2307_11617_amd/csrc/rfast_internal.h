@@ -63,7 +63,7 @@ struct RfastDev {
   int32_t* round_no;      // [1]
   int32_t* err;           // [4] code, round, kind, edge (first error wins)
   // per-round plan written by the resolver, read by the state kernels
-  int32_t* n_active;      // [1]
+  int32_t* n_active;      // [2]: active nodes of the round, round counter after it
   // [n + 8] work slots of the round: {node, t_node at the start of the round}, the active nodes in
   // increasing order first, then {-1, 0}.  One 8-byte load tells a workgroup whether it has work, for
   // which node and at which counter (instead of a chain of three dependent loads).
@@ -127,6 +127,10 @@ struct rfast_ctx {
   int32_t use_blocks = 1;       // 1: where it pays, 2: wherever possible; rfast_run / rfast_run_generated may advance several rounds per launch
   int32_t* blk_plan_base = nullptr;  // kBlockRounds plan records
   int32_t max_degree = 0;       // most in-edges of R, in-edges of C or out-edges of C at any node
+  // the per-round plan arrays of RfastDev exist kResolveAhead times; `plan_set` is the set d points at
+  char* plan_set0 = nullptr;
+  size_t plan_set_bytes = 0;
+  int32_t plan_set = 0;
 };
 
 enum { RFAST_MODE_FUSED = 0, RFAST_MODE_MIX = 1, RFAST_MODE_TRACK = 2 };
@@ -138,6 +142,8 @@ enum { RFAST_MODE_FUSED = 0, RFAST_MODE_MIX = 1, RFAST_MODE_TRACK = 2 };
 constexpr int kBlockRounds = 512;
 constexpr int kPlanChunk = 16;
 constexpr int kBlockMinRoundsLarge = 8;
+// rounds the resolver may run ahead of the kernels that read its plans (rfast_run, one pass per round)
+constexpr int kResolveAhead = 32;
 struct RfastBlock {
   float gamma;                // step size of its rounds (a launch does not straddle a decay step)
   int32_t rounds;             // 1 .. kBlockRounds
@@ -145,7 +151,8 @@ struct RfastBlock {
 
 // launchers (each enqueues on ctx->stream and returns a hipError_t)
 hipError_t rfast_launch_resolve(rfast_ctx* c, const uint8_t* active, const int32_t* delay_R,
-                                const int32_t* delay_C, const uint8_t* drop_R, const uint8_t* drop_C, int rounds = 1);
+                                const int32_t* delay_C, const uint8_t* drop_R, const uint8_t* drop_C, int rounds = 1,
+                                size_t plan_stride = 0);
 hipError_t rfast_launch_state(rfast_ctx* c, int mode, float gamma);
 hipError_t rfast_launch_rebase(rfast_ctx* c);
 // several rounds of the separable objective on LDS-resident tiles; the rounds' plans are in blk_plan

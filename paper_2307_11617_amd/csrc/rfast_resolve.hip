@@ -113,12 +113,17 @@ __device__ inline void edge_decide(const RfastDev& s, int kind, int e, int r, co
 constexpr int kResolveThreads = 1024;
 constexpr int kAhead = 2;  // edges per lane whose loads are issued before the node pass
 
+template <class P> __device__ inline void advance(P*& ptr, size_t bytes) {
+  ptr = reinterpret_cast<P*>(reinterpret_cast<char*>(ptr) + bytes);
+}
+
 // rounds > 1: consecutive rounds in one launch, the schedule arrays of round q at offset q of each
-// pointer and its plan record behind the previous one (the per-round plan arrays then hold the last
-// round only, so this form serves the multi-round kernel, which reads records).  The rounds are
-// sequential -- each reads the counters, stamps and delivery bits the one before wrote -- with the
-// workgroup's barrier between them.
-__global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev s, int rounds, const uint8_t* active,
+// pointer, its plan record (multi-round kernels) behind the previous one and its per-round plan
+// arrays plan_stride bytes behind those of the previous round (0: every round overwrites the same
+// arrays, which then hold the last round only).  The rounds are sequential -- each reads the
+// counters, stamps and delivery bits the one before wrote -- with the workgroup's barrier between
+// them.
+__global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev s, int rounds, size_t plan_stride, const uint8_t* active,
                                                                          const int32_t* delay_R, const int32_t* delay_C,
                                                                          const uint8_t* drop_R, const uint8_t* drop_C) {
   __shared__ int wave_cnt[kResolveThreads / 64];
@@ -167,7 +172,10 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev
       }
       __syncthreads();
     }
-    if (threadIdx.x == 0) *s.n_active = base;
+    if (threadIdx.x == 0) {
+      s.n_active[0] = base;
+      s.n_active[1] = r + 1;
+    }
     for (int q = base + threadIdx.x; q < s.n + 8; q += kResolveThreads) s.active_plan[q] = make_int2(-1, 0);
     // edge pass (node_spill was cleared above, before the barriers); nothing in it depends on the node pass
 #pragma unroll
@@ -193,6 +201,13 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev
       delay_C += s.eC;
       drop_C += s.eC;
       if (s.blk_plan) s.blk_plan += s.n + E + 1;
+      advance(s.n_active, plan_stride);
+      advance(s.active_plan, plan_stride);
+      advance(s.plan_t, plan_stride);
+      advance(s.slot_r, plan_stride);
+      advance(s.slot_c, plan_stride);
+      advance(s.plan_c, plan_stride);
+      advance(s.node_spill, plan_stride);
     }
   }
   if (threadIdx.x == 0) *s.round_no = r0 + rounds;
@@ -201,8 +216,9 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev
 }  // namespace
 
 hipError_t rfast_launch_resolve(rfast_ctx* c, const uint8_t* active, const int32_t* delay_R,
-                                const int32_t* delay_C, const uint8_t* drop_R, const uint8_t* drop_C, int rounds) {
-  hipLaunchKernelGGL(rfast_resolve_kernel, dim3(1), dim3(kResolveThreads), 0, c->stream, c->d, rounds, active, delay_R,
-                     delay_C, drop_R, drop_C);
+                                const int32_t* delay_C, const uint8_t* drop_R, const uint8_t* drop_C, int rounds,
+                                size_t plan_stride) {
+  hipLaunchKernelGGL(rfast_resolve_kernel, dim3(1), dim3(kResolveThreads), 0, c->stream, c->d, rounds, plan_stride, active,
+                     delay_R, delay_C, drop_R, drop_C);
   return hipGetLastError();
 }

@@ -270,6 +270,7 @@ __global__ void __launch_bounds__(256) rfast_sync_plan_kernel(RfastDev s, int ro
     *s.n_active = s.n;
     for (int q = 0; q < 8; ++q) s.active_plan[s.n + q] = make_int2(-1, 0);
     *s.round_no = *s.round_no + rounds;
+    s.n_active[1] = *s.round_no;
   }
 }
 

@@ -62,7 +62,9 @@ __device__ inline void edge_level2(const RfastDev& s, int r, const uint8_t* acti
   q->u = at <= 0 ? 0 : (at >= r ? q->tj : s.t_hist[(size_t)q->j * s.H + (at % s.H)]);
 }
 
-__device__ inline void edge_decide(const RfastDev& s, int kind, int e, int r, const EdgeIn& q) {
+// Decides edge e for round r and leaves the new stamp and delivery bits in q as well (a lane that
+// keeps its edges over several rounds goes on from them).
+__device__ inline void edge_decide(const RfastDev& s, int kind, int e, int r, EdgeIn& q) {
   int32_t* tau = kind ? s.tau_c : s.tau_r;
   int32_t* slot = kind ? s.slot_c : s.slot_r;
   unsigned long long* deliv = kind ? s.deliv_c : s.deliv_r;
@@ -74,6 +76,7 @@ __device__ inline void edge_decide(const RfastDev& s, int kind, int e, int r, co
     const int old = q.old;
     const int now = u > old ? u : old;
     tau[e] = now;
+    q.old = now;
     slot[e] = now % s.M;
     if (s.blk_plan && !kind) s.blk_plan[s.n + e] = now % s.M;
     if (kind) {
@@ -106,7 +109,8 @@ __device__ inline void edge_decide(const RfastDev& s, int kind, int e, int r, co
       ok = all_lost;
     }
     const unsigned long long bit = 1ull << (vn % s.M);
-    deliv[e] = ok ? (q.bits | bit) : (q.bits & ~bit);
+    q.bits = ok ? (q.bits | bit) : (q.bits & ~bit);
+    deliv[e] = q.bits;
   }
 }
 
@@ -213,11 +217,149 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev
   if (threadIdx.x == 0) *s.round_no = r0 + rounds;
 }
 
+// ---------------------------------------------------------------------------
+// The same rounds with everything a round reads held on chip: the schedule of all rounds of the
+// launch (delay and loss of every edge as 16-bit words, the activity masks) is copied to LDS first,
+// the counters t and their history live in LDS, and every lane keeps the stamp and the delivery bits
+// of its (at most two) edges in registers.  A round then costs LDS gathers and barriers; what it
+// writes to global memory (plans, stamps, bits, counters, history) nobody waits for.  For graphs of
+// up to 1024 nodes and 2048 edges whose schedule fits into LDS; bit for bit the plans of the kernel
+// above.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kResolveThreads) rfast_resolve_cached_kernel(RfastDev s, int rounds, size_t plan_stride,
+                                                                                const uint8_t* active, const int32_t* delay_R,
+                                                                                const int32_t* delay_C, const uint8_t* drop_R,
+                                                                                const uint8_t* drop_C) {
+  extern __shared__ int lds_i[];
+  __shared__ int wave_cnt[kResolveThreads / 64];
+  const int n = s.n, E = s.eR + s.eC, H = s.H;
+  int* t_l = lds_i;                                                      // [n]
+  int* hist_l = t_l + n;                                                 // [n][H]
+  unsigned short* sched_l = reinterpret_cast<unsigned short*>(hist_l + n * H);  // [rounds][E]: delay | loss << 8 | out of range << 15
+  uint8_t* act_l = reinterpret_cast<uint8_t*>(sched_l + (size_t)rounds * E + ((size_t)rounds * E & 1));  // [rounds][n]
+  const int r0 = *s.round_no;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int w = threadIdx.x; w < rounds * E; w += kResolveThreads) {
+    const int q = w / E, e = w - q * E;
+    const bool kind = e >= s.eR;
+    const int d = kind ? delay_C[(size_t)q * s.eC + (e - s.eR)] : delay_R[(size_t)q * s.eR + e];
+    const bool lost = (kind ? drop_C[(size_t)q * s.eC + (e - s.eR)] : drop_R[(size_t)q * s.eR + e]) != 0;
+    const bool bad = d < 0 || d > s.d_max;
+    sched_l[w] = (unsigned short)((d < 0 ? 0 : (d > s.d_max ? s.d_max : d)) | (lost ? 1 << 8 : 0) | (bad ? 1 << 15 : 0));
+  }
+  for (int w = threadIdx.x; w < rounds * n; w += kResolveThreads) act_l[w] = active[w];
+  for (int i = threadIdx.x; i < n; i += kResolveThreads) t_l[i] = s.t[i];
+  for (int w = threadIdx.x; w < n * H; w += kResolveThreads) hist_l[w] = s.t_hist[w];
+  EdgeIn mine[kAhead];
+#pragma unroll
+  for (int a = 0; a < kAhead; ++a) {
+    const int e = threadIdx.x + a * kResolveThreads;
+    if (e < E) {
+      const bool kind = e >= s.eR;
+      const int el = kind ? e - s.eR : e;
+      mine[a].i = (kind ? s.c_dst : s.r_dst)[el];
+      mine[a].j = (kind ? s.c_src : s.r_src)[el];
+      mine[a].bits = (kind ? s.deliv_c : s.deliv_r)[el];
+      mine[a].old = (kind ? s.tau_c : s.tau_r)[el];
+    }
+  }
+  __syncthreads();
+  const int i = threadIdx.x;  // the node this lane looks after (n <= kResolveThreads)
+  for (int rq = 0; rq < rounds; ++rq) {
+    const int r = r0 + rq;
+    const uint8_t* act = act_l + (size_t)rq * n;
+    // what the lane's edges see: schedule, activity and the sender's counters, all from LDS
+#pragma unroll
+    for (int a = 0; a < kAhead; ++a) {
+      const int e = threadIdx.x + a * kResolveThreads;
+      if (e < E) {
+        EdgeIn& q = mine[a];
+        const unsigned sw = sched_l[(size_t)rq * E + e];
+        const int d = sw & 0xFF;
+        q.d = (sw >> 15) ? -1 : d;  // out of range: reported by edge_decide, resolved with the clamped value
+        q.dropped = (sw >> 8) & 1;
+        q.act_i = act[q.i] != 0;
+        q.act_j = act[q.j] != 0;
+        q.tj = t_l[q.j];
+        const int at = r - d;
+        q.u = at <= 0 ? 0 : (at >= r ? q.tj : hist_l[q.j * H + (at % H)]);
+      }
+    }
+    if (threadIdx.x == 0 && s.blk_plan) s.blk_plan[n + E] = 0;  // a record ends with a word that is always zero
+    // node pass: snapshot of the counters, and the ordered list of active nodes (ballot + prefix)
+    bool on = false;
+    int ti = 0;
+    if (i < n) {
+      ti = t_l[i];
+      s.plan_t[i] = ti;
+      s.node_spill[i] = 0;
+      s.t_hist[(size_t)i * H + (r % H)] = ti;
+      on = act[i] != 0;
+      if (s.blk_plan) s.blk_plan[i] = (ti & 0x3FFFFFFF) | (on ? (int)0x80000000 : 0);
+    }
+    const unsigned long long m = __ballot(on);
+    if (lane == 0) wave_cnt[wave] = __popcll(m);
+    __syncthreads();  // also: every lane has read the history of this round's delays
+    if (i < n) hist_l[i * H + (r % H)] = ti;
+    int off = 0, total = 0;
+    for (int w = 0; w < kResolveThreads / 64; ++w) {
+      if (w < wave) off += wave_cnt[w];
+      total += wave_cnt[w];
+    }
+    if (on) s.active_plan[off + __popcll(m & ((1ull << lane) - 1ull))] = make_int2(i, ti);
+    if (threadIdx.x == 0) {
+      s.n_active[0] = total;
+      s.n_active[1] = r + 1;
+    }
+    for (int q = total + threadIdx.x; q < n + 8; q += kResolveThreads) s.active_plan[q] = make_int2(-1, 0);
+#pragma unroll
+    for (int a = 0; a < kAhead; ++a) {
+      const int e = threadIdx.x + a * kResolveThreads;
+      if (e < E) edge_decide(s, e >= s.eR, e >= s.eR ? e - s.eR : e, r, mine[a]);
+    }
+    __syncthreads();  // every read of the counters is done (and wave_cnt may be reused)
+    if (on) {
+      t_l[i] = ti + 1;
+      s.t[i] = ti + 1;
+    }
+    __syncthreads();  // the next round reads what this one wrote
+    if (s.blk_plan) s.blk_plan += n + E + 1;
+    advance(s.n_active, plan_stride);
+    advance(s.active_plan, plan_stride);
+    advance(s.plan_t, plan_stride);
+    advance(s.slot_r, plan_stride);
+    advance(s.slot_c, plan_stride);
+    advance(s.plan_c, plan_stride);
+    advance(s.node_spill, plan_stride);
+  }
+  if (threadIdx.x == 0) *s.round_no = r0 + rounds;
+}
+
+size_t cached_lds_bytes(const RfastDev& d, int rounds) {
+  const size_t E = (size_t)d.eR + d.eC;
+  return ((size_t)d.n + (size_t)d.n * d.H) * sizeof(int) + (((size_t)rounds * E + 1) & ~(size_t)1) * sizeof(unsigned short) +
+         (size_t)rounds * d.n;
+}
+
 }  // namespace
 
 hipError_t rfast_launch_resolve(rfast_ctx* c, const uint8_t* active, const int32_t* delay_R,
                                 const int32_t* delay_C, const uint8_t* drop_R, const uint8_t* drop_C, int rounds,
                                 size_t plan_stride) {
+  const RfastDev& d = c->d;
+  const size_t lds = cached_lds_bytes(d, rounds);
+  if (rounds > 1 && d.n <= kResolveThreads && d.eR + d.eC <= kAhead * kResolveThreads && lds <= 150 * 1024) {
+    static bool raised = false;
+    if (!raised) {  // more than 64 KB of dynamic LDS has to be asked for once (the kernel has 64 B of static LDS too)
+      const hipError_t e = hipFuncSetAttribute((const void*)rfast_resolve_cached_kernel,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
+      if (e != hipSuccess) return e;
+      raised = true;
+    }
+    hipLaunchKernelGGL(rfast_resolve_cached_kernel, dim3(1), dim3(kResolveThreads), lds, c->stream, c->d, rounds, plan_stride,
+                       active, delay_R, delay_C, drop_R, drop_C);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(rfast_resolve_kernel, dim3(1), dim3(kResolveThreads), 0, c->stream, c->d, rounds, plan_stride, active,
                      delay_R, delay_C, drop_R, drop_C);
   return hipGetLastError();

@@ -36,6 +36,7 @@ struct Offsets {
   size_t t, t_hist, tau_r, tau_c, deliv_r, deliv_c, round_no, err;
   size_t n_active, active_plan, plan_t, slot_r, slot_c, plan_c, node_spill, plan_set_bytes, blk_plan;
   size_t gen_active, gen_delay_r, gen_delay_c, gen_drop_r, gen_drop_c, gen_batch, gen_cdf;
+  int32_t gen_depth;
   size_t xbar, resid, gscratch, diag;
   size_t total;
 };
@@ -100,12 +101,17 @@ Offsets layout(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, cons
   o.plan_set_bytes = L.total - o.n_active;
   (void)L.take((size_t)(kResolveAhead - 1) * o.plan_set_bytes);
   o.blk_plan = L.take((size_t)kBlockRounds * ((size_t)n + eR + eC + 1) * 4);
-  o.gen_active = L.take(n);
-  o.gen_delay_r = L.take(eR * 4);
-  o.gen_delay_c = L.take(eC * 4);
-  o.gen_drop_r = L.take(eR);
-  o.gen_drop_c = L.take(eC);
-  o.gen_batch = L.take((size_t)n * (size_t)(prob->kind == RFAST_OBJ_DIAG_QUADRATIC ? 0 : prob->batch) * 4);
+  // the generator draws the schedule of up to gen_depth rounds per launch (as many as fit 64 MB, at most kBlockRounds)
+  const size_t gen_rows = (size_t)n * (size_t)(prob->kind == RFAST_OBJ_DIAG_QUADRATIC ? 0 : prob->batch);
+  const size_t gen_round = (size_t)n + 5 * (eR + eC) + 4 * gen_rows;
+  const size_t G = std::max<size_t>(1, std::min<size_t>(kBlockRounds, ((size_t)64 << 20) / gen_round));
+  o.gen_depth = (int32_t)G;
+  o.gen_active = L.take(G * n);
+  o.gen_delay_r = L.take(G * eR * 4);
+  o.gen_delay_c = L.take(G * eC * 4);
+  o.gen_drop_r = L.take(G * eR);
+  o.gen_drop_c = L.take(G * eC);
+  o.gen_batch = L.take(G * gen_rows * 4);
   o.gen_cdf = L.take(n * 4);
   o.xbar = L.take(vec);
   o.resid = L.take(rfast_gemv_scratch_floats(n, prob) * 4);
@@ -452,6 +458,7 @@ int rfast_create(rfast_ctx** out, int32_t n, int64_t p, const int32_t* R_rowptr,
   d.gen_delay_c = (int32_t*)(b + o.gen_delay_c); d.gen_drop_r = (uint8_t*)(b + o.gen_drop_r);
   d.gen_drop_c = (uint8_t*)(b + o.gen_drop_c); d.gen_batch = (int32_t*)(b + o.gen_batch);
   d.gen_cdf = (uint32_t*)(b + o.gen_cdf);
+  c->gen_depth = o.gen_depth;
   d.xbar = (float*)(b + o.xbar);
   d.mom = nullptr; d.beta = 0.f; d.wd = 0.f;
   d.resid = (float*)(b + o.resid); d.gscratch = (void*)(b + o.gscratch);
@@ -604,32 +611,19 @@ static int32_t block_length(const rfast_ctx* c, int32_t rounds, int64_t at_round
   return len >= (large && c->use_blocks != 2 ? kBlockMinRoundsLarge : 2) ? len : 0;
 }
 
-// Resolves `len` rounds (schedule arrays of round q at offset q of each pointer, or generated on
-// the device when seed_gen is set) into plan records and advances them with one launch.
+// Resolves `len` rounds (schedule arrays of round q at offset q of each pointer) into plan records,
+// one launch, and advances them with one launch.
 static int run_block(rfast_ctx* c, int32_t len, const uint8_t* d_active, const int32_t* d_delay_R,
-                     const int32_t* d_delay_C, const uint8_t* d_drop_R, const uint8_t* d_drop_C, float gamma,
-                     bool generated, uint64_t seed, const float* d_p_active, int32_t max_delay, float p_drop) {
+                     const int32_t* d_delay_C, const uint8_t* d_drop_R, const uint8_t* d_drop_C, float gamma) {
   RfastDev& d = c->d;
   if (fold_sync(c) != RFAST_OK) return RFAST_EHIP;
-  const size_t PL = (size_t)d.n + d.eR + d.eC + 1;  // a record ends with a word that is always zero
   RfastBlock blk;
   blk.rounds = len;
-  hipError_t e = hipSuccess;
+  blk.gamma = gamma_now(c, gamma);  // of the first round: a launch does not straddle a decay step
   time_begin(c, 2);
-  if (!generated) {  // uploaded schedules: every round of the launch resolved by one launch
-    d.blk_plan = c->blk_plan_base;
-    e = rfast_launch_resolve(c, d_active, d_delay_R, d_delay_C, d_drop_R, d_drop_C, len);
-  }
-  blk.gamma = gamma_now(c, gamma);
-  for (int32_t q = 0; q < len && e == hipSuccess; ++q) {
-    if (generated) {  // the generator draws one round at a time
-      d.blk_plan = c->blk_plan_base + (size_t)q * PL;
-      e = rfast_launch_generate(c, seed, d_p_active, max_delay, p_drop, false);
-      if (e == hipSuccess)
-        e = rfast_launch_resolve(c, d.gen_active, d.gen_delay_r, d.gen_delay_c, d.gen_drop_r, d.gen_drop_c);
-    }
-    c->host_round++;
-  }
+  d.blk_plan = c->blk_plan_base;
+  hipError_t e = rfast_launch_resolve(c, d_active, d_delay_R, d_delay_C, d_drop_R, d_drop_C, len);
+  c->host_round += len;
   time_end(c, 2);
   d.blk_plan = c->blk_plan_base;
   if (e == hipSuccess) {
@@ -677,7 +671,7 @@ int rfast_run(rfast_ctx* c, int32_t rounds, const uint8_t* d_active, const int32
       const int rc = run_block(c, len, d_active + (size_t)r * d.n, d_delay_R ? d_delay_R + (size_t)r * d.eR : nullptr,
                                d_delay_C ? d_delay_C + (size_t)r * d.eC : nullptr,
                                d_drop_R ? d_drop_R + (size_t)r * d.eR : nullptr,
-                               d_drop_C ? d_drop_C + (size_t)r * d.eC : nullptr, gamma, false, 0, nullptr, 0, 0.f);
+                               d_drop_C ? d_drop_C + (size_t)r * d.eC : nullptr, gamma);
       if (rc != RFAST_OK) return rc;
       r += len - 1;
       continue;
@@ -734,14 +728,6 @@ int rfast_run_generated(rfast_ctx* c, int32_t rounds, uint64_t seed, const float
   if (c->needs_init) return fail(c, RFAST_EINVAL, "rfast_init must follow rfast_set_optimizer");
   const bool graphs = c->use_graphs && !c->profiling;
   while (rounds > 0) {
-    const int32_t len = graphs ? 0 : block_length(c, rounds);
-    if (len > 0) {
-      const int rc = run_block(c, len, nullptr, nullptr, nullptr, nullptr, nullptr, gamma, true, seed, d_p_active, max_delay,
-                               p_drop);
-      if (rc != RFAST_OK) return rc;
-      rounds -= len;
-      continue;
-    }
     // a graph bakes the step size in, so a replay must not straddle a decay step of the schedule,
     // and it must hold no rebase, so it must end before the next multiple of the rebase interval
     const bool one_step_size = c->gamma_step <= 0 || c->host_round % c->gamma_step + kGraphRounds <= c->gamma_step;
@@ -758,14 +744,20 @@ int rfast_run_generated(rfast_ctx* c, int32_t rounds, uint64_t seed, const float
       const hipError_t e = hipGraphLaunch(c->graph_exec, c->stream);
       if (e != hipSuccess) return hipfail(c, e, "hipGraphLaunch");
       c->host_round += kGraphRounds;
+      c->gen_last = 0;
       rounds -= kGraphRounds;
       continue;
     }
-    const hipError_t e = rfast_launch_generate(c, seed, d_p_active, max_delay, p_drop, false);
+    // no replay: the schedule of the next stretch of rounds in one launch, then as an uploaded one
+    // (several rounds per launch where that applies, else the resolver ahead of the round kernels)
+    int32_t len = rounds < c->gen_depth ? rounds : c->gen_depth;
+    if (graphs && len > kGraphRounds) len = kGraphRounds;  // a replay may become possible again after a boundary
+    const hipError_t e = rfast_launch_generate(c, seed, d_p_active, max_delay, p_drop, false, len);
     if (e != hipSuccess) return hipfail(c, e, "schedule generator launch");
-    const int rc = rfast_round(c, d.gen_active, d.gen_delay_r, d.gen_delay_c, d.gen_drop_r, d.gen_drop_c, gamma, d.gen_batch);
+    const int rc = rfast_run(c, len, d.gen_active, d.gen_delay_r, d.gen_delay_c, d.gen_drop_r, d.gen_drop_c, gamma, d.gen_batch);
     if (rc != RFAST_OK) return rc;
-    --rounds;
+    c->gen_last = len - 1;
+    rounds -= len;
   }
   return RFAST_OK;
 }
@@ -798,6 +790,7 @@ int rfast_run_events(rfast_ctx* c, int32_t iterations, uint64_t seed, const floa
   if (e == hipSuccess) e = hipStreamSynchronize(c->stream);  // the host vector dies with this scope
   if (e != hipSuccess) return hipfail(c, e, "uploading selection thresholds");
   for (int32_t k = 0; k < iterations; ++k) {
+    c->gen_last = 0;
     e = rfast_launch_generate(c, seed, nullptr, max_delay, p_drop, true);
     if (e != hipSuccess) return hipfail(c, e, "schedule generator launch");
     const int rc = rfast_round(c, d.gen_active, d.gen_delay_r, d.gen_delay_c, d.gen_drop_r, d.gen_drop_c, gamma, d.gen_batch);
@@ -944,12 +937,15 @@ int rfast_read_state(rfast_ctx* c, int32_t field, void* host_dst, size_t bytes) 
     case RFAST_DELIV_R: src = d.deliv_r; break;
     case RFAST_DELIV_C: src = d.deliv_c; break;
     case RFAST_T_HIST: src = d.t_hist; break;
-    case RFAST_SCHED_ACTIVE: src = d.gen_active; break;
-    case RFAST_SCHED_DELAY_R: src = d.gen_delay_r; break;
-    case RFAST_SCHED_DELAY_C: src = d.gen_delay_c; break;
-    case RFAST_SCHED_DROP_R: src = d.gen_drop_r; break;
-    case RFAST_SCHED_DROP_C: src = d.gen_drop_c; break;
-    case RFAST_SCHED_BATCH: src = d.gen_batch; break;
+    // the generator's arrays hold a stretch of rounds; these fields are the last round executed
+    case RFAST_SCHED_ACTIVE: src = d.gen_active + (size_t)c->gen_last * d.n; break;
+    case RFAST_SCHED_DELAY_R: src = d.gen_delay_r + (size_t)c->gen_last * d.eR; break;
+    case RFAST_SCHED_DELAY_C: src = d.gen_delay_c + (size_t)c->gen_last * d.eC; break;
+    case RFAST_SCHED_DROP_R: src = d.gen_drop_r + (size_t)c->gen_last * d.eR; break;
+    case RFAST_SCHED_DROP_C: src = d.gen_drop_c + (size_t)c->gen_last * d.eC; break;
+    case RFAST_SCHED_BATCH:
+      src = d.gen_batch + (size_t)c->gen_last * d.n * (d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC ? 0 : d.prob.batch);
+      break;
     case RFAST_MOMENTUM: src = d.mom; break;
     default: break;
   }

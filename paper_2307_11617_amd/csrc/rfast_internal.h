@@ -131,6 +131,8 @@ struct rfast_ctx {
   char* plan_set0 = nullptr;
   size_t plan_set_bytes = 0;
   int32_t plan_set = 0;
+  int32_t gen_depth = 1;        // rounds the generator's arrays hold
+  int32_t gen_last = 0;         // which of them the last round executed used (reads of the SCHED fields)
 };
 
 enum { RFAST_MODE_FUSED = 0, RFAST_MODE_MIX = 1, RFAST_MODE_TRACK = 2 };
@@ -162,7 +164,8 @@ hipError_t rfast_launch_wave(rfast_ctx* c, const RfastBlock& blk);
 bool rfast_block_eligible(const rfast_ctx* c);  // the multi-round kernel with one tile per workgroup
 int rfast_block_lanes(const rfast_ctx* c);  // lanes per node of the multi-round kernel, 0 if no tile fits
 hipError_t rfast_launch_block(rfast_ctx* c, const RfastBlock& blk);
-hipError_t rfast_launch_generate(rfast_ctx* c, uint64_t seed, const float* d_p_active, int d_max, float p_drop, bool events);
+hipError_t rfast_launch_generate(rfast_ctx* c, uint64_t seed, const float* d_p_active, int d_max, float p_drop, bool events,
+                                 int rounds = 1);
 hipError_t rfast_launch_sync(rfast_ctx* c, int phase, float gamma, int parity);
 hipError_t rfast_launch_sync_plan(rfast_ctx* c, int rounds);
 bool rfast_sync_wave_eligible(const rfast_ctx* c);  // several synchronous steps per launch

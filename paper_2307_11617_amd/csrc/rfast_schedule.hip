@@ -30,9 +30,18 @@ __device__ inline unsigned long long threshold(float prob) {
   return (unsigned long long)floor((double)prob * 4294967296.0);
 }
 
+// blockIdx.y: the round, counted from the current one; its arrays follow those of the round before
+// (the layout rfast_run takes uploaded schedules in)
 __global__ void __launch_bounds__(256) rfast_generate_kernel(RfastDev s, uint64_t seed, const float* p_active, int d_max,
                                                              float p_drop, int B, bool events) {
-  const uint32_t r = (uint32_t)*s.round_no;
+  const uint32_t r = (uint32_t)*s.round_no + blockIdx.y;
+  const size_t y = blockIdx.y;
+  s.gen_active += y * s.n;
+  s.gen_delay_r += y * s.eR;
+  s.gen_delay_c += y * s.eC;
+  s.gen_drop_r += y * s.eR;
+  s.gen_drop_c += y * s.eC;
+  s.gen_batch += y * s.n * B;
   int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (q < s.n) {
     if (events) {
@@ -83,11 +92,13 @@ __global__ void __launch_bounds__(256) rfast_generate_kernel(RfastDev s, uint64_
 
 }  // namespace
 
-hipError_t rfast_launch_generate(rfast_ctx* c, uint64_t seed, const float* d_p_active, int d_max, float p_drop, bool events) {
+hipError_t rfast_launch_generate(rfast_ctx* c, uint64_t seed, const float* d_p_active, int d_max, float p_drop, bool events,
+                                 int rounds) {
   const RfastDev& d = c->d;
   const int B = d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC ? 0 : d.prob.batch;
   const int64_t total = (int64_t)d.n + 2 * (int64_t)d.eR + 2 * (int64_t)d.eC + (int64_t)d.n * B;
-  hipLaunchKernelGGL(rfast_generate_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, c->stream, d, seed,
-                     d_p_active, d_max, p_drop, B, events);
+  if (rounds < 1 || rounds > c->gen_depth || rounds > 65535) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(rfast_generate_kernel, dim3((unsigned)((total + 255) / 256), (unsigned)rounds), dim3(256), 0, c->stream, d,
+                     seed, d_p_active, d_max, p_drop, B, events);
   return hipGetLastError();
 }

@@ -200,7 +200,8 @@ int rfast_run(rfast_ctx* ctx, int32_t rounds, const uint8_t* d_active, const int
  *   length of samples-1, at least 1), cycle-walked into range, round keys
  *   Philox(counter (i, 5, r, 0)); round function on half R with key K:
  *   t = R*0x9E3779B1 + K; t ^= t >> 15; t *= 0x85EBCA77; F = t >> (32-h) (mod 2^32).
- * d_p_active: DEVICE fp32 [n].  max_delay in [0, D-burst+1] (RFAST_ERANGE). */
+ * The schedule of a stretch of rounds is drawn by one launch and then runs as rfast_run runs an
+ * uploaded one.  d_p_active: DEVICE fp32 [n].  max_delay in [0, D-burst+1] (RFAST_ERANGE). */
 int rfast_run_generated(rfast_ctx* ctx, int32_t rounds, uint64_t seed, const float* d_p_active,
                         int32_t max_delay, float p_drop, float gamma);
 

@@ -789,14 +789,24 @@ int rfast_run_events(rfast_ctx* c, int32_t iterations, uint64_t seed, const floa
   hipError_t e = hipMemcpyAsync(d.gen_cdf, cdf.data(), (size_t)d.n * 4, hipMemcpyHostToDevice, c->stream);
   if (e == hipSuccess) e = hipStreamSynchronize(c->stream);  // the host vector dies with this scope
   if (e != hipSuccess) return hipfail(c, e, "uploading selection thresholds");
-  for (int32_t k = 0; k < iterations; ++k) {
-    c->gen_last = 0;
-    e = rfast_launch_generate(c, seed, nullptr, max_delay, p_drop, true);
-    if (e != hipSuccess) return hipfail(c, e, "schedule generator launch");
-    const int rc = rfast_round(c, d.gen_active, d.gen_delay_r, d.gen_delay_c, d.gen_drop_r, d.gen_drop_c, gamma, d.gen_batch);
-    if (rc != RFAST_OK) return rc;
+  // A stretch of iterations drawn by one launch, then one pass per iteration with the resolver ahead (a
+  // multi-round launch, where one lane in n would work, is not what a single activation wants).
+  const int32_t blocks = c->use_blocks;
+  c->use_blocks = 0;
+  int rc = RFAST_OK;
+  for (int32_t k = 0; k < iterations && rc == RFAST_OK;) {
+    const int32_t len = iterations - k < c->gen_depth ? iterations - k : c->gen_depth;
+    e = rfast_launch_generate(c, seed, nullptr, max_delay, p_drop, true, len);
+    if (e != hipSuccess) {
+      rc = hipfail(c, e, "schedule generator launch");
+      break;
+    }
+    rc = rfast_run(c, len, d.gen_active, d.gen_delay_r, d.gen_delay_c, d.gen_drop_r, d.gen_drop_c, gamma, d.gen_batch);
+    c->gen_last = len - 1;
+    k += len;
   }
-  return RFAST_OK;
+  c->use_blocks = blocks;
+  return rc;
 }
 
 int rfast_sync_round(rfast_ctx* c, float gamma, const int32_t* d_batch_idx) {

@@ -94,9 +94,11 @@ __device__ inline void edge_decide(const RfastDev& s, int kind, int e, int r, Ed
     slot[e] = -1;
     if (s.blk_plan && !kind) s.blk_plan[s.n + e] = 0;
     if (kind) {
+      // bits 0-7 of a spill word: the slot of the version that leaves (as in the word of an active receiver)
       const bool spill = q.act_j && q.old == lo;
-      s.plan_c[e] = spill ? 1 << 18 : 0;
-      if (s.blk_plan) s.blk_plan[s.n + s.eR + e] = spill ? 1 << 18 : 0;
+      const int word = spill ? (lo % s.M) | 1 << 18 : 0;
+      s.plan_c[e] = word;
+      if (s.blk_plan) s.blk_plan[s.n + s.eR + e] = word;
       if (spill) s.node_spill[q.j] = 1;
     }
   }

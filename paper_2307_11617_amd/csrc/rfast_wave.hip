@@ -56,7 +56,6 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const bool mine = i < n && k < p;
   float4* v_l = lds4;                          // [n][M][lw]
   float4* sg_l = v_l + (size_t)n * M * lw;     // [n][M][lw]
-  float* const rt_g = s.rho_tilde + k;         // + e p: these coordinates of the S4 buffer of edge e
   // LDS addresses are byte offsets: column of the lane in a node's ring + slot * bytes per slot, one
   // 24-bit multiply-add each
   const unsigned slot_bytes = (unsigned)lw * sizeof(float4);
@@ -67,46 +66,45 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   float4 x, z, g, h, c, m = make_float4(0.f, 0.f, 0.f, 0.f);
   constexpr bool momentum = MOM;  // the optimizer variant's heavy-ball buffer is in use
   int ce0 = 0, dR = 0, dI = 0, dO = 0;
+  // The S4 buffers of the node's in-edges, in registers: a buffer matters only once its version has left
+  // the sender's ring, and the receiver's own lanes copy it from that ring in the round in which it leaves
+  // (active or not), so no other lane and no global memory is involved between load and store.
+  float4 rt[kDeg];
   float r_self = 0.f, c_self = 0.f;
   // the node's edges, in registers for the whole launch: LDS column of the sender's ring, weight,
   // position of the edge's plan word in a record; a missing edge has weight zero, the node's own
   // column and the zero word of the record
   unsigned r_col[kDeg], c_col[kDeg];
   // positions of plan words as unsigned byte offsets: a 32-bit offset from a uniform base, no 64-bit address arithmetic
-  unsigned r_pw[kDeg], c_pw[kDeg], o_pw[kDeg];
-  int o_eid[kDeg];
-  float r_w[kDeg], c_w[kDeg], o_w[kDeg];
+  unsigned r_pw[kDeg], c_pw[kDeg];
+  float r_w[kDeg], c_w[kDeg];
 #pragma unroll
   for (int u = 0; u < kDeg; ++u) {
     r_col[u] = c_col[u] = 0;
-    o_eid[u] = 0;
-    r_pw[u] = c_pw[u] = o_pw[u] = 4u * (W1 - 1);
-    r_w[u] = c_w[u] = o_w[u] = 0.f;
+    r_pw[u] = c_pw[u] = 4u * (W1 - 1);
+    r_w[u] = c_w[u] = 0.f;
+    rt[u] = make_float4(0.f, 0.f, 0.f, 0.f);
   }
   const unsigned own = (unsigned)(i * M * lw + ln) * sizeof(float4);  // this lane's column in the rings of its node
   unsigned node_pw = 4u * (W1 - 1);
   if (mine) {
     node_pw = 4u * i;
-    const int re0 = s.r_ptr[i], o0 = s.co_ptr[i];
+    const int re0 = s.r_ptr[i];
     dR = s.r_ptr[i + 1] - re0;
     ce0 = s.c_ptr[i];
     dI = s.c_ptr[i + 1] - ce0;
-    dO = s.co_ptr[i + 1] - o0;
+    dO = s.co_ptr[i + 1] - s.co_ptr[i];
     r_self = s.r_self[i];
     c_self = s.c_self[i];
 #pragma unroll
     for (int u = 0; u < kDeg; ++u) {
-      const bool hr = u < dR, hc = u < dI, ho = u < dO;
-      const int oe = ho ? s.co_eid[o0 + u] : 0;
+      const bool hr = u < dR, hc = u < dI;
       r_col[u] = (unsigned)((hr ? s.r_src[re0 + u] : i) * M * lw + ln) * sizeof(float4);
       r_w[u] = hr ? s.r_w[re0 + u] : 0.f;
       r_pw[u] = 4u * (hr ? n + re0 + u : W1 - 1);
       c_col[u] = (unsigned)((hc ? s.c_src[ce0 + u] : i) * M * lw + ln) * sizeof(float4);
       c_w[u] = hc ? s.c_w[ce0 + u] : 0.f;
       c_pw[u] = 4u * (hc ? n + s.eR + ce0 + u : W1 - 1);
-      o_w[u] = ho ? s.co_w[o0 + u] : 0.f;
-      o_pw[u] = 4u * (ho ? n + s.eR + oe : W1 - 1);
-      o_eid[u] = oe;
     }
   }
   // Plan words are read through a buffer descriptor over the records of this launch: the address is
@@ -118,12 +116,11 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   auto word = [&](int round, unsigned byte_offset) {
     return __builtin_amdgcn_raw_buffer_load_b32(plans, byte_offset, round * W1 * (int)sizeof(int), 0);
   };
-  int node_w = word(0, node_pw), r_slot[kDeg], c_pl[kDeg], o_pl[kDeg];
+  int node_w = word(0, node_pw), r_slot[kDeg], c_pl[kDeg];
 #pragma unroll
   for (int u = 0; u < kDeg; ++u) {
     r_slot[u] = word(0, r_pw[u]);
     c_pl[u] = word(0, c_pw[u]);
-    o_pl[u] = word(0, o_pw[u]);
   }
   if (mine) {
     const size_t off = (size_t)i * p + k;
@@ -132,6 +129,9 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     h = V<VEC>::ld((const float*)s.prob.data0 + off);
     c = V<VEC>::ld((const float*)s.prob.data1 + off);
     if (momentum) m = V<VEC>::ld(s.mom + off);
+#pragma unroll
+    for (int u = 0; u < kDeg; ++u)
+      if (u < dI) rt[u] = V<VEC>::ld(s.rho_tilde + (size_t)(ce0 + u) * p + k);
     // rings: eight slots of both rings (sixteen loads) in flight at a time, then into LDS
     const float* vg = s.v_ring + (size_t)i * M * p + k;
     const float* sgg = s.sigma_ring + (size_t)i * M * p + k;
@@ -164,8 +164,12 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   for (int q = 0; q < blk.rounds; ++q) {
     const bool active = node_w < 0;  // bit 31: node i is activated in this round (never set in the zero word)
     const int slot_new = slot_cur + 1 == M ? 0 : slot_cur + 1;
-    const int leaving = slot_new + 1 == M ? 0 : slot_new + 1;
-    float4 nb[kDeg], cur[kDeg], last[kDeg], sig_cur, sig_leaving;
+    float4 nb[kDeg], cur[kDeg], last[kDeg], sig_cur;
+    // S4 for a buffer whose version leaves its sender's ring in this round without the receiver consuming
+    // a newer one (bit 18; the word then names the slot of that version): copied while it is still there
+#pragma unroll
+    for (int u = 0; u < kDeg; ++u)
+      if (c_pl[u] & (1 << 18)) rt[u] = mul_s(c_w[u], at(sg_l, c_col[u], c_pl[u] & 0xFF));
     if (active) {
       // every ring value of the round in one batch of LDS reads (what a missing or idle edge reads
       // is a valid address and is not used)
@@ -177,23 +181,16 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
         cur[u] = at(sg_l, c_col[u], c_pl[u] & 0xFF);
         last[u] = at(sg_l, c_col[u], prev != 0xFF ? prev : 0);
       }
-#pragma unroll
-      for (int u = 0; u < kDeg; ++u)  // rare: the version consumed last time has left the sender's ring
-        if ((c_pl[u] & (1 << 16)) && ((c_pl[u] >> 8) & 0xFF) == 0xFF) last[u] = V<VEC>::ld(rt_g + (size_t)(ce0 + u) * p);
       sig_cur = at(sg_l, own, slot_cur);
-      sig_leaving = at(sg_l, own, leaving);
     }
-    // The plan words of the next round, from global memory, used one round from now.  Issued after the
-    // loads of the S4 buffers above: the vector memory counter is in order, so a wait for those does
-    // not wait for these.
+    // the plan words of the next round, from global memory, used one round from now
     const int qn = q + 1 < blk.rounds ? q + 1 : q;
     const int n_node = word(qn, node_pw);
-    int n_r[kDeg], n_c[kDeg], n_o[kDeg];
+    int n_r[kDeg], n_c[kDeg];
 #pragma unroll
     for (int u = 0; u < kDeg; ++u) {
       n_r[u] = word(qn, r_pw[u]);
       n_c[u] = word(qn, c_pw[u]);
-      n_o[u] = word(qn, o_pw[u]);
     }
     if (active) {
       const int t_old = node_w & 0x3FFFFFFF;
@@ -211,20 +208,14 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
       for (int u = 0; u < kDeg; ++u)
         if (c_pl[u] & (1 << 16)) {
-          z_half = track_edge(z_half, c_w[u], cur[u], last[u], ((c_pl[u] >> 8) & 0xFF) != 0xFF);
-          if (c_pl[u] & (1 << 17)) V<VEC>::st(rt_g + (size_t)(ce0 + u) * p, mul_s(c_w[u], cur[u]));
+          const bool from_ring = ((c_pl[u] >> 8) & 0xFF) != 0xFF;  // else the version consumed last time has left the ring
+          z_half = track_edge(z_half, c_w[u], cur[u], from_ring ? last[u] : rt[u], from_ring);
+          if (c_pl[u] & (1 << 17)) rt[u] = mul_s(c_w[u], cur[u]);  // consumed, and leaving the ring in this round
         }
       z_half = sub(add(z_half, g_new), g);
       // S3: publish version t+1 (slots nobody reads in this round); S2c: keep a_ii, push
       at(v_l, own, slot_new) = v;
-      if (dO > 0) {
-        at(sg_l, own, slot_new) = add(sig_cur, z_half);
-        // S4 for receivers that do not do it themselves: version t - D leaves the ring; it sits two
-        // slots ahead of the current one
-#pragma unroll
-        for (int u = 0; u < kDeg; ++u)
-          if (o_pl[u] & (1 << 18)) V<VEC>::st(rt_g + (size_t)o_eid[u] * p, mul_s(o_w[u], sig_leaving));
-      }
+      if (dO > 0) at(sg_l, own, slot_new) = add(sig_cur, z_half);
       x = x_new;
       z = mul_s(c_self, z_half);
       g = g_new;
@@ -236,7 +227,6 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     for (int u = 0; u < kDeg; ++u) {
       r_slot[u] = n_r[u];
       c_pl[u] = n_c[u];
-      o_pl[u] = n_o[u];
     }
   }
 
@@ -245,6 +235,9 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     V<VEC>::st(s.x + off, x);
     V<VEC>::st(s.z + off, z);
     if (momentum) V<VEC>::st(s.mom + off, m);
+#pragma unroll
+    for (int u = 0; u < kDeg; ++u)
+      if (u < dI) V<VEC>::st(s.rho_tilde + (size_t)(ce0 + u) * p + k, rt[u]);
     float* vg = s.v_ring + (size_t)i * M * p + k;
     float* sgg = s.sigma_ring + (size_t)i * M * p + k;
     for (int m0 = 0; m0 < M; m0 += 8) {

@@ -9,7 +9,11 @@
 // any other wavefront, the wavefronts of a CU drift out of step, and while one waits for its LDS
 // reads another computes.  The plan words of a round are read from global memory one round ahead
 // (the records of all rounds are a few KB that every wavefront of the chip reads, so they stay in the
-// caches), which leaves LDS to the rings and takes the plan reads out of the critical path.
+// caches), which leaves LDS to the rings and takes the plan reads out of the critical path.  The S4
+// buffers live in the registers of the receiving node's lanes: a buffer is needed only after its
+// version has left the sender's ring, and in the round in which it leaves the receiver's lanes copy
+// it from that ring themselves (the resolver marks the round and names the slot), whether the
+// receiver is active or not.  So the round loop touches global memory for the plan words only.
 //
 // The arithmetic is, operation for operation, that of rfast_state_kernel<FUSED> and of
 // rfast_block_kernel: the three paths give the same bits.

@@ -212,8 +212,8 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
       for (int u = 0; u < kDeg; ++u)
         if (c_pl[u] & (1 << 16)) {
-          const bool from_ring = ((c_pl[u] >> 8) & 0xFF) != 0xFF;  // else the version consumed last time has left the ring
-          z_half = track_edge(z_half, c_w[u], cur[u], from_ring ? last[u] : rt[u], from_ring);
+          if (((c_pl[u] >> 8) & 0xFF) != 0xFF) z_half = track_edge(z_half, c_w[u], cur[u], last[u], true);
+          else z_half = track_edge(z_half, c_w[u], cur[u], rt[u], false);  // the version consumed last time has left the ring
           if (c_pl[u] & (1 << 17)) rt[u] = mul_s(c_w[u], cur[u]);  // consumed, and leaving the ring in this round
         }
       z_half = sub(add(z_half, g_new), g);

@@ -120,12 +120,19 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   auto word = [&](int round, unsigned byte_offset) {
     return __builtin_amdgcn_raw_buffer_load_b32(plans, byte_offset, round * W1 * (int)sizeof(int), 0);
   };
-  int node_w = word(0, node_pw), r_slot[kDeg], c_pl[kDeg];
+  struct Plan {
+    int node, r[kDeg], c[kDeg];
+  };
+  auto fetch = [&](int round, Plan& P) {
+    P.node = word(round, node_pw);
 #pragma unroll
-  for (int u = 0; u < kDeg; ++u) {
-    r_slot[u] = word(0, r_pw[u]);
-    c_pl[u] = word(0, c_pw[u]);
-  }
+    for (int u = 0; u < kDeg; ++u) {
+      P.r[u] = word(round, r_pw[u]);
+      P.c[u] = word(round, c_pw[u]);
+    }
+  };
+  Plan plan_a, plan_b;  // two register sets that take turns: one in use, one arriving
+  fetch(0, plan_a);
   if (mine) {
     const size_t off = (size_t)i * p + k;
     x = V<VEC>::ld(s.x + off);
@@ -159,45 +166,39 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // does the ring slot of the node's current version (advanced without a division).
   int slot_cur = 0;
   if (mine) {
-    const int t0 = node_w & 0x3FFFFFFF;
+    const int t0 = plan_a.node & 0x3FFFFFFF;
     g = diag_sample<VEC>(s, h, c, x, i, t0, k);
     slot_cur = t0 % M;
   }
   wave_sync();
 
-  for (int q = 0; q < blk.rounds; ++q) {
-    const bool active = node_w < 0;  // bit 31: node i is activated in this round (never set in the zero word)
+  // one round with the plan words P, while those of the round after it arrive in N
+  auto round = [&](int q, const Plan& P, Plan& N) {
+    const bool active = P.node < 0;  // bit 31: node i is activated in this round (never set in the zero word)
     const int slot_new = slot_cur + 1 == M ? 0 : slot_cur + 1;
     float4 nb[kDeg], cur[kDeg], last[kDeg], sig_cur;
     // S4 for a buffer whose version leaves its sender's ring in this round without the receiver consuming
     // a newer one (bit 18; the word then names the slot of that version): copied while it is still there
 #pragma unroll
     for (int u = 0; u < kDeg; ++u)
-      if (c_pl[u] & (1 << 18)) rt[u] = mul_s(c_w[u], at(sg_l, c_col[u], c_pl[u] & 0xFF));
+      if (P.c[u] & (1 << 18)) rt[u] = mul_s(c_w[u], at(sg_l, c_col[u], P.c[u] & 0xFF));
     if (active) {
       // every ring value of the round in one batch of LDS reads (what a missing or idle edge reads
       // is a valid address and is not used)
 #pragma unroll
-      for (int u = 0; u < kDeg; ++u) nb[u] = at(v_l, r_col[u], r_slot[u]);
+      for (int u = 0; u < kDeg; ++u) nb[u] = at(v_l, r_col[u], P.r[u]);
 #pragma unroll
       for (int u = 0; u < kDeg; ++u) {
-        const int prev = (c_pl[u] >> 8) & 0xFF;
-        cur[u] = at(sg_l, c_col[u], c_pl[u] & 0xFF);
+        const int prev = (P.c[u] >> 8) & 0xFF;
+        cur[u] = at(sg_l, c_col[u], P.c[u] & 0xFF);
         last[u] = at(sg_l, c_col[u], prev != 0xFF ? prev : 0);
       }
       sig_cur = at(sg_l, own, slot_cur);
     }
     // the plan words of the next round, from global memory, used one round from now
-    const int qn = q + 1 < blk.rounds ? q + 1 : q;
-    const int n_node = word(qn, node_pw);
-    int n_r[kDeg], n_c[kDeg];
-#pragma unroll
-    for (int u = 0; u < kDeg; ++u) {
-      n_r[u] = word(qn, r_pw[u]);
-      n_c[u] = word(qn, c_pw[u]);
-    }
+    fetch(q + 1 < blk.rounds ? q + 1 : q, N);
     if (active) {
-      const int t_old = node_w & 0x3FFFFFFF;
+      const int t_old = P.node & 0x3FFFFFFF;
       // S1: local descent; with the optimizer variant along the heavy-ball buffer m <- beta m + z
       if (momentum) m = fma_s(s.beta, m, z);
       const float4 v = fma_s(-blk.gamma, momentum ? m : z, x);
@@ -211,10 +212,10 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       float4 z_half = z;
 #pragma unroll
       for (int u = 0; u < kDeg; ++u)
-        if (c_pl[u] & (1 << 16)) {
-          if (((c_pl[u] >> 8) & 0xFF) != 0xFF) z_half = track_edge(z_half, c_w[u], cur[u], last[u], true);
+        if (P.c[u] & (1 << 16)) {
+          if (((P.c[u] >> 8) & 0xFF) != 0xFF) z_half = track_edge(z_half, c_w[u], cur[u], last[u], true);
           else z_half = track_edge(z_half, c_w[u], cur[u], rt[u], false);  // the version consumed last time has left the ring
-          if (c_pl[u] & (1 << 17)) rt[u] = mul_s(c_w[u], cur[u]);  // consumed, and leaving the ring in this round
+          if (P.c[u] & (1 << 17)) rt[u] = mul_s(c_w[u], cur[u]);  // consumed, and leaving the ring in this round
         }
       z_half = sub(add(z_half, g_new), g);
       // S3: publish version t+1 (slots nobody reads in this round); S2c: keep a_ii, push
@@ -226,12 +227,10 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       slot_cur = slot_new;
     }
     wave_sync();  // S5: the round is over, its publications are visible to the lanes of this wavefront
-    node_w = n_node;
-#pragma unroll
-    for (int u = 0; u < kDeg; ++u) {
-      r_slot[u] = n_r[u];
-      c_pl[u] = n_c[u];
-    }
+  };
+  for (int q = 0; q < blk.rounds; q += 2) {
+    round(q, plan_a, plan_b);
+    if (q + 1 < blk.rounds) round(q + 1, plan_b, plan_a);
   }
 
   if (mine) {

@@ -68,7 +68,9 @@ __device__ inline void sincos_turns(uint32_t w, float* s, float* c) {
 }
 
 __device__ inline void box_muller(uint32_t ou, uint32_t oa, float* n0, float* n1) {
-  const float u = (float)((ou >> 8) + 1u) * (1.0f / 16777216.0f);
+  // (m + 1) 2^-24 for the 24-bit m, as one exact multiply-add (no rounding: the result has 25 bits at most
+  // only for m + 1 = 2^24, a power of two)
+  const float u = fmaf((float)(ou >> 8), 1.0f / 16777216.0f, 1.0f / 16777216.0f);
   // u lies in [2^-24, 1]: no denormal, zero or negative argument, so the hardware log2 and square
   // root (1 ulp each) serve without the range fix-ups of the library routines
   const float r = __builtin_amdgcn_sqrtf(-1.3862943611198906f * __builtin_amdgcn_logf(u));

@@ -179,9 +179,15 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     float4 nb[kDeg], cur[kDeg], last[kDeg], sig_cur;
     // S4 for a buffer whose version leaves its sender's ring in this round without the receiver consuming
     // a newer one (bit 18; the word then names the slot of that version): copied while it is still there
+    // (rare: one test for all in-edges of the node)
+    int leaving = 0;
 #pragma unroll
-    for (int u = 0; u < kDeg; ++u)
-      if (P.c[u] & (1 << 18)) rt[u] = mul_s(c_w[u], at(sg_l, c_col[u], P.c[u] & 0xFF));
+    for (int u = 0; u < kDeg; ++u) leaving |= P.c[u];
+    if (leaving & (1 << 18)) {
+#pragma unroll
+      for (int u = 0; u < kDeg; ++u)
+        if (P.c[u] & (1 << 18)) rt[u] = mul_s(c_w[u], at(sg_l, c_col[u], P.c[u] & 0xFF));
+    }
     if (active) {
       // every ring value of the round in one batch of LDS reads (what a missing or idle edge reads
       // is a valid address and is not used)
@@ -189,9 +195,9 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       for (int u = 0; u < kDeg; ++u) nb[u] = at(v_l, r_col[u], P.r[u]);
 #pragma unroll
       for (int u = 0; u < kDeg; ++u) {
-        const int prev = (P.c[u] >> 8) & 0xFF;
+        const int prev = (P.c[u] >> 8) & 0xFF;  // 0xFF: not in the ring (any slot will do, the value is not used)
         cur[u] = at(sg_l, c_col[u], P.c[u] & 0xFF);
-        last[u] = at(sg_l, c_col[u], prev != 0xFF ? prev : 0);
+        last[u] = at(sg_l, c_col[u], min(prev, M - 1));
       }
       sig_cur = at(sg_l, own, slot_cur);
     }

@@ -163,19 +163,34 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
   }
   // The stored sample of S2b is a function of (x_i, t_i); from here on it lives in registers, and so
-  // does the ring slot of the node's current version (advanced without a division).
-  int slot_cur = 0;
+  // does the LDS address of the node's current version in its v ring (advanced by one slot per activation,
+  // back to the first slot after the last: no division, no multiplication).
+  // These are LDS addresses proper (32 bits, the start of the array included), so that the access needs no
+  // further addition.
+  typedef float Vec4 __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) Vec4 LdsVec4;
+  const unsigned a_own = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds4 + own;
+  unsigned a_cur = a_own;
+  const unsigned a_end = a_own + __umul24((unsigned)M, slot_bytes), sg_off = (unsigned)n * M * slot_bytes;
+  auto own_ld = [&](unsigned a) {
+    const Vec4 t = *(LdsVec4*)(uintptr_t)a;
+    return make_float4(t.x, t.y, t.z, t.w);
+  };
+  auto own_st = [&](unsigned a, float4 w) {
+    const Vec4 t = {w.x, w.y, w.z, w.w};
+    *(LdsVec4*)(uintptr_t)a = t;
+  };
   if (mine) {
     const int t0 = plan_a.node & 0x3FFFFFFF;
     g = diag_sample<VEC>(s, h, c, x, i, t0, k);
-    slot_cur = t0 % M;
+    a_cur = a_own + __umul24((unsigned)(t0 % M), slot_bytes);
   }
   wave_sync();
 
   // one round with the plan words P, while those of the round after it arrive in N
   auto round = [&](int q, const Plan& P, Plan& N) {
     const bool active = P.node < 0;  // bit 31: node i is activated in this round (never set in the zero word)
-    const int slot_new = slot_cur + 1 == M ? 0 : slot_cur + 1;
+    const unsigned a_new = a_cur + slot_bytes == a_end ? a_own : a_cur + slot_bytes;
     float4 nb[kDeg], cur[kDeg], last[kDeg], sig_cur;
     // S4 for a buffer whose version leaves its sender's ring in this round without the receiver consuming
     // a newer one (bit 18; the word then names the slot of that version): copied while it is still there
@@ -199,7 +214,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
         cur[u] = at(sg_l, c_col[u], P.c[u] & 0xFF);
         last[u] = at(sg_l, c_col[u], min(prev, M - 1));
       }
-      sig_cur = at(sg_l, own, slot_cur);
+      sig_cur = own_ld(a_cur + sg_off);
     }
     // the plan words of the next round, from global memory, used one round from now
     fetch(q + 1 < blk.rounds ? q + 1 : q, N);
@@ -219,18 +234,24 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
       for (int u = 0; u < kDeg; ++u)
         if (P.c[u] & (1 << 16)) {
-          if (((P.c[u] >> 8) & 0xFF) != 0xFF) z_half = track_edge(z_half, c_w[u], cur[u], last[u], true);
-          else z_half = track_edge(z_half, c_w[u], cur[u], rt[u], false);  // the version consumed last time has left the ring
-          if (P.c[u] & (1 << 17)) rt[u] = mul_s(c_w[u], cur[u]);  // consumed, and leaving the ring in this round
+          // one comparison for the usual case: previous version in the ring (bits 8-15 below 0xFF), consumed
+          // version not leaving it (bit 17 clear)
+          if ((P.c[u] & 0x2FF00) < 0xFF00) {
+            z_half = track_edge(z_half, c_w[u], cur[u], last[u], true);
+          } else {
+            if (((P.c[u] >> 8) & 0xFF) != 0xFF) z_half = track_edge(z_half, c_w[u], cur[u], last[u], true);
+            else z_half = track_edge(z_half, c_w[u], cur[u], rt[u], false);  // the version consumed last time has left the ring
+            if (P.c[u] & (1 << 17)) rt[u] = mul_s(c_w[u], cur[u]);  // consumed, and leaving the ring in this round
+          }
         }
       z_half = sub(add(z_half, g_new), g);
       // S3: publish version t+1 (slots nobody reads in this round); S2c: keep a_ii, push
-      at(v_l, own, slot_new) = v;
-      if (dO > 0) at(sg_l, own, slot_new) = add(sig_cur, z_half);
+      own_st(a_new, v);
+      if (dO > 0) own_st(a_new + sg_off, add(sig_cur, z_half));
       x = x_new;
       z = mul_s(c_self, z_half);
       g = g_new;
-      slot_cur = slot_new;
+      a_cur = a_new;
     }
     wave_sync();  // S5: the round is over, its publications are visible to the lanes of this wavefront
   };

@@ -67,38 +67,43 @@ __device__ inline void sincos_turns(uint32_t w, float* s, float* c) {
   *c = __builtin_amdgcn_cosf(t);
 }
 
-__device__ inline void box_muller(uint32_t ou, uint32_t oa, float* n0, float* n1) {
+// Box-Muller on two Philox words, in polar form: radius scale * sqrt(-2 ln u) and the sine and cosine of the
+// angle, so that the caller adds radius * cos and radius * sin to its sums with one multiply-add each.
+// scale2 = scale * sqrt(2 ln 2): -2 ln u = (2 ln 2)(-log2 u), and the negation is the square root's source
+// modifier.
+__device__ inline void box_muller_polar(uint32_t ou, uint32_t oa, float scale2, float* r, float* s, float* c) {
   // (m + 1) 2^-24 for the 24-bit m, as one exact multiply-add (no rounding: the result has 25 bits at most
   // only for m + 1 = 2^24, a power of two)
   const float u = fmaf((float)(ou >> 8), 1.0f / 16777216.0f, 1.0f / 16777216.0f);
   // u lies in [2^-24, 1]: no denormal, zero or negative argument, so the hardware log2 and square
   // root (1 ulp each) serve without the range fix-ups of the library routines
-  const float r = __builtin_amdgcn_sqrtf(-1.3862943611198906f * __builtin_amdgcn_logf(u));
-  float s, c;
-  sincos_turns(oa, &s, &c);
-  *n0 = r * c;
-  *n1 = r * s;
+  *r = scale2 * __builtin_amdgcn_sqrtf(-__builtin_amdgcn_logf(u));
+  sincos_turns(oa, s, c);
 }
 
-// four normals of coordinate group q
-__device__ inline float4 noise4(uint64_t seed, uint32_t node, uint32_t version, uint64_t q) {
+// g + scale * (four normals of coordinate group q)
+__device__ inline float4 add_noise4(float4 g, float scale, uint64_t seed, uint32_t node, uint32_t version, uint64_t q) {
   uint32_t o[4];
   rfast_philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), node, version, (uint32_t)seed, (uint32_t)(seed >> 32), o);
-  float4 z;
-  box_muller(o[0], o[1], &z.x, &z.y);
-  box_muller(o[2], o[3], &z.z, &z.w);
-  return z;
+  const float scale2 = scale * 1.17741002251547469f;  // sqrt(2 ln 2)
+  float r0, s0, c0, r1, s1, c1;
+  box_muller_polar(o[0], o[1], scale2, &r0, &s0, &c0);
+  box_muller_polar(o[2], o[3], scale2, &r1, &s1, &c1);
+  return make_float4(fmaf(r0, c0, g.x), fmaf(r0, s0, g.y), fmaf(r1, c1, g.z), fmaf(r1, s1, g.w));
 }
-template <int VEC> __device__ inline typename V<VEC>::T noise_at(uint64_t seed, uint32_t node, uint32_t ver, int64_t k);
-template <> __device__ inline float4 noise_at<4>(uint64_t seed, uint32_t node, uint32_t ver, int64_t k) {
-  return noise4(seed, node, ver, (uint64_t)k >> 2);
+template <int VEC>
+__device__ inline typename V<VEC>::T add_noise(typename V<VEC>::T g, float scale, uint64_t seed, uint32_t node, uint32_t ver, int64_t k);
+template <> __device__ inline float4 add_noise<4>(float4 g, float scale, uint64_t seed, uint32_t node, uint32_t ver, int64_t k) {
+  return add_noise4(g, scale, seed, node, ver, (uint64_t)k >> 2);
 }
-template <> __device__ inline float4 noise_at<-4>(uint64_t seed, uint32_t node, uint32_t ver, int64_t k) {
-  return noise4(seed, node, ver, (uint64_t)k >> 2);
+template <> __device__ inline float4 add_noise<-4>(float4 g, float scale, uint64_t seed, uint32_t node, uint32_t ver, int64_t k) {
+  return add_noise4(g, scale, seed, node, ver, (uint64_t)k >> 2);
 }
-template <> __device__ inline float noise_at<1>(uint64_t seed, uint32_t node, uint32_t ver, int64_t k) {
-  const float4 z = noise4(seed, node, ver, (uint64_t)k >> 2);
+// one coordinate: the same instructions on its group of four, so that it gets the very bits the vector form gives it
+template <> __device__ inline float add_noise<1>(float g, float scale, uint64_t seed, uint32_t node, uint32_t ver, int64_t k) {
   const int l = (int)(k & 3);
+  const float4 g4 = make_float4(g, g, g, g);
+  const float4 z = add_noise4(g4, scale, seed, node, ver, (uint64_t)k >> 2);
   return l == 0 ? z.x : l == 1 ? z.y : l == 2 ? z.z : z.w;
 }
 
@@ -119,7 +124,7 @@ __device__ inline typename V<VEC>::T diag_sample(const RfastDev& s, typename V<V
                                                  typename V<VEC>::T x, int node, int version, int64_t k) {
   typename V<VEC>::T g = mul(h, sub(x, c));
   if (s.prob.noise_std != 0.0f)
-    g = fma_s(s.prob.noise_std, noise_at<VEC>(s.prob.noise_seed, (uint32_t)node, (uint32_t)version, k), g);
+    g = add_noise<VEC>(g, s.prob.noise_std, s.prob.noise_seed, (uint32_t)node, (uint32_t)version, k);
   if (s.wd != 0.0f) g = fma_s(s.wd, x, g);  // weight decay is part of the sampled gradient
   return g;
 }

@@ -225,9 +225,9 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       const float4 v = fma_s(-blk.gamma, momentum ? m : z, x);
       // S2a: pull the stamped neighbour copies and mix with row-stochastic weights
       float4 x_new = mul_s(r_self, v);
+      // (a missing edge has weight zero and reads the node's own ring: it adds zero, without a branch)
 #pragma unroll
-      for (int u = 0; u < kDeg; ++u)
-        if (u < dR) x_new = fma_s(r_w[u], nb[u], x_new);
+      for (int u = 0; u < kDeg; ++u) x_new = fma_s(r_w[u], nb[u], x_new);
       const float4 g_new = diag_sample<VEC>(s, h, c, x_new, i, t_old + 1, k);
       // S2b: tracker sum over the in-edges of C; S4: buffer what was consumed
       float4 z_half = z;

@@ -232,18 +232,20 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       // S2b: tracker sum over the in-edges of C; S4: buffer what was consumed
       float4 z_half = z;
 #pragma unroll
-      for (int u = 0; u < kDeg; ++u)
-        if (P.c[u] & (1 << 16)) {
-          // one comparison for the usual case: previous version in the ring (bits 8-15 below 0xFF), consumed
-          // version not leaving it (bit 17 clear)
-          if ((P.c[u] & 0x2FF00) < 0xFF00) {
-            z_half = track_edge(z_half, c_w[u], cur[u], last[u], true);
-          } else {
-            if (((P.c[u] >> 8) & 0xFF) != 0xFF) z_half = track_edge(z_half, c_w[u], cur[u], last[u], true);
-            else z_half = track_edge(z_half, c_w[u], cur[u], rt[u], false);  // the version consumed last time has left the ring
-            if (P.c[u] & (1 << 17)) rt[u] = mul_s(c_w[u], cur[u]);  // consumed, and leaving the ring in this round
-          }
+      for (int u = 0; u < kDeg; ++u) {
+        // The usual case — a live edge (bit 16) whose previous version is still in the ring (bits 8-15 below
+        // 0xFF) and whose consumed version does not leave it (bit 17 clear) — and the idle edge run through the
+        // same multiply-add, the idle edge with weight zero (it adds zero to z): no branch; the other live
+        // cases are rare and branch.
+        const unsigned key = (unsigned)P.c[u] & 0x3FF00u;
+        const float a_eff = key - 0x10000u < 0xFF00u ? c_w[u] : 0.f;
+        z_half = track_edge(z_half, a_eff, cur[u], last[u], true);
+        if (key >= 0x1FF00u) {
+          if (((P.c[u] >> 8) & 0xFF) != 0xFF) z_half = track_edge(z_half, c_w[u], cur[u], last[u], true);
+          else z_half = track_edge(z_half, c_w[u], cur[u], rt[u], false);  // the version consumed last time has left the ring
+          if (P.c[u] & (1 << 17)) rt[u] = mul_s(c_w[u], cur[u]);  // consumed, and leaving the ring in this round
         }
+      }
       z_half = sub(add(z_half, g_new), g);
       // S3: publish version t+1 (slots nobody reads in this round); S2c: keep a_ii, push
       own_st(a_new, v);

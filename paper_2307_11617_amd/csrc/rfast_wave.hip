@@ -117,8 +117,9 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // First those of round 0 (every lane: the lanes of a wavefront without a node read the zero word).
   const __amdgpu_buffer_rsrc_t plans = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<int*>(s.blk_plan), 0, blk.rounds * W1 * (int)sizeof(int), 0x00020000);
+  const int rec_bytes = W1 * (int)sizeof(int);
   auto word = [&](int round, unsigned byte_offset) {
-    return __builtin_amdgcn_raw_buffer_load_b32(plans, byte_offset, round * W1 * (int)sizeof(int), 0);
+    return __builtin_amdgcn_raw_buffer_load_b32(plans, byte_offset, round * rec_bytes, 0);
   };
   struct Plan {
     int node, r[kDeg], c[kDeg];
@@ -203,9 +204,11 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       for (int u = 0; u < kDeg; ++u)
         if (P.c[u] & (1 << 18)) rt[u] = mul_s(c_w[u], at(sg_l, c_col[u], P.c[u] & 0xFF));
     }
+    // the plan words of the next round, from global memory, used one round from now
+    fetch(min(q + 1, blk.rounds - 1), N);
     if (active) {
       // every ring value of the round in one batch of LDS reads (what a missing or idle edge reads
-      // is a valid address and is not used)
+      // is a valid address; its value is multiplied by zero)
 #pragma unroll
       for (int u = 0; u < kDeg; ++u) nb[u] = at(v_l, r_col[u], P.r[u]);
 #pragma unroll
@@ -215,10 +218,6 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
         last[u] = at(sg_l, c_col[u], min(prev, M - 1));
       }
       sig_cur = own_ld(a_cur + sg_off);
-    }
-    // the plan words of the next round, from global memory, used one round from now
-    fetch(q + 1 < blk.rounds ? q + 1 : q, N);
-    if (active) {
       const int t_old = P.node & 0x3FFFFFFF;
       // S1: local descent; with the optimizer variant along the heavy-ball buffer m <- beta m + z
       if (momentum) m = fma_s(s.beta, m, z);

@@ -119,12 +119,13 @@ __device__ inline unsigned short rfast_f32_to_bf16(float f) {
 // A pure function of (x, node, version): the "stored" sample of step S2b is recomputed
 // from the node's own x and counter wherever it is needed, with these very
 // instructions, instead of being written to and read back from memory.
-template <int VEC>
+// (WD = false: the caller knows that there is no weight decay, and the test goes away)
+template <int VEC, bool WD = true>
 __device__ inline typename V<VEC>::T diag_sample(const RfastDev& s, typename V<VEC>::T h, typename V<VEC>::T c,
                                                  typename V<VEC>::T x, int node, int version, int64_t k) {
   typename V<VEC>::T g = mul(h, sub(x, c));
   if (s.prob.noise_std != 0.0f)
     g = add_noise<VEC>(g, s.prob.noise_std, s.prob.noise_seed, (uint32_t)node, (uint32_t)version, k);
-  if (s.wd != 0.0f) g = fma_s(s.wd, x, g);  // weight decay is part of the sampled gradient
+  if (WD && s.wd != 0.0f) g = fma_s(s.wd, x, g);  // weight decay is part of the sampled gradient
   return g;
 }

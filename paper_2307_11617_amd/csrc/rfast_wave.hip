@@ -35,8 +35,8 @@ __device__ inline void wave_sync() {
 }
 
 // lw: lanes per node (64 / n, rounded down); kDeg: edge slots per node and kind; MOM: the optimizer
-// variant's heavy-ball buffer is in use (a template flag, so that the plain method carries neither
-// the registers nor the copies at the join).
+// variant is in use, heavy-ball buffer, weight decay or both (a template flag, so that the plain method
+// carries neither the registers and the copies at the join nor the tests).
 // A workgroup is one wavefront with a tile of 4 lw coordinates (two and four such wavefronts per
 // workgroup were 1.5 % and 2 % slower on 16 nodes x 11.2 M coordinates).  Occupancy is pinned to two
 // wavefronts per SIMD, which is what the LDS of a CU holds at nine ring slots: once the registers
@@ -68,7 +68,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   };
 
   float4 x, z, g, h, c, m = make_float4(0.f, 0.f, 0.f, 0.f);
-  constexpr bool momentum = MOM;  // the optimizer variant's heavy-ball buffer is in use
+  const bool momentum = MOM && s.mom != nullptr;  // the heavy-ball buffer of the optimizer variant is in use
   int ce0 = 0, dR = 0, dI = 0, dO = 0;
   // The S4 buffers of the node's in-edges, in registers: a buffer matters only once its version has left
   // the sender's ring, and the receiver's own lanes copy it from that ring in the round in which it leaves
@@ -183,7 +183,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   };
   if (mine) {
     const int t0 = plan_a.node & 0x3FFFFFFF;
-    g = diag_sample<VEC>(s, h, c, x, i, t0, k);
+    g = diag_sample<VEC, MOM>(s, h, c, x, i, t0, k);
     a_cur = a_own + __umul24((unsigned)(t0 % M), slot_bytes);
   }
   wave_sync();
@@ -227,7 +227,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       // (a missing edge has weight zero and reads the node's own ring: it adds zero, without a branch)
 #pragma unroll
       for (int u = 0; u < kDeg; ++u) x_new = fma_s(r_w[u], nb[u], x_new);
-      const float4 g_new = diag_sample<VEC>(s, h, c, x_new, i, t_old + 1, k);
+      const float4 g_new = diag_sample<VEC, MOM>(s, h, c, x_new, i, t_old + 1, k);
       // S2b: tracker sum over the in-edges of C; S4: buffer what was consumed
       float4 z_half = z;
 #pragma unroll
@@ -401,7 +401,7 @@ static hipError_t launch_wave(rfast_ctx* c, const RfastBlock& blk) {
 }
 
 hipError_t rfast_launch_wave(rfast_ctx* c, const RfastBlock& blk) {
-  if (c->d.mom) return c->max_degree <= 2 ? launch_wave<2, true>(c, blk) : launch_wave<kWaveMaxDeg, true>(c, blk);
+  if (c->d.mom || c->d.wd != 0.f) return c->max_degree <= 2 ? launch_wave<2, true>(c, blk) : launch_wave<kWaveMaxDeg, true>(c, blk);
   return c->max_degree <= 2 ? launch_wave<2, false>(c, blk) : launch_wave<kWaveMaxDeg, false>(c, blk);
 }
 

@@ -183,3 +183,12 @@ def test_odd_p_runs_one_pass_per_round_and_momentum_variant_same_bits():
     _same(a, b, "momentum")
     assert np.array_equal(a.read("MOMENTUM"), b.read("MOMENTUM"))
     assert np.abs(a.read("MOMENTUM")).max() > 0
+    # weight decay alone: the variant's kernel without a heavy-ball buffer
+    a, b = _pair(w)
+    for g in (a, b):
+        g.set_optimizer(0.0, 0.02)
+        g.init(None, None)
+    for g in (a, b):
+        g.run(40, *[dev[k] for k in ("active", "delay_R", "delay_C", "drop_R", "drop_C")], w.gamma)
+        g.check()
+    _same(a, b, "weight decay")

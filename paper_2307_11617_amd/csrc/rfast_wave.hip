@@ -347,13 +347,11 @@ __global__ void __launch_bounds__(64) rfast_sync_wave_kernel(RfastDev s, float g
     }
     float4 x_new = mul_s(r_self, v);
 #pragma unroll
-    for (int u = 0; u < kDeg; ++u)
-      if (u < dR) x_new = fma_s(r_w[u], nb[u], x_new);
+    for (int u = 0; u < kDeg; ++u) x_new = fma_s(r_w[u], nb[u], x_new);  // a missing edge: weight zero, own row
     const float4 g_new = diag_sample<VEC>(s, h, c, x_new, i, t + 1, k);
     float4 z_new = mul_s(c_self, z);
 #pragma unroll
-    for (int u = 0; u < kDeg; ++u)
-      if (u < dI) z_new = fma_s(c_w[u], zb[u], z_new);
+    for (int u = 0; u < kDeg; ++u) z_new = fma_s(c_w[u], zb[u], z_new);
     z_new = sub(add(z_new, g_new), g);
     wave_sync();  // every read of this step is done before the next one overwrites the rows
     x = x_new;

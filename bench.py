@@ -122,8 +122,11 @@ def cpu_baseline(w, seconds_target=8.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed rounds (default: the 500 rounds of config 2, the headline workload; 100 for the other configs)")
+    ap.add_argument("--warmup", type=int, default=None,
+                    help="untimed rounds before them (default 12 with config 2, so that the timed rounds end where launches are cut "
+                         "anyway, at a multiple of 512 rounds; else 10)")
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--p", type=int, default=0, help="override p (not the headline workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -164,7 +167,10 @@ def main():
     t_gen = time.perf_counter()
     w = configs.CONFIGS[args.config](**kw)
     gen_s = time.perf_counter() - t_gen
-    K, W = args.steps, args.warmup
+    # Config 2 is a run of 500 rounds: by default all of them are timed, as one launch of the multi-round kernel
+    # (launches are cut at multiples of 512 rounds, so 12 warm-up rounds put the timed 500 into one launch).
+    K = args.steps if args.steps is not None else (500 if args.config == 2 and not args.p else 100)
+    W = args.warmup if args.warmup is not None else (12 if args.config == 2 and not args.p and args.steps is None else 10)
     if args.noise_std is not None:
         w.noise_std = args.noise_std
     gpu = harness.make_gpu(w)

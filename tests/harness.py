@@ -70,7 +70,7 @@ def rel_l2(a, b, floor=0.0):
 
 def run_parity(w, rounds, every=100, coords=None, x0=None, tol=None, check_rings=True, verbose=False, rebase=False,
                momentum=0.0, weight_decay=0.0, gamma_schedule=None):
-    """Runs `rounds` rounds on both sides; at every checkpoint compares integer
+    """Runs `rounds` rounds on both sides, `every` rounds per call (or calls of the listed lengths); at every checkpoint compares integer
     state exactly and x, z (and g, rho~) in relative L2.  Returns the worst errors.
     momentum / weight_decay / gamma_schedule = (step_rounds, factor): the optimizer variant."""
     from oracle.rfast_oracle import step_gamma
@@ -92,8 +92,14 @@ def run_parity(w, rounds, every=100, coords=None, x0=None, tol=None, check_rings
     worst = {"x": 0.0, "z": 0.0, "g": 0.0}
     g0 = gpu.read("G")[:, sel]
     assert rel_l2(g0, orc.g) < 1e-5, ("initial gradient", rel_l2(g0, orc.g))
-    for r0 in range(0, rounds, every):
-        r1 = min(r0 + every, rounds)
+    # every: rounds per call, or the lengths of the calls one by one
+    if isinstance(every, int):
+        cuts = [(r0, min(r0 + every, rounds)) for r0 in range(0, rounds, every)]
+    else:
+        ends = np.cumsum(every)
+        assert ends[-1] == rounds
+        cuts = list(zip([0] + [int(e) for e in ends[:-1]], [int(e) for e in ends]))
+    for r0, r1 in cuts:
         st, dev = upload_chunk(gpu, w, r0, r1)
         gpu.run(r1 - r0, dev["active"], dev["delay_R"], dev["delay_C"], dev["drop_R"], dev["drop_C"], w.gamma,
                 dev["batch_idx"])

@@ -34,6 +34,15 @@ def test_config2_full_sampled():
     _report(w.name + f" ({c.size} sampled coordinates)", worst)
 
 
+def test_config2_full_sampled_in_the_launches_of_the_benchmark():
+    """bench.py's default: 12 warm-up rounds, then the 500 rounds of the workload as one call, which is one
+    launch of the multi-round kernel ending at round 512 (where the automatic rebase falls due)."""
+    w = configs.config2()
+    c = _coords(w.p, 173 * 8)
+    worst, orc, gpu = harness.run_parity(w, 512, every=[12, 500], coords=c, verbose=True)
+    _report(w.name + f" ({c.size} sampled coordinates, calls of 12 and 500 rounds)", worst)
+
+
 def test_config3_full_sampled():
     w = configs.config3()
     c = _coords(w.p, 173)

@@ -16,7 +16,10 @@
 // receiver is active or not.  So the round loop touches global memory for the plan words only.
 //
 // The arithmetic is, operation for operation, that of rfast_state_kernel<FUSED> and of
-// rfast_block_kernel: the three paths give the same bits.
+// rfast_block_kernel: the three paths give the same bits.  (One liberty: where those skip a missing
+// or idle edge, this kernel runs it through the multiply-add with weight zero, which spares the round
+// loop most of its branches.  Adding zero changes nothing but the sign of a sum that is exactly zero,
+// as long as the ring values are finite.)
 #include "rfast_vec.h"
 
 namespace {

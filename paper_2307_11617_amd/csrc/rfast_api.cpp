@@ -619,6 +619,10 @@ static int run_block(rfast_ctx* c, int32_t len, const uint8_t* d_active, const i
   if (fold_sync(c) != RFAST_OK) return RFAST_EHIP;
   RfastBlock blk;
   blk.rounds = len;
+  // a rebase that falls due when these rounds are done costs the wavefront-tile kernel nothing: it shifts the
+  // running sums while it writes its tiles back (the other kernel is followed by the rebase kernel)
+  const bool rebase_due = c->rebase_interval > 0 && (c->host_round + len) % c->rebase_interval == 0;
+  blk.rebase = rebase_due && rfast_wave_eligible(c) ? 1 : 0;
   blk.gamma = gamma_now(c, gamma);  // of the first round: a launch does not straddle a decay step
   time_begin(c, 2);
   d.blk_plan = c->blk_plan_base;
@@ -633,7 +637,7 @@ static int run_block(rfast_ctx* c, int32_t len, const uint8_t* d_active, const i
   }
   d.blk_plan = nullptr;
   if (e != hipSuccess) return hipfail(c, e, "multi-round launch");
-  if (c->rebase_interval > 0 && c->host_round % c->rebase_interval == 0) {
+  if (rebase_due && !blk.rebase) {
     e = rfast_launch_rebase(c);
     if (e != hipSuccess) return hipfail(c, e, "rebase launch");
   }

@@ -149,6 +149,7 @@ constexpr int kResolveAhead = 32;
 struct RfastBlock {
   float gamma;                // step size of its rounds (a launch does not straddle a decay step)
   int32_t rounds;             // 1 .. kBlockRounds
+  int32_t rebase;             // wavefront-tile kernel: the running sums are rebased as the tiles are written back
 };
 
 // launchers (each enqueues on ctx->stream and returns a hipError_t)

@@ -268,14 +268,15 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     if (q + 1 < blk.rounds) round(q + 1, plan_b, plan_a);
   }
 
+  // Write-back.  With blk.rebase the running sums are rebased on the way (what rfast_rebase_kernel does, and with
+  // its operations): sender j's latest sum leaves every slot of its ring, and a_ij times it every buffer it feeds.
+  float4 base = make_float4(0.f, 0.f, 0.f, 0.f);
   if (mine) {
     const size_t off = (size_t)i * p + k;
     V<VEC>::st(s.x + off, x);
     V<VEC>::st(s.z + off, z);
     if (momentum) V<VEC>::st(s.mom + off, m);
-#pragma unroll
-    for (int u = 0; u < kDeg; ++u)
-      if (u < dI) V<VEC>::st(s.rho_tilde + (size_t)(ce0 + u) * p + k, rt[u]);
+    if (blk.rebase && dO > 0) base = own_ld(a_cur + sg_off);  // nobody reads the sums of a node without out-edges
     float* vg = s.v_ring + (size_t)i * M * p + k;
     float* sgg = s.sigma_ring + (size_t)i * M * p + k;
     for (int m0 = 0; m0 < M; m0 += 8) {
@@ -285,6 +286,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
         if (m0 + u < M) {
           tv[u] = at(v_l, own, m0 + u);
           ts[u] = at(sg_l, own, m0 + u);
+          if (blk.rebase && dO > 0) ts[u] = sub(ts[u], base);
         }
 #pragma unroll
       for (int u = 0; u < 8; ++u)
@@ -293,6 +295,21 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
           V<VEC>::st(sgg + (size_t)(m0 + u) * p, ts[u]);
         }
     }
+  }
+  if (blk.rebase) {
+    // every node's latest sum to its receivers, through slot 0 of its v ring (whose contents are on their way out)
+    if (mine) at(v_l, own, 0) = base;
+    wave_sync();
+    if (mine) {
+#pragma unroll
+      for (int u = 0; u < kDeg; ++u)
+        if (u < dI) rt[u] = sub(rt[u], mul_s(c_w[u], at(v_l, c_col[u], 0)));
+    }
+  }
+  if (mine) {
+#pragma unroll
+    for (int u = 0; u < kDeg; ++u)
+      if (u < dI) V<VEC>::st(s.rho_tilde + (size_t)(ce0 + u) * p + k, rt[u]);
   }
 }
 

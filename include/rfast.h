@@ -273,7 +273,9 @@ int rfast_rebase(rfast_ctx* ctx);
  * (logistic regression at p = 4096: 1e-4 relative after about 3500 rounds), with
  * it linearly and about a hundred times more slowly.  One rebase costs about one
  * and a half rounds of a sparse graph (2(D+2) + 2 dO + 1 words per coordinate
- * per sender), i.e. 0.3 % of a run at the default. */
+ * per sender), i.e. 0.3 % of a run at the default; where the wavefront-tile kernel
+ * of rfast_use_blocks ends a launch at such a round it rebases while it writes its
+ * tiles back, at no cost. */
 int rfast_set_rebase_interval(rfast_ctx* ctx, int32_t rounds);
 
 /* Optimizer variant.  The large-scale experiment of the paper (Section

@@ -179,6 +179,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   typedef __attribute__((address_space(3))) Vec4 LdsVec4;
   const unsigned a_own = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds4 + own;
   unsigned a_cur = a_own;
+  int ver_next = 1;  // version of the node's next activation (counted here: the plan's copy would need a mask and an add)
   const unsigned a_end = a_own + __umul24((unsigned)M, slot_bytes), sg_off = (unsigned)n * M * slot_bytes;
   auto own_ld = [&](unsigned a) {
     const Vec4 t = *(LdsVec4*)(uintptr_t)a;
@@ -192,6 +193,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int t0 = plan_a.node & 0x3FFFFFFF;
     g = diag_sample<VEC, MOM>(s, h, c, x, i, t0, k);
     a_cur = a_own + __umul24((unsigned)(t0 % M), slot_bytes);
+    ver_next = t0 + 1;
   }
   wave_sync();
 
@@ -225,7 +227,6 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
         last[u] = at(sg_l, c_col[u], min(prev, M - 1));
       }
       sig_cur = own_ld(a_cur + sg_off);
-      const int t_old = P.node & 0x3FFFFFFF;
       // S1: local descent; with the optimizer variant along the heavy-ball buffer m <- beta m + z
       if (momentum) m = fma_s(s.beta, m, z);
       const float4 v = fma_s(-blk.gamma, momentum ? m : z, x);
@@ -234,7 +235,8 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       // (a missing edge has weight zero and reads the node's own ring: it adds zero, without a branch)
 #pragma unroll
       for (int u = 0; u < kDeg; ++u) x_new = fma_s(r_w[u], nb[u], x_new);
-      const float4 g_new = diag_sample<VEC, MOM>(s, h, c, x_new, i, t_old + 1, k);
+      const float4 g_new = diag_sample<VEC, MOM>(s, h, c, x_new, i, ver_next, k);
+      ++ver_next;
       // S2b: tracker sum over the in-edges of C; S4: buffer what was consumed
       float4 z_half = z;
 #pragma unroll

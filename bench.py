@@ -291,6 +291,12 @@ def main():
                                "traffic": hbm["traffic"],
                                "source": "VALU instructions per round from the committed counter summary (SQ_INSTS_VALU) "
                                          "x rounds / kernel time measured here with HIP events"}
+            # for context, the arithmetic of the method alone against the fp32 vector peak: about 40 flops per
+            # coordinate and node-update (Algorithm 1 with two in-edges per graph: 21; the rest the float side of
+            # the noise), the integer work of the counter-based generator not counted
+            flops = 40.0 * w.p * float(act_prof.sum())
+            out["roofline"]["algorithmic_tflops"] = flops / (ms_state * 1e-3) / 1e12
+            out["roofline"]["algorithmic_frac_of_fp32_vector_peak"] = out["roofline"]["algorithmic_tflops"] / 157.3
     if w.objective == "softmax_bf16":
         # the two GEMMs of the softmax gradient: 2*B*d*K flops each per node-update
         flops = 4.0 * w.sched.batch * w.extra["d"] * w.extra["K"] * float(act_prof.sum())

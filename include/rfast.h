@@ -96,7 +96,10 @@ typedef enum rfast_field {
   RFAST_G = 2,         /* fp32 [n][p]  stored gradient sample of each node.  For the diagonal quadratic the
                           sample is a pure function of (x_i, t_i): it is recomputed where needed and on
                           read; writing it is accepted and has no effect                              */
-  RFAST_V_RING = 3,    /* fp32 [n][D+2][p]  slot s of node j = version t, t mod (D+2) == s */
+  RFAST_V_RING = 3,    /* fp32 [n][D+2][p]  slot s of node j = version t, t mod (D+2) == s.  In the three ring
+                          fields a slot whose version no receiver can pick up any more (stamps never go
+                          back, S2a / S2b: it is older than every stamp held on its sender's out-edges of
+                          that graph) reads as zeros; the library does not keep such slots up to date */
   RFAST_RHO_RING = 4,  /* fp32 [nnzC_off][D+2][p]  sender-side running sums rho_ij = a_ij * sigma_j (expanded on read) */
   RFAST_RHO_TILDE = 5, /* fp32 [nnzC_off][p]  receiver-side buffers (assembled on read: a buffer whose version
                           is still in its sender's ring is taken from there, cf. RFAST_SIGMA_RING)   */
@@ -243,6 +246,11 @@ int rfast_use_blocks(rfast_ctx* ctx, int32_t on);
  * else the number of lanes per node of the multi-round kernel (its tile is 4 * lanes coordinates);
  * *tile_per_wavefront (may be NULL) = 1 if a tile belongs to one wavefront, 0 if to a workgroup. */
 int rfast_block_info(rfast_ctx* ctx, int32_t* lanes_per_node, int32_t* tile_per_wavefront);
+/* Tuning knob of the wavefront-tile kernel of rfast_use_blocks: wavefronts per workgroup (1, 2 or 4; 0 = chosen by
+ * the library).  The wavefronts of a workgroup own neighbouring tiles and move their rings between HBM and LDS
+ * together, so a row segment of a load or store is that many times as wide; the rounds themselves are unaffected
+ * and the results are the same bits.  A value whose tiles do not fit the LDS of a CU falls back to 1. */
+int rfast_set_tile_group(rfast_ctx* ctx, int32_t wavefronts);
 
 /* One step of the synchronous push-pull recursion the method is developed from
  * (eq. (2) of the paper), on the same x, z and stored gradient samples:

@@ -33,7 +33,7 @@ RFAST_FIELDS = {"X": 0, "Z": 1, "G": 2, "V_RING": 3, "RHO_RING": 4, "RHO_TILDE":
                 "TAU_C": 8, "SLOT_R": 9, "SLOT_C": 10, "ROUND": 11, "SIGMA_RING": 12, "DELIV_R": 13, "DELIV_C": 14,
                 "T_HIST": 15, "SCHED_ACTIVE": 16, "SCHED_DELAY_R": 17, "SCHED_DELAY_C": 18, "SCHED_DROP_R": 19,
                 "SCHED_DROP_C": 20, "SCHED_BATCH": 21, "MOMENTUM": 22}
-EXPORTS = ["rfast_common_roots", "rfast_workspace_bytes", "rfast_create", "rfast_init", "rfast_round", "rfast_run", "rfast_run_generated", "rfast_run_events", "rfast_use_graphs", "rfast_use_blocks", "rfast_block_info", "rfast_sync_round", "rfast_sync_run", "rfast_rebase", "rfast_set_rebase_interval", "rfast_set_optimizer", "rfast_set_gamma_schedule", "rfast_check",
+EXPORTS = ["rfast_common_roots", "rfast_workspace_bytes", "rfast_create", "rfast_init", "rfast_round", "rfast_run", "rfast_run_generated", "rfast_run_events", "rfast_use_graphs", "rfast_use_blocks", "rfast_block_info", "rfast_set_tile_group", "rfast_sync_round", "rfast_sync_run", "rfast_rebase", "rfast_set_rebase_interval", "rfast_set_optimizer", "rfast_set_gamma_schedule", "rfast_check",
            "rfast_read_state", "rfast_write_state", "rfast_diagnostics", "rfast_profile_enable", "rfast_kernel_time", "rfast_last_error",
            "rfast_destroy"]
 
@@ -66,6 +66,8 @@ def lib():
     L.rfast_run_events.argtypes = [vp, i32, C.c_uint64, vp, i32, C.c_float, C.c_float]
     L.rfast_block_info.restype = C.c_int
     L.rfast_block_info.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    L.rfast_set_tile_group.restype = C.c_int
+    L.rfast_set_tile_group.argtypes = [vp, i32]
     L.rfast_use_blocks.restype = C.c_int
     L.rfast_use_blocks.argtypes = [vp, i32]
     L.rfast_use_graphs.restype = C.c_int
@@ -174,6 +176,10 @@ def rfast_block_info(ctx, with_kind=False):
     lanes, wave = C.c_int32(0), C.c_int32(0)
     _chk(lib().rfast_block_info(ctx, C.byref(lanes), C.byref(wave)), ctx)
     return (lanes.value, bool(wave.value)) if with_kind else lanes.value
+
+
+def rfast_set_tile_group(ctx, wavefronts=0):
+    _chk(lib().rfast_set_tile_group(ctx, wavefronts), ctx)
 
 
 def rfast_use_blocks(ctx, on=True):

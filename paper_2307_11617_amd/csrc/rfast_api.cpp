@@ -34,7 +34,7 @@ struct Offsets {
   size_t x, z, g, v_ring, sigma_ring, rho_tilde;
   size_t r_ptr, r_src, r_dst, r_w, r_self, c_ptr, c_src, c_dst, c_w, c_self, co_ptr, co_eid, co_w, ro_ptr, ro_eid;
   size_t t, t_hist, tau_r, tau_c, deliv_r, deliv_c, round_no, err;
-  size_t n_active, active_plan, plan_t, slot_r, slot_c, plan_c, node_spill, plan_set_bytes, blk_plan;
+  size_t n_active, active_plan, plan_t, slot_r, slot_c, plan_c, node_spill, plan_set_bytes, blk_plan, blk_head;
   size_t gen_active, gen_delay_r, gen_delay_c, gen_drop_r, gen_drop_c, gen_batch, gen_cdf;
   int32_t gen_depth;
   size_t xbar, resid, gscratch, diag;
@@ -101,6 +101,7 @@ Offsets layout(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, cons
   o.plan_set_bytes = L.total - o.n_active;
   (void)L.take((size_t)(kResolveAhead - 1) * o.plan_set_bytes);
   o.blk_plan = L.take((size_t)kBlockRounds * ((size_t)n + eR + eC + 1) * 4);
+  o.blk_head = L.take((2 * (size_t)n + eC) * 4);
   // the generator draws the schedule of up to gen_depth rounds per launch (as many as fit 64 MB, at most kBlockRounds)
   const size_t gen_rows = (size_t)n * (size_t)(prob->kind == RFAST_OBJ_DIAG_QUADRATIC ? 0 : prob->batch);
   const size_t gen_round = (size_t)n + 5 * (eR + eC) + 4 * gen_rows;
@@ -258,6 +259,29 @@ size_t field_bytes(const rfast_ctx* c, int32_t field) {
     case RFAST_MOMENTUM: return d.mom ? d.n * vec : (size_t)-1;
     default: return (size_t)-1;
   }
+}
+
+// Ring slots whose version no receiver can pick up any more: stamps never go back, so a version older
+// than every stamp held on its sender's out-edges (all versions, if the sender has none) is dead.  The
+// kernels are free not to keep such slots up to date; reads of the ring fields return them as zeros.
+// `ring` is a host copy of `rings` rings of [M][p] floats, ring q belonging to sender sender_of[q].
+hipError_t zero_dead_slots(const rfast_ctx* c, bool sums, float* ring, int rings, const int32_t* sender_of) {
+  const RfastDev& d = c->d;
+  const int E = sums ? d.eC : d.eR;
+  std::vector<int32_t> t(d.n), src(E), tau(E), lo(d.n, 0x7fffffff);
+  hipError_t e = hipMemcpy(t.data(), d.t, (size_t)d.n * 4, hipMemcpyDeviceToHost);
+  if (e == hipSuccess && E) e = hipMemcpy(src.data(), sums ? d.c_src : d.r_src, (size_t)E * 4, hipMemcpyDeviceToHost);
+  if (e == hipSuccess && E) e = hipMemcpy(tau.data(), sums ? d.tau_c : d.tau_r, (size_t)E * 4, hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return e;
+  for (int q = 0; q < E; ++q) lo[src[q]] = std::min(lo[src[q]], tau[q]);
+  for (int q = 0; q < rings; ++q) {
+    const int j = sender_of ? sender_of[q] : q;
+    for (int m = 0; m < d.M; ++m) {
+      const int back = ((t[j] - m) % d.M + d.M) % d.M, ver = t[j] - back;  // version held by slot m
+      if (ver < lo[j]) memset(ring + ((size_t)q * d.M + m) * d.p, 0, (size_t)d.p * 4);
+    }
+  }
+  return hipSuccess;
 }
 
 void time_begin(rfast_ctx* c, int which) {
@@ -450,7 +474,9 @@ int rfast_create(rfast_ctx** out, int32_t n, int64_t p, const int32_t* R_rowptr,
   d.plan_t = (int32_t*)(b + o.plan_t); d.slot_r = (int32_t*)(b + o.slot_r); d.slot_c = (int32_t*)(b + o.slot_c);
   d.plan_c = (int32_t*)(b + o.plan_c); d.node_spill = (uint8_t*)(b + o.node_spill);
   d.blk_plan = nullptr;
+  d.blk_head = nullptr;
   c->blk_plan_base = (int32_t*)(b + o.blk_plan);
+  c->blk_head_base = (int32_t*)(b + o.blk_head);
   c->plan_set0 = b + o.n_active;
   c->plan_set_bytes = o.plan_set_bytes;
   c->plan_set = 0;
@@ -626,16 +652,17 @@ static int run_block(rfast_ctx* c, int32_t len, const uint8_t* d_active, const i
   blk.gamma = gamma_now(c, gamma);  // of the first round: a launch does not straddle a decay step
   time_begin(c, 2);
   d.blk_plan = c->blk_plan_base;
+  d.blk_head = c->blk_head_base;
   hipError_t e = rfast_launch_resolve(c, d_active, d_delay_R, d_delay_C, d_drop_R, d_drop_C, len);
   c->host_round += len;
   time_end(c, 2);
-  d.blk_plan = c->blk_plan_base;
   if (e == hipSuccess) {
     time_begin(c, 0);
     e = rfast_wave_eligible(c) ? rfast_launch_wave(c, blk) : rfast_launch_block(c, blk);
     time_end(c, 0);
   }
   d.blk_plan = nullptr;
+  d.blk_head = nullptr;
   if (e != hipSuccess) return hipfail(c, e, "multi-round launch");
   if (rebase_due && !blk.rebase) {
     e = rfast_launch_rebase(c);
@@ -649,6 +676,14 @@ int rfast_block_info(rfast_ctx* c, int32_t* lanes_per_node, int32_t* tile_per_wa
   const bool taken = block_length(c, kBlockRounds) > 0, wave = rfast_wave_eligible(c);
   *lanes_per_node = taken ? (wave ? rfast_wave_lanes(c) : rfast_block_lanes(c)) : 0;
   if (tile_per_wavefront) *tile_per_wavefront = taken && wave ? 1 : 0;
+  return RFAST_OK;
+}
+
+int rfast_set_tile_group(rfast_ctx* c, int32_t wavefronts) {
+  if (!c) return RFAST_EINVAL;
+  if (wavefronts != 0 && wavefronts != 1 && wavefronts != 2 && wavefronts != 4)
+    return fail(c, RFAST_EINVAL, "wavefronts per workgroup must be 0 (automatic), 1, 2 or 4");
+  c->wave_group = wavefronts;
   return RFAST_OK;
 }
 
@@ -976,6 +1011,7 @@ int rfast_read_state(rfast_ctx* c, int32_t field, void* host_dst, size_t bytes) 
       e = hipMemcpy(dst, d.sigma_ring + (size_t)src_h[q] * ring, ring * 4, hipMemcpyDeviceToHost);
       for (size_t k = 0; k < ring; ++k) dst[k] = w_h[q] * dst[k];
     }
+    if (e == hipSuccess) e = zero_dead_slots(c, true, (float*)host_dst, d.eC, src_h.data());
   } else if (field == RFAST_RHO_TILDE) {
     // rho~_ij = a_ij * sigma_j[tau_ij] lives in the sender's ring while tau_ij >= t_j - D and in the
     // array otherwise: put the two together
@@ -1008,6 +1044,8 @@ int rfast_read_state(rfast_ctx* c, int32_t field, void* host_dst, size_t bytes) 
       e = hipMemcpy((char*)host_dst + i * vec, (const char*)d.g + ((size_t)(t[i] & 1) * d.n + i) * vec, vec, hipMemcpyDeviceToHost);
   } else {
     e = hipMemcpy(host_dst, src, bytes, hipMemcpyDeviceToHost);
+    if (e == hipSuccess && (field == RFAST_V_RING || field == RFAST_SIGMA_RING))
+      e = zero_dead_slots(c, field == RFAST_SIGMA_RING, (float*)host_dst, d.n, nullptr);
   }
   if (e != hipSuccess) return hipfail(c, e, "copying state to host");
   return RFAST_OK;

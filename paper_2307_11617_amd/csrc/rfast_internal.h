@@ -83,6 +83,12 @@ struct RfastDev {
   // in LDS over several rounds (NULL: not wanted): [n] node words (bit 31 active, low 30 bits the
   // counter at the start of the round), [eR] ring slot per R edge, [eC] plan word per C edge.
   int32_t* blk_plan;
+  // What a multi-round launch needs to know about the state before its first round, written by the
+  // resolver ahead of the rounds it resolves (NULL: not wanted): [n] the oldest version of node j's v
+  // ring that a receiver can still pick up (the smallest stamp held on j's out-edges over R; INT_MAX
+  // if j has none), [n] the same for its ring of running sums (out-edges over C), [eC] 1 if the S4
+  // buffer of the edge lives in the rho_tilde array (its version has left the sender's ring), else 0.
+  int32_t* blk_head;
   // schedule of the current round when it is generated on the device
   uint8_t* gen_active;    // [n]
   int32_t* gen_delay_r;   // [eR]
@@ -125,7 +131,9 @@ struct rfast_ctx {
   float gamma_factor = 1.f;
   bool needs_init = false;      // rfast_set_optimizer was called and rfast_init has not followed yet
   int32_t use_blocks = 1;       // 1: where it pays, 2: wherever possible; rfast_run / rfast_run_generated may advance several rounds per launch
+  int32_t wave_group = 0;       // wavefronts per workgroup of the wavefront-tile kernel (0: chosen by the launcher)
   int32_t* blk_plan_base = nullptr;  // kBlockRounds plan records
+  int32_t* blk_head_base = nullptr;  // 2 n + eC words, see RfastDev::blk_head
   int32_t max_degree = 0;       // most in-edges of R, in-edges of C or out-edges of C at any node
   // the per-round plan arrays of RfastDev exist kResolveAhead times; `plan_set` is the set d points at
   char* plan_set0 = nullptr;

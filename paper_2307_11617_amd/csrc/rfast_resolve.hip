@@ -116,6 +116,20 @@ __device__ inline void edge_decide(const RfastDev& s, int kind, int e, int r, Ed
   }
 }
 
+// The state before the first round of a multi-round launch, for the kernel that moves the rings
+// (RfastDev::blk_head).  Called by every lane of the one workgroup, before any round is resolved.
+__device__ inline void block_head(const RfastDev& s) {
+  for (int q = threadIdx.x; q < 2 * s.n; q += blockDim.x) s.blk_head[q] = 0x7fffffff;
+  __syncthreads();
+  for (int e = threadIdx.x; e < s.eR; e += blockDim.x) atomicMin(&s.blk_head[s.r_src[e]], s.tau_r[e]);
+  for (int e = threadIdx.x; e < s.eC; e += blockDim.x) {
+    const int j = s.c_src[e], tau = s.tau_c[e];
+    atomicMin(&s.blk_head[s.n + j], tau);
+    s.blk_head[2 * s.n + e] = tau < s.t[j] - (s.M - 2) ? 1 : 0;
+  }
+  __syncthreads();  // the rounds below move the stamps and the counters
+}
+
 constexpr int kResolveThreads = 1024;
 constexpr int kAhead = 2;  // edges per lane whose loads are issued before the node pass
 
@@ -137,6 +151,7 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev
   const int r0 = *s.round_no;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int E = s.eR + s.eC;
+  if (s.blk_head) block_head(s);
   for (int rq = 0; rq < rounds; ++rq) {
     const int r = r0 + rq;
     EdgeIn ahead[kAhead];
@@ -241,6 +256,7 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_cached_kernel(R
   uint8_t* act_l = reinterpret_cast<uint8_t*>(sched_l + (size_t)rounds * E + ((size_t)rounds * E & 1));  // [rounds][n]
   const int r0 = *s.round_no;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (s.blk_head) block_head(s);
   for (int w = threadIdx.x; w < rounds * E; w += kResolveThreads) {
     const int q = w / E, e = w - q * E;
     const bool kind = e >= s.eR;

@@ -20,6 +20,8 @@
 // or idle edge, this kernel runs it through the multiply-add with weight zero, which spares the round
 // loop most of its branches.  Adding zero changes nothing but the sign of a sum that is exactly zero,
 // as long as the ring values are finite.)
+#include <algorithm>
+
 #include "rfast_vec.h"
 
 namespace {
@@ -41,37 +43,82 @@ __device__ inline void wave_sync() {
 // lw: lanes per node (64 / n, rounded down); kDeg: edge slots per node and kind; MOM: the optimizer
 // variant is in use, heavy-ball buffer, weight decay or both (a template flag, so that the plain method
 // carries neither the registers and the copies at the join nor the tests).
-// A workgroup is one wavefront with a tile of 4 lw coordinates (two and four such wavefronts per
-// workgroup were 1.5 % and 2 % slower on 16 nodes x 11.2 M coordinates).  Occupancy is pinned to two
-// wavefronts per SIMD, which is what the LDS of a CU holds at nine ring slots: once the registers
-// allowed three, the eight wavefronts of a CU were spread unevenly over its SIMDs and the launch
-// took 4 % longer.
-template <int kDeg, bool MOM>
-__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) rfast_wave_kernel(RfastDev s, RfastBlock blk, int lw) {
+// W: wavefronts per workgroup.  Every wavefront still owns a tile of 4 lw coordinates and runs its
+// rounds without looking at the others; the W tiles of a workgroup are neighbours, and the workgroup
+// moves their rings between HBM and LDS together, so that a row segment is W times as wide (16 nodes,
+// W = 2: 128 B, a whole cache line per row; with one wavefront per workgroup every load and store
+// instruction touched 16 half lines).  The barriers this costs stand before and after the round loop,
+// not in it.
+// (A persistent grid, as many workgroups as the chip holds with each streaming through a region of
+// its own, was measured and dropped: its workgroups run in step, so that all of them move tiles at one
+// time and compute at another, and a launch of 20 rounds took 10.9 ms against 8.6 ms.)
+// Occupancy is pinned to two wavefronts per SIMD, which is what the LDS of a CU holds at nine ring
+// slots: once the registers allowed three, the eight wavefronts of a CU were spread unevenly over
+// its SIMDs and the launch took 4 % longer.
+//
+// Only what can matter is moved.  Stamps never go back (S2a / S2b take the largest stamp received), so
+// a version older than every stamp held on its sender's out-edges will never be read again: such a
+// slot is neither loaded (LDS gets zeros, which the multiply-adds with weight zero need to be finite)
+// nor, if the launch wrote it and it is out of reach again by the end, stored; slots the launch did
+// not write are not stored either, nor x and z of a node it never activated, and an S4 buffer is moved
+// only while its version is outside its sender's ring.  With the delays of the bidirectional-ring
+// workload that is 30 rows per node instead of 46.
+template <int kDeg, bool MOM, int W>
+__global__ void __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 2))) rfast_wave_kernel(RfastDev s, RfastBlock blk, int lw) {
   constexpr int VEC = 4;
   extern __shared__ float4 lds4[];
   const int n = s.n, M = s.M;
   const int64_t p = s.p;
   const int W1 = n + s.eR + s.eC + 1;  // words of a plan record; the last one is always zero
-  const int lane = threadIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i = lane / lw, ln = lane - i * lw;
-  // Workgroup b runs on XCD b mod 8, each with an L2 of its own.  A tile row of 4 lw coordinates can be
-  // half a cache line (16 nodes: 64 B), so neighbouring tiles go to the same XCD, one right after the
-  // other: the second finds the line in that L2 instead of fetching it from HBM again.  Runs of 64 tiles
-  // (4 KB of every row on 16 nodes) also keep the rows that an XCD moves at one time on few pages: a
-  // launch of 10 rounds, which is all moving, takes 8.1 ms with them and 9.3 ms with runs of 4.
+  // Workgroup b runs on XCD b mod 8, each with an L2 of its own.  Neighbouring workgroups go to the same
+  // XCD, one right after the other, in runs that cover kTileRun tiles (4 KB of every row on 16 nodes):
+  // that keeps the rows an XCD moves at one time on few pages (a launch of 10 rounds, which is all moving,
+  // took 8.1 ms with such runs and 9.3 ms with runs of 4 tiles), and where a row segment is less than a
+  // cache line the neighbour finds the other part in that L2.
+  constexpr unsigned kRun = kTileRun / W;
   const unsigned xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
-  const int64_t tile = ((int64_t)(slot / kTileRun) * kXcds + xcd) * kTileRun + slot % kTileRun;
-  if (tile * (4 * lw) >= p) return;  // a tile past the end (the grid is whole runs); nothing below waits for another wavefront
-  const int64_t k = tile * (4 * lw) + ln * 4;
+  const int64_t group = ((int64_t)(slot / kRun) * kXcds + xcd) * kRun + slot % kRun;
+  const int64_t k_wg = group * (4 * lw * W);  // first coordinate of the workgroup
+  if (k_wg >= p) return;  // a workgroup past the end (the grid is whole runs): all of its wavefronts leave
+  const int64_t k = k_wg + (wave * lw + ln) * 4;
+  const bool wave_has = k_wg + (int64_t)wave * lw * 4 < p;  // this wavefront has a tile (the last workgroup may be ragged)
   const bool mine = i < n && k < p;
-  float4* v_l = lds4;                          // [n][M][lw]
-  float4* sg_l = v_l + (size_t)n * M * lw;     // [n][M][lw]
+  const size_t ring_f4 = (size_t)n * M * lw;   // float4 of one ring of one wavefront's tile
+  float4* v_l = lds4 + (size_t)wave * 2 * ring_f4;  // [n][M][lw], the tile of this wavefront
+  float4* sg_l = v_l + ring_f4;                     // [n][M][lw]
   // LDS addresses are byte offsets: column of the lane in a node's ring + slot * bytes per slot, one
   // 24-bit multiply-add each
   const unsigned slot_bytes = (unsigned)lw * sizeof(float4);
   auto at = [&](float4* ring, unsigned column, int slot) -> float4& {
     return *reinterpret_cast<float4*>(reinterpret_cast<char*>(ring) + (__umul24((unsigned)slot, slot_bytes) + column));
+  };
+  // Moving the rings: lane T of the workgroup moves column cT (of the lw W columns of a row segment) of
+  // node iT, i.e. column lT of the tile of wavefront wT.  With W = 1 that is the lane's own column.
+  const int seg = lw * W;
+  const int iT = (int)threadIdx.x / seg, cT = (int)threadIdx.x - iT * seg;
+  const int wT = cT / lw, lT = cT - wT * lw;
+  const int64_t kT = k_wg + 4 * cT;
+  const bool moves = iT < n && kT < p;
+  float4* mv_l = lds4 + (size_t)wT * 2 * ring_f4 + (size_t)iT * M * lw + lT;  // + slot * lw (+ ring_f4 for the sums)
+  // Counters of the moved node before the launch (the node word of the first plan record) and after it (the
+  // resolver has advanced s.t over the rounds of this launch already), and the oldest versions of its two
+  // rings that a receiver could pick up before (from the resolver) and can pick up after the launch.
+  int t0_T = 0, te_T = 0, lo0_v = 0x7fffffff, lo0_s = 0x7fffffff, lo1_v = 0x7fffffff, lo1_s = 0x7fffffff;
+  if (moves) {
+    t0_T = s.blk_plan[iT] & 0x3FFFFFFF;
+    te_T = s.t[iT];
+    lo0_v = s.blk_head[iT];
+    lo0_s = s.blk_head[n + iT];
+    for (int o = s.ro_ptr[iT]; o < s.ro_ptr[iT + 1]; ++o) lo1_v = min(lo1_v, s.tau_r[s.ro_eid[o]]);
+    for (int o = s.co_ptr[iT]; o < s.co_ptr[iT + 1]; ++o) lo1_s = min(lo1_s, s.tau_c[s.co_eid[o]]);
+  }
+  const int s0_T = t0_T % M, se_T = te_T % M;  // slots of the node's latest version before and after
+  // version held by slot m when the latest version, in slot s_latest, is t_latest (negative: never written)
+  auto version_in = [&](int m, int s_latest, int t_latest) {
+    const int back = s_latest - m;
+    return t_latest - (back < 0 ? back + M : back);
   };
 
   float4 x, z, g, h, c, m = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -89,11 +136,13 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // positions of plan words as unsigned byte offsets: a 32-bit offset from a uniform base, no 64-bit address arithmetic
   unsigned r_pw[kDeg], c_pw[kDeg];
   float r_w[kDeg], c_w[kDeg];
+  int c_from[kDeg];  // sender of each in-edge of C
 #pragma unroll
   for (int u = 0; u < kDeg; ++u) {
     r_col[u] = c_col[u] = 0;
     r_pw[u] = c_pw[u] = 4u * (W1 - 1);
     r_w[u] = c_w[u] = 0.f;
+    c_from[u] = 0;
     rt[u] = make_float4(0.f, 0.f, 0.f, 0.f);
   }
   const unsigned own = (unsigned)(i * M * lw + ln) * sizeof(float4);  // this lane's column in the rings of its node
@@ -113,7 +162,8 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       r_col[u] = (unsigned)((hr ? s.r_src[re0 + u] : i) * M * lw + ln) * sizeof(float4);
       r_w[u] = hr ? s.r_w[re0 + u] : 0.f;
       r_pw[u] = 4u * (hr ? n + re0 + u : W1 - 1);
-      c_col[u] = (unsigned)((hc ? s.c_src[ce0 + u] : i) * M * lw + ln) * sizeof(float4);
+      c_from[u] = hc ? s.c_src[ce0 + u] : i;
+      c_col[u] = (unsigned)(c_from[u] * M * lw + ln) * sizeof(float4);
       c_w[u] = hc ? s.c_w[ce0 + u] : 0.f;
       c_pw[u] = 4u * (hc ? n + s.eR + ce0 + u : W1 - 1);
     }
@@ -148,25 +198,32 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     h = V<VEC>::ld((const float*)s.prob.data0 + off);
     c = V<VEC>::ld((const float*)s.prob.data1 + off);
     if (momentum) m = V<VEC>::ld(s.mom + off);
+    // an S4 buffer is in the rho_tilde array only while its version is outside its sender's ring (rare)
 #pragma unroll
     for (int u = 0; u < kDeg; ++u)
-      if (u < dI) rt[u] = V<VEC>::ld(s.rho_tilde + (size_t)(ce0 + u) * p + k);
-    // rings: eight slots of both rings (sixteen loads) in flight at a time, then into LDS
-    const float* vg = s.v_ring + (size_t)i * M * p + k;
-    const float* sgg = s.sigma_ring + (size_t)i * M * p + k;
+      if (u < dI && s.blk_head[2 * n + ce0 + u] != 0) rt[u] = V<VEC>::ld(s.rho_tilde + (size_t)(ce0 + u) * p + k);
+  }
+  // rings: eight slots of both rings (sixteen loads) in flight at a time, then into LDS; a slot whose
+  // version nobody can read any more gets zeros instead
+  if (moves) {
+    const float* vg = s.v_ring + (size_t)iT * M * p + kT;
+    const float* sgg = s.sigma_ring + (size_t)iT * M * p + kT;
     for (int m0 = 0; m0 < M; m0 += 8) {
       float4 tv[8], ts[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u)
+      for (int u = 0; u < 8; ++u) {
+        tv[u] = ts[u] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (m0 + u < M) {
-          tv[u] = V<VEC>::ld(vg + (size_t)(m0 + u) * p);
-          ts[u] = V<VEC>::ld(sgg + (size_t)(m0 + u) * p);
+          const int ver = version_in(m0 + u, s0_T, t0_T);
+          if (ver >= lo0_v) tv[u] = V<VEC>::ld(vg + (size_t)(m0 + u) * p);
+          if (ver >= lo0_s) ts[u] = V<VEC>::ld(sgg + (size_t)(m0 + u) * p);
         }
+      }
 #pragma unroll
       for (int u = 0; u < 8; ++u)
         if (m0 + u < M) {
-          at(v_l, own, m0 + u) = tv[u];
-          at(sg_l, own, m0 + u) = ts[u];
+          mv_l[(size_t)(m0 + u) * lw] = tv[u];
+          mv_l[ring_f4 + (size_t)(m0 + u) * lw] = ts[u];
         }
     }
   }
@@ -177,9 +234,10 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // further addition.
   typedef float Vec4 __attribute__((ext_vector_type(4)));
   typedef __attribute__((address_space(3))) Vec4 LdsVec4;
-  const unsigned a_own = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds4 + own;
+  const unsigned a_own =
+      (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds4 + (unsigned)(wave * 2 * ring_f4 * sizeof(float4)) + own;
   unsigned a_cur = a_own;
-  int ver_next = 1;  // version of the node's next activation (counted here: the plan's copy would need a mask and an add)
+  int ver_next = 1, ver_first = 1;  // version of the node's next activation (counted here: the plan's copy would need a mask and an add)
   const unsigned a_end = a_own + __umul24((unsigned)M, slot_bytes), sg_off = (unsigned)n * M * slot_bytes;
   auto own_ld = [&](unsigned a) {
     const Vec4 t = *(LdsVec4*)(uintptr_t)a;
@@ -193,9 +251,10 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int t0 = plan_a.node & 0x3FFFFFFF;
     g = diag_sample<VEC, MOM>(s, h, c, x, i, t0, k);
     a_cur = a_own + __umul24((unsigned)(t0 % M), slot_bytes);
-    ver_next = t0 + 1;
+    ver_next = ver_first = t0 + 1;
   }
-  wave_sync();
+  if (W > 1) __syncthreads();  // the tiles of the workgroup are in LDS
+  else wave_sync();
 
   // one round with the plan words P, while those of the round after it arrive in N
   auto round = [&](int q, const Plan& P, Plan& N) {
@@ -265,53 +324,63 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
     wave_sync();  // S5: the round is over, its publications are visible to the lanes of this wavefront
   };
-  for (int q = 0; q < blk.rounds; q += 2) {
-    round(q, plan_a, plan_b);
-    if (q + 1 < blk.rounds) round(q + 1, plan_b, plan_a);
+  if (wave_has) {
+    for (int q = 0; q < blk.rounds; q += 2) {
+      round(q, plan_a, plan_b);
+      if (q + 1 < blk.rounds) round(q + 1, plan_b, plan_a);
+    }
   }
 
   // Write-back.  With blk.rebase the running sums are rebased on the way (what rfast_rebase_kernel does, and with
   // its operations): sender j's latest sum leaves every slot of its ring, and a_ij times it every buffer it feeds.
-  float4 base = make_float4(0.f, 0.f, 0.f, 0.f);
+  // s.t holds the counters after the launch, and t mod M is the slot of a node's latest version then.
   if (mine) {
     const size_t off = (size_t)i * p + k;
-    V<VEC>::st(s.x + off, x);
-    V<VEC>::st(s.z + off, z);
-    if (momentum) V<VEC>::st(s.mom + off, m);
-    if (blk.rebase && dO > 0) base = own_ld(a_cur + sg_off);  // nobody reads the sums of a node without out-edges
-    float* vg = s.v_ring + (size_t)i * M * p + k;
-    float* sgg = s.sigma_ring + (size_t)i * M * p + k;
-    for (int m0 = 0; m0 < M; m0 += 8) {
-      float4 tv[8], ts[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u)
-        if (m0 + u < M) {
-          tv[u] = at(v_l, own, m0 + u);
-          ts[u] = at(sg_l, own, m0 + u);
-          if (blk.rebase && dO > 0) ts[u] = sub(ts[u], base);
-        }
-#pragma unroll
-      for (int u = 0; u < 8; ++u)
-        if (m0 + u < M) {
-          V<VEC>::st(vg + (size_t)(m0 + u) * p, tv[u]);
-          V<VEC>::st(sgg + (size_t)(m0 + u) * p, ts[u]);
-        }
+    if (ver_next != ver_first) {  // x and z of a node that was not activated are what they were
+      V<VEC>::st(s.x + off, x);
+      V<VEC>::st(s.z + off, z);
+      if (momentum) V<VEC>::st(s.mom + off, m);
     }
-  }
-  if (blk.rebase) {
-    // every node's latest sum to its receivers, through slot 0 of its v ring (whose contents are on their way out)
-    if (mine) at(v_l, own, 0) = base;
-    wave_sync();
-    if (mine) {
-#pragma unroll
-      for (int u = 0; u < kDeg; ++u)
-        if (u < dI) rt[u] = sub(rt[u], mul_s(c_w[u], at(v_l, c_col[u], 0)));
-    }
-  }
-  if (mine) {
 #pragma unroll
     for (int u = 0; u < kDeg; ++u)
-      if (u < dI) V<VEC>::st(s.rho_tilde + (size_t)(ce0 + u) * p + k, rt[u]);
+      if (u < dI) {
+        const int tj = s.t[c_from[u]];
+        // the buffer lives in the array only if its version is outside the sender's ring now
+        if (s.tau_c[ce0 + u] < tj - (M - 2)) {
+          if (blk.rebase) rt[u] = sub(rt[u], mul_s(c_w[u], at(sg_l, c_col[u], tj % M)));
+          V<VEC>::st(s.rho_tilde + (size_t)(ce0 + u) * p + k, rt[u]);
+        }
+      }
+  }
+  if (W > 1) __syncthreads();  // every wavefront of the workgroup is through with its rounds
+  else wave_sync();
+  if (moves) {
+    float4 base = make_float4(0.f, 0.f, 0.f, 0.f);
+    const bool shift = blk.rebase && lo1_s != 0x7fffffff;  // nobody reads the sums of a node without out-edges
+    if (shift) base = mv_l[ring_f4 + (size_t)se_T * lw];
+    float* vg = s.v_ring + (size_t)iT * M * p + kT;
+    float* sgg = s.sigma_ring + (size_t)iT * M * p + kT;
+    for (int m0 = 0; m0 < M; m0 += 8) {
+      float4 tv[8], ts[8];
+      bool put_v[8], put_s[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        // a slot goes back if the launch wrote it (or shifted it) and somebody can still read its version
+        const int ver = m0 + u < M ? version_in(m0 + u, se_T, te_T) : -1;
+        put_v[u] = m0 + u < M && ver > t0_T && ver >= lo1_v;
+        put_s[u] = m0 + u < M && (ver > t0_T || shift) && ver >= lo1_s;
+        if (put_v[u]) tv[u] = mv_l[(size_t)(m0 + u) * lw];
+        if (put_s[u]) {
+          ts[u] = mv_l[ring_f4 + (size_t)(m0 + u) * lw];
+          if (shift) ts[u] = sub(ts[u], base);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (put_v[u]) V<VEC>::st(vg + (size_t)(m0 + u) * p, tv[u]);
+        if (put_s[u]) V<VEC>::st(sgg + (size_t)(m0 + u) * p, ts[u]);
+      }
+    }
   }
 }
 
@@ -405,28 +474,52 @@ bool rfast_wave_eligible(const rfast_ctx* c) {
 
 int rfast_wave_lanes(const rfast_ctx* c) { return 64 / c->d.n; }
 
-template <int kDeg, bool MOM>
+// Wavefronts per workgroup: as many (4, 2 or 1) as make a row segment at least a cache line of 128 B wide
+// without costing a wavefront of the occupancy that LDS allows (measured on 16 nodes x 11.2 M coordinates,
+// nine ring slots, tile movement alone: 7.6 ms with 64 B segments, 6.3 ms with 128 B and with 256 B).
+static int wave_group(const rfast_ctx* c) {
+  const RfastDev& d = c->d;
+  const int lw = 64 / d.n;
+  const size_t one = wave_lds_bytes(d, lw), cu = 160 * 1024;
+  if (c->wave_group == 1 || c->wave_group == 2 || c->wave_group == 4) return (size_t)c->wave_group * one <= cu ? c->wave_group : 1;
+  const size_t resident = std::min<size_t>(cu / one, 8);  // wavefronts of this kernel a CU holds (two per SIMD at most)
+  int w = 1;
+  while (w < 4 && (size_t)(w * lw) * sizeof(float4) < 128 && std::min<size_t>(cu / (2 * w * one) * (2 * w), 8) >= resident) w *= 2;
+  return w;
+}
+
+template <int kDeg, bool MOM, int W>
 static hipError_t launch_wave(rfast_ctx* c, const RfastBlock& blk) {
   static bool raised = false;
   if (!raised) {  // more than 64 KB of dynamic LDS has to be asked for once per kernel
-    const hipError_t e = hipFuncSetAttribute((const void*)rfast_wave_kernel<kDeg, MOM>,
+    const hipError_t e = hipFuncSetAttribute((const void*)rfast_wave_kernel<kDeg, MOM, W>,
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     raised = true;
   }
   const RfastDev& d = c->d;
+  if (!d.blk_plan || !d.blk_head) return hipErrorInvalidValue;
   const int lw = 64 / d.n;
-  const int64_t run = (int64_t)kXcds * kTileRun;
-  const int64_t tiles = ((d.p + 4 * lw - 1) / (4 * lw) + run - 1) / run * run;  // whole runs: a tile past the end has no lanes
-  if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((rfast_wave_kernel<kDeg, MOM>), dim3((unsigned)tiles), dim3(64), wave_lds_bytes(d, lw), c->stream, c->d, blk,
-                     lw);
+  const int64_t run = (int64_t)kXcds * (kTileRun / W), per = (int64_t)4 * lw * W;
+  const int64_t groups = ((d.p + per - 1) / per + run - 1) / run * run;  // whole runs: a workgroup past the end leaves at once
+  if (groups > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((rfast_wave_kernel<kDeg, MOM, W>), dim3((unsigned)groups), dim3(64 * W), (size_t)W * wave_lds_bytes(d, lw),
+                     c->stream, c->d, blk, lw);
   return hipGetLastError();
 }
 
+template <int kDeg, bool MOM>
+static hipError_t launch_wave_w(rfast_ctx* c, const RfastBlock& blk) {
+  switch (wave_group(c)) {
+    case 4: return launch_wave<kDeg, MOM, 4>(c, blk);
+    case 2: return launch_wave<kDeg, MOM, 2>(c, blk);
+    default: return launch_wave<kDeg, MOM, 1>(c, blk);
+  }
+}
+
 hipError_t rfast_launch_wave(rfast_ctx* c, const RfastBlock& blk) {
-  if (c->d.mom || c->d.wd != 0.f) return c->max_degree <= 2 ? launch_wave<2, true>(c, blk) : launch_wave<kWaveMaxDeg, true>(c, blk);
-  return c->max_degree <= 2 ? launch_wave<2, false>(c, blk) : launch_wave<kWaveMaxDeg, false>(c, blk);
+  if (c->d.mom || c->d.wd != 0.f) return c->max_degree <= 2 ? launch_wave_w<2, true>(c, blk) : launch_wave_w<kWaveMaxDeg, true>(c, blk);
+  return c->max_degree <= 2 ? launch_wave_w<2, false>(c, blk) : launch_wave_w<kWaveMaxDeg, false>(c, blk);
 }
 
 // The synchronous mode through the multi-step kernel: the separable objective, p a multiple of 4,

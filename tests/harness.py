@@ -134,10 +134,17 @@ def run_parity(w, rounds, every=100, coords=None, x0=None, tol=None, check_rings
             gpu.rebase()   # shifts rho and rho~ by a common offset: only their difference is comparable afterwards
         if compare_rings:
             vr, rr, rt = gpu.read("V_RING"), gpu.read("RHO_RING"), gpu.read("RHO_TILDE")
+            # versions that a receiver can still pick up (not older than every stamp on the sender's out-edges)
+            oldest = np.full(w.n, np.iinfo(np.int64).max)
+            for e, (i, j) in enumerate(orc.edges_R):
+                oldest[j] = min(oldest[j], int(sl["tau_v"][e]))
             for j in range(w.n):
                 tj = int(orc.t[j])
                 for ver in range(max(0, tj - w.D), tj + 1):
-                    assert rel_l2(vr[j, ver % M], orc.v[j][ver], 1e-6) <= 10 * tol
+                    if ver >= oldest[j]:
+                        assert rel_l2(vr[j, ver % M], orc.v[j][ver], 1e-6) <= 10 * tol
+                    else:
+                        assert not vr[j, ver % M].any()
             for e, (i, j) in enumerate(orc.edges_C):
                 tj = int(orc.t[j])
                 scale = 1e-3 * gnorm + 1e-6

@@ -6,6 +6,20 @@ gradients) over one batch of synthetic input that is already resident in HBM.
 The default workload is config 2 (n=16 bidirectional ring, diagonal quadratic,
 p = 11.2 M, every node active), the configuration the HBM-roofline target is
 quoted on.  Prints ONE JSON line.
+
+Three legs, all on the same context, one after the other:
+  1. W warm-up rounds, then the K timed rounds as one rfast_run call (wall clock between two
+     device synchronisations): `value`, `ms_per_step`.
+  2. the next K rounds once more with HIP events around every launch on the library's stream:
+     `roofline` of the kernel that ran them (for the separable objective on a small graph one
+     launch of the multi-round kernel; its bytes are computed from the counters and stamps
+     read before and after the launch, by the rules the kernel moves its tiles by).
+  3. (separable objective) up to 20 further rounds with one kernel pass per round
+     (rfast_use_blocks off), events around every pass: `roofline_one_pass`, the HBM view of
+     `rfast_state_kernel<FUSED>`; its bytes are counted per round from the stamps that moved.
+Nothing in the output is a constant taken from a file, except `traffic` (HBM bytes counted by
+rocprofv3 --pmc in a run of its own, see profiles/), which is carried only when the summary
+names the same kernel, workload and launch length, and is labelled as not measured here.
 """
 import argparse
 import json
@@ -14,13 +28,20 @@ import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
-for pth in (ROOT, os.path.join(ROOT, "tests")):
-    if pth not in sys.path:
-        sys.path.insert(0, pth)
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
 
 import numpy as np  # noqa: E402
 
-HBM_PEAK_GBS = 8000.0
+HBM_PEAK_GBS = 8000.0        # MI355X, published
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+REBASE_INTERVAL = 512        # rounds between rebases of the running sums (set below; also the library's default)
+FLOPS_PER_COORDINATE = 40.0  # Algorithm 1 with two in-edges per graph: 21; the float side of the Gaussian noise: the rest
+
+
+def degrees(w):
+    Rd, Cd = w.R.dense(), w.C.dense()
+    return (Rd != 0).sum(axis=1) - 1, (Cd != 0).sum(axis=1) - 1, (Cd != 0).sum(axis=0) - 1   # dR, dI, dO
 
 
 def algorithmic_bytes_per_round(w, active_counts, layout=False):
@@ -31,10 +52,7 @@ def algorithmic_bytes_per_round(w, active_counts, layout=False):
     layout=True: the words this library's layout has to move (one running sum per
     sender instead of one per out-edge: 2 words instead of 2 dO; no write of the S4
     buffer; no stored sample for the separable objective), skips not credited."""
-    Rd, Cd = w.R.dense(), w.C.dense()
-    dR = (Rd != 0).sum(axis=1) - 1
-    dI = (Cd != 0).sum(axis=1) - 1
-    dO = (Cd != 0).sum(axis=0) - 1
+    dR, dI, dO = degrees(w)
     push = 2 * np.minimum(dO, 1) if layout else 2 * dO
     words = 7 + dR + 3 * dI + push + (2 if w.objective == "diag_quadratic" else 1)
     if layout:
@@ -44,27 +62,90 @@ def algorithmic_bytes_per_round(w, active_counts, layout=False):
     return float((words * active_counts).sum() * 4.0 * w.p)
 
 
-def profile_figure(workload_name, kernel, key):
-    """A figure per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if any."""
-    for suffix in ("hbm_traffic", "stats"):
-        path = os.path.join(ROOT, "profiles", f"{workload_name}_{kernel}_kernel_{suffix}.md")
-        try:
-            with open(path) as f:
-                for line in f:
-                    if line.startswith(key + ":"):
-                        return float(line.split(":")[1])
-        except OSError:
-            pass
-    return None
+def edge_lists(w):
+    """(sender, receiver) of the off-diagonal entries of R and C in CSR order (row = receiver)."""
+    out = []
+    for g in (w.R, w.C):
+        src, dst = [], []
+        for i in range(w.n):
+            for k in range(g.rowptr[i], g.rowptr[i + 1]):
+                if g.col[k] != i:
+                    src.append(int(g.col[k]))
+                    dst.append(i)
+        out.append((np.array(src, dtype=np.int64), np.array(dst, dtype=np.int64)))
+    return out
 
 
-def measured_traffic(workload_name, kernel="state"):
-    return profile_figure(workload_name, kernel, "traffic_bytes_per_launch")
+def read_stamps(gpu):
+    return {"t": gpu.read("T_NODE").astype(np.int64), "tau_r": gpu.read("TAU_R").astype(np.int64),
+            "tau_c": gpu.read("TAU_C").astype(np.int64)}
 
 
-# vector ALU: 256 CUs x 4 SIMDs x 16 lanes, one instruction per lane and clock at 2.4 GHz (the published
-# 157.3 TFLOP/s counts a packed fp32 FMA on each lane as 4 flops)
-VALU_LANE_PEAK = 256 * 4 * 16 * 2.4e9
+def one_pass_bytes(w, edges, before, after, active):
+    """Bytes one pass of rfast_state_kernel<FUSED> moves for a round, from the stamps before and after it:
+    per active node and coordinate it reads x, z, h, c, one v per in-edge of R, its own current running sum
+    (if it has out-edges over C) and two running sums (the one consumed now, the one consumed last time) per
+    in-edge of C whose stamp moved; it writes x, z, v and the new running sum.  (The rare copies of an S4
+    buffer that leaves its sender's ring are not counted.)"""
+    dR, dI, dO = degrees(w)
+    (_, _), (c_src, c_dst) = edges
+    live = np.zeros(w.n, dtype=np.int64)
+    moved = after["tau_c"] != before["tau_c"]
+    np.add.at(live, c_dst[moved], 1)
+    act = active.astype(bool)
+    pushes = (dO > 0).astype(np.int64)
+    words = (4 + dR + pushes + 2 * live) + (3 + pushes)
+    return float(words[act].sum()) * 4.0 * w.p
+
+
+def multi_round_bytes(w, edges, before, after, rebased):
+    """Bytes one launch of the multi-round kernel moves, from the counters and stamps before and after it,
+    by the kernel's rules: of every node it reads x, z, h, c, the ring slots whose version a receiver could
+    still pick up before the launch, and the S4 buffers that were outside their sender's ring; it writes x, z
+    of the nodes it activated, the ring slots it wrote (or shifted) that a receiver can still pick up after
+    the launch, and the S4 buffers that are outside their sender's ring then."""
+    M = w.D + 2
+    (r_src, _), (c_src, c_dst) = edges
+    big = np.iinfo(np.int64).max
+    rows_in = rows_out = 0
+    for kind, src, tau0, tau1 in (("v", r_src, before["tau_r"], after["tau_r"]), ("s", c_src, before["tau_c"], after["tau_c"])):
+        lo0, lo1 = np.full(w.n, big), np.full(w.n, big)
+        np.minimum.at(lo0, src, tau0)
+        np.minimum.at(lo1, src, tau1)
+        for j in range(w.n):
+            t0, te = int(before["t"][j]), int(after["t"][j])
+            for m in range(M):
+                ver0, ver1 = t0 - ((t0 - m) % M), te - ((te - m) % M)
+                rows_in += ver0 >= lo0[j]
+                shift = rebased and kind == "s" and lo1[j] != big
+                rows_out += (ver1 > t0 or shift) and ver1 >= lo1[j]
+    rows_in += 4 * w.n + int((before["tau_c"] < before["t"][c_src] - (M - 2)).sum())
+    rows_out += 2 * int((after["t"] != before["t"]).sum()) + int((after["tau_c"] < after["t"][c_src] - (M - 2)).sum())
+    return float(rows_in + rows_out) * 4.0 * w.p, int(rows_in), int(rows_out)
+
+
+def counted_traffic(workload_name, kernel, rounds_per_launch):
+    """HBM bytes per launch counted by rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE) in a run of its own, from the
+    committed summary, if that summary is about this kernel, workload and launch length; else None."""
+    path = os.path.join(ROOT, "profiles", f"{workload_name}_{kernel}_kernel_hbm_traffic.md")
+    fields = {}
+    try:
+        with open(path) as f:
+            for line in f:
+                if ":" in line and not line.startswith(("#", "|", " ")):
+                    k, v = line.split(":", 1)
+                    fields[k.strip()] = v.strip()
+    except OSError:
+        return None
+    try:
+        if fields.get("workload") != workload_name or not fields.get("kernel", "").startswith(f"rfast_{kernel}_kernel"):
+            return None
+        if int(fields.get("rounds_per_launch", "1")) != int(rounds_per_launch):
+            return None
+        return {"bytes_per_launch": float(fields["traffic_bytes_per_launch"]),
+                "source": f"profiles/{os.path.basename(path)} (rocprofv3 --pmc run of its own, not measured in this run)"}
+    except (KeyError, ValueError):
+        return None
 
 
 def _time_rounds(step, w, seconds_target):
@@ -83,7 +164,7 @@ def cpu_baseline(w, seconds_target=8.0):
     (the separable objective costs exactly its share on a subset).  For the
     separable objective: the plain-C oracle on all host threads (`value`), the
     same on one thread, and the NumPy oracle; otherwise the NumPy oracle only."""
-    import harness
+    from oracle.from_workload import make_oracle
     if w.objective == "diag_quadratic":
         p_sub = min(w.p, 400_000)
         coords = np.arange(p_sub, dtype=np.int64) * (w.p // p_sub)
@@ -91,7 +172,7 @@ def cpu_baseline(w, seconds_target=8.0):
         coords, p_sub = None, w.p
     frac = p_sub / w.p
     what = f"the same schedule on {p_sub} of {w.p} coordinates (every {w.p // p_sub}-th), scaled by {frac:.4g}"
-    orc = harness.make_oracle(w, coords)
+    orc = make_oracle(w, coords)
     rounds, updates, dt = _time_rounds(
         lambda q: orc.round(q.active, q.delay_R, q.delay_C, q.drop_R, q.drop_C, w.gamma, q.batch_idx), w, seconds_target)
     numpy_rate = updates * frac / dt
@@ -142,6 +223,9 @@ def main():
                     help="one kernel pass per round even where several rounds per launch are possible")
     ap.add_argument("--force-blocks", action="store_true",
                     help="several rounds per launch wherever possible, also where streaming is faster (measurement)")
+    ap.add_argument("--tile-group", type=int, default=0, help="wavefronts per workgroup of the multi-round kernel (0: automatic)")
+    ap.add_argument("--one-pass-rounds", type=int, default=20,
+                    help="rounds of the one-pass-per-round leg (roofline_one_pass); 0 skips it")
     ap.add_argument("--noise-std", type=float, default=None, help="override the gradient noise (not the headline workload)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only a plain 1 GiB device copy (10 launches): calibrates HBM byte counters")
@@ -159,8 +243,8 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_probe_bytes_read": a.numel() * 4, "copy_probe_bytes_written": a.numel() * 4, "launches": 10}))
         return
-    import harness
     from rfast_workloads import configs
+    from rfast_workloads.device import make_gpu, upload_chunk
     import paper_2307_11617_amd as rf
 
     kw = {"p": args.p} if args.p else {}
@@ -173,80 +257,156 @@ def main():
     W = args.warmup if args.warmup is not None else (12 if args.config == 2 and not args.p and args.steps is None else 10)
     if args.noise_std is not None:
         w.noise_std = args.noise_std
-    gpu = harness.make_gpu(w)
+    separable = w.objective == "diag_quadratic"
+    K1 = 0 if (args.sync or args.generated or not separable) else max(0, min(args.one_pass_rounds, K))
+    gpu = make_gpu(w)
     if args.no_blocks:
         rf.rfast_use_blocks(gpu.ctx, False)
     if args.force_blocks:
         rf.rfast_use_blocks(gpu.ctx, 2)
+    rf.rfast_set_rebase_interval(gpu.ctx, REBASE_INTERVAL)
+    if args.tile_group:
+        rf.rfast_set_tile_group(gpu.ctx, args.tile_group)
     variant = args.momentum != 0.0 or args.weight_decay != 0.0
     if variant:
         gpu.set_optimizer(args.momentum, args.weight_decay)
     gpu.init(None, w.sched.initial_batch())
-    st, dev = harness.upload_chunk(gpu, w, 0, W + 2 * K)
-    sl = lambda name, a, b: None if dev[name] is None else dev[name][a:b].contiguous()
-    run = lambda a, b: gpu.run(b - a, sl("active", a, b), sl("delay_R", a, b), sl("delay_C", a, b), sl("drop_R", a, b),
-                               sl("drop_C", a, b), w.gamma, sl("batch_idx", a, b))
+    st, dev = upload_chunk(gpu, w, 0, W + 2 * K + K1)
+    names = ("active", "delay_R", "delay_C", "drop_R", "drop_C", "batch_idx")
+    cut = lambda a, b: [None if dev[k] is None else dev[k][a:b].contiguous() for k in names]   # noqa: E731
+    run_args = lambda c, n_rounds: (n_rounds, c[0], c[1], c[2], c[3], c[4], w.gamma, c[5])      # noqa: E731
+    run = lambda c, n_rounds: gpu.run(*run_args(c, n_rounds))                                    # noqa: E731
     if args.generated:
         p_act = torch.from_numpy(w.sched.p_active.astype(np.float32)).to(gpu.device)
         if args.graphs:
             rf.rfast_use_graphs(gpu.ctx, True)
-        run = lambda a, b: gpu.run_generated(b - a, 20231117, p_act, w.sched.d_max, w.sched.p_drop, w.gamma)
+        run = lambda c, n_rounds: gpu.run_generated(n_rounds, 20231117, p_act, w.sched.d_max, w.sched.p_drop, w.gamma)  # noqa: E731
     if args.sync:
-        bi = lambda a, b: sl("batch_idx", a, b)
-        run = lambda a, b: gpu.sync_run(b - a, w.gamma, bi(a, b))
-    run(0, W)
+        run = lambda c, n_rounds: gpu.sync_run(n_rounds, w.gamma, c[5])   # noqa: E731
+    c_warm, c_timed, c_prof = cut(0, W), cut(W, W + K), cut(W + K, W + 2 * K)
+
+    # ---- leg 1: warm-up, then the timed rounds
+    run(c_warm, W)
     torch.cuda.synchronize()
     t_before = int(gpu.read("T_NODE").sum()) if args.generated else 0
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
-    run(W, W + K)
+    run(c_timed, K)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     gpu.check()
     t_after = int(gpu.read("T_NODE").sum()) if args.generated else 0
 
-    # second pass with HIP events around every kernel launch (on the library's stream)
-    rf.rfast_profile_enable(gpu.ctx, True)
-    run(W + K, W + 2 * K)
-    ms_state, n_state = rf.rfast_kernel_time(gpu.ctx, 0)
-    ms_grad, n_grad = rf.rfast_kernel_time(gpu.ctx, 1)
-    ms_res, n_res = rf.rfast_kernel_time(gpu.ctx, 2)
-    rf.rfast_profile_enable(gpu.ctx, False)
+    # ---- leg 2: the next K rounds with HIP events around every kernel launch (on the library's stream).  The library
+    # cuts multi-round launches at the multiples of the rebase interval; the calls here are cut at the same rounds,
+    # so that the counters and stamps can be read between the launches.
+    multi = (not args.sync and not args.generated and separable and rf.rfast_block_info(gpu.ctx) != 0)
+    segs, r = [], W + K
+    while r < W + 2 * K:
+        nxt = min(W + 2 * K, (r // REBASE_INTERVAL + 1) * REBASE_INTERVAL) if multi else W + 2 * K
+        segs.append((r, nxt))
+        r = nxt
+    ms_state = ms_grad = ms_res = 0.0
+    n_state = n_grad = n_res = 0
+    launches_multi = []   # (rounds, ms, stamps before, stamps after, rebased) of every multi-round launch
+    stamps0 = read_stamps(gpu)
+    for lo, hi in segs:
+        before = read_stamps(gpu)
+        rf.rfast_profile_enable(gpu.ctx, True)
+        run(cut(lo, hi), hi - lo)
+        ms, cnt = rf.rfast_kernel_time(gpu.ctx, 0)
+        ms_g, cnt_g = rf.rfast_kernel_time(gpu.ctx, 1)
+        ms_r, cnt_r = rf.rfast_kernel_time(gpu.ctx, 2)
+        rf.rfast_profile_enable(gpu.ctx, False)
+        ms_state, ms_grad, ms_res = ms_state + ms, ms_grad + ms_g, ms_res + ms_r
+        n_state, n_grad, n_res = n_state + cnt, n_grad + cnt_g, n_res + cnt_r
+        if multi and cnt == 1 and hi - lo > 1:
+            launches_multi.append((hi - lo, ms, before, read_stamps(gpu), hi % REBASE_INTERVAL == 0))
+    stamps1 = read_stamps(gpu)
 
     act_timed = st["active"][W:W + K].astype(np.int64)
     act_prof = st["active"][W + K:W + 2 * K].astype(np.int64)
     if args.sync:
         act_timed, act_prof = np.ones_like(act_timed), np.ones_like(act_prof)
-    if args.generated:   # the masks live on the device; count the activations from the counters
-        updates = t_after - t_before
-    else:
-        updates = int(act_timed.sum())
-    bytes_prof = sum(algorithmic_bytes_per_round(w, a) for a in act_prof)
+    updates = (t_after - t_before) if args.generated else int(act_timed.sum())
+    bytes_alg = sum(algorithmic_bytes_per_round(w, a) for a in act_prof)
     bytes_layout = sum(algorithmic_bytes_per_round(w, a, layout=True) for a in act_prof)
     if args.sync:
         # descent: x, z -> v (3 words); step: 1+dR v's, 1+dI z's in, x and z out, plus
         #   separable objective: the old x (its sample is recomputed, not stored), h, c in (3 words)
         #   otherwise: the old and the new sample in (2 words)
-        dR = (w.R.dense() != 0).sum(axis=1) - 1
-        dI = (w.C.dense() != 0).sum(axis=1) - 1
-        words = 3 + (1 + dR) + (1 + dI) + 2 + (3 if w.objective == "diag_quadratic" else 2)
-        bytes_prof = bytes_layout = float(words.sum() * 4.0 * w.p * K)
+        dR, dI, _ = degrees(w)
+        words = 3 + (1 + dR) + (1 + dI) + 2 + (3 if separable else 2)
+        bytes_alg = bytes_layout = float(words.sum() * 4.0 * w.p * K)
     if args.momentum != 0.0:   # read and write of the buffer m_i
         extra = 8.0 * w.p * (w.n * K if args.sync else float(act_prof.sum()))
-        bytes_prof, bytes_layout = bytes_prof + extra, bytes_layout + extra
+        bytes_alg, bytes_layout = bytes_alg + extra, bytes_layout + extra
     launches = max(n_state, 1)
     avg_ms = ms_state / launches
     # several rounds per launch with the state resident in LDS (the default where it applies)
     # (graph replays, which the timed pass of --graphs uses, are one pass per round; the event-timed pass cannot replay)
-    blocked = not args.sync and not args.graphs and w.objective == "diag_quadratic" and 0 < n_state < K
+    blocked = not args.sync and not args.graphs and separable and 0 < n_state < K
     lanes, per_wave = rf.rfast_block_info(gpu.ctx, with_kind=True) if blocked else (0, False)
     if args.sync:
         kernel = "rfast_sync_wave_kernel (several steps per launch, state in registers and LDS)" if 0 < n_state < K else "rfast_sync_descent+step"
     elif blocked:
         kernel = f"rfast_wave_kernel<{lanes} lanes per node>" if per_wave else f"rfast_block_kernel<{lanes} lanes per node>"
     else:
-        kernel = "rfast_state_kernel" + ("<FUSED>" if w.objective == "diag_quadratic" else "<MIX>+<TRACK>")
-    headline = not (args.p or args.sync or variant or args.generated)
-    achieved = bytes_prof / (ms_state * 1e-3) / 1e9 if ms_state > 0 else 0.0
+        kernel = "rfast_state_kernel" + ("<FUSED>" if separable else "<MIX>+<TRACK>")
+    headline = not (args.p or args.sync or variant or args.generated or args.noise_std is not None)
+    edges = edge_lists(w)
+    secs = ms_state * 1e-3
+
+    if blocked and launches_multi:
+        # Launches that took their rounds with the state in LDS.  Such a launch has to do the method's arithmetic for its
+        # rounds and to move the live state once in and once out; whichever takes longer at the published peaks bounds it.
+        moved = flops = secs = 0.0
+        rows_in = rows_out = 0
+        for rounds_l, ms_l, b_l, a_l, rebased in launches_multi:
+            if per_wave:
+                mv, ri, ro = multi_round_bytes(w, edges, b_l, a_l, rebased)
+            else:   # the workgroup-tile kernel moves every ring slot and every buffer in and out
+                ri = w.n * (2 * (w.D + 2) + 4) + w.C.nnz_off
+                ro = w.n * (2 * (w.D + 2) + 2) + w.C.nnz_off
+                mv = float(ri + ro) * 4.0 * w.p
+            moved, rows_in, rows_out = moved + mv, rows_in + ri, rows_out + ro
+            flops += FLOPS_PER_COORDINATE * w.p * float((a_l["t"] - b_l["t"]).sum())
+            secs += ms_l * 1e-3
+        n_multi = len(launches_multi)
+        rounds_multi = sum(l[0] for l in launches_multi)
+        moved, flops, rows_in, rows_out = moved / n_multi, flops / n_multi, rows_in / n_multi, rows_out / n_multi
+        secs /= n_multi   # per launch from here on
+        avg_ms = secs * 1e3
+        t_alu, t_hbm = flops / (FP32_VECTOR_PEAK_TFLOPS * 1e12), moved / (HBM_PEAK_GBS * 1e9)
+        counted = counted_traffic(w.name, "wave", rounds_multi // n_multi) if headline and rounds_multi % n_multi == 0 else None
+        if t_hbm >= t_alu:
+            roof = {"bound": "hbm", "achieved": moved / secs / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+        else:
+            roof = {"bound": "alu", "achieved": flops / secs / 1e12, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s"}
+        roof["frac"] = roof["achieved"] / roof["peak"]
+        roof.update({"kernel": kernel, "avg_kernel_ms": avg_ms, "launches": n_multi, "rounds_per_launch": rounds_multi / n_multi,
+                     "bytes_per_launch": moved, "rows_per_node_in": rows_in / w.n, "rows_per_node_out": rows_out / w.n,
+                     "flops_per_launch": flops, "intensity_flop_per_byte": flops / moved,
+                     "ridge_flop_per_byte": FP32_VECTOR_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9),
+                     "time_at_hbm_peak_ms": t_hbm * 1e3, "time_at_fp32_vector_peak_ms": t_alu * 1e3,
+                     "achieved_gbs": moved / secs / 1e9, "achieved_tflops": flops / secs / 1e12,
+                     "traffic": counted["bytes_per_launch"] if counted else None,
+                     "traffic_source": counted["source"] if counted else None,
+                     "note": "bytes_per_launch: what the launch moves by its own rules (live ring slots, x, z, h, c, buffers "
+                             "outside their ring), computed here from the counters and stamps read before and after it; "
+                             "flops_per_launch: 40 per coordinate and node-update (Algorithm 1 and the float side of the "
+                             "Gaussian noise; the integer work of the counter-based generator is not a flop)"})
+    else:
+        achieved = bytes_layout / secs / 1e9 if secs > 0 else 0.0
+        roof = {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "avg_kernel_ms": avg_ms, "launches": n_state,
+                "bytes_per_launch": bytes_layout / launches,
+                "algorithmic_bytes_per_launch": bytes_alg / launches,
+                "algorithmic_gbs": bytes_alg / secs / 1e9 if secs > 0 else 0.0,
+                "traffic": None,
+                "note": "bytes_per_launch: the words this layout has to move per node-update (skipped edges not credited); "
+                        "algorithmic_*: the literal count of Algorithm 1, which this layout undercuts (not a bound)"}
+
     out = {
         "metric": "node-updates/sec",
         "value": updates / dt,
@@ -257,50 +417,52 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name + ("/synchronous-push-pull" if args.sync else "") +
                                ("/generated-schedule" if args.generated else "") + ("/hip-graphs" if args.graphs else "") +
-                               (f"/momentum={args.momentum},weight_decay={args.weight_decay}" if variant else ""), "n": w.n, "p": w.p, "D": w.D, "ring_slots": w.D + 2, "objective": w.objective,
+                               (f"/momentum={args.momentum},weight_decay={args.weight_decay}" if variant else ""),
+                   "n": w.n, "p": w.p, "D": w.D, "ring_slots": w.D + 2, "objective": w.objective,
                    "mean_active_per_round": updates / K, "gamma": w.gamma},
-        "roofline": {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "avg_kernel_ms": avg_ms, "launches": n_state,
-                     "algorithmic_bytes_per_launch": bytes_prof / launches,
-                     "layout_bytes_per_launch": bytes_layout / launches,
-                     "achieved_layout": achieved * bytes_layout / bytes_prof if bytes_prof else 0.0,
-                     "frac_layout": achieved * bytes_layout / bytes_prof / HBM_PEAK_GBS if bytes_prof else 0.0,
-                     "traffic": measured_traffic(w.name, ("wave" if per_wave else "block") if blocked else "state") if headline else None},
+        "roofline": roof,
         "kernel_ms": {"state": ms_state, "gradient": ms_grad, "resolver": ms_res,
                       "launches": {"state": n_state, "gradient": n_grad, "resolver": n_res}},
         "host_data_generation_s": gen_s,
     }
-    if blocked:
-        # The launch keeps the state in LDS over rounds_per_launch rounds, so the HBM traffic the
-        # algorithmic figure counts per round is not moved: frac above 1 says so, and what bounds the
-        # kernel is instruction issue.  VALU instructions per wavefront from the committed counter summary.
-        out["roofline"]["rounds_per_launch"] = K / launches
-        out["roofline"]["note"] = ("state resident in LDS over rounds_per_launch rounds: HBM moves every ring slot once "
-                                   "per launch (traffic), not the per-round words of the algorithmic figure")
-        per_round = profile_figure(w.name, "wave" if per_wave else "block", "valu_wave_instructions_per_round") if headline else None
-        if per_round:
-            # the bound that holds: vector instructions issued (64 lanes per wavefront instruction)
-            rate = per_round * 64.0 * K / (ms_state * 1e-3)
-            hbm = out["roofline"]
-            out["roofline_hbm"] = hbm
-            out["roofline"] = {"bound": "alu", "kernel": kernel, "achieved": rate / 1e12, "peak": VALU_LANE_PEAK / 1e12,
-                               "unit": "T lane-instructions/s", "frac": rate / VALU_LANE_PEAK,
-                               "avg_kernel_ms": avg_ms, "launches": n_state, "rounds_per_launch": K / launches,
-                               "instructions_per_launch": per_round * 64.0 * K / launches,
-                               "traffic": hbm["traffic"],
-                               "source": "VALU instructions per round from the committed counter summary (SQ_INSTS_VALU) "
-                                         "x rounds / kernel time measured here with HIP events"}
-            # for context, the arithmetic of the method alone against the fp32 vector peak: about 40 flops per
-            # coordinate and node-update (Algorithm 1 with two in-edges per graph: 21; the rest the float side of
-            # the noise), the integer work of the counter-based generator not counted
-            flops = 40.0 * w.p * float(act_prof.sum())
-            out["roofline"]["algorithmic_tflops"] = flops / (ms_state * 1e-3) / 1e12
-            out["roofline"]["algorithmic_frac_of_fp32_vector_peak"] = out["roofline"]["algorithmic_tflops"] / 157.3
+
+    # ---- leg 3: one kernel pass per round, the HBM view of the fused round kernel
+    if K1 > 0:
+        rf.rfast_use_blocks(gpu.ctx, False)
+        r0 = W + 2 * K
+        moved = 0.0
+        ms_one = 0.0
+        for q in range(K1):
+            before = read_stamps(gpu)
+            rf.rfast_profile_enable(gpu.ctx, True)
+            run(cut(r0 + q, r0 + q + 1), 1)
+            ms, cnt = rf.rfast_kernel_time(gpu.ctx, 0)
+            rf.rfast_profile_enable(gpu.ctx, False)
+            assert cnt == 1, cnt
+            ms_one += ms
+            moved += one_pass_bytes(w, edges, before, read_stamps(gpu), st["active"][r0 + q])
+        act1 = st["active"][r0:r0 + K1].astype(np.int64)
+        alg1 = sum(algorithmic_bytes_per_round(w, a) for a in act1)
+        lay1 = sum(algorithmic_bytes_per_round(w, a, layout=True) for a in act1)
+        s1 = ms_one * 1e-3
+        counted = counted_traffic(w.name, "state", 1) if headline else None
+        out["roofline_one_pass"] = {
+            "bound": "hbm", "kernel": "rfast_state_kernel<FUSED>", "launches": K1, "avg_kernel_ms": ms_one / K1,
+            "achieved": moved / s1 / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": moved / s1 / 1e9 / HBM_PEAK_GBS,
+            "bytes_per_launch": moved / K1,
+            "layout_bytes_per_launch": lay1 / K1, "layout_gbs": lay1 / s1 / 1e9,
+            "algorithmic_bytes_per_launch": alg1 / K1, "algorithmic_gbs": alg1 / s1 / 1e9,
+            "node_updates_per_s": float(act1.sum()) / s1,
+            "traffic": counted["bytes_per_launch"] if counted else None,
+            "traffic_source": counted["source"] if counted else None,
+            "note": "one pass over HBM per round; bytes_per_launch counts what the pass reads and writes, edges whose stamp did "
+                    "not move skipped (computed per round from the stamps before and after it); layout_*: the words of this "
+                    "layout with no skip credited; algorithmic_*: the literal count of Algorithm 1 (7 + dR + 3 dI + 2 dO + 2 "
+                    "words), which the layout undercuts, so its rate may exceed the peak and is not a fraction of it"}
     if w.objective == "softmax_bf16":
         # the two GEMMs of the softmax gradient: 2*B*d*K flops each per node-update
-        flops = 4.0 * w.sched.batch * w.extra["d"] * w.extra["K"] * float(act_prof.sum())
-        tf = flops / (ms_grad * 1e-3) / 1e12 if ms_grad > 0 else 0.0
+        gflops = 4.0 * w.sched.batch * w.extra["d"] * w.extra["K"] * float(act_prof.sum())
+        tf = gflops / (ms_grad * 1e-3) / 1e12 if ms_grad > 0 else 0.0
         out["roofline_mfma"] = {"bound": "mfma", "kernel": "rfast_softmax_prep+forward+backward", "achieved": tf,
                                 "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0,
                                 "intensity_limited_peak": 680.0, "avg_ms_per_round": ms_grad / max(n_grad, 1)}

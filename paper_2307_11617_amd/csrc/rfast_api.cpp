@@ -101,7 +101,7 @@ Offsets layout(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, cons
   o.plan_set_bytes = L.total - o.n_active;
   (void)L.take((size_t)(kResolveAhead - 1) * o.plan_set_bytes);
   o.blk_plan = L.take((size_t)kBlockRounds * ((size_t)n + eR + eC + 1) * 4);
-  o.blk_head = L.take((2 * (size_t)n + eC) * 4);
+  o.blk_head = L.take((8 * (size_t)n + eC) * 4);
   // the generator draws the schedule of up to gen_depth rounds per launch (as many as fit 64 MB, at most kBlockRounds)
   const size_t gen_rows = (size_t)n * (size_t)(prob->kind == RFAST_OBJ_DIAG_QUADRATIC ? 0 : prob->batch);
   const size_t gen_round = (size_t)n + 5 * (eR + eC) + 4 * gen_rows;
@@ -500,6 +500,7 @@ int rfast_create(rfast_ctx** out, int32_t n, int64_t p, const int32_t* R_rowptr,
   chk(upload(c, b, o.ro_ptr, gr.out_ptr)); chk(upload(c, b, o.ro_eid, gr.out_eid));
   for (int i = 0; i < n; ++i)
     c->max_degree = std::max({c->max_degree, gr.ptr[i + 1] - gr.ptr[i], gc.ptr[i + 1] - gc.ptr[i], gc.out_ptr[i + 1] - gc.out_ptr[i]});
+  chk(rfast_wave_prime(c));
   chk(hipStreamSynchronize(c->stream));  // the host vectors die with this scope
   if (e != hipSuccess) {
     const int r = hipfail(nullptr, e, "uploading graph");
@@ -921,6 +922,8 @@ int rfast_set_optimizer(rfast_ctx* c, float momentum, float weight_decay, float*
   c->d.wd = weight_decay;
   c->d.mom = momentum != 0.f ? d_momentum : nullptr;
   c->needs_init = true;
+  const hipError_t e = rfast_wave_prime(c);  // the variant has instantiations of its own
+  if (e != hipSuccess) return hipfail(c, e, "loading the multi-round kernel");
   return RFAST_OK;
 }
 
@@ -954,8 +957,8 @@ int rfast_check(rfast_ctx* c) {
   e = hipMemcpy(err, c->d.err, 16, hipMemcpyDeviceToHost);
   if (e != hipSuccess) return hipfail(c, e, "reading device status");
   if (err[0] == 0) return RFAST_OK;
-  static const char* kinds[] = {"delay on R edge", "delay on C edge", "sample row of node"};
-  const char* what = err[2] >= 0 && err[2] <= 2 ? kinds[err[2]] : "value";
+  static const char* kinds[] = {"delay on R edge", "delay on C edge", "sample row of node", "class label of a sample of node"};
+  const char* what = err[2] >= 0 && err[2] <= 3 ? kinds[err[2]] : "value";
   return fail(c, err[0], std::string(what) + " " + std::to_string(err[3]) + " out of range in round " + std::to_string(err[1]) +
                              " (clamped on the device)");
 }

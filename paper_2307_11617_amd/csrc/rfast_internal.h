@@ -83,11 +83,13 @@ struct RfastDev {
   // in LDS over several rounds (NULL: not wanted): [n] node words (bit 31 active, low 30 bits the
   // counter at the start of the round), [eR] ring slot per R edge, [eC] plan word per C edge.
   int32_t* blk_plan;
-  // What a multi-round launch needs to know about the state before its first round, written by the
-  // resolver ahead of the rounds it resolves (NULL: not wanted): [n] the oldest version of node j's v
-  // ring that a receiver can still pick up (the smallest stamp held on j's out-edges over R; INT_MAX
-  // if j has none), [n] the same for its ring of running sums (out-edges over C), [eC] 1 if the S4
-  // buffer of the edge lives in the rho_tilde array (its version has left the sender's ring), else 0.
+  // What a multi-round launch needs to know about the state before its first round and after its last,
+  // written by the resolver around the rounds it resolves (NULL: not wanted).  [n][8] per node j: its
+  // counter before and after; the oldest version of its v ring that a receiver could still pick up
+  // before (the smallest stamp held on j's out-edges over R; INT_MAX if j has none), the same for its
+  // ring of running sums (out-edges over C); both once more for after; two unused words.  Then [eC]
+  // per C edge: bit 0 set if its S4 buffer was in the rho_tilde array before (its version outside the
+  // sender's ring), bit 1 if it is after.
   int32_t* blk_head;
   // schedule of the current round when it is generated on the device
   uint8_t* gen_active;    // [n]
@@ -133,7 +135,7 @@ struct rfast_ctx {
   int32_t use_blocks = 1;       // 1: where it pays, 2: wherever possible; rfast_run / rfast_run_generated may advance several rounds per launch
   int32_t wave_group = 0;       // wavefronts per workgroup of the wavefront-tile kernel (0: chosen by the launcher)
   int32_t* blk_plan_base = nullptr;  // kBlockRounds plan records
-  int32_t* blk_head_base = nullptr;  // 2 n + eC words, see RfastDev::blk_head
+  int32_t* blk_head_base = nullptr;  // 8 n + eC words, see RfastDev::blk_head
   int32_t max_degree = 0;       // most in-edges of R, in-edges of C or out-edges of C at any node
   // the per-round plan arrays of RfastDev exist kResolveAhead times; `plan_set` is the set d points at
   char* plan_set0 = nullptr;
@@ -170,6 +172,7 @@ hipError_t rfast_launch_rebase(rfast_ctx* c);
 bool rfast_wave_eligible(const rfast_ctx* c);   // the multi-round kernel with one tile per wavefront
 int rfast_wave_lanes(const rfast_ctx* c);       // its lanes per node
 hipError_t rfast_launch_wave(rfast_ctx* c, const RfastBlock& blk);
+hipError_t rfast_wave_prime(rfast_ctx* c);      // loads the kernels this context can launch, with launches that do nothing
 bool rfast_block_eligible(const rfast_ctx* c);  // the multi-round kernel with one tile per workgroup
 int rfast_block_lanes(const rfast_ctx* c);  // lanes per node of the multi-round kernel, 0 if no tile fits
 hipError_t rfast_launch_block(rfast_ctx* c, const RfastBlock& blk);

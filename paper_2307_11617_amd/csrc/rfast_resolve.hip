@@ -1,7 +1,7 @@
 // Integer schedule resolver: turns one round's masks into ring-slot indices.
 //
-// For an active receiver i and in-edge e = (j -> i) the stamp picked up is
-// "the largest local iteration stamp received" (Algorithm 1, S2a / S2b): the
+// For an active receiver i and in-edge e = (j -> i) the stamp picked up is the
+// newest one that has arrived on the edge (Algorithm 1, S2a / S2b), i.e. the
 // newest version of j that (a) j had published before round r - delay_e and
 // (b) was not lost on e, and never older than the stamp already held.  Losses
 // are decided when a version is sent (experiments section: a node either sends
@@ -116,18 +116,27 @@ __device__ inline void edge_decide(const RfastDev& s, int kind, int e, int r, Ed
   }
 }
 
-// The state before the first round of a multi-round launch, for the kernel that moves the rings
-// (RfastDev::blk_head).  Called by every lane of the one workgroup, before any round is resolved.
-__device__ inline void block_head(const RfastDev& s) {
-  for (int q = threadIdx.x; q < 2 * s.n; q += blockDim.x) s.blk_head[q] = 0x7fffffff;
+// What the kernel that moves the rings of a multi-round launch needs to know about the state before
+// the first round (when = 0, called ahead of the rounds) and after the last (when = 1), see
+// RfastDev::blk_head.  Called by every lane of the one workgroup.
+__device__ inline void block_head(const RfastDev& s, int when) {
+  int32_t* H = s.blk_head;
+  __syncthreads();  // when = 1: the last round's counters and stamps are written
+  for (int j = threadIdx.x; j < s.n; j += blockDim.x) {
+    H[8 * j + when] = s.t[j];
+    H[8 * j + 2 + 2 * when] = 0x7fffffff;
+    H[8 * j + 3 + 2 * when] = 0x7fffffff;
+  }
   __syncthreads();
-  for (int e = threadIdx.x; e < s.eR; e += blockDim.x) atomicMin(&s.blk_head[s.r_src[e]], s.tau_r[e]);
+  for (int e = threadIdx.x; e < s.eR; e += blockDim.x) atomicMin(&H[8 * s.r_src[e] + 2 + 2 * when], s.tau_r[e]);
   for (int e = threadIdx.x; e < s.eC; e += blockDim.x) {
     const int j = s.c_src[e], tau = s.tau_c[e];
-    atomicMin(&s.blk_head[s.n + j], tau);
-    s.blk_head[2 * s.n + e] = tau < s.t[j] - (s.M - 2) ? 1 : 0;
+    atomicMin(&H[8 * j + 3 + 2 * when], tau);
+    const int outside = tau < s.t[j] - (s.M - 2) ? 1 : 0;  // the S4 buffer of the edge is in the rho_tilde array
+    if (when == 0) H[8 * s.n + e] = outside;
+    else H[8 * s.n + e] |= outside << 1;
   }
-  __syncthreads();  // the rounds below move the stamps and the counters
+  __syncthreads();  // when = 0: the rounds below move the stamps and the counters
 }
 
 constexpr int kResolveThreads = 1024;
@@ -151,7 +160,7 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev
   const int r0 = *s.round_no;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int E = s.eR + s.eC;
-  if (s.blk_head) block_head(s);
+  if (s.blk_head) block_head(s, 0);
   for (int rq = 0; rq < rounds; ++rq) {
     const int r = r0 + rq;
     EdgeIn ahead[kAhead];
@@ -231,6 +240,7 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev
       advance(s.node_spill, plan_stride);
     }
   }
+  if (s.blk_head) block_head(s, 1);
   if (threadIdx.x == 0) *s.round_no = r0 + rounds;
 }
 
@@ -256,7 +266,7 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_cached_kernel(R
   uint8_t* act_l = reinterpret_cast<uint8_t*>(sched_l + (size_t)rounds * E + ((size_t)rounds * E & 1));  // [rounds][n]
   const int r0 = *s.round_no;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  if (s.blk_head) block_head(s);
+  if (s.blk_head) block_head(s, 0);
   for (int w = threadIdx.x; w < rounds * E; w += kResolveThreads) {
     const int q = w / E, e = w - q * E;
     const bool kind = e >= s.eR;
@@ -350,6 +360,7 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_cached_kernel(R
     advance(s.plan_c, plan_stride);
     advance(s.node_spill, plan_stride);
   }
+  if (s.blk_head) block_head(s, 1);
   if (threadIdx.x == 0) *s.round_no = r0 + rounds;
 }
 

@@ -217,6 +217,15 @@ __global__ void __launch_bounds__(64 * NW) rfast_softmax_forward(RfastDev s, con
     const int row = sample_row(s, batch_idx, i, b0 + tid, B);
     rows[tid] = row;
     my_label = labels[row];
+    // a label outside [0, K) would index the logits in LDS out of bounds: clamped and reported, like a sample row
+    if (my_label < 0 || my_label >= K) {
+      if (atomicCAS(&s.err[0], 0, RFAST_ERANGE) == 0) {
+        s.err[1] = s.n_active[1];
+        s.err[2] = 3;
+        s.err[3] = i;
+      }
+      my_label = my_label < 0 ? 0 : K - 1;
+    }
   }
   __syncthreads();
 

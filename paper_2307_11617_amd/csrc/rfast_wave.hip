@@ -102,17 +102,14 @@ __global__ void __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 
   const int64_t kT = k_wg + 4 * cT;
   const bool moves = iT < n && kT < p;
   float4* mv_l = lds4 + (size_t)wT * 2 * ring_f4 + (size_t)iT * M * lw + lT;  // + slot * lw (+ ring_f4 for the sums)
-  // Counters of the moved node before the launch (the node word of the first plan record) and after it (the
-  // resolver has advanced s.t over the rounds of this launch already), and the oldest versions of its two
-  // rings that a receiver could pick up before (from the resolver) and can pick up after the launch.
+  // Counters of the moved node before and after the launch, and the oldest versions of its two rings that a
+  // receiver could pick up before and can pick up after it (the resolver has been through all rounds of the
+  // launch already and left both in one record per node).
   int t0_T = 0, te_T = 0, lo0_v = 0x7fffffff, lo0_s = 0x7fffffff, lo1_v = 0x7fffffff, lo1_s = 0x7fffffff;
   if (moves) {
-    t0_T = s.blk_plan[iT] & 0x3FFFFFFF;
-    te_T = s.t[iT];
-    lo0_v = s.blk_head[iT];
-    lo0_s = s.blk_head[n + iT];
-    for (int o = s.ro_ptr[iT]; o < s.ro_ptr[iT + 1]; ++o) lo1_v = min(lo1_v, s.tau_r[s.ro_eid[o]]);
-    for (int o = s.co_ptr[iT]; o < s.co_ptr[iT + 1]; ++o) lo1_s = min(lo1_s, s.tau_c[s.co_eid[o]]);
+    const int4 a = *reinterpret_cast<const int4*>(s.blk_head + 8 * iT);
+    const int2 b = *reinterpret_cast<const int2*>(s.blk_head + 8 * iT + 4);
+    t0_T = a.x; te_T = a.y; lo0_v = a.z; lo0_s = a.w; lo1_v = b.x; lo1_s = b.y;
   }
   const int s0_T = t0_T % M, se_T = te_T % M;  // slots of the node's latest version before and after
   // version held by slot m when the latest version, in slot s_latest, is t_latest (negative: never written)
@@ -137,8 +134,10 @@ __global__ void __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 
   unsigned r_pw[kDeg], c_pw[kDeg];
   float r_w[kDeg], c_w[kDeg];
   int c_from[kDeg];  // sender of each in-edge of C
+  int rt_where[kDeg], end_slot[kDeg];
 #pragma unroll
   for (int u = 0; u < kDeg; ++u) {
+    rt_where[u] = end_slot[u] = 0;
     r_col[u] = c_col[u] = 0;
     r_pw[u] = c_pw[u] = 4u * (W1 - 1);
     r_w[u] = c_w[u] = 0.f;
@@ -201,17 +200,22 @@ __global__ void __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 
     // an S4 buffer is in the rho_tilde array only while its version is outside its sender's ring (rare)
 #pragma unroll
     for (int u = 0; u < kDeg; ++u)
-      if (u < dI && s.blk_head[2 * n + ce0 + u] != 0) rt[u] = V<VEC>::ld(s.rho_tilde + (size_t)(ce0 + u) * p + k);
+      if (u < dI) {
+        rt_where[u] = s.blk_head[8 * n + ce0 + u];
+        end_slot[u] = s.blk_head[8 * c_from[u] + 1] % M;  // of the sender's latest version after the launch
+        if (rt_where[u] & 1) rt[u] = V<VEC>::ld(s.rho_tilde + (size_t)(ce0 + u) * p + k);
+      }
   }
-  // rings: eight slots of both rings (sixteen loads) in flight at a time, then into LDS; a slot whose
-  // version nobody can read any more gets zeros instead
+  // rings: kBatch slots of both rings in flight at a time (rings of up to twelve slots in one round trip to
+  // memory), then into LDS; a slot whose version nobody can read any more gets zeros instead
+  constexpr int kBatch = kDeg <= 2 ? 12 : 10;
   if (moves) {
     const float* vg = s.v_ring + (size_t)iT * M * p + kT;
     const float* sgg = s.sigma_ring + (size_t)iT * M * p + kT;
-    for (int m0 = 0; m0 < M; m0 += 8) {
-      float4 tv[8], ts[8];
+    for (int m0 = 0; m0 < M; m0 += kBatch) {
+      float4 tv[kBatch], ts[kBatch];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      for (int u = 0; u < kBatch; ++u) {
         tv[u] = ts[u] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (m0 + u < M) {
           const int ver = version_in(m0 + u, s0_T, t0_T);
@@ -220,7 +224,7 @@ __global__ void __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 
         }
       }
 #pragma unroll
-      for (int u = 0; u < 8; ++u)
+      for (int u = 0; u < kBatch; ++u)
         if (m0 + u < M) {
           mv_l[(size_t)(m0 + u) * lw] = tv[u];
           mv_l[ring_f4 + (size_t)(m0 + u) * lw] = ts[u];
@@ -343,13 +347,10 @@ __global__ void __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 
     }
 #pragma unroll
     for (int u = 0; u < kDeg; ++u)
-      if (u < dI) {
-        const int tj = s.t[c_from[u]];
-        // the buffer lives in the array only if its version is outside the sender's ring now
-        if (s.tau_c[ce0 + u] < tj - (M - 2)) {
-          if (blk.rebase) rt[u] = sub(rt[u], mul_s(c_w[u], at(sg_l, c_col[u], tj % M)));
-          V<VEC>::st(s.rho_tilde + (size_t)(ce0 + u) * p + k, rt[u]);
-        }
+      // the buffer lives in the array only if its version is outside the sender's ring now
+      if (u < dI && (rt_where[u] & 2)) {
+        if (blk.rebase) rt[u] = sub(rt[u], mul_s(c_w[u], at(sg_l, c_col[u], end_slot[u])));
+        V<VEC>::st(s.rho_tilde + (size_t)(ce0 + u) * p + k, rt[u]);
       }
   }
   if (W > 1) __syncthreads();  // every wavefront of the workgroup is through with its rounds
@@ -474,14 +475,18 @@ bool rfast_wave_eligible(const rfast_ctx* c) {
 
 int rfast_wave_lanes(const rfast_ctx* c) { return 64 / c->d.n; }
 
-// Wavefronts per workgroup: as many (4, 2 or 1) as make a row segment at least a cache line of 128 B wide
-// without costing a wavefront of the occupancy that LDS allows (measured on 16 nodes x 11.2 M coordinates,
-// nine ring slots, tile movement alone: 7.6 ms with 64 B segments, 6.3 ms with 128 B and with 256 B).
-static int wave_group(const rfast_ctx* c) {
+// Wavefronts per workgroup.  Short launches, which are mostly tile movement, gain from row segments of a
+// whole cache line of 128 B (as many wavefronts, 2 or 4, as that takes, unless LDS then holds fewer
+// wavefronts per CU); long ones lose more to the workgroup's barriers and to its wavefronts leaving together
+// than the wider segments save.  Measured on 16 nodes x 11.2 M coordinates, nine ring slots, ms per launch
+// with 1 / 2 / 4 wavefronts: 10 rounds 5.60 / 5.29 / 5.35, 20 rounds 7.15 / 7.17 / 7.27, 100 rounds
+// 22.5 / 23.4 / 23.1.
+static int wave_group(const rfast_ctx* c, int rounds) {
   const RfastDev& d = c->d;
   const int lw = 64 / d.n;
   const size_t one = wave_lds_bytes(d, lw), cu = 160 * 1024;
   if (c->wave_group == 1 || c->wave_group == 2 || c->wave_group == 4) return (size_t)c->wave_group * one <= cu ? c->wave_group : 1;
+  if (rounds >= 16) return 1;
   const size_t resident = std::min<size_t>(cu / one, 8);  // wavefronts of this kernel a CU holds (two per SIMD at most)
   int w = 1;
   while (w < 4 && (size_t)(w * lw) * sizeof(float4) < 128 && std::min<size_t>(cu / (2 * w * one) * (2 * w), 8) >= resident) w *= 2;
@@ -508,9 +513,42 @@ static hipError_t launch_wave(rfast_ctx* c, const RfastBlock& blk) {
   return hipGetLastError();
 }
 
+// A launch that does nothing (one workgroup that finds no coordinates and leaves): the first launch of a kernel
+// pays for loading its code, about 0.7 ms, which belongs to setting a context up and not to its first run.
+template <int kDeg, bool MOM, int W>
+static hipError_t prime_wave(rfast_ctx* c) {
+  const hipError_t e = hipFuncSetAttribute((const void*)rfast_wave_kernel<kDeg, MOM, W>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  if (e != hipSuccess) return e;
+  RfastDev none = c->d;
+  none.p = 0;
+  RfastBlock blk;
+  blk.gamma = 0.f;
+  blk.rounds = 0;
+  blk.rebase = 0;
+  hipLaunchKernelGGL((rfast_wave_kernel<kDeg, MOM, W>), dim3(1), dim3(64 * W), 0, c->stream, none, blk, 64 / c->d.n);
+  return hipGetLastError();
+}
+
+template <int kDeg, bool MOM>
+static hipError_t prime_wave_w(rfast_ctx* c) {
+  const size_t one = wave_lds_bytes(c->d, 64 / c->d.n), cu = 160 * 1024;
+  hipError_t e = prime_wave<kDeg, MOM, 1>(c);
+  if (e == hipSuccess && 2 * one <= cu) e = prime_wave<kDeg, MOM, 2>(c);
+  if (e == hipSuccess && 4 * one <= cu) e = prime_wave<kDeg, MOM, 4>(c);
+  return e;
+}
+
+// Loads the instantiations of the multi-round kernel that this context can launch (rfast_create,
+// rfast_set_optimizer).
+hipError_t rfast_wave_prime(rfast_ctx* c) {
+  if (!rfast_wave_eligible(c)) return hipSuccess;
+  if (c->d.mom || c->d.wd != 0.f) return c->max_degree <= 2 ? prime_wave_w<2, true>(c) : prime_wave_w<kWaveMaxDeg, true>(c);
+  return c->max_degree <= 2 ? prime_wave_w<2, false>(c) : prime_wave_w<kWaveMaxDeg, false>(c);
+}
+
 template <int kDeg, bool MOM>
 static hipError_t launch_wave_w(rfast_ctx* c, const RfastBlock& blk) {
-  switch (wave_group(c)) {
+  switch (wave_group(c, blk.rounds)) {
     case 4: return launch_wave<kDeg, MOM, 4>(c, blk);
     case 2: return launch_wave<kDeg, MOM, 2>(c, blk);
     default: return launch_wave<kDeg, MOM, 1>(c, blk);

@@ -101,6 +101,17 @@ def test_out_of_range_sample_row_is_clamped_and_reported():
     assert np.isfinite(gpu.read("X")).all()
 
 
+def test_out_of_range_class_label_is_clamped_and_reported():
+    w = configs.config4(d=64, K=32, samples=128, batch=64, rounds=2)
+    w.data["labels"][7, :] = 32          # one past the last class, in every sample of node 7
+    gpu = harness.make_gpu(w)
+    gpu.init(None, w.sched.initial_batch())
+    with pytest.raises(rf.RFastError) as ei:
+        gpu.check()
+    assert ei.value.code == -4 and "label" in str(ei.value) and "node 7" in str(ei.value)
+    assert np.isfinite(gpu.read("G")).all()
+
+
 def test_binding_rejects_wrong_schedule_shapes():
     w = configs.config0(rounds=2)
     gpu = harness.make_gpu(w)

@@ -329,6 +329,19 @@ int rfast_write_state(rfast_ctx* ctx, int32_t field, const void* host_src, size_
 /* Reductions over the current state (synchronous).  d_xstar: device fp32 [p] or NULL. */
 int rfast_diagnostics(rfast_ctx* ctx, const float* d_xstar, rfast_diag* host_out);
 
+/* rfast_diagnostics for callers that cannot allocate or wait: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same reductions and kernels, but their scratch (the fp64 accumulators
+ * and, for the objectives whose loss needs it, the node average xbar) lives in a static device array of the
+ * library instead of the workspace, nothing is allocated, freed or copied to the host, and the call does not
+ * wait: the six results are written, in the order of rfast_diag, to d_out (DEVICE, 6 doubles, 8-byte aligned)
+ * by the last kernel enqueued on the context's stream.  xbar_gap_sq is -1 without d_xstar.
+ * Limit: least squares, logistic and softmax objectives need p <= 1 048 576 (the xbar part of the scratch,
+ * 4 MiB + 256 B per GPU for the life of the process); larger p returns RFAST_ERANGE.  The diagonal quadratic
+ * has no limit.  All contexts on one GPU share the array: calls that overlap on one GPU (different streams)
+ * race; calls on one stream, or otherwise ordered, do not.  (rfast_sync_round's pending z is folded back
+ * first, as in rfast_diagnostics.) */
+int rfast_diagnostics_static(rfast_ctx* ctx, const float* d_xstar, double* d_out);
+
 /* Kernel timing: when enabled, HIP events bracket the state-update kernels and
  * the gradient kernels of each round (at most 4096 rounds are kept since the
  * last enable).  rfast_kernel_time waits for the stream and returns the summed

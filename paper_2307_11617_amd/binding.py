@@ -34,7 +34,7 @@ RFAST_FIELDS = {"X": 0, "Z": 1, "G": 2, "V_RING": 3, "RHO_RING": 4, "RHO_TILDE":
                 "T_HIST": 15, "SCHED_ACTIVE": 16, "SCHED_DELAY_R": 17, "SCHED_DELAY_C": 18, "SCHED_DROP_R": 19,
                 "SCHED_DROP_C": 20, "SCHED_BATCH": 21, "MOMENTUM": 22}
 EXPORTS = ["rfast_common_roots", "rfast_workspace_bytes", "rfast_create", "rfast_init", "rfast_round", "rfast_run", "rfast_run_generated", "rfast_run_events", "rfast_use_graphs", "rfast_use_blocks", "rfast_block_info", "rfast_set_tile_group", "rfast_sync_round", "rfast_sync_run", "rfast_rebase", "rfast_set_rebase_interval", "rfast_set_optimizer", "rfast_set_gamma_schedule", "rfast_check",
-           "rfast_read_state", "rfast_write_state", "rfast_diagnostics", "rfast_profile_enable", "rfast_kernel_time", "rfast_last_error",
+           "rfast_read_state", "rfast_write_state", "rfast_diagnostics", "rfast_diagnostics_static", "rfast_profile_enable", "rfast_kernel_time", "rfast_last_error",
            "rfast_destroy"]
 
 
@@ -92,6 +92,8 @@ def lib():
     L.rfast_write_state.argtypes = [vp, i32, vp, sz]
     L.rfast_diagnostics.restype = C.c_int
     L.rfast_diagnostics.argtypes = [vp, vp, C.POINTER(RfastDiag)]
+    L.rfast_diagnostics_static.restype = C.c_int
+    L.rfast_diagnostics_static.argtypes = [vp, vp, vp]
     L.rfast_profile_enable.restype = C.c_int
     L.rfast_profile_enable.argtypes = [vp, i32]
     L.rfast_kernel_time.restype = C.c_int
@@ -234,6 +236,11 @@ def rfast_diagnostics(ctx, xstar=None):
     d = RfastDiag()
     _chk(lib().rfast_diagnostics(ctx, _dev_ptr(xstar), C.byref(d)), ctx)
     return {k: getattr(d, k) for k, _ in RfastDiag._fields_}
+
+
+def rfast_diagnostics_static(ctx, xstar, out):
+    """out: device tensor of 6 float64; asynchronous (read it after synchronising the stream)."""
+    _chk(lib().rfast_diagnostics_static(ctx, _dev_ptr(xstar), _dev_ptr(out)), ctx)
 
 
 def rfast_profile_enable(ctx, on=True):

@@ -491,7 +491,7 @@ int rfast_create(rfast_ctx** out, int32_t n, int64_t p, const int32_t* R_rowptr,
   c->d_diag = (double*)(b + o.diag);
   d.prob = *prob;
 
-  hipError_t e = hipSuccess;
+  hipError_t e = rfast_static_scratch_init();  // for rfast_diagnostics_static, which may not look anything up later
   auto chk = [&](hipError_t r) { if (e == hipSuccess) e = r; };
   chk(upload(c, b, o.r_ptr, gr.ptr)); chk(upload(c, b, o.r_src, gr.src)); chk(upload(c, b, o.r_dst, gr.dst)); chk(upload(c, b, o.r_w, gr.w));
   chk(upload(c, b, o.r_self, gr.self));
@@ -1115,6 +1115,19 @@ int rfast_diagnostics(rfast_ctx* c, const float* d_xstar, rfast_diag* host_out) 
   // variant each add n * coefficient/2 * ||xbar||^2
   const double l2 = (c->d.prob.kind == RFAST_OBJ_LOGISTIC ? (double)c->d.prob.lambda : 0.0) + (double)c->d.wd;
   host_out->loss_at_xbar = h[5] + 0.5 * l2 * c->d.n * h[6];
+  return RFAST_OK;
+}
+
+int rfast_diagnostics_static(rfast_ctx* c, const float* d_xstar, double* d_out) {
+  if (!c || !d_out) return RFAST_EINVAL;
+  if (c->d.prob.kind != RFAST_OBJ_DIAG_QUADRATIC && c->d.p > rfast_static_max_coords())
+    return fail(c, RFAST_ERANGE, "rfast_diagnostics_static: p = " + std::to_string(c->d.p) + " exceeds the " +
+                                     std::to_string(rfast_static_max_coords()) +
+                                     " coordinates its static scratch holds for this objective (use rfast_diagnostics)");
+  if (fold_sync(c) != RFAST_OK) return RFAST_EHIP;
+  const double l2 = (c->d.prob.kind == RFAST_OBJ_LOGISTIC ? (double)c->d.prob.lambda : 0.0) + (double)c->d.wd;
+  const hipError_t e = rfast_launch_diag_static(c, d_xstar, d_out, 0.5 * l2 * c->d.n);
+  if (e != hipSuccess) return hipfail(c, e, "diagnostics launch (static scratch)");
   return RFAST_OK;
 }
 

@@ -65,7 +65,7 @@ __global__ void __launch_bounds__(kThreads) rfast_diag_kernel(RfastDev s, const 
       reinterpret_cast<float*>(&xbar_f)[u] = (float)xbar[u];
       acc[6] += xbar[u] * xbar[u];
     }
-    V<VEC>::st(s.xbar + k, xbar_f);
+    if (s.xbar) V<VEC>::st(s.xbar + k, xbar_f);  // staged for the loss kernels of the objectives that need it
 #pragma unroll 2
     for (int i = 0; i < s.n; ++i) {
       const size_t off = (size_t)i * p + k;
@@ -148,7 +148,63 @@ __global__ void __launch_bounds__(kThreads) rfast_loss_rows_kernel(RfastDev s, d
   }
 }
 
+// The six results in the order of rfast_diag, from the accumulators (what rfast_diagnostics does on the host).
+__global__ void rfast_diag_finish(const double* acc, double l2_half_n, int has_xstar, double* out) {
+  if (threadIdx.x == 0) {
+    out[0] = acc[0];
+    out[1] = acc[1];
+    out[2] = acc[2];
+    out[3] = acc[3];
+    out[4] = has_xstar ? acc[4] : -1.0;
+    out[5] = acc[5] + l2_half_n * acc[6];
+  }
+}
+
+// Scratch of rfast_diagnostics_static, the entry point that allocates nothing: the fp64 accumulators of the
+// reductions, then the node average xbar that the loss kernels of the non-separable objectives read.  One copy per
+// GPU, held until the process ends; every call on a GPU shares it.
+constexpr size_t kStaticAccBytes = 256;
+constexpr int64_t kStaticMaxCoords = 1 << 20;
+__device__ __align__(256) unsigned char scratch[kStaticAccBytes + kStaticMaxCoords * sizeof(float)];
+constexpr int kMaxDevices = 64;
+void* g_scratch[kMaxDevices] = {};  // device address of `scratch` on each GPU (the array's name is no device address in host code)
+
 }  // namespace
+
+// Looks up the address of the static scratch array on the current device, once per device.
+hipError_t rfast_static_scratch_init() {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  if (g_scratch[dev]) return hipSuccess;
+  void* ptr = nullptr;
+  e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+  if (e != hipSuccess) return e;
+  if (!ptr) return hipErrorInvalidSymbol;
+  g_scratch[dev] = ptr;
+  return hipSuccess;
+}
+
+int64_t rfast_static_max_coords() { return kStaticMaxCoords; }
+
+// rfast_launch_diag with the accumulators and xbar in the static scratch of the current device, and the six
+// results written to d_out (device) by a last small kernel.  The caller has checked the size.
+hipError_t rfast_launch_diag_static(rfast_ctx* c, const float* d_xstar, double* d_out, double l2_half_n) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices || !g_scratch[dev]) return hipErrorNotInitialized;
+  unsigned char* base = static_cast<unsigned char*>(g_scratch[dev]);
+  double* acc = reinterpret_cast<double*>(base);
+  float* keep = c->d.xbar;
+  c->d.xbar = c->d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC ? nullptr : reinterpret_cast<float*>(base + kStaticAccBytes);
+  e = rfast_launch_diag(c, d_xstar, acc);  // clears the accumulators with a kernel first
+  c->d.xbar = keep;
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(rfast_diag_finish, dim3(1), dim3(64), 0, c->stream, acc, l2_half_n, d_xstar ? 1 : 0, d_out);
+  return hipGetLastError();
+}
 
 hipError_t rfast_launch_diag(rfast_ctx* c, const float* d_xstar, double* d_out) {
   hipLaunchKernelGGL(rfast_diag_zero, dim3(1), dim3(64), 0, c->stream, d_out);

@@ -186,6 +186,9 @@ hipError_t rfast_launch_init_grad(rfast_ctx* c, const int32_t* batch_idx0);
 hipError_t rfast_diag_init_gradient(rfast_ctx* c);  // separable objective: g[t_i & 1][i] = sample(x_i, t_i) for every node
 hipError_t rfast_launch_gradient(rfast_ctx* c, const int32_t* batch_idx);
 hipError_t rfast_launch_diag(rfast_ctx* c, const float* d_xstar, double* d_out);
+hipError_t rfast_static_scratch_init();  // address of the static scratch array on the current device (once per device)
+int64_t rfast_static_max_coords();
+hipError_t rfast_launch_diag_static(rfast_ctx* c, const float* d_xstar, double* d_out, double l2_half_n);
 hipError_t rfast_softmax_loss(rfast_ctx* c, double* d_out);  // adds sum_i f_i(xbar) to *d_out
 bool rfast_softmax_prep_is_fused(const rfast_problem* prob);
 size_t rfast_grad_scratch_bytes(int32_t n, int64_t p, const rfast_problem* prob);

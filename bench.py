@@ -140,10 +140,9 @@ def counted_traffic(workload_name, kernel, rounds_per_launch):
     try:
         if fields.get("workload") != workload_name or not fields.get("kernel", "").startswith(f"rfast_{kernel}_kernel"):
             return None
-        if int(fields.get("rounds_per_launch", "1")) != int(rounds_per_launch):
-            return None
-        return {"bytes_per_launch": float(fields["traffic_bytes_per_launch"]),
-                "source": f"profiles/{os.path.basename(path)} (rocprofv3 --pmc run of its own, not measured in this run)"}
+        return {"bytes_per_launch": float(fields[f"traffic_bytes_per_launch@{int(rounds_per_launch)}"]),
+                "source": f"profiles/{os.path.basename(path)} (rocprofv3 --pmc run of its own on this workload, kernel and "
+                          f"launch length; not measured in this run)"}
     except (KeyError, ValueError):
         return None
 

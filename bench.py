@@ -10,13 +10,16 @@ quoted on.  Prints ONE JSON line.
 Three legs, all on the same context, one after the other:
   1. W warm-up rounds, then the K timed rounds as one rfast_run call (wall clock between two
      device synchronisations): `value`, `ms_per_step`.
-  2. the next K rounds once more with HIP events around every launch on the library's stream:
-     `roofline` of the kernel that ran them (for the separable objective on a small graph one
-     launch of the multi-round kernel; its bytes are computed from the counters and stamps
-     read before and after the launch, by the rules the kernel moves its tiles by).
-  3. (separable objective) up to 20 further rounds with one kernel pass per round
-     (rfast_use_blocks off), events around every pass: `roofline_one_pass`, the HBM view of
-     `rfast_state_kernel<FUSED>`; its bytes are counted per round from the stamps that moved.
+  2. the next K rounds once more with HIP events around every launch on the library's stream, in
+     calls cut where the counters and stamps can be read between launches: `roofline` of the kernel
+     that ran them.  A launch of the multi-round kernel is priced against whichever of its two needs
+     takes longer at the published peaks: the method's arithmetic (40 flop per coordinate and
+     node-update, 157.3 TFLOP/s) or the bytes it moves (8 TB/s), the bytes computed from the counters
+     and stamps read before and after the launch by the rules the kernel moves its tiles by.  Rounds
+     that run one pass over HBM each are priced in bytes, counted per round from the stamps that moved.
+  3. (where leg 2 ran several rounds per launch) up to 20 further rounds with one kernel pass per
+     round (rfast_use_blocks off), events around every pass: `roofline_one_pass`, the HBM view of
+     `rfast_state_kernel<FUSED>`.
 Nothing in the output is a constant taken from a file, except `traffic` (HBM bytes counted by
 rocprofv3 --pmc in a run of its own, see profiles/), which is carried only when the summary
 names the same kernel, workload and launch length, and is labelled as not measured here.
@@ -82,19 +85,25 @@ def read_stamps(gpu):
 
 
 def one_pass_bytes(w, edges, before, after, active):
-    """Bytes one pass of rfast_state_kernel<FUSED> moves for a round, from the stamps before and after it:
-    per active node and coordinate it reads x, z, h, c, one v per in-edge of R, its own current running sum
-    (if it has out-edges over C) and two running sums (the one consumed now, the one consumed last time) per
-    in-edge of C whose stamp moved; it writes x, z, v and the new running sum.  (The rare copies of an S4
-    buffer that leaves its sender's ring are not counted.)"""
+    """Bytes the state kernels move for one round that ran one pass (two for the objectives whose gradient kernels
+    run between a mixing and a tracking pass), from the stamps before and after it.  Per active node and coordinate,
+    separable objective (`rfast_state_kernel<FUSED>`): reads x, z, h, c, one v per in-edge of R, the node's own current
+    running sum (if it has out-edges over C) and two running sums (the one consumed now, the one consumed last time)
+    per in-edge of C whose stamp moved; writes x, z, v and the new running sum.  Other objectives (`<MIX>` then
+    `<TRACK>`): x, z, the v's in and x, v out (softmax: plus the bf16 copy of the weights, half a word), then z, the old
+    and the new sample, the own running sum and the two sums per moved edge in, z and the new running sum out.  (The
+    rare copies of an S4 buffer that leaves its sender's ring are not counted.)"""
     dR, dI, dO = degrees(w)
     (_, _), (c_src, c_dst) = edges
     live = np.zeros(w.n, dtype=np.int64)
     moved = after["tau_c"] != before["tau_c"]
     np.add.at(live, c_dst[moved], 1)
-    act = active.astype(bool)
-    pushes = (dO > 0).astype(np.int64)
-    words = (4 + dR + pushes + 2 * live) + (3 + pushes)
+    act = np.asarray(active).astype(bool)
+    pushes = (dO > 0).astype(np.float64)
+    if w.objective == "diag_quadratic":
+        words = (4 + dR + pushes + 2 * live) + (3 + pushes)
+    else:
+        words = (2 + dR) + 2 + (0.5 if w.objective == "softmax_bf16" else 0.0) + (3 + pushes + 2 * live) + (1 + pushes)
     return float(words[act].sum()) * 4.0 * w.p
 
 
@@ -296,21 +305,30 @@ def main():
     gpu.check()
     t_after = int(gpu.read("T_NODE").sum()) if args.generated else 0
 
-    # ---- leg 2: the next K rounds with HIP events around every kernel launch (on the library's stream).  The library
-    # cuts multi-round launches at the multiples of the rebase interval; the calls here are cut at the same rounds,
-    # so that the counters and stamps can be read between the launches.
-    multi = (not args.sync and not args.generated and separable and rf.rfast_block_info(gpu.ctx) != 0)
+    # ---- leg 2: the next K rounds with HIP events around every kernel launch (on the library's stream), in calls cut
+    # so that the counters and stamps can be read between the launches: where the library takes several rounds per
+    # launch, at the multiples of the rebase interval (where it cuts its launches itself); else round by round.
+    multi = not args.sync and separable and rf.rfast_block_info(gpu.ctx) != 0
+    momentum_words = 2.0 if args.momentum != 0.0 else 0.0
+    edges = edge_lists(w)
     segs, r = [], W + K
     while r < W + 2 * K:
-        nxt = min(W + 2 * K, (r // REBASE_INTERVAL + 1) * REBASE_INTERVAL) if multi else W + 2 * K
+        if args.sync:
+            nxt = W + 2 * K
+        elif multi:
+            nxt = min(W + 2 * K, (r // REBASE_INTERVAL + 1) * REBASE_INTERVAL)
+        else:
+            nxt = r + 1
         segs.append((r, nxt))
         r = nxt
     ms_state = ms_grad = ms_res = 0.0
     n_state = n_grad = n_res = 0
-    launches_multi = []   # (rounds, ms, stamps before, stamps after, rebased) of every multi-round launch
-    stamps0 = read_stamps(gpu)
+    # launches of the multi-round kernel (rounds, ms, bytes, rows in, rows out, node-updates) and, of the rounds that ran
+    # one pass each, time, bytes and node-updates
+    launches_multi, one_ms, one_bytes, one_updates, one_launches = [], 0.0, 0.0, 0, 0
+    lanes, per_wave = rf.rfast_block_info(gpu.ctx, with_kind=True) if multi else (0, False)
     for lo, hi in segs:
-        before = read_stamps(gpu)
+        before = None if args.sync else read_stamps(gpu)
         rf.rfast_profile_enable(gpu.ctx, True)
         run(cut(lo, hi), hi - lo)
         ms, cnt = rf.rfast_kernel_time(gpu.ctx, 0)
@@ -319,76 +337,74 @@ def main():
         rf.rfast_profile_enable(gpu.ctx, False)
         ms_state, ms_grad, ms_res = ms_state + ms, ms_grad + ms_g, ms_res + ms_r
         n_state, n_grad, n_res = n_state + cnt, n_grad + cnt_g, n_res + cnt_r
+        if args.sync:
+            continue
+        after = read_stamps(gpu)
+        done = int((after["t"] - before["t"]).sum())
         if multi and cnt == 1 and hi - lo > 1:
-            launches_multi.append((hi - lo, ms, before, read_stamps(gpu), hi % REBASE_INTERVAL == 0))
-    stamps1 = read_stamps(gpu)
-
-    act_timed = st["active"][W:W + K].astype(np.int64)
-    act_prof = st["active"][W + K:W + 2 * K].astype(np.int64)
-    if args.sync:
-        act_timed, act_prof = np.ones_like(act_timed), np.ones_like(act_prof)
-    updates = (t_after - t_before) if args.generated else int(act_timed.sum())
-    bytes_alg = sum(algorithmic_bytes_per_round(w, a) for a in act_prof)
-    bytes_layout = sum(algorithmic_bytes_per_round(w, a, layout=True) for a in act_prof)
-    if args.sync:
-        # descent: x, z -> v (3 words); step: 1+dR v's, 1+dI z's in, x and z out, plus
-        #   separable objective: the old x (its sample is recomputed, not stored), h, c in (3 words)
-        #   otherwise: the old and the new sample in (2 words)
-        dR, dI, _ = degrees(w)
-        words = 3 + (1 + dR) + (1 + dI) + 2 + (3 if separable else 2)
-        bytes_alg = bytes_layout = float(words.sum() * 4.0 * w.p * K)
-    if args.momentum != 0.0:   # read and write of the buffer m_i
-        extra = 8.0 * w.p * (w.n * K if args.sync else float(act_prof.sum()))
-        bytes_alg, bytes_layout = bytes_alg + extra, bytes_layout + extra
-    launches = max(n_state, 1)
-    avg_ms = ms_state / launches
-    # several rounds per launch with the state resident in LDS (the default where it applies)
-    # (graph replays, which the timed pass of --graphs uses, are one pass per round; the event-timed pass cannot replay)
-    blocked = not args.sync and not args.graphs and separable and 0 < n_state < K
-    lanes, per_wave = rf.rfast_block_info(gpu.ctx, with_kind=True) if blocked else (0, False)
-    if args.sync:
-        kernel = "rfast_sync_wave_kernel (several steps per launch, state in registers and LDS)" if 0 < n_state < K else "rfast_sync_descent+step"
-    elif blocked:
-        kernel = f"rfast_wave_kernel<{lanes} lanes per node>" if per_wave else f"rfast_block_kernel<{lanes} lanes per node>"
-    else:
-        kernel = "rfast_state_kernel" + ("<FUSED>" if separable else "<MIX>+<TRACK>")
-    headline = not (args.p or args.sync or variant or args.generated or args.noise_std is not None)
-    edges = edge_lists(w)
-    secs = ms_state * 1e-3
-
-    if blocked and launches_multi:
-        # Launches that took their rounds with the state in LDS.  Such a launch has to do the method's arithmetic for its
-        # rounds and to move the live state once in and once out; whichever takes longer at the published peaks bounds it.
-        moved = flops = secs = 0.0
-        rows_in = rows_out = 0
-        for rounds_l, ms_l, b_l, a_l, rebased in launches_multi:
             if per_wave:
-                mv, ri, ro = multi_round_bytes(w, edges, b_l, a_l, rebased)
+                mv, ri, ro = multi_round_bytes(w, edges, before, after, hi % REBASE_INTERVAL == 0)
             else:   # the workgroup-tile kernel moves every ring slot and every buffer in and out
                 ri = w.n * (2 * (w.D + 2) + 4) + w.C.nnz_off
                 ro = w.n * (2 * (w.D + 2) + 2) + w.C.nnz_off
                 mv = float(ri + ro) * 4.0 * w.p
-            moved, rows_in, rows_out = moved + mv, rows_in + ri, rows_out + ro
-            flops += FLOPS_PER_COORDINATE * w.p * float((a_l["t"] - b_l["t"]).sum())
-            secs += ms_l * 1e-3
-        n_multi = len(launches_multi)
-        rounds_multi = sum(l[0] for l in launches_multi)
-        moved, flops, rows_in, rows_out = moved / n_multi, flops / n_multi, rows_in / n_multi, rows_out / n_multi
-        secs /= n_multi   # per launch from here on
-        avg_ms = secs * 1e3
+            mv += momentum_words * 4.0 * w.p * w.n
+            launches_multi.append((hi - lo, ms, mv, ri, ro, done))
+        elif hi - lo == 1:
+            act = (after["t"] != before["t"])
+            one_bytes += one_pass_bytes(w, edges, before, after, act) + momentum_words * 4.0 * w.p * float(act.sum())
+            one_ms, one_updates, one_launches = one_ms + ms, one_updates + done, one_launches + cnt
+
+    act_timed = st["active"][W:W + K].astype(np.int64)
+    act_prof = st["active"][W + K:W + 2 * K].astype(np.int64)
+    updates = (t_after - t_before) if args.generated else (w.n * K if args.sync else int(act_timed.sum()))
+    headline = not (args.p or args.sync or variant or args.generated or args.noise_std is not None)
+
+    def hbm_or_alu(moved, flops, secs):
+        """The roofline of work that needs `moved` bytes of HBM traffic and `flops` of fp32 vector arithmetic and took
+        `secs`: the bound is whichever takes longer at the published peak, and the fraction is against that peak."""
         t_alu, t_hbm = flops / (FP32_VECTOR_PEAK_TFLOPS * 1e12), moved / (HBM_PEAK_GBS * 1e9)
-        counted = counted_traffic(w.name, "wave", rounds_multi // n_multi) if headline and rounds_multi % n_multi == 0 else None
         if t_hbm >= t_alu:
             roof = {"bound": "hbm", "achieved": moved / secs / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
         else:
             roof = {"bound": "alu", "achieved": flops / secs / 1e12, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s"}
         roof["frac"] = roof["achieved"] / roof["peak"]
-        roof.update({"kernel": kernel, "avg_kernel_ms": avg_ms, "launches": n_multi, "rounds_per_launch": rounds_multi / n_multi,
-                     "bytes_per_launch": moved, "rows_per_node_in": rows_in / w.n, "rows_per_node_out": rows_out / w.n,
-                     "flops_per_launch": flops, "intensity_flop_per_byte": flops / moved,
+        roof.update({"bytes_per_launch": moved, "flops_per_launch": flops, "intensity_flop_per_byte": flops / moved,
                      "ridge_flop_per_byte": FP32_VECTOR_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9),
                      "time_at_hbm_peak_ms": t_hbm * 1e3, "time_at_fp32_vector_peak_ms": t_alu * 1e3,
-                     "achieved_gbs": moved / secs / 1e9, "achieved_tflops": flops / secs / 1e12,
+                     "achieved_gbs": moved / secs / 1e9, "achieved_tflops": flops / secs / 1e12})
+        return roof
+
+    if args.sync:
+        # eq. (2), all nodes at once.  One step per launch pair: descent x, z -> v (3 words), step 1 + dR v's and 1 + dI
+        # z's in, x and z out, plus the old x, h, c (separable objective: its sample is recomputed) or the old and the
+        # new sample.  Several steps per launch: x, z, h, c in, x, z, v out once per launch.
+        dR, dI, _ = degrees(w)
+        many = 0 < n_state < K
+        if many:
+            moved = (7.0 + momentum_words) * 4.0 * w.p * w.n
+            kernel = "rfast_sync_wave_kernel (several steps per launch, state in registers and LDS)"
+        else:
+            moved = float((3 + (1 + dR) + (1 + dI) + 2 + (3 if separable else 2) + momentum_words).sum()) * 4.0 * w.p
+            kernel = "rfast_sync_descent_kernel + rfast_sync_step_kernel"
+        per = max(n_state if many else K, 1)
+        flops = FLOPS_PER_COORDINATE * w.p * w.n * (K / per if many else 1.0) if separable else 0.0
+        roof = hbm_or_alu(moved, flops, ms_state * 1e-3 / per)
+        roof.update({"kernel": kernel, "avg_kernel_ms": ms_state / per, "launches": per, "traffic": None})
+    elif launches_multi:
+        # Launches that took their rounds with the state in LDS.  Such a launch has to do the method's arithmetic for its
+        # rounds and to move the live state once in and once out.
+        n_multi = len(launches_multi)
+        rounds_multi = sum(l[0] for l in launches_multi)
+        secs = sum(l[1] for l in launches_multi) * 1e-3 / n_multi
+        moved = sum(l[2] for l in launches_multi) / n_multi
+        flops = FLOPS_PER_COORDINATE * w.p * sum(l[5] for l in launches_multi) / n_multi
+        kernel = f"rfast_wave_kernel<{lanes} lanes per node>" if per_wave else f"rfast_block_kernel<{lanes} lanes per node>"
+        counted = counted_traffic(w.name, "wave", rounds_multi // n_multi) if headline and per_wave and rounds_multi % n_multi == 0 else None
+        roof = hbm_or_alu(moved, flops, secs)
+        roof.update({"kernel": kernel, "avg_kernel_ms": secs * 1e3, "launches": n_multi, "rounds_per_launch": rounds_multi / n_multi,
+                     "rows_per_node_in": sum(l[3] for l in launches_multi) / n_multi / w.n,
+                     "rows_per_node_out": sum(l[4] for l in launches_multi) / n_multi / w.n,
                      "traffic": counted["bytes_per_launch"] if counted else None,
                      "traffic_source": counted["source"] if counted else None,
                      "note": "bytes_per_launch: what the launch moves by its own rules (live ring slots, x, z, h, c, buffers "
@@ -396,15 +412,25 @@ def main():
                              "flops_per_launch: 40 per coordinate and node-update (Algorithm 1 and the float side of the "
                              "Gaussian noise; the integer work of the counter-based generator is not a flop)"})
     else:
-        achieved = bytes_layout / secs / 1e9 if secs > 0 else 0.0
-        roof = {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "avg_kernel_ms": avg_ms, "launches": n_state,
-                "bytes_per_launch": bytes_layout / launches,
-                "algorithmic_bytes_per_launch": bytes_alg / launches,
-                "algorithmic_gbs": bytes_alg / secs / 1e9 if secs > 0 else 0.0,
-                "traffic": None,
-                "note": "bytes_per_launch: the words this layout has to move per node-update (skipped edges not credited); "
-                        "algorithmic_*: the literal count of Algorithm 1, which this layout undercuts (not a bound)"}
+        # One pass over HBM per round (two for the objectives whose gradient runs between them).
+        secs = one_ms * 1e-3
+        launches = max(one_launches, 1)
+        kernel = "rfast_state_kernel" + ("<FUSED>" if separable else "<MIX> + <TRACK>")
+        act1 = act_prof
+        alg1 = sum(algorithmic_bytes_per_round(w, a) for a in act1)
+        lay1 = sum(algorithmic_bytes_per_round(w, a, layout=True) for a in act1)
+        counted = counted_traffic(w.name, "state", 1) if headline and separable else None
+        roof = {"bound": "hbm", "kernel": kernel, "achieved": one_bytes / secs / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": one_bytes / secs / 1e9 / HBM_PEAK_GBS, "avg_kernel_ms": one_ms / launches, "launches": one_launches,
+                "bytes_per_launch": one_bytes / launches,
+                "layout_bytes_per_launch": lay1 / launches, "layout_gbs": lay1 / secs / 1e9,
+                "algorithmic_bytes_per_launch": alg1 / launches, "algorithmic_gbs": alg1 / secs / 1e9,
+                "traffic": counted["bytes_per_launch"] if counted else None,
+                "traffic_source": counted["source"] if counted else None,
+                "note": "bytes_per_launch counts what the state kernels read and write, edges whose stamp did not move "
+                        "skipped (computed per round from the stamps before and after it); layout_*: the words of this "
+                        "layout with no skip credited; algorithmic_*: the literal count of Algorithm 1, which the layout "
+                        "undercuts, so its rate may exceed the peak and is not a fraction of it"}
 
     out = {
         "metric": "node-updates/sec",
@@ -425,8 +451,8 @@ def main():
         "host_data_generation_s": gen_s,
     }
 
-    # ---- leg 3: one kernel pass per round, the HBM view of the fused round kernel
-    if K1 > 0:
+    # ---- leg 3 (where leg 2 ran several rounds per launch): one kernel pass per round, the HBM view of the fused round kernel
+    if K1 > 0 and launches_multi:
         rf.rfast_use_blocks(gpu.ctx, False)
         r0 = W + 2 * K
         moved = 0.0
@@ -439,7 +465,9 @@ def main():
             rf.rfast_profile_enable(gpu.ctx, False)
             assert cnt == 1, cnt
             ms_one += ms
-            moved += one_pass_bytes(w, edges, before, read_stamps(gpu), st["active"][r0 + q])
+            after = read_stamps(gpu)
+            act = after["t"] != before["t"]
+            moved += one_pass_bytes(w, edges, before, after, act) + momentum_words * 4.0 * w.p * float(act.sum())
         act1 = st["active"][r0:r0 + K1].astype(np.int64)
         alg1 = sum(algorithmic_bytes_per_round(w, a) for a in act1)
         lay1 = sum(algorithmic_bytes_per_round(w, a, layout=True) for a in act1)

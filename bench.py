@@ -309,13 +309,15 @@ def main():
     # so that the counters and stamps can be read between the launches: where the library takes several rounds per
     # launch, at the multiples of the rebase interval (where it cuts its launches itself); else round by round.
     multi = not args.sync and separable and rf.rfast_block_info(gpu.ctx) != 0
+    # least squares / logistic problems that fit the LDS of one CU: one workgroup takes a stretch of rounds per launch
+    tiny = not args.sync and not separable and rf.rfast_block_info(gpu.ctx) != 0
     momentum_words = 2.0 if args.momentum != 0.0 else 0.0
     edges = edge_lists(w)
     segs, r = [], W + K
     while r < W + 2 * K:
         if args.sync:
             nxt = W + 2 * K
-        elif multi:
+        elif multi or tiny:
             nxt = min(W + 2 * K, (r // REBASE_INTERVAL + 1) * REBASE_INTERVAL)
         else:
             nxt = r + 1
@@ -341,7 +343,11 @@ def main():
             continue
         after = read_stamps(gpu)
         done = int((after["t"] - before["t"]).sum())
-        if multi and cnt == 1 and hi - lo > 1:
+        if tiny and cnt == 1 and hi - lo > 1:
+            # the whole state once in and once out per launch: x, z, the stored sample, every ring slot, every S4 buffer
+            rows_state = w.n * (3 + 2 * (w.D + 2)) + w.C.nnz_off
+            launches_multi.append((hi - lo, ms, 2.0 * rows_state * 4.0 * w.p, rows_state, rows_state, done))
+        elif multi and cnt == 1 and hi - lo > 1:
             if per_wave:
                 mv, ri, ro = multi_round_bytes(w, edges, before, after, hi % REBASE_INTERVAL == 0)
             else:   # the workgroup-tile kernel moves every ring slot and every buffer in and out
@@ -399,7 +405,12 @@ def main():
         secs = sum(l[1] for l in launches_multi) * 1e-3 / n_multi
         moved = sum(l[2] for l in launches_multi) / n_multi
         flops = FLOPS_PER_COORDINATE * w.p * sum(l[5] for l in launches_multi) / n_multi
+        if tiny:   # the GEMV pair of the sampled gradient: 4 B p flop per node-update, plus Algorithm 1's own 21 per coordinate
+            flops = (4.0 * (w.sched.batch or w.data["A" if w.objective == "least_squares" else "X"].shape[1]) + 21.0) * w.p * \
+                sum(l[5] for l in launches_multi) / n_multi
         kernel = f"rfast_wave_kernel<{lanes} lanes per node>" if per_wave else f"rfast_block_kernel<{lanes} lanes per node>"
+        if tiny:
+            kernel = "rfast_tiny_kernel (one workgroup, the whole problem in LDS)"
         counted = counted_traffic(w.name, "wave", rounds_multi // n_multi) if headline and per_wave and rounds_multi % n_multi == 0 else None
         roof = hbm_or_alu(moved, flops, secs)
         roof.update({"kernel": kernel, "avg_kernel_ms": secs * 1e3, "launches": n_multi, "rounds_per_launch": rounds_multi / n_multi,
@@ -410,7 +421,12 @@ def main():
                      "note": "bytes_per_launch: what the launch moves by its own rules (live ring slots, x, z, h, c, buffers "
                              "outside their ring), computed here from the counters and stamps read before and after it; "
                              "flops_per_launch: 40 per coordinate and node-update (Algorithm 1 and the float side of the "
-                             "Gaussian noise; the integer work of the counter-based generator is not a flop)"})
+                             "Gaussian noise; the integer work of the counter-based generator is not a flop)"
+                             if not tiny else
+                             "one workgroup on one of 256 compute units, bound by instruction issue and LDS latency: the "
+                             "fraction of the chip's peak says how small the problem is, not how good the kernel is; "
+                             "bytes_per_launch: the whole state in and out once (the objective data, copied to LDS once per "
+                             "launch when they fit, not counted); flops_per_launch: (4 B + 21) p per node-update"})
     else:
         # One pass over HBM per round (two for the objectives whose gradient runs between them).
         secs = one_ms * 1e-3

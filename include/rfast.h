@@ -239,11 +239,19 @@ int rfast_use_graphs(rfast_ctx* ctx, int32_t on);
  * large state earns back only over that many rounds); rounds that do not qualify run one pass
  * each.  Every step of a round is elementwise in the coordinate, so a tile of coordinates can stay
  * in LDS over several rounds; the results are the same bits as round-by-round execution.
+ * Least squares and logistic regression (whose gradient couples the coordinates of a node, so that
+ * there are no tiles) take the same stretches of rounds with one launch of a single workgroup when the
+ * whole problem fits the LDS of one CU: p a multiple of 4, no heavy-ball buffer, (3 + 2 (D+2)) n p +
+ * eC p floats of state plus the graph, n (batch, or samples) residuals and row numbers and two plan
+ * records within 150 KB (the samples themselves too if they still fit, else they are read from global
+ * memory), at most 4096 sampled rows per round and n + eR + eC < 1024; same bits as the chain of
+ * four kernels per round.
  * on == 0: always one kernel pass per round.  on == 2: as the default, but 2 rounds are enough at
  * any size (for measurements). */
 int rfast_use_blocks(rfast_ctx* ctx, int32_t on);
 /* *lanes_per_node = 0 if a call of rfast_run for several rounds would now run one pass per round,
- * else the number of lanes per node of the multi-round kernel (its tile is 4 * lanes coordinates);
+ * else the number of lanes per node of the multi-round kernel (its tile is 4 * lanes coordinates;
+ * 1024 / n, at least 1, for the single workgroup of the non-separable objectives);
  * *tile_per_wavefront (may be NULL) = 1 if a tile belongs to one wavefront, 0 if to a workgroup. */
 int rfast_block_info(rfast_ctx* ctx, int32_t* lanes_per_node, int32_t* tile_per_wavefront);
 /* Tuning knob of the wavefront-tile kernel of rfast_use_blocks: wavefronts per workgroup (1, 2 or 4; 0 = chosen by

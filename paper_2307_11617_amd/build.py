@@ -13,7 +13,7 @@ ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "librfast.so")
 OBJ = os.path.join(PKG, "_build")
 SOURCES = ["rfast_api.cpp", "rfast_resolve.hip", "rfast_round.hip", "rfast_block.hip", "rfast_wave.hip", "rfast_grad.hip", "rfast_softmax.hip",
-           "rfast_diag.hip", "rfast_schedule.hip"]
+           "rfast_diag.hip", "rfast_schedule.hip", "rfast_tiny.hip"]
 # no floating-point contraction: the kernels that implement the separable round must round alike
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -623,7 +623,7 @@ static int float_round(rfast_ctx* c, float gamma, const int32_t* d_batch_idx) {
 // step of the step-size schedule; and it reads and writes every ring slot once, which a large
 // state earns back only over enough rounds.
 static int32_t block_length(const rfast_ctx* c, int32_t rounds, int64_t at_round = -1) {
-  if (!c->use_blocks || !(rfast_wave_eligible(c) || rfast_block_eligible(c))) return 0;
+  if (!c->use_blocks || !(rfast_wave_eligible(c) || rfast_block_eligible(c) || rfast_tiny_eligible(c))) return 0;
   const int64_t now = at_round >= 0 ? at_round : c->host_round;  // the round the launch would start with
   int32_t len = rounds < kBlockRounds ? rounds : kBlockRounds;
   if (c->rebase_interval > 0) {
@@ -641,7 +641,8 @@ static int32_t block_length(const rfast_ctx* c, int32_t rounds, int64_t at_round
 // Resolves `len` rounds (schedule arrays of round q at offset q of each pointer) into plan records,
 // one launch, and advances them with one launch.
 static int run_block(rfast_ctx* c, int32_t len, const uint8_t* d_active, const int32_t* d_delay_R,
-                     const int32_t* d_delay_C, const uint8_t* d_drop_R, const uint8_t* d_drop_C, float gamma) {
+                     const int32_t* d_delay_C, const uint8_t* d_drop_R, const uint8_t* d_drop_C, float gamma,
+                     const int32_t* d_batch_idx) {
   RfastDev& d = c->d;
   if (fold_sync(c) != RFAST_OK) return RFAST_EHIP;
   RfastBlock blk;
@@ -659,7 +660,8 @@ static int run_block(rfast_ctx* c, int32_t len, const uint8_t* d_active, const i
   time_end(c, 2);
   if (e == hipSuccess) {
     time_begin(c, 0);
-    e = rfast_wave_eligible(c) ? rfast_launch_wave(c, blk) : rfast_launch_block(c, blk);
+    if (rfast_tiny_eligible(c)) e = rfast_launch_tiny(c, blk, d_batch_idx, (int)(c->host_round - len));
+    else e = rfast_wave_eligible(c) ? rfast_launch_wave(c, blk) : rfast_launch_block(c, blk);
     time_end(c, 0);
   }
   d.blk_plan = nullptr;
@@ -675,6 +677,11 @@ static int run_block(rfast_ctx* c, int32_t len, const uint8_t* d_active, const i
 int rfast_block_info(rfast_ctx* c, int32_t* lanes_per_node, int32_t* tile_per_wavefront) {
   if (!c || !lanes_per_node) return RFAST_EINVAL;
   const bool taken = block_length(c, kBlockRounds) > 0, wave = rfast_wave_eligible(c);
+  if (taken && rfast_tiny_eligible(c)) {  // one workgroup holds the whole problem
+    *lanes_per_node = 1024 / c->d.n > 0 ? 1024 / c->d.n : 1;
+    if (tile_per_wavefront) *tile_per_wavefront = 0;
+    return RFAST_OK;
+  }
   *lanes_per_node = taken ? (wave ? rfast_wave_lanes(c) : rfast_block_lanes(c)) : 0;
   if (tile_per_wavefront) *tile_per_wavefront = taken && wave ? 1 : 0;
   return RFAST_OK;
@@ -708,10 +715,12 @@ int rfast_run(rfast_ctx* c, int32_t rounds, const uint8_t* d_active, const int32
         return fail(c, RFAST_EINVAL, "NULL schedule pointer");
       if (!std::isfinite(gamma)) return fail(c, RFAST_EINVAL, "gamma is not finite");
       if (c->needs_init) return fail(c, RFAST_EINVAL, "rfast_init must follow rfast_set_optimizer");
+      if (B > 0 && !d_batch_idx) return fail(c, RFAST_EINVAL, "sample rows are required when batch > 0");
       const int rc = run_block(c, len, d_active + (size_t)r * d.n, d_delay_R ? d_delay_R + (size_t)r * d.eR : nullptr,
                                d_delay_C ? d_delay_C + (size_t)r * d.eC : nullptr,
                                d_drop_R ? d_drop_R + (size_t)r * d.eR : nullptr,
-                               d_drop_C ? d_drop_C + (size_t)r * d.eC : nullptr, gamma);
+                               d_drop_C ? d_drop_C + (size_t)r * d.eC : nullptr, gamma,
+                               d_batch_idx ? d_batch_idx + (size_t)r * d.n * B : nullptr);
       if (rc != RFAST_OK) return rc;
       r += len - 1;
       continue;

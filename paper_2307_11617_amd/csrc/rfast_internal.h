@@ -176,6 +176,8 @@ hipError_t rfast_wave_prime(rfast_ctx* c);      // loads the kernels this contex
 bool rfast_block_eligible(const rfast_ctx* c);  // the multi-round kernel with one tile per workgroup
 int rfast_block_lanes(const rfast_ctx* c);  // lanes per node of the multi-round kernel, 0 if no tile fits
 hipError_t rfast_launch_block(rfast_ctx* c, const RfastBlock& blk);
+bool rfast_tiny_eligible(const rfast_ctx* c);   // the multi-round kernel for least squares / logistic problems that fit one CU's LDS
+hipError_t rfast_launch_tiny(rfast_ctx* c, const RfastBlock& blk, const int32_t* d_batch_idx, int round0);
 hipError_t rfast_launch_generate(rfast_ctx* c, uint64_t seed, const float* d_p_active, int d_max, float p_drop, bool events,
                                  int rounds = 1);
 hipError_t rfast_launch_sync(rfast_ctx* c, int phase, float gamma, int parity);

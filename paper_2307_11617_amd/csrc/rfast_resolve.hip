@@ -19,8 +19,20 @@
 
 namespace {
 
-__device__ inline bool delivered(unsigned long long bits, int v, int M) {
-  return v <= 0 || ((bits >> (v % M)) & 1ull);
+// v mod d for 0 <= v < 2^31 and a divisor fixed for the launch, without the integer division (some thirty
+// instructions per remainder, and a round takes about ten per edge): the quotient by the rounded-down reciprocal is at
+// most one short, so one conditional subtraction finishes it.
+struct FastMod {
+  unsigned d, magic;
+  __device__ explicit FastMod(int d_) : d((unsigned)d_), magic(0xFFFFFFFFu / (unsigned)d_) {}
+  __device__ int operator()(int v) const {
+    const unsigned r = (unsigned)v - __umulhi((unsigned)v, magic) * d;
+    return (int)(r >= d ? r - d : r);
+  }
+};
+
+__device__ inline bool delivered(unsigned long long bits, int v, const FastMod& modM) {
+  return v <= 0 || ((bits >> modM(v)) & 1ull);
 }
 
 __device__ inline void record_error(int32_t* err, int code, int round, int kind, int e) {
@@ -64,7 +76,7 @@ __device__ inline void edge_level2(const RfastDev& s, int r, const uint8_t* acti
 
 // Decides edge e for round r and leaves the new stamp and delivery bits in q as well (a lane that
 // keeps its edges over several rounds goes on from them).
-__device__ inline void edge_decide(const RfastDev& s, int kind, int e, int r, EdgeIn& q) {
+__device__ inline void edge_decide(const RfastDev& s, const FastMod& modM, int kind, int e, int r, EdgeIn& q) {
   int32_t* tau = kind ? s.tau_c : s.tau_r;
   int32_t* slot = kind ? s.slot_c : s.slot_r;
   unsigned long long* deliv = kind ? s.deliv_c : s.deliv_r;
@@ -72,19 +84,20 @@ __device__ inline void edge_decide(const RfastDev& s, int kind, int e, int r, Ed
   if (q.act_i) {
     if (q.d < 0 || q.d > s.d_max) record_error(s.err, RFAST_ERANGE, r, kind, e);  // clamped in edge_level2
     int u = q.u;
-    while (!delivered(q.bits, u, s.M)) --u;  // at most burst-1 steps; version 0 always counts as delivered
+    while (!delivered(q.bits, u, modM)) --u;  // at most burst-1 steps; version 0 always counts as delivered
     const int old = q.old;
     const int now = u > old ? u : old;
     tau[e] = now;
     q.old = now;
-    slot[e] = now % s.M;
-    if (s.blk_plan && !kind) s.blk_plan[s.n + e] = now % s.M;
+    const int now_slot = modM(now);
+    slot[e] = now_slot;
+    if (s.blk_plan && !kind) s.blk_plan[s.n + e] = now_slot;
     if (kind) {
       const bool live = now != old;
       // after this round the ring of an active sender no longer covers version lo
       const bool leaves = q.act_j && now == lo;
       const bool spill = !live && leaves;
-      const int word = (now % s.M) | ((old >= lo ? old % s.M : 0xFF) << 8) | (live ? 1 << 16 : 0) |
+      const int word = now_slot | ((old >= lo ? modM(old) : 0xFF) << 8) | (live ? 1 << 16 : 0) |
                        (live && leaves ? 1 << 17 : 0) | (spill ? 1 << 18 : 0);
       s.plan_c[e] = word;
       if (s.blk_plan) s.blk_plan[s.n + s.eR + e] = word;
@@ -96,7 +109,7 @@ __device__ inline void edge_decide(const RfastDev& s, int kind, int e, int r, Ed
     if (kind) {
       // bits 0-7 of a spill word: the slot of the version that leaves (as in the word of an active receiver)
       const bool spill = q.act_j && q.old == lo;
-      const int word = spill ? (lo % s.M) | 1 << 18 : 0;
+      const int word = spill ? modM(lo) | 1 << 18 : 0;
       s.plan_c[e] = word;
       if (s.blk_plan) s.blk_plan[s.n + s.eR + e] = word;
       if (spill) s.node_spill[q.j] = 1;
@@ -107,10 +120,10 @@ __device__ inline void edge_decide(const RfastDev& s, int kind, int e, int r, Ed
     bool ok = !q.dropped;
     if (!ok) {
       bool all_lost = true;
-      for (int k = 1; k < s.burst; ++k) all_lost = all_lost && !delivered(q.bits, vn - k, s.M);
+      for (int k = 1; k < s.burst; ++k) all_lost = all_lost && !delivered(q.bits, vn - k, modM);
       ok = all_lost;
     }
-    const unsigned long long bit = 1ull << (vn % s.M);
+    const unsigned long long bit = 1ull << modM(vn);
     q.bits = ok ? (q.bits | bit) : (q.bits & ~bit);
     deliv[e] = q.bits;
   }
@@ -160,6 +173,7 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev
   const int r0 = *s.round_no;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int E = s.eR + s.eC;
+  const FastMod modM(s.M);
   if (s.blk_head) block_head(s, 0);
   for (int rq = 0; rq < rounds; ++rq) {
     const int r = r0 + rq;
@@ -211,14 +225,14 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev
 #pragma unroll
     for (int a = 0; a < kAhead; ++a) {
       const int e = threadIdx.x + a * kResolveThreads;
-      if (e < E) edge_decide(s, e >= s.eR, e >= s.eR ? e - s.eR : e, r, ahead[a]);
+      if (e < E) edge_decide(s, modM, e >= s.eR, e >= s.eR ? e - s.eR : e, r, ahead[a]);
     }
     for (int e = threadIdx.x + kAhead * kResolveThreads; e < E; e += kResolveThreads) {  // more than 2048 edges
       const int kind = e >= s.eR, el = kind ? e - s.eR : e;
       EdgeIn q;
       edge_level1(s, kind, el, kind ? delay_C : delay_R, kind ? drop_C : drop_R, &q);
       edge_level2(s, r, active, &q);
-      edge_decide(s, kind, el, r, q);
+      edge_decide(s, modM, kind, el, r, q);
     }
     __syncthreads();  // every read of the counters is done
     for (int i = threadIdx.x; i < s.n; i += kResolveThreads)
@@ -260,6 +274,8 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_cached_kernel(R
   extern __shared__ int lds_i[];
   __shared__ int wave_cnt[kResolveThreads / 64];
   const int n = s.n, E = s.eR + s.eC, H = s.H;
+  const int T = blockDim.x;  // a multiple of 64 with n <= T and E <= kAhead T: barriers among few wavefronts are cheap
+  const FastMod modM(s.M), modH(H);
   int* t_l = lds_i;                                                      // [n]
   int* hist_l = t_l + n;                                                 // [n][H]
   unsigned short* sched_l = reinterpret_cast<unsigned short*>(hist_l + n * H);  // [rounds][E]: delay | loss << 8 | out of range << 15
@@ -267,7 +283,7 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_cached_kernel(R
   const int r0 = *s.round_no;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (s.blk_head) block_head(s, 0);
-  for (int w = threadIdx.x; w < rounds * E; w += kResolveThreads) {
+  for (int w = threadIdx.x; w < rounds * E; w += T) {
     const int q = w / E, e = w - q * E;
     const bool kind = e >= s.eR;
     const int d = kind ? delay_C[(size_t)q * s.eC + (e - s.eR)] : delay_R[(size_t)q * s.eR + e];
@@ -275,13 +291,13 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_cached_kernel(R
     const bool bad = d < 0 || d > s.d_max;
     sched_l[w] = (unsigned short)((d < 0 ? 0 : (d > s.d_max ? s.d_max : d)) | (lost ? 1 << 8 : 0) | (bad ? 1 << 15 : 0));
   }
-  for (int w = threadIdx.x; w < rounds * n; w += kResolveThreads) act_l[w] = active[w];
-  for (int i = threadIdx.x; i < n; i += kResolveThreads) t_l[i] = s.t[i];
-  for (int w = threadIdx.x; w < n * H; w += kResolveThreads) hist_l[w] = s.t_hist[w];
+  for (int w = threadIdx.x; w < rounds * n; w += T) act_l[w] = active[w];
+  for (int i = threadIdx.x; i < n; i += T) t_l[i] = s.t[i];
+  for (int w = threadIdx.x; w < n * H; w += T) hist_l[w] = s.t_hist[w];
   EdgeIn mine[kAhead];
 #pragma unroll
   for (int a = 0; a < kAhead; ++a) {
-    const int e = threadIdx.x + a * kResolveThreads;
+    const int e = threadIdx.x + a * T;
     if (e < E) {
       const bool kind = e >= s.eR;
       const int el = kind ? e - s.eR : e;
@@ -291,15 +307,24 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_cached_kernel(R
       mine[a].old = (kind ? s.tau_c : s.tau_r)[el];
     }
   }
+  // The loads above must have landed before the round loop starts: the compiler puts the wait for a loaded register at
+  // its first use, which is inside the loop, and a wait on the memory counter there also waits for every store of the
+  // round before (a microsecond per round that nothing needs).  An empty asm that takes the registers is a use.
+#pragma unroll
+  for (int a = 0; a < kAhead; ++a) {
+    unsigned lo = (unsigned)mine[a].bits, hi = (unsigned)(mine[a].bits >> 32);
+    asm volatile("" : "+v"(mine[a].i), "+v"(mine[a].j), "+v"(mine[a].old), "+v"(lo), "+v"(hi));
+    mine[a].bits = ((unsigned long long)hi << 32) | lo;
+  }
   __syncthreads();
-  const int i = threadIdx.x;  // the node this lane looks after (n <= kResolveThreads)
+  const int i = threadIdx.x;  // the node this lane looks after (n <= T)
   for (int rq = 0; rq < rounds; ++rq) {
-    const int r = r0 + rq;
+    const int r = r0 + rq, r_slot = modH(r);
     const uint8_t* act = act_l + (size_t)rq * n;
     // what the lane's edges see: schedule, activity and the sender's counters, all from LDS
 #pragma unroll
     for (int a = 0; a < kAhead; ++a) {
-      const int e = threadIdx.x + a * kResolveThreads;
+      const int e = threadIdx.x + a * T;
       if (e < E) {
         EdgeIn& q = mine[a];
         const unsigned sw = sched_l[(size_t)rq * E + e];
@@ -310,7 +335,7 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_cached_kernel(R
         q.act_j = act[q.j] != 0;
         q.tj = t_l[q.j];
         const int at = r - d;
-        q.u = at <= 0 ? 0 : (at >= r ? q.tj : hist_l[q.j * H + (at % H)]);
+        q.u = at <= 0 ? 0 : (at >= r ? q.tj : hist_l[q.j * H + modH(at)]);
       }
     }
     if (threadIdx.x == 0 && s.blk_plan) s.blk_plan[n + E] = 0;  // a record ends with a word that is always zero
@@ -321,16 +346,16 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_cached_kernel(R
       ti = t_l[i];
       s.plan_t[i] = ti;
       s.node_spill[i] = 0;
-      s.t_hist[(size_t)i * H + (r % H)] = ti;
+      s.t_hist[(size_t)i * H + r_slot] = ti;
       on = act[i] != 0;
       if (s.blk_plan) s.blk_plan[i] = (ti & 0x3FFFFFFF) | (on ? (int)0x80000000 : 0);
     }
     const unsigned long long m = __ballot(on);
     if (lane == 0) wave_cnt[wave] = __popcll(m);
     __syncthreads();  // also: every lane has read the history of this round's delays
-    if (i < n) hist_l[i * H + (r % H)] = ti;
+    if (i < n) hist_l[i * H + r_slot] = ti;
     int off = 0, total = 0;
-    for (int w = 0; w < kResolveThreads / 64; ++w) {
+    for (int w = 0; w < T / 64; ++w) {
       if (w < wave) off += wave_cnt[w];
       total += wave_cnt[w];
     }
@@ -339,11 +364,11 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_cached_kernel(R
       s.n_active[0] = total;
       s.n_active[1] = r + 1;
     }
-    for (int q = total + threadIdx.x; q < n + 8; q += kResolveThreads) s.active_plan[q] = make_int2(-1, 0);
+    for (int q = total + threadIdx.x; q < n + 8; q += T) s.active_plan[q] = make_int2(-1, 0);
 #pragma unroll
     for (int a = 0; a < kAhead; ++a) {
-      const int e = threadIdx.x + a * kResolveThreads;
-      if (e < E) edge_decide(s, e >= s.eR, e >= s.eR ? e - s.eR : e, r, mine[a]);
+      const int e = threadIdx.x + a * T;
+      if (e < E) edge_decide(s, modM, e >= s.eR, e >= s.eR ? e - s.eR : e, r, mine[a]);
     }
     __syncthreads();  // every read of the counters is done (and wave_cnt may be reused)
     if (on) {
@@ -385,7 +410,10 @@ hipError_t rfast_launch_resolve(rfast_ctx* c, const uint8_t* active, const int32
       if (e != hipSuccess) return e;
       raised = true;
     }
-    hipLaunchKernelGGL(rfast_resolve_cached_kernel, dim3(1), dim3(kResolveThreads), lds, c->stream, c->d, rounds, plan_stride,
+    // as many lanes as the graph has nodes, or half its edges; at least four wavefronts for the copy of the schedule
+    int threads = d.n > (d.eR + d.eC + kAhead - 1) / kAhead ? d.n : (d.eR + d.eC + kAhead - 1) / kAhead;
+    threads = threads < 256 ? 256 : (threads + 63) / 64 * 64;
+    hipLaunchKernelGGL(rfast_resolve_cached_kernel, dim3(1), dim3(threads), lds, c->stream, c->d, rounds, plan_stride,
                        active, delay_R, delay_C, drop_R, drop_C);
     return hipGetLastError();
   }

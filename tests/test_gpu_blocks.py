@@ -192,3 +192,48 @@ def test_odd_p_runs_one_pass_per_round_and_momentum_variant_same_bits():
         g.run(40, *[dev[k] for k in ("active", "delay_R", "delay_C", "drop_R", "drop_C")], w.gamma)
         g.check()
     _same(a, b, "weight decay")
+
+
+@pytest.mark.parametrize("case", ["least_squares_full_gradient", "logistic_minibatches", "least_squares_weight_decay",
+                                  "several_coordinates_per_lane", "rows_longer_than_a_wavefront_pass"])
+def test_whole_problem_in_one_workgroup(case):
+    """Least squares and logistic regression small enough for the LDS of one compute unit: rfast_run takes
+    stretches of rounds with one launch of a single workgroup; same bits as the chain of four kernels per round
+    (launches cut by the rebase interval and by the step-size schedule, a single round in between, generated
+    schedules; with the objective data in LDS and without)."""
+    if case == "logistic_minibatches":
+        w = configs.config1(p=32, samples=96, batch=16, rounds=0)       # data stay in global memory
+    elif case == "several_coordinates_per_lane":
+        w = configs.config0(p=192, rounds=0)     # n p = 1536 > 1024 lanes, p / 4 = 48 and p no powers of two
+    elif case == "rows_longer_than_a_wavefront_pass":
+        # p / 4 = 128: two float4 per lane of the rows kernel's wavefront; 12 rows: no multiple of 4 x 4; data in LDS
+        from rfast_workloads import graphs, problems
+        r, c = graphs.directed_ring(3)
+        w = configs._mk("ring3_least_squares_p512", 3, 512, r, c, 1, 0.01, 0, "least_squares",
+                        problems.least_squares(3, 512, 12, 5), 0.6, 0.1, 5, samples=12, burst=2)
+    else:
+        w = configs.config0(rounds=0)                                   # data in LDS too
+    a, b = _pair(w)
+    assert rfast_block_info(a.ctx) != 0 and rfast_block_info(b.ctx) == 0
+    rng = np.random.default_rng(3)
+    x0 = (0.1 * rng.standard_normal((w.n, w.p))).astype(np.float32)
+    for g in (a, b):
+        rfast_set_rebase_interval(g.ctx, 29)
+        if case == "least_squares_weight_decay":
+            g.set_optimizer(0.0, 0.01)
+        g.set_gamma_schedule(25, 0.8)
+        g.init(x0, w.sched.initial_batch())
+    st, dev = harness.upload_chunk(a, w, 0, 120)
+    names = ("active", "delay_R", "delay_C", "drop_R", "drop_C")
+    for lo, hi in ((0, 50), (50, 51), (51, 120)):
+        for g in (a, b):
+            bi = None if dev["batch_idx"] is None else dev["batch_idx"][lo:hi].contiguous()
+            g.run(hi - lo, *[dev[k][lo:hi].contiguous() for k in names], w.gamma, bi)
+            g.check()
+        _same(a, b, (case, hi))
+    p_act = torch.full((w.n,), 0.6, dtype=torch.float32)
+    for g in (a, b):
+        g.run_generated(70, 5, p_act.to(g.device), w.sched.d_max, 0.1, w.gamma)
+        g.check()
+    _same(a, b, (case, "generated"))
+    assert np.abs(a.read("X") - x0).max() > 1e-3

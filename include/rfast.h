@@ -230,8 +230,8 @@ int rfast_use_graphs(rfast_ctx* ctx, int32_t on);
 
 /* on != 0 (the default): rfast_run and rfast_run_generated advance up to 512 rounds with one
  * launch where that is possible and pays -- the separable objective (diagonal quadratic, with or
- * without the optimizer variant), p a multiple of 4, at most 64 nodes, no node with more than 4
- * in-edges of R, in-edges of C or out-edges of C, a tile of coordinates of every node's two rings
+ * without the optimizer variant), p a multiple of 4, at most 64 nodes, no node with more than 6
+ * (33 to 64 nodes: 4) in-edges of R, in-edges of C or out-edges of C, a tile of coordinates of every node's two rings
  * fitting into the 160 KB of LDS of a CU (up to 32 nodes: 64 / n lanes of one wavefront per node, 4
  * coordinates per lane, n * (D+2) * (64 / n) * 32 B; beyond: at least 16 lanes of one workgroup per
  * node, n * (D+2) * 512 B + plans), and at least 2 rounds to run before the next multiple of the
@@ -269,7 +269,7 @@ int rfast_set_tile_group(rfast_ctx* ctx, int32_t wavefronts);
  * rfast_round on the same context without an rfast_init in between.
  * d_batch_idx: device int32 [n][batch] (objectives with batch > 0), else NULL.
  * rfast_sync_run: `rounds` steps from sample rows stacked [rounds][n][batch].  Where rfast_use_blocks
- * allows it (separable objective, p a multiple of 4, at most 32 nodes with at most 4 edges of a kind)
+ * allows it (separable objective, p a multiple of 4, at most 32 nodes with at most 6 edges of a kind)
  * the steps between two decay steps of the step-size schedule are taken by one launch that keeps
  * x, z and the samples in registers and exchanges x - gamma z and z through LDS: same bits. */
 int rfast_sync_round(rfast_ctx* ctx, float gamma, const int32_t* d_batch_idx);

@@ -26,7 +26,9 @@
 
 namespace {
 
-constexpr int kWaveMaxDeg = 4;  // most in-edges of R, in-edges of C and out-edges of C a node may have on this path
+constexpr int kWaveMaxDeg = 6;  // most in-edges of R, in-edges of C and out-edges of C a node may have on this path
+                                // (kernels for 2, 4 and 6 edge slots per node: an exponential graph on 32 nodes has 5
+                                // edges per node and kind; 8 slots would not fit the registers of two wavefronts per SIMD)
 constexpr int kWaveMaxNodes = 32;  // at least 2 lanes (8 coordinates, 32 B of a row) per node
 constexpr unsigned kXcds = 8;      // accelerator dies; consecutive workgroups go round them
 constexpr unsigned kTileRun = 64;  // neighbouring tiles that one XCD takes in a row
@@ -208,7 +210,7 @@ __global__ void __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 
   }
   // rings: kBatch slots of both rings in flight at a time (rings of up to twelve slots in one round trip to
   // memory), then into LDS; a slot whose version nobody can read any more gets zeros instead
-  constexpr int kBatch = kDeg <= 2 ? 12 : 10;
+  constexpr int kBatch = kDeg <= 2 ? 12 : (kDeg <= 4 ? 10 : 8);
   if (moves) {
     const float* vg = s.v_ring + (size_t)iT * M * p + kT;
     const float* sgg = s.sigma_ring + (size_t)iT * M * p + kT;
@@ -542,8 +544,10 @@ static hipError_t prime_wave_w(rfast_ctx* c) {
 // rfast_set_optimizer).
 hipError_t rfast_wave_prime(rfast_ctx* c) {
   if (!rfast_wave_eligible(c)) return hipSuccess;
-  if (c->d.mom || c->d.wd != 0.f) return c->max_degree <= 2 ? prime_wave_w<2, true>(c) : prime_wave_w<kWaveMaxDeg, true>(c);
-  return c->max_degree <= 2 ? prime_wave_w<2, false>(c) : prime_wave_w<kWaveMaxDeg, false>(c);
+  const int deg = c->max_degree;
+  if (c->d.mom || c->d.wd != 0.f)
+    return deg <= 2 ? prime_wave_w<2, true>(c) : (deg <= 4 ? prime_wave_w<4, true>(c) : prime_wave_w<kWaveMaxDeg, true>(c));
+  return deg <= 2 ? prime_wave_w<2, false>(c) : (deg <= 4 ? prime_wave_w<4, false>(c) : prime_wave_w<kWaveMaxDeg, false>(c));
 }
 
 template <int kDeg, bool MOM>
@@ -556,8 +560,10 @@ static hipError_t launch_wave_w(rfast_ctx* c, const RfastBlock& blk) {
 }
 
 hipError_t rfast_launch_wave(rfast_ctx* c, const RfastBlock& blk) {
-  if (c->d.mom || c->d.wd != 0.f) return c->max_degree <= 2 ? launch_wave_w<2, true>(c, blk) : launch_wave_w<kWaveMaxDeg, true>(c, blk);
-  return c->max_degree <= 2 ? launch_wave_w<2, false>(c, blk) : launch_wave_w<kWaveMaxDeg, false>(c, blk);
+  const int deg = c->max_degree;
+  if (c->d.mom || c->d.wd != 0.f)
+    return deg <= 2 ? launch_wave_w<2, true>(c, blk) : (deg <= 4 ? launch_wave_w<4, true>(c, blk) : launch_wave_w<kWaveMaxDeg, true>(c, blk));
+  return deg <= 2 ? launch_wave_w<2, false>(c, blk) : (deg <= 4 ? launch_wave_w<4, false>(c, blk) : launch_wave_w<kWaveMaxDeg, false>(c, blk));
 }
 
 // The synchronous mode through the multi-step kernel: the separable objective, p a multiple of 4,
@@ -580,7 +586,10 @@ static hipError_t launch_sync_wave(rfast_ctx* c, float gamma, int rounds) {
 }
 
 hipError_t rfast_launch_sync_wave(rfast_ctx* c, float gamma, int rounds) {
+  const int deg = c->max_degree;
   if (c->d.mom)
-    return c->max_degree <= 2 ? launch_sync_wave<2, true>(c, gamma, rounds) : launch_sync_wave<kWaveMaxDeg, true>(c, gamma, rounds);
-  return c->max_degree <= 2 ? launch_sync_wave<2, false>(c, gamma, rounds) : launch_sync_wave<kWaveMaxDeg, false>(c, gamma, rounds);
+    return deg <= 2 ? launch_sync_wave<2, true>(c, gamma, rounds)
+                    : (deg <= 4 ? launch_sync_wave<4, true>(c, gamma, rounds) : launch_sync_wave<kWaveMaxDeg, true>(c, gamma, rounds));
+  return deg <= 2 ? launch_sync_wave<2, false>(c, gamma, rounds)
+                  : (deg <= 4 ? launch_sync_wave<4, false>(c, gamma, rounds) : launch_sync_wave<kWaveMaxDeg, false>(c, gamma, rounds));
 }

@@ -27,15 +27,21 @@ def _same(a, b, where):
         assert np.array_equal(a.read(f), b.read(f)), (where, f)
 
 
-@pytest.mark.parametrize("seed", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("seed", [0, 1, 2, 3, 4, 5, 6])
 def test_uploaded_schedules(seed):
-    """Seeds 1-3: random graphs with at most four edges of a kind per node; seed 4 has more, and must
-    run one pass per round."""
+    """Seeds 1-3: random graphs with at most four edges of a kind per node; seed 4 has six (the widest kernel of the
+    tile-per-wavefront path); seed 5 has eight, and must run one pass per round; seed 6: the exponential graph on
+    32 nodes (five edges of a kind per node, two lanes per node)."""
     rng = np.random.default_rng(seed)
-    n = [16, 5, 33, 9, 9][seed]
-    p = [1028, 64, 260, 4100, 512][seed]
-    d_max, burst = [4, 0, 2, 1, 1][seed], [4, 1, 2, 3, 2][seed]
-    wr, wc = graphs.random_digraph(n, rng, extra=[0, 0.4, 0.02, 0.2, 0.4][seed]) if seed else graphs.bidirectional_ring(n)
+    n = [16, 5, 33, 9, 9, 9, 32][seed]
+    p = [1028, 64, 260, 4100, 512, 512, 1036][seed]
+    d_max, burst = [4, 0, 2, 1, 1, 1, 3][seed], [4, 1, 2, 3, 2, 2, 3][seed]
+    if seed == 0:
+        wr, wc = graphs.bidirectional_ring(n)
+    elif seed == 6:
+        wr, wc = graphs.exponential(n)
+    else:
+        wr, wc = graphs.random_digraph(n, rng, extra=[0, 0.4, 0.02, 0.2, 0.4, 0.8][seed])
     R, C = graphs.from_dense(wr), graphs.from_dense(wc)
     p_act = np.where(np.arange(n) % 4 == 1, 0.1, 0.9)
     sched = ScheduleSpec(n, R.nnz_off, C.nnz_off, p_act, d_max, 0.3, seed=seed)
@@ -44,7 +50,8 @@ def test_uploaded_schedules(seed):
     a, b = _pair(w)
     off = lambda m: (m != 0) & ~np.eye(n, dtype=bool)
     degree = max(off(wr).sum(1).max(), off(wc).sum(1).max(), off(wc).sum(0).max())   # in R, in C, out C
-    assert (rfast_block_info(a.ctx) != 0) == (degree <= 4), degree
+    assert degree == [2, 3, 4, 4, 6, 8, 5][seed]
+    assert (rfast_block_info(a.ctx) != 0) == (degree <= (6 if n <= 32 else 4)), degree
     x0 = rng.standard_normal((n, p)).astype(np.float32)
     for g in (a, b):
         rfast_set_rebase_interval(g.ctx, 23)       # launches end on multiples of 23

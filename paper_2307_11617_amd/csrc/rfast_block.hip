@@ -32,10 +32,16 @@ constexpr int kPlanPerLane = 10;
 
 // kLanes: lanes per node, each owning 4 coordinates of a tile of 4 kLanes; TPB: upper bound of the
 // workgroup size (n kLanes lanes, rounded up to whole wavefronts), which sets how many registers
-// the compiler may use (at 1024 it is held to 128 and spills some to scratch); kDeg: edge slots per node and kind (2 for rings and paths, else kMaxDeg)
+// the compiler may use; kDeg: edge slots per node and kind (2 for rings and paths, else kMaxDeg).
+// More than 32 nodes at 16 lanes each are more than 512 lanes, so the kernel runs with 128 registers: with two
+// edge slots it fits them (four ring slots in flight while the tile moves instead of eight), with four it
+// spills some 55 to scratch.  The alternative without spills, 8 lanes per node in workgroups of 512 with 186
+// registers, was measured and is slower, because it halves the wavefronts per CU: 0.201 against 0.192 ms per
+// round on a 6 x 6 mesh at p = 1 M, 0.149 against 0.088 ms on a ring of 36 nodes.
 template <int kLanes, int TPB, int kDeg>
 __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock blk) {
   constexpr int VEC = 4;
+  constexpr int kRingBatch = TPB > 512 ? 4 : 8;  // ring slots (of both rings) in flight while the tile is moved
   extern __shared__ float4 lds4[];
   const int n = s.n, M = s.M;
   const int64_t p = s.p;
@@ -99,16 +105,16 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
     // rings: eight slots of both rings (sixteen loads) in flight at a time, then into LDS
     const float* vg = s.v_ring + (size_t)i * M * p + k;
     const float* sgg = s.sigma_ring + (size_t)i * M * p + k;
-    for (int m0 = 0; m0 < M; m0 += 8) {
-      float4 tv[8], ts[8];
+    for (int m0 = 0; m0 < M; m0 += kRingBatch) {
+      float4 tv[kRingBatch], ts[kRingBatch];
 #pragma unroll
-      for (int u = 0; u < 8; ++u)
+      for (int u = 0; u < kRingBatch; ++u)
         if (m0 + u < M) {
           tv[u] = V<VEC>::ld(vg + (size_t)(m0 + u) * p);
           ts[u] = V<VEC>::ld(sgg + (size_t)(m0 + u) * p);
         }
 #pragma unroll
-      for (int u = 0; u < 8; ++u)
+      for (int u = 0; u < kRingBatch; ++u)
         if (m0 + u < M) {
           v_l[own + (m0 + u) * kLanes] = tv[u];
           sg_l[own + (m0 + u) * kLanes] = ts[u];
@@ -226,16 +232,16 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
     if (momentum) V<VEC>::st(s.mom + off, m);
     float* vg = s.v_ring + (size_t)i * M * p + k;
     float* sgg = s.sigma_ring + (size_t)i * M * p + k;
-    for (int m0 = 0; m0 < M; m0 += 8) {
-      float4 tv[8], ts[8];
+    for (int m0 = 0; m0 < M; m0 += kRingBatch) {
+      float4 tv[kRingBatch], ts[kRingBatch];
 #pragma unroll
-      for (int u = 0; u < 8; ++u)
+      for (int u = 0; u < kRingBatch; ++u)
         if (m0 + u < M) {
           tv[u] = v_l[own + (m0 + u) * kLanes];
           ts[u] = sg_l[own + (m0 + u) * kLanes];
         }
 #pragma unroll
-      for (int u = 0; u < 8; ++u)
+      for (int u = 0; u < kRingBatch; ++u)
         if (m0 + u < M) {
           V<VEC>::st(vg + (size_t)(m0 + u) * p, tv[u]);
           V<VEC>::st(sgg + (size_t)(m0 + u) * p, ts[u]);

@@ -246,8 +246,11 @@ int rfast_use_graphs(rfast_ctx* ctx, int32_t on);
  * records within 150 KB (the samples themselves too if they still fit, else they are read from global
  * memory), at most 4096 sampled rows per round and n + eR + eC < 1024; same bits as the chain of
  * four kernels per round.
- * on == 0: always one kernel pass per round.  on == 2: as the default, but 2 rounds are enough at
- * any size (for measurements). */
+ * Where these objectives do not fit one workgroup (and p is a multiple of 4, no heavy-ball buffer), rfast_run and
+ * rfast_run_generated run a round as two kernels instead of four: the sampled rows' residuals, then one kernel
+ * that forms the gradient, does the tracker update and mixes the same coordinates for the next round; same bits.
+ * on == 0: always one kernel pass per round (four kernels for these objectives).  on == 2: as the default, but
+ * 2 rounds are enough at any size (for measurements). */
 int rfast_use_blocks(rfast_ctx* ctx, int32_t on);
 /* *lanes_per_node = 0 if a call of rfast_run for several rounds would now run one pass per round,
  * else the number of lanes per node of the multi-round kernel (its tile is 4 * lanes coordinates;

@@ -305,11 +305,13 @@ int fold_sync(rfast_ctx* c) {
 
 constexpr int32_t kGraphRounds = 16;
 
-// step size of the round about to run: gamma * factor^(round div step_rounds)
-float gamma_now(const rfast_ctx* c, float gamma) {
+// step size of round `round`: gamma * factor^(round div step_rounds)
+float gamma_at(const rfast_ctx* c, float gamma, int64_t round) {
   if (c->gamma_step <= 0) return gamma;
-  return gamma * powf(c->gamma_factor, (float)(c->host_round / c->gamma_step));
+  return gamma * powf(c->gamma_factor, (float)(round / c->gamma_step));
 }
+// ... of the round about to run
+float gamma_now(const rfast_ctx* c, float gamma) { return gamma_at(c, gamma, c->host_round); }
 
 void drop_graph(rfast_ctx* c) {
   if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
@@ -617,6 +619,37 @@ static int float_round(rfast_ctx* c, float gamma, const int32_t* d_batch_idx) {
   return after_round(c);
 }
 
+// `count` consecutive rounds of least squares or logistic regression whose plans the resolver has written into plan
+// sets 0 .. count-1: two kernels per round instead of four (the lane that tracks a coordinate in one round mixes it for
+// the next).  d_active, d_batch_idx: the activity flags and the rows of the first of these rounds, those of the others
+// behind them.
+static int chained_rounds(rfast_ctx* c, int32_t count, float gamma, const uint8_t* d_active, const int32_t* d_batch_idx) {
+  const RfastDev& d = c->d;
+  const size_t rows = (size_t)d.n * (size_t)d.prob.batch;
+  use_plan_set(c, 0);
+  time_begin(c, 0);
+  hipError_t e = rfast_launch_state(c, RFAST_MODE_MIX, gamma_now(c, gamma));
+  time_end(c, 0);
+  if (e != hipSuccess) return hipfail(c, e, "mix launch");
+  for (int32_t q = 0; q < count; ++q) {
+    use_plan_set(c, q);
+    const int32_t* bi = d_batch_idx ? d_batch_idx + (size_t)q * rows : nullptr;
+    const uint8_t* act = d_active + (size_t)q * d.n;
+    time_begin(c, 1);
+    e = rfast_launch_rows(c, bi, act);
+    time_end(c, 1);
+    if (e != hipSuccess) return hipfail(c, e, "rows launch");
+    time_begin(c, 0);
+    e = rfast_launch_cols_track_mix(c, bi, act, q + 1 < count ? act + d.n : nullptr, c->plan_set_bytes,
+                                    gamma_at(c, gamma, c->host_round + 1));
+    time_end(c, 0);
+    if (e != hipSuccess) return hipfail(c, e, "columns, track and mix launch");
+    const int rc = after_round(c);
+    if (rc != RFAST_OK) return rc;
+  }
+  return RFAST_OK;
+}
+
 // How many of the next `rounds` rounds one launch of the LDS-resident kernel should take (0: run
 // the next round as one pass).  A launch holds no rebase, so it must end at the latest on the next
 // multiple of the rebase interval, and it runs with one step size, so it must end with the current
@@ -746,10 +779,15 @@ int rfast_run(rfast_ctx* c, int32_t rounds, const uint8_t* d_active, const int32
                                               d_drop_C ? d_drop_C + (size_t)r * d.eC : nullptr, ahead, c->plan_set_bytes);
     time_end(c, 2);
     if (e != hipSuccess) return hipfail(c, e, "resolver launch");
-    for (int32_t q = 0; q < ahead; ++q) {
-      use_plan_set(c, q);
-      rc = float_round(c, gamma, d_batch_idx ? d_batch_idx + (size_t)(r + q) * d.n * B : nullptr);
+    if (c->use_blocks && rfast_chain_eligible(c)) {
+      rc = chained_rounds(c, ahead, gamma, d_active + (size_t)r * d.n, d_batch_idx ? d_batch_idx + (size_t)r * d.n * B : nullptr);
       if (rc != RFAST_OK) return rc;
+    } else {
+      for (int32_t q = 0; q < ahead; ++q) {
+        use_plan_set(c, q);
+        rc = float_round(c, gamma, d_batch_idx ? d_batch_idx + (size_t)(r + q) * d.n * B : nullptr);
+        if (rc != RFAST_OK) return rc;
+      }
     }
     r += ahead - 1;
   }

@@ -176,6 +176,11 @@ hipError_t rfast_wave_prime(rfast_ctx* c);      // loads the kernels this contex
 bool rfast_block_eligible(const rfast_ctx* c);  // the multi-round kernel with one tile per workgroup
 int rfast_block_lanes(const rfast_ctx* c);  // lanes per node of the multi-round kernel, 0 if no tile fits
 hipError_t rfast_launch_block(rfast_ctx* c, const RfastBlock& blk);
+// least squares / logistic regression: consecutive rounds as two kernels each (rows; columns + track + the next mixing)
+bool rfast_chain_eligible(const rfast_ctx* c);
+hipError_t rfast_launch_rows(rfast_ctx* c, const int32_t* d_batch_idx, const uint8_t* d_active);
+hipError_t rfast_launch_cols_track_mix(rfast_ctx* c, const int32_t* d_batch_idx, const uint8_t* d_active, const uint8_t* d_active_next,
+                                       size_t next_set_bytes, float gamma_next);
 bool rfast_tiny_eligible(const rfast_ctx* c);   // the multi-round kernel for least squares / logistic problems that fit one CU's LDS
 hipError_t rfast_launch_tiny(rfast_ctx* c, const RfastBlock& blk, const int32_t* d_batch_idx, int round0);
 hipError_t rfast_launch_generate(rfast_ctx* c, uint64_t seed, const float* d_p_active, int d_max, float p_drop, bool events,

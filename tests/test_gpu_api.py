@@ -215,7 +215,7 @@ def test_automatic_rebase_interval_equals_manual_calls():
 
 
 def test_profiling_hooks_count_launches():
-    w = configs.config1(p=256, samples=64, batch=16, rounds=10)
+    w = configs.config1(p=256, samples=64, batch=16, rounds=20)
     gpu = harness.make_gpu(w)
     gpu.init(None, w.sched.initial_batch())
     rf.rfast_profile_enable(gpu.ctx, True)
@@ -224,6 +224,13 @@ def test_profiling_hooks_count_launches():
     ms_s, n_s = rf.rfast_kernel_time(gpu.ctx, 0)
     ms_g, n_g = rf.rfast_kernel_time(gpu.ctx, 1)
     ms_r, n_r = rf.rfast_kernel_time(gpu.ctx, 2)
-    # two state passes and one gradient per round; the resolver takes the ten rounds in one launch
-    assert (n_s, n_g, n_r) == (20, 10, 1) and ms_s > 0 and ms_g > 0 and ms_r > 0
+    # consecutive rounds of this objective are two kernels each (rows; columns + track + the next round's mixing) after
+    # one mixing pass for the first; the resolver takes the ten rounds in one launch
+    assert (n_s, n_g, n_r) == (11, 10, 1) and ms_s > 0 and ms_g > 0 and ms_r > 0
+    # with rfast_use_blocks off: two state passes and one gradient (two kernels) per round
+    rf.rfast_use_blocks(gpu.ctx, False)
+    rf.rfast_profile_enable(gpu.ctx, True)
+    st, dev = harness.upload_chunk(gpu, w, 10, 20)
+    gpu.run(10, dev["active"], dev["delay_R"], dev["delay_C"], dev["drop_R"], dev["drop_C"], w.gamma, dev["batch_idx"])
+    assert [rf.rfast_kernel_time(gpu.ctx, q)[1] for q in (0, 1, 2)] == [20, 10, 1]
     rf.rfast_profile_enable(gpu.ctx, False)

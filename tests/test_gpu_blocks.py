@@ -244,3 +244,55 @@ def test_whole_problem_in_one_workgroup(case):
         g.check()
     _same(a, b, (case, "generated"))
     assert np.abs(a.read("X") - x0).max() > 1e-3
+@pytest.mark.parametrize("case", ["logistic_minibatches", "least_squares_full_gradient", "rows_longer_than_one_pass",
+                                  "weight_decay_many_in_edges"])
+def test_round_as_two_kernels(case):
+    """Least squares and logistic regression too large for one workgroup: consecutive rounds are two kernels each
+    (rows; columns + track + the mixing of the next round) instead of four; same bits.  Uploaded schedules in
+    calls of several lengths (a single round runs the four kernels), then a generated one; a batch that is no
+    multiple of the four wavefronts, rows of more than 4096 coordinates, more in-edges than one batch of loads,
+    buffers that leave their sender's ring (losses in bursts), a step-size schedule (the mixing of the next round
+    runs with the next round's step size)."""
+    if case == "logistic_minibatches":
+        w = configs.config1(p=512, samples=128, batch=22, rounds=0)
+    elif case == "least_squares_full_gradient":
+        w = configs.config0(p=2048, m=19, rounds=0)
+    elif case == "rows_longer_than_one_pass":
+        w = configs.config1(p=4616, samples=64, batch=9, rounds=0)       # 4096 + 520: a second, ragged pass over a row
+    else:
+        # a star: the root pulls from and pushes to 11 leaves (more in-edges than the eight loaded at a time)
+        n = 12
+        adj = np.eye(n)
+        adj[0, :] = 1
+        adj[:, 0] = 1
+        wr = adj / adj.sum(1, keepdims=True)
+        wc = adj / adj.sum(0, keepdims=True)
+        w = configs._mk("star12_logistic", n, 260, wr, wc, 2, 0.05, 0, "logistic", problems.logistic(n, 260, 40, 3), 0.6,
+                        0.3, 3, batch=8, samples=40, burst=3)
+    if case == "least_squares_full_gradient":
+        w.gamma = 0.002                      # 19 rows in 2048 dimensions: the largest curvature is about a hundred
+    a, b = _pair(w)
+    assert rfast_block_info(a.ctx) == 0     # no launch over several rounds here: it is the round itself that differs
+    rng = np.random.default_rng(11)
+    x0 = (0.1 * rng.standard_normal((w.n, w.p))).astype(np.float32)
+    for g in (a, b):
+        rfast_set_rebase_interval(g.ctx, 31)
+        if case == "weight_decay_many_in_edges":
+            g.set_optimizer(0.0, 0.01)
+        g.set_gamma_schedule(20, 0.8)
+        g.init(x0, w.sched.initial_batch())
+    st, dev = harness.upload_chunk(a, w, 0, 80)
+    names = ("active", "delay_R", "delay_C", "drop_R", "drop_C")
+    for lo, hi in ((0, 45), (45, 46), (46, 80)):
+        for g in (a, b):
+            bi = None if dev["batch_idx"] is None else dev["batch_idx"][lo:hi].contiguous()
+            g.run(hi - lo, *[dev[k][lo:hi].contiguous() for k in names], w.gamma, bi)
+            g.check()
+        _same(a, b, (case, hi))
+    p_act = torch.full((w.n,), 0.6, dtype=torch.float32)
+    for g in (a, b):
+        g.run_generated(40, 5, p_act.to(g.device), w.sched.d_max, 0.1, w.gamma)
+        g.check()
+    _same(a, b, (case, "generated"))
+    assert np.abs(a.read("X") - x0).max() > 1e-3
+    assert np.isfinite(a.read("X")).all() and np.isfinite(a.read("Z")).all()

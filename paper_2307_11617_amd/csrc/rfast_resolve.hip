@@ -31,9 +31,13 @@ struct FastMod {
   }
 };
 
-__device__ inline bool delivered(unsigned long long bits, int v, const FastMod& modM) {
-  return v <= 0 || ((bits >> modM(v)) & 1ull);
+// bit b (< 64) of a 64-bit word through one of its halves: 32-bit shifts run at full rate, 64-bit ones at a quarter
+__device__ inline bool bit_of(unsigned long long bits, int b) {
+  const unsigned half = b < 32 ? (unsigned)bits : (unsigned)(bits >> 32);
+  return (half >> (b & 31)) & 1u;
 }
+
+__device__ inline bool delivered(unsigned long long bits, int v, const FastMod& modM) { return v <= 0 || bit_of(bits, modM(v)); }
 
 __device__ inline void record_error(int32_t* err, int code, int round, int kind, int e) {
   if (atomicCAS(&err[0], 0, code) == 0) {
@@ -75,58 +79,63 @@ __device__ inline void edge_level2(const RfastDev& s, int r, const uint8_t* acti
 }
 
 // Decides edge e for round r and leaves the new stamp and delivery bits in q as well (a lane that
-// keeps its edges over several rounds goes on from them).
-__device__ inline void edge_decide(const RfastDev& s, const FastMod& modM, int kind, int e, int r, EdgeIn& q) {
-  int32_t* tau = kind ? s.tau_c : s.tau_r;
-  int32_t* slot = kind ? s.slot_c : s.slot_r;
-  unsigned long long* deliv = kind ? s.deliv_c : s.deliv_r;
+// keeps its edges over several rounds goes on from them).  KIND 0: graph R, 1: graph C.
+// Written without branches on what differs from lane to lane (an active or idle receiver, a lost packet):
+// one wavefront runs this for every round of a launch, and every divergent branch costs it both sides and
+// the bookkeeping of the execution mask.  What an idle receiver does not change is stored again unchanged.
+template <int KIND>
+__device__ inline void edge_decide_t(const RfastDev& s, const FastMod& modM, int e, int r, EdgeIn& q) {
+  int32_t* tau = KIND ? s.tau_c : s.tau_r;
+  int32_t* slot = KIND ? s.slot_c : s.slot_r;
+  unsigned long long* deliv = KIND ? s.deliv_c : s.deliv_r;
   const int lo = q.tj - (s.M - 2);  // oldest version that stays readable in j's ring during this round
-  if (q.act_i) {
-    if (q.d < 0 || q.d > s.d_max) record_error(s.err, RFAST_ERANGE, r, kind, e);  // clamped in edge_level2
-    int u = q.u;
-    while (!delivered(q.bits, u, modM)) --u;  // at most burst-1 steps; version 0 always counts as delivered
-    const int old = q.old;
-    const int now = u > old ? u : old;
-    tau[e] = now;
-    q.old = now;
-    const int now_slot = modM(now);
-    slot[e] = now_slot;
-    if (s.blk_plan && !kind) s.blk_plan[s.n + e] = now_slot;
-    if (kind) {
-      const bool live = now != old;
-      // after this round the ring of an active sender no longer covers version lo
-      const bool leaves = q.act_j && now == lo;
-      const bool spill = !live && leaves;
-      const int word = now_slot | ((old >= lo ? modM(old) : 0xFF) << 8) | (live ? 1 << 16 : 0) |
-                       (live && leaves ? 1 << 17 : 0) | (spill ? 1 << 18 : 0);
-      s.plan_c[e] = word;
-      if (s.blk_plan) s.blk_plan[s.n + s.eR + e] = word;
-      if (spill) s.node_spill[q.j] = 1;
-    }
+  if (q.act_i && (q.d < 0 || q.d > s.d_max)) record_error(s.err, RFAST_ERANGE, r, KIND, e);  // clamped in edge_level2
+  // S2a / S2b: the newest delivered version that is not newer than u: at most burst-1 steps back (a version is
+  // delivered by force once the burst-1 before it were all lost; version 0 always counts as delivered)
+  int u = q.u;
+  for (int k = 1; k < s.burst; ++k) u -= delivered(q.bits, u, modM) ? 0 : 1;
+  const int old = q.old;
+  const int now = q.act_i && u > old ? u : old;
+  const int now_slot = modM(now);
+  tau[e] = now;
+  q.old = now;
+  slot[e] = q.act_i ? now_slot : -1;
+  if (KIND == 0) {
+    if (s.blk_plan) s.blk_plan[s.n + e] = q.act_i ? now_slot : 0;
   } else {
-    slot[e] = -1;
-    if (s.blk_plan && !kind) s.blk_plan[s.n + e] = 0;
-    if (kind) {
-      // bits 0-7 of a spill word: the slot of the version that leaves (as in the word of an active receiver)
-      const bool spill = q.act_j && q.old == lo;
-      const int word = spill ? modM(lo) | 1 << 18 : 0;
-      s.plan_c[e] = word;
-      if (s.blk_plan) s.blk_plan[s.n + s.eR + e] = word;
-      if (spill) s.node_spill[q.j] = 1;
-    }
+    const bool live = now != old;  // never with an idle receiver
+    // after this round the ring of an active sender no longer covers version lo
+    const bool leaves = q.act_j && now == lo;
+    const bool spill = !live && leaves;  // the receiver does not consume, and the version its buffer holds leaves
+    // bits 0-7 of a spill word: the slot of the version that leaves (now == lo then)
+    const int word = q.act_i ? now_slot | ((old >= lo ? modM(old) : 0xFF) << 8) | (live ? 1 << 16 : 0) | (live && leaves ? 1 << 17 : 0) |
+                                   (spill ? 1 << 18 : 0)
+                             : (spill ? now_slot | 1 << 18 : 0);
+    s.plan_c[e] = word;
+    if (s.blk_plan) s.blk_plan[s.n + s.eR + e] = word;
+    if (spill) s.node_spill[q.j] = 1;
   }
-  if (q.act_j) {  // the sender publishes version t_j + 1 this round
-    const int vn = q.tj + 1;
-    bool ok = !q.dropped;
-    if (!ok) {
-      bool all_lost = true;
-      for (int k = 1; k < s.burst; ++k) all_lost = all_lost && !delivered(q.bits, vn - k, modM);
-      ok = all_lost;
-    }
-    const unsigned long long bit = 1ull << modM(vn);
-    q.bits = ok ? (q.bits | bit) : (q.bits & ~bit);
-    deliv[e] = q.bits;
-  }
+  // the sender publishes version t_j + 1 this round (if it is active): lost only if the schedule says so and not all
+  // of the burst-1 versions before it were lost too
+  const int vn = q.tj + 1;
+  bool all_lost = true;
+  for (int k = 1; k < s.burst; ++k) all_lost = all_lost && !delivered(q.bits, vn - k, modM);
+  const bool ok = !q.dropped || all_lost;
+  const int b = modM(vn);
+  const unsigned mask = 1u << (b & 31);
+  unsigned w_lo = (unsigned)q.bits, w_hi = (unsigned)(q.bits >> 32);
+  const bool in_lo = b < 32;
+  const unsigned half = in_lo ? w_lo : w_hi;
+  const unsigned changed = q.act_j ? (ok ? half | mask : half & ~mask) : half;
+  w_lo = in_lo ? changed : w_lo;
+  w_hi = in_lo ? w_hi : changed;
+  q.bits = ((unsigned long long)w_hi << 32) | w_lo;
+  deliv[e] = q.bits;
+}
+
+__device__ inline void edge_decide(const RfastDev& s, const FastMod& modM, int kind, int e, int r, EdgeIn& q) {
+  if (kind) edge_decide_t<1>(s, modM, e, r, q);
+  else edge_decide_t<0>(s, modM, e, r, q);
 }
 
 // What the kernel that moves the rings of a multi-round launch needs to know about the state before
@@ -264,17 +273,23 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_kernel(RfastDev
 // the counters t and their history live in LDS, and every lane keeps the stamp and the delivery bits
 // of its (at most two) edges in registers.  A round then costs LDS gathers and barriers; what it
 // writes to global memory (plans, stamps, bits, counters, history) nobody waits for.  For graphs of
-// up to 1024 nodes and 2048 edges whose schedule fits into LDS; bit for bit the plans of the kernel
-// above.
+// up to 1024 nodes and about 2048 edges whose schedule fits into LDS; bit for bit the plans of the
+// kernel above.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_cached_kernel(RfastDev s, int rounds, size_t plan_stride,
                                                                                 const uint8_t* active, const int32_t* delay_R,
                                                                                 const int32_t* delay_C, const uint8_t* drop_R,
-                                                                                const uint8_t* drop_C) {
+                                                                                const uint8_t* drop_C, int lanes_R, int lanes_C) {
   extern __shared__ int lds_i[];
   __shared__ int wave_cnt[kResolveThreads / 64];
   const int n = s.n, E = s.eR + s.eC, H = s.H;
-  const int T = blockDim.x;  // a multiple of 64 with n <= T and E <= kAhead T: barriers among few wavefronts are cheap
+  const int T = blockDim.x;  // a multiple of 64, n <= T: barriers among few wavefronts are cheap
+  // The first lanes_R lanes (whole wavefronts) look after the edges of R, the next lanes_C after those of C, up to
+  // kAhead edges each: the kind of an edge is the same for all lanes of a wavefront, and small graphs have their
+  // edges decided side by side in different wavefronts rather than one after the other in one.
+  const bool kind = (int)threadIdx.x >= lanes_R;
+  const int lane_k = kind ? (int)threadIdx.x - lanes_R : (int)threadIdx.x, lanes_k = kind ? lanes_C : lanes_R;
+  const int edges_k = (int)threadIdx.x < lanes_R + lanes_C ? (kind ? s.eC : s.eR) : 0;
   const FastMod modM(s.M), modH(H);
   int* t_l = lds_i;                                                      // [n]
   int* hist_l = t_l + n;                                                 // [n][H]
@@ -297,10 +312,8 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_cached_kernel(R
   EdgeIn mine[kAhead];
 #pragma unroll
   for (int a = 0; a < kAhead; ++a) {
-    const int e = threadIdx.x + a * T;
-    if (e < E) {
-      const bool kind = e >= s.eR;
-      const int el = kind ? e - s.eR : e;
+    const int el = lane_k + a * lanes_k;
+    if (el < edges_k) {
       mine[a].i = (kind ? s.c_dst : s.r_dst)[el];
       mine[a].j = (kind ? s.c_src : s.r_src)[el];
       mine[a].bits = (kind ? s.deliv_c : s.deliv_r)[el];
@@ -324,8 +337,9 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_cached_kernel(R
     // what the lane's edges see: schedule, activity and the sender's counters, all from LDS
 #pragma unroll
     for (int a = 0; a < kAhead; ++a) {
-      const int e = threadIdx.x + a * T;
-      if (e < E) {
+      const int el = lane_k + a * lanes_k;
+      const int e = kind ? s.eR + el : el;  // position in a round's schedule words: R's edges, then C's
+      if (el < edges_k) {
         EdgeIn& q = mine[a];
         const unsigned sw = sched_l[(size_t)rq * E + e];
         const int d = sw & 0xFF;
@@ -367,8 +381,8 @@ __global__ void __launch_bounds__(kResolveThreads) rfast_resolve_cached_kernel(R
     for (int q = total + threadIdx.x; q < n + 8; q += T) s.active_plan[q] = make_int2(-1, 0);
 #pragma unroll
     for (int a = 0; a < kAhead; ++a) {
-      const int e = threadIdx.x + a * T;
-      if (e < E) edge_decide(s, modM, e >= s.eR, e >= s.eR ? e - s.eR : e, r, mine[a]);
+      const int el = lane_k + a * lanes_k;
+      if (el < edges_k) edge_decide(s, modM, kind, el, r, mine[a]);
     }
     __syncthreads();  // every read of the counters is done (and wave_cnt may be reused)
     if (on) {
@@ -402,7 +416,7 @@ hipError_t rfast_launch_resolve(rfast_ctx* c, const uint8_t* active, const int32
                                 size_t plan_stride) {
   const RfastDev& d = c->d;
   const size_t lds = cached_lds_bytes(d, rounds);
-  if (rounds > 1 && d.n <= kResolveThreads && d.eR + d.eC <= kAhead * kResolveThreads && lds <= 150 * 1024) {
+  if (rounds > 1 && d.n <= kResolveThreads && (d.eR + 127) / 128 + (d.eC + 127) / 128 <= kResolveThreads / 64 && lds <= 150 * 1024) {
     static bool raised = false;
     if (!raised) {  // more than 64 KB of dynamic LDS has to be asked for once (the kernel has 64 B of static LDS too)
       const hipError_t e = hipFuncSetAttribute((const void*)rfast_resolve_cached_kernel,
@@ -410,11 +424,18 @@ hipError_t rfast_launch_resolve(rfast_ctx* c, const uint8_t* active, const int32
       if (e != hipSuccess) return e;
       raised = true;
     }
-    // as many lanes as the graph has nodes, or half its edges; at least four wavefronts for the copy of the schedule
-    int threads = d.n > (d.eR + d.eC + kAhead - 1) / kAhead ? d.n : (d.eR + d.eC + kAhead - 1) / kAhead;
-    threads = threads < 256 ? 256 : (threads + 63) / 64 * 64;
+    // whole wavefronts for the edges of R, then for those of C: one edge per lane if that fits 1024 lanes, else two;
+    // as many lanes as the graph has nodes, at least four wavefronts for the copy of the schedule
+    auto whole = [](int v) { return (v + 63) / 64 * 64; };
+    int lanes_R = whole(d.eR), lanes_C = whole(d.eC);
+    if (lanes_R + lanes_C > kResolveThreads) {
+      lanes_R = whole((d.eR + 1) / 2);
+      lanes_C = whole((d.eC + 1) / 2);
+    }
+    int threads = lanes_R + lanes_C > whole(d.n) ? lanes_R + lanes_C : whole(d.n);
+    threads = threads < 256 ? 256 : threads;
     hipLaunchKernelGGL(rfast_resolve_cached_kernel, dim3(1), dim3(threads), lds, c->stream, c->d, rounds, plan_stride,
-                       active, delay_R, delay_C, drop_R, drop_C);
+                       active, delay_R, delay_C, drop_R, drop_C, lanes_R, lanes_C);
     return hipGetLastError();
   }
   hipLaunchKernelGGL(rfast_resolve_kernel, dim3(1), dim3(kResolveThreads), 0, c->stream, c->d, rounds, plan_stride, active,

@@ -26,7 +26,7 @@ __device__ inline float wave_sum(float v) {
 __device__ inline int checked_row(const RfastDev& s, int i, int row) {
   if (row < 0 || row >= s.prob.samples) {
     if (atomicCAS(&s.err[0], 0, RFAST_ERANGE) == 0) {
-      s.err[1] = s.n_active[1];  // the round counter as this round's plan recorded it
+      s.err[1] = s.n_active[1] - 1;  // the number of this round (its plan recorded the count of rounds including it)
       s.err[2] = 2;
       s.err[3] = i;
     }
@@ -40,7 +40,7 @@ __device__ inline int sample_row(const RfastDev& s, const int32_t* batch_idx, in
   int row = batch_idx[(size_t)i * B + b];
   if (row < 0 || row >= s.prob.samples) {
     if (atomicCAS(&s.err[0], 0, RFAST_ERANGE) == 0) {
-      s.err[1] = s.n_active[1];  // the round counter as this round's plan recorded it
+      s.err[1] = s.n_active[1] - 1;  // the number of this round (its plan recorded the count of rounds including it)
       s.err[2] = 2;
       s.err[3] = i;
     }

@@ -61,7 +61,7 @@ __device__ inline int sample_row(const RfastDev& s, const int32_t* batch_idx, in
   int row = batch_idx[(size_t)i * B + b];
   if (row < 0 || row >= s.prob.samples) {
     if (atomicCAS(&s.err[0], 0, RFAST_ERANGE) == 0) {
-      s.err[1] = s.n_active[1];  // the round counter as this round's plan recorded it
+      s.err[1] = s.n_active[1] - 1;  // the number of this round (its plan recorded the count of rounds including it)
       s.err[2] = 2;
       s.err[3] = i;
     }
@@ -220,7 +220,7 @@ __global__ void __launch_bounds__(64 * NW) rfast_softmax_forward(RfastDev s, con
     // a label outside [0, K) would index the logits in LDS out of bounds: clamped and reported, like a sample row
     if (my_label < 0 || my_label >= K) {
       if (atomicCAS(&s.err[0], 0, RFAST_ERANGE) == 0) {
-        s.err[1] = s.n_active[1];
+        s.err[1] = s.n_active[1] - 1;
         s.err[2] = 3;
         s.err[3] = i;
       }

@@ -97,8 +97,28 @@ def test_out_of_range_sample_row_is_clamped_and_reported():
     gpu.round(act, dR, dC, xR, xC, w.gamma, bi)
     with pytest.raises(rf.RFastError) as ei:
         gpu.check()
-    assert ei.value.code == -4 and "node 5" in str(ei.value)
+    assert ei.value.code == -4 and "node 5" in str(ei.value) and "round 0" in str(ei.value)
     assert np.isfinite(gpu.read("X")).all()
+
+
+@pytest.mark.parametrize("path", ["two kernels per round", "one workgroup"])
+def test_out_of_range_sample_row_in_a_later_round_of_a_run(path):
+    """The same report from the kernels that rfast_run uses for stretches of rounds: the round is named by its number
+    (counted from rfast_init, from zero), the row is clamped."""
+    w = configs.config1(p=256, samples=64, batch=16, rounds=6) if path == "two kernels per round" else \
+        configs.config1(p=32, samples=96, batch=16, rounds=6)
+    gpu = harness.make_gpu(w)
+    assert (rf.rfast_block_info(gpu.ctx) != 0) == (path == "one workgroup")
+    gpu.init(None, w.sched.initial_batch())
+    st, dev = harness.upload_chunk(gpu, w, 0, 6)
+    assert st["active"][4, 5]           # node 5 is active in round 4 of this seed
+    bi = dev["batch_idx"].clone()
+    bi[4, 5, 2] = w.sched.samples + 3
+    gpu.run(6, dev["active"], dev["delay_R"], dev["delay_C"], dev["drop_R"], dev["drop_C"], w.gamma, bi)
+    with pytest.raises(rf.RFastError) as ei:
+        gpu.check()
+    assert ei.value.code == -4 and "node 5" in str(ei.value) and "round 4" in str(ei.value), str(ei.value)
+    assert np.isfinite(gpu.read("X")).all() and np.isfinite(gpu.read("Z")).all()
 
 
 def test_out_of_range_class_label_is_clamped_and_reported():

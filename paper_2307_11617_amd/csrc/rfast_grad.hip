@@ -8,6 +8,9 @@
 // kernel gives one wavefront per sampled row (float4 loads, 64-lane reduction);
 // the columns kernel gives one float4 of g per lane of a wavefront and streams the
 // same rows again, coalesced along k, its four wavefronts sharing the rows.
+// In a run of consecutive rounds the column sums share a kernel with the tracker
+// update of their round and the mixing of the next (rfast_cols_track_mix_kernel,
+// further down): two kernels per round instead of four.
 #include "rfast_internal.h"
 #include "rfast_vec.h"
 

@@ -245,7 +245,8 @@ int rfast_use_graphs(rfast_ctx* ctx, int32_t on);
  * eC p floats of state plus the graph, n (batch, or samples) residuals and row numbers and two plan
  * records within 150 KB (the samples themselves too if they still fit, else they are read from global
  * memory), at most 4096 sampled rows per round and n + eR + eC < 1024; same bits as the chain of
- * four kernels per round.
+ * four kernels per round.  With at most 64 nodes and 64 edges of a kind that workgroup also resolves
+ * the stamps of its rounds itself (no resolver kernel runs ahead of it).
  * Where these objectives do not fit one workgroup (and p is a multiple of 4, no heavy-ball buffer), rfast_run and
  * rfast_run_generated run a round as two kernels instead of four: the sampled rows' residuals, then one kernel
  * that forms the gradient, does the tracker update and mixes the same coordinates for the next round; same bits.

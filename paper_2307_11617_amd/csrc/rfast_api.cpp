@@ -685,15 +685,20 @@ static int run_block(rfast_ctx* c, int32_t len, const uint8_t* d_active, const i
   const bool rebase_due = c->rebase_interval > 0 && (c->host_round + len) % c->rebase_interval == 0;
   blk.rebase = rebase_due && rfast_wave_eligible(c) ? 1 : 0;
   blk.gamma = gamma_now(c, gamma);  // of the first round: a launch does not straddle a decay step
-  time_begin(c, 2);
+  const bool own_resolver = rfast_tiny_resolves(c);  // the one-workgroup kernel resolves its rounds itself
+  hipError_t e = hipSuccess;
   d.blk_plan = c->blk_plan_base;
   d.blk_head = c->blk_head_base;
-  hipError_t e = rfast_launch_resolve(c, d_active, d_delay_R, d_delay_C, d_drop_R, d_drop_C, len);
+  if (!own_resolver) {
+    time_begin(c, 2);
+    e = rfast_launch_resolve(c, d_active, d_delay_R, d_delay_C, d_drop_R, d_drop_C, len);
+    time_end(c, 2);
+  }
   c->host_round += len;
-  time_end(c, 2);
   if (e == hipSuccess) {
     time_begin(c, 0);
-    if (rfast_tiny_eligible(c)) e = rfast_launch_tiny(c, blk, d_batch_idx, (int)(c->host_round - len));
+    if (rfast_tiny_eligible(c))
+      e = rfast_launch_tiny(c, blk, d_batch_idx, (int)(c->host_round - len), d_active, d_delay_R, d_delay_C, d_drop_R, d_drop_C);
     else e = rfast_wave_eligible(c) ? rfast_launch_wave(c, blk) : rfast_launch_block(c, blk);
     time_end(c, 0);
   }

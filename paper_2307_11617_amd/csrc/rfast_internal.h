@@ -182,7 +182,9 @@ hipError_t rfast_launch_rows(rfast_ctx* c, const int32_t* d_batch_idx, const uin
 hipError_t rfast_launch_cols_track_mix(rfast_ctx* c, const int32_t* d_batch_idx, const uint8_t* d_active, const uint8_t* d_active_next,
                                        size_t next_set_bytes, float gamma_next);
 bool rfast_tiny_eligible(const rfast_ctx* c);   // the multi-round kernel for least squares / logistic problems that fit one CU's LDS
-hipError_t rfast_launch_tiny(rfast_ctx* c, const RfastBlock& blk, const int32_t* d_batch_idx, int round0);
+bool rfast_tiny_resolves(const rfast_ctx* c);   // ... and it resolves its rounds itself (no resolver launch ahead of it)
+hipError_t rfast_launch_tiny(rfast_ctx* c, const RfastBlock& blk, const int32_t* d_batch_idx, int round0, const uint8_t* d_active,
+                             const int32_t* d_delay_R, const int32_t* d_delay_C, const uint8_t* d_drop_R, const uint8_t* d_drop_C);
 hipError_t rfast_launch_generate(rfast_ctx* c, uint64_t seed, const float* d_p_active, int d_max, float p_drop, bool events,
                                  int rounds = 1);
 hipError_t rfast_launch_sync(rfast_ctx* c, int phase, float gamma, int parity);

@@ -15,47 +15,10 @@
 // (by the receiver if it consumes exactly that version in this round, else by the sender).
 //
 // One workgroup, one lane per edge; every step is integer and deterministic.
+#include "rfast_edge.h"
 #include "rfast_internal.h"
 
 namespace {
-
-// v mod d for 0 <= v < 2^31 and a divisor fixed for the launch, without the integer division (some thirty
-// instructions per remainder, and a round takes about ten per edge): the quotient by the rounded-down reciprocal is at
-// most one short, so one conditional subtraction finishes it.
-struct FastMod {
-  unsigned d, magic;
-  __device__ explicit FastMod(int d_) : d((unsigned)d_), magic(0xFFFFFFFFu / (unsigned)d_) {}
-  __device__ int operator()(int v) const {
-    const unsigned r = (unsigned)v - __umulhi((unsigned)v, magic) * d;
-    return (int)(r >= d ? r - d : r);
-  }
-};
-
-// bit b (< 64) of a 64-bit word through one of its halves: 32-bit shifts run at full rate, 64-bit ones at a quarter
-__device__ inline bool bit_of(unsigned long long bits, int b) {
-  const unsigned half = b < 32 ? (unsigned)bits : (unsigned)(bits >> 32);
-  return (half >> (b & 31)) & 1u;
-}
-
-__device__ inline bool delivered(unsigned long long bits, int v, const FastMod& modM) { return v <= 0 || bit_of(bits, modM(v)); }
-
-__device__ inline void record_error(int32_t* err, int code, int round, int kind, int e) {
-  if (atomicCAS(&err[0], 0, code) == 0) {
-    err[1] = round;
-    err[2] = kind;
-    err[3] = e;
-  }
-}
-
-// What one lane knows about its edge before it decides anything.  The loads come in two levels of
-// dependency (by edge number; by the node numbers and the delay found there), and both are issued
-// ahead of the node pass of the kernel, so that the whole resolver costs about two memory round
-// trips instead of four or five.
-struct EdgeIn {
-  int i, j, d, old, tj, u;
-  unsigned long long bits;
-  bool act_i, act_j, dropped;
-};
 
 // kind 0: graph R (v packets), kind 1: graph C (rho packets); e counts within its graph
 __device__ inline void edge_level1(const RfastDev& s, int kind, int e, const int32_t* delay, const uint8_t* drop, EdgeIn* q) {
@@ -78,59 +41,22 @@ __device__ inline void edge_level2(const RfastDev& s, int r, const uint8_t* acti
   q->u = at <= 0 ? 0 : (at >= r ? q->tj : s.t_hist[(size_t)q->j * s.H + (at % s.H)]);
 }
 
-// Decides edge e for round r and leaves the new stamp and delivery bits in q as well (a lane that
-// keeps its edges over several rounds goes on from them).  KIND 0: graph R, 1: graph C.
-// Written without branches on what differs from lane to lane (an active or idle receiver, a lost packet):
-// one wavefront runs this for every round of a launch, and every divergent branch costs it both sides and
-// the bookkeeping of the execution mask.  What an idle receiver does not change is stored again unchanged.
+// Decides edge e for round r, leaves the new stamp and delivery bits in q as well (a lane that keeps its edges
+// over several rounds goes on from them) and writes the round's plan; what an idle receiver does not change is
+// stored again unchanged.  KIND 0: graph R, 1: graph C.
 template <int KIND>
 __device__ inline void edge_decide_t(const RfastDev& s, const FastMod& modM, int e, int r, EdgeIn& q) {
-  int32_t* tau = KIND ? s.tau_c : s.tau_r;
-  int32_t* slot = KIND ? s.slot_c : s.slot_r;
-  unsigned long long* deliv = KIND ? s.deliv_c : s.deliv_r;
-  const int lo = q.tj - (s.M - 2);  // oldest version that stays readable in j's ring during this round
-  if (q.act_i && (q.d < 0 || q.d > s.d_max)) record_error(s.err, RFAST_ERANGE, r, KIND, e);  // clamped in edge_level2
-  // S2a / S2b: the newest delivered version that is not newer than u: at most burst-1 steps back (a version is
-  // delivered by force once the burst-1 before it were all lost; version 0 always counts as delivered)
-  int u = q.u;
-  for (int k = 1; k < s.burst; ++k) u -= delivered(q.bits, u, modM) ? 0 : 1;
-  const int old = q.old;
-  const int now = q.act_i && u > old ? u : old;
-  const int now_slot = modM(now);
-  tau[e] = now;
-  q.old = now;
-  slot[e] = q.act_i ? now_slot : -1;
+  const EdgeOut o = edge_compute<KIND>(s, modM, e, r, q);
+  (KIND ? s.tau_c : s.tau_r)[e] = q.old;
+  (KIND ? s.slot_c : s.slot_r)[e] = o.slot;
   if (KIND == 0) {
-    if (s.blk_plan) s.blk_plan[s.n + e] = q.act_i ? now_slot : 0;
+    if (s.blk_plan) s.blk_plan[s.n + e] = o.word;
   } else {
-    const bool live = now != old;  // never with an idle receiver
-    // after this round the ring of an active sender no longer covers version lo
-    const bool leaves = q.act_j && now == lo;
-    const bool spill = !live && leaves;  // the receiver does not consume, and the version its buffer holds leaves
-    // bits 0-7 of a spill word: the slot of the version that leaves (now == lo then)
-    const int word = q.act_i ? now_slot | ((old >= lo ? modM(old) : 0xFF) << 8) | (live ? 1 << 16 : 0) | (live && leaves ? 1 << 17 : 0) |
-                                   (spill ? 1 << 18 : 0)
-                             : (spill ? now_slot | 1 << 18 : 0);
-    s.plan_c[e] = word;
-    if (s.blk_plan) s.blk_plan[s.n + s.eR + e] = word;
-    if (spill) s.node_spill[q.j] = 1;
+    s.plan_c[e] = o.word;
+    if (s.blk_plan) s.blk_plan[s.n + s.eR + e] = o.word;
+    if (o.spill) s.node_spill[q.j] = 1;
   }
-  // the sender publishes version t_j + 1 this round (if it is active): lost only if the schedule says so and not all
-  // of the burst-1 versions before it were lost too
-  const int vn = q.tj + 1;
-  bool all_lost = true;
-  for (int k = 1; k < s.burst; ++k) all_lost = all_lost && !delivered(q.bits, vn - k, modM);
-  const bool ok = !q.dropped || all_lost;
-  const int b = modM(vn);
-  const unsigned mask = 1u << (b & 31);
-  unsigned w_lo = (unsigned)q.bits, w_hi = (unsigned)(q.bits >> 32);
-  const bool in_lo = b < 32;
-  const unsigned half = in_lo ? w_lo : w_hi;
-  const unsigned changed = q.act_j ? (ok ? half | mask : half & ~mask) : half;
-  w_lo = in_lo ? changed : w_lo;
-  w_hi = in_lo ? w_hi : changed;
-  q.bits = ((unsigned long long)w_hi << 32) | w_lo;
-  deliv[e] = q.bits;
+  (KIND ? s.deliv_c : s.deliv_r)[e] = q.bits;
 }
 
 __device__ inline void edge_decide(const RfastDev& s, const FastMod& modM, int kind, int e, int r, EdgeIn& q) {

@@ -29,12 +29,15 @@
 // the lane) and ends with the two quad steps.  The columns kernel sums the rows in four interleaved
 // groups and adds the groups in order; the four lanes of a quad are those groups.
 // The integer plans of the rounds are the records the resolver writes for the multi-round kernels.
+#include "rfast_edge.h"
 #include "rfast_vec.h"
 
 
 namespace {
 
 constexpr int kTinyThreads = 1024;
+constexpr int kTinyResWaves = 2;      // resolver wavefronts: one for the edges of R, one for those of C
+constexpr int kTinyResThreads = 576 + 64 * kTinyResWaves;  // nine wavefronts of workers and the resolvers (170 registers each)
 constexpr size_t kTinyLds = 150 * 1024;
 constexpr int kTinyMaxItems = 4;  // sampled rows per lane in flight from global memory: n B <= kTinyMaxItems * kTinyThreads
 
@@ -61,7 +64,7 @@ struct TinyShape {
   size_t bytes;
 };
 
-__host__ __device__ inline TinyShape tiny_shape(const RfastDev& d, bool data_in_lds) {
+__host__ __device__ inline TinyShape tiny_shape(const RfastDev& d, bool data_in_lds, bool resolver = false) {
   TinyShape t;
   const size_t n = d.n, M = d.M, p = (size_t)d.p;
   const size_t B = d.prob.batch > 0 ? d.prob.batch : d.prob.samples;
@@ -72,14 +75,40 @@ __host__ __device__ inline TinyShape tiny_shape(const RfastDev& d, bool data_in_
   // graph: three pointer arrays, two self weights, R: src, w; C: src, w, out eid, out w; the active list and its
   // length; residuals of a round; row numbers of two rounds (sampled batches only); two plan records
   t.ints = 3 * (n + 1) + 2 * n + 2 * (size_t)d.eR + 4 * (size_t)d.eC + n + 1 + n * B + (d.prob.batch > 0 ? 2 * n * B : 0) +
-           2 * (n + d.eR + d.eC + 1);
+           2 * (n + d.eR + d.eC + 1) + (resolver ? kTinyResWaves * n * (2 + (size_t)d.H) : 0);  // resolvers: counters, activity flags, history, one set each
   t.bytes = t.state_f * 4 + ((t.data_f + 3) / 4 * 4) * 4 + t.ints * 4;
   return t;
 }
 
+// The caller's schedule of the rounds of a launch (the arguments of rfast_run), for the kernel that resolves them itself
+struct TinySched {
+  const uint8_t* active;     // [rounds][n]
+  const int32_t* delay_R;    // [rounds][eR]
+  const int32_t* delay_C;    // [rounds][eC]
+  const uint8_t* drop_R;     // [rounds][eR]
+  const uint8_t* drop_C;     // [rounds][eC]
+};
+
+__device__ inline void tiny_wave_sync() {  // orders the LDS accesses of the lanes of one wavefront
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // DATA: the objective data (rows and targets) are copied into LDS at the start.
-template <bool DATA>
-__global__ void __launch_bounds__(kTinyThreads) rfast_tiny_kernel(RfastDev s, RfastBlock blk, const int32_t* batch_idx, int round0) {
+// RES: graphs of up to 64 nodes and 64 edges of a kind: the last two wavefronts of the workgroup are resolvers, one
+// for the edges of R, one for those of C.  Lane L of either looks after node L and edge L of its graph, keeps the
+// counters and their history in LDS (each wavefront its own copy, so that the two never wait for each other) and its
+// edge's stamp and delivery bits in registers, reads the caller's schedule a round ahead, and forms its part of the
+// plan record of round q+2 while the other wavefronts finish round q (the decisions are those of the resolver
+// kernels: edge_compute).  Nothing integer goes to global memory before the end of the launch, and no resolver kernel
+// runs ahead of this one: on one compute unit next to another that idles, the resolver's 1.6 us per round is more
+// than half of this kernel's.
+template <bool DATA, bool RES>
+__global__ void __launch_bounds__(RES ? kTinyResThreads : kTinyThreads)
+    rfast_tiny_kernel(RfastDev s, RfastBlock blk, const int32_t* batch_idx, int round0, TinySched sched) {
+  constexpr int T = RES ? kTinyResThreads : kTinyThreads;  // lanes of the workgroup
+  constexpr int WORK = RES ? T - 64 * kTinyResWaves : T;    // ... that do the floating-point work
   extern __shared__ float4 lds4[];
   const int n = s.n, M = s.M, eR = s.eR, eC = s.eC;
   const int p = (int)s.p, P4 = p >> 2;
@@ -90,7 +119,9 @@ __global__ void __launch_bounds__(kTinyThreads) rfast_tiny_kernel(RfastDev s, Rf
   const int nB = n * B;
   const int W1 = n + eR + eC + 1;
   const int tid = threadIdx.x, lane = tid & 63, j = tid & 3;
-  const TinyShape shape = tiny_shape(s, DATA);
+  const bool worker = tid < WORK, res_wave = RES && tid >= WORK;
+  const int res_kind = res_wave ? (tid - WORK) >> 6 : 0;  // 0: the resolver of graph R (and of the node words), 1: of graph C
+  const TinyShape shape = tiny_shape(s, DATA, RES);
   const int ps = shape.ps;
   float* x_l = reinterpret_cast<float*>(lds4);  // [n][p]
   float* z_l = x_l + np;                        // [n][p]
@@ -115,63 +146,150 @@ __global__ void __launch_bounds__(kTinyThreads) rfast_tiny_kernel(RfastDev s, Rf
   int* nact_l = ip;             ip += 1;
   float* resid_l = reinterpret_cast<float*>(ip); ip += nB;   // [n][B] residuals of the round
   int* row_l = ip;              ip += sampled ? 2 * nB : 0;  // [2][n][B] sampled rows of this round and the next
-  int* plan_l = ip;                                          // [2][W1]
+  int* plan_l = ip;             ip += 2 * W1;                // [2][W1]
+  // resolvers, a set each: the counters, the activity flags of the round being resolved, [n][H] counters at the
+  // start of the last H rounds
+  int* t_l = ip + res_kind * n * (2 + s.H);
+  int* act2_l = t_l + n;
+  int* hist_l = act2_l + n;
+  const int* t_first = ip;  // the counters of the first resolver
 
   // ---- everything on chip: graph, state, first plan record, objective data
-  for (int q = tid; q <= n; q += kTinyThreads) {
+  for (int q = tid; q <= n; q += T) {
     r_ptr[q] = s.r_ptr[q];
     c_ptr[q] = s.c_ptr[q];
     co_ptr[q] = s.co_ptr[q];
   }
-  for (int q = tid; q < n; q += kTinyThreads) {
+  for (int q = tid; q < n; q += T) {
     r_self[q] = s.r_self[q];
     c_self[q] = s.c_self[q];
   }
-  for (int q = tid; q < eR; q += kTinyThreads) {
+  for (int q = tid; q < eR; q += T) {
     r_src[q] = s.r_src[q];
     r_w[q] = s.r_w[q];
   }
-  for (int q = tid; q < eC; q += kTinyThreads) {
+  for (int q = tid; q < eC; q += T) {
     c_src[q] = s.c_src[q];
     c_w[q] = s.c_w[q];
     co_eid[q] = s.co_eid[q];
     co_w[q] = s.co_w[q];
   }
-  if (tid < W1) plan_l[tid] = s.blk_plan[tid];
-  for (int q = tid; q < np / 4; q += kTinyThreads) {
+  if (!RES && tid < W1) plan_l[tid] = s.blk_plan[tid];
+  for (int q = tid; q < np / 4; q += T) {
     const int i = q / P4, k4 = q - i * P4;
-    const int t0 = s.blk_plan[i] & 0x3FFFFFFF;  // the node's counter before the first round
+    const int t0 = RES ? s.t[i] : s.blk_plan[i] & 0x3FFFFFFF;  // the node's counter before the first round
     reinterpret_cast<float4*>(x_l)[q] = reinterpret_cast<const float4*>(s.x)[q];
     reinterpret_cast<float4*>(z_l)[q] = reinterpret_cast<const float4*>(s.z)[q];
     reinterpret_cast<float4*>(g_l)[q] = reinterpret_cast<const float4*>(s.g + (size_t)(t0 & 1) * np)[(size_t)i * P4 + k4];
   }
-  for (int q = tid; q < np * M / 4; q += kTinyThreads) {
+  for (int q = tid; q < np * M / 4; q += T) {
     reinterpret_cast<float4*>(v_l)[q] = reinterpret_cast<const float4*>(s.v_ring)[q];
     reinterpret_cast<float4*>(sg_l)[q] = reinterpret_cast<const float4*>(s.sigma_ring)[q];
   }
-  for (int q = tid; q < eC * P4; q += kTinyThreads) reinterpret_cast<float4*>(rt_l)[q] = reinterpret_cast<const float4*>(s.rho_tilde)[q];
+  for (int q = tid; q < eC * P4; q += T) reinterpret_cast<float4*>(rt_l)[q] = reinterpret_cast<const float4*>(s.rho_tilde)[q];
   if (DATA) {
     const int rows = n * S;
-    for (int q = tid; q < rows * P4; q += kTinyThreads) {
+    for (int q = tid; q < rows * P4; q += T) {
       const int r = q / P4, k4 = q - r * P4;
       *reinterpret_cast<float4*>(data_l + (size_t)r * ps + 4 * k4) = reinterpret_cast<const float4*>(s.prob.data0)[q];
     }
-    for (int q = tid; q < rows; q += kTinyThreads) data_l[(size_t)rows * ps + q] = ((const float*)s.prob.data1)[q];
+    for (int q = tid; q < rows; q += T) data_l[(size_t)rows * ps + q] = ((const float*)s.prob.data1)[q];
   }
   if (sampled)
-    for (int q = tid; q < nB; q += kTinyThreads) row_l[q] = batch_idx[q];
+    for (int q = tid; q < nB; q += T) row_l[q] = batch_idx[q];
 
   const unsigned m_magic = 0xFFFFFFFFu / (unsigned)M;
   const int b_sh = (B & (B - 1)) == 0 ? __ffs(B) - 1 : -1;
   const int p_sh = (p & (p - 1)) == 0 ? __ffs(p) - 1 : -1;
+  // ---- the resolver wavefront: its state, the record of round 0 into LDS, that of round 1 into registers
+  const FastMod modM(M), modH(s.H);
+  const int H = s.H, r0 = RES ? *s.round_no : 0;
+  const int edges = res_kind ? eC : eR;    // of this resolver's graph
+  EdgeIn ed;                               // the lane's edge
+  int last_slot = -1;                      // its slot in the last round resolved (what reads of the slot fields return)
+  int sc_act = 0, sc_d = 0, sc_x = 0;      // the schedule of the next round to resolve, fetched a round ahead
+  int pend_node = 0, pend_edge = 0;        // its record, formed a round before it is parked in LDS
+  // schedule of round rel (counted from the first round of the launch) into the registers above
+  auto fetch_schedule = [&](int rel) {
+    if (rel >= blk.rounds) return;
+    if (lane < n) sc_act = sched.active[(size_t)rel * n + lane];
+    if (lane < edges) {
+      sc_d = (res_kind ? sched.delay_C : sched.delay_R)[(size_t)rel * edges + lane];
+      sc_x = (res_kind ? sched.drop_C : sched.drop_R)[(size_t)rel * edges + lane];
+    }
+  };
+  // resolves round rel from the schedule in the registers: the record into pend_*, the state one round on
+  auto resolve = [&](int rel) {
+    const int r = r0 + rel;
+    if (lane < n) act2_l[lane] = sc_act != 0;
+    tiny_wave_sync();
+    if (lane < edges) {
+      ed.d = sc_d;
+      ed.dropped = sc_x != 0;
+      ed.act_i = act2_l[ed.i] != 0;
+      ed.act_j = act2_l[ed.j] != 0;
+      ed.tj = t_l[ed.j];
+      const int d = sc_d < 0 ? 0 : (sc_d > s.d_max ? s.d_max : sc_d);
+      const int at = r - d;
+      // the sender's counter at the start of round `at`; round r itself is the current counter
+      ed.u = at <= 0 ? 0 : (at >= r ? ed.tj : hist_l[ed.j * H + modH(at)]);
+    }
+    tiny_wave_sync();  // every lane has read the history of this round's delays
+    int ti = 0;
+    bool on = false;
+    if (lane < n) {
+      ti = t_l[lane];
+      on = sc_act != 0;
+      hist_l[lane * H + modH(r)] = ti;
+    }
+    pend_node = (ti & 0x3FFFFFFF) | (on ? (int)0x80000000 : 0);
+    if (lane < edges) {
+      const EdgeOut o = res_kind ? edge_compute<1>(s, modM, lane, r, ed) : edge_compute<0>(s, modM, lane, r, ed);
+      pend_edge = o.word;
+      last_slot = o.slot;
+    }
+    tiny_wave_sync();  // every read of the counters is done
+    if (on) t_l[lane] = ti + 1;
+    tiny_wave_sync();
+  };
+  // parks the record in pend_* as that of a round with the given parity
+  auto park = [&](int parity) {
+    int* rec = plan_l + parity * W1;
+    if (res_kind == 0) {
+      if (lane < n) rec[lane] = pend_node;
+      if (lane < eR) rec[n + lane] = pend_edge;
+      if (lane == 0) rec[W1 - 1] = 0;  // a record ends with a word that is always zero
+    } else if (lane < eC) {
+      rec[n + eR + lane] = pend_edge;
+    }
+  };
+  if (res_wave) {
+    if (lane < n) t_l[lane] = s.t[lane];
+    for (int q = lane; q < n * H; q += 64) hist_l[q] = s.t_hist[q];
+    if (lane < edges) {
+      ed.i = (res_kind ? s.c_dst : s.r_dst)[lane];
+      ed.j = (res_kind ? s.c_src : s.r_src)[lane];
+      ed.bits = (res_kind ? s.deliv_c : s.deliv_r)[lane];
+      ed.old = (res_kind ? s.tau_c : s.tau_r)[lane];
+    }
+    fetch_schedule(0);
+    tiny_wave_sync();
+    resolve(0);
+    park(0);
+    fetch_schedule(1);
+    if (blk.rounds > 1) {
+      resolve(1);
+      fetch_schedule(2);
+    }
+  }
   // the plan record and the row numbers of the round after next travel in registers for one round
   int pend_plan = 0, pend_row[kTinyMaxItems] = {0, 0, 0, 0};
   if (blk.rounds > 1) {
-    if (tid < W1) pend_plan = s.blk_plan[(size_t)W1 + tid];
+    if (!RES && tid < W1) pend_plan = s.blk_plan[(size_t)W1 + tid];
     if (sampled) {
 #pragma unroll
       for (int u = 0; u < kTinyMaxItems; ++u)
-        if (tid + u * kTinyThreads < nB) pend_row[u] = batch_idx[(size_t)nB + tid + u * kTinyThreads];
+        if (tid + u * T < nB) pend_row[u] = batch_idx[(size_t)nB + tid + u * T];
     }
   }
   __syncthreads();
@@ -188,7 +306,7 @@ __global__ void __launch_bounds__(kTinyThreads) rfast_tiny_kernel(RfastDev s, Rf
 
     // ---- S1, S2a, S3 (v half): as rfast_state_kernel<MIX>; lane t, t + 1024, ... of the flattened [n][p]
 #pragma unroll 1
-    for (int t = tid; t < np; t += kTinyThreads) {
+    for (int t = worker ? tid : np; t < np; t += WORK) {
       const int i = div_small(t, p, p_sh), k = t - i * p;
       const int word = P[i];
       if (word < 0) {  // bit 31: active
@@ -204,7 +322,7 @@ __global__ void __launch_bounds__(kTinyThreads) rfast_tiny_kernel(RfastDev s, Rf
       }
     }
     // the round's active nodes in order, by the last wavefront
-    if (tid >= kTinyThreads - 64) {
+    if (tid >= T - 64) {
       int cnt = 0;
       for (int base = 0; base < n; base += 64) {
         const bool a = base + lane < n && P[base + lane] < 0;
@@ -219,25 +337,29 @@ __global__ void __launch_bounds__(kTinyThreads) rfast_tiny_kernel(RfastDev s, Rf
     // the next round's record and rows: fetched a round ago, parked now (their buffers were last read before this
     // barrier), and the fetch for the round after that goes out
     if (q + 1 < blk.rounds) {
-      if (tid < W1) plan_l[((q + 1) & 1) * W1 + tid] = pend_plan;
+      if (RES) {
+        if (res_wave) park((q + 1) & 1);
+      } else if (tid < W1) {
+        plan_l[((q + 1) & 1) * W1 + tid] = pend_plan;
+      }
       if (sampled) {
 #pragma unroll
         for (int u = 0; u < kTinyMaxItems; ++u)
-          if (tid + u * kTinyThreads < nB) row_l[((q + 1) & 1) * nB + tid + u * kTinyThreads] = pend_row[u];
+          if (tid + u * T < nB) row_l[((q + 1) & 1) * nB + tid + u * T] = pend_row[u];
       }
       if (q + 2 < blk.rounds) {
-        if (tid < W1) pend_plan = s.blk_plan[(size_t)(q + 2) * W1 + tid];
+        if (!RES && tid < W1) pend_plan = s.blk_plan[(size_t)(q + 2) * W1 + tid];
         if (sampled) {
 #pragma unroll
           for (int u = 0; u < kTinyMaxItems; ++u)
-            if (tid + u * kTinyThreads < nB) pend_row[u] = batch_idx[(size_t)(q + 2) * nB + tid + u * kTinyThreads];
+            if (tid + u * T < nB) pend_row[u] = batch_idx[(size_t)(q + 2) * nB + tid + u * T];
         }
       }
     }
 
     // ---- gradient, rows: as rfast_rows_kernel; a quad per (active node, sampled row)
     const int tasks = *nact_l * B;
-    for (int f = tid >> 2; f < tasks; f += kTinyThreads / 4) {
+    for (int f = worker ? tid >> 2 : tasks; f < tasks; f += WORK / 4) {
       const int a = div_small(f, B, b_sh);
       const int i = act_l[a], b = f - a * B;
       int row = b;
@@ -301,8 +423,13 @@ __global__ void __launch_bounds__(kTinyThreads) rfast_tiny_kernel(RfastDev s, Rf
     // ---- gradient, columns (as rfast_cols_kernel<4>): lane j of a quad sums rows j, j + 4, ... for the quad's four
     // coordinates; every lane then adds the four sums of its own coordinate in order;
     // then S2b, S2c, S3 (rho half), S4 (as rfast_state_kernel<TRACK>)
+    // the resolver goes on to the round after next while the others finish this one
+    if (res_wave && q + 2 < blk.rounds) {
+      resolve(q + 2);
+      fetch_schedule(q + 3);
+    }
 #pragma unroll 1
-    for (int t = tid; t < np; t += kTinyThreads) {
+    for (int t = worker ? tid : np; t < np; t += WORK) {
       const int i = div_small(t, p, p_sh), k = t - i * p;
       const int word = P[i];
       if (word < 0) {
@@ -384,33 +511,54 @@ __global__ void __launch_bounds__(kTinyThreads) rfast_tiny_kernel(RfastDev s, Rf
   }
   __syncthreads();
 
-  // ---- write-back; the resolver has advanced the counters already: s.t holds those after the launch
-  for (int q = tid; q < np / 4; q += kTinyThreads) {
+  // ---- write-back; the counters after the launch are the resolver's: those of the resolver kernel that ran ahead
+  // of this one (s.t), or those of the resolver wavefront, which stores its integer state now
+  if (res_wave) {
+    if (res_kind == 0) {
+      if (lane < n) s.t[lane] = t_l[lane];
+      for (int q = lane; q < n * H; q += 64) s.t_hist[q] = hist_l[q];
+      if (lane == 0) *s.round_no = r0 + blk.rounds;
+    }
+    if (lane < edges) {
+      (res_kind ? s.tau_c : s.tau_r)[lane] = ed.old;
+      (res_kind ? s.deliv_c : s.deliv_r)[lane] = ed.bits;
+      (res_kind ? s.slot_c : s.slot_r)[lane] = last_slot;
+    }
+  }
+  for (int q = tid; q < np / 4; q += T) {
     const int i = q / P4, k4 = q - i * P4;
     reinterpret_cast<float4*>(s.x)[q] = reinterpret_cast<const float4*>(x_l)[q];
     reinterpret_cast<float4*>(s.z)[q] = reinterpret_cast<const float4*>(z_l)[q];
-    reinterpret_cast<float4*>(s.g + (size_t)(s.t[i] & 1) * np)[(size_t)i * P4 + k4] = reinterpret_cast<const float4*>(g_l)[q];
+    const int t_end = RES ? t_first[i] : s.t[i];
+    reinterpret_cast<float4*>(s.g + (size_t)(t_end & 1) * np)[(size_t)i * P4 + k4] = reinterpret_cast<const float4*>(g_l)[q];
   }
-  for (int q = tid; q < np * M / 4; q += kTinyThreads) {
+  for (int q = tid; q < np * M / 4; q += T) {
     reinterpret_cast<float4*>(s.v_ring)[q] = reinterpret_cast<const float4*>(v_l)[q];
     reinterpret_cast<float4*>(s.sigma_ring)[q] = reinterpret_cast<const float4*>(sg_l)[q];
   }
-  for (int q = tid; q < eC * P4; q += kTinyThreads) reinterpret_cast<float4*>(s.rho_tilde)[q] = reinterpret_cast<const float4*>(rt_l)[q];
+  for (int q = tid; q < eC * P4; q += T) reinterpret_cast<float4*>(s.rho_tilde)[q] = reinterpret_cast<const float4*>(rt_l)[q];
 }
 
 bool tiny_data_fits(const RfastDev& d) { return tiny_shape(d, true).bytes <= kTinyLds; }
 
-template <bool DATA>
-hipError_t launch_tiny(rfast_ctx* c, const RfastBlock& blk, const int32_t* bi, int round0) {
+// whether the graph is small enough for the resolver wavefront: a lane per node, per edge of R and per edge of C
+bool tiny_resolves(const RfastDev& d) {
+  const int64_t B = d.prob.batch > 0 ? d.prob.batch : d.prob.samples;
+  return d.n <= 64 && d.eR <= 64 && d.eC <= 64 && (int64_t)d.n * d.p <= 4 * (kTinyResThreads - 64) &&
+         (int64_t)d.n * B <= (int64_t)kTinyMaxItems * kTinyResThreads && tiny_shape(d, false, true).bytes <= kTinyLds;
+}
+
+template <bool DATA, bool RES>
+hipError_t launch_tiny(rfast_ctx* c, const RfastBlock& blk, const int32_t* bi, int round0, const TinySched& sched) {
   static bool raised = false;
   if (!raised) {  // more than 64 KB of dynamic LDS has to be asked for once per kernel
     const hipError_t e =
-        hipFuncSetAttribute((const void*)rfast_tiny_kernel<DATA>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        hipFuncSetAttribute((const void*)rfast_tiny_kernel<DATA, RES>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     raised = true;
   }
-  hipLaunchKernelGGL((rfast_tiny_kernel<DATA>), dim3(1), dim3(kTinyThreads), tiny_shape(c->d, DATA).bytes, c->stream, c->d, blk,
-                     bi, round0);
+  hipLaunchKernelGGL((rfast_tiny_kernel<DATA, RES>), dim3(1), dim3(RES ? kTinyResThreads : kTinyThreads),
+                     tiny_shape(c->d, DATA, RES).bytes, c->stream, c->d, blk, bi, round0, sched);
   return hipGetLastError();
 }
 
@@ -429,10 +577,25 @@ bool rfast_tiny_eligible(const rfast_ctx* c) {
   return tiny_shape(d, false).bytes <= kTinyLds;
 }
 
-hipError_t rfast_launch_tiny(rfast_ctx* c, const RfastBlock& blk, const int32_t* d_batch_idx, int round0) {
+// ... and a graph small enough for the kernel to resolve its rounds itself: no resolver launch ahead of it, and the
+// caller's schedule goes to rfast_launch_tiny instead
+bool rfast_tiny_resolves(const rfast_ctx* c) { return rfast_tiny_eligible(c) && tiny_resolves(c->d); }
+
+// The schedule pointers are those of rfast_run for the first round of the launch; they are read only if
+// rfast_tiny_resolves(c), otherwise the plan records of the resolver kernel (c->d.blk_plan) are.
+hipError_t rfast_launch_tiny(rfast_ctx* c, const RfastBlock& blk, const int32_t* d_batch_idx, int round0, const uint8_t* d_active,
+                             const int32_t* d_delay_R, const int32_t* d_delay_C, const uint8_t* d_drop_R, const uint8_t* d_drop_C) {
   const RfastDev& d = c->d;
-  if (!d.blk_plan || !rfast_tiny_eligible(c)) return hipErrorInvalidValue;
+  if (!rfast_tiny_eligible(c)) return hipErrorInvalidValue;
+  const bool res = tiny_resolves(d);
+  if (!res && !d.blk_plan) return hipErrorInvalidValue;
   const int32_t* bi = d.prob.batch > 0 ? d_batch_idx : nullptr;
   if (d.prob.batch > 0 && !bi) return hipErrorInvalidValue;
-  return tiny_data_fits(d) ? launch_tiny<true>(c, blk, bi, round0) : launch_tiny<false>(c, blk, bi, round0);
+  const TinySched sched = {d_active, d_delay_R, d_delay_C, d_drop_R, d_drop_C};
+  if (res) {
+    if (!d_active || (d.eR && (!d_delay_R || !d_drop_R)) || (d.eC && (!d_delay_C || !d_drop_C))) return hipErrorInvalidValue;
+    return tiny_shape(d, true, true).bytes <= kTinyLds ? launch_tiny<true, true>(c, blk, bi, round0, sched)
+                                                       : launch_tiny<false, true>(c, blk, bi, round0, sched);
+  }
+  return tiny_data_fits(d) ? launch_tiny<true, false>(c, blk, bi, round0, sched) : launch_tiny<false, false>(c, blk, bi, round0, sched);
 }

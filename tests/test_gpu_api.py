@@ -101,6 +101,32 @@ def test_out_of_range_sample_row_is_clamped_and_reported():
     assert np.isfinite(gpu.read("X")).all()
 
 
+def test_out_of_range_delay_in_a_run_that_resolves_its_own_rounds():
+    """Config 0 runs as one workgroup whose last wavefronts are the resolver: the same clamp and the same report."""
+    w = configs.config0(rounds=6)
+    gpu = harness.make_gpu(w)
+    assert rf.rfast_block_info(gpu.ctx) != 0
+    gpu.init()
+    st, dev = harness.upload_chunk(gpu, w, 0, 6)
+    assert st["active"][4].any()
+    dC = dev["delay_C"].clone()
+    dC[4, :] = w.D + 5            # every C edge of round 4: whichever has an active receiver is reported
+    gpu.run(6, dev["active"], dev["delay_R"], dC, dev["drop_R"], dev["drop_C"], w.gamma, None)
+    with pytest.raises(rf.RFastError) as ei:
+        gpu.check()
+    assert ei.value.code == -4 and "C edge" in str(ei.value) and "round 4" in str(ei.value), str(ei.value)
+    assert np.isfinite(gpu.read("X")).all() and np.isfinite(gpu.read("Z")).all()
+    # the clamped run is the run with the largest delay allowed
+    ref = harness.make_gpu(w)
+    ref.init()
+    dC2 = dev["delay_C"].clone()
+    dC2[4, :] = w.sched.d_max
+    ref.run(6, dev["active"], dev["delay_R"], dC2, dev["drop_R"], dev["drop_C"], w.gamma, None)
+    ref.check()
+    for f in ("X", "Z", "T_NODE", "TAU_R", "TAU_C"):
+        assert np.array_equal(gpu.read(f), ref.read(f)), f
+
+
 @pytest.mark.parametrize("path", ["two kernels per round", "one workgroup"])
 def test_out_of_range_sample_row_in_a_later_round_of_a_run(path):
     """The same report from the kernels that rfast_run uses for stretches of rounds: the round is named by its number

@@ -14,6 +14,7 @@ import harness
 
 pytestmark = pytest.mark.gpu
 FIELDS = ("X", "Z", "G", "V_RING", "SIGMA_RING", "RHO_TILDE", "T_NODE", "TAU_R", "TAU_C", "SLOT_R", "SLOT_C", "ROUND")
+INTEGER_REST = ("DELIV_R", "DELIV_C", "T_HIST")   # what else a resolver leaves behind (the kernel of small graphs has its own)
 
 
 def _pair(w):
@@ -22,8 +23,8 @@ def _pair(w):
     return a, b
 
 
-def _same(a, b, where):
-    for f in FIELDS:
+def _same(a, b, where, more=()):
+    for f in FIELDS + tuple(more):
         assert np.array_equal(a.read(f), b.read(f)), (where, f)
 
 
@@ -237,12 +238,12 @@ def test_whole_problem_in_one_workgroup(case):
             bi = None if dev["batch_idx"] is None else dev["batch_idx"][lo:hi].contiguous()
             g.run(hi - lo, *[dev[k][lo:hi].contiguous() for k in names], w.gamma, bi)
             g.check()
-        _same(a, b, (case, hi))
+        _same(a, b, (case, hi), INTEGER_REST)
     p_act = torch.full((w.n,), 0.6, dtype=torch.float32)
     for g in (a, b):
         g.run_generated(70, 5, p_act.to(g.device), w.sched.d_max, 0.1, w.gamma)
         g.check()
-    _same(a, b, (case, "generated"))
+    _same(a, b, (case, "generated"), INTEGER_REST)
     assert np.abs(a.read("X") - x0).max() > 1e-3
 @pytest.mark.parametrize("case", ["logistic_minibatches", "least_squares_full_gradient", "rows_longer_than_one_pass",
                                   "weight_decay_many_in_edges"])

@@ -432,6 +432,10 @@ def main():
         secs = one_ms * 1e-3
         launches = max(one_launches, 1)
         kernel = "rfast_state_kernel" + ("<FUSED>" if separable else "<MIX> + <TRACK>")
+        if w.objective in ("least_squares", "logistic") and not args.no_blocks:
+            # this leg runs its rounds in calls of one: a mixing pass, then the kernel that does the column sums and the
+            # tracker update (in a longer call it also mixes for the next round and the mixing pass runs once per stretch)
+            kernel = "rfast_state_kernel<MIX> + rfast_cols_track_mix_kernel"
         act1 = act_prof
         alg1 = sum(algorithmic_bytes_per_round(w, a) for a in act1)
         lay1 = sum(algorithmic_bytes_per_round(w, a, layout=True) for a in act1)

@@ -28,10 +28,10 @@
 // the sixteen sums c = j, j+4, ..., adds them in that butterfly's order (distances 32 .. 4 stay inside
 // the lane) and ends with the two quad steps.  The columns kernel sums the rows in four interleaved
 // groups and adds the groups in order; the four lanes of a quad are those groups.
-// The integer plans of the rounds are the records the resolver writes for the multi-round kernels.
+// The integer plans of the rounds are the records the resolver writes for the multi-round kernels, or, on
+// small graphs, records of the same form that two more wavefronts of this workgroup write (RES below).
 #include "rfast_edge.h"
 #include "rfast_vec.h"
-
 
 namespace {
 

@@ -77,8 +77,11 @@ __device__ inline EdgeOut edge_compute(const RfastDev& s, const FastMod& modM, i
     const bool leaves = q.act_j && now == lo;
     o.spill = !live && leaves;  // the receiver does not consume, and the version its buffer holds leaves
     // bits 0-7 of a spill word: the slot of the version that leaves (now == lo then)
+    // bits 30 and 31 sort the live edges for a consumer that wants one compare per case: the usual one (what was
+    // consumed last time is still in the ring, what is consumed now stays there) and the rest
+    const bool usual = live && !leaves && old >= lo;
     o.word = q.act_i ? now_slot | ((old >= lo ? modM(old) : 0xFF) << 8) | (live ? 1 << 16 : 0) | (live && leaves ? 1 << 17 : 0) |
-                           (o.spill ? 1 << 18 : 0)
+                           (o.spill ? 1 << 18 : 0) | (usual ? 1 << 30 : 0) | (live && !usual ? (int)0x80000000 : 0)
                      : (o.spill ? now_slot | 1 << 18 : 0);
   }
   // the sender publishes version t_j + 1 this round (if it is active): lost only if the schedule says so and not all

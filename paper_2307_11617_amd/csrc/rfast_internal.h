@@ -77,6 +77,8 @@ struct RfastDev {
   //   bit 16     live: the receiver is active and its stamp moved (otherwise the edge contributes exactly zero)
   //   bit 17     the receiver writes what it consumes to the rho_tilde array
   //   bit 18     the sender copies a_ij * sigma_j[t_j - D] to the rho_tilde array
+  //   bit 30     live, bits 8-15 are a slot and bit 17 is clear (the usual live edge)
+  //   bit 31     live otherwise
   int32_t* plan_c;        // [eC]
   uint8_t* node_spill;    // [n]   some out-edge of this node has bit 18 set
   // The plan of one round once more, as one record for the kernel that keeps a tile of coordinates

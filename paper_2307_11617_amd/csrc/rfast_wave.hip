@@ -310,10 +310,10 @@ __global__ void __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 
         // 0xFF) and whose consumed version does not leave it (bit 17 clear) — and the idle edge run through the
         // same multiply-add, the idle edge with weight zero (it adds zero to z): no branch; the other live
         // cases are rare and branch.
-        const unsigned key = (unsigned)P.c[u] & 0x3FF00u;
-        const float a_eff = key - 0x10000u < 0xFF00u ? c_w[u] : 0.f;
+        // (bits 30 and 31 of the word say which case it is: one signed compare each)
+        const float a_eff = P.c[u] > 0x3FFFFFFF ? c_w[u] : 0.f;
         z_half = track_edge(z_half, a_eff, cur[u], last[u], true);
-        if (key >= 0x1FF00u) {
+        if (P.c[u] < 0) {
           if (((P.c[u] >> 8) & 0xFF) != 0xFF) z_half = track_edge(z_half, c_w[u], cur[u], last[u], true);
           else z_half = track_edge(z_half, c_w[u], cur[u], rt[u], false);  // the version consumed last time has left the ring
           if (P.c[u] & (1 << 17)) rt[u] = mul_s(c_w[u], cur[u]);  // consumed, and leaving the ring in this round

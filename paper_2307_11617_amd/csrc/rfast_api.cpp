@@ -101,7 +101,7 @@ Offsets layout(int32_t n, int64_t p, int32_t nnzR, int32_t nnzC, int32_t D, cons
   o.plan_set_bytes = L.total - o.n_active;
   (void)L.take((size_t)(kResolveAhead - 1) * o.plan_set_bytes);
   o.blk_plan = L.take((size_t)kBlockRounds * ((size_t)n + eR + eC + 1) * 4);
-  o.blk_head = L.take((8 * (size_t)n + eC) * 4);
+  o.blk_head = L.take((kHeadWords * (size_t)n + eC) * 4);
   // the generator draws the schedule of up to gen_depth rounds per launch (as many as fit 64 MB, at most kBlockRounds)
   const size_t gen_rows = (size_t)n * (size_t)(prob->kind == RFAST_OBJ_DIAG_QUADRATIC ? 0 : prob->batch);
   const size_t gen_round = (size_t)n + 5 * (eR + eC) + 4 * gen_rows;

@@ -86,12 +86,19 @@ struct RfastDev {
   // counter at the start of the round), [eR] ring slot per R edge, [eC] plan word per C edge.
   int32_t* blk_plan;
   // What a multi-round launch needs to know about the state before its first round and after its last,
-  // written by the resolver around the rounds it resolves (NULL: not wanted).  [n][8] per node j: its
-  // counter before and after; the oldest version of its v ring that a receiver could still pick up
-  // before (the smallest stamp held on j's out-edges over R; INT_MAX if j has none), the same for its
-  // ring of running sums (out-edges over C); both once more for after; two unused words.  Then [eC]
-  // per C edge: bit 0 set if its S4 buffer was in the rho_tilde array before (its version outside the
-  // sender's ring), bit 1 if it is after.
+  // written by the resolver around the rounds it resolves (NULL: not wanted).  [n][kHeadWords] per node j:
+  //   0, 1    its counter before and after
+  //   2, 3    the oldest version of its v ring that a receiver could still pick up before (the smallest stamp held
+  //           on j's out-edges over R; INT_MAX if j has none), the same for its ring of running sums (out-edges over C)
+  //   4, 5    both once more for after
+  //   8, 9    the ring slot of its latest version before and after (the counter mod M)
+  //   10, 11  one bit per slot of its v ring / its ring of sums: the slot holds a version that can still be picked
+  //           up before the launch (such slots are loaded, the others are zeros in LDS)
+  //   12      one bit per slot: the launch writes the slot
+  //   13, 14  as 10, 11, for after the launch (what is stored is a slot of 12 that is also one of 13 or 14; with a
+  //           rebase on the way out, every slot of 14)
+  // (rings of up to 32 slots).  Then [eC] per C edge: bit 0 set if its S4 buffer was in the rho_tilde array before
+  // (its version outside the sender's ring), bit 1 if it is after.
   int32_t* blk_head;
   // schedule of the current round when it is generated on the device
   uint8_t* gen_active;    // [n]
@@ -137,7 +144,7 @@ struct rfast_ctx {
   int32_t use_blocks = 1;       // 1: where it pays, 2: wherever possible; rfast_run / rfast_run_generated may advance several rounds per launch
   int32_t wave_group = 0;       // wavefronts per workgroup of the wavefront-tile kernel (0: chosen by the launcher)
   int32_t* blk_plan_base = nullptr;  // kBlockRounds plan records
-  int32_t* blk_head_base = nullptr;  // 8 n + eC words, see RfastDev::blk_head
+  int32_t* blk_head_base = nullptr;  // kHeadWords n + eC words, see RfastDev::blk_head
   int32_t max_degree = 0;       // most in-edges of R, in-edges of C or out-edges of C at any node
   // the per-round plan arrays of RfastDev exist kResolveAhead times; `plan_set` is the set d points at
   char* plan_set0 = nullptr;
@@ -153,6 +160,7 @@ enum { RFAST_MODE_FUSED = 0, RFAST_MODE_MIX = 1, RFAST_MODE_TRACK = 2 };
 // in LDS at a time, and the shortest launch that pays where the state is large (the launch moves
 // every ring slot in and out once: measured on 16 nodes x 11.2 M coordinates, about 7 ms per launch
 // plus 0.33 ms per round against 1.53 ms per round of the streaming kernel: even from 6 rounds on)
+constexpr int kHeadWords = 16;  // words per node in RfastDev::blk_head
 constexpr int kBlockRounds = 512;
 constexpr int kPlanChunk = 16;
 constexpr int kBlockMinRoundsLarge = 8;

@@ -69,22 +69,47 @@ __device__ inline void edge_decide(const RfastDev& s, const FastMod& modM, int k
 // RfastDev::blk_head.  Called by every lane of the one workgroup.
 __device__ inline void block_head(const RfastDev& s, int when) {
   int32_t* H = s.blk_head;
+  constexpr int K = kHeadWords;
   __syncthreads();  // when = 1: the last round's counters and stamps are written
   for (int j = threadIdx.x; j < s.n; j += blockDim.x) {
-    H[8 * j + when] = s.t[j];
-    H[8 * j + 2 + 2 * when] = 0x7fffffff;
-    H[8 * j + 3 + 2 * when] = 0x7fffffff;
+    H[K * j + when] = s.t[j];
+    H[K * j + 2 + 2 * when] = 0x7fffffff;
+    H[K * j + 3 + 2 * when] = 0x7fffffff;
   }
   __syncthreads();
-  for (int e = threadIdx.x; e < s.eR; e += blockDim.x) atomicMin(&H[8 * s.r_src[e] + 2 + 2 * when], s.tau_r[e]);
+  for (int e = threadIdx.x; e < s.eR; e += blockDim.x) atomicMin(&H[K * s.r_src[e] + 2 + 2 * when], s.tau_r[e]);
   for (int e = threadIdx.x; e < s.eC; e += blockDim.x) {
     const int j = s.c_src[e], tau = s.tau_c[e];
-    atomicMin(&H[8 * j + 3 + 2 * when], tau);
+    atomicMin(&H[K * j + 3 + 2 * when], tau);
     const int outside = tau < s.t[j] - (s.M - 2) ? 1 : 0;  // the S4 buffer of the edge is in the rho_tilde array
-    if (when == 0) H[8 * s.n + e] = outside;
-    else H[8 * s.n + e] |= outside << 1;
+    if (when == 0) H[K * s.n + e] = outside;
+    else H[K * s.n + e] |= outside << 1;
   }
   __syncthreads();  // when = 0: the rounds below move the stamps and the counters
+  if (when == 0) return;
+  // the same facts per ring slot, so that the lanes of the launch test a bit where they would compute a version
+  for (int j = threadIdx.x; j < s.n; j += blockDim.x) {
+    const int M = s.M, t0 = H[K * j], te = H[K * j + 1];
+    const int s0 = t0 % M, se = te % M;
+    unsigned in_v = 0, in_s = 0, written = 0, out_v = 0, out_s = 0;
+    for (int m = 0; m < M && m < 32; ++m) {
+      // version held by slot m when the latest version t is in slot t mod M (negative: never written)
+      const int v0 = t0 - (s0 - m < 0 ? s0 - m + M : s0 - m), v1 = te - (se - m < 0 ? se - m + M : se - m);
+      const unsigned bit = 1u << m;
+      if (v0 >= H[K * j + 2]) in_v |= bit;
+      if (v0 >= H[K * j + 3]) in_s |= bit;
+      if (v1 > t0) written |= bit;
+      if (v1 >= H[K * j + 4]) out_v |= bit;
+      if (v1 >= H[K * j + 5]) out_s |= bit;
+    }
+    H[K * j + 8] = s0;
+    H[K * j + 9] = se;
+    H[K * j + 10] = (int)in_v;
+    H[K * j + 11] = (int)in_s;
+    H[K * j + 12] = (int)written;
+    H[K * j + 13] = (int)out_v;
+    H[K * j + 14] = (int)out_s;
+  }
 }
 
 constexpr int kResolveThreads = 1024;

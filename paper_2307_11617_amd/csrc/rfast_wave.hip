@@ -65,15 +65,29 @@ __device__ inline void wave_sync() {
 // not write are not stored either, nor x and z of a node it never activated, and an S4 buffer is moved
 // only while its version is outside its sender's ring.  With the delays of the bidirectional-ring
 // workload that is 30 rows per node instead of 46.
+// Multipliers for the two divisions of a lane number that the kernel starts with, by the lanes per node and by the
+// lanes of a row segment: x / d = (x * ceil(2^16 / d)) >> 16 for x < 256 and d <= 256 (the error of the quotient,
+// x (d ceil(2^16 / d) - 2^16) / (2^16 d), stays below 1 / d).  The division itself is some 25 instructions, which
+// every wavefront of a launch would run.
+struct WaveDiv {
+  unsigned lanes, segment;
+};
+static WaveDiv wave_div(int lw, int W) {
+  WaveDiv dv;
+  dv.lanes = (65536u + (unsigned)lw - 1) / (unsigned)lw;
+  dv.segment = (65536u + (unsigned)(lw * W) - 1) / (unsigned)(lw * W);
+  return dv;
+}
+
 template <int kDeg, bool MOM, int W>
-__global__ void __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 2))) rfast_wave_kernel(RfastDev s, RfastBlock blk, int lw) {
+__global__ void __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 2))) rfast_wave_kernel(RfastDev s, RfastBlock blk, int lw, WaveDiv dv) {
   constexpr int VEC = 4;
   extern __shared__ float4 lds4[];
   const int n = s.n, M = s.M;
   const int64_t p = s.p;
   const int W1 = n + s.eR + s.eC + 1;  // words of a plan record; the last one is always zero
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int i = lane / lw, ln = lane - i * lw;
+  const int i = (int)(((unsigned)lane * dv.lanes) >> 16), ln = lane - i * lw;  // lane / lw
   // Workgroup b runs on XCD b mod 8, each with an L2 of its own.  Neighbouring workgroups go to the same
   // XCD, one right after the other, in runs that cover kTileRun tiles (4 KB of every row on 16 nodes):
   // that keeps the rows an XCD moves at one time on few pages (a launch of 10 rounds, which is all moving,
@@ -99,26 +113,26 @@ __global__ void __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 
   // Moving the rings: lane T of the workgroup moves column cT (of the lw W columns of a row segment) of
   // node iT, i.e. column lT of the tile of wavefront wT.  With W = 1 that is the lane's own column.
   const int seg = lw * W;
-  const int iT = (int)threadIdx.x / seg, cT = (int)threadIdx.x - iT * seg;
-  const int wT = cT / lw, lT = cT - wT * lw;
+  const int iT = W == 1 ? i : (int)((threadIdx.x * dv.segment) >> 16), cT = (int)threadIdx.x - iT * seg;  // threadIdx.x / seg
+  const int wT = W == 1 ? 0 : (int)(((unsigned)cT * dv.lanes) >> 16), lT = cT - wT * lw;                  // cT / lw
   const int64_t kT = k_wg + 4 * cT;
   const bool moves = iT < n && kT < p;
   float4* mv_l = lds4 + (size_t)wT * 2 * ring_f4 + (size_t)iT * M * lw + lT;  // + slot * lw (+ ring_f4 for the sums)
-  // Counters of the moved node before and after the launch, and the oldest versions of its two rings that a
-  // receiver could pick up before and can pick up after it (the resolver has been through all rounds of the
-  // launch already and left both in one record per node).
-  int t0_T = 0, te_T = 0, lo0_v = 0x7fffffff, lo0_s = 0x7fffffff, lo1_v = 0x7fffffff, lo1_s = 0x7fffffff;
+  // What the resolver, which has been through all rounds of the launch already, left about the moved node: the slot
+  // of its latest version after the launch and, one bit per ring slot, which slots hold versions that a receiver
+  // can still pick up before the launch (the others are not loaded), which the launch writes, and which hold
+  // versions that can still be picked up after it (RfastDev::blk_head).
+  int se_T = 0;
+  unsigned in_v = 0, in_s = 0, put_v = 0, put_s = 0;
   if (moves) {
-    const int4 a = *reinterpret_cast<const int4*>(s.blk_head + 8 * iT);
-    const int2 b = *reinterpret_cast<const int2*>(s.blk_head + 8 * iT + 4);
-    t0_T = a.x; te_T = a.y; lo0_v = a.z; lo0_s = a.w; lo1_v = b.x; lo1_s = b.y;
+    const int4 a = *reinterpret_cast<const int4*>(s.blk_head + kHeadWords * iT + 8);   // s0, se, in_v, in_s
+    const int4 b = *reinterpret_cast<const int4*>(s.blk_head + kHeadWords * iT + 12);  // written, out_v, out_s
+    se_T = a.y; in_v = (unsigned)a.z; in_s = (unsigned)a.w;
+    // a slot goes back if the launch wrote it and somebody can still read its version; with a rebase on the way
+    // out every readable slot of the running sums is shifted, written or not
+    put_v = (unsigned)b.x & (unsigned)b.y;
+    put_s = blk.rebase ? (unsigned)b.z : (unsigned)b.x & (unsigned)b.z;
   }
-  const int s0_T = t0_T % M, se_T = te_T % M;  // slots of the node's latest version before and after
-  // version held by slot m when the latest version, in slot s_latest, is t_latest (negative: never written)
-  auto version_in = [&](int m, int s_latest, int t_latest) {
-    const int back = s_latest - m;
-    return t_latest - (back < 0 ? back + M : back);
-  };
 
   float4 x, z, g, h, c, m = make_float4(0.f, 0.f, 0.f, 0.f);
   const bool momentum = MOM && s.mom != nullptr;  // the heavy-ball buffer of the optimizer variant is in use
@@ -203,8 +217,8 @@ __global__ void __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 
 #pragma unroll
     for (int u = 0; u < kDeg; ++u)
       if (u < dI) {
-        rt_where[u] = s.blk_head[8 * n + ce0 + u];
-        end_slot[u] = s.blk_head[8 * c_from[u] + 1] % M;  // of the sender's latest version after the launch
+        rt_where[u] = s.blk_head[kHeadWords * n + ce0 + u];
+        end_slot[u] = s.blk_head[kHeadWords * c_from[u] + 9];  // of the sender's latest version after the launch
         if (rt_where[u] & 1) rt[u] = V<VEC>::ld(s.rho_tilde + (size_t)(ce0 + u) * p + k);
       }
   }
@@ -216,14 +230,14 @@ __global__ void __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 
     const float* sgg = s.sigma_ring + (size_t)iT * M * p + kT;
     for (int m0 = 0; m0 < M; m0 += kBatch) {
       float4 tv[kBatch], ts[kBatch];
+      const unsigned get_v = in_v >> m0, get_s = in_s >> m0;  // bits past the last slot are clear
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
         tv[u] = ts[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (m0 + u < M) {
-          const int ver = version_in(m0 + u, s0_T, t0_T);
-          if (ver >= lo0_v) tv[u] = V<VEC>::ld(vg + (size_t)(m0 + u) * p);
-          if (ver >= lo0_s) ts[u] = V<VEC>::ld(sgg + (size_t)(m0 + u) * p);
-        }
+        if (get_v & (1u << u)) tv[u] = V<VEC>::ld(vg);
+        if (get_s & (1u << u)) ts[u] = V<VEC>::ld(sgg);
+        vg += p;
+        sgg += p;
       }
 #pragma unroll
       for (int u = 0; u < kBatch; ++u)
@@ -256,7 +270,7 @@ __global__ void __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 
   if (mine) {
     const int t0 = plan_a.node & 0x3FFFFFFF;
     g = diag_sample<VEC, MOM>(s, h, c, x, i, t0, k);
-    a_cur = a_own + __umul24((unsigned)(t0 % M), slot_bytes);
+    a_cur = a_own + __umul24((unsigned)s.blk_head[kHeadWords * i + 8], slot_bytes);  // the slot of version t0
     ver_next = ver_first = t0 + 1;
   }
   if (W > 1) __syncthreads();  // the tiles of the workgroup are in LDS
@@ -336,6 +350,16 @@ __global__ void __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 
       if (q + 1 < blk.rounds) round(q + 1, plan_b, plan_a);
     }
   }
+  // The last plan words asked for are not used.  They are looked at here all the same, on every path: memory
+  // operations complete in order, and as long as the compiler has to assume that a load may still be under way on
+  // some path, each wait it places for that load in the write-back is a wait for every store issued before it.
+  auto settle = [](const Plan& P) {
+    asm volatile("" ::"v"(P.node));
+#pragma unroll
+    for (int u = 0; u < kDeg; ++u) asm volatile("" ::"v"(P.r[u]), "v"(P.c[u]));
+  };
+  settle(plan_a);
+  settle(plan_b);
 
   // Write-back.  With blk.rebase the running sums are rebased on the way (what rfast_rebase_kernel does, and with
   // its operations): sender j's latest sum leaves every slot of its ring, and a_ij times it every buffer it feeds.
@@ -359,29 +383,27 @@ __global__ void __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 
   else wave_sync();
   if (moves) {
     float4 base = make_float4(0.f, 0.f, 0.f, 0.f);
-    const bool shift = blk.rebase && lo1_s != 0x7fffffff;  // nobody reads the sums of a node without out-edges
+    const bool shift = blk.rebase && put_s != 0;  // nobody reads the sums of a node without out-edges
     if (shift) base = mv_l[ring_f4 + (size_t)se_T * lw];
     float* vg = s.v_ring + (size_t)iT * M * p + kT;
     float* sgg = s.sigma_ring + (size_t)iT * M * p + kT;
-    for (int m0 = 0; m0 < M; m0 += 8) {
-      float4 tv[8], ts[8];
-      bool put_v[8], put_s[8];
+    for (int m0 = 0; m0 < M; m0 += kBatch) {
+      float4 tv[kBatch], ts[kBatch];
+      const unsigned back_v = put_v >> m0, back_s = put_s >> m0;  // bits past the last slot are clear
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        // a slot goes back if the launch wrote it (or shifted it) and somebody can still read its version
-        const int ver = m0 + u < M ? version_in(m0 + u, se_T, te_T) : -1;
-        put_v[u] = m0 + u < M && ver > t0_T && ver >= lo1_v;
-        put_s[u] = m0 + u < M && (ver > t0_T || shift) && ver >= lo1_s;
-        if (put_v[u]) tv[u] = mv_l[(size_t)(m0 + u) * lw];
-        if (put_s[u]) {
+      for (int u = 0; u < kBatch; ++u) {
+        if (back_v & (1u << u)) tv[u] = mv_l[(size_t)(m0 + u) * lw];
+        if (back_s & (1u << u)) {
           ts[u] = mv_l[ring_f4 + (size_t)(m0 + u) * lw];
           if (shift) ts[u] = sub(ts[u], base);
         }
       }
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        if (put_v[u]) V<VEC>::st(vg + (size_t)(m0 + u) * p, tv[u]);
-        if (put_s[u]) V<VEC>::st(sgg + (size_t)(m0 + u) * p, ts[u]);
+      for (int u = 0; u < kBatch; ++u) {
+        if (back_v & (1u << u)) V<VEC>::st(vg, tv[u]);
+        if (back_s & (1u << u)) V<VEC>::st(sgg, ts[u]);
+        vg += p;
+        sgg += p;
       }
     }
   }
@@ -468,11 +490,12 @@ size_t wave_lds_bytes(const RfastDev& d, int lw) { return (size_t)2 * d.n * d.M 
 }  // namespace
 
 // The separable objective, p a multiple of 4, at most 32 nodes with at most kWaveMaxDeg edges of a
-// kind each, and the rings of one wavefront's tile fitting into LDS.
+// kind each, rings of at most 32 slots (one bit per slot in the records of the resolver), and the rings of one
+// wavefront's tile fitting into LDS.
 bool rfast_wave_eligible(const rfast_ctx* c) {
   const RfastDev& d = c->d;
   return d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC && (d.p % 4) == 0 && c->max_degree <= kWaveMaxDeg &&
-         d.n <= kWaveMaxNodes && wave_lds_bytes(d, 64 / d.n) <= 156 * 1024;
+         d.n <= kWaveMaxNodes && d.M <= 32 && wave_lds_bytes(d, 64 / d.n) <= 156 * 1024;
 }
 
 int rfast_wave_lanes(const rfast_ctx* c) { return 64 / c->d.n; }
@@ -511,7 +534,7 @@ static hipError_t launch_wave(rfast_ctx* c, const RfastBlock& blk) {
   const int64_t groups = ((d.p + per - 1) / per + run - 1) / run * run;  // whole runs: a workgroup past the end leaves at once
   if (groups > 0x7fffffffLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL((rfast_wave_kernel<kDeg, MOM, W>), dim3((unsigned)groups), dim3(64 * W), (size_t)W * wave_lds_bytes(d, lw),
-                     c->stream, c->d, blk, lw);
+                     c->stream, c->d, blk, lw, wave_div(lw, W));
   return hipGetLastError();
 }
 
@@ -527,7 +550,7 @@ static hipError_t prime_wave(rfast_ctx* c) {
   blk.gamma = 0.f;
   blk.rounds = 0;
   blk.rebase = 0;
-  hipLaunchKernelGGL((rfast_wave_kernel<kDeg, MOM, W>), dim3(1), dim3(64 * W), 0, c->stream, none, blk, 64 / c->d.n);
+  hipLaunchKernelGGL((rfast_wave_kernel<kDeg, MOM, W>), dim3(1), dim3(64 * W), 0, c->stream, none, blk, 64 / c->d.n, wave_div(64 / c->d.n, W));
   return hipGetLastError();
 }
 

@@ -53,7 +53,10 @@ __device__ inline void wave_sync() {
 // not in it.
 // (A persistent grid, as many workgroups as the chip holds with each streaming through a region of
 // its own, was measured and dropped: its workgroups run in step, so that all of them move tiles at one
-// time and compute at another, and a launch of 20 rounds took 10.9 ms against 8.6 ms.)
+// time and compute at another, and a launch of 20 rounds took 10.9 ms against 8.6 ms.  With a delay of
+// its own for every workgroup at the start, up to 14 us, and what depends on the node alone set up once
+// per wavefront, 10 rounds took 5.1 ms against 5.3, but 20 rounds 7.4 against 7.1 and 500 rounds 101.8
+// against 93.9: the same round loop, instruction for instruction, ran 8 % slower.)
 // Occupancy is pinned to two wavefronts per SIMD, which is what the LDS of a CU holds at nine ring
 // slots: once the registers allowed three, the eight wavefronts of a CU were spread unevenly over
 // its SIMDs and the launch took 4 % longer.

@@ -105,6 +105,29 @@ def test_tile_widths(n, d_max, burst, p, lanes):
     _same(a, b, lanes)
 
 
+@pytest.mark.parametrize("n,d_max,burst,wave", [(8, 12, 4, True), (4, 29, 4, False)])
+def test_deep_rings(n, d_max, burst, wave):
+    """Rings of 17 slots, which the multi-round kernel moves in two batches, and of 34 slots, one more than the
+    records of the resolver have bits for: those rounds go to the other kernels.  Same bits either way."""
+    wr, wc = graphs.bidirectional_ring(n)
+    R, C = graphs.from_dense(wr), graphs.from_dense(wc)
+    p = 16_388
+    sched = ScheduleSpec(n, R.nnz_off, C.nnz_off, np.full(n, 0.7), d_max, 0.3, seed=n)
+    w = configs.Workload(f"deep_{n}", n, p, R, C, d_max + burst - 1, burst, 0.02, 0, "diag_quadratic",
+                         problems.diag_quadratic(n, p, n), sched, 0.1, 70 + n, 1e-4)
+    a, b = _pair(w)
+    assert rfast_block_info(a.ctx, with_kind=True)[1] == wave and rfast_block_info(b.ctx) == 0
+    for g in (a, b):
+        g.init(None, None)
+    st, dev = harness.upload_chunk(a, w, 0, 60)
+    cut = lambda lo, hi: [dev[k][lo:hi] for k in ("active", "delay_R", "delay_C", "drop_R", "drop_C")]
+    for g in (a, b):
+        g.run(45, *cut(0, 45), w.gamma)
+        g.run(15, *cut(45, 60), w.gamma)
+        g.check()
+    _same(a, b, n)
+
+
 def test_large_state_short_and_long_calls():
     """Above 8 MB of x a launch needs 8 rounds to pay: shorter calls run one pass per round, longer
     ones take the multi-round kernel (four refills of its plan records at 70 rounds), same bits."""

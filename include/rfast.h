@@ -235,8 +235,9 @@ int rfast_use_graphs(rfast_ctx* ctx, int32_t on);
  * fitting into the 160 KB of LDS of a CU (up to 32 nodes: 64 / n lanes of one wavefront per node, 4
  * coordinates per lane, n * (D+2) * (64 / n) * 32 B; beyond: at least 16 lanes of one workgroup per
  * node, n * (D+2) * 512 B + plans), and at least 2 rounds to run before the next multiple of the
- * rebase interval and the next decay step of the step-size schedule (8 where n * p * 4 > 8 MB: a launch moves every ring slot in and out once, which a
- * large state earns back only over that many rounds); rounds that do not qualify run one pass
+ * rebase interval and the next decay step of the step-size schedule (8 where n * p * 4 > 8 MB: a launch
+ * moves every ring slot that can still be read in and out once, which a large state earns back only
+ * over that many rounds), rings of at most 32 slots (D <= 30); rounds that do not qualify run one pass
  * each.  Every step of a round is elementwise in the coordinate, so a tile of coordinates can stay
  * in LDS over several rounds; the results are the same bits as round-by-round execution.
  * Least squares and logistic regression (whose gradient couples the coordinates of a node, so that

@@ -76,6 +76,7 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
   int r_col[kDeg], c_col[kDeg], r_pw[kDeg], c_pw[kDeg], o_pw[kDeg], o_eid[kDeg];
   float r_w[kDeg], c_w[kDeg], o_w[kDeg];
   const int own = i * M * kLanes + ln;  // this lane's column in the rings of its node (LDS offsets fit in 32 bits)
+  unsigned put_v = 0, put_s = 0;        // one bit per slot of the node's rings: the slot is stored when the launch ends
   if (mine) {
     const size_t off = (size_t)i * p + k;
     x = V<VEC>::ld(s.x + off);
@@ -102,17 +103,26 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
       o_pw[u] = ho ? n + s.eR + oe : PL;
       o_eid[u] = oe;
     }
-    // rings: eight slots of both rings (sixteen loads) in flight at a time, then into LDS
+    // rings: eight slots of both rings (sixteen loads) in flight at a time, then into LDS.  Only what can matter
+    // is moved, as in the kernel with one tile per wavefront: the resolver has left one bit per slot saying whether
+    // a receiver can still pick up the version it holds (RfastDev::blk_head); the other slots are zeros in LDS
+    // (finite, for the multiply-adds with weight zero) and, further down, a slot goes back only if the launch wrote
+    // it and its version is within reach afterwards.
+    const int4 hd = *reinterpret_cast<const int4*>(s.blk_head + kHeadWords * i + 8);  // s0, se, in_v, in_s
+    const int4 he = *reinterpret_cast<const int4*>(s.blk_head + kHeadWords * i + 12);  // written, out_v, out_s
+    put_v = (unsigned)he.x & (unsigned)he.y;
+    put_s = (unsigned)he.x & (unsigned)he.z;
     const float* vg = s.v_ring + (size_t)i * M * p + k;
     const float* sgg = s.sigma_ring + (size_t)i * M * p + k;
     for (int m0 = 0; m0 < M; m0 += kRingBatch) {
       float4 tv[kRingBatch], ts[kRingBatch];
+      const unsigned get_v = (unsigned)hd.z >> m0, get_s = (unsigned)hd.w >> m0;  // bits past the last slot are clear
 #pragma unroll
-      for (int u = 0; u < kRingBatch; ++u)
-        if (m0 + u < M) {
-          tv[u] = V<VEC>::ld(vg + (size_t)(m0 + u) * p);
-          ts[u] = V<VEC>::ld(sgg + (size_t)(m0 + u) * p);
-        }
+      for (int u = 0; u < kRingBatch; ++u) {
+        tv[u] = ts[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (get_v & (1u << u)) tv[u] = V<VEC>::ld(vg + (size_t)(m0 + u) * p);
+        if (get_s & (1u << u)) ts[u] = V<VEC>::ld(sgg + (size_t)(m0 + u) * p);
+      }
 #pragma unroll
       for (int u = 0; u < kRingBatch; ++u)
         if (m0 + u < M) {
@@ -234,18 +244,17 @@ __global__ void __launch_bounds__(TPB) rfast_block_kernel(RfastDev s, RfastBlock
     float* sgg = s.sigma_ring + (size_t)i * M * p + k;
     for (int m0 = 0; m0 < M; m0 += kRingBatch) {
       float4 tv[kRingBatch], ts[kRingBatch];
+      const unsigned back_v = put_v >> m0, back_s = put_s >> m0;
 #pragma unroll
-      for (int u = 0; u < kRingBatch; ++u)
-        if (m0 + u < M) {
-          tv[u] = v_l[own + (m0 + u) * kLanes];
-          ts[u] = sg_l[own + (m0 + u) * kLanes];
-        }
+      for (int u = 0; u < kRingBatch; ++u) {
+        if (back_v & (1u << u)) tv[u] = v_l[own + (m0 + u) * kLanes];
+        if (back_s & (1u << u)) ts[u] = sg_l[own + (m0 + u) * kLanes];
+      }
 #pragma unroll
-      for (int u = 0; u < kRingBatch; ++u)
-        if (m0 + u < M) {
-          V<VEC>::st(vg + (size_t)(m0 + u) * p, tv[u]);
-          V<VEC>::st(sgg + (size_t)(m0 + u) * p, ts[u]);
-        }
+      for (int u = 0; u < kRingBatch; ++u) {
+        if (back_v & (1u << u)) V<VEC>::st(vg + (size_t)(m0 + u) * p, tv[u]);
+        if (back_s & (1u << u)) V<VEC>::st(sgg + (size_t)(m0 + u) * p, ts[u]);
+      }
     }
   }
 }
@@ -277,8 +286,8 @@ int block_lanes(const RfastDev& d) {
 // separable objective (the heavy-ball buffer of the optimizer variant is one more register set).
 bool rfast_block_eligible(const rfast_ctx* c) {
   const RfastDev& d = c->d;
-  return d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC && (d.p % 4) == 0 && c->max_degree <= kMaxDeg &&
-         block_lanes(d) != 0;
+  return d.prob.kind == RFAST_OBJ_DIAG_QUADRATIC && (d.p % 4) == 0 && c->max_degree <= kMaxDeg && d.M <= 32 &&
+         block_lanes(d) != 0;  // (rings of at most 32 slots: one bit per slot in the records of the resolver)
 }
 
 int rfast_block_lanes(const rfast_ctx* c) { return block_lanes(c->d); }

@@ -4,7 +4,8 @@
 //   the residual of the tracking-conservation identity of Lemma 3,
 //   sum_i z_i + sum_e (rho_e latest - rho~_e) - sum_i g_i  (zero in exact arithmetic).
 // One lane owns four consecutive coordinates (one when p is not a multiple of four)
-// and walks over nodes and edges (coalesced along k); partial sums are kept in fp64, reduced across the 64 lanes with shuffles
+// and walks over the nodes once, then over the edges of C (coalesced along k, the arrays of the nodes read once);
+// partial sums are kept in fp64, reduced across the 64 lanes with shuffles
 // then across the workgroup through LDS, and added to the result with one fp64 atomic per workgroup.
 #include "rfast_vec.h"
 
@@ -28,7 +29,7 @@ __device__ inline float comp(const typename V<VEC>::T& v, int u) { return reinte
 // VEC = 4: four coordinates per lane (float4 loads, one Philox call per node for the four);
 // VEC = 1: p not a multiple of four.
 template <int VEC>
-__global__ void __launch_bounds__(kThreads) rfast_diag_kernel(RfastDev s, const float* xstar, double* out) {
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4))) rfast_diag_kernel(RfastDev s, const float* xstar, double* out) {
   using T = typename V<VEC>::T;
   constexpr int W = V<VEC>::W;
   const int64_t p = s.p;
@@ -37,51 +38,50 @@ __global__ void __launch_bounds__(kThreads) rfast_diag_kernel(RfastDev s, const 
   const float* cp = (const float*)s.prob.data1;
   double acc[7] = {0, 0, 0, 0, 0, 0, 0};
   for (int64_t k = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * W; k < p; k += (int64_t)gridDim.x * kThreads * W) {
-    double xs[W], zs[W], gs[W], flight[W];
+    // One walk over the nodes, their arrays read once.  What needs the average xbar, which is known only after
+    // the walk, is accumulated about a reference that is known from the start, node 0's own value:
+    //   sum_i (x_i - xbar)^2 = sum_i d_i^2 - 2 dx sum_i d_i + n dx^2,       d_i = x_i - x_0, dx = xbar - x_0
+    //   sum_i h_i (xbar - c_i)^2 = dc^2 sum_i h_i - 2 dc sum_i h_i f_i + sum_i h_i f_i^2,  f_i = c_i - c_0, dc = xbar - c_0
+    // (differences of fp32 values, exact in fp64; whatever cancels in these sums is of the size of the spread of
+    // the x_i, or of the c_i, not of the values themselves).
+    double gs[W], flight[W], sd[W], sd2[W], sh[W], shf[W], shf2[W];  // flight: sum of the z_i, then what is on the edges too
+    float x0[W], c0[W];
 #pragma unroll
-    for (int u = 0; u < W; ++u) xs[u] = zs[u] = gs[u] = flight[u] = 0.0;
-#pragma unroll 2
+    for (int u = 0; u < W; ++u) {
+      gs[u] = flight[u] = sd[u] = sd2[u] = sh[u] = shf[u] = shf2[u] = 0.0;
+      x0[u] = c0[u] = 0.f;
+    }
+#pragma unroll 1
     for (int i = 0; i < s.n; ++i) {
       const size_t off = (size_t)i * p + k;
       const int ti = s.t[i];
       const T x = V<VEC>::ld(s.x + off), z = V<VEC>::ld(s.z + off);
-      // the separable objective keeps no sample in memory: it is a function of (x_i, t_i)
-      const T g = separable ? diag_sample<VEC>(s, V<VEC>::ld(hp + off), V<VEC>::ld(cp + off), x, i, ti, k)
-                            : V<VEC>::ld(s.g + (size_t)(ti & 1) * s.n * p + off);
+      T h, c, g;
+      if (separable) {
+        // the separable objective keeps no sample in memory: it is a function of (x_i, t_i)
+        h = V<VEC>::ld(hp + off);
+        c = V<VEC>::ld(cp + off);
+        g = diag_sample<VEC>(s, h, c, x, i, ti, k);
+      } else {
+        g = V<VEC>::ld(s.g + (size_t)(ti & 1) * s.n * p + off);
+      }
 #pragma unroll
       for (int u = 0; u < W; ++u) {
         const double zi = comp<VEC>(z, u);
-        xs[u] += comp<VEC>(x, u);
-        zs[u] += zi;
+        if (i == 0) x0[u] = comp<VEC>(x, u);
+        const double d = (double)comp<VEC>(x, u) - (double)x0[u];
+        sd[u] += d;
+        sd2[u] += d * d;
+        flight[u] += zi;
         acc[1] += zi * zi;
         gs[u] += comp<VEC>(g, u);
-      }
-    }
-    double xbar[W];
-    T xbar_f;
-#pragma unroll
-    for (int u = 0; u < W; ++u) {
-      xbar[u] = xs[u] / s.n;
-      reinterpret_cast<float*>(&xbar_f)[u] = (float)xbar[u];
-      acc[6] += xbar[u] * xbar[u];
-    }
-    if (s.xbar) V<VEC>::st(s.xbar + k, xbar_f);  // staged for the loss kernels of the objectives that need it
-#pragma unroll 2
-    for (int i = 0; i < s.n; ++i) {
-      const size_t off = (size_t)i * p + k;
-      const T x = V<VEC>::ld(s.x + off);
-      T h, c;
-      if (separable) {
-        h = V<VEC>::ld(hp + off);
-        c = V<VEC>::ld(cp + off);
-      }
-#pragma unroll
-      for (int u = 0; u < W; ++u) {
-        const double dx = (double)comp<VEC>(x, u) - xbar[u];
-        acc[0] += dx * dx;
         if (separable) {
-          const double d = xbar[u] - (double)comp<VEC>(c, u);
-          acc[5] += 0.5 * (double)comp<VEC>(h, u) * d * d;
+          const double hi = comp<VEC>(h, u);
+          if (i == 0) c0[u] = comp<VEC>(c, u);
+          const double f = (double)comp<VEC>(c, u) - (double)c0[u];
+          sh[u] += hi;
+          shf[u] += hi * f;
+          shf2[u] += hi * f * f;
         }
       }
     }
@@ -101,15 +101,24 @@ __global__ void __launch_bounds__(kThreads) rfast_diag_kernel(RfastDev s, const 
         flight[u] += (double)(a * comp<VEC>(latest, u)) - (double)rt;
       }
     }
-    T xs_f;
+    T xbar_f, xs_f;
     if (xstar) xs_f = V<VEC>::ld(xstar + k);
 #pragma unroll
     for (int u = 0; u < W; ++u) {
-      const double res = zs[u] + flight[u] - gs[u];
+      const double dx = sd[u] / s.n, xbar = (double)x0[u] + dx;
+      reinterpret_cast<float*>(&xbar_f)[u] = (float)xbar;
+      acc[6] += xbar * xbar;
+      acc[0] += sd2[u] - 2.0 * dx * sd[u] + s.n * dx * dx;
+      if (separable) {
+        const double dc = xbar - (double)c0[u];
+        acc[5] += 0.5 * (dc * dc * sh[u] - 2.0 * dc * shf[u] + shf2[u]);
+      }
+      const double res = flight[u] - gs[u];
       acc[2] += res * res;
       acc[3] += gs[u] * gs[u];
-      if (xstar) acc[4] += (xbar[u] - comp<VEC>(xs_f, u)) * (xbar[u] - comp<VEC>(xs_f, u));
+      if (xstar) acc[4] += (xbar - comp<VEC>(xs_f, u)) * (xbar - comp<VEC>(xs_f, u));
     }
+    if (s.xbar) V<VEC>::st(s.xbar + k, xbar_f);  // staged for the loss kernels of the objectives that need it
   }
   // one fp64 atomic per quantity and workgroup: the seven results are single addresses, and
   // tens of thousands of atomics on them would serialise

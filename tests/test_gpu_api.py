@@ -32,6 +32,28 @@ def test_diagnostics_match_oracle():
     assert gpu.diagnostics(None)["xbar_gap_sq"] == -1.0
 
 
+def test_diagnostics_near_consensus():
+    """Nodes that agree to a few units in the last place of large values: the consensus error is the sum of squared
+    deviations from the mean, a quantity 1e-14 of the squared values; computed in one walk over the nodes it must
+    not be lost to cancellation.  Expected value from the same fp32 numbers in NumPy fp64 (the definition)."""
+    w = configs.config2(p=4100, rounds=5)
+    gpu = harness.make_gpu(w)
+    gpu.init()
+    rng = np.random.default_rng(5)
+    base = rng.normal(100.0, 30.0, size=w.p).astype(np.float32)
+    x = np.stack([np.nextafter(base, np.float32(np.inf)) if i % 3 == 0 else base for i in range(w.n)]).astype(np.float32)
+    x[1] = np.nextafter(np.nextafter(base, np.float32(-np.inf)), np.float32(-np.inf))
+    gpu.write("X", x)
+    x64 = x.astype(np.float64)
+    xbar = x64.mean(axis=0)
+    want = float(((x64 - xbar) ** 2).sum())
+    got = gpu.diagnostics()
+    assert want > 0 and abs(got["consensus_sq"] - want) <= 1e-9 * want, (got["consensus_sq"], want)
+    c, h = w.data["c"].astype(np.float64), w.data["h"].astype(np.float64)
+    loss = float((0.5 * h * (xbar - c) ** 2).sum())
+    assert abs(got["loss_at_xbar"] - loss) <= 1e-12 * loss, (got["loss_at_xbar"], loss)
+
+
 @pytest.mark.parametrize("which", ["least_squares", "logistic", "softmax"])
 def test_training_loss_at_the_average_matches_oracle(which):
     """sum_i f_i(xbar) over every node's full local data, for the objectives with per-sample losses."""

@@ -22,7 +22,7 @@ Readings taken where the paper is silent (each also listed in the design notes):
    exclude the node itself; w_ii and a_ii enter through the explicit terms;
  * the "old" gradient of S2b is the stored sample, not a re-evaluation
    (Lemma 3's proof keeps the sample unchanged for inactive nodes);
- * stamps never decrease ("largest stamp received");
+ * stamps never decrease (a receiver keeps the newest one it has picked up: S2a, S2b);
  * a batched round activates a set of nodes that all read the state as of the
    start of the round; delay d on an edge means the receiver sees what the
    sender had published before round r-d;
